@@ -1,0 +1,180 @@
+"""The benchmark configurations as seeded synthetic workloads.
+
+The five named configurations stand in for the public datasets the paper
+measures on (co-authorship, citation, co-purchase and social graphs), which are
+not available offline; only their shape statistics (computation graphs of
+about 1e3 to 1e6 edges, 2-3 layer GCNs, 2e4 to 6e5 samples) inform these.
+Reduced variants ("*_small") keep the structure at sizes a CPU oracle finishes
+in seconds.
+"""
+from dataclasses import dataclass, field
+import numpy as np
+
+from . import graphs
+
+
+@dataclass
+class Workload:
+    name: str
+    num_nodes: int
+    row_ptr: np.ndarray          # int64[N+1]
+    col: np.ndarray              # int32[nnz]
+    features: np.ndarray         # float32[N, d0]
+    dims: tuple                  # (d0, d1, ..., dL)
+    weights: list                # float32[d_{l-1}, d_l] per layer
+    targets: list                # global node ids to explain
+    n_samples: int
+    seed: int
+    solver: str                  # "gram_chol" | "cgls"
+    transform_dtype: str = "f32"  # "f32" | "bf16"
+    tol: float = 1e-6
+    info: dict = field(default_factory=dict)
+
+    @property
+    def num_layers(self):
+        return len(self.dims) - 1
+
+
+def glorot_uniform(rng, fan_in, fan_out):
+    lim = np.sqrt(6.0 / (fan_in + fan_out))
+    return rng.uniform(-lim, lim, size=(fan_in, fan_out)).astype(np.float32)
+
+
+def _model(rng, dims):
+    return [glorot_uniform(rng, dims[i], dims[i + 1]) for i in range(len(dims) - 1)]
+
+
+def _walk_estimate(row_ptr, col, hops):
+    """Number of walks of length `hops`+1 starting at each node: a cheap
+    over-estimate of the size of its k-hop induced graph, used only to rank
+    candidate targets."""
+    n = len(row_ptr) - 1
+    deg = np.diff(row_ptr).astype(np.float64)
+    est = deg.copy()
+    rows = np.repeat(np.arange(n), np.diff(row_ptr))
+    for _ in range(hops):
+        est = np.bincount(rows, weights=est[col], minlength=n)
+    return est
+
+
+def pick_targets(row_ptr, col, hops, want_edges, count=1, examine=400,
+                 min_degree=1):
+    """Choose `count` nodes whose `hops`-hop induced graph has a number of
+    undirected edges closest to `want_edges`.  Candidates are ranked by the
+    walk estimate; a sweep up that ranking finds where the exact count crosses
+    the wanted size, and about `examine` candidates around that point are
+    counted exactly."""
+    deg = np.diff(row_ptr)
+    est = _walk_estimate(row_ptr, col, hops)
+    cand = np.flatnonzero(deg >= min_degree)
+    cand = cand[np.argsort(est[cand], kind="stable")]
+    exact = {}
+
+    def count_at(i):
+        v = int(cand[i])
+        if v not in exact:
+            inside, sizes = graphs.khop_ball(row_ptr, col, v, hops)
+            exact[v] = (graphs.induced_undirected_edge_count(row_ptr, col, inside), sizes)
+        return exact[v][0]
+
+    # geometric sweep up the ranking until the exact count passes the wanted
+    # size twice in a row, then a strided window around the crossing
+    steps = sorted({min(len(cand) - 1, int(1.3 ** t)) for t in range(80)} | {0})
+    lo, hi, seen_above = 0, len(cand) - 1, 0
+    for i in steps:
+        if count_at(i) >= want_edges:
+            seen_above += 1
+            if seen_above == 1:
+                hi = i
+            if seen_above == 2:
+                break
+        elif seen_above == 0:
+            lo = i
+    a, b = lo // 2, min(len(cand), 2 * hi + 2)
+    stride = max(1, (b - a) // examine)
+    for i in range(a, b, stride):
+        count_at(i)
+    scored = sorted((abs(m - want_edges), v, m, sizes) for v, (m, sizes) in exact.items())
+    return scored[:count]
+
+
+def _finish(name, cfg_id, N, row_ptr, col, d0, dims, targets, n_samples, solver,
+            rng, transform_dtype="f32", info=None):
+    X = rng.standard_normal((N, d0), dtype=np.float32)
+    W = _model(rng, dims)
+    return Workload(name=name, num_nodes=N, row_ptr=row_ptr, col=col, features=X,
+                    dims=tuple(dims), weights=W, targets=list(targets),
+                    n_samples=n_samples, seed=22668_000 + cfg_id, solver=solver,
+                    transform_dtype=transform_dtype, info=info or {})
+
+
+def _rng(cfg_id):
+    return np.random.default_rng(22668 * 10 + cfg_id)
+
+
+def _c1():
+    rng = _rng(1)
+    N, rp, ci = graphs.tiny_graph()
+    return _finish("c1_tiny_exact", 1, N, rp, ci, 16, (16, 16, 4), [0], 4096,
+                   "gram_chol", rng)
+
+
+def _c2():
+    rng = _rng(2)
+    N, rp, ci = graphs.barabasi_albert(10_000, 5, rng)
+    (_, v, m, sizes), = pick_targets(rp, ci, 3, 1000, examine=300, min_degree=5)
+    return _finish("c2_ba10k_1k_edges", 2, N, rp, ci, 128, (128, 64, 64, 10), [v],
+                   20_000, "gram_chol", rng, info={"players": m, "balls": sizes})
+
+
+def _rmat_workload(name, cfg_id, scale, want, d0, dims, n_samples, solver,
+                   count=1, transform_dtype="f32", examine=400, edge_factor=16):
+    rng = _rng(cfg_id)
+    N, rp, ci = graphs.rmat(scale, edge_factor, rng)
+    picks = pick_targets(rp, ci, 3, want, count=count, examine=examine)
+    return _finish(name, cfg_id, N, rp, ci, d0, dims, [p[1] for p in picks],
+                   n_samples, solver, rng, transform_dtype=transform_dtype,
+                   info={"players": [p[2] for p in picks],
+                         "balls": [p[3] for p in picks]})
+
+
+WORKLOADS = {
+    "c1": _c1,
+    "c2": _c2,
+    "c3": lambda: _rmat_workload("c3_rmat18_100k_edges", 3, 18, 100_000, 256,
+                                 (256, 128, 128, 16), 200_000, "cgls"),
+    "c4": lambda: _rmat_workload("c4_rmat20_1m_edges", 4, 20, 1_000_000, 128,
+                                 (128, 64, 64, 10), 400_000, "cgls"),
+    "c5": lambda: _rmat_workload("c5_rmat18_batch64", 5, 18, 10_000, 512,
+                                 (512, 256, 256, 32), 50_000, "gram_chol",
+                                 count=64, transform_dtype="bf16", examine=1200),
+    # reduced variants: same structure, sizes the CPU oracle finishes in seconds
+    "c2_small": lambda: _small_ba(),
+    "c3_small": lambda: _rmat_workload("c3_small_rmat13", 13, 13, 3_000, 64,
+                                       (64, 32, 32, 8), 8_000, "cgls", examine=200,
+                                       edge_factor=3),
+    "c4_small": lambda: _rmat_workload("c4_small_rmat13_underdet", 14, 13, 6_000, 32,
+                                       (32, 16, 16, 5), 4_000, "cgls", examine=200,
+                                       edge_factor=3),
+    "c5_small": lambda: _rmat_workload("c5_small_rmat13_batch4", 15, 13, 400, 64,
+                                       (64, 32, 32, 8), 3_000, "gram_chol", count=4,
+                                       transform_dtype="bf16", examine=300,
+                                       edge_factor=3),
+}
+
+
+def _small_ba():
+    rng = _rng(12)
+    N, rp, ci = graphs.barabasi_albert(600, 3, rng)
+    (_, v, m, sizes), = pick_targets(rp, ci, 3, 200, examine=200, min_degree=3)
+    return _finish("c2_small_ba600", 12, N, rp, ci, 32, (32, 16, 16, 6), [v], 3_000,
+                   "gram_chol", rng, info={"players": m, "balls": sizes})
+
+
+_cache = {}
+
+
+def make_workload(key):
+    if key not in _cache:
+        _cache[key] = WORKLOADS[key]()
+    return _cache[key]
