@@ -1,0 +1,220 @@
+/*
+ * distshap.h - C ABI of the MI355X (gfx950) Kernel-SHAP edge-attribution library.
+ *
+ * The library computes, on one GPU, the hot path of DistShap (arxiv 2506.22668):
+ * for a target node v of a graph and a trained GCN f, the players of the game are
+ * the edges of v's computational graph G_c(v) (paper, "Overview of DistShap",
+ * step 1), coalitions are sampled as rows of a binary mask matrix ("Distributed
+ * Subgraph Sampling"), f is evaluated on every masked sub-graph ("Distributed
+ * Model Prediction"), and the Shapley-kernel weighted least-squares problem is
+ * solved for one score per edge ("Distributed Shapley Computations", Alg. 1).
+ *
+ * Conventions
+ *  - Plain C; every call returns an int status (DS_OK == 0). No exception crosses
+ *    the boundary. ds_last_error() gives a human-readable message for the last
+ *    failing call on that context.
+ *  - Unless a parameter is marked [host], pointers are DEVICE pointers on the
+ *    context's GPU. The caller owns every buffer it passes in; the library never
+ *    frees them and keeps pointers only for the ds_set_* calls (those buffers
+ *    must stay valid and unchanged until the context is destroyed or re-set).
+ *  - All work is issued on the context's stream; calls that return host values
+ *    synchronise that stream before returning.
+ *  - A context is not thread-safe; use one per thread.
+ *  - Player order (bit j of a mask row <-> player j <-> phi[j]):
+ *      undirected: unordered node pairs {a < b} (global ids) joined by an edge
+ *                  with both ends in G_c(v), ascending by (a, b);
+ *      directed:   CSR entries (dst, src), src != dst, both ends in G_c(v),
+ *                  ascending by (dst, src).
+ *  - Mask rows are bit-packed: row i occupies W = ceil(n/64) uint64 words at
+ *    Z[i*W .. i*W+W-1]; player j is bit (j & 63) of word (j >> 6); padding bits
+ *    are zero.
+ */
+#ifndef DISTSHAP_H
+#define DISTSHAP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ds_ctx ds_ctx;       /* library context (device, stream, model, workspace) */
+typedef struct ds_cgraph ds_cgraph; /* an extracted computational graph, owned by the library */
+
+enum ds_status {
+  DS_OK = 0,
+  DS_EINVAL = 1,    /* bad argument, malformed or asymmetric CSR, n_samples too small */
+  DS_ECAPACITY = 2, /* an output buffer is too small; the needed size is written back */
+  DS_ENOMEM = 3,    /* device allocation failed */
+  DS_ENOTCONV = 4,  /* CGLS stopped at max_iter; phi holds the last iterate */
+  DS_EDEVICE = 5,   /* a HIP call failed */
+  DS_ESINGULAR = 6, /* Cholesky met a non-positive pivot (Gram matrix rank-deficient) */
+  DS_EINTERNAL = 7  /* an internal capacity was exceeded; no result was produced */
+};
+
+enum ds_dtype {
+  DS_F32 = 0,            /* fp32 storage and arithmetic */
+  DS_BF16_IN_F32_ACC = 1 /* dense transforms round their inputs to bf16, accumulate in fp32 */
+};
+
+enum ds_score { DS_SCORE_PROB = 0, DS_SCORE_LOGIT = 1 };
+enum ds_solver { DS_SOLVER_AUTO = 0, DS_SOLVER_GRAM_CHOL = 1, DS_SOLVER_CGLS = 2 };
+
+/* Options of an explanation. Zero-initialise for the defaults. */
+typedef struct ds_options {
+  int32_t hops;       /* radius of the computational graph; 0 -> number of GCN layers */
+  int32_t directed;   /* 0: a player is an undirected edge (both CSR entries); 1: one CSR entry */
+  int32_t score;      /* ds_score: softmax probability (default) or raw logit of the class
+                         predicted on the full computational graph */
+  int32_t solver;     /* ds_solver; AUTO picks GRAM_CHOL for n <= 16384, else CGLS */
+  double tol;         /* CGLS: stop when |s_i| / |s_0| <= tol; 0 -> 1e-6 */
+  int32_t max_iter;   /* CGLS: 0 -> min(n, 10000) */
+  int32_t batch_rows; /* coalition rows evaluated per launch; 0 -> automatic */
+  int32_t paired;     /* ds_solve only: 1 promises that rows 2r and 2r+1 are complements with
+                         equal weights (the layout ds_sample writes), which lets CGLS read only
+                         one member of each pair; 0 makes no assumption. ds_explain always
+                         uses its own paired rows. */
+} ds_options;
+
+/* What an explanation did (all [host]). Times are wall-clock milliseconds measured
+ * with HIP events on the context's stream. */
+typedef struct ds_report {
+  int64_t num_players;    /* n */
+  int64_t num_nodes;      /* |V_c| */
+  int64_t num_entries;    /* directed CSR entries of G_c (self-loops excluded) */
+  int64_t num_rows;       /* k: rows of the mask matrix actually used */
+  int32_t enumerated;     /* 1 if all 2^n coalitions were enumerated */
+  int32_t pred_class;     /* class predicted on the full computational graph */
+  int32_t solver_used;    /* ds_solver */
+  int32_t cgls_iterations;
+  double cgls_rel_residual; /* |s_i| / |s_0| at exit */
+  double f_empty;         /* f(no edges) = phi_0 */
+  double f_full;          /* f(all edges) */
+  float ms_extract, ms_sample, ms_eval, ms_solve, ms_total;
+} ds_report;
+
+typedef struct ds_cgraph_info {
+  int64_t num_players;
+  int64_t num_nodes;
+  int64_t num_entries;
+  int64_t target;    /* global id */
+  int32_t hops;
+  int32_t directed;
+  int64_t ball[8];   /* ball[h] = number of nodes within h hops, h = 0..hops (hops <= 7) */
+} ds_cgraph_info;
+
+/* ---- context --------------------------------------------------------------- */
+
+/* Create a context on HIP device `device`. `stream` is a hipStream_t passed as
+ * void* (NULL = the default stream). [host] out. */
+int ds_create(ds_ctx** out, int device, void* stream);
+/* Release the context, its workspace and every computational graph still alive. */
+int ds_destroy(ds_ctx* ctx);
+/* Message of the last failing call on this context (static storage, [host]). */
+const char* ds_last_error(const ds_ctx* ctx);
+
+/* Graph G(V, E) as a CSR adjacency (paper, "Background & Related Work"): row i
+ * lists the in-neighbours j of node i (messages flow j -> i), strictly ascending,
+ * ids in [0, N). row_ptr: int64[N+1], col: int32[row_ptr[N]]. Self-loop entries
+ * are allowed and ignored. The structure is validated on the device; a malformed
+ * CSR gives DS_EINVAL. */
+int ds_set_graph(ds_ctx* ctx, int64_t num_nodes, const int64_t* row_ptr, const int32_t* col);
+
+/* Node features X, row-major [N x d0], fp32 (dtype must be DS_F32). */
+int ds_set_features(ds_ctx* ctx, const void* X, int32_t d0, int32_t dtype);
+
+/* GCN weights (paper, "GNN Models": L-layer GCN with ReLU; layer rule of Kipf &
+ * Welling with degrees renormalised for every coalition):
+ *   H^l = ReLU(A^_S H^(l-1) W_l + b_l), no ReLU on layer L.
+ * dims [host]: int32[L+1] = d0..dL. W [host]: array of L device pointers, W_l
+ * row-major fp32 [d_(l-1) x d_l]. bias [host]: NULL, or array of L device
+ * pointers (entries may be NULL) to fp32[d_l]. 1 <= L <= 7, dL <= 1024.
+ * transform_dtype: ds_dtype applied to the dense transforms. */
+int ds_set_gcn(ds_ctx* ctx, int32_t num_layers, const int32_t* dims, const void* const* W,
+               const void* const* bias, int32_t transform_dtype);
+
+/* ---- one-shot explanation --------------------------------------------------- */
+
+/* Explain the prediction for `target`: extract G_c, draw n_samples coalitions
+ * (seeded; identical (seed, target, n) always give the same masks), evaluate the
+ * GCN on each, solve for phi.
+ *   phi:       float[capacity]  out, phi[j] = attribution of player j
+ *   M_inout:   [host] in: capacity of phi / edge_src / edge_dst; out: n
+ *   edge_src, edge_dst: int64[capacity] out or NULL, global ids of the players
+ *   report:    [host] out or NULL
+ * n == 0 is a success with *M_inout = 0. n_samples < 4 is DS_EINVAL when n >= 2.
+ * DS_ECAPACITY writes the needed n to *M_inout and touches no output buffer. */
+int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, const ds_options* opts,
+               float* phi, int64_t* M_inout, int64_t* edge_src, int64_t* edge_dst, ds_report* report);
+
+/* Explain T targets one after another (each exactly as ds_explain would).
+ *   targets [host]: int64[T]; phi_concat: float[capacity] out, target t's scores at
+ *   offsets[t] .. offsets[t+1]-1; M_out [host]: int64[T]; offsets [host]: int64[T+1];
+ *   edge_src/edge_dst: int64[capacity] or NULL; reports [host]: ds_report[T] or NULL.
+ * If the total exceeds `capacity`, DS_ECAPACITY is returned, offsets[T] holds the
+ * needed total and the targets that fitted are complete. */
+int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, int64_t n_samples,
+                     uint64_t seed, const ds_options* opts, float* phi_concat, int64_t* M_out,
+                     int64_t* offsets, int64_t* edge_src, int64_t* edge_dst, int64_t capacity,
+                     ds_report* reports);
+
+/* ---- stage-wise calls (the same kernels, exposed for parity checks) ---------- */
+
+/* Computational graph of `target` (paper: the L-hop neighbourhood and the edges
+ * among its nodes). Local node order: ascending (hop, global id). *out [host] is
+ * owned by the library; release with ds_cgraph_free. Uses opts->hops/directed. */
+int ds_extract(ds_ctx* ctx, int64_t target, const ds_options* opts, ds_cgraph** out);
+int ds_cgraph_get_info(const ds_cgraph* cg, ds_cgraph_info* info /* [host] */);
+/* Copy out the player list (global ids; undirected: src = a < dst = b). int64[n] each, may be NULL. */
+int ds_cgraph_edges(ds_ctx* ctx, const ds_cgraph* cg, int64_t* edge_src, int64_t* edge_dst);
+/* Copy out node_gid int64[|V_c|] and hop int32[|V_c|] in local order (either may be NULL). */
+int ds_cgraph_nodes(ds_ctx* ctx, const ds_cgraph* cg, int64_t* node_gid, int32_t* hop);
+/* Copy out the shared first-layer product X_c W_1 (paper's |V_c| d^2 term, computed once per
+ * target on the matrix cores): float[|V_c| x d_1], local node order. */
+int ds_cgraph_first_transform(ds_ctx* ctx, ds_cgraph* cg, float* out);
+int ds_cgraph_free(ds_ctx* ctx, ds_cgraph* cg);
+
+/* Number of mask rows k that n_samples yields for n players, and whether all
+ * coalitions are enumerated (n <= 24 and n_samples >= 2^n). Pure host function.
+ * k = 2*floor(n_samples/2) otherwise. [host] outputs. */
+int ds_sample_plan(int64_t n, int64_t n_samples, int64_t* k_out, int32_t* enumerated_out);
+
+/* Sampler (paper, "Distributed Subgraph Sampling": size-stratified allocation by
+ * the kernel mass of each size, complementary pairs, one mask row per coalition).
+ * Row 0 is the empty and row 1 the full coalition (weight 0: they are imposed as
+ * constraints); pair r >= 1 is rows 2r (small member) and 2r+1 (complement), pairs
+ * ascending by size. Random keys come from Philox4x32-10 with key = seed and
+ * counter (column/4, r, tag), so any pair range can be regenerated alone.
+ *   Z: uint64[k*W] out; w: float[k] out (per-row regression weight);
+ *   sz: int32[k] out (coalition sizes); k_out [host]. tag: stream id (the
+ *   explanation uses the low 32 bits of the target's global id). */
+int ds_sample(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, uint64_t* Z,
+              float* w, int32_t* sz, int64_t* k_out);
+/* Only pairs pair_begin <= r < pair_end: writes rows 2*pair_begin .. 2*pair_end-1
+ * to Z[0..], w[0..], sz[0..] (what one GPU of a sharded run would generate). */
+int ds_sample_range(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag,
+                    int64_t pair_begin, int64_t pair_end, uint64_t* Z, float* w, int32_t* sz);
+
+/* Masked GCN inference (paper, "Distributed Model Prediction"): y[i] = f(S_i) for
+ * the k coalitions in Z (any rows, not necessarily paired), using the context's
+ * features and GCN. y: float[k] out. score: ds_score. pred_class_out [host] may be
+ * NULL. */
+int ds_eval(ds_ctx* ctx, const ds_cgraph* cg, const uint64_t* Z, int64_t k, int32_t score, float* y,
+            int32_t* pred_class_out);
+
+/* Constrained weighted least squares (paper, Eq. for Kernel-SHAP regression, the
+ * efficiency decomposition, and Alg. 1): rows 0/1 of Z must be the empty/full
+ * coalitions; phi minimises sum_{i>=2} w_i (y_i - y_0 - z_i.phi)^2 subject to
+ * sum(phi) = y_1 - y_0; when rank-deficient the solution closest to the uniform
+ * split is returned (CGLS only). phi: float[n] out. report [host] may be NULL
+ * (fills solver_used, cgls_*). */
+int ds_solve(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
+             const ds_options* opts, float* phi, ds_report* report);
+
+/* Library version string ([host], static). */
+const char* ds_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DISTSHAP_H */

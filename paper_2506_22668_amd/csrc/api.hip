@@ -1,0 +1,447 @@
+// C ABI entry points: argument checks, workspace, and the end-to-end explanation.
+#include "internal.h"
+
+int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+int ds_arena_reserve(ds_ctx* ctx, size_t bytes) {
+  if (ctx->arena_used != 0) return ds_fail(ctx, DS_EINTERNAL, "arena reserve while allocations are live");
+  bytes = ds_align(bytes) + 4096;
+  if (bytes <= ctx->arena_bytes) return DS_OK;
+  if (ctx->arena) {
+    hipStreamSynchronize(ctx->stream);
+    hipFree(ctx->arena);
+    ctx->arena = nullptr;
+    ctx->arena_bytes = 0;
+  }
+  if (hipMalloc((void**)&ctx->arena, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return ds_fail(ctx, DS_ENOMEM, "cannot allocate a %zu-byte workspace", bytes);
+  }
+  ctx->arena_bytes = bytes;
+  return DS_OK;
+}
+
+void* ds_arena_alloc(ds_ctx* ctx, size_t bytes) {
+  bytes = ds_align(bytes ? bytes : 1);
+  if (ctx->arena_used + bytes > ctx->arena_bytes) return nullptr;
+  void* p = ctx->arena + ctx->arena_used;
+  ctx->arena_used += bytes;
+  return p;
+}
+
+int ds_mail_fetch(ds_ctx* ctx, int count) {
+  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, ctx->d_mail, count * sizeof(int64_t), hipMemcpyDeviceToHost, ctx->stream));
+  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return DS_OK;
+}
+
+extern "C" {
+
+const char* ds_version(void) { return "distshap-hip 0.1 (gfx950)"; }
+
+int ds_create(ds_ctx** out, int device, void* stream) {
+  if (!out) return DS_EINVAL;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return DS_EDEVICE;
+  if (hipSetDevice(device) != hipSuccess) return DS_EDEVICE;
+  ds_ctx* ctx = new ds_ctx();
+  ctx->device = device;
+  ctx->stream = (hipStream_t)stream;
+  ctx->err[0] = 0;
+  ctx->N = ctx->nnz = 0;
+  ctx->row_ptr = nullptr;
+  ctx->col = nullptr;
+  ctx->X = nullptr;
+  ctx->d0 = 0;
+  ctx->L = 0;
+  ctx->transform_dtype = DS_F32;
+  ctx->model_version = 0;
+  ctx->arena = nullptr;
+  ctx->arena_bytes = ctx->arena_used = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) { delete ctx; return DS_EDEVICE; }
+  ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  if (hipMalloc((void**)&ctx->d_mail, 64 * sizeof(int64_t)) != hipSuccess ||
+      hipHostMalloc((void**)&ctx->h_mail, 64 * sizeof(int64_t), hipHostMallocDefault) != hipSuccess) {
+    delete ctx;
+    return DS_ENOMEM;
+  }
+  for (int i = 0; i < 6; ++i)
+    if (hipEventCreate(&ctx->ev[i]) != hipSuccess) { delete ctx; return DS_EDEVICE; }
+  *out = ctx;
+  return DS_OK;
+}
+
+int ds_destroy(ds_ctx* ctx) {
+  if (!ctx) return DS_OK;
+  hipSetDevice(ctx->device);
+  hipStreamSynchronize(ctx->stream);
+  for (ds_cgraph* g : ctx->graphs) {
+    if (g->block) hipFree(g->block);
+    delete g;
+  }
+  ctx->graphs.clear();
+  if (ctx->arena) hipFree(ctx->arena);
+  if (ctx->d_mail) hipFree(ctx->d_mail);
+  if (ctx->h_mail) hipHostFree(ctx->h_mail);
+  for (int i = 0; i < 6; ++i) hipEventDestroy(ctx->ev[i]);
+  delete ctx;
+  return DS_OK;
+}
+
+const char* ds_last_error(const ds_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+int ds_set_graph(ds_ctx* ctx, int64_t num_nodes, const int64_t* row_ptr, const int32_t* col) {
+  if (!ctx) return DS_EINVAL;
+  if (num_nodes < 0 || num_nodes > 0x7fffffffLL || !row_ptr || (!col && num_nodes > 0))
+    return ds_fail(ctx, DS_EINVAL, "bad graph arguments (N=%lld)", (long long)num_nodes);
+  DS_HIP(ctx, hipSetDevice(ctx->device));
+  ctx->N = num_nodes;
+  ctx->row_ptr = row_ptr;
+  ctx->col = col;
+  int rc = ds_validate_csr(ctx);
+  if (rc != DS_OK) {
+    ctx->row_ptr = nullptr;
+    ctx->col = nullptr;
+    ctx->N = 0;
+  }
+  return rc;
+}
+
+int ds_set_features(ds_ctx* ctx, const void* X, int32_t d0, int32_t dtype) {
+  if (!ctx) return DS_EINVAL;
+  if (!X || d0 < 1 || dtype != DS_F32) return ds_fail(ctx, DS_EINVAL, "features must be fp32 with d0 >= 1");
+  ctx->X = (const float*)X;
+  ctx->d0 = d0;
+  return DS_OK;
+}
+
+int ds_set_gcn(ds_ctx* ctx, int32_t num_layers, const int32_t* dims, const void* const* W, const void* const* bias,
+               int32_t transform_dtype) {
+  if (!ctx) return DS_EINVAL;
+  if (num_layers < 1 || num_layers > DS_MAX_LAYERS || !dims || !W)
+    return ds_fail(ctx, DS_EINVAL, "the GCN needs 1..%d layers", DS_MAX_LAYERS);
+  if (transform_dtype != DS_F32 && transform_dtype != DS_BF16_IN_F32_ACC)
+    return ds_fail(ctx, DS_EINVAL, "unknown transform dtype %d", transform_dtype);
+  for (int l = 0; l <= num_layers; ++l)
+    if (dims[l] < 1 || dims[l] > 4096) return ds_fail(ctx, DS_EINVAL, "layer width %d out of range [1, 4096]", dims[l]);
+  if (dims[num_layers] > 1024) return ds_fail(ctx, DS_EINVAL, "at most 1024 classes");
+  for (int l = 0; l < num_layers; ++l)
+    if (!W[l]) return ds_fail(ctx, DS_EINVAL, "weight matrix %d is null", l);
+  ctx->L = num_layers;
+  for (int l = 0; l <= num_layers; ++l) ctx->dims[l] = dims[l];
+  for (int l = 0; l < num_layers; ++l) {
+    ctx->W[l] = (const float*)W[l];
+    ctx->bias[l] = bias ? (const float*)bias[l] : nullptr;
+  }
+  ctx->transform_dtype = transform_dtype;
+  ctx->model_version += 1;
+  return DS_OK;
+}
+
+static ds_options default_options(const ds_options* in) {
+  ds_options o;
+  memset(&o, 0, sizeof(o));
+  if (in) o = *in;
+  return o;
+}
+
+int ds_extract(ds_ctx* ctx, int64_t target, const ds_options* opts, ds_cgraph** out) {
+  if (!ctx || !out) return DS_EINVAL;
+  *out = nullptr;
+  DS_HIP(ctx, hipSetDevice(ctx->device));
+  ds_options o = default_options(opts);
+  int hops = o.hops > 0 ? o.hops : ctx->L;
+  if (hops < 1) return ds_fail(ctx, DS_EINVAL, "hops is 0 and no model is set");
+  if (ctx->d0 > 0 && ctx->L > 0 && ctx->d0 != ctx->dims[0])
+    return ds_fail(ctx, DS_EINVAL, "feature width %d does not match the model's input width %d", ctx->d0, ctx->dims[0]);
+  return ds_extract_impl(ctx, target, hops, o.directed ? 1 : 0, out);
+}
+
+int ds_cgraph_get_info(const ds_cgraph* cg, ds_cgraph_info* info) {
+  if (!cg || !info) return DS_EINVAL;
+  *info = cg->info;
+  return DS_OK;
+}
+
+// local ids -> global ids for the player list
+__global__ void export_edges_kernel(const int32_t* pl_src, const int32_t* pl_dst, const int64_t* node_gid, int64_t n,
+                                    int64_t* es, int64_t* ed) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= n) return;
+  if (es) es[p] = node_gid[pl_src[p]];
+  if (ed) ed[p] = node_gid[pl_dst[p]];
+}
+
+int ds_cgraph_edges(ds_ctx* ctx, const ds_cgraph* cg, int64_t* edge_src, int64_t* edge_dst) {
+  if (!ctx || !cg) return DS_EINVAL;
+  const int64_t n = cg->info.num_players;
+  if (n == 0 || (!edge_src && !edge_dst)) return DS_OK;
+  hipLaunchKernelGGL(export_edges_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, cg->pl_src,
+                     cg->pl_dst, cg->node_gid, n, edge_src, edge_dst);
+  DS_HIP(ctx, hipGetLastError());
+  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return DS_OK;
+}
+
+int ds_cgraph_nodes(ds_ctx* ctx, const ds_cgraph* cg, int64_t* node_gid, int32_t* hop) {
+  if (!ctx || !cg) return DS_EINVAL;
+  const int64_t V = cg->info.num_nodes;
+  if (node_gid) DS_HIP(ctx, hipMemcpyAsync(node_gid, cg->node_gid, V * 8, hipMemcpyDeviceToDevice, ctx->stream));
+  if (hop) DS_HIP(ctx, hipMemcpyAsync(hop, cg->hop, V * 4, hipMemcpyDeviceToDevice, ctx->stream));
+  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return DS_OK;
+}
+
+int ds_cgraph_first_transform(ds_ctx* ctx, ds_cgraph* cg, float* out) {
+  if (!ctx || !cg || !out) return DS_EINVAL;
+  ds_arena_reset(ctx);
+  DS_TRY(ds_arena_reserve(ctx, ds_eval_arena_bytes(ctx, cg, 1)));
+  int rc = ds_prepare_model(ctx, cg);
+  ds_arena_reset(ctx);
+  DS_TRY(rc);
+  DS_HIP(ctx, hipMemcpyAsync(out, cg->P, (size_t)cg->info.num_nodes * ctx->dims[1] * 4, hipMemcpyDeviceToDevice, ctx->stream));
+  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return DS_OK;
+}
+
+int ds_cgraph_free(ds_ctx* ctx, ds_cgraph* cg) {
+  if (!cg) return DS_OK;
+  if (!ctx) ctx = cg->owner;
+  hipStreamSynchronize(ctx->stream);
+  for (size_t i = 0; i < ctx->graphs.size(); ++i)
+    if (ctx->graphs[i] == cg) {
+      ctx->graphs.erase(ctx->graphs.begin() + i);
+      break;
+    }
+  if (cg->block) hipFree(cg->block);
+  delete cg;
+  return DS_OK;
+}
+
+static int sample_checked(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, int64_t pb, int64_t pe,
+                          bool whole, uint64_t* Z, float* w, int32_t* sz, int64_t* k_out) {
+  if (!ctx) return DS_EINVAL;
+  if (!Z || !w || !sz) return ds_fail(ctx, DS_EINVAL, "null output buffer");
+  DS_HIP(ctx, hipSetDevice(ctx->device));
+  ds_plan plan;
+  DS_TRY(ds_make_plan(ctx, n, n_samples, &plan));
+  if (whole) { pb = 0; pe = plan.k / 2; }
+  ds_arena_reset(ctx);
+  DS_TRY(ds_arena_reserve(ctx, ds_sample_arena_bytes(plan)));
+  int rc = ds_sample_launch(ctx, plan, seed, tag, pb, pe, Z, w, sz);
+  ds_arena_reset(ctx);
+  if (k_out) *k_out = plan.k;
+  return rc;
+}
+
+int ds_sample(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, uint64_t* Z, float* w,
+              int32_t* sz, int64_t* k_out) {
+  return sample_checked(ctx, n, n_samples, seed, tag, 0, 0, true, Z, w, sz, k_out);
+}
+
+int ds_sample_range(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, int64_t pair_begin,
+                    int64_t pair_end, uint64_t* Z, float* w, int32_t* sz) {
+  return sample_checked(ctx, n, n_samples, seed, tag, pair_begin, pair_end, false, Z, w, sz, nullptr);
+}
+
+int ds_eval(ds_ctx* ctx, const ds_cgraph* cg_in, const uint64_t* Z, int64_t k, int32_t score, float* y,
+            int32_t* pred_class_out) {
+  if (!ctx || !cg_in) return DS_EINVAL;
+  if (k < 0 || (k > 0 && (!Z || !y))) return ds_fail(ctx, DS_EINVAL, "bad eval arguments");
+  if (score != DS_SCORE_PROB && score != DS_SCORE_LOGIT) return ds_fail(ctx, DS_EINVAL, "unknown score %d", score);
+  DS_HIP(ctx, hipSetDevice(ctx->device));
+  ds_cgraph* cg = const_cast<ds_cgraph*>(cg_in);
+  ds_arena_reset(ctx);
+  DS_TRY(ds_arena_reserve(ctx, ds_eval_arena_bytes(ctx, cg, k)));
+  int rc = ds_eval_impl(ctx, cg, Z, k, score, y, 0);
+  if (rc == DS_OK && hipStreamSynchronize(ctx->stream) != hipSuccess) rc = ds_fail(ctx, DS_EDEVICE, "eval kernel failed");
+  ds_arena_reset(ctx);
+  if (rc == DS_OK && pred_class_out) *pred_class_out = cg->pred_class;
+  return rc;
+}
+
+static int solve_dispatch(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
+                          const ds_options& o, int paired, float* phi, ds_report* rep) {
+  int solver = o.solver;
+  if (solver == DS_SOLVER_AUTO) solver = n <= 16384 ? DS_SOLVER_GRAM_CHOL : DS_SOLVER_CGLS;
+  int rc = DS_OK;
+  if (solver == DS_SOLVER_GRAM_CHOL) {
+    rc = ds_solve_gram_chol(ctx, n, k, Z, w, y, phi);
+    if (rc == DS_ESINGULAR && o.solver == DS_SOLVER_AUTO) solver = DS_SOLVER_CGLS;  // fall through to the minimum-norm solve
+  }
+  int iters = 0;
+  double rel = 0.0;
+  if (solver == DS_SOLVER_CGLS) rc = ds_solve_cgls_impl(ctx, n, k, Z, w, y, paired, o.tol, o.max_iter, phi, &iters, &rel);
+  if (rep) {
+    rep->solver_used = solver;
+    rep->cgls_iterations = iters;
+    rep->cgls_rel_residual = rel;
+  }
+  return rc;
+}
+
+static size_t solve_arena_bytes(int64_t n, int64_t k, int solver_opt) {
+  size_t a = 0, b = 0;
+  if (solver_opt != DS_SOLVER_CGLS && (solver_opt == DS_SOLVER_GRAM_CHOL || n <= 16384)) a = ds_gram_arena_bytes(n, k);
+  if (solver_opt != DS_SOLVER_GRAM_CHOL) b = ds_cgls_arena_bytes(n, k);
+  if (solver_opt == DS_SOLVER_AUTO && n > 16384) a = 0;
+  return a > b ? a : b;
+}
+
+int ds_solve(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
+             const ds_options* opts, float* phi, ds_report* report) {
+  if (!ctx) return DS_EINVAL;
+  if (n < 2 || k < 2 || !Z || !w || !y || !phi) return ds_fail(ctx, DS_EINVAL, "bad solve arguments (n=%lld, k=%lld)", (long long)n, (long long)k);
+  DS_HIP(ctx, hipSetDevice(ctx->device));
+  ds_options o = default_options(opts);
+  if (report) memset(report, 0, sizeof(*report));
+  ds_arena_reset(ctx);
+  DS_TRY(ds_arena_reserve(ctx, solve_arena_bytes(n, k, o.solver)));
+  int rc = solve_dispatch(ctx, n, k, Z, w, y, o, o.paired ? 1 : 0, phi, report);
+  hipStreamSynchronize(ctx->stream);
+  ds_arena_reset(ctx);
+  if (report) {
+    report->num_players = n;
+    report->num_rows = k;
+  }
+  return rc;
+}
+
+__global__ void single_player_kernel(const float* y, float* phi) { phi[0] = y[1] - y[0]; }
+
+int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, const ds_options* opts, float* phi,
+               int64_t* M_inout, int64_t* edge_src, int64_t* edge_dst, ds_report* report) {
+  if (!ctx || !M_inout) return DS_EINVAL;
+  DS_HIP(ctx, hipSetDevice(ctx->device));
+  ds_options o = default_options(opts);
+  ds_report rep;
+  memset(&rep, 0, sizeof(rep));
+  hipStream_t st = ctx->stream;
+  if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "ds_set_gcn has not been called");
+  DS_HIP(ctx, hipEventRecord(ctx->ev[0], st));
+  ds_cgraph* cg = nullptr;
+  DS_TRY(ds_extract(ctx, target, &o, &cg));
+  struct Guard {
+    ds_ctx* c; ds_cgraph* g;
+    ~Guard() { ds_cgraph_free(c, g); ds_arena_reset(c); }
+  } guard{ctx, cg};
+  const int64_t n = cg->info.num_players;
+  rep.num_players = n;
+  rep.num_nodes = cg->info.num_nodes;
+  rep.num_entries = cg->info.num_entries;
+  const int64_t capacity = *M_inout;
+  *M_inout = n;
+  if (n > capacity) return ds_fail(ctx, DS_ECAPACITY, "phi holds %lld entries but the computational graph has %lld players", (long long)capacity, (long long)n);
+  if (n > 0 && !phi) return ds_fail(ctx, DS_EINVAL, "phi is null");
+  if (n == 0) {
+    if (report) *report = rep;
+    return DS_OK;
+  }
+  DS_TRY(ds_cgraph_edges(ctx, cg, edge_src, edge_dst));
+  DS_HIP(ctx, hipEventRecord(ctx->ev[1], st));
+
+  const int64_t W = (n + 63) / 64;
+  int64_t k;
+  ds_plan plan;
+  if (n == 1) {
+    k = 2;
+  } else {
+    DS_TRY(ds_make_plan(ctx, n, n_samples, &plan));
+    k = plan.k;
+  }
+  rep.num_rows = k;
+  rep.enumerated = n >= 2 ? plan.enumerate : 1;
+  // workspace: Z, w, sz, y live for the whole call; stage temporaries follow them
+  size_t persistent = ds_align((size_t)k * W * 8) + ds_align(k * 4) * 3 + 1024;
+  size_t stage = n >= 2 ? ds_sample_arena_bytes(plan) : 0;
+  size_t e = ds_eval_arena_bytes(ctx, cg, k);
+  if (e > stage) stage = e;
+  if (n >= 2) {
+    size_t s = solve_arena_bytes(n, k, o.solver);
+    if (s > stage) stage = s;
+  }
+  ds_arena_reset(ctx);
+  DS_TRY(ds_arena_reserve(ctx, persistent + stage));
+  uint64_t* Z = (uint64_t*)ds_arena_alloc(ctx, (size_t)k * W * 8);
+  float* w = (float*)ds_arena_alloc(ctx, k * 4);
+  int32_t* sz = (int32_t*)ds_arena_alloc(ctx, k * 4);
+  float* y = (float*)ds_arena_alloc(ctx, k * 4);
+  if (!Z || !w || !sz || !y) return ds_fail(ctx, DS_EINTERNAL, "explain: arena exhausted");
+  const size_t mark = ctx->arena_used;
+
+  if (n == 1) {
+    const uint64_t rows[2] = {0ull, 1ull};
+    DS_HIP(ctx, hipMemcpyAsync(Z, rows, sizeof(rows), hipMemcpyHostToDevice, st));
+    DS_HIP(ctx, hipStreamSynchronize(st));
+  } else {
+    DS_TRY(ds_sample_launch(ctx, plan, seed, (uint32_t)((uint64_t)target & 0xFFFFFFFFull), 0, k / 2, Z, w, sz));
+  }
+  ctx->arena_used = mark;
+  DS_HIP(ctx, hipEventRecord(ctx->ev[2], st));
+
+  DS_TRY(ds_eval_impl(ctx, cg, Z, k, o.score, y, o.batch_rows));
+  ctx->arena_used = mark;
+  DS_HIP(ctx, hipEventRecord(ctx->ev[3], st));
+  rep.pred_class = cg->pred_class;
+
+  int rc = DS_OK;
+  if (n == 1) {
+    hipLaunchKernelGGL(single_player_kernel, dim3(1), dim3(1), 0, st, y, phi);
+  } else {
+    rc = solve_dispatch(ctx, n, k, Z, w, y, o, 1, phi, &rep);
+  }
+  if (rc != DS_OK && rc != DS_ENOTCONV) return rc;
+  DS_HIP(ctx, hipEventRecord(ctx->ev[4], st));
+  float f01[2];
+  DS_HIP(ctx, hipMemcpyAsync(f01, y, 2 * sizeof(float), hipMemcpyDeviceToHost, st));
+  DS_HIP(ctx, hipStreamSynchronize(st));
+  rep.f_empty = f01[0];
+  rep.f_full = f01[1];
+  hipEventElapsedTime(&rep.ms_extract, ctx->ev[0], ctx->ev[1]);
+  hipEventElapsedTime(&rep.ms_sample, ctx->ev[1], ctx->ev[2]);
+  hipEventElapsedTime(&rep.ms_eval, ctx->ev[2], ctx->ev[3]);
+  hipEventElapsedTime(&rep.ms_solve, ctx->ev[3], ctx->ev[4]);
+  hipEventElapsedTime(&rep.ms_total, ctx->ev[0], ctx->ev[4]);
+  if (report) *report = rep;
+  return rc;
+}
+
+int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, int64_t n_samples, uint64_t seed,
+                     const ds_options* opts, float* phi_concat, int64_t* M_out, int64_t* offsets, int64_t* edge_src,
+                     int64_t* edge_dst, int64_t capacity, ds_report* reports) {
+  if (!ctx || !targets || num_targets < 0 || !M_out || !offsets) return DS_EINVAL;
+  int64_t off = 0;
+  int worst = DS_OK;
+  bool full = false;
+  offsets[0] = 0;
+  for (int32_t t = 0; t < num_targets; ++t) {
+    int64_t m = full ? 0 : capacity - off;
+    int rc = ds_explain(ctx, targets[t], n_samples, seed, opts, phi_concat ? phi_concat + off : nullptr, &m,
+                        edge_src ? edge_src + off : nullptr, edge_dst ? edge_dst + off : nullptr,
+                        reports ? reports + t : nullptr);
+    if (rc == DS_ECAPACITY) {
+      full = true;
+      worst = DS_ECAPACITY;
+    } else if (rc != DS_OK && rc != DS_ENOTCONV) {
+      return rc;
+    } else if (rc == DS_ENOTCONV && worst == DS_OK) {
+      worst = rc;
+    }
+    M_out[t] = m;
+    off += m;
+    offsets[t + 1] = off;
+  }
+  return worst;
+}
+
+}  // extern "C"

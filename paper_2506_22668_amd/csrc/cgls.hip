@@ -1,0 +1,297 @@
+// Conjugate gradients for least squares on the bit-packed mask matrix.
+//
+// Paper, Alg. 1 (CGLS on sqrt(W) M with a 1D row layout; here one GPU holds all
+// rows, so the two all-reduces of the algorithm are plain device reductions). The
+// iteration is the standard Hestenes-Stiefel form (the step ratio is
+// |s_i|^2/|s_(i-1)|^2), started from zero, on the matrix sqrt(W) Z P with
+// P = I - 11^T/n, so the iterate stays orthogonal to 1 and, when the problem is
+// rank-deficient, converges to the minimum-norm solution.
+//
+// Both products walk set bits only. With complementary pairs (rows 2r, 2r+1 with
+// one weight) only the small member of each pair is read:
+//   forward:  d_r = sum_{j in S_r} u_j;  v_2r = a_r d_r,  v_2r+1 = a_r (sum(u) - d_r)
+//   adjoint:  s = P sum_r a_r (r_2r - r_2r+1) z_r          (constants vanish under P)
+// and the adjoint runs the same row kernel on a transposed copy of the small rows.
+// Without the pairing promise every row is walked and the transpose holds all rows.
+// All vectors and sums are fp64 (fp64 adds run at the rate of unpacked fp32 here).
+#include "internal.h"
+#include "solve_common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRed = 256;  // blocks (and partials) of every reduction
+
+// out[i] = sum over set bits j of row i of x[j]; one wave per row, lanes over words.
+__global__ __launch_bounds__(kThreads) void bit_spmv_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
+                                                            int64_t row_first, int64_t row_step, const double* x,
+                                                            double* out) {
+  const int64_t Wc = (cols + 63) / 64;
+  const uint64_t tail = (cols & 63) ? ((1ull << (cols & 63)) - 1ull) : ~0ull;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+  for (int64_t i = wave; i < rows; i += nwaves) {
+    const uint64_t* row = B + (row_first + i * row_step) * stride;
+    double acc = 0.0;
+    for (int64_t wd = lane; wd < Wc; wd += 64) {
+      uint64_t word = row[wd] & (wd == Wc - 1 ? tail : ~0ull);  // padding bits name no column
+      const double* xb = x + wd * 64;
+      while (word) {
+        acc += xb[__ffsll((long long)word) - 1];
+        word &= word - 1;
+      }
+    }
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (lane == 0) out[i] = acc;
+  }
+}
+
+__device__ __forceinline__ void block_reduce2(double a, double b, double* pa, double* pb) {
+  __shared__ double sh[2][kThreads / 64];
+  for (int o = 32; o > 0; o >>= 1) {
+    a += __shfl_xor(a, o, 64);
+    b += __shfl_xor(b, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    sh[0][threadIdx.x >> 6] = a;
+    sh[1][threadIdx.x >> 6] = b;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double x = 0, y = 0;
+    for (int i = 0; i < kThreads / 64; ++i) {
+      x += sh[0][i];
+      y += sh[1][i];
+    }
+    *pa = x;
+    *pb = y;
+  }
+  __syncthreads();
+}
+
+// scalars (device doubles): 0 gamma, 1 delta, 2 theta, 3 beta, 4 sum(u), 5 mean(s_raw), 6 gamma_new, 7 gamma0
+struct Vecs {
+  int64_t n, k, R;   // R = rows of the forward matrix (pairs or rows)
+  int paired;
+  const double* sqw; // [k]
+  double *x, *u, *s, *r, *v, *d, *h;  // n, n, n, k, k, R, R
+  double* scal;
+  double* part;      // [2 * kRed]
+};
+
+// r = sqrt(w) t ; h from r
+__global__ void init_r_kernel(Vecs a, const double* t) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < a.k) a.r[i] = a.sqw[i] * t[i];
+}
+__global__ void make_h_kernel(Vecs a) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= a.R) return;
+  a.h[i] = a.paired ? a.sqw[2 * i] * (a.r[2 * i] - a.r[2 * i + 1]) : a.sqw[i] * a.r[i];
+}
+
+// v from d; partial |v|^2
+__global__ __launch_bounds__(kThreads) void make_v_kernel(Vecs a) {
+  const double U = a.scal[4];
+  double acc = 0.0;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < a.R; i += (int64_t)gridDim.x * kThreads) {
+    if (a.paired) {
+      const double w = a.sqw[2 * i], d = a.d[i];
+      const double v0 = w * d, v1 = w * (U - d);
+      a.v[2 * i] = v0;
+      a.v[2 * i + 1] = v1;
+      acc += v0 * v0 + v1 * v1;
+    } else {
+      const double v0 = a.sqw[i] * a.d[i];
+      a.v[i] = v0;
+      acc += v0 * v0;
+    }
+  }
+  double dummy;
+  block_reduce2(acc, 0.0, &a.part[blockIdx.x], &dummy);
+}
+
+__global__ void fin_delta_kernel(Vecs a, int nparts) {
+  double s = 0;
+  for (int i = 0; i < nparts; ++i) s += a.part[i];
+  a.scal[1] = s;
+  a.scal[2] = s > 0.0 ? a.scal[0] / s : 0.0;
+}
+
+// r -= theta v, then h
+__global__ void update_r_kernel(Vecs a) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= a.R) return;
+  const double th = a.scal[2];
+  if (a.paired) {
+    const double r0 = a.r[2 * i] - th * a.v[2 * i], r1 = a.r[2 * i + 1] - th * a.v[2 * i + 1];
+    a.r[2 * i] = r0;
+    a.r[2 * i + 1] = r1;
+    a.h[i] = a.sqw[2 * i] * (r0 - r1);
+  } else {
+    const double r0 = a.r[i] - th * a.v[i];
+    a.r[i] = r0;
+    a.h[i] = a.sqw[i] * r0;
+  }
+}
+
+// partial sum and sum of squares of the raw adjoint
+__global__ __launch_bounds__(kThreads) void s_stats_kernel(Vecs a) {
+  double s1 = 0, s2 = 0;
+  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) {
+    const double v = a.s[j];
+    s1 += v;
+    s2 += v * v;
+  }
+  block_reduce2(s1, s2, &a.part[blockIdx.x], &a.part[kRed + blockIdx.x]);
+}
+
+// mean, gamma_new = |P s|^2 = sum s^2 - n mean^2, beta; first call sets gamma0 and beta = 0
+__global__ void fin_gamma_kernel(Vecs a, int nparts, int first) {
+  double s1 = 0, s2 = 0;
+  for (int i = 0; i < nparts; ++i) {
+    s1 += a.part[i];
+    s2 += a.part[kRed + i];
+  }
+  const double mean = s1 / (double)a.n;
+  double g = s2 - (double)a.n * mean * mean;
+  if (g < 0) g = 0;
+  a.scal[5] = mean;
+  a.scal[6] = g;
+  if (first) {
+    a.scal[7] = g;
+    a.scal[3] = 0.0;
+    a.scal[2] = 0.0;
+  } else {
+    a.scal[3] = a.scal[0] > 0.0 ? g / a.scal[0] : 0.0;
+  }
+}
+
+// x += theta u ; u = (s - mean) + beta u ; partial sum(u) ; then gamma <- gamma_new (by block 0 after use)
+__global__ __launch_bounds__(kThreads) void update_xu_kernel(Vecs a) {
+  const double th = a.scal[2], beta = a.scal[3], mean = a.scal[5];
+  double acc = 0;
+  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) {
+    const double uo = a.u[j];
+    a.x[j] += th * uo;
+    const double un = (a.s[j] - mean) + beta * uo;
+    a.u[j] = un;
+    acc += un;
+  }
+  double dummy;
+  block_reduce2(acc, 0.0, &a.part[blockIdx.x], &dummy);
+}
+
+__global__ void fin_u_kernel(Vecs a, int nparts) {
+  double s = 0;
+  for (int i = 0; i < nparts; ++i) s += a.part[i];
+  a.scal[4] = s;
+  a.scal[0] = a.scal[6];
+}
+
+// x += theta u only (last step, u not needed any more)
+__global__ void final_x_kernel(Vecs a, const float* y, float* phi) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= a.n) return;
+  const double delta = (double)y[1] - (double)y[0];
+  phi[j] = (float)(a.x[j] + a.scal[2] * a.u[j] + delta / (double)a.n);
+}
+
+inline unsigned nblocks(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
+
+}  // namespace
+
+size_t ds_cgls_arena_bytes(int64_t n, int64_t k) {
+  const int64_t KW = (k + 63) / 64;
+  return ds_align((size_t)n * KW * 8) + ds_align(k * 4) + 5 * ds_align(k * 8) + 4 * ds_align(n * 8) + 8192 + ds_align(k * 4);
+}
+
+int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y, int paired,
+                       double tol, int max_iter, float* phi, int* iters_out, double* relres_out) {
+  hipStream_t st = ctx->stream;
+  const int64_t W = (n + 63) / 64;
+  if (paired && (k & 1)) return ds_fail(ctx, DS_EINVAL, "paired rows need an even row count");
+  const int64_t R = paired ? k / 2 : k;
+  const int64_t RW = (R + 63) / 64;
+  if (tol <= 0) tol = 1e-6;
+  if (max_iter <= 0) max_iter = (int)(n < 10000 ? n : 10000);
+
+  uint64_t* Zt = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * RW * 8);
+  int32_t* sz = (int32_t*)ds_arena_alloc(ctx, k * 4);
+  float* wc = (float*)ds_arena_alloc(ctx, k * 4);
+  double* t = (double*)ds_arena_alloc(ctx, k * 8);
+  Vecs a;
+  a.n = n; a.k = k; a.R = R; a.paired = paired;
+  double* sqw = (double*)ds_arena_alloc(ctx, k * 8);
+  a.sqw = sqw;
+  a.r = (double*)ds_arena_alloc(ctx, k * 8);
+  a.v = (double*)ds_arena_alloc(ctx, k * 8);
+  a.d = (double*)ds_arena_alloc(ctx, R * 8);
+  a.h = (double*)ds_arena_alloc(ctx, R * 8);
+  a.x = (double*)ds_arena_alloc(ctx, n * 8);
+  a.u = (double*)ds_arena_alloc(ctx, n * 8);
+  a.s = (double*)ds_arena_alloc(ctx, n * 8);
+  a.scal = (double*)ds_arena_alloc(ctx, 64);
+  a.part = (double*)ds_arena_alloc(ctx, 2 * kRed * 8);
+  if (!Zt || !sz || !wc || !t || !sqw || !a.r || !a.v || !a.d || !a.h || !a.x || !a.u || !a.s || !a.scal || !a.part)
+    return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
+
+  DS_TRY(ds_row_prep(ctx, Z, k, n, w, y, sz, t, sqw, wc));
+  DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, Zt));
+  DS_HIP(ctx, hipMemsetAsync(a.x, 0, n * 8, st));
+  DS_HIP(ctx, hipMemsetAsync(a.u, 0, n * 8, st));
+  DS_HIP(ctx, hipMemsetAsync(a.scal, 0, 64, st));
+
+  const unsigned gb = (unsigned)ctx->num_cus * 8;
+  const unsigned red_n = nblocks(n, kThreads) < (unsigned)kRed ? nblocks(n, kThreads) : (unsigned)kRed;
+  const unsigned red_r = nblocks(R, kThreads) < (unsigned)kRed ? nblocks(R, kThreads) : (unsigned)kRed;
+  auto spmv_rows = [&](unsigned rows) { int64_t b = ((int64_t)rows * 64 + kThreads - 1) / kThreads; return (unsigned)(b < gb ? (b < 1 ? 1 : b) : gb); };
+
+  // s_0 = P A^T r_0, u_0 = s_0
+  hipLaunchKernelGGL(init_r_kernel, dim3(nblocks(k, 256)), dim3(256), 0, st, a, t);
+  hipLaunchKernelGGL(make_h_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(bit_spmv_kernel, dim3(spmv_rows((unsigned)(n < 0x7fffffff ? n : 0x7fffffff))), dim3(kThreads), 0, st, Zt, n, R, RW, (int64_t)0, (int64_t)1, a.h, a.s);
+  hipLaunchKernelGGL(s_stats_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL(fin_gamma_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n, 1);
+  hipLaunchKernelGGL(update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a);  // theta = beta = 0: u = s - mean
+  hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
+  DS_HIP(ctx, hipGetLastError());
+  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, a.scal, 64, hipMemcpyDeviceToHost, st));
+  DS_HIP(ctx, hipStreamSynchronize(st));
+  const double gamma0 = ((double*)ctx->h_mail)[7];
+  int it = 0;
+  double rel = gamma0 > 0 ? 1.0 : 0.0;
+  bool converged = !(gamma0 > 0);
+  while (!converged && it < max_iter) {
+    hipLaunchKernelGGL(bit_spmv_kernel, dim3(spmv_rows((unsigned)R)), dim3(kThreads), 0, st, Z, R, n, W, (int64_t)0, (int64_t)(paired ? 2 : 1), a.u, a.d);
+    hipLaunchKernelGGL(make_v_kernel, dim3(red_r), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(fin_delta_kernel, dim3(1), dim3(1), 0, st, a, (int)red_r);
+    hipLaunchKernelGGL(update_r_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(bit_spmv_kernel, dim3(spmv_rows((unsigned)n)), dim3(kThreads), 0, st, Zt, n, R, RW, (int64_t)0, (int64_t)1, a.h, a.s);
+    hipLaunchKernelGGL(s_stats_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(fin_gamma_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n, 0);
+    DS_HIP(ctx, hipGetLastError());
+    DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, a.scal, 64, hipMemcpyDeviceToHost, st));
+    DS_HIP(ctx, hipStreamSynchronize(st));
+    const double* sc = (const double*)ctx->h_mail;
+    ++it;
+    if (!(sc[1] > 0.0)) { converged = true; break; }  // u in the null space: nothing left to gain
+    rel = sqrt(sc[6]) / sqrt(gamma0);
+    if (rel <= tol) { converged = true; break; }
+    if (it >= max_iter) break;
+    hipLaunchKernelGGL(update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
+  }
+  // the last step's x += theta u is folded into the output (theta is 0 if no step was taken)
+  hipLaunchKernelGGL(final_x_kernel, dim3(nblocks(n, 256)), dim3(256), 0, st, a, y, phi);
+  DS_HIP(ctx, hipGetLastError());
+  DS_HIP(ctx, hipStreamSynchronize(st));
+  if (iters_out) *iters_out = it;
+  if (relres_out) *relres_out = rel;
+  if (!converged) {
+    ds_fail(ctx, DS_ENOTCONV, "CGLS reached max_iter=%d with relative residual %.3e (tol %.1e)", max_iter, rel, tol);
+    return DS_ENOTCONV;
+  }
+  return DS_OK;
+}

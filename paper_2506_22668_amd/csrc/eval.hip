@@ -1,0 +1,442 @@
+// Masked GCN inference of the target node for many edge coalitions.
+//
+// Paper, "Distributed Model Prediction": the GNN is evaluated once per sampled
+// sub-graph; the paper batches by stacking block-diagonal copies of the adjacency
+// and multiplying element-wise with a block-diagonal mask. Here the mask bits are
+// read in place: one workgroup evaluates one coalition at a time with every
+// per-coalition intermediate in LDS, so nothing but the mask row is streamed from
+// HBM and nothing but one float is written back.
+//
+// GCN layer under a coalition S (Kipf & Welling, as cited by the paper; degrees
+// renormalised per coalition):  A~ = A_S + I, d_i = row sum of A~,
+//   H^l = act( D^-1/2 A~ D^-1/2 H^(l-1) W_l + b_l ).
+// The result is identical to evaluating all of G_c, but only the rows that can
+// reach the target are produced: layer l is computed on the nodes within L-l hops.
+// Layer 1 uses the coalition-independent product P = X_c W_1 (computed once per
+// target with MFMA) and aggregates it; layers >= 2 aggregate, then transform.
+#include "internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+struct EvalArgs {
+  int32_t V, n, L, directed, score, pred_class, bf16;
+  int32_t dims[DS_MAX_LAYERS + 1];
+  int32_t rows_out[DS_MAX_LAYERS + 1];  // rows produced by layer l (1..L)
+  int64_t W, k;
+  const int32_t *row_ptr, *col, *eid, *pl_src, *pl_dst;
+  const float* P;
+  const float* Wl[DS_MAX_LAYERS];
+  const float* bias[DS_MAX_LAYERS];
+  const uint64_t* Z;
+  float* y;
+  float* logits_out;  // optional: [k x d_L]
+  float* gws;         // per-workgroup global scratch when LDS is too small
+  int64_t gws_stride; // floats per workgroup
+  int32_t bufA_floats, bufB_floats;
+};
+
+__device__ __forceinline__ float bf16_round(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even (finite inputs)
+  return __uint_as_float(u & 0xFFFF0000u);
+}
+
+__device__ __forceinline__ int block_sum_int(int v, int* sh) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  int t = 0;
+#pragma unroll
+  for (int i = 0; i < kWaves; ++i) t += sh[i];
+  __syncthreads();
+  return t;
+}
+
+__device__ __forceinline__ int readlane_i(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
+__device__ __forceinline__ float readlane_f(float v, int l) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+
+// dst[t, :] = rs[t] * ( sum_{active e in row t} rs[col e] * src[col e, :] + rs[t] * src[t, :] ) (+bias, ReLU)
+// One wave per row; lanes hold features; the 64 entries of a chunk test their mask
+// bits together and the set bits of the ballot are walked in order.
+__device__ __forceinline__ void aggregate_rows(const EvalArgs& a, const uint64_t* z, const float* rs,
+                                               const float* src, int stride, int rows, int width,
+                                               float* dst, const float* bias, bool relu) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int t = wave; t < rows; t += kWaves) {
+    const int e0 = a.row_ptr[t], e1 = a.row_ptr[t + 1];
+    const float rst = rs[t];
+    for (int f0 = 0; f0 < width; f0 += 256) {
+      const int f = f0 + lane;
+      float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+      const bool h0 = f < width, h1 = f + 64 < width, h2 = f + 128 < width, h3 = f + 192 < width;
+      for (int base = e0; base < e1; base += 64) {
+        const int e = base + lane;
+        int srcn = 0;
+        float coef = 0.f;
+        bool bit = false;
+        if (e < e1) {
+          const int p = a.eid[e];
+          srcn = a.col[e];
+          bit = (z[p >> 6] >> (p & 63)) & 1ull;
+          coef = rs[srcn];
+        }
+        unsigned long long mask = __ballot(bit);
+        while (mask) {
+          const int i = __ffsll((long long)mask) - 1;
+          mask &= mask - 1;
+          const int s = readlane_i(srcn, i);
+          const float c = readlane_f(coef, i);
+          const float* sp = src + (size_t)s * stride + f;
+          if (h0) acc0 += c * sp[0];
+          if (h1) acc1 += c * sp[64];
+          if (h2) acc2 += c * sp[128];
+          if (h3) acc3 += c * sp[192];
+        }
+      }
+      const float* sp = src + (size_t)t * stride + f;
+      float* dp = dst + (size_t)t * width + f;
+      float v;
+      if (h0) { v = rst * (acc0 + rst * sp[0]);   if (bias) v += bias[f];       dp[0]   = relu ? fmaxf(v, 0.f) : v; }
+      if (h1) { v = rst * (acc1 + rst * sp[64]);  if (bias) v += bias[f + 64];  dp[64]  = relu ? fmaxf(v, 0.f) : v; }
+      if (h2) { v = rst * (acc2 + rst * sp[128]); if (bias) v += bias[f + 128]; dp[128] = relu ? fmaxf(v, 0.f) : v; }
+      if (h3) { v = rst * (acc3 + rst * sp[192]); if (bias) v += bias[f + 192]; dp[192] = relu ? fmaxf(v, 0.f) : v; }
+    }
+  }
+}
+
+// dst[t, j] = act( sum_i q[t, i] * W[i, j] + b[j] )
+__device__ __forceinline__ void transform_rows(const float* q, int rows, int din, int dout, const float* Wm,
+                                               const float* bias, bool relu, bool bf16, float* dst) {
+  for (int idx = threadIdx.x; idx < rows * dout; idx += kThreads) {
+    const int t = idx / dout, j = idx - t * dout;
+    const float* qr = q + (size_t)t * din;
+    float acc = 0.f;
+    if (bf16) {
+      for (int i = 0; i < din; ++i) acc += bf16_round(qr[i]) * bf16_round(Wm[(size_t)i * dout + j]);
+    } else {
+      for (int i = 0; i < din; ++i) acc += qr[i] * Wm[(size_t)i * dout + j];
+    }
+    if (bias) acc += bias[j];
+    dst[idx] = relu ? fmaxf(acc, 0.f) : acc;
+  }
+}
+
+template <bool RS_LDS, bool BUF_LDS>
+__global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
+  extern __shared__ float smem[];
+  int* red = (int*)smem;  // 16 ints of reduction scratch
+  float* rs;
+  float* bufA;
+  float* bufB;
+  {
+    float* lds = smem + 16;
+    float* g = a.gws + (size_t)blockIdx.x * a.gws_stride;
+    if (RS_LDS) { rs = lds; lds += a.V; } else { rs = g; g += a.V; }
+    if (BUF_LDS) { bufA = lds; bufB = lds + a.bufA_floats; } else { bufA = g; bufB = g + a.bufA_floats; }
+  }
+  const int tid = threadIdx.x;
+  const int64_t W = a.W;
+  const uint64_t tail_mask = (a.n & 63) ? ((1ull << (a.n & 63)) - 1ull) : ~0ull;
+
+  for (int64_t row = blockIdx.x; row < a.k; row += gridDim.x) {
+    const uint64_t* z = a.Z + row * W;
+    // coalition size decides which polarity is cheaper to walk
+    int c = 0;
+    for (int64_t w = tid; w < W; w += kThreads) c += __popcll(z[w] & (w == W - 1 ? tail_mask : ~0ull));
+    const int total = block_sum_int(c, red);
+    const bool dense = 2 * (int64_t)total > a.n;
+    const int step = dense ? -1 : 1;
+    int* deg = (int*)rs;
+    for (int i = tid; i < a.V; i += kThreads) deg[i] = dense ? (a.row_ptr[i + 1] - a.row_ptr[i] + 1) : 1;
+    __syncthreads();
+    for (int64_t w = tid; w < W; w += kThreads) {
+      uint64_t bits = dense ? ~z[w] : z[w];
+      if (w == W - 1) bits &= tail_mask;  // padding bits never name a player
+      while (bits) {
+        const int j = __ffsll((long long)bits) - 1;
+        bits &= bits - 1;
+        const int64_t p = w * 64 + j;
+        atomicAdd(&deg[a.pl_dst[p]], step);
+        if (!a.directed) atomicAdd(&deg[a.pl_src[p]], step);
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < a.V; i += kThreads) {
+      const float d = (float)deg[i];
+      rs[i] = 1.0f / sqrtf(d);
+    }
+    __syncthreads();
+
+    // layer 1: aggregate the shared product P = X_c W_1
+    aggregate_rows(a, z, rs, a.P, a.dims[1], a.rows_out[1], a.dims[1], bufA, a.bias[0], a.L > 1);
+    __syncthreads();
+    for (int l = 2; l <= a.L; ++l) {
+      aggregate_rows(a, z, rs, bufA, a.dims[l - 1], a.rows_out[l], a.dims[l - 1], bufB, nullptr, false);
+      __syncthreads();
+      transform_rows(bufB, a.rows_out[l], a.dims[l - 1], a.dims[l], a.Wl[l - 1], a.bias[l - 1], l < a.L,
+                     a.bf16 != 0, bufA);
+      __syncthreads();
+    }
+    // readout: logits of the target are bufA[0 .. d_L)
+    if (tid < 64) {
+      const int C = a.dims[a.L];
+      float m = -INFINITY;
+      for (int cidx = tid; cidx < C; cidx += 64) m = fmaxf(m, bufA[cidx]);
+      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+      float s = 0.f;
+      for (int cidx = tid; cidx < C; cidx += 64) s += expf(bufA[cidx] - m);
+      for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      if (tid == 0) {
+        const float zc = bufA[a.pred_class];
+        a.y[row] = a.score == DS_SCORE_LOGIT ? zc : expf(zc - m) / s;
+      }
+      if (a.logits_out)
+        for (int cidx = tid; cidx < C; cidx += 64) a.logits_out[row * C + cidx] = bufA[cidx];
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------- shared first transform P = X_c W_1 on the matrix cores ----------------
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ short bf16_bits(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (short)(u >> 16);
+}
+
+// One wave per 32x32 tile of C = A[M x K] * B[K x Nn] (row-major, fp32 in memory).
+// MFMA 32x32x2 f32: lane l supplies A[row l%32][k l/32] and B[k l/32][col l%32]; the
+// accumulator register i of lane l is C[8*(i/4) + 4*(l/32) + i%4][l%32].
+// BF16: 32x32x8 bf16, lane l supplies k = 4*(l/32) .. +3.
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void first_transform_kernel(const float* A, const float* B, float* C, int M, int K, int Nn) {
+  const int lane = threadIdx.x & 63;
+  const int wave_global = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int tiles_n = (Nn + 31) / 32;
+  const int tiles_m = (M + 31) / 32;
+  if (wave_global >= tiles_m * tiles_n) return;
+  const int m0 = (wave_global / tiles_n) * 32, n0 = (wave_global % tiles_n) * 32;
+  const int r = lane & 31, half = lane >> 5;
+  float16_t acc;
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  const int am = m0 + r, bn = n0 + r;
+  if (BF16) {
+    for (int k0 = 0; k0 < K; k0 += 8) {
+      short4_t av, bv;
+      for (int j = 0; j < 4; ++j) {
+        const int kk = k0 + 4 * half + j;
+        const float x = (am < M && kk < K) ? A[(size_t)am * K + kk] : 0.f;
+        const float w = (bn < Nn && kk < K) ? B[(size_t)kk * Nn + bn] : 0.f;
+        av[j] = bf16_bits(x);
+        bv[j] = bf16_bits(w);
+      }
+      acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(av, bv, acc, 0, 0, 0);
+    }
+  } else {
+    for (int k0 = 0; k0 < K; k0 += 2) {
+      const int kk = k0 + half;
+      const float x = (am < M && kk < K) ? A[(size_t)am * K + kk] : 0.f;
+      const float w = (bn < Nn && kk < K) ? B[(size_t)kk * Nn + bn] : 0.f;
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x, w, acc, 0, 0, 0);
+    }
+  }
+  for (int i = 0; i < 16; ++i) {
+    const int row = m0 + 8 * (i / 4) + 4 * half + (i % 4);
+    if (row < M && bn < Nn) C[(size_t)row * Nn + bn] = acc[i];
+  }
+}
+
+__global__ void fill_full_mask(uint64_t* z, int64_t W, int n) {
+  const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= W) return;
+  const uint64_t tail = (n & 63) ? ((1ull << (n & 63)) - 1ull) : ~0ull;
+  z[w] = (w == W - 1) ? tail : ~0ull;
+}
+
+constexpr size_t kLdsLimit = 160 * 1024 - 512;
+
+struct EvalLayout {
+  bool rs_lds, buf_lds;
+  size_t lds_bytes;
+  int64_t gws_floats;  // per workgroup
+  int32_t bufA, bufB;
+};
+
+void fill_rows(const ds_ctx* ctx, const ds_cgraph* cg, int32_t rows_out[DS_MAX_LAYERS + 1]) {
+  const int L = ctx->L, hops = cg->info.hops;
+  rows_out[0] = 0;
+  for (int l = 1; l <= L; ++l) {
+    int h = L - l;
+    if (h > hops) h = hops;
+    rows_out[l] = (int32_t)cg->info.ball[h];
+  }
+}
+
+EvalLayout make_layout(const ds_ctx* ctx, const ds_cgraph* cg) {
+  int32_t rows_out[DS_MAX_LAYERS + 1];
+  fill_rows(ctx, cg, rows_out);
+  const int L = ctx->L;
+  int64_t A = ctx->dims[L], B = 1;
+  for (int l = 1; l <= L; ++l) {
+    const int64_t out = (int64_t)rows_out[l] * ctx->dims[l];
+    if (out > A) A = out;
+    if (l >= 2) {
+      const int64_t q = (int64_t)rows_out[l] * ctx->dims[l - 1];
+      if (q > B) B = q;
+    }
+  }
+  EvalLayout lay;
+  lay.bufA = (int32_t)A;
+  lay.bufB = (int32_t)B;
+  const size_t rs_b = (size_t)cg->info.num_nodes * 4, buf_b = (size_t)(A + B) * 4, fix = 64;
+  if (fix + rs_b + buf_b <= kLdsLimit) { lay.rs_lds = true; lay.buf_lds = true; }
+  else if (fix + buf_b <= kLdsLimit && buf_b <= rs_b) { lay.rs_lds = false; lay.buf_lds = true; }
+  else if (fix + rs_b <= kLdsLimit) { lay.rs_lds = true; lay.buf_lds = false; }
+  else if (fix + buf_b <= kLdsLimit) { lay.rs_lds = false; lay.buf_lds = true; }
+  else { lay.rs_lds = false; lay.buf_lds = false; }
+  lay.lds_bytes = fix + (lay.rs_lds ? rs_b : 0) + (lay.buf_lds ? buf_b : 0);
+  lay.gws_floats = (lay.rs_lds ? 0 : cg->info.num_nodes) + (lay.buf_lds ? 0 : (A + B));
+  lay.gws_floats = (lay.gws_floats + 63) & ~(int64_t)63;
+  return lay;
+}
+
+int grid_for(const ds_ctx* ctx, const EvalLayout& lay, int64_t k) {
+  int occ = (int)(kLdsLimit / (lay.lds_bytes ? lay.lds_bytes : 1));
+  if (occ < 1) occ = 1;
+  if (occ > 8) occ = 8;
+  int64_t g = (int64_t)ctx->num_cus * occ;
+  if (g > k) g = k;
+  if (g < 1) g = 1;
+  return (int)g;
+}
+
+int launch_eval(ds_ctx* ctx, const EvalArgs& a, const EvalLayout& lay, int grid) {
+  const void* fn;
+  if (lay.rs_lds && lay.buf_lds) fn = (const void*)masked_gcn_eval_kernel<true, true>;
+  else if (lay.rs_lds) fn = (const void*)masked_gcn_eval_kernel<true, false>;
+  else if (lay.buf_lds) fn = (const void*)masked_gcn_eval_kernel<false, true>;
+  else fn = (const void*)masked_gcn_eval_kernel<false, false>;
+  if (lay.lds_bytes > 48 * 1024)
+    DS_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lay.lds_bytes));
+  if (lay.rs_lds && lay.buf_lds)
+    hipLaunchKernelGGL((masked_gcn_eval_kernel<true, true>), dim3(grid), dim3(kThreads), lay.lds_bytes, ctx->stream, a);
+  else if (lay.rs_lds)
+    hipLaunchKernelGGL((masked_gcn_eval_kernel<true, false>), dim3(grid), dim3(kThreads), lay.lds_bytes, ctx->stream, a);
+  else if (lay.buf_lds)
+    hipLaunchKernelGGL((masked_gcn_eval_kernel<false, true>), dim3(grid), dim3(kThreads), lay.lds_bytes, ctx->stream, a);
+  else
+    hipLaunchKernelGGL((masked_gcn_eval_kernel<false, false>), dim3(grid), dim3(kThreads), lay.lds_bytes, ctx->stream, a);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
+
+void fill_args(const ds_ctx* ctx, const ds_cgraph* cg, const EvalLayout& lay, EvalArgs* a) {
+  memset(a, 0, sizeof(*a));
+  a->V = (int32_t)cg->info.num_nodes;
+  a->n = (int32_t)cg->info.num_players;
+  a->L = ctx->L;
+  a->directed = cg->info.directed;
+  a->bf16 = ctx->transform_dtype == DS_BF16_IN_F32_ACC;
+  for (int i = 0; i <= ctx->L; ++i) a->dims[i] = ctx->dims[i];
+  fill_rows(ctx, cg, a->rows_out);
+  a->W = (cg->info.num_players + 63) / 64;
+  a->row_ptr = cg->row_ptr;
+  a->col = cg->col;
+  a->eid = cg->eid;
+  a->pl_src = cg->pl_src;
+  a->pl_dst = cg->pl_dst;
+  a->P = cg->P;
+  for (int l = 0; l < ctx->L; ++l) {
+    a->Wl[l] = ctx->W[l];
+    a->bias[l] = ctx->bias[l];
+  }
+  a->bufA_floats = lay.bufA;
+  a->bufB_floats = lay.bufB;
+  a->gws_stride = lay.gws_floats;
+}
+
+}  // namespace
+
+size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
+  const EvalLayout lay = make_layout(ctx, cg);
+  const int grid = grid_for(ctx, lay, k > 1 ? k : 1);
+  const size_t W = (cg->info.num_players + 63) / 64;
+  return ds_align((size_t)lay.gws_floats * 4 * grid) + ds_align(W * 8 + 8) + ds_align(ctx->dims[ctx->L] * 4 + 8) + 1024;
+}
+
+// Shared first transform and the class predicted on the full computational graph;
+// cached in the graph until the model changes. Uses the arena (caller reserved it).
+int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg) {
+  if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "ds_set_gcn has not been called");
+  if (cg->d0 != ctx->dims[0]) return ds_fail(ctx, DS_EINVAL, "feature width %d does not match the model's input width %d", cg->d0, ctx->dims[0]);
+  if (cg->model_version == ctx->model_version) return DS_OK;
+  if (cg->d1 != ctx->dims[1]) return ds_fail(ctx, DS_EINVAL, "the computational graph was extracted for a model with first hidden width %d (now %d): extract again", cg->d1, ctx->dims[1]);
+  const int M = (int)cg->info.num_nodes, K = ctx->dims[0], Nn = ctx->dims[1];
+  const int tiles = ((M + 31) / 32) * ((Nn + 31) / 32);
+  const int blocks = (tiles + kWaves - 1) / kWaves;
+  if (ctx->transform_dtype == DS_BF16_IN_F32_ACC)
+    hipLaunchKernelGGL((first_transform_kernel<true>), dim3(blocks), dim3(kThreads), 0, ctx->stream, cg->Xc, ctx->W[0], cg->P, M, K, Nn);
+  else
+    hipLaunchKernelGGL((first_transform_kernel<false>), dim3(blocks), dim3(kThreads), 0, ctx->stream, cg->Xc, ctx->W[0], cg->P, M, K, Nn);
+  DS_HIP(ctx, hipGetLastError());
+  // predicted class: evaluate the full coalition once and take the first maximum
+  const int64_t n = cg->info.num_players;
+  const int64_t W = (n + 63) / 64;
+  const int C = ctx->dims[ctx->L];
+  const EvalLayout lay = make_layout(ctx, cg);
+  uint64_t* zfull = (uint64_t*)ds_arena_alloc(ctx, W * 8 + 8);
+  float* logits = (float*)ds_arena_alloc(ctx, C * 4 + 8);
+  float* gws = lay.gws_floats ? (float*)ds_arena_alloc(ctx, (size_t)lay.gws_floats * 4) : nullptr;
+  if (!zfull || !logits || (lay.gws_floats && !gws)) return ds_fail(ctx, DS_EINTERNAL, "prepare: arena exhausted");
+  if (W > 0) hipLaunchKernelGGL(fill_full_mask, dim3((unsigned)((W + 255) / 256)), dim3(256), 0, ctx->stream, zfull, W, (int)n);
+  EvalArgs a;
+  fill_args(ctx, cg, lay, &a);
+  a.Z = zfull;
+  a.k = 1;
+  a.y = logits + C;  // one float of scratch after the logits
+  a.logits_out = logits;
+  a.gws = gws;
+  a.score = DS_SCORE_LOGIT;
+  a.pred_class = 0;
+  DS_TRY(launch_eval(ctx, a, lay, 1));
+  std::vector<float> h(C);
+  DS_HIP(ctx, hipMemcpyAsync(h.data(), logits, C * 4, hipMemcpyDeviceToHost, ctx->stream));
+  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  int best = 0;
+  for (int c = 1; c < C; ++c)
+    if (h[c] > h[best]) best = c;
+  cg->pred_class = best;
+  cg->model_version = ctx->model_version;
+  return DS_OK;
+}
+
+int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y, int batch_rows) {
+  (void)batch_rows;
+  DS_TRY(ds_prepare_model(ctx, cg));
+  if (k <= 0) return DS_OK;
+  const EvalLayout lay = make_layout(ctx, cg);
+  const int grid = grid_for(ctx, lay, k);
+  float* gws = nullptr;
+  if (lay.gws_floats) {
+    gws = (float*)ds_arena_alloc(ctx, (size_t)lay.gws_floats * 4 * grid);
+    if (!gws) return ds_fail(ctx, DS_EINTERNAL, "eval: arena exhausted");
+  }
+  EvalArgs a;
+  fill_args(ctx, cg, lay, &a);
+  a.Z = Z;
+  a.k = k;
+  a.y = y;
+  a.logits_out = nullptr;
+  a.gws = gws;
+  a.score = score;
+  a.pred_class = cg->pred_class;
+  return launch_eval(ctx, a, lay, grid);
+}

@@ -1,0 +1,116 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+#include <string.h>
+#include <vector>
+
+#include "../../include/distshap.h"
+
+#define DS_MAX_LAYERS 7
+#define DS_MAX_HOPS 7
+#define DS_ENUM_MAX_PLAYERS 24
+#define DS_WAVE 64
+
+struct ds_cgraph {
+  ds_ctx* owner;
+  ds_cgraph_info info;
+  void* block;            // one device allocation holding every array below
+  size_t block_bytes;
+  int32_t* row_ptr;       // [V+1] local CSR, row t lists local in-neighbours
+  int32_t* col;           // [nnz]
+  int32_t* eid;           // [nnz] CSR entry -> player
+  int32_t* pl_src;        // [n] local id of a (undirected: smaller global id) / message source
+  int32_t* pl_dst;        // [n] local id of b / message destination
+  int64_t* node_gid;      // [V]
+  int32_t* hop;           // [V]
+  float* Xc;              // [V x d0] gathered feature rows
+  float* P;               // [V x d1] shared first transform Xc * W_1 (valid if model_version matches)
+  uint64_t model_version; // model the cached P / pred_class belong to (0 = none)
+  int32_t pred_class;
+  int32_t d0, d1;
+};
+
+struct ds_ctx {
+  int device;
+  hipStream_t stream;
+  char err[512];
+  // graph and features (caller-owned device memory)
+  int64_t N, nnz;
+  const int64_t* row_ptr;
+  const int32_t* col;
+  const float* X;
+  int32_t d0;
+  // model
+  int32_t L;
+  int32_t dims[DS_MAX_LAYERS + 1];
+  const float* W[DS_MAX_LAYERS];
+  const float* bias[DS_MAX_LAYERS];
+  int32_t transform_dtype;
+  uint64_t model_version;
+  // bump arena for temporaries (grown only while nothing is live)
+  char* arena;
+  size_t arena_bytes, arena_used;
+  // small device<->host mailbox
+  int64_t* d_mail;  // device int64[64]
+  int64_t* h_mail;  // pinned host int64[64]
+  int num_cus;
+  hipEvent_t ev[6];
+  std::vector<ds_cgraph*> graphs;
+};
+
+int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...);
+
+#define DS_HIP(ctx, call)                                                                   \
+  do {                                                                                      \
+    hipError_t e__ = (call);                                                                \
+    if (e__ != hipSuccess)                                                                  \
+      return ds_fail(ctx, DS_EDEVICE, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e__), \
+                     __FILE__, __LINE__);                                                   \
+  } while (0)
+
+#define DS_TRY(expr)            \
+  do {                          \
+    int rc__ = (expr);          \
+    if (rc__ != DS_OK) return rc__; \
+  } while (0)
+
+// arena
+int ds_arena_reserve(ds_ctx* ctx, size_t bytes);  // only when arena_used == 0
+void* ds_arena_alloc(ds_ctx* ctx, size_t bytes);  // nullptr when exhausted
+static inline void ds_arena_reset(ds_ctx* ctx) { ctx->arena_used = 0; }
+static inline size_t ds_align(size_t b) { return (b + 255) & ~(size_t)255; }
+// copy `count` int64 values from the device mailbox to the host mailbox (synchronises)
+int ds_mail_fetch(ds_ctx* ctx, int count);
+
+// ---- stages (host drivers; each launches its kernels on ctx->stream) ----
+struct ds_plan {
+  int64_t n, k, K, H;
+  int enumerate;
+  std::vector<int64_t> b;   // class boundaries b[0..H]
+  std::vector<float> wtab;  // weight per pair class, wtab[0..H]
+};
+int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan);
+int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t tag, int64_t pair_begin,
+                     int64_t pair_end, uint64_t* Z, float* w, int32_t* sz);
+size_t ds_sample_arena_bytes(const ds_plan& plan);
+
+int ds_scan_exclusive_i32(ds_ctx* ctx, const int32_t* in, int32_t* out, int64_t count, int64_t* total_mail_slot);
+size_t ds_scan_arena_bytes(int64_t count);
+
+int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgraph** out);
+int ds_validate_csr(ds_ctx* ctx);
+
+int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y,
+                 int batch_rows);
+int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg);  // shared first transform + predicted class
+size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
+
+int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
+                       float* phi);
+size_t ds_gram_arena_bytes(int64_t n, int64_t k);
+int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
+                       int paired, double tol, int max_iter, float* phi, int* iters, double* relres);
+size_t ds_cgls_arena_bytes(int64_t n, int64_t k);

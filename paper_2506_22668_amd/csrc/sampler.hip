@@ -1,0 +1,293 @@
+// Coalition sampler: bit-packed mask rows, regression weights and sizes.
+//
+// Paper, "Distributed Subgraph Sampling": samples are rows of a k x n binary mask
+// matrix, drawn non-uniformly by coalition size, every sample with its complement
+// (only half of the rows need random numbers), sorted by size so that any range of
+// pairs can be produced independently of the others.
+//
+// A row of size s is the set of the s columns with the smallest (key, column),
+// where key(r, j) is word j%4 of Philox4x32-10 (Salmon et al., SC'11) under key =
+// seed and counter = (j/4, r_lo, r_hi, tag). One workgroup builds one pair: it finds
+// the s-th smallest (key, column) by a radix select over regenerated keys
+// (12 + 12 bits by LDS histograms, then an explicit candidate list for the last 8
+// bits and the column tie-break), then emits both rows with wave ballots.
+#include "internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kBins = 4096;
+constexpr int kCandMax = 2048;
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t out[4]) {
+  const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    if (r > 0) {
+      k0 += 0x9E3779B9u;
+      k1 += 0xBB67AE85u;
+    }
+    uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+  }
+  out[0] = c0;
+  out[1] = c1;
+  out[2] = c2;
+  out[3] = c3;
+}
+
+// Smallest bin whose inclusive prefix count reaches `want` (1-based rank); returns
+// the bin and the count of elements in earlier bins. Whole block participates.
+__device__ void select_bin(const uint32_t* hist, uint32_t* part, uint32_t want, uint32_t* res) {
+  const int t = threadIdx.x;
+  uint32_t s = 0;
+#pragma unroll
+  for (int i = 0; i < kBins / kThreads; ++i) s += hist[t * (kBins / kThreads) + i];
+  part[t] = s;
+  __syncthreads();
+  if (t == 0) {
+    uint32_t cum = 0;
+    int p = 0;
+    while (p < kThreads - 1 && cum + part[p] < want) cum += part[p++];
+    int b = p * (kBins / kThreads);
+    const int bend = b + (kBins / kThreads) - 1;
+    while (b < bend && cum + hist[b] < want) cum += hist[b++];
+    res[0] = (uint32_t)b;
+    res[1] = cum;
+  }
+  __syncthreads();
+}
+
+struct SampleArgs {
+  int64_t n, W, K, H;
+  int64_t pair_begin, pair_end;
+  const int64_t* b;     // class boundaries [H+1]
+  const float* wtab;    // [H+1]
+  uint32_t seed_lo, seed_hi, tag;
+  uint64_t* Z;
+  float* w;
+  int32_t* sz;
+  int* error_flag;
+};
+
+__global__ __launch_bounds__(kThreads) void sample_pairs_kernel(SampleArgs a) {
+  __shared__ uint32_t hist[kBins];
+  __shared__ uint32_t part[kThreads];
+  __shared__ uint32_t res[2];
+  __shared__ unsigned long long cand[kCandMax];
+  __shared__ uint32_t cand_count;
+  __shared__ unsigned long long threshold;
+
+  const int t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
+  const int64_t n = a.n, W = a.W;
+  const int64_t nq = (n + 3) >> 2;
+  const uint64_t tail_mask = (n & 63) ? ((1ull << (n & 63)) - 1ull) : ~0ull;
+
+  for (int64_t r = a.pair_begin + blockIdx.x; r < a.pair_end; r += gridDim.x) {
+    uint64_t* row_small = a.Z + (2 * (r - a.pair_begin)) * W;
+    uint64_t* row_big = row_small + W;
+    if (r == 0) {  // (empty, full): the two constraint rows
+      for (int64_t wd = t; wd < W; wd += kThreads) {
+        row_small[wd] = 0ull;
+        row_big[wd] = (wd == W - 1) ? tail_mask : ~0ull;
+      }
+      if (t == 0) {
+        a.w[0] = 0.f;
+        a.w[1] = 0.f;
+        a.sz[0] = 0;
+        a.sz[1] = (int32_t)n;
+      }
+      continue;
+    }
+    // size of the small member: s = min{s : b_s >= r}
+    int64_t lo = 1, hi = a.H;
+    while (lo < hi) {
+      int64_t mid = (lo + hi) >> 1;
+      if (a.b[mid] >= r) hi = mid; else lo = mid + 1;
+    }
+    const uint32_t s = (uint32_t)lo;
+    const uint32_t r_lo = (uint32_t)r, r_hi = (uint32_t)((uint64_t)r >> 32);
+
+    // pass A: histogram of the top 12 key bits
+    for (int i = t; i < kBins; i += kThreads) hist[i] = 0;
+    if (t == 0) cand_count = 0;
+    __syncthreads();
+    for (int64_t q = t; q < nq; q += kThreads) {
+      uint32_t key[4];
+      philox4x32_10((uint32_t)q, r_lo, r_hi, a.tag, a.seed_lo, a.seed_hi, key);
+      const int64_t j0 = q << 2;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (j0 + i < n) atomicAdd(&hist[key[i] >> 20], 1u);
+    }
+    __syncthreads();
+    select_bin(hist, part, s, res);
+    const uint32_t bin1 = res[0];
+    const uint32_t want2 = s - res[1];
+    __syncthreads();
+
+    // pass B: next 12 bits among keys in bin1
+    for (int i = t; i < kBins; i += kThreads) hist[i] = 0;
+    __syncthreads();
+    for (int64_t q = t; q < nq; q += kThreads) {
+      uint32_t key[4];
+      philox4x32_10((uint32_t)q, r_lo, r_hi, a.tag, a.seed_lo, a.seed_hi, key);
+      const int64_t j0 = q << 2;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (j0 + i < n && (key[i] >> 20) == bin1) atomicAdd(&hist[(key[i] >> 8) & 0xFFFu], 1u);
+    }
+    __syncthreads();
+    select_bin(hist, part, want2, res);
+    const uint32_t prefix24 = (bin1 << 12) | res[0];
+    const uint32_t want3 = want2 - res[1];  // 1-based rank among the candidates
+    __syncthreads();
+
+    // pass C: list the keys sharing the 24-bit prefix, as (key, column) composites
+    for (int64_t q = t; q < nq; q += kThreads) {
+      uint32_t key[4];
+      philox4x32_10((uint32_t)q, r_lo, r_hi, a.tag, a.seed_lo, a.seed_hi, key);
+      const int64_t j0 = q << 2;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (j0 + i < n && (key[i] >> 8) == prefix24) {
+          uint32_t pos = atomicAdd(&cand_count, 1u);
+          if (pos < kCandMax) cand[pos] = ((unsigned long long)key[i] << 32) | (uint32_t)(j0 + i);
+        }
+    }
+    __syncthreads();
+    uint32_t nc = cand_count;
+    if (nc > kCandMax) {  // never in practice (needs > 2048 of n keys in one 2^-24 slice)
+      if (t == 0) atomicExch(a.error_flag, 1);
+      nc = kCandMax;
+    }
+    for (uint32_t i = t; i < nc; i += kThreads) {
+      const unsigned long long me = cand[i];
+      uint32_t rank = 0;
+      for (uint32_t o = 0; o < nc; ++o) rank += (cand[o] < me) ? 1u : 0u;
+      if (rank == want3 - 1) threshold = me;
+    }
+    __syncthreads();
+    const unsigned long long thr = threshold;
+
+    // pass D: emit. Each wave covers 4 words (256 columns) per step: lane l owns
+    // the quad of columns 4l..4l+3 of that span.
+    for (int64_t span = wave; span * 4 < W; span += kThreads / 64) {
+      const int64_t q = span * 64 + lane;
+      uint32_t nib = 0;
+      if (q < nq) {
+        uint32_t key[4];
+        philox4x32_10((uint32_t)q, r_lo, r_hi, a.tag, a.seed_lo, a.seed_hi, key);
+        const int64_t j0 = q << 2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const unsigned long long comp = ((unsigned long long)key[i] << 32) | (uint32_t)(j0 + i);
+          if (j0 + i < n && comp <= thr) nib |= (1u << i);
+        }
+      }
+      // OR the 16 nibbles of each 16-lane group into one 64-bit word
+      const int pos = (lane & 15) * 4;
+      uint32_t wlo = pos < 32 ? (nib << pos) : 0u;
+      uint32_t whi = pos >= 32 ? (nib << (pos - 32)) : 0u;
+#pragma unroll
+      for (int m = 1; m < 16; m <<= 1) {
+        wlo |= (uint32_t)__shfl_xor((int)wlo, m, 64);
+        whi |= (uint32_t)__shfl_xor((int)whi, m, 64);
+      }
+      const int64_t wd = span * 4 + (lane >> 4);
+      if ((lane & 15) == 0 && wd < W) {
+        const uint64_t word = ((uint64_t)whi << 32) | wlo;
+        row_small[wd] = word;
+        row_big[wd] = ~word & ((wd == W - 1) ? tail_mask : ~0ull);
+      }
+    }
+    if (t == 0) {
+      const float wt = a.wtab[s];
+      const int64_t o = 2 * (r - a.pair_begin);
+      a.w[o] = wt;
+      a.w[o + 1] = wt;
+      a.sz[o] = (int32_t)s;
+      a.sz[o + 1] = (int32_t)(n - s);
+    }
+    __syncthreads();
+  }
+}
+
+// Enumeration (n <= 24): pair r = (bit pattern r, its complement).
+__global__ void enumerate_pairs_kernel(SampleArgs a) {
+  const int64_t r = a.pair_begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= a.pair_end) return;
+  const uint64_t full = (1ull << a.n) - 1ull;
+  const uint64_t small = (uint64_t)r, big = ~small & full;
+  const int pc = __popcll(small);
+  const int cls = pc < (int)a.n - pc ? pc : (int)a.n - pc;
+  const int64_t o = 2 * (r - a.pair_begin);
+  a.Z[o] = small;
+  a.Z[o + 1] = big;
+  const float wt = cls == 0 ? 0.f : a.wtab[cls];
+  a.w[o] = wt;
+  a.w[o + 1] = wt;
+  a.sz[o] = pc;
+  a.sz[o + 1] = (int)a.n - pc;
+}
+
+}  // namespace
+
+size_t ds_sample_arena_bytes(const ds_plan& plan) {
+  return ds_align((plan.H + 1) * sizeof(int64_t)) + ds_align((plan.H + 1) * sizeof(float)) + 256;
+}
+
+int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t tag, int64_t pair_begin,
+                     int64_t pair_end, uint64_t* Z, float* w, int32_t* sz) {
+  if (pair_begin < 0 || pair_end > plan.k / 2 || pair_begin > pair_end)
+    return ds_fail(ctx, DS_EINVAL, "pair range [%lld, %lld) outside [0, %lld)", (long long)pair_begin,
+                   (long long)pair_end, (long long)(plan.k / 2));
+  if (pair_begin == pair_end) return DS_OK;
+  const int64_t H = plan.H;
+  int64_t* d_b = (int64_t*)ds_arena_alloc(ctx, (H + 1) * sizeof(int64_t));
+  float* d_wtab = (float*)ds_arena_alloc(ctx, (H + 1) * sizeof(float));
+  int* d_err = (int*)ds_arena_alloc(ctx, 256);
+  if (!d_b || !d_wtab || !d_err) return ds_fail(ctx, DS_EINTERNAL, "sampler: arena exhausted");
+  DS_HIP(ctx, hipMemcpyAsync(d_b, plan.b.data(), (H + 1) * sizeof(int64_t), hipMemcpyHostToDevice, ctx->stream));
+  DS_HIP(ctx, hipMemcpyAsync(d_wtab, plan.wtab.data(), (H + 1) * sizeof(float), hipMemcpyHostToDevice, ctx->stream));
+  DS_HIP(ctx, hipMemsetAsync(d_err, 0, sizeof(int), ctx->stream));
+  // the host vectors must outlive the asynchronous copies
+  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  SampleArgs a;
+  a.n = plan.n;
+  a.W = (plan.n + 63) / 64;
+  a.K = plan.K;
+  a.H = H;
+  a.pair_begin = pair_begin;
+  a.pair_end = pair_end;
+  a.b = d_b;
+  a.wtab = d_wtab;
+  a.seed_lo = (uint32_t)seed;
+  a.seed_hi = (uint32_t)(seed >> 32);
+  a.tag = tag;
+  a.Z = Z;
+  a.w = w;
+  a.sz = sz;
+  a.error_flag = d_err;
+  const int64_t pairs = pair_end - pair_begin;
+  if (plan.enumerate) {
+    const int threads = 256;
+    const int64_t blocks = (pairs + threads - 1) / threads;
+    hipLaunchKernelGGL(enumerate_pairs_kernel, dim3((unsigned)blocks), dim3(threads), 0, ctx->stream, a);
+  } else {
+    const int64_t blocks = pairs < (int64_t)ctx->num_cus * 64 ? pairs : (int64_t)ctx->num_cus * 64;
+    hipLaunchKernelGGL(sample_pairs_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, a);
+  }
+  DS_HIP(ctx, hipGetLastError());
+  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, d_err, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  if (*(int*)ctx->h_mail != 0)
+    return ds_fail(ctx, DS_EINTERNAL, "sampler: candidate list overflow (more than %d keys share a 24-bit prefix)", kCandMax);
+  return DS_OK;
+}

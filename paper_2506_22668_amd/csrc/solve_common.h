@@ -1,0 +1,11 @@
+// Helpers shared by the two least-squares solvers (internal).
+#pragma once
+#include "internal.h"
+
+// sz[i] = |S_i|, t[i] = y_i - y_0 - ((y_1-y_0)/n)|S_i| (0 for the two constraint rows),
+// sqw[i] = sqrt(w_i), wc[i] = w_i (both 0 for the two constraint rows)
+int ds_row_prep(ds_ctx* ctx, const uint64_t* Z, int64_t k, int64_t n, const float* w, const float* y, int32_t* sz,
+                double* t, double* sqw, float* wc);
+// out[cols x ceil(rows/64)] = transpose of the rows row_first + i*row_step (i < rows) of `in`
+int ds_bit_transpose(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols, int64_t in_stride, int64_t row_first,
+                     int64_t row_step, uint64_t* out);

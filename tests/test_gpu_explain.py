@@ -1,0 +1,117 @@
+"""End-to-end parity: ds_explain on the GPU vs the oracle's explanation, same seeded inputs."""
+import numpy as np
+import pytest
+
+from oracle import explain as oexplain
+from synth import csr_from_undirected_edges, make_workload
+from tests.gpu_common import make_context, say
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+SOLVERS = {"gram_chol": 1, "cgls": 2}
+
+
+def _explain_case(key, tol, solver=None, oracle_solver="lstsq", targets=None):
+    from paper_2506_22668_amd import Options
+    w = make_workload(key)
+    dtype = 1 if w.transform_dtype == "bf16" else 0
+    ctx = make_context(w, transform_dtype=dtype)
+    opts = Options(solver=SOLVERS[solver or w.solver], tol=w.tol)
+    for target in (targets or w.targets):
+        say(f"explain {key} target={target}")
+        phi, es, ed, rep, rc = ctx.explain(target, w.n_samples, w.seed, opts)
+        ref = oexplain.explain(w.row_ptr, w.col, w.features, w.weights, target, w.n_samples, w.seed,
+                               solver=oracle_solver, tol=1e-12)
+        assert rep.num_players == ref["n"] and rep.num_rows == ref["k"]
+        assert rep.pred_class == ref["pred_class"]
+        assert np.array_equal(es.cpu().numpy(), ref["cg"]["edge_src"])
+        assert np.array_equal(ed.cpu().numpy(), ref["cg"]["edge_dst"])
+        got = phi.cpu().numpy().astype(np.float64)
+        scale = np.abs(ref["phi"]).max()
+        err = np.abs(got - ref["phi"]).max()
+        say(f"  n={ref['n']} k={ref['k']} max|phi|={scale:.3e} err={err:.3e} iters={rep.cgls_iterations} "
+            f"ms: ext={rep.ms_extract:.2f} smp={rep.ms_sample:.2f} eval={rep.ms_eval:.2f} solve={rep.ms_solve:.2f}")
+        assert err <= tol * scale
+        # efficiency: sum(phi) = f(full) - f(empty)
+        assert abs(got.sum() - (rep.f_full - rep.f_empty)) <= 1e-5
+        assert abs(rep.f_full - ref["y"][1]) <= 1e-5 * (1 if dtype == 0 else 1e3)
+    ctx.close()
+
+
+def test_tiny_exact_config_equals_exact_shapley():
+    from oracle import gcn, shapley
+    _explain_case("c1", 1e-4)
+    _explain_case("c1", 1e-4, solver="cgls")
+    # and the oracle it is compared with equals brute-force Shapley on this config
+    w = make_workload("c1")
+    ref = oexplain.explain(w.row_ptr, w.col, w.features, w.weights, 0, w.n_samples, w.seed)
+    f = gcn.ValueFunction(ref["cg"], w.features, w.weights, dense=True)
+    exact = shapley.exact_shapley(shapley.all_values(f, 12), 12)
+    assert np.abs(ref["phi"] - exact).max() < 1e-8
+
+
+def test_small_ba_config_gram_cholesky():
+    _explain_case("c2_small", 1e-4)
+
+
+def test_small_rmat_config_cgls():
+    _explain_case("c3_small", 1e-4, oracle_solver="cgls")
+
+
+def test_small_underdetermined_config_cgls_minimum_norm():
+    _explain_case("c4_small", 1e-4, oracle_solver="cgls")
+
+
+def test_small_batched_bf16_config():
+    _explain_case("c5_small", 1e-2)
+
+
+def test_full_ba_config_20000_coalitions():
+    _explain_case("c2", 1e-4)
+
+
+def test_explain_batch_equals_single_explanations():
+    from paper_2506_22668_amd import Options, DS_ECAPACITY
+    w = make_workload("c5_small")
+    say("explain_batch c5_small")
+    ctx = make_context(w, transform_dtype=1)
+    singles = [ctx.explain(t, w.n_samples, w.seed)[0] for t in w.targets]
+    total = sum(len(s) for s in singles)
+    phi, M, off, es, ed, reps, rc = ctx.explain_batch(w.targets, w.n_samples, w.seed, capacity=total)
+    assert rc == 0 and off[-1] == total and M == [len(s) for s in singles]
+    for i, s in enumerate(singles):
+        assert torch.equal(phi[off[i]:off[i + 1]], s)
+    phi, M, off, es, ed, reps, rc = ctx.explain_batch(w.targets, w.n_samples, w.seed, capacity=len(singles[0]))
+    assert rc == DS_ECAPACITY and off[-1] == total
+    ctx.close()
+
+
+def test_degenerate_graphs_and_error_paths():
+    from paper_2506_22668_amd import DistShapError, Options, DS_ECAPACITY, DS_EINVAL
+    from synth.workloads import Workload
+    say("explain degenerate")
+    rp, ci = csr_from_undirected_edges(6, [0, 1, 4], [1, 2, 5])
+    rng = np.random.default_rng(0)
+    W = [rng.standard_normal((4, 3)).astype(np.float32), rng.standard_normal((3, 2)).astype(np.float32)]
+    w = Workload("deg", 6, rp, ci, rng.standard_normal((6, 4), dtype=np.float32), (4, 3, 2), W, [3], 16, 1, "gram_chol")
+    ctx = make_context(w)
+    phi, es, ed, rep, rc = ctx.explain(3, 16, 1)                 # isolated: no players
+    assert len(phi) == 0 and rep.num_players == 0
+    phi, es, ed, rep, rc = ctx.explain(4, 16, 1)                 # one player: phi = delta
+    ref = oexplain.explain(rp, ci, w.features, W, 4, 16, 1)
+    assert ref["n"] == 1 and abs(float(phi[0]) - ref["phi"][0]) <= 1e-6
+    phi, es, ed, rep, rc = ctx.explain(0, 16, 1)                 # two players: enumerated
+    ref = oexplain.explain(rp, ci, w.features, W, 0, 16, 1)
+    assert ref["n"] == 2 and np.abs(phi.cpu().numpy() - ref["phi"]).max() <= 1e-6
+    w2 = make_workload("c2_small")
+    ctx2 = make_context(w2)
+    with pytest.raises(DistShapError) as e:
+        ctx2.explain(w2.targets[0], 3, 1)
+    assert e.value.code == DS_EINVAL
+    with pytest.raises(DistShapError) as e:
+        ctx2.explain(w2.targets[0], 100, 1, capacity=5)
+    assert e.value.code == DS_ECAPACITY
+    ctx.close()
+    ctx2.close()
