@@ -91,6 +91,10 @@ typedef struct ds_report {
   double f_empty;         /* f(no edges) = phi_0 */
   double f_full;          /* f(all edges) */
   float ms_extract, ms_sample, ms_eval, ms_solve, ms_total;
+  /* single-kernel durations inside the stages above (0 when the kernel did not run):
+   * the masked-inference kernel over all k rows, the popcount Gram kernel, the
+   * Cholesky factorisation launches, and the CGLS loop (all iterations). */
+  float ms_k_eval, ms_k_gram, ms_k_chol, ms_k_cgls;
 } ds_report;
 
 typedef struct ds_cgraph_info {

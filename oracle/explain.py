@@ -8,7 +8,7 @@ from . import compgraph, gcn, sampling, solve
 
 def explain(row_ptr, col, X, weights, target, n_samples, seed, biases=None,
             hops=None, undirected=True, score="prob", solver="lstsq",
-            tol=1e-10, max_iter=None, dense_adjacency=False):
+            tol=1e-10, max_iter=None, dense_adjacency=False, bf16=False):
     L = len(weights)
     hops = L if hops is None or hops == 0 else hops
     cg = compgraph.extract(row_ptr, col, target, hops, undirected)
@@ -17,7 +17,7 @@ def explain(row_ptr, col, X, weights, target, n_samples, seed, biases=None,
     if n == 0:
         out.update(phi=np.zeros(0), k=0)
         return out
-    f = gcn.ValueFunction(cg, X, weights, biases, score, dense=dense_adjacency)
+    f = gcn.ValueFunction(cg, X, weights, biases, score, dense=dense_adjacency, bf16=bf16)
     if n == 1:
         f0, f1 = f(np.zeros(1, bool)), f(np.ones(1, bool))
         out.update(phi=np.array([f1 - f0]), k=2, y=np.array([f0, f1]), pred_class=f.pred_class)

@@ -45,12 +45,31 @@ def adjacency_sparse(cg, active):
     return (D @ A @ D).tocsr()
 
 
-def forward(Ahat, X, weights, biases=None):
-    """Logits of every node. X float64[n, d0]."""
+def round_bf16(x):
+    """Round to the nearest bfloat16 (ties to even), returned as float64."""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))) & np.uint64(0xFFFF0000)
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def forward(Ahat, X, weights, biases=None, bf16=False):
+    """Logits of every node. X float64[n, d0].
+
+    bf16=True is the reduced-precision configuration: the two operands of every
+    dense transform are rounded to bfloat16 and the products are accumulated
+    exactly.  Layer 1 is then taken as A^ (X W_1) (equal to (A^ X) W_1 in real
+    arithmetic), so the rounded operands are X and W_1; for the later layers
+    they are the aggregated activations A^ H and W_l."""
     H = np.asarray(X, dtype=np.float64)
     L = len(weights)
     for l, W in enumerate(weights):
-        H = (Ahat @ H) @ np.asarray(W, dtype=np.float64)
+        W = np.asarray(W, dtype=np.float64)
+        if not bf16:
+            H = (Ahat @ H) @ W
+        elif l == 0:
+            H = Ahat @ (round_bf16(H) @ round_bf16(W))
+        else:
+            H = round_bf16(Ahat @ H) @ round_bf16(W)
         if biases is not None and biases[l] is not None:
             H = H + np.asarray(biases[l], dtype=np.float64)
         if l < L - 1:
@@ -66,7 +85,8 @@ def softmax(z):
 class ValueFunction:
     """f(S) for the target of a computational graph."""
 
-    def __init__(self, cg, X_global, weights, biases=None, score="prob", dense=False):
+    def __init__(self, cg, X_global, weights, biases=None, score="prob", dense=False, bf16=False):
+        self.bf16 = bf16
         self.cg = cg
         self.X = np.asarray(X_global, dtype=np.float64)[cg["node_gid"]]
         self.weights = weights
@@ -78,7 +98,7 @@ class ValueFunction:
 
     def logits(self, active):
         Ahat = self.adj(self.cg, np.asarray(active, dtype=bool))
-        return forward(Ahat, self.X, self.weights, self.biases)[self.cg["target_local"]]
+        return forward(Ahat, self.X, self.weights, self.biases, self.bf16)[self.cg["target_local"]]
 
     def __call__(self, active):
         z = self.logits(active)

@@ -33,7 +33,9 @@ class Report(C.Structure):
                 ("solver_used", C.c_int32), ("cgls_iterations", C.c_int32),
                 ("cgls_rel_residual", C.c_double), ("f_empty", C.c_double), ("f_full", C.c_double),
                 ("ms_extract", C.c_float), ("ms_sample", C.c_float), ("ms_eval", C.c_float),
-                ("ms_solve", C.c_float), ("ms_total", C.c_float)]
+                ("ms_solve", C.c_float), ("ms_total", C.c_float),
+                ("ms_k_eval", C.c_float), ("ms_k_gram", C.c_float), ("ms_k_chol", C.c_float),
+                ("ms_k_cgls", C.c_float)]
 
     def as_dict(self):
         return {name: getattr(self, name) for name, _ in self._fields_}

@@ -37,6 +37,20 @@ void* ds_arena_alloc(ds_ctx* ctx, size_t bytes) {
   return p;
 }
 
+int ds_kernel_mark(ds_ctx* ctx, int slot, int end) {
+  DS_HIP(ctx, hipEventRecord(ctx->kev[2 * slot + end], ctx->stream));
+  if (end) ctx->kev_set[slot] = true;
+  return DS_OK;
+}
+
+static void kernel_times(ds_ctx* ctx, ds_report* rep) {
+  float* out[4] = {&rep->ms_k_eval, &rep->ms_k_gram, &rep->ms_k_chol, &rep->ms_k_cgls};
+  for (int s = 0; s < 4; ++s) {
+    *out[s] = 0.f;
+    if (ctx->kev_set[s]) (void)hipEventElapsedTime(out[s], ctx->kev[2 * s], ctx->kev[2 * s + 1]);
+  }
+}
+
 int ds_mail_fetch(ds_ctx* ctx, int count) {
   DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, ctx->d_mail, count * sizeof(int64_t), hipMemcpyDeviceToHost, ctx->stream));
   DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -77,6 +91,9 @@ int ds_create(ds_ctx** out, int device, void* stream) {
   }
   for (int i = 0; i < 6; ++i)
     if (hipEventCreate(&ctx->ev[i]) != hipSuccess) { delete ctx; return DS_EDEVICE; }
+  for (int i = 0; i < 8; ++i)
+    if (hipEventCreate(&ctx->kev[i]) != hipSuccess) { delete ctx; return DS_EDEVICE; }
+  for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
   *out = ctx;
   return DS_OK;
 }
@@ -94,6 +111,7 @@ int ds_destroy(ds_ctx* ctx) {
   if (ctx->d_mail) hipFree(ctx->d_mail);
   if (ctx->h_mail) hipHostFree(ctx->h_mail);
   for (int i = 0; i < 6; ++i) hipEventDestroy(ctx->ev[i]);
+  for (int i = 0; i < 8; ++i) hipEventDestroy(ctx->kev[i]);
   delete ctx;
   return DS_OK;
 }
@@ -307,10 +325,12 @@ int ds_solve(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* 
   if (report) memset(report, 0, sizeof(*report));
   ds_arena_reset(ctx);
   DS_TRY(ds_arena_reserve(ctx, solve_arena_bytes(n, k, o.solver)));
+  for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
   int rc = solve_dispatch(ctx, n, k, Z, w, y, o, o.paired ? 1 : 0, phi, report);
   hipStreamSynchronize(ctx->stream);
   ds_arena_reset(ctx);
   if (report) {
+    kernel_times(ctx, report);
     report->num_players = n;
     report->num_rows = k;
   }
@@ -328,6 +348,7 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   memset(&rep, 0, sizeof(rep));
   hipStream_t st = ctx->stream;
   if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "ds_set_gcn has not been called");
+  for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
   DS_HIP(ctx, hipEventRecord(ctx->ev[0], st));
   ds_cgraph* cg = nullptr;
   DS_TRY(ds_extract(ctx, target, &o, &cg));
@@ -412,6 +433,7 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   hipEventElapsedTime(&rep.ms_eval, ctx->ev[2], ctx->ev[3]);
   hipEventElapsedTime(&rep.ms_solve, ctx->ev[3], ctx->ev[4]);
   hipEventElapsedTime(&rep.ms_total, ctx->ev[0], ctx->ev[4]);
+  kernel_times(ctx, &rep);
   if (report) *report = rep;
   return rc;
 }

@@ -136,28 +136,38 @@ __global__ void update_r_kernel(Vecs a) {
   }
 }
 
-// partial sum and sum of squares of the raw adjoint
-__global__ __launch_bounds__(kThreads) void s_stats_kernel(Vecs a) {
-  double s1 = 0, s2 = 0;
-  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) {
-    const double v = a.s[j];
-    s1 += v;
-    s2 += v * v;
-  }
-  block_reduce2(s1, s2, &a.part[blockIdx.x], &a.part[kRed + blockIdx.x]);
+// partial sums of the raw adjoint (for its mean)
+__global__ __launch_bounds__(kThreads) void s_sum_kernel(Vecs a) {
+  double s1 = 0;
+  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) s1 += a.s[j];
+  double dummy;
+  block_reduce2(s1, 0.0, &a.part[blockIdx.x], &dummy);
 }
 
-// mean, gamma_new = |P s|^2 = sum s^2 - n mean^2, beta; first call sets gamma0 and beta = 0
-__global__ void fin_gamma_kernel(Vecs a, int nparts, int first) {
-  double s1 = 0, s2 = 0;
-  for (int i = 0; i < nparts; ++i) {
-    s1 += a.part[i];
-    s2 += a.part[kRed + i];
+__global__ void fin_mean_kernel(Vecs a, int nparts) {
+  double s1 = 0;
+  for (int i = 0; i < nparts; ++i) s1 += a.part[i];
+  a.scal[5] = s1 / (double)a.n;
+}
+
+// s <- P s (subtract the mean in place) and partial |P s|^2. Two passes on purpose:
+// the raw adjoint carries a large common offset, and sum(s^2) - n mean^2 would cancel.
+__global__ __launch_bounds__(kThreads) void s_center_kernel(Vecs a) {
+  const double mean = a.scal[5];
+  double s2 = 0;
+  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) {
+    const double v = a.s[j] - mean;
+    a.s[j] = v;
+    s2 += v * v;
   }
-  const double mean = s1 / (double)a.n;
-  double g = s2 - (double)a.n * mean * mean;
-  if (g < 0) g = 0;
-  a.scal[5] = mean;
+  double dummy;
+  block_reduce2(s2, 0.0, &a.part[blockIdx.x], &dummy);
+}
+
+// gamma_new = |P s|^2 and beta; the first call sets gamma0 and beta = theta = 0
+__global__ void fin_gamma_kernel(Vecs a, int nparts, int first) {
+  double g = 0;
+  for (int i = 0; i < nparts; ++i) g += a.part[i];
   a.scal[6] = g;
   if (first) {
     a.scal[7] = g;
@@ -168,14 +178,14 @@ __global__ void fin_gamma_kernel(Vecs a, int nparts, int first) {
   }
 }
 
-// x += theta u ; u = (s - mean) + beta u ; partial sum(u) ; then gamma <- gamma_new (by block 0 after use)
+// x += theta u ; u = s + beta u (s already projected) ; partial sum(u)
 __global__ __launch_bounds__(kThreads) void update_xu_kernel(Vecs a) {
-  const double th = a.scal[2], beta = a.scal[3], mean = a.scal[5];
+  const double th = a.scal[2], beta = a.scal[3];
   double acc = 0;
   for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) {
     const double uo = a.u[j];
     a.x[j] += th * uo;
-    const double un = (a.s[j] - mean) + beta * uo;
+    const double un = a.s[j] + beta * uo;
     a.u[j] = un;
     acc += un;
   }
@@ -252,9 +262,11 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   hipLaunchKernelGGL(init_r_kernel, dim3(nblocks(k, 256)), dim3(256), 0, st, a, t);
   hipLaunchKernelGGL(make_h_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
   hipLaunchKernelGGL(bit_spmv_kernel, dim3(spmv_rows((unsigned)(n < 0x7fffffff ? n : 0x7fffffff))), dim3(kThreads), 0, st, Zt, n, R, RW, (int64_t)0, (int64_t)1, a.h, a.s);
-  hipLaunchKernelGGL(s_stats_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL(s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
+  hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
   hipLaunchKernelGGL(fin_gamma_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n, 1);
-  hipLaunchKernelGGL(update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a);  // theta = beta = 0: u = s - mean
+  hipLaunchKernelGGL(update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a);  // theta = beta = 0: u = s
   hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
   DS_HIP(ctx, hipGetLastError());
   DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, a.scal, 64, hipMemcpyDeviceToHost, st));
@@ -263,13 +275,16 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   int it = 0;
   double rel = gamma0 > 0 ? 1.0 : 0.0;
   bool converged = !(gamma0 > 0);
+  DS_TRY(ds_kernel_mark(ctx, 3, 0));
   while (!converged && it < max_iter) {
     hipLaunchKernelGGL(bit_spmv_kernel, dim3(spmv_rows((unsigned)R)), dim3(kThreads), 0, st, Z, R, n, W, (int64_t)0, (int64_t)(paired ? 2 : 1), a.u, a.d);
     hipLaunchKernelGGL(make_v_kernel, dim3(red_r), dim3(kThreads), 0, st, a);
     hipLaunchKernelGGL(fin_delta_kernel, dim3(1), dim3(1), 0, st, a, (int)red_r);
     hipLaunchKernelGGL(update_r_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
     hipLaunchKernelGGL(bit_spmv_kernel, dim3(spmv_rows((unsigned)n)), dim3(kThreads), 0, st, Zt, n, R, RW, (int64_t)0, (int64_t)1, a.h, a.s);
-    hipLaunchKernelGGL(s_stats_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
+    hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
     hipLaunchKernelGGL(fin_gamma_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n, 0);
     DS_HIP(ctx, hipGetLastError());
     DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, a.scal, 64, hipMemcpyDeviceToHost, st));
@@ -283,6 +298,7 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
     hipLaunchKernelGGL(update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
     hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
   }
+  DS_TRY(ds_kernel_mark(ctx, 3, 1));
   // the last step's x += theta u is folded into the output (theta is 0 if no step was taken)
   hipLaunchKernelGGL(final_x_kernel, dim3(nblocks(n, 256)), dim3(256), 0, st, a, y, phi);
   DS_HIP(ctx, hipGetLastError());

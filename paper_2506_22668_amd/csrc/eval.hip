@@ -438,5 +438,7 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
   a.gws = gws;
   a.score = score;
   a.pred_class = cg->pred_class;
-  return launch_eval(ctx, a, lay, grid);
+  DS_TRY(ds_kernel_mark(ctx, 0, 0));
+  DS_TRY(launch_eval(ctx, a, lay, grid));
+  return ds_kernel_mark(ctx, 0, 1);
 }

@@ -382,13 +382,16 @@ int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   DS_TRY(ds_bit_transpose(ctx, Z, k, n, W, 0, 1, Zt));
   hipLaunchKernelGGL(word_weights_kernel, dim3(nblocks(KW, 256)), dim3(256), 0, st, wc, k, KW, wu, uni);
   const unsigned tiles = nblocks(n, kTile);
+  DS_TRY(ds_kernel_mark(ctx, 1, 0));
   hipLaunchKernelGGL(gram_kernel, dim3(tiles, tiles), dim3(kThreads), 0, st, Zt, n, k, KW, wc, wu, uni, G);
+  DS_TRY(ds_kernel_mark(ctx, 1, 1));
   const unsigned wblocks = (unsigned)(((n * 64 + kThreads - 1) / kThreads) < (int64_t)ctx->num_cus * 8 ? ((n * 64 + kThreads - 1) / kThreads) : (int64_t)ctx->num_cus * 8);
   hipLaunchKernelGGL(rhs_kernel, dim3(wblocks), dim3(kThreads), 0, st, Zt, n, k, KW, wc, t, c);
   hipLaunchKernelGGL(row_mean_kernel, dim3(wblocks), dim3(kThreads), 0, st, G, n, m);
   hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(kThreads), 0, st, G, m, c, n, stats);
   hipLaunchKernelGGL(build_system_kernel, dim3(nblocks(n * n, 256)), dim3(256), 0, st, G, m, c, stats, n);
   DS_HIP(ctx, hipGetLastError());
+  DS_TRY(ds_kernel_mark(ctx, 2, 0));
   for (int64_t j0 = 0; j0 < n; j0 += NB) {
     const int nb = (int)(n - j0 < NB ? n - j0 : NB);
     hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, G, n, j0, nb, flag);
@@ -399,6 +402,7 @@ int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
       hipLaunchKernelGGL(chol_update_kernel, dim3(tt, tt), dim3(kThreads), 0, st, G, n, j0, nb);
     }
   }
+  DS_TRY(ds_kernel_mark(ctx, 2, 1));
   hipLaunchKernelGGL(chol_solve_kernel, dim3(1), dim3(kThreads), 0, st, G, n, c);
   hipLaunchKernelGGL(finish_phi_kernel, dim3(nblocks(n, 256)), dim3(256), 0, st, c, y, n, phi);
   DS_HIP(ctx, hipGetLastError());

@@ -58,6 +58,8 @@ struct ds_ctx {
   int64_t* h_mail;  // pinned host int64[64]
   int num_cus;
   hipEvent_t ev[6];
+  hipEvent_t kev[8];   // begin/end pairs: 0 masked inference, 1 Gram, 2 Cholesky, 3 CGLS loop
+  bool kev_set[4];
   std::vector<ds_cgraph*> graphs;
 };
 
@@ -82,6 +84,8 @@ int ds_arena_reserve(ds_ctx* ctx, size_t bytes);  // only when arena_used == 0
 void* ds_arena_alloc(ds_ctx* ctx, size_t bytes);  // nullptr when exhausted
 static inline void ds_arena_reset(ds_ctx* ctx) { ctx->arena_used = 0; }
 static inline size_t ds_align(size_t b) { return (b + 255) & ~(size_t)255; }
+// record the begin (end=0) or end (end=1) event of kernel slot `slot`
+int ds_kernel_mark(ds_ctx* ctx, int slot, int end);
 // copy `count` int64 values from the device mailbox to the host mailbox (synchronises)
 int ds_mail_fetch(ds_ctx* ctx, int count);
 

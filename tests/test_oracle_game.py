@@ -246,3 +246,28 @@ def test_sampled_estimate_approaches_exact_shapley():
         errs.append(np.mean(e))
     assert errs[1] < 0.5 * errs[0]
     assert errs[1] < 0.05 * np.abs(exact).max() + 1e-3
+
+
+def test_bf16_rounding_is_nearest_even():
+    # bfloat16 keeps 8 significand bits: spacing 2^-7 in [1, 2)
+    assert gcn.round_bf16(1.0) == 1.0
+    assert gcn.round_bf16(1.0 + 2.0 ** -8) == 1.0                    # tie -> even
+    assert gcn.round_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6    # tie -> even (up)
+    assert gcn.round_bf16(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7
+    assert gcn.round_bf16(-3.1415927) == -3.140625
+    x = np.random.default_rng(0).standard_normal(1000)
+    r = gcn.round_bf16(x)
+    assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8 * (1 + 1e-6))
+    assert np.array_equal(gcn.round_bf16(r), r)
+
+
+def test_bf16_mode_stays_close_to_full_precision():
+    w = make_workload("c2_small")
+    cg = compgraph.extract(w.row_ptr, w.col, w.targets[0], 3)
+    f64 = gcn.ValueFunction(cg, w.features, w.weights)
+    f16 = gcn.ValueFunction(cg, w.features, w.weights, bf16=True)
+    rng = np.random.default_rng(1)
+    for _ in range(4):
+        m = rng.random(cg["num_players"]) < 0.5
+        assert abs(f64(m) - f16(m)) < 2e-2
+        assert f64(m) != f16(m)
