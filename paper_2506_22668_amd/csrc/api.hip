@@ -294,7 +294,7 @@ static int solve_dispatch(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, 
   if (solver == DS_SOLVER_AUTO) solver = n <= 16384 ? DS_SOLVER_GRAM_CHOL : DS_SOLVER_CGLS;
   int rc = DS_OK;
   if (solver == DS_SOLVER_GRAM_CHOL) {
-    rc = ds_solve_gram_chol(ctx, n, k, Z, w, y, phi);
+    rc = ds_solve_gram_chol(ctx, n, k, Z, w, y, paired, phi);
     if (rc == DS_ESINGULAR && o.solver == DS_SOLVER_AUTO) solver = DS_SOLVER_CGLS;  // fall through to the minimum-norm solve
   }
   int iters = 0;

@@ -57,7 +57,43 @@ __global__ __launch_bounds__(kThreads) void bit_transpose_kernel(const uint64_t*
     if (c < cols) out[c * Wout + rb] = mine;
   }
 }
+// out[i] = sum over set bits j of row i of x[j]; one wave per row, lanes over words.
+__global__ __launch_bounds__(kThreads) void bit_spmv_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
+                                                            int64_t row_first, int64_t row_step, const double* x,
+                                                            double* out) {
+  const int64_t Wc = (cols + 63) / 64;
+  const uint64_t tail = (cols & 63) ? ((1ull << (cols & 63)) - 1ull) : ~0ull;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+  for (int64_t i = wave; i < rows; i += nwaves) {
+    const uint64_t* row = B + (row_first + i * row_step) * stride;
+    double acc = 0.0;
+    for (int64_t wd = lane; wd < Wc; wd += 64) {
+      uint64_t word = row[wd] & (wd == Wc - 1 ? tail : ~0ull);  // padding bits name no column
+      const double* xb = x + wd * 64;
+      while (word) {
+        acc += xb[__ffsll((long long)word) - 1];
+        word &= word - 1;
+      }
+    }
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (lane == 0) out[i] = acc;
+  }
+}
+
 }  // namespace
+
+int ds_bit_spmv(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
+                int64_t row_step, const double* x, double* out) {
+  if (rows <= 0) return DS_OK;
+  int64_t blocks = (rows * 64 + kThreads - 1) / kThreads;
+  if (blocks > (int64_t)ctx->num_cus * 8) blocks = (int64_t)ctx->num_cus * 8;
+  hipLaunchKernelGGL(bit_spmv_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, B, rows, cols, stride,
+                     row_first, row_step, x, out);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
 
 int ds_row_prep(ds_ctx* ctx, const uint64_t* Z, int64_t k, int64_t n, const float* w, const float* y, int32_t* sz,
                 double* t, double* sqw, float* wc) {

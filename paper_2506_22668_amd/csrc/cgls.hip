@@ -22,31 +22,6 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kRed = 256;  // blocks (and partials) of every reduction
 
-// out[i] = sum over set bits j of row i of x[j]; one wave per row, lanes over words.
-__global__ __launch_bounds__(kThreads) void bit_spmv_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
-                                                            int64_t row_first, int64_t row_step, const double* x,
-                                                            double* out) {
-  const int64_t Wc = (cols + 63) / 64;
-  const uint64_t tail = (cols & 63) ? ((1ull << (cols & 63)) - 1ull) : ~0ull;
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-  for (int64_t i = wave; i < rows; i += nwaves) {
-    const uint64_t* row = B + (row_first + i * row_step) * stride;
-    double acc = 0.0;
-    for (int64_t wd = lane; wd < Wc; wd += 64) {
-      uint64_t word = row[wd] & (wd == Wc - 1 ? tail : ~0ull);  // padding bits name no column
-      const double* xb = x + wd * 64;
-      while (word) {
-        acc += xb[__ffsll((long long)word) - 1];
-        word &= word - 1;
-      }
-    }
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if (lane == 0) out[i] = acc;
-  }
-}
-
 __device__ __forceinline__ void block_reduce2(double a, double b, double* pa, double* pb) {
   __shared__ double sh[2][kThreads / 64];
   for (int o = 32; o > 0; o >>= 1) {
@@ -253,15 +228,13 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   DS_HIP(ctx, hipMemsetAsync(a.u, 0, n * 8, st));
   DS_HIP(ctx, hipMemsetAsync(a.scal, 0, 64, st));
 
-  const unsigned gb = (unsigned)ctx->num_cus * 8;
   const unsigned red_n = nblocks(n, kThreads) < (unsigned)kRed ? nblocks(n, kThreads) : (unsigned)kRed;
   const unsigned red_r = nblocks(R, kThreads) < (unsigned)kRed ? nblocks(R, kThreads) : (unsigned)kRed;
-  auto spmv_rows = [&](unsigned rows) { int64_t b = ((int64_t)rows * 64 + kThreads - 1) / kThreads; return (unsigned)(b < gb ? (b < 1 ? 1 : b) : gb); };
 
   // s_0 = P A^T r_0, u_0 = s_0
   hipLaunchKernelGGL(init_r_kernel, dim3(nblocks(k, 256)), dim3(256), 0, st, a, t);
   hipLaunchKernelGGL(make_h_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
-  hipLaunchKernelGGL(bit_spmv_kernel, dim3(spmv_rows((unsigned)(n < 0x7fffffff ? n : 0x7fffffff))), dim3(kThreads), 0, st, Zt, n, R, RW, (int64_t)0, (int64_t)1, a.h, a.s);
+  DS_TRY(ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, a.h, a.s));
   hipLaunchKernelGGL(s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
   hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
   hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
@@ -277,11 +250,11 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   bool converged = !(gamma0 > 0);
   DS_TRY(ds_kernel_mark(ctx, 3, 0));
   while (!converged && it < max_iter) {
-    hipLaunchKernelGGL(bit_spmv_kernel, dim3(spmv_rows((unsigned)R)), dim3(kThreads), 0, st, Z, R, n, W, (int64_t)0, (int64_t)(paired ? 2 : 1), a.u, a.d);
+    DS_TRY(ds_bit_spmv(ctx, Z, R, n, W, 0, paired ? 2 : 1, a.u, a.d));
     hipLaunchKernelGGL(make_v_kernel, dim3(red_r), dim3(kThreads), 0, st, a);
     hipLaunchKernelGGL(fin_delta_kernel, dim3(1), dim3(1), 0, st, a, (int)red_r);
     hipLaunchKernelGGL(update_r_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
-    hipLaunchKernelGGL(bit_spmv_kernel, dim3(spmv_rows((unsigned)n)), dim3(kThreads), 0, st, Zt, n, R, RW, (int64_t)0, (int64_t)1, a.h, a.s);
+    DS_TRY(ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, a.h, a.s));
     hipLaunchKernelGGL(s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
     hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
     hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);

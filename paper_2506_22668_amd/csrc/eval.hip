@@ -86,16 +86,34 @@ __device__ __forceinline__ void aggregate_rows(const EvalArgs& a, const uint64_t
           coef = rs[srcn];
         }
         unsigned long long mask = __ballot(bit);
+        // four active entries per step: their row loads are independent and issue back to back
         while (mask) {
-          const int i = __ffsll((long long)mask) - 1;
-          mask &= mask - 1;
-          const int s = readlane_i(srcn, i);
-          const float c = readlane_f(coef, i);
-          const float* sp = src + (size_t)s * stride + f;
-          if (h0) acc0 += c * sp[0];
-          if (h1) acc1 += c * sp[64];
-          if (h2) acc2 += c * sp[128];
-          if (h3) acc3 += c * sp[192];
+          int idx[4];
+          float cf[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const bool live = mask != 0ull;
+            const int i = live ? __ffsll((long long)mask) - 1 : 0;
+            if (live) mask &= mask - 1;
+            idx[u] = readlane_i(srcn, i);
+            cf[u] = live ? readlane_f(coef, i) : 0.f;
+          }
+          float v0[4], v1[4], v2[4], v3[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float* sp = src + (size_t)idx[u] * stride + f;
+            v0[u] = h0 ? sp[0] : 0.f;
+            v1[u] = h1 ? sp[64] : 0.f;
+            v2[u] = h2 ? sp[128] : 0.f;
+            v3[u] = h3 ? sp[192] : 0.f;
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            acc0 += cf[u] * v0[u];
+            acc1 += cf[u] * v1[u];
+            acc2 += cf[u] * v2[u];
+            acc3 += cf[u] * v3[u];
+          }
         }
       }
       const float* sp = src + (size_t)t * stride + f;

@@ -20,6 +20,22 @@ constexpr int kThreads = 256;
 constexpr int kTile = 64;
 constexpr int kChunk = 32;  // 64-row words per LDS chunk
 
+// which rows enter the sums, with which weight and right-hand-side coefficient.
+// Paired rows (2r, 2r+1 complementary, one weight w): z z^T + zc zc^T = 2 z z^T - z 1^T - 1 z^T + 11^T and
+// t z + tc zc = (t - tc) z + tc 1; the terms with 1 vanish under the projection P, so only the small
+// member is used, with weight 2w and coefficient w (t_2r - t_2r+1). Otherwise every row is used.
+__global__ void used_rows_kernel(const float* wc, const double* t, int64_t R, int paired, float* gw, double* gc) {
+  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= R) return;
+  if (paired) {
+    gw[r] = 2.0f * wc[2 * r];
+    gc[r] = (double)wc[2 * r] * (t[2 * r] - t[2 * r + 1]);
+  } else {
+    gw[r] = wc[r];
+    gc[r] = (double)wc[r] * t[r];
+  }
+}
+
 // per word of 64 rows: the common weight, or non-uniform
 __global__ void word_weights_kernel(const float* w, int64_t k, int64_t KW, float* wu, int32_t* uni) {
   const int64_t wd = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -35,8 +51,11 @@ __global__ void word_weights_kernel(const float* w, int64_t k, int64_t KW, float
   uni[wd] = same;
 }
 
+// One 64x64 tile of G per workgroup and slice of the row words (split-K); each slice
+// writes its own full symmetric partial matrix, summed later in a fixed order.
 __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int64_t n, int64_t k, int64_t KW,
-                                                        const float* w, const float* wu, const int32_t* uni, double* G) {
+                                                        const float* w, const float* wu, const int32_t* uni,
+                                                        double* Gp, int64_t words_per_slice) {
   const int ta = blockIdx.y, tb = blockIdx.x;
   if (tb > ta) return;
   __shared__ uint64_t As[kTile][kChunk + 1];
@@ -46,16 +65,19 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
   __shared__ int unis[kChunk];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const int64_t a0 = (int64_t)ta * kTile, b0 = (int64_t)tb * kTile;
+  double* G = Gp + (size_t)blockIdx.z * n * n;
+  const int64_t wbeg = (int64_t)blockIdx.z * words_per_slice;
+  const int64_t wend = wbeg + words_per_slice < KW ? wbeg + words_per_slice : KW;
   double acc[4][4];
   for (int i = 0; i < 4; ++i)
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
-  for (int64_t wd0 = 0; wd0 < KW; wd0 += kChunk) {
+  for (int64_t wd0 = wbeg; wd0 < wend; wd0 += kChunk) {
     __syncthreads();
     for (int idx = tid; idx < kTile * kChunk; idx += kThreads) {
       const int r = idx / kChunk, c = idx - r * kChunk;
       const int64_t wd = wd0 + c;
-      As[r][c] = (a0 + r < n && wd < KW) ? Zt[(a0 + r) * KW + wd] : 0ull;
-      Bs[r][c] = (b0 + r < n && wd < KW) ? Zt[(b0 + r) * KW + wd] : 0ull;
+      As[r][c] = (a0 + r < n && wd < wend) ? Zt[(a0 + r) * KW + wd] : 0ull;
+      Bs[r][c] = (b0 + r < n && wd < wend) ? Zt[(b0 + r) * KW + wd] : 0ull;
     }
     for (int idx = tid; idx < kChunk * 64; idx += kThreads) {
       const int64_t i = wd0 * 64 + idx;
@@ -63,8 +85,8 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
     }
     if (tid < kChunk) {
       const int64_t wd = wd0 + tid;
-      wus[tid] = wd < KW ? wu[wd] : 0.f;
-      unis[tid] = wd < KW ? uni[wd] : 1;
+      wus[tid] = wd < wend ? wu[wd] : 0.f;
+      unis[tid] = wd < wend ? uni[wd] : 1;
     }
     __syncthreads();
     float f[4][4];
@@ -112,32 +134,19 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
     }
 }
 
-// c_j = sum_i w_i t_i z_ij, one wave per column of the transposed matrix
-__global__ __launch_bounds__(kThreads) void rhs_kernel(const uint64_t* Zt, int64_t n, int64_t k, int64_t KW,
-                                                       const float* w, const double* t, double* c) {
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-  for (int64_t j = wave; j < n; j += nwaves) {
-    double s = 0.0;
-    for (int64_t wd = 0; wd < KW; ++wd) {
-      const uint64_t word = Zt[j * KW + wd];
-      const int64_t i = wd * 64 + lane;
-      if (i < k && ((word >> lane) & 1ull)) s += (double)w[i] * t[i];
-    }
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    if (lane == 0) c[j] = s;
-  }
-}
-
-// row means of G
-__global__ __launch_bounds__(kThreads) void row_mean_kernel(const double* G, int64_t n, double* m) {
+// G = sum of the slices (into slice 0) and the row means of G; one wave per row
+__global__ __launch_bounds__(kThreads) void sum_slices_row_mean_kernel(double* Gp, int64_t n, int slices, double* m) {
   const int lane = threadIdx.x & 63;
   const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
   for (int64_t a = wave; a < n; a += nwaves) {
     double s = 0.0;
-    for (int64_t b = lane; b < n; b += 64) s += G[a * n + b];
+    for (int64_t b = lane; b < n; b += 64) {
+      double g = Gp[a * n + b];
+      for (int z = 1; z < slices; ++z) g += Gp[(size_t)z * n * n + a * n + b];
+      Gp[a * n + b] = g;
+      s += g;
+    }
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
     if (lane == 0) m[a] = s / (double)n;
   }
@@ -170,8 +179,12 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(const double* G, const 
   }
 }
 
-// A = P G P + gamma 11^T / n in place; rhs = c - mean(c). gamma = trace(PGP)/(n-1).
-__global__ void build_system_kernel(double* G, const double* m, double* c, const double* stats, int64_t n) {
+// The system in one (n+1) x ld array M: rows 0..n-1 = A = P G P + gamma 11^T / n (lower triangle is
+// what the factorisation reads), row n = the right-hand side c - mean(c). Factorising with row n carried
+// along as an ordinary sub-diagonal row leaves L^-1 rhs in it (the forward solve comes for free).
+// gamma = trace(PGP)/(n-1) keeps the added direction at the scale of the other eigenvalues.
+__global__ void build_system_kernel(const double* G, const double* m, const double* c, const double* stats, int64_t n,
+                                    int64_t ld, double* M) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const double mu = stats[0];
   const double tr = stats[1] - (double)n * mu;
@@ -179,74 +192,107 @@ __global__ void build_system_kernel(double* G, const double* m, double* c, const
   if (!(gamma > 0.0)) gamma = 1.0;
   if (idx < n * n) {
     const int64_t a = idx / n, b = idx - a * n;
-    G[idx] = G[idx] - m[a] - m[b] + mu + gamma / (double)n;
+    M[a * ld + b] = G[idx] - m[a] - m[b] + mu + gamma / (double)n;
   }
-  if (idx < n) c[idx] -= stats[2];
+  if (idx < n) M[n * ld + idx] = c[idx] - stats[2];
 }
 
 // ---------------- blocked Cholesky (lower, in place, fp64) ----------------
 constexpr int NB = 64;
 
-__global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* A, int64_t n, int64_t j0, int nb, int* flag) {
-  __shared__ double S[NB][NB + 1];
-  for (int idx = threadIdx.x; idx < NB * NB; idx += kThreads) {
-    const int r = idx / NB, c = idx - r * NB;
-    S[r][c] = (r < nb && c < nb) ? A[(j0 + r) * n + j0 + c] : (r == c ? 1.0 : 0.0);
-  }
-  __syncthreads();
-  for (int kk = 0; kk < nb; ++kk) {
-    if (threadIdx.x == 0) {
-      double p = S[kk][kk];
-      if (!(p > 0.0)) {
-        atomicExch(flag, 1);
-        p = 1.0;
-      }
-      S[kk][kk] = sqrt(p);
-    }
-    __syncthreads();
-    const double d = S[kk][kk];
-    for (int r = kk + 1 + threadIdx.x; r < nb; r += kThreads) S[r][kk] /= d;
-    __syncthreads();
-    const int rem = nb - kk - 1;
-    for (int idx = threadIdx.x; idx < rem * rem; idx += kThreads) {
-      const int r = kk + 1 + idx / rem, c = kk + 1 + idx % rem;
-      if (c <= r) S[r][c] -= S[r][kk] * S[c][kk];
-    }
-    __syncthreads();
-  }
-  for (int idx = threadIdx.x; idx < NB * NB; idx += kThreads) {
-    const int r = idx / NB, c = idx - r * NB;
-    if (r < nb && c <= r) A[(j0 + r) * n + j0 + c] = S[r][c];
-  }
+__device__ __forceinline__ double readlane_d(double v, int l) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+  return __hiloint2double(hi, lo);
 }
 
-// rows below the diagonal block: X L11^T = A21, one thread per row
-__global__ __launch_bounds__(64) void chol_panel_kernel(double* A, int64_t n, int64_t j0, int nb) {
-  __shared__ double Ls[NB][NB + 1];
-  for (int idx = threadIdx.x; idx < NB * NB; idx += 64) {
-    const int r = idx / NB, c = idx - r * NB;
-    Ls[r][c] = (r < nb && c <= r) ? A[(j0 + r) * n + j0 + c] : (r == c ? 1.0 : 0.0);
+// Factor the nb x nb diagonal block at j0 and invert the factor, in one wave with no barriers:
+// lane r keeps row r of the block in registers (the loops are fully unrolled, so every column
+// index is a register name); column kk is scaled by 1/sqrt(pivot) and the trailing columns take
+// a rank-1 update whose second factor comes from lane c by a lane read. The inverse X = L^-1 is
+// built the same way with lane c holding column c of X: X[r][c] = (d_rc - sum_{m<r} L[r][m] X[m][c]) / L[r][r].
+// Linv (NB x NB, identity-padded) goes to linv_out.
+__global__ __launch_bounds__(64) void chol_diag_kernel(double* M, int64_t ld, int64_t j0, int nb, double* linv_out,
+                                                       int* flag) {
+  __shared__ double S[NB][NB + 1];
+  const int lane = threadIdx.x;
+  for (int idx = lane; idx < NB * NB; idx += 64) {
+    const int r = idx >> 6, c = idx & 63;
+    S[r][c] = (r < nb && c < nb) ? M[(j0 + r) * ld + j0 + c] : (r == c ? 1.0 : 0.0);
   }
   __syncthreads();
-  const int64_t i = j0 + nb + (int64_t)blockIdx.x * 64 + threadIdx.x;
-  if (i >= n) return;
+  double a[NB];
+#pragma unroll
+  for (int c = 0; c < NB; ++c) a[c] = S[lane][c];
+  bool bad = false;
+#pragma unroll
+  for (int kk = 0; kk < NB; ++kk) {
+    double p = readlane_d(a[kk], kk);
+    if (!(p > 0.0)) {
+      bad = true;
+      p = 1.0;
+    }
+    const double rinv = 1.0 / sqrt(p);
+    const double l = a[kk] * rinv;
+    a[kk] = l;
+#pragma unroll
+    for (int c = kk + 1; c < NB; ++c) a[c] -= l * readlane_d(l, c);
+  }
+  if (bad && lane == 0) atomicExch(flag, 1);
   double x[NB];
 #pragma unroll
-  for (int c = 0; c < NB; ++c) x[c] = c < nb ? A[i * n + j0 + c] : 0.0;
+  for (int r = 0; r < NB; ++r) {
+    double s = (lane == r) ? 1.0 : 0.0;
 #pragma unroll
-  for (int c = 0; c < NB; ++c) {
-    double v = x[c];
-#pragma unroll
-    for (int m = 0; m < c; ++m) v -= x[m] * Ls[c][m];
-    x[c] = v / Ls[c][c];
+    for (int m = 0; m < r; ++m) s -= readlane_d(a[m], r) * x[m];
+    x[r] = s / readlane_d(a[r], r);
   }
 #pragma unroll
   for (int c = 0; c < NB; ++c)
-    if (c < nb) A[i * n + j0 + c] = x[c];
+    if (lane < nb && c <= lane) M[(j0 + lane) * ld + j0 + c] = a[c];
+#pragma unroll
+  for (int r = 0; r < NB; ++r) linv_out[r * NB + lane] = x[r];
 }
 
-// trailing update A22 -= L21 L21^T on the lower tiles
-__global__ __launch_bounds__(kThreads) void chol_update_kernel(double* A, int64_t n, int64_t j0, int nb) {
+// rows below the diagonal block: X = A21 L11^-T = A21 Linv^T, a 64x64 product per workgroup
+__global__ __launch_bounds__(kThreads) void chol_panel_kernel(double* M, int64_t ld, int64_t rows_total, int64_t j0,
+                                                              int nb, const double* linv) {
+  __shared__ double As[kTile][NB + 1];
+  __shared__ double Ls[NB][NB + 1];
+  const int64_t i0 = j0 + nb + (int64_t)blockIdx.x * kTile;
+  for (int idx = threadIdx.x; idx < kTile * NB; idx += kThreads) {
+    const int r = idx >> 6, c = idx & 63;
+    As[r][c] = (i0 + r < rows_total && c < nb) ? M[(i0 + r) * ld + j0 + c] : 0.0;
+    Ls[r][c] = linv[idx];
+  }
+  __syncthreads();
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  double acc[4][4];
+  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+  for (int m = 0; m < NB; ++m) {
+    double a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a[i] = As[ty + 16 * i][m];
+      b[i] = Ls[tx + 16 * i][m];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+  }
+  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 4; ++j) {
+      const int64_t r = i0 + ty + 16 * i;
+      const int c = tx + 16 * j;
+      if (r < rows_total && c < nb) M[r * ld + j0 + c] = acc[i][j];
+    }
+}
+
+// trailing update A22 -= L21 L21^T on the lower tiles (rows up to rows_total, columns below n)
+__global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_t ld, int64_t rows_total, int64_t n,
+                                                               int64_t j0, int nb) {
   const int ti = blockIdx.y, tj = blockIdx.x;
   if (tj > ti) return;
   __shared__ double Li[kTile][NB + 1];
@@ -254,9 +300,9 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* A, int64_
   const int64_t base = j0 + nb;
   const int64_t i0 = base + (int64_t)ti * kTile, c0 = base + (int64_t)tj * kTile;
   for (int idx = threadIdx.x; idx < kTile * NB; idx += kThreads) {
-    const int r = idx / NB, c = idx - r * NB;
-    Li[r][c] = (i0 + r < n && c < nb) ? A[(i0 + r) * n + j0 + c] : 0.0;
-    Lj[r][c] = (c0 + r < n && c < nb) ? A[(c0 + r) * n + j0 + c] : 0.0;
+    const int r = idx >> 6, c = idx & 63;
+    Li[r][c] = (i0 + r < rows_total && c < nb) ? M[(i0 + r) * ld + j0 + c] : 0.0;
+    Lj[r][c] = (c0 + r < n && c < nb) ? M[(c0 + r) * ld + j0 + c] : 0.0;
   }
   __syncthreads();
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -278,133 +324,147 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* A, int64_
   for (int i = 0; i < 4; ++i)
     for (int j = 0; j < 4; ++j) {
       const int64_t r = i0 + ty + 16 * i, c = c0 + tx + 16 * j;
-      if (r < n && c <= r) A[r * n + c] -= acc[i][j];
+      if (r < rows_total && c < n && c <= r) M[r * ld + c] -= acc[i][j];
     }
 }
 
-// L y = b then L^T x = y, single workgroup, blocked by NB; b is overwritten by x.
-__global__ __launch_bounds__(kThreads) void chol_solve_kernel(const double* A, int64_t n, double* b) {
-  __shared__ double Ls[NB][NB + 1];
+// L^T psi = y (y = row n of M after the factorisation), block by block from the end, using
+// the stored inverses of the diagonal blocks; single workgroup. psi -> out, then phi.
+constexpr int kSolveThreads = 1024;
+__global__ __launch_bounds__(kSolveThreads) void chol_back_solve_kernel(const double* M, int64_t ld, int64_t n,
+                                                                        const double* linv_all, double* yv,
+                                                                        const float* y01, float* phi) {
+  __shared__ double Xs[NB][NB + 1];
+  __shared__ double yb[NB];
   __shared__ double xs[NB];
   const int tid = threadIdx.x;
-  // forward
-  for (int64_t j0 = 0; j0 < n; j0 += NB) {
-    const int nb = (int)(n - j0 < NB ? n - j0 : NB);
-    for (int idx = tid; idx < NB * NB; idx += kThreads) {
-      const int r = idx / NB, c = idx - r * NB;
-      Ls[r][c] = (r < nb && c <= r) ? A[(j0 + r) * n + j0 + c] : (r == c ? 1.0 : 0.0);
-    }
-    __syncthreads();
-    if (tid < 64) {
-      double v = tid < nb ? b[j0 + tid] : 0.0;
-      for (int c = 0; c < nb; ++c) {
-        const double piv = __shfl(v, c, 64) / Ls[c][c];
-        if (tid == c) v = piv;
-        if (tid > c) v -= Ls[tid][c] * piv;
-      }
-      xs[tid] = v;
-      if (tid < nb) b[j0 + tid] = v;
-    }
-    __syncthreads();
-    for (int64_t i = j0 + nb + tid; i < n; i += kThreads) {
-      double s = 0.0;
-      for (int c = 0; c < nb; ++c) s += A[i * n + j0 + c] * xs[c];
-      b[i] -= s;
-    }
-    __syncthreads();
-  }
-  // backward
+  for (int64_t j = tid; j < n; j += kSolveThreads) yv[j] = M[n * ld + j];
+  __syncthreads();
   const int64_t nblk = (n + NB - 1) / NB;
   for (int64_t bk = nblk - 1; bk >= 0; --bk) {
     const int64_t j0 = bk * NB;
     const int nb = (int)(n - j0 < NB ? n - j0 : NB);
-    for (int idx = tid; idx < NB * NB; idx += kThreads) {
-      const int r = idx / NB, c = idx - r * NB;
-      Ls[r][c] = (r < nb && c <= r) ? A[(j0 + r) * n + j0 + c] : (r == c ? 1.0 : 0.0);
-    }
+    const double* linv = linv_all + (size_t)bk * NB * NB;
+    for (int idx = tid; idx < NB * NB; idx += kSolveThreads) Xs[idx >> 6][idx & 63] = linv[idx];
+    if (tid < NB) yb[tid] = tid < nb ? yv[j0 + tid] : 0.0;
     __syncthreads();
-    if (tid < 64) {
-      double v = tid < nb ? b[j0 + tid] : 0.0;
-      for (int c = nb - 1; c >= 0; --c) {
-        const double piv = __shfl(v, c, 64) / Ls[c][c];
-        if (tid == c) v = piv;
-        if (tid < c) v -= Ls[c][tid] * piv;
-      }
-      xs[tid] = v;
-      if (tid < nb) b[j0 + tid] = v;
-    }
-    __syncthreads();
-    for (int64_t j = tid; j < j0; j += kThreads) {
+    // psi_c = sum_{r >= c} Linv[r][c] y_r : 16 threads per c
+    {
+      const int c = tid >> 4, part = tid & 15;
       double s = 0.0;
-      for (int r = 0; r < nb; ++r) s += A[(j0 + r) * n + j] * xs[r];
-      b[j] -= s;
+      for (int r = c + part; r < NB; r += 16) s += Xs[r][c] * yb[r];
+      for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      if (part == 0) xs[c] = s;
+    }
+    __syncthreads();
+    if (tid < nb) yv[j0 + tid] = xs[tid];
+    for (int64_t j = tid; j < j0; j += kSolveThreads) {
+      double s = 0.0;
+      for (int r = 0; r < nb; ++r) s += M[(j0 + r) * ld + j] * xs[r];
+      yv[j] -= s;
     }
     __syncthreads();
   }
-}
-
-__global__ void finish_phi_kernel(const double* psi, const float* y, int64_t n, float* phi) {
-  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= n) return;
-  const double delta = (double)y[1] - (double)y[0];
-  phi[j] = (float)(psi[j] + delta / (double)n);
+  const double delta = (double)y01[1] - (double)y01[0];
+  for (int64_t j = tid; j < n; j += kSolveThreads) phi[j] = (float)(yv[j] + delta / (double)n);
 }
 
 inline unsigned nblocks(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
+struct GramDims {
+  int64_t R, RW, ld, nblk;
+  int slices;
+  int64_t words_per_slice;
+};
+
+GramDims gram_dims(int64_t n, int64_t k, int paired, int num_cus) {
+  GramDims d;
+  d.R = paired ? k / 2 : k;
+  d.RW = (d.R + 63) / 64;
+  d.ld = (n + 1 + 7) & ~(int64_t)7;
+  d.nblk = (n + NB - 1) / NB;
+  const int64_t tiles = (n + kTile - 1) / kTile;
+  const int64_t lower = tiles * (tiles + 1) / 2;
+  if (num_cus > 256) num_cus = 256;
+  int64_t s = (2 * (int64_t)num_cus + lower - 1) / lower;
+  const int64_t chunks = (d.RW + kChunk - 1) / kChunk;
+  if (s > chunks) s = chunks;
+  if (s > 16) s = 16;
+  if (s < 1) s = 1;
+  const int64_t cps = (chunks + s - 1) / s;  // chunks per slice
+  d.words_per_slice = cps * kChunk;
+  d.slices = (int)((chunks + cps - 1) / cps);
+  return d;
+}
+
 }  // namespace
 
 size_t ds_gram_arena_bytes(int64_t n, int64_t k) {
-  const int64_t KW = (k + 63) / 64;
-  return ds_align((size_t)n * KW * 8) + ds_align((size_t)n * n * 8) + 2 * ds_align(k * 4) + 2 * ds_align(k * 8) +
-         ds_align(KW * 4) * 2 + 3 * ds_align(n * 8) + 4096;
+  const GramDims d = gram_dims(n, k, 0, 256);  // the unpaired layout is the larger one
+  const GramDims dp = gram_dims(n, k, 1, 256);
+  const size_t slices = (size_t)(d.slices > dp.slices ? d.slices : dp.slices) + 1;  // +1: CU counts differ a little
+  return ds_align((size_t)n * d.RW * 8) + ds_align(slices * (size_t)n * n * 8) + ds_align((size_t)(n + 1) * d.ld * 8) +
+         ds_align((size_t)d.nblk * NB * NB * 8) + 2 * ds_align(k * 4) + 2 * ds_align(k * 8) + ds_align(k * 4) +
+         ds_align(k * 8) + ds_align(d.RW * 4) * 2 + 4 * ds_align(n * 8) + 8192;
 }
 
-int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y, float* phi) {
+int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y, int paired,
+                       float* phi) {
   hipStream_t st = ctx->stream;
-  const int64_t KW = (k + 63) / 64, W = (n + 63) / 64;
-  uint64_t* Zt = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * KW * 8);
-  double* G = (double*)ds_arena_alloc(ctx, (size_t)n * n * 8);
+  if (paired && (k & 1)) return ds_fail(ctx, DS_EINVAL, "paired rows need an even row count");
+  const int64_t W = (n + 63) / 64;
+  const GramDims d = gram_dims(n, k, paired, ctx->num_cus);
+  const int64_t R = d.R, RW = d.RW, ld = d.ld;
+  uint64_t* Zt = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * RW * 8);
+  double* Gp = (double*)ds_arena_alloc(ctx, (size_t)d.slices * n * n * 8);
+  double* M = (double*)ds_arena_alloc(ctx, (size_t)(n + 1) * ld * 8);
+  double* linv = (double*)ds_arena_alloc(ctx, (size_t)d.nblk * NB * NB * 8);
   int32_t* sz = (int32_t*)ds_arena_alloc(ctx, k * 4);
   float* wc = (float*)ds_arena_alloc(ctx, k * 4);
   double* t = (double*)ds_arena_alloc(ctx, k * 8);
   double* sqw = (double*)ds_arena_alloc(ctx, k * 8);
-  float* wu = (float*)ds_arena_alloc(ctx, KW * 4);
-  int32_t* uni = (int32_t*)ds_arena_alloc(ctx, KW * 4);
+  float* gw = (float*)ds_arena_alloc(ctx, R * 4);
+  double* gc = (double*)ds_arena_alloc(ctx, R * 8);
+  float* wu = (float*)ds_arena_alloc(ctx, RW * 4);
+  int32_t* uni = (int32_t*)ds_arena_alloc(ctx, RW * 4);
   double* c = (double*)ds_arena_alloc(ctx, n * 8);
   double* m = (double*)ds_arena_alloc(ctx, n * 8);
+  double* yv = (double*)ds_arena_alloc(ctx, n * 8);
   double* stats = (double*)ds_arena_alloc(ctx, 64);
   int* flag = (int*)ds_arena_alloc(ctx, 64);
-  if (!Zt || !G || !sz || !wc || !t || !sqw || !wu || !uni || !c || !m || !stats || !flag)
+  if (!Zt || !Gp || !M || !linv || !sz || !wc || !t || !sqw || !gw || !gc || !wu || !uni || !c || !m || !yv || !stats || !flag)
     return ds_fail(ctx, DS_EINTERNAL, "gram: arena exhausted");
   DS_HIP(ctx, hipMemsetAsync(flag, 0, sizeof(int), st));
   DS_TRY(ds_row_prep(ctx, Z, k, n, w, y, sz, t, sqw, wc));
-  DS_TRY(ds_bit_transpose(ctx, Z, k, n, W, 0, 1, Zt));
-  hipLaunchKernelGGL(word_weights_kernel, dim3(nblocks(KW, 256)), dim3(256), 0, st, wc, k, KW, wu, uni);
+  hipLaunchKernelGGL(used_rows_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, wc, t, R, paired, gw, gc);
+  DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, Zt));
+  hipLaunchKernelGGL(word_weights_kernel, dim3(nblocks(RW, 256)), dim3(256), 0, st, gw, R, RW, wu, uni);
   const unsigned tiles = nblocks(n, kTile);
   DS_TRY(ds_kernel_mark(ctx, 1, 0));
-  hipLaunchKernelGGL(gram_kernel, dim3(tiles, tiles), dim3(kThreads), 0, st, Zt, n, k, KW, wc, wu, uni, G);
+  hipLaunchKernelGGL(gram_kernel, dim3(tiles, tiles, d.slices), dim3(kThreads), 0, st, Zt, n, R, RW, gw, wu, uni, Gp,
+                     d.words_per_slice);
   DS_TRY(ds_kernel_mark(ctx, 1, 1));
+  DS_TRY(ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, gc, c));  // c_j = sum over the rows containing j of gc
   const unsigned wblocks = (unsigned)(((n * 64 + kThreads - 1) / kThreads) < (int64_t)ctx->num_cus * 8 ? ((n * 64 + kThreads - 1) / kThreads) : (int64_t)ctx->num_cus * 8);
-  hipLaunchKernelGGL(rhs_kernel, dim3(wblocks), dim3(kThreads), 0, st, Zt, n, k, KW, wc, t, c);
-  hipLaunchKernelGGL(row_mean_kernel, dim3(wblocks), dim3(kThreads), 0, st, G, n, m);
-  hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(kThreads), 0, st, G, m, c, n, stats);
-  hipLaunchKernelGGL(build_system_kernel, dim3(nblocks(n * n, 256)), dim3(256), 0, st, G, m, c, stats, n);
+  hipLaunchKernelGGL(sum_slices_row_mean_kernel, dim3(wblocks), dim3(kThreads), 0, st, Gp, n, d.slices, m);
+  hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(kThreads), 0, st, Gp, m, c, n, stats);
+  hipLaunchKernelGGL(build_system_kernel, dim3(nblocks(n * n, 256)), dim3(256), 0, st, Gp, m, c, stats, n, ld, M);
   DS_HIP(ctx, hipGetLastError());
   DS_TRY(ds_kernel_mark(ctx, 2, 0));
+  const int64_t rows_total = n + 1;  // row n carries the right-hand side
   for (int64_t j0 = 0; j0 < n; j0 += NB) {
     const int nb = (int)(n - j0 < NB ? n - j0 : NB);
-    hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, G, n, j0, nb, flag);
-    const int64_t rest = n - j0 - nb;
-    if (rest > 0) {
-      hipLaunchKernelGGL(chol_panel_kernel, dim3(nblocks(rest, 64)), dim3(64), 0, st, G, n, j0, nb);
+    double* li = linv + (size_t)(j0 / NB) * NB * NB;
+    hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(64), 0, st, M, ld, j0, nb, li, flag);
+    const int64_t rest = rows_total - j0 - nb;
+    hipLaunchKernelGGL(chol_panel_kernel, dim3(nblocks(rest, kTile)), dim3(kThreads), 0, st, M, ld, rows_total, j0, nb, li);
+    if (n - j0 - nb > 0) {
       const unsigned tt = nblocks(rest, kTile);
-      hipLaunchKernelGGL(chol_update_kernel, dim3(tt, tt), dim3(kThreads), 0, st, G, n, j0, nb);
+      hipLaunchKernelGGL(chol_update_kernel, dim3(tt, tt), dim3(kThreads), 0, st, M, ld, rows_total, n, j0, nb);
     }
   }
   DS_TRY(ds_kernel_mark(ctx, 2, 1));
-  hipLaunchKernelGGL(chol_solve_kernel, dim3(1), dim3(kThreads), 0, st, G, n, c);
-  hipLaunchKernelGGL(finish_phi_kernel, dim3(nblocks(n, 256)), dim3(256), 0, st, c, y, n, phi);
+  hipLaunchKernelGGL(chol_back_solve_kernel, dim3(1), dim3(kSolveThreads), 0, st, M, ld, n, linv, yv, y, phi);
   DS_HIP(ctx, hipGetLastError());
   DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, flag, sizeof(int), hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipStreamSynchronize(st));

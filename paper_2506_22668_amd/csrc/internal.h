@@ -113,7 +113,7 @@ int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg);  // shared first transform + p
 size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
 
 int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
-                       float* phi);
+                       int paired, float* phi);
 size_t ds_gram_arena_bytes(int64_t n, int64_t k);
 int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
                        int paired, double tol, int max_iter, float* phi, int* iters, double* relres);

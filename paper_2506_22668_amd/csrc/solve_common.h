@@ -9,3 +9,6 @@ int ds_row_prep(ds_ctx* ctx, const uint64_t* Z, int64_t k, int64_t n, const floa
 // out[cols x ceil(rows/64)] = transpose of the rows row_first + i*row_step (i < rows) of `in`
 int ds_bit_transpose(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols, int64_t in_stride, int64_t row_first,
                      int64_t row_step, uint64_t* out);
+// out[i] = sum of x[j] over the set bits j < cols of row (row_first + i*row_step) of B, i < rows (fp64)
+int ds_bit_spmv(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
+                int64_t row_step, const double* x, double* out);
