@@ -57,28 +57,80 @@ __global__ __launch_bounds__(kThreads) void bit_transpose_kernel(const uint64_t*
     if (c < cols) out[c * Wout + rb] = mine;
   }
 }
-// out[i] = sum over set bits j of row i of x[j]; one wave per row, lanes over words.
+// out[i] = sum over the set bits j of row i of x[j] (fp64).
+// The vector is staged through LDS in chunks of 8192 columns, so the one gather per set bit is an
+// LDS read instead of an L2 transaction; the matrix is streamed once, each (row, chunk) segment
+// being 1 KB of contiguous words. A wave owns 16 rows and keeps their partial sums in registers
+// across all chunks (one cross-lane reduction per row at the very end); per chunk it first loads
+// the two words of each of its rows into registers (16 independent row loads in flight), then walks
+// their set bits. The LDS copy is pitched 65 doubles per 64-column word to spread the banks.
+constexpr int kSpmvChunkWords = 128;
+constexpr int kSpmvRowsPerWave = 16;
+constexpr int kSpmvPitch = 65;
+
 __global__ __launch_bounds__(kThreads) void bit_spmv_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
                                                             int64_t row_first, int64_t row_step, const double* x,
                                                             double* out) {
+  __shared__ double xs[kSpmvChunkWords * kSpmvPitch];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t Wc = (cols + 63) / 64;
   const uint64_t tail = (cols & 63) ? ((1ull << (cols & 63)) - 1ull) : ~0ull;
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-  for (int64_t i = wave; i < rows; i += nwaves) {
-    const uint64_t* row = B + (row_first + i * row_step) * stride;
-    double acc = 0.0;
-    for (int64_t wd = lane; wd < Wc; wd += 64) {
-      uint64_t word = row[wd] & (wd == Wc - 1 ? tail : ~0ull);  // padding bits name no column
-      const double* xb = x + wd * 64;
-      while (word) {
-        acc += xb[__ffsll((long long)word) - 1];
-        word &= word - 1;
+  // blocks walk the rows from the end: mask rows are sorted by size, so the long (dense) rows start first
+  const int64_t row0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * (kSpmvRowsPerWave * (kThreads / 64)) + (int64_t)wave * kSpmvRowsPerWave;
+  double acc[kSpmvRowsPerWave];
+#pragma unroll
+  for (int i = 0; i < kSpmvRowsPerWave; ++i) acc[i] = 0.0;
+  const double* xa = xs + (2 * lane) * kSpmvPitch;
+  const double* xb = xs + (2 * lane + 1) * kSpmvPitch;
+  for (int64_t c0 = 0; c0 < Wc; c0 += kSpmvChunkWords) {
+    __syncthreads();
+    for (int i = tid; i < kSpmvChunkWords * 64; i += kThreads) {
+      const int64_t col = c0 * 64 + i;
+      xs[(i >> 6) * kSpmvPitch + (i & 63)] = col < cols ? x[col] : 0.0;
+    }
+    __syncthreads();
+    const int64_t wa = c0 + 2 * lane, wb = wa + 1;
+    uint64_t w0[kSpmvRowsPerWave], w1[kSpmvRowsPerWave];
+#pragma unroll
+    for (int i = 0; i < kSpmvRowsPerWave; ++i) {
+      const int64_t r = row0 + i;
+      w0[i] = 0ull;
+      w1[i] = 0ull;
+      if (r < rows) {
+        const uint64_t* p = B + (row_first + r * row_step) * stride;
+        if (wa < Wc) w0[i] = p[wa] & (wa == Wc - 1 ? tail : ~0ull);  // padding bits name no column
+        if (wb < Wc) w1[i] = p[wb] & (wb == Wc - 1 ? tail : ~0ull);
       }
     }
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if (lane == 0) out[i] = acc;
+    // four rows (eight words) are walked together so that eight LDS reads are in flight
+#pragma unroll
+    for (int i = 0; i < kSpmvRowsPerWave; i += 4) {
+      uint64_t m[8] = {w0[i], w1[i], w0[i + 1], w1[i + 1], w0[i + 2], w1[i + 2], w0[i + 3], w1[i + 3]};
+      double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      while (m[0] | m[1] | m[2] | m[3] | m[4] | m[5] | m[6] | m[7]) {
+        double v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const bool live = m[q] != 0ull;
+          const int bit = live ? __ffsll((long long)m[q]) - 1 : 0;
+          const double xv = (q & 1) ? xb[bit] : xa[bit];
+          v[q] = live ? xv : 0.0;
+          m[q] &= m[q] - 1;  // 0 stays 0
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s[q] += v[q];
+      }
+      acc[i] += s[0] + s[1];
+      acc[i + 1] += s[2] + s[3];
+      acc[i + 2] += s[4] + s[5];
+      acc[i + 3] += s[6] + s[7];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kSpmvRowsPerWave; ++i) {
+    double s = acc[i];
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (lane == 0 && row0 + i < rows) out[row0 + i] = s;
   }
 }
 
@@ -87,8 +139,8 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_kernel(const uint64_t* B, i
 int ds_bit_spmv(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
                 int64_t row_step, const double* x, double* out) {
   if (rows <= 0) return DS_OK;
-  int64_t blocks = (rows * 64 + kThreads - 1) / kThreads;
-  if (blocks > (int64_t)ctx->num_cus * 8) blocks = (int64_t)ctx->num_cus * 8;
+  const int64_t rows_per_block = kSpmvRowsPerWave * (kThreads / 64);
+  const int64_t blocks = (rows + rows_per_block - 1) / rows_per_block;
   hipLaunchKernelGGL(bit_spmv_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, B, rows, cols, stride,
                      row_first, row_step, x, out);
   DS_HIP(ctx, hipGetLastError());

@@ -189,7 +189,7 @@ inline unsigned nblocks(int64_t n, int per) { return (unsigned)((n + per - 1) / 
 
 size_t ds_cgls_arena_bytes(int64_t n, int64_t k) {
   const int64_t KW = (k + 63) / 64;
-  return ds_align((size_t)n * KW * 8) + ds_align(k * 4) + 5 * ds_align(k * 8) + 4 * ds_align(n * 8) + 8192 + ds_align(k * 4);
+  return ds_align((size_t)n * KW * 8) + 2 * ds_align(k * 4) + 7 * ds_align(k * 8) + 4 * ds_align(n * 8) + 16384;
 }
 
 int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y, int paired,

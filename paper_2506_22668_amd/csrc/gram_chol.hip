@@ -200,58 +200,70 @@ __global__ void build_system_kernel(const double* G, const double* m, const doub
 // ---------------- blocked Cholesky (lower, in place, fp64) ----------------
 constexpr int NB = 64;
 
-__device__ __forceinline__ double readlane_d(double v, int l) {
-  const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
-  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
-  return __hiloint2double(hi, lo);
-}
-
-// Factor the nb x nb diagonal block at j0 and invert the factor, in one wave with no barriers:
-// lane r keeps row r of the block in registers (the loops are fully unrolled, so every column
-// index is a register name); column kk is scaled by 1/sqrt(pivot) and the trailing columns take
-// a rank-1 update whose second factor comes from lane c by a lane read. The inverse X = L^-1 is
-// built the same way with lane c holding column c of X: X[r][c] = (d_rc - sum_{m<r} L[r][m] X[m][c]) / L[r][r].
+// Factor the nb x nb diagonal block at j0 and invert the factor. Factorisation: 16x16 threads,
+// 4x4 elements each, right-looking with ONE barrier per column: step kk reads column kk and the
+// pivot (final since step kk-1) and updates only columns > kk with S[r][c] -= S[r][kk] S[c][kk] / p,
+// so the column is scaled by 1/sqrt(p) only at the end. Inverse X = L^-1: column c of X depends
+// on nothing but L and itself, so one wave builds all 64 columns with no barrier (lane c:
+// X[r][c] = (d_rc - sum_{m<r} L[r][m] X[m][c]) / L[r][r], rows of L as LDS broadcast reads).
 // Linv (NB x NB, identity-padded) goes to linv_out.
-__global__ __launch_bounds__(64) void chol_diag_kernel(double* M, int64_t ld, int64_t j0, int nb, double* linv_out,
-                                                       int* flag) {
+__global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t ld, int64_t j0, int nb, double* linv_out,
+                                                             int* flag) {
   __shared__ double S[NB][NB + 1];
-  const int lane = threadIdx.x;
-  for (int idx = lane; idx < NB * NB; idx += 64) {
+  __shared__ double X[NB][NB + 1];
+  __shared__ double dinv[NB];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  for (int idx = tid; idx < NB * NB; idx += kThreads) {
     const int r = idx >> 6, c = idx & 63;
     S[r][c] = (r < nb && c < nb) ? M[(j0 + r) * ld + j0 + c] : (r == c ? 1.0 : 0.0);
   }
   __syncthreads();
-  double a[NB];
-#pragma unroll
-  for (int c = 0; c < NB; ++c) a[c] = S[lane][c];
   bool bad = false;
-#pragma unroll
   for (int kk = 0; kk < NB; ++kk) {
-    double p = readlane_d(a[kk], kk);
+    double p = S[kk][kk];
     if (!(p > 0.0)) {
       bad = true;
       p = 1.0;
     }
-    const double rinv = 1.0 / sqrt(p);
-    const double l = a[kk] * rinv;
-    a[kk] = l;
+    const double rinv = rsqrt(p);
+    const double inv_p = rinv * rinv;
+    double lr[4], lc[4];
 #pragma unroll
-    for (int c = kk + 1; c < NB; ++c) a[c] -= l * readlane_d(l, c);
+    for (int i = 0; i < 4; ++i) {
+      lr[i] = S[ty + 16 * i][kk] * inv_p;
+      lc[i] = S[tx + 16 * i][kk];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int r = ty + 16 * i, c = tx + 16 * j;
+        if (c > kk && r >= c) S[r][c] -= lr[i] * lc[j];
+      }
+    if (tid == 0) dinv[kk] = rinv;
+    __syncthreads();
   }
-  if (bad && lane == 0) atomicExch(flag, 1);
-  double x[NB];
-#pragma unroll
-  for (int r = 0; r < NB; ++r) {
-    double s = (lane == r) ? 1.0 : 0.0;
-#pragma unroll
-    for (int m = 0; m < r; ++m) s -= readlane_d(a[m], r) * x[m];
-    x[r] = s / readlane_d(a[r], r);
+  if (bad && tid == 0) atomicExch(flag, 1);
+  for (int idx = tid; idx < NB * NB; idx += kThreads) {
+    const int r = idx >> 6, c = idx & 63;
+    S[r][c] = (c <= r) ? S[r][c] * dinv[c] : 0.0;
   }
-#pragma unroll
-  for (int c = 0; c < NB; ++c)
-    if (lane < nb && c <= lane) M[(j0 + lane) * ld + j0 + c] = a[c];
-#pragma unroll
-  for (int r = 0; r < NB; ++r) linv_out[r * NB + lane] = x[r];
+  __syncthreads();
+  if (tid < 64) {
+#pragma unroll 1
+    for (int r = 0; r < NB; ++r) {
+      double acc = (tid == r) ? 1.0 : 0.0;
+#pragma unroll 8
+      for (int m = 0; m < r; ++m) acc -= S[r][m] * X[m][tid];
+      X[r][tid] = acc * dinv[r];
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < NB * NB; idx += kThreads) {
+    const int r = idx >> 6, c = idx & 63;
+    if (r < nb && c <= r) M[(j0 + r) * ld + j0 + c] = S[r][c];
+    linv_out[idx] = X[r][c];
+  }
 }
 
 // rows below the diagonal block: X = A21 L11^-T = A21 Linv^T, a 64x64 product per workgroup
@@ -360,6 +372,7 @@ __global__ __launch_bounds__(kSolveThreads) void chol_back_solve_kernel(const do
     if (tid < nb) yv[j0 + tid] = xs[tid];
     for (int64_t j = tid; j < j0; j += kSolveThreads) {
       double s = 0.0;
+#pragma unroll 16
       for (int r = 0; r < nb; ++r) s += M[(j0 + r) * ld + j] * xs[r];
       yv[j] -= s;
     }
@@ -455,7 +468,7 @@ int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   for (int64_t j0 = 0; j0 < n; j0 += NB) {
     const int nb = (int)(n - j0 < NB ? n - j0 : NB);
     double* li = linv + (size_t)(j0 / NB) * NB * NB;
-    hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(64), 0, st, M, ld, j0, nb, li, flag);
+    hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, j0, nb, li, flag);
     const int64_t rest = rows_total - j0 - nb;
     hipLaunchKernelGGL(chol_panel_kernel, dim3(nblocks(rest, kTile)), dim3(kThreads), 0, st, M, ld, rows_total, j0, nb, li);
     if (n - j0 - nb > 0) {

@@ -28,6 +28,7 @@ class Workload:
     solver: str                  # "gram_chol" | "cgls"
     transform_dtype: str = "f32"  # "f32" | "bf16"
     tol: float = 1e-6
+    max_iter: int = 0            # CGLS iteration cap (0 = library default)
     info: dict = field(default_factory=dict)
 
     @property
@@ -141,10 +142,12 @@ def _rmat_workload(name, cfg_id, scale, want, d0, dims, n_samples, solver,
 WORKLOADS = {
     "c1": _c1,
     "c2": _c2,
-    "c3": lambda: _rmat_workload("c3_rmat18_100k_edges", 3, 18, 100_000, 256,
-                                 (256, 128, 128, 16), 200_000, "cgls"),
-    "c4": lambda: _rmat_workload("c4_rmat20_1m_edges", 4, 20, 1_000_000, 128,
-                                 (128, 64, 64, 10), 400_000, "cgls"),
+    # with two rows per player, most of them tiny or huge, the regression is close to
+    # rank-deficient and CGLS converges sub-linearly: it needs more than the default cap
+    "c3": lambda: _with(_rmat_workload("c3_rmat18_100k_edges", 3, 18, 100_000, 256,
+                                       (256, 128, 128, 16), 200_000, "cgls"), max_iter=40_000),
+    "c4": lambda: _with(_rmat_workload("c4_rmat20_1m_edges", 4, 20, 1_000_000, 128,
+                                       (128, 64, 64, 10), 400_000, "cgls"), max_iter=40_000),
     "c5": lambda: _rmat_workload("c5_rmat18_batch64", 5, 18, 10_000, 512,
                                  (512, 256, 256, 32), 50_000, "gram_chol",
                                  count=64, transform_dtype="bf16", examine=1200),
@@ -161,6 +164,12 @@ WORKLOADS = {
                                        transform_dtype="bf16", examine=300,
                                        edge_factor=3),
 }
+
+
+def _with(w, **kw):
+    for k, v in kw.items():
+        setattr(w, k, v)
+    return w
 
 
 def _small_ba():
