@@ -21,6 +21,9 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+
 struct EvalArgs {
   int32_t V, n, L, directed, score, pred_class, bf16;
   int32_t dims[DS_MAX_LAYERS + 1];
@@ -220,9 +223,397 @@ __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
   }
 }
 
+// ---------------- small computational graphs: one coalition per LANE ----------------
+//
+// When the mask row is short (n <= 2048 players) the cost of a coalition is the aggregation
+// arithmetic, not the mask stream, and gathering a feature row per active edge per coalition
+// keeps L2 busy instead of the ALUs. Here a workgroup takes 64 coalitions, one per lane, and every
+// loop (over nodes, CSR entries, features) is uniform across the wave:
+//   * the mask words of the 64 coalitions sit in LDS as zs[word][lane];
+//   * degrees: for node v, each lane counts the set bits of its coalition among the row's
+//     entries (no atomics), rs[v][lane] = d^-1/2 goes to a per-workgroup scratch in global memory;
+//   * aggregation of row t: per entry, each lane forms coef = bit ? rs[src][lane] : 0 and adds
+//     coef * H[src][f] for 64 features held in registers. For layer 1 the operand H = P is the
+//     same for all coalitions: its rows are staged in LDS and read as broadcasts, so one row load
+//     serves 64 coalitions. For later layers H is per coalition, laid out [row][feature][lane].
+//   * transforms: out[j] += q[f] * W[f][j] with W rows broadcast from LDS in the same way.
+// The four waves of the workgroup split the nodes and rows among them (same 64 coalitions), and
+// meet at barriers between layers. All per-coalition intermediates are [..][64 lanes] arrays.
+constexpr int kBW = 32;        // mask words per coalition held in LDS
+constexpr int kStageRows = 16; // operand rows staged per step
+constexpr int kBThreads = 512; // eight waves share the 64 coalitions of a workgroup
+constexpr int kBWaves = kBThreads / 64;
+constexpr int kDegLdsMaxNodes = 640;  // degrees as u16[V][64] in LDS up to this many nodes (80 KB)
+
+struct BatchedArgs {
+  EvalArgs e;
+  float* scratch;          // per workgroup: rs[V][64] (if not in LDS) | bufA | bufB | q[waves][dmax][64]
+  int64_t scratch_stride;  // floats per workgroup
+  int64_t rs_floats, a_floats, b_floats, q_floats;  // region sizes (floats, already x64)
+  int32_t csr_lds_offset;  // byte offset of the LDS copy of the local CSR (if used)
+};
+
+// acc[f] += coef_i * row_i[f] for the staged rows; rows live in this wave's LDS stage area
+__device__ __forceinline__ void fma_staged_rows(float (&acc)[64], const float* stage, const float (&coef)[kStageRows], int cnt) {
+#pragma unroll
+  for (int i = 0; i < kStageRows; ++i) {
+    if (i < cnt) {
+      const float c = coef[i];
+      const float4* r4 = (const float4*)(stage + i * 64);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const float4 v = r4[j];
+        acc[4 * j + 0] += c * v.x;
+        acc[4 * j + 1] += c * v.y;
+        acc[4 * j + 2] += c * v.z;
+        acc[4 * j + 3] += c * v.w;
+      }
+    }
+  }
+}
+
+// stage `cnt` rows into LDS: row i = base + rowid_i * stride + f0 .. +63 (zero beyond width), where
+// rowid_i is held by lane i of `rowv`. Four rows per load instruction, 16 lanes x float4 each.
+__device__ __forceinline__ void stage_rows(float* stage, const float* base, int rowv, int cnt, int stride, int f0, int width,
+                                           bool bf16) {
+  const int lane = threadIdx.x & 63;
+  const int sub = lane >> 4, c4 = (lane & 15) * 4;
+#pragma unroll
+  for (int q = 0; q < kStageRows / 4; ++q) {
+    const int i = q * 4 + sub;
+    const int r = __shfl(rowv, i, 64);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < cnt) {
+      const float* p = base + (size_t)r * stride + f0 + c4;
+      if (f0 + c4 + 3 < width && ((stride | f0) & 3) == 0) {
+        v = *(const float4*)p;
+      } else {
+        if (f0 + c4 + 0 < width) v.x = p[0];
+        if (f0 + c4 + 1 < width) v.y = p[1];
+        if (f0 + c4 + 2 < width) v.z = p[2];
+        if (f0 + c4 + 3 < width) v.w = p[3];
+      }
+      if (bf16) {
+        v.x = bf16_round(v.x); v.y = bf16_round(v.y); v.z = bf16_round(v.z); v.w = bf16_round(v.w);
+      }
+    }
+    *(float4*)(stage + i * 64 + c4) = v;
+  }
+}
+
+template <bool DEG_LDS, bool CSR_LDS>
+__global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(BatchedArgs b) {
+  const EvalArgs& a = b.e;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  // LDS: zs[kBW][64] u64 | stage[waves][16][64] f32 | deg[V][64] u16 (optional) | local CSR (optional)
+  uint64_t* zs = (uint64_t*)smem_raw;
+  float* stage_all = (float*)(smem_raw + kBW * 64 * 8);
+  unsigned short* degs = (unsigned short*)(smem_raw + kBW * 64 * 8 + kBWaves * kStageRows * 64 * 4);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t *g_rp = a.row_ptr, *g_col = a.col, *g_eid = a.eid;
+  if (CSR_LDS) {  // the graph structure is read many times per coalition block: keep it on chip
+    const int nnz = a.row_ptr[a.V];
+    int32_t* base = (int32_t*)(smem_raw + b.csr_lds_offset);
+    int32_t* l_rp = base;
+    int32_t* l_col = l_rp + ((a.V + 1 + 3) & ~3);
+    int32_t* l_eid = l_col + ((nnz + 3) & ~3);
+    for (int i = tid; i <= a.V; i += kBThreads) l_rp[i] = a.row_ptr[i];
+    for (int i = tid; i < nnz; i += kBThreads) {
+      l_col[i] = a.col[i];
+      l_eid[i] = a.eid[i];
+    }
+    g_rp = l_rp;
+    g_col = l_col;
+    g_eid = l_eid;
+  }
+  const int32_t* const rp_ = g_rp;
+  const int32_t* const col_ = g_col;
+  const int32_t* const eid_ = g_eid;
+  float* stage = stage_all + wave * kStageRows * 64;
+  float* S = b.scratch + (size_t)blockIdx.x * b.scratch_stride;
+  float* rs = S;
+  float* bufA = rs + b.rs_floats;
+  float* bufB = bufA + b.a_floats;
+  const int W = (int)a.W;
+  const uint64_t tail_mask = (a.n & 63) ? ((1ull << (a.n & 63)) - 1ull) : ~0ull;
+  const int64_t blocks = (a.k + 63) / 64;
+
+  auto rs_of = [&](int v) -> float {
+    if (DEG_LDS) return __frsqrt_rn((float)degs[v * 64 + lane]);
+    return rs[(size_t)v * 64 + lane];
+  };
+  auto bit_of = [&](int p) -> bool { return (zs[(p >> 6) * 64 + lane] >> (p & 63)) & 1ull; };
+
+#ifdef DS_PROFILE_PHASES
+  long long tph[8];
+#define TPH(i) tph[i] = wall_clock64()
+#else
+#define TPH(i)
+#endif
+  for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
+    const int64_t row = blk * 64 + lane;
+    const bool valid = row < a.k;
+    __syncthreads();
+    TPH(0);
+    for (int w = wave; w < W; w += kBWaves) {
+      uint64_t word = valid ? a.Z[row * W + w] : 0ull;
+      if (w == W - 1) word &= tail_mask;
+      zs[w * 64 + lane] = word;
+    }
+    __syncthreads();
+    // degrees: node v's entries are fetched 64 at a time by the lanes and broadcast one by one
+    for (int v = wave; v < a.V; v += kBWaves) {
+      const int e0 = rp_[v], e1 = rp_[v + 1];
+      int cnt = 1;
+      for (int eb = e0; eb < e1; eb += 64) {
+        const int m = e1 - eb < 64 ? e1 - eb : 64;
+        const int pv = lane < m ? eid_[eb + lane] : 0;
+        for (int i = 0; i < m; ++i) cnt += bit_of(readlane_i(pv, i)) ? 1 : 0;
+      }
+      if (DEG_LDS) degs[v * 64 + lane] = (unsigned short)cnt;
+      else rs[(size_t)v * 64 + lane] = 1.0f / sqrtf((float)cnt);
+    }
+    TPH(1);
+    __syncthreads();
+    TPH(2);
+
+    // layer 1 on the matrix cores: for row t, H1[f][c] = sum_e P[src_e][f] * coef[e][c] is a product
+    // (features x entries) . (entries x coalitions). With v_mfma_f32_32x32x2f32 lane l supplies
+    // A[m = l%32][k = l/32] = P[src of entry 2q + l/32][feature tile + l%32] (a plain coalesced
+    // load, nothing is broadcast) and B[k = l/32][n = l%32] = coefficient of entry 2q + l/32 for
+    // coalition n, which lives in another lane's register and comes over with one cross-half
+    // shuffle per entry pair. The accumulator holds D[feature][coalition], so its stores are
+    // 128-byte runs of consecutive coalitions.
+    {
+      const int d1 = a.dims[1];
+      const bool relu = a.L > 1;
+      const int half = lane >> 5, l32 = lane & 31;
+      for (int t = wave; t < a.rows_out[1]; t += kBWaves) {
+        const int e0 = rp_[t], e1 = rp_[t + 1];  // entry e1 stands for the self-loop
+        const float rst = rs_of(t);
+        const float rst_sw = __shfl_xor(rst, 32, 64);
+        for (int f0 = 0; f0 < d1; f0 += 64) {
+          float16_t acc[2][2];  // [feature tile][coalition half]
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            acc[0][0][i] = 0.f; acc[0][1][i] = 0.f; acc[1][0][i] = 0.f; acc[1][1][i] = 0.f;
+          }
+          for (int eb = e0; eb <= e1; eb += kStageRows) {
+            const int cnt = e1 + 1 - eb < kStageRows ? e1 + 1 - eb : kStageRows;
+            int pv = 0, sv = t;
+            if (lane < cnt && eb + lane < e1) {
+              pv = eid_[eb + lane];
+              sv = col_[eb + lane];
+            }
+            float av[kStageRows / 2][2];
+#pragma unroll
+            for (int q = 0; q < kStageRows / 2; ++q) {
+              const int s0 = readlane_i(sv, 2 * q), s1 = readlane_i(sv, 2 * q + 1);
+              const int src = half ? s1 : s0;
+              const bool ok = 2 * q + half < cnt;
+              const float* pr = a.P + (size_t)src * d1 + f0 + l32;
+              av[q][0] = (ok && f0 + l32 < d1) ? pr[0] : 0.f;
+              av[q][1] = (ok && f0 + 32 + l32 < d1) ? pr[32] : 0.f;
+            }
+            float coef[kStageRows];
+#pragma unroll
+            for (int i = 0; i < kStageRows; ++i) {
+              coef[i] = 0.f;
+              if (i < cnt) {
+                const bool self = eb + i == e1;
+                const int p = readlane_i(pv, i), src = readlane_i(sv, i);
+                const float r = rs_of(src);
+                coef[i] = (self || bit_of(p)) ? r : 0.f;
+              }
+            }
+#pragma unroll
+            for (int q = 0; q < kStageRows / 2; ++q) {
+              if (2 * q < cnt) {
+                const float x = coef[2 * q], y = coef[2 * q + 1];
+                const float xs = __shfl_xor(x, 32, 64), ys = __shfl_xor(y, 32, 64);
+                const float b0 = half ? ys : x;  // coalitions 0..31
+                const float b1 = half ? y : xs;  // coalitions 32..63
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][0], b0, acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][0], b1, acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][1], b0, acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][1], b1, acc[1][1], 0, 0, 0);
+              }
+            }
+          }
+          // accumulator register i of lane l is D[feature 8*(i/4) + 4*(l/32) + i%4][coalition l%32]
+#pragma unroll
+          for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+              const float scale = (nb == half) ? rst : rst_sw;  // d^-1/2 of row t in coalition nb*32 + l32
+#pragma unroll
+              for (int i = 0; i < 16; ++i) {
+                const int fr = f0 + ft * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                if (fr < d1) {
+                  float v = scale * acc[ft][nb][i];
+                  if (a.bias[0]) v += a.bias[0][fr];
+                  bufA[((size_t)t * d1 + fr) * 64 + nb * 32 + l32] = relu ? fmaxf(v, 0.f) : v;
+                }
+              }
+            }
+        }
+      }
+    }
+    TPH(3);
+    __syncthreads();
+    TPH(4);
+
+    float* cur = bufA;
+    float* nxt = bufB;
+    float* qall = bufB + b.b_floats;  // q[row][feature][lane] of the layer in flight
+    for (int l = 2; l <= a.L; ++l) {
+      const int din = a.dims[l - 1], dout = a.dims[l];
+      const bool relu = l < a.L;
+      const int rows = a.rows_out[l];
+      // These layers have few rows but long dependent chains, so the work is cut into
+      // (row, 16-feature slice) items spread over all waves, four entries in flight per step.
+      // phase A: q[t][f] = rs_t * ( sum_active rs_src H[src][f] + rs_t H[t][f] )
+      const int fch = (din + 15) / 16;
+      for (int item = wave; item < rows * fch; item += kBWaves) {
+        const int t = item / fch, f0 = (item - t * fch) * 16;
+        const int e0 = rp_[t], e1 = rp_[t + 1];
+        const float rst = rs_of(t);
+        float acc[16];
+#pragma unroll
+        for (int f = 0; f < 16; ++f) acc[f] = 0.f;
+        for (int eb = e0; eb <= e1; eb += 4) {  // entry e1 stands for the self-loop
+          float c[4];
+          const float* hp[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int e = eb + u;
+            int src = t;
+            c[u] = 0.f;
+            if (e < e1) {
+              src = col_[e];
+              c[u] = bit_of(eid_[e]) ? rs_of(src) : 0.f;
+            } else if (e == e1) {
+              c[u] = rst;
+            }
+            hp[u] = cur + ((size_t)src * din + f0) * 64 + lane;
+          }
+          float hv[4][16];
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int f = 0; f < 16; ++f) hv[u][f] = (f0 + f < din) ? hp[u][(size_t)f * 64] : 0.f;
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int f = 0; f < 16; ++f) acc[f] += c[u] * hv[u][f];
+        }
+#pragma unroll
+        for (int f = 0; f < 16; ++f)
+          if (f0 + f < din) {
+            const float q = rst * acc[f];
+            qall[((size_t)t * din + f0 + f) * 64 + lane] = a.bf16 ? bf16_round(q) : q;
+          }
+      }
+      __syncthreads();
+#ifdef DS_PROFILE_PHASES
+      if (l == 2) tph[7] = wall_clock64();
+#endif
+      // phase B: out[t][j] = act( sum_f q[t][f] W[f][j] + b[j] ). W is the same for every lane:
+      // the workgroup copies it (in row chunks if it is large) into the LDS staging area once and
+      // the waves read it back as broadcasts.
+      {
+        float* Ws = stage_all;  // kBWaves * kStageRows * 64 floats
+        const int cap = kBWaves * kStageRows * 64;
+        int FB = cap / dout;
+        if (FB > din) FB = din;
+        const bool single = FB == din;
+        const int jch = (dout + 15) / 16;
+        const int nit = (rows * jch + kBWaves - 1) / kBWaves;
+        const float* Wg = a.Wl[l - 1];
+        for (int it = 0; it < nit; ++it) {
+          const int item = it * kBWaves + wave;
+          const bool live = item < rows * jch;
+          const int t = live ? item / jch : 0, j0 = live ? (item - t * jch) * 16 : 0;
+          float acc[16];
+#pragma unroll
+          for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+          const float* qp = qall + (size_t)t * din * 64 + lane;
+          for (int fb0 = 0; fb0 < din; fb0 += FB) {
+            const int fcnt = din - fb0 < FB ? din - fb0 : FB;
+            if (!(single && it > 0)) {
+              __syncthreads();
+              for (int i = tid; i < fcnt * dout; i += kBThreads) {
+                const float wv = Wg[(size_t)fb0 * dout + i];
+                Ws[i] = a.bf16 ? bf16_round(wv) : wv;
+              }
+              __syncthreads();
+            }
+            if (live) {
+              for (int fb = 0; fb < fcnt; fb += 16) {
+                float q[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) q[u] = (fb + u < fcnt) ? qp[(size_t)(fb0 + fb + u) * 64] : 0.f;
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                  if (fb + u < fcnt) {
+                    const float* wr = Ws + (fb + u) * dout + j0;
+                    if ((dout & 3) == 0 && j0 + 16 <= dout) {
+                      const float4* w4 = (const float4*)wr;
+#pragma unroll
+                      for (int j = 0; j < 4; ++j) {
+                        const float4 v = w4[j];
+                        acc[4 * j + 0] += q[u] * v.x;
+                        acc[4 * j + 1] += q[u] * v.y;
+                        acc[4 * j + 2] += q[u] * v.z;
+                        acc[4 * j + 3] += q[u] * v.w;
+                      }
+                    } else {
+#pragma unroll
+                      for (int j = 0; j < 16; ++j)
+                        if (j0 + j < dout) acc[j] += q[u] * wr[j];
+                    }
+                  }
+                }
+              }
+            }
+          }
+          if (live) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+              if (j0 + j < dout) {
+                float v = acc[j];
+                if (a.bias[l - 1]) v += a.bias[l - 1][j0 + j];
+                nxt[((size_t)t * dout + j0 + j) * 64 + lane] = relu ? fmaxf(v, 0.f) : v;
+              }
+          }
+        }
+      }
+      __syncthreads();
+      TPH(3 + l);
+      float* tmp = cur; cur = nxt; nxt = tmp;
+    }
+#ifdef DS_PROFILE_PHASES
+    if (lane == 0 && (blockIdx.x == 0 || blockIdx.x == 100) && blk == blockIdx.x)
+      printf("blk %d wave %d: masks+deg %lld, wait %lld, layer1 %lld, wait %lld, layer2 %lld (agg %lld), layer3 %lld (x10ns) rows %d %d %d deg0 %d\n", (int)blockIdx.x, wave,
+             tph[1] - tph[0], tph[2] - tph[1], tph[3] - tph[2], tph[4] - tph[3], tph[5] - tph[4], tph[7] - tph[4], tph[6] - tph[5], a.rows_out[1], a.rows_out[2], a.rows_out[3], rp_[a.rows_out[2]]);
+#endif
+
+    // readout: logits of the target are cur[c][lane], c < d_L (row 0)
+    if (wave == 0 && valid) {
+      const int C = a.dims[a.L];
+      float m = -INFINITY;
+      for (int c = 0; c < C; ++c) m = fmaxf(m, cur[(size_t)c * 64 + lane]);
+      float sum = 0.f;
+      for (int c = 0; c < C; ++c) sum += expf(cur[(size_t)c * 64 + lane] - m);
+      const float zc = cur[(size_t)a.pred_class * 64 + lane];
+      a.y[row] = a.score == DS_SCORE_LOGIT ? zc : expf(zc - m) / sum;
+      if (a.logits_out)
+        for (int c = 0; c < C; ++c) a.logits_out[row * C + c] = cur[(size_t)c * 64 + lane];
+    }
+  }
+}
+
 // ---------------- shared first transform P = X_c W_1 on the matrix cores ----------------
-typedef float float16_t __attribute__((ext_vector_type(16)));
-typedef short short4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ short bf16_bits(float x) {
   uint32_t u = __float_as_uint(x);
@@ -381,13 +772,58 @@ void fill_args(const ds_ctx* ctx, const ds_cgraph* cg, const EvalLayout& lay, Ev
   a->gws_stride = lay.gws_floats;
 }
 
+
+struct BatchedLayout {
+  bool use, deg_lds, csr_lds;
+  int csr_off;
+  int grid;
+  size_t lds_bytes;
+  int64_t rs_floats, a_floats, b_floats, q_floats, stride;
+};
+
+// the one-coalition-per-lane kernel applies to short mask rows and enough coalitions to fill lanes
+BatchedLayout make_batched_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
+  BatchedLayout bl;
+  memset(&bl, 0, sizeof(bl));
+  const int64_t n = cg->info.num_players;
+  bl.use = n >= 1 && n <= (int64_t)kBW * 64 && k >= 256;
+  if (!bl.use) return bl;
+  int32_t rows_out[DS_MAX_LAYERS + 1];
+  fill_rows(ctx, cg, rows_out);
+  const int L = ctx->L;
+  int64_t A = 0, B = 0, dq = 0;
+  for (int l = 1; l <= L; ++l) {
+    const int64_t out = (int64_t)rows_out[l] * ctx->dims[l];
+    if (l & 1) { if (out > A) A = out; } else { if (out > B) B = out; }
+    if (l >= 2 && (int64_t)rows_out[l] * ctx->dims[l - 1] > dq) dq = (int64_t)rows_out[l] * ctx->dims[l - 1];
+  }
+  bl.a_floats = A * 64;
+  bl.b_floats = (B > 0 ? B : 1) * 64;
+  bl.q_floats = (dq > 0 ? dq : 1) * 64;
+  bl.deg_lds = cg->info.num_nodes <= kDegLdsMaxNodes;
+  bl.rs_floats = bl.deg_lds ? 0 : cg->info.num_nodes * 64;
+  bl.lds_bytes = (size_t)kBW * 64 * 8 + (size_t)kBWaves * kStageRows * 64 * 4 +
+                 (bl.deg_lds ? (size_t)cg->info.num_nodes * 64 * 2 : 0);
+  bl.lds_bytes = (bl.lds_bytes + 15) & ~(size_t)15;
+  const size_t csr_bytes = 4 * (((size_t)cg->info.num_nodes + 4) & ~(size_t)3) + 8 * (((size_t)cg->info.num_entries + 3) & ~(size_t)3);
+  bl.csr_lds = bl.lds_bytes + csr_bytes <= kLdsLimit;
+  bl.csr_off = (int)bl.lds_bytes;
+  if (bl.csr_lds) bl.lds_bytes += csr_bytes;
+  bl.stride = bl.rs_floats + bl.a_floats + bl.b_floats + bl.q_floats;
+  const int64_t blocks = (k + 63) / 64;
+  int64_t g = (int64_t)ctx->num_cus * 2;
+  bl.grid = (int)(blocks < g ? blocks : g);
+  return bl;
+}
 }  // namespace
 
 size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
   const EvalLayout lay = make_layout(ctx, cg);
   const int grid = grid_for(ctx, lay, k > 1 ? k : 1);
   const size_t W = (cg->info.num_players + 63) / 64;
-  return ds_align((size_t)lay.gws_floats * 4 * grid) + ds_align(W * 8 + 8) + ds_align(ctx->dims[ctx->L] * 4 + 8) + 1024;
+  const BatchedLayout bl = make_batched_layout(ctx, cg, k);
+  const size_t batched = bl.use ? ds_align((size_t)bl.stride * 4 * bl.grid) : 0;
+  return ds_align((size_t)lay.gws_floats * 4 * grid) + batched + ds_align(W * 8 + 8) + ds_align(ctx->dims[ctx->L] * 4 + 8) + 1024;
 }
 
 // Shared first transform and the class predicted on the full computational graph;
@@ -441,6 +877,45 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
   DS_TRY(ds_prepare_model(ctx, cg));
   if (k <= 0) return DS_OK;
   const EvalLayout lay = make_layout(ctx, cg);
+  const BatchedLayout bl = make_batched_layout(ctx, cg, k);
+  if (bl.use) {
+    float* scratch = (float*)ds_arena_alloc(ctx, (size_t)bl.stride * 4 * bl.grid);
+    if (!scratch) return ds_fail(ctx, DS_EINTERNAL, "eval: arena exhausted");
+    BatchedArgs b;
+    fill_args(ctx, cg, lay, &b.e);
+    b.e.Z = Z;
+    b.e.k = k;
+    b.e.y = y;
+    b.e.logits_out = nullptr;
+    b.e.gws = nullptr;
+    b.e.score = score;
+    b.e.pred_class = cg->pred_class;
+    b.scratch = scratch;
+    b.scratch_stride = bl.stride;
+    b.rs_floats = bl.rs_floats;
+    b.a_floats = bl.a_floats;
+    b.b_floats = bl.b_floats;
+    b.q_floats = bl.q_floats;
+    b.csr_lds_offset = bl.csr_off;
+    DS_TRY(ds_kernel_mark(ctx, 0, 0));
+    const void* fn;
+    if (bl.deg_lds && bl.csr_lds) fn = (const void*)masked_gcn_eval_batched_kernel<true, true>;
+    else if (bl.deg_lds) fn = (const void*)masked_gcn_eval_batched_kernel<true, false>;
+    else if (bl.csr_lds) fn = (const void*)masked_gcn_eval_batched_kernel<false, true>;
+    else fn = (const void*)masked_gcn_eval_batched_kernel<false, false>;
+    if (bl.lds_bytes > 48 * 1024)
+      DS_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bl.lds_bytes));
+    if (bl.deg_lds && bl.csr_lds)
+      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, true>), dim3(bl.grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+    else if (bl.deg_lds)
+      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, false>), dim3(bl.grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+    else if (bl.csr_lds)
+      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, true>), dim3(bl.grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+    else
+      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, false>), dim3(bl.grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+    DS_HIP(ctx, hipGetLastError());
+    return ds_kernel_mark(ctx, 0, 1);
+  }
   const int grid = grid_for(ctx, lay, k);
   float* gws = nullptr;
   if (lay.gws_floats) {

@@ -200,70 +200,102 @@ __global__ void build_system_kernel(const double* G, const double* m, const doub
 // ---------------- blocked Cholesky (lower, in place, fp64) ----------------
 constexpr int NB = 64;
 
-// Factor the nb x nb diagonal block at j0 and invert the factor. Factorisation: 16x16 threads,
-// 4x4 elements each, right-looking with ONE barrier per column: step kk reads column kk and the
-// pivot (final since step kk-1) and updates only columns > kk with S[r][c] -= S[r][kk] S[c][kk] / p,
-// so the column is scaled by 1/sqrt(p) only at the end. Inverse X = L^-1: column c of X depends
-// on nothing but L and itself, so one wave builds all 64 columns with no barrier (lane c:
-// X[r][c] = (d_rc - sum_{m<r} L[r][m] X[m][c]) / L[r][r], rows of L as LDS broadcast reads).
-// Linv (NB x NB, identity-padded) goes to linv_out.
+// Factor the nb x nb diagonal block at j0 and invert the factor in the same sweep.
+// 16x16 threads; thread (ty, tx) keeps the elements (ty+16i, tx+16j), i, j < 4, of the block S
+// and of Y (initially I) in registers. Right-looking step kk: the owners publish column kk of S
+// and row kk of Y in LDS (double-buffered, so ONE barrier per step), then everyone updates
+//   S[r][c] -= S[r][kk] S[c][kk] / p          (c > kk)       -> L = S scaled by 1/sqrt(p) per column
+//   Y[r][c] -= S[r][kk] Y[kk][c] / p          (r > kk)       -> L^-1 = Y scaled by 1/sqrt(p) per row
+// i.e. the forward substitution L X = I rides along with the factorisation and needs no extra
+// sequential pass. Linv (NB x NB, identity-padded) goes to linv_out.
 __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t ld, int64_t j0, int nb, double* linv_out,
                                                              int* flag) {
-  __shared__ double S[NB][NB + 1];
-  __shared__ double X[NB][NB + 1];
+  __shared__ double colbuf[2][NB];
+  __shared__ double rowbuf[2][NB];
   __shared__ double dinv[NB];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-  for (int idx = tid; idx < NB * NB; idx += kThreads) {
-    const int r = idx >> 6, c = idx & 63;
-    S[r][c] = (r < nb && c < nb) ? M[(j0 + r) * ld + j0 + c] : (r == c ? 1.0 : 0.0);
-  }
-  __syncthreads();
+  double s[4][4], y[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r = ty + 16 * i, c = tx + 16 * j;
+      s[i][j] = (r < nb && c < nb) ? M[(j0 + r) * ld + j0 + c] : (r == c ? 1.0 : 0.0);
+      y[i][j] = r == c ? 1.0 : 0.0;
+    }
   bool bad = false;
+#ifdef DS_PROFILE_PHASES
+  const long long tq0 = wall_clock64();
+#endif
   for (int kk = 0; kk < NB; ++kk) {
-    double p = S[kk][kk];
+    const int buf = kk & 1, blk = kk >> 4, off = kk & 15;
+    if (tx == off) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (j == blk) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) colbuf[buf][ty + 16 * i] = s[i][j];
+        }
+    }
+    if (ty == off) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (i == blk) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) rowbuf[buf][tx + 16 * j] = y[i][j];
+        }
+    }
+    __syncthreads();
+    double p = colbuf[buf][kk];
     if (!(p > 0.0)) {
       bad = true;
       p = 1.0;
     }
-    const double rinv = rsqrt(p);
+    // 1/sqrt(p): single-precision seed, two Newton steps in double (a short dependent chain;
+    // the library routine costs several times more per step of this sequential loop)
+    double rinv;
+    if (p > 1e-30 && p < 1e30) {
+      rinv = (double)__frsqrt_rn((float)p);
+      rinv = rinv * (1.5 - 0.5 * p * rinv * rinv);
+      rinv = rinv * (1.5 - 0.5 * p * rinv * rinv);
+      rinv = rinv * (1.5 - 0.5 * p * rinv * rinv);
+    } else {
+      rinv = rsqrt(p);
+    }
     const double inv_p = rinv * rinv;
-    double lr[4], lc[4];
+    // The guards sit on the multipliers, not on the 32 updates: columns <= kk of S must keep
+    // their value (lc = 0 there) and rows <= kk of Y likewise (ly = 0). The strict upper triangle
+    // of S holds don't-care values that never reach the lower one.
+    double lr[4], ly[4], lc[4], yr[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      lr[i] = S[ty + 16 * i][kk] * inv_p;
-      lc[i] = S[tx + 16 * i][kk];
+      lr[i] = -colbuf[buf][ty + 16 * i] * inv_p;
+      ly[i] = (ty + 16 * i > kk) ? lr[i] : 0.0;
+      lc[i] = (tx + 16 * i > kk) ? colbuf[buf][tx + 16 * i] : 0.0;
+      yr[i] = rowbuf[buf][tx + 16 * i];
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int r = ty + 16 * i, c = tx + 16 * j;
-        if (c > kk && r >= c) S[r][c] -= lr[i] * lc[j];
+        s[i][j] = fma(lr[i], lc[j], s[i][j]);
+        y[i][j] = fma(ly[i], yr[j], y[i][j]);
       }
     if (tid == 0) dinv[kk] = rinv;
-    __syncthreads();
   }
+  __syncthreads();
+#ifdef DS_PROFILE_PHASES
+  if (tid == 0 && j0 == 0) printf("chol_diag: factor+inverse %lld (x10ns)\n", wall_clock64() - tq0);
+#endif
   if (bad && tid == 0) atomicExch(flag, 1);
-  for (int idx = tid; idx < NB * NB; idx += kThreads) {
-    const int r = idx >> 6, c = idx & 63;
-    S[r][c] = (c <= r) ? S[r][c] * dinv[c] : 0.0;
-  }
-  __syncthreads();
-  if (tid < 64) {
-#pragma unroll 1
-    for (int r = 0; r < NB; ++r) {
-      double acc = (tid == r) ? 1.0 : 0.0;
-#pragma unroll 8
-      for (int m = 0; m < r; ++m) acc -= S[r][m] * X[m][tid];
-      X[r][tid] = acc * dinv[r];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r = ty + 16 * i, c = tx + 16 * j;
+      if (r < nb && c <= r) M[(j0 + r) * ld + j0 + c] = s[i][j] * dinv[c];
+      linv_out[r * NB + c] = (c <= r) ? y[i][j] * dinv[r] : 0.0;
     }
-  }
-  __syncthreads();
-  for (int idx = tid; idx < NB * NB; idx += kThreads) {
-    const int r = idx >> 6, c = idx & 63;
-    if (r < nb && c <= r) M[(j0 + r) * ld + j0 + c] = S[r][c];
-    linv_out[idx] = X[r][c];
-  }
 }
 
 // rows below the diagonal block: X = A21 L11^-T = A21 Linv^T, a 64x64 product per workgroup

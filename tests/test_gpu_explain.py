@@ -37,7 +37,9 @@ def _explain_case(key, tol, solver=None, oracle_solver="lstsq", targets=None):
             f"ms: ext={rep.ms_extract:.2f} smp={rep.ms_sample:.2f} eval={rep.ms_eval:.2f} solve={rep.ms_solve:.2f}")
         assert err <= tol * scale
         if oracle_solver == "cgls":
-            assert abs(rep.cgls_iterations - ref["iterations"]) <= 1
+            # the residual creeps over the threshold slowly near the end, so round-off can move the
+            # stopping iteration by a few steps; phi above is what has to agree
+            assert abs(rep.cgls_iterations - ref["iterations"]) <= 2 + ref["iterations"] // 50
         # efficiency: sum(phi) = f(full) - f(empty)
         assert abs(got.sum() - (rep.f_full - rep.f_empty)) <= 1e-5
         assert abs(rep.f_full - ref["y"][1]) <= 1e-5 * (1 if dtype == 0 else 1e3)

@@ -207,7 +207,10 @@ def test_masked_inference_matches_oracle(key, hops, directed, score, with_bias, 
     if with_bias:
         L = layers or w.num_layers
         biases = [0.1 * rng.standard_normal(w.dims[l + 1]).astype(np.float32) for l in range(L)]
+    # 96 rows go through the one-workgroup-per-coalition kernel; 320 rows through the
+    # one-coalition-per-lane kernel when the graph has at most 2048 players
     _eval_case(w, hops, directed, score, biases, 96, rng, layers=layers)
+    _eval_case(w, hops, directed, score, biases, 320, rng, layers=layers)
 
 
 def test_masked_inference_all_enumerated_rows_tiny(ctx_tiny):
