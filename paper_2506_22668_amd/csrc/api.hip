@@ -94,6 +94,13 @@ int ds_create(ds_ctx** out, int device, void* stream) {
   for (int i = 0; i < 8; ++i)
     if (hipEventCreate(&ctx->kev[i]) != hipSuccess) { delete ctx; return DS_EDEVICE; }
   for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
+  ctx->cg_spare = nullptr;
+  ctx->cg_spare_bytes = 0;
+  ctx->h_stage = nullptr;
+  ctx->h_stage_bytes = 0;
+  ctx->stage_busy = false;
+  if (hipEventCreate(&ctx->stage_ev) != hipSuccess) { delete ctx; return DS_EDEVICE; }
+  if (hipMemset(ctx->d_mail, 0, 64 * sizeof(int64_t)) != hipSuccess) { delete ctx; return DS_EDEVICE; }
   *out = ctx;
   return DS_OK;
 }
@@ -108,6 +115,9 @@ int ds_destroy(ds_ctx* ctx) {
   }
   ctx->graphs.clear();
   if (ctx->arena) hipFree(ctx->arena);
+  if (ctx->cg_spare) hipFree(ctx->cg_spare);
+  if (ctx->h_stage) hipHostFree(ctx->h_stage);
+  hipEventDestroy(ctx->stage_ev);
   if (ctx->d_mail) hipFree(ctx->d_mail);
   if (ctx->h_mail) hipHostFree(ctx->h_mail);
   for (int i = 0; i < 6; ++i) hipEventDestroy(ctx->ev[i]);
@@ -235,13 +245,26 @@ int ds_cgraph_first_transform(ds_ctx* ctx, ds_cgraph* cg, float* out) {
 int ds_cgraph_free(ds_ctx* ctx, ds_cgraph* cg) {
   if (!cg) return DS_OK;
   if (!ctx) ctx = cg->owner;
-  hipStreamSynchronize(ctx->stream);
   for (size_t i = 0; i < ctx->graphs.size(); ++i)
     if (ctx->graphs[i] == cg) {
       ctx->graphs.erase(ctx->graphs.begin() + i);
       break;
     }
-  if (cg->block) hipFree(cg->block);
+  if (cg->block) {
+    // keep the larger of (this block, the spare) for the next extraction; later work on the
+    // context's stream is ordered after everything that still reads the block
+    if (cg->block_bytes > ctx->cg_spare_bytes) {
+      if (ctx->cg_spare) {
+        hipStreamSynchronize(ctx->stream);
+        hipFree(ctx->cg_spare);
+      }
+      ctx->cg_spare = cg->block;
+      ctx->cg_spare_bytes = cg->block_bytes;
+    } else {
+      hipStreamSynchronize(ctx->stream);
+      hipFree(cg->block);
+    }
+  }
   delete cg;
   return DS_OK;
 }
@@ -257,6 +280,7 @@ static int sample_checked(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t se
   ds_arena_reset(ctx);
   DS_TRY(ds_arena_reserve(ctx, ds_sample_arena_bytes(plan)));
   int rc = ds_sample_launch(ctx, plan, seed, tag, pb, pe, Z, w, sz);
+  if (rc == DS_OK) rc = ds_sample_check(ctx);
   ds_arena_reset(ctx);
   if (k_out) *k_out = plan.k;
   return rc;
@@ -284,7 +308,10 @@ int ds_eval(ds_ctx* ctx, const ds_cgraph* cg_in, const uint64_t* Z, int64_t k, i
   int rc = ds_eval_impl(ctx, cg, Z, k, score, y, 0);
   if (rc == DS_OK && hipStreamSynchronize(ctx->stream) != hipSuccess) rc = ds_fail(ctx, DS_EDEVICE, "eval kernel failed");
   ds_arena_reset(ctx);
-  if (rc == DS_OK && pred_class_out) *pred_class_out = cg->pred_class;
+  if (rc == DS_OK && pred_class_out) {
+    rc = ds_fetch_pred_class(ctx, cg);
+    *pred_class_out = cg->pred_class;
+  }
   return rc;
 }
 
@@ -413,7 +440,6 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   DS_TRY(ds_eval_impl(ctx, cg, Z, k, o.score, y, o.batch_rows));
   ctx->arena_used = mark;
   DS_HIP(ctx, hipEventRecord(ctx->ev[3], st));
-  rep.pred_class = cg->pred_class;
 
   int rc = DS_OK;
   if (n == 1) {
@@ -423,11 +449,18 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   }
   if (rc != DS_OK && rc != DS_ENOTCONV) return rc;
   DS_HIP(ctx, hipEventRecord(ctx->ev[4], st));
-  float f01[2];
+  // one round trip for everything the host still needs: f(empty), f(full), predicted class, sampler flag
+  float* f01 = (float*)(ctx->h_mail + 32);
   DS_HIP(ctx, hipMemcpyAsync(f01, y, 2 * sizeof(float), hipMemcpyDeviceToHost, st));
+  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + 34, cg->d_pred, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + DS_MAIL_SAMPLER, ctx->d_mail + DS_MAIL_SAMPLER, sizeof(int64_t), hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipStreamSynchronize(st));
+  if (n >= 2 && ctx->h_mail[DS_MAIL_SAMPLER] != 0)
+    return ds_fail(ctx, DS_EINTERNAL, "sampler: candidate list overflow (too many keys share a 24-bit prefix)");
   rep.f_empty = f01[0];
   rep.f_full = f01[1];
+  rep.pred_class = *(int32_t*)(ctx->h_mail + 34);
+  cg->pred_class = rep.pred_class;
   hipEventElapsedTime(&rep.ms_extract, ctx->ev[0], ctx->ev[1]);
   hipEventElapsedTime(&rep.ms_sample, ctx->ev[1], ctx->ev[2]);
   hipEventElapsedTime(&rep.ms_eval, ctx->ev[2], ctx->ev[3]);

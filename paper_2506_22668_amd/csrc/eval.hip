@@ -25,7 +25,8 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
 
 struct EvalArgs {
-  int32_t V, n, L, directed, score, pred_class, bf16;
+  int32_t V, n, L, directed, score, bf16;
+  const int32_t* pred_ptr;  // device: index of the class whose score is returned
   int32_t dims[DS_MAX_LAYERS + 1];
   int32_t rows_out[DS_MAX_LAYERS + 1];  // rows produced by layer l (1..L)
   int64_t W, k;
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
       for (int cidx = tid; cidx < C; cidx += 64) s += expf(bufA[cidx] - m);
       for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
       if (tid == 0) {
-        const float zc = bufA[a.pred_class];
+        const float zc = bufA[*a.pred_ptr];
         a.y[row] = a.score == DS_SCORE_LOGIT ? zc : expf(zc - m) / s;
       }
       if (a.logits_out)
@@ -605,7 +606,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
       for (int c = 0; c < C; ++c) m = fmaxf(m, cur[(size_t)c * 64 + lane]);
       float sum = 0.f;
       for (int c = 0; c < C; ++c) sum += expf(cur[(size_t)c * 64 + lane] - m);
-      const float zc = cur[(size_t)a.pred_class * 64 + lane];
+      const float zc = cur[(size_t)(*a.pred_ptr) * 64 + lane];
       a.y[row] = a.score == DS_SCORE_LOGIT ? zc : expf(zc - m) / sum;
       if (a.logits_out)
         for (int c = 0; c < C; ++c) a.logits_out[row * C + c] = cur[(size_t)c * 64 + lane];
@@ -661,6 +662,23 @@ __global__ __launch_bounds__(kThreads) void first_transform_kernel(const float* 
     const int row = m0 + 8 * (i / 4) + 4 * half + (i % 4);
     if (row < M && bn < Nn) C[(size_t)row * Nn + bn] = acc[i];
   }
+}
+
+// first maximum of logits[0..C) (ties -> lowest index), one wave
+__global__ void argmax_kernel(const float* logits, int C, int32_t* out) {
+  const int lane = threadIdx.x;
+  float best = -INFINITY;
+  int arg = 0x7fffffff;
+  for (int c = lane; c < C; c += 64) {
+    const float v = logits[c];
+    if (v > best) { best = v; arg = c; }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ob = __shfl_xor(best, o, 64);
+    const int oa = __shfl_xor(arg, o, 64);
+    if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+  }
+  if (lane == 0) *out = arg == 0x7fffffff ? 0 : arg;
 }
 
 __global__ void fill_full_mask(uint64_t* z, int64_t W, int n) {
@@ -859,15 +877,12 @@ int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg) {
   a.logits_out = logits;
   a.gws = gws;
   a.score = DS_SCORE_LOGIT;
-  a.pred_class = 0;
+  DS_HIP(ctx, hipMemsetAsync(cg->d_pred, 0, sizeof(int32_t), ctx->stream));
+  a.pred_ptr = cg->d_pred;
   DS_TRY(launch_eval(ctx, a, lay, 1));
-  std::vector<float> h(C);
-  DS_HIP(ctx, hipMemcpyAsync(h.data(), logits, C * 4, hipMemcpyDeviceToHost, ctx->stream));
-  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
-  int best = 0;
-  for (int c = 1; c < C; ++c)
-    if (h[c] > h[best]) best = c;
-  cg->pred_class = best;
+  hipLaunchKernelGGL(argmax_kernel, dim3(1), dim3(64), 0, ctx->stream, logits, C, cg->d_pred);
+  DS_HIP(ctx, hipGetLastError());
+  cg->pred_class = -1;
   cg->model_version = ctx->model_version;
   return DS_OK;
 }
@@ -889,7 +904,7 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
     b.e.logits_out = nullptr;
     b.e.gws = nullptr;
     b.e.score = score;
-    b.e.pred_class = cg->pred_class;
+    b.e.pred_ptr = cg->d_pred;
     b.scratch = scratch;
     b.scratch_stride = bl.stride;
     b.rs_floats = bl.rs_floats;
@@ -930,8 +945,16 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
   a.logits_out = nullptr;
   a.gws = gws;
   a.score = score;
-  a.pred_class = cg->pred_class;
+  a.pred_ptr = cg->d_pred;
   DS_TRY(ds_kernel_mark(ctx, 0, 0));
   DS_TRY(launch_eval(ctx, a, lay, grid));
   return ds_kernel_mark(ctx, 0, 1);
+}
+
+int ds_fetch_pred_class(ds_ctx* ctx, ds_cgraph* cg) {
+  if (cg->pred_class >= 0) return DS_OK;
+  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + 34, cg->d_pred, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  cg->pred_class = *(int32_t*)(ctx->h_mail + 34);
+  return DS_OK;
 }

@@ -427,10 +427,19 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
   const size_t o_rp = carve((V + 1) * 4), o_col = carve(nnz_c * 4 + 4), o_eid = carve(nnz_c * 4 + 4);
   const size_t o_ps = carve(n * 4 + 4), o_pd = carve(n * 4 + 4), o_gid = carve(V * 8), o_hop = carve(V * 4);
   const size_t o_x = carve((size_t)V * d0 * 4), o_p = carve((size_t)V * (d1 > 0 ? d1 : 1) * 4);
-  cg->block_bytes = off;
-  if (hipMalloc(&cg->block, off) != hipSuccess) {
-    delete cg;
-    return ds_fail(ctx, DS_ENOMEM, "extract: cannot allocate %zu bytes for the computational graph", off);
+  const size_t o_pred = carve(256);
+  if (ctx->cg_spare && ctx->cg_spare_bytes >= off) {
+    cg->block = ctx->cg_spare;
+    cg->block_bytes = ctx->cg_spare_bytes;
+    ctx->cg_spare = nullptr;
+    ctx->cg_spare_bytes = 0;
+  } else {
+    cg->block_bytes = off;
+    if (hipMalloc(&cg->block, off) != hipSuccess) {
+      (void)hipGetLastError();
+      delete cg;
+      return ds_fail(ctx, DS_ENOMEM, "extract: cannot allocate %zu bytes for the computational graph", off);
+    }
   }
   char* base = (char*)cg->block;
   cg->row_ptr = (int32_t*)(base + o_rp);
@@ -442,6 +451,8 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
   cg->hop = (int32_t*)(base + o_hop);
   cg->Xc = (float*)(base + o_x);
   cg->P = (float*)(base + o_p);
+  cg->d_pred = (int32_t*)(base + o_pred);
+  cg->pred_class = -1;
   cg->d0 = d0;
   cg->d1 = d1;
   cg->info.num_players = n;

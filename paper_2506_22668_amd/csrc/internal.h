@@ -28,8 +28,9 @@ struct ds_cgraph {
   int32_t* hop;           // [V]
   float* Xc;              // [V x d0] gathered feature rows
   float* P;               // [V x d1] shared first transform Xc * W_1 (valid if model_version matches)
-  uint64_t model_version; // model the cached P / pred_class belong to (0 = none)
-  int32_t pred_class;
+  int32_t* d_pred;        // device: class predicted on the full graph (valid with model_version)
+  uint64_t model_version; // model the cached P / d_pred belong to (0 = none)
+  int32_t pred_class;     // host copy, -1 until fetched
   int32_t d0, d1;
 };
 
@@ -61,6 +62,14 @@ struct ds_ctx {
   hipEvent_t kev[8];   // begin/end pairs: 0 masked inference, 1 Gram, 2 Cholesky, 3 CGLS loop
   bool kev_set[4];
   std::vector<ds_cgraph*> graphs;
+  // one released computational-graph block is kept for the next extraction (no malloc/free per explanation)
+  void* cg_spare;
+  size_t cg_spare_bytes;
+  // pinned staging for the sampling plan tables, and the event that says the last upload from it is done
+  char* h_stage;
+  size_t h_stage_bytes;
+  hipEvent_t stage_ev;
+  bool stage_busy;
 };
 
 int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...);
@@ -97,8 +106,12 @@ struct ds_plan {
   std::vector<float> wtab;  // weight per pair class, wtab[0..H]
 };
 int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan);
+// launches the sampler; the overflow flag is left in device mailbox slot DS_MAIL_SAMPLER (checked by the caller)
 int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t tag, int64_t pair_begin,
                      int64_t pair_end, uint64_t* Z, float* w, int32_t* sz);
+int ds_sample_check(ds_ctx* ctx);  // synchronises and turns the flag into a status
+#define DS_MAIL_SAMPLER 20
+int ds_fetch_pred_class(ds_ctx* ctx, ds_cgraph* cg);  // device -> host copy of the predicted class (synchronises)
 size_t ds_sample_arena_bytes(const ds_plan& plan);
 
 int ds_scan_exclusive_i32(ds_ctx* ctx, const int32_t* in, int32_t* out, int64_t count, int64_t* total_mail_slot);

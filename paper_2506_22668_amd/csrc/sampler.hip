@@ -252,13 +252,31 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
   const int64_t H = plan.H;
   int64_t* d_b = (int64_t*)ds_arena_alloc(ctx, (H + 1) * sizeof(int64_t));
   float* d_wtab = (float*)ds_arena_alloc(ctx, (H + 1) * sizeof(float));
-  int* d_err = (int*)ds_arena_alloc(ctx, 256);
-  if (!d_b || !d_wtab || !d_err) return ds_fail(ctx, DS_EINTERNAL, "sampler: arena exhausted");
-  DS_HIP(ctx, hipMemcpyAsync(d_b, plan.b.data(), (H + 1) * sizeof(int64_t), hipMemcpyHostToDevice, ctx->stream));
-  DS_HIP(ctx, hipMemcpyAsync(d_wtab, plan.wtab.data(), (H + 1) * sizeof(float), hipMemcpyHostToDevice, ctx->stream));
-  DS_HIP(ctx, hipMemsetAsync(d_err, 0, sizeof(int), ctx->stream));
-  // the host vectors must outlive the asynchronous copies
-  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  if (!d_b || !d_wtab) return ds_fail(ctx, DS_EINTERNAL, "sampler: arena exhausted");
+  // the plan tables go through pinned staging so that the upload is asynchronous
+  const size_t need = ds_align((H + 1) * sizeof(int64_t)) + ds_align((H + 1) * sizeof(float));
+  if (ctx->stage_busy) {
+    DS_HIP(ctx, hipEventSynchronize(ctx->stage_ev));
+    ctx->stage_busy = false;
+  }
+  if (need > ctx->h_stage_bytes) {
+    if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+    ctx->h_stage = nullptr;
+    ctx->h_stage_bytes = 0;
+    if (hipHostMalloc((void**)&ctx->h_stage, need, hipHostMallocDefault) != hipSuccess)
+      return ds_fail(ctx, DS_ENOMEM, "sampler: cannot allocate %zu bytes of pinned staging", need);
+    ctx->h_stage_bytes = need;
+  }
+  char* hb = ctx->h_stage;
+  char* hw = ctx->h_stage + ds_align((H + 1) * sizeof(int64_t));
+  memcpy(hb, plan.b.data(), (H + 1) * sizeof(int64_t));
+  memcpy(hw, plan.wtab.data(), (H + 1) * sizeof(float));
+  DS_HIP(ctx, hipMemcpyAsync(d_b, hb, (H + 1) * sizeof(int64_t), hipMemcpyHostToDevice, ctx->stream));
+  DS_HIP(ctx, hipMemcpyAsync(d_wtab, hw, (H + 1) * sizeof(float), hipMemcpyHostToDevice, ctx->stream));
+  DS_HIP(ctx, hipEventRecord(ctx->stage_ev, ctx->stream));
+  ctx->stage_busy = true;
+  int* d_err = (int*)(ctx->d_mail + DS_MAIL_SAMPLER);
+  DS_HIP(ctx, hipMemsetAsync(d_err, 0, sizeof(int64_t), ctx->stream));
   SampleArgs a;
   a.n = plan.n;
   a.W = (plan.n + 63) / 64;
@@ -285,9 +303,14 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
     hipLaunchKernelGGL(sample_pairs_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, a);
   }
   DS_HIP(ctx, hipGetLastError());
-  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, d_err, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+  return DS_OK;
+}
+
+int ds_sample_check(ds_ctx* ctx) {
+  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + DS_MAIL_SAMPLER, ctx->d_mail + DS_MAIL_SAMPLER, sizeof(int64_t),
+                             hipMemcpyDeviceToHost, ctx->stream));
   DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
-  if (*(int*)ctx->h_mail != 0)
+  if (ctx->h_mail[DS_MAIL_SAMPLER] != 0)
     return ds_fail(ctx, DS_EINTERNAL, "sampler: candidate list overflow (more than %d keys share a 24-bit prefix)", kCandMax);
   return DS_OK;
 }
