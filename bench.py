@@ -50,6 +50,21 @@ def cpu_baseline(w, budget_s=15.0):
             f"masked inference only, {wall:.1f} s"}
 
 
+def read_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` on `workload`, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a plain copy of known
+    size). None if no summary covers it."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 4 and parts[0] == "traffic_bytes" and parts[1] == workload and parts[2] == kernel:
+                return float(parts[3])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +72,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB first (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs one GPU's share on one GPU; --gpus must be 1 "
@@ -94,6 +111,8 @@ def main():
         return ctx.explain(targets[i % len(targets)], w.n_samples, w.seed, opts, capacity=capacity,
                            want_edges=False)
 
+    if args.copy_probe_mib > 0:
+        ctx.copy_probe(args.copy_probe_mib << 20)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -131,6 +150,7 @@ def main():
         v["frac"] = v["achieved"] / v["peak"]
     dom_name = max(kernels, key=lambda name: kernels[name]["ms"])
     dom = kernels[dom_name]
+    traffic = read_traffic(dom_name, w.name)
     out = {
         "metric": "masked-GCN coalition evals/sec; end-to-end seconds per explained node",
         "value": k / elapsed,
@@ -147,7 +167,7 @@ def main():
         "stage_ms": {s: mean("ms_" + s) for s in ("extract", "sample", "eval", "solve", "total")},
         "cgls_iterations": mean("cgls_iterations"),
         "roofline": {"kernel": dom_name, "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                     "unit": dom["unit"], "frac": dom["frac"], "traffic": None,
+                     "unit": dom["unit"], "frac": dom["frac"], "traffic": traffic,
                      "avg_launch_ms": dom["ms"]},
         "kernels": {name: {kk: v[kk] for kk in ("ms", "bound", "achieved", "peak", "unit", "frac")}
                     for name, v in kernels.items()},

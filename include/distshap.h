@@ -215,6 +215,11 @@ int ds_eval(ds_ctx* ctx, const ds_cgraph* cg, const uint64_t* Z, int64_t k, int3
 int ds_solve(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
              const ds_options* opts, float* phi, ds_report* report);
 
+/* Measurement aid: a plain device-to-device copy of `bytes` bytes (multiple of 16) by a simple
+ * streaming kernel on the context's stream. Profilers' HBM byte counters are calibrated against it
+ * (its traffic is exactly `bytes` read and `bytes` written). dst and src must not overlap. */
+int ds_copy_probe(ds_ctx* ctx, void* dst, const void* src, int64_t bytes);
+
 /* Library version string ([host], static). */
 const char* ds_version(void);
 

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "ds_create", "ds_destroy", "ds_last_error", "ds_set_graph", "ds_set_features", "ds_set_gcn",
     "ds_explain", "ds_explain_batch", "ds_extract", "ds_cgraph_get_info", "ds_cgraph_edges",
     "ds_cgraph_nodes", "ds_cgraph_first_transform", "ds_cgraph_free", "ds_sample_plan", "ds_sample",
-    "ds_sample_range", "ds_eval", "ds_solve", "ds_version",
+    "ds_sample_range", "ds_eval", "ds_solve", "ds_copy_probe", "ds_version",
 ]
 
 
@@ -90,6 +90,7 @@ def load_library():
         "ds_sample_range": [p, i64, i64, u64, u32, i64, i64, p, p, p],
         "ds_eval": [p, p, p, i64, i32, p, C.POINTER(i32)],
         "ds_solve": [p, i64, i64, p, p, p, C.POINTER(Options), p, C.POINTER(Report)],
+        "ds_copy_probe": [p, p, p, i64],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -304,6 +305,14 @@ class Context:
         self._sync_inputs()
         self._check(self.lib.ds_eval(self.h, cg, _ptr(Z), k, score, _ptr(y), C.byref(pc)))
         return y[:k], pc.value
+
+    def copy_probe(self, nbytes):
+        """Plain device copy of nbytes (calibration of profiler byte counters)."""
+        t = self.torch
+        src = t.zeros(nbytes // 8, dtype=t.int64, device=self.device)
+        dst = t.empty_like(src)
+        self._sync_inputs()
+        self._check(self.lib.ds_copy_probe(self.h, _ptr(dst), _ptr(src), int(nbytes)))
 
     def solve(self, n, Z, w, y, options=None, allow_not_converged=False):
         t = self.torch

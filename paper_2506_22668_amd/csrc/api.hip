@@ -366,6 +366,20 @@ int ds_solve(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* 
 
 __global__ void single_player_kernel(const float* y, float* phi) { phi[0] = y[1] - y[0]; }
 
+__global__ void copy_probe_kernel(uint4* dst, const uint4* src, int64_t count) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+int ds_copy_probe(ds_ctx* ctx, void* dst, const void* src, int64_t bytes) {
+  if (!ctx || !dst || !src || bytes < 0 || (bytes & 15)) return ds_fail(ctx, DS_EINVAL, "copy probe: bytes must be a non-negative multiple of 16");
+  if (bytes == 0) return DS_OK;
+  hipLaunchKernelGGL(copy_probe_kernel, dim3(ctx->num_cus * 16), dim3(256), 0, ctx->stream, (uint4*)dst, (const uint4*)src, bytes / 16);
+  DS_HIP(ctx, hipGetLastError());
+  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return DS_OK;
+}
+
 int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, const ds_options* opts, float* phi,
                int64_t* M_inout, int64_t* edge_src, int64_t* edge_dst, ds_report* report) {
   if (!ctx || !M_inout) return DS_EINVAL;

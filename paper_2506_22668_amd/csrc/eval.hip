@@ -345,17 +345,10 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
   };
   auto bit_of = [&](int p) -> bool { return (zs[(p >> 6) * 64 + lane] >> (p & 63)) & 1ull; };
 
-#ifdef DS_PROFILE_PHASES
-  long long tph[8];
-#define TPH(i) tph[i] = wall_clock64()
-#else
-#define TPH(i)
-#endif
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
     const int64_t row = blk * 64 + lane;
     const bool valid = row < a.k;
     __syncthreads();
-    TPH(0);
     for (int w = wave; w < W; w += kBWaves) {
       uint64_t word = valid ? a.Z[row * W + w] : 0ull;
       if (w == W - 1) word &= tail_mask;
@@ -374,9 +367,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
       if (DEG_LDS) degs[v * 64 + lane] = (unsigned short)cnt;
       else rs[(size_t)v * 64 + lane] = 1.0f / sqrtf((float)cnt);
     }
-    TPH(1);
     __syncthreads();
-    TPH(2);
 
     // layer 1 on the matrix cores: for row t, H1[f][c] = sum_e P[src_e][f] * coef[e][c] is a product
     // (features x entries) . (entries x coalitions). With v_mfma_f32_32x32x2f32 lane l supplies
@@ -460,9 +451,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
         }
       }
     }
-    TPH(3);
     __syncthreads();
-    TPH(4);
 
     float* cur = bufA;
     float* nxt = bufB;
@@ -516,9 +505,6 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
           }
       }
       __syncthreads();
-#ifdef DS_PROFILE_PHASES
-      if (l == 2) tph[7] = wall_clock64();
-#endif
       // phase B: out[t][j] = act( sum_f q[t][f] W[f][j] + b[j] ). W is the same for every lane:
       // the workgroup copies it (in row chunks if it is large) into the LDS staging area once and
       // the waves read it back as broadcasts.
@@ -590,14 +576,8 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
         }
       }
       __syncthreads();
-      TPH(3 + l);
       float* tmp = cur; cur = nxt; nxt = tmp;
     }
-#ifdef DS_PROFILE_PHASES
-    if (lane == 0 && (blockIdx.x == 0 || blockIdx.x == 100) && blk == blockIdx.x)
-      printf("blk %d wave %d: masks+deg %lld, wait %lld, layer1 %lld, wait %lld, layer2 %lld (agg %lld), layer3 %lld (x10ns) rows %d %d %d deg0 %d\n", (int)blockIdx.x, wave,
-             tph[1] - tph[0], tph[2] - tph[1], tph[3] - tph[2], tph[4] - tph[3], tph[5] - tph[4], tph[7] - tph[4], tph[6] - tph[5], a.rows_out[1], a.rows_out[2], a.rows_out[3], rp_[a.rows_out[2]]);
-#endif
 
     // readout: logits of the target are cur[c][lane], c < d_L (row 0)
     if (wave == 0 && valid) {

@@ -224,9 +224,6 @@ __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t 
       y[i][j] = r == c ? 1.0 : 0.0;
     }
   bool bad = false;
-#ifdef DS_PROFILE_PHASES
-  const long long tq0 = wall_clock64();
-#endif
   for (int kk = 0; kk < NB; ++kk) {
     const int buf = kk & 1, blk = kk >> 4, off = kk & 15;
     if (tx == off) {
@@ -284,9 +281,6 @@ __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t 
     if (tid == 0) dinv[kk] = rinv;
   }
   __syncthreads();
-#ifdef DS_PROFILE_PHASES
-  if (tid == 0 && j0 == 0) printf("chol_diag: factor+inverse %lld (x10ns)\n", wall_clock64() - tq0);
-#endif
   if (bad && tid == 0) atomicExch(flag, 1);
 #pragma unroll
   for (int i = 0; i < 4; ++i)
