@@ -215,6 +215,15 @@ int ds_eval(ds_ctx* ctx, const ds_cgraph* cg, const uint64_t* Z, int64_t k, int3
 int ds_solve(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
              const ds_options* opts, float* phi, ds_report* report);
 
+/* Top-k explanation sub-graph and its fidelity (paper, overview step 5 and the evaluation-metric
+ * equations): for each k = topk[t], G_s = the k players with the largest phi (ties to the lower
+ * index), fid_plus[t] = |f(G_c) - f(G_c \ G_s)|, fid_minus[t] = |f(G_c) - f(G_s)|, with f the masked
+ * GCN inference of ds_eval. phi: float[n] (device). topk [host]: int64[num_k], values outside [0, n]
+ * are clamped. fid_plus, fid_minus [host]: float[num_k] out. masks_out: NULL, or uint64[2*num_k*W]
+ * (device) receiving row 2t = G_s and row 2t+1 = its complement. 1 <= num_k <= 4096. */
+int ds_fidelity(ds_ctx* ctx, const ds_cgraph* cg, const float* phi, const int64_t* topk, int32_t num_k,
+                int32_t score, float* fid_plus, float* fid_minus, uint64_t* masks_out);
+
 /* Measurement aid: a plain device-to-device copy of `bytes` bytes (multiple of 16) by a simple
  * streaming kernel on the context's stream. Profilers' HBM byte counters are calibrated against it
  * (its traffic is exactly `bytes` read and `bytes` written). dst and src must not overlap. */

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "ds_create", "ds_destroy", "ds_last_error", "ds_set_graph", "ds_set_features", "ds_set_gcn",
     "ds_explain", "ds_explain_batch", "ds_extract", "ds_cgraph_get_info", "ds_cgraph_edges",
     "ds_cgraph_nodes", "ds_cgraph_first_transform", "ds_cgraph_free", "ds_sample_plan", "ds_sample",
-    "ds_sample_range", "ds_eval", "ds_solve", "ds_copy_probe", "ds_version",
+    "ds_sample_range", "ds_eval", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
 ]
 
 
@@ -91,6 +91,7 @@ def load_library():
         "ds_eval": [p, p, p, i64, i32, p, C.POINTER(i32)],
         "ds_solve": [p, i64, i64, p, p, p, C.POINTER(Options), p, C.POINTER(Report)],
         "ds_copy_probe": [p, p, p, i64],
+        "ds_fidelity": [p, p, p, C.POINTER(i64), i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), p],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -305,6 +306,20 @@ class Context:
         self._sync_inputs()
         self._check(self.lib.ds_eval(self.h, cg, _ptr(Z), k, score, _ptr(y), C.byref(pc)))
         return y[:k], pc.value
+
+    def fidelity(self, cg, phi, ks, score=DS_SCORE_PROB, want_masks=False):
+        """(fid_plus, fid_minus[, masks]) for the top-k sub-graphs, k in ks."""
+        t = self.torch
+        T = len(ks)
+        n = self.cgraph_info(cg).num_players
+        phi = phi.contiguous()
+        kk = (C.c_int64 * T)(*[int(x) for x in ks])
+        fp, fm = (C.c_float * T)(), (C.c_float * T)()
+        masks = t.empty((2 * T, max((n + 63) // 64, 1)), dtype=t.int64, device=self.device) if want_masks else None
+        self._sync_inputs()
+        self._check(self.lib.ds_fidelity(self.h, cg, _ptr(phi), kk, T, score, fp, fm, _ptr(masks)))
+        out = (list(fp), list(fm))
+        return out + (masks,) if want_masks else out
 
     def copy_probe(self, nbytes):
         """Plain device copy of nbytes (calibration of profiler byte counters)."""

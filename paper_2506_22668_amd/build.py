@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdistshap_hip.so")
 SOURCES = ["api.hip", "sampler.hip", "extract.hip", "eval.hip", "bitmat.hip",
-           "gram_chol.hip", "cgls.hip", "plan.cpp"]
+           "gram_chol.hip", "cgls.hip", "fidelity.hip", "plan.cpp"]
 
 
 def build_library(verbose=True):
