@@ -134,6 +134,158 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_kernel(const uint64_t* B, i
   }
 }
 
+
+// ---- dense rows: byte-table product -------------------------------------------------------
+// out[i] = sum over set bits j of row i of x[j], for rows that are dense enough that walking
+// bits one by one costs more than it should. For a chunk of 512 columns the workgroup builds,
+// in LDS, the 64 tables T_g[b] = sum of x over the bits of byte value b within column group g
+// (from two 16-entry nibble tables per group), and every thread then adds eight table entries
+// per 64-bit word of its rows: one LDS read per 8 matrix bits, whatever the density. A
+// workgroup covers 2048 rows x a range of chunks; the per-range partial sums are added up in a
+// fixed order by a second kernel.
+constexpr int kTabCols = 512;
+constexpr int kTabWords = kTabCols / 64;
+constexpr int kTabGroups = kTabCols / 8;
+constexpr int kTabRpt = 8;  // rows per thread
+constexpr int kTabRows = kThreads * kTabRpt;
+
+__global__ __launch_bounds__(kThreads) void bit_spmv_tab_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
+                                                                int64_t row_first, int64_t row_step, const double* x,
+                                                                double* partial, int64_t chunks_per_group, int64_t n_chunks) {
+  extern __shared__ double tab_smem[];
+  double* tab = tab_smem;                       // [64 groups][256]
+  double* nib = tab_smem + kTabGroups * 256;    // [64 groups][2 nibbles][16]
+  const int tid = threadIdx.x;
+  const int64_t Wc = (cols + 63) / 64;
+  const uint64_t tail = (cols & 63) ? ((1ull << (cols & 63)) - 1ull) : ~0ull;
+  const int64_t rbase = (int64_t)blockIdx.x * kTabRows;
+  double acc[kTabRpt];
+#pragma unroll
+  for (int i = 0; i < kTabRpt; ++i) acc[i] = 0.0;
+  const int64_t c_begin = (int64_t)blockIdx.y * chunks_per_group;
+  const int64_t c_end = c_begin + chunks_per_group < n_chunks ? c_begin + chunks_per_group : n_chunks;
+  for (int64_t c = c_begin; c < c_end; ++c) {
+    __syncthreads();
+    for (int e = tid; e < kTabGroups * 32; e += kThreads) {
+      const int g = e >> 5, half = (e >> 4) & 1, m = e & 15;
+      const int64_t col0 = c * kTabCols + g * 8 + half * 4;
+      double sum = 0.0;
+#pragma unroll
+      for (int bbit = 0; bbit < 4; ++bbit)
+        if ((m >> bbit) & 1) sum += (col0 + bbit < cols) ? x[col0 + bbit] : 0.0;
+      nib[e] = sum;
+    }
+    __syncthreads();
+    for (int e = tid; e < kTabGroups * 256; e += kThreads) {
+      const int g = e >> 8, byte = e & 255;
+      tab[e] = nib[g * 32 + (byte & 15)] + nib[g * 32 + 16 + (byte >> 4)];
+    }
+    __syncthreads();
+    // all words of the thread's rows for this chunk are requested first (their latency overlaps);
+    // then, word by word, the eight table reads are issued together and summed as a tree, so that
+    // the LDS pipeline stays full instead of waiting on one read at a time
+    uint64_t wv[kTabRpt][kTabWords];
+#pragma unroll
+    for (int i = 0; i < kTabRpt; ++i) {
+      const int64_t r = rbase + (int64_t)i * kThreads + tid;
+      const uint64_t* p = B + (row_first + (r < rows ? r : 0) * row_step) * stride + c * kTabWords;
+#pragma unroll
+      for (int q = 0; q < kTabWords; ++q) {
+        const int64_t wd = c * kTabWords + q;
+        uint64_t v = (r < rows && wd < Wc) ? p[q] : 0ull;
+        if (wd == Wc - 1) v &= tail;
+        wv[i][q] = v;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kTabRpt; ++i) {
+      double rowsum = 0.0;
+#pragma unroll
+      for (int q = 0; q < kTabWords; ++q) {
+        const uint32_t lo = (uint32_t)wv[i][q], hi = (uint32_t)(wv[i][q] >> 32);
+        const double* tq = tab + q * 8 * 256;
+        const double t0 = tq[0 * 256 + (lo & 0xFF)];
+        const double t1 = tq[1 * 256 + ((lo >> 8) & 0xFF)];
+        const double t2 = tq[2 * 256 + ((lo >> 16) & 0xFF)];
+        const double t3 = tq[3 * 256 + (lo >> 24)];
+        const double t4 = tq[4 * 256 + (hi & 0xFF)];
+        const double t5 = tq[5 * 256 + ((hi >> 8) & 0xFF)];
+        const double t6 = tq[6 * 256 + ((hi >> 16) & 0xFF)];
+        const double t7 = tq[7 * 256 + (hi >> 24)];
+        rowsum += ((t0 + t1) + (t2 + t3)) + ((t4 + t5) + (t6 + t7));
+      }
+      acc[i] += rowsum;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kTabRpt; ++i) {
+    const int64_t r = rbase + (int64_t)i * kThreads + tid;
+    if (r < rows) partial[(int64_t)blockIdx.y * rows + r] = acc[i];
+  }
+}
+
+__global__ void tab_reduce_kernel(const double* partial, int64_t rows, int groups, const double* addend, double* out) {
+  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= rows) return;
+  double s = addend ? addend[r] : 0.0;
+  for (int g = 0; g < groups; ++g) s += partial[(int64_t)g * rows + r];
+  out[r] = s;
+}
+
+// ---- sparse rows: index lists ----------------------------------------------------------------
+// idx[off[i] .. off[i+1]) = ascending columns of the set bits of row i; one wave per row
+__global__ __launch_bounds__(kThreads) void rows_to_csr_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
+                                                               int64_t row_first, int64_t row_step, const int32_t* off,
+                                                               int32_t* idx) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+  const int64_t Wc = (cols + 63) / 64;
+  const uint64_t tail = (cols & 63) ? ((1ull << (cols & 63)) - 1ull) : ~0ull;
+  for (int64_t i = wave; i < rows; i += nwaves) {
+    const uint64_t* row = B + (row_first + i * row_step) * stride;
+    int32_t base = off[i];
+    for (int64_t w0 = 0; w0 < Wc; w0 += 64) {
+      const int64_t wd = w0 + lane;
+      uint64_t word = wd < Wc ? row[wd] : 0ull;
+      if (wd == Wc - 1) word &= tail;
+      const int cnt = __popcll(word);
+      int pre = cnt;  // inclusive scan over the lanes
+      for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(pre, o, 64);
+        if (lane >= o) pre += v;
+      }
+      int32_t at = base + pre - cnt;
+      while (word) {
+        idx[at++] = (int32_t)(wd * 64 + __ffsll((long long)word) - 1);
+        word &= word - 1;
+      }
+      base += __shfl(pre, 63, 64);
+    }
+  }
+}
+
+// out[i] = sum_{e in [off[i], off[i+1])} x[idx[e]]; one wave per row, rows taken from the long end first
+__global__ __launch_bounds__(kThreads) void csr_gather_kernel(const int32_t* off, const int32_t* idx, int64_t rows,
+                                                              const double* x, double* out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+  for (int64_t w = wave; w < rows; w += nwaves) {
+    const int64_t i = rows - 1 - w;
+    const int32_t a = off[i], b = off[i + 1];
+    double s0 = 0.0, s1 = 0.0;
+    int32_t e = a + lane;
+    for (; e + 64 < b; e += 128) {
+      s0 += x[idx[e]];
+      s1 += x[idx[e + 64]];
+    }
+    if (e < b) s0 += x[idx[e]];
+    double s = s0 + s1;
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (lane == 0) out[i] = s;
+  }
+}
 }  // namespace
 
 int ds_bit_spmv(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
@@ -165,6 +317,59 @@ int ds_bit_transpose(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols
   if (blocks < 1) return DS_OK;
   hipLaunchKernelGGL(bit_transpose_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, in, rows, cols,
                      in_stride, row_first, row_step, out, Wout);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
+
+size_t ds_bit_spmv_tab_ws_doubles(const ds_ctx* ctx, int64_t rows, int64_t cols) {
+  const int64_t row_groups = (rows + kTabRows - 1) / kTabRows;
+  const int64_t n_chunks = (cols + kTabCols - 1) / kTabCols;
+  int64_t groups = (6 * (int64_t)ctx->num_cus + row_groups - 1) / (row_groups > 0 ? row_groups : 1);
+  if (groups > n_chunks) groups = n_chunks;
+  if (groups < 1) groups = 1;
+  return (size_t)groups * (size_t)rows;
+}
+
+int ds_bit_spmv_tab(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
+                    int64_t row_step, const double* x, const double* addend, double* out, double* ws) {
+  if (rows <= 0) return DS_OK;
+  const int64_t row_groups = (rows + kTabRows - 1) / kTabRows;
+  const int64_t n_chunks = (cols + kTabCols - 1) / kTabCols;
+  int64_t groups = (6 * (int64_t)ctx->num_cus + row_groups - 1) / row_groups;
+  if (groups > n_chunks) groups = n_chunks;
+  if (groups < 1) groups = 1;
+  const int64_t cpg = (n_chunks + groups - 1) / groups;
+  groups = (n_chunks + cpg - 1) / cpg;
+  const size_t lds = (size_t)(kTabGroups * 256 + kTabGroups * 32) * sizeof(double);
+  static bool attr_set = false;
+  if (!attr_set) {
+    DS_HIP(ctx, hipFuncSetAttribute((const void*)bit_spmv_tab_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(bit_spmv_tab_kernel, dim3((unsigned)row_groups, (unsigned)groups), dim3(kThreads), lds, ctx->stream, B,
+                     rows, cols, stride, row_first, row_step, x, ws, cpg, n_chunks);
+  hipLaunchKernelGGL(tab_reduce_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, ctx->stream, ws, rows,
+                     (int)groups, addend, out);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
+
+int ds_rows_to_csr(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
+                   int64_t row_step, const int32_t* off, int32_t* idx) {
+  if (rows <= 0) return DS_OK;
+  int64_t blocks = (rows * 64 + kThreads - 1) / kThreads;
+  if (blocks > (int64_t)ctx->num_cus * 16) blocks = (int64_t)ctx->num_cus * 16;
+  hipLaunchKernelGGL(rows_to_csr_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, B, rows, cols, stride,
+                     row_first, row_step, off, idx);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
+
+int ds_csr_gather(ds_ctx* ctx, const int32_t* off, const int32_t* idx, int64_t rows, const double* x, double* out) {
+  if (rows <= 0) return DS_OK;
+  int64_t blocks = (rows * 64 + kThreads - 1) / kThreads;
+  if (blocks > (int64_t)ctx->num_cus * 16) blocks = (int64_t)ctx->num_cus * 16;
+  hipLaunchKernelGGL(csr_gather_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, off, idx, rows, x, out);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }

@@ -185,11 +185,42 @@ __global__ void final_x_kernel(Vecs a, const float* y, float* phi) {
 
 inline unsigned nblocks(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
+// ---- hybrid storage of the small members (paired rows, sorted by size) ----
+// cnt[r] = size of the small member of pair r; mail[0] = rows with cnt <= thr, mail[1] = 1 if not ascending
+__global__ void pair_sizes_kernel(const int32_t* sz, int64_t R, int32_t thr, int32_t* cnt, int64_t* mail) {
+  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= R) return;
+  const int32_t c = sz[2 * r];
+  cnt[r] = c;
+  if (c <= thr) atomicAdd((unsigned long long*)&mail[0], 1ull);
+  if (r > 0 && sz[2 * (r - 1)] > c) atomicExch((unsigned long long*)&mail[1], 1ull);
+}
+
+// cnt[i] = number of set bits of row i (rows of `words` 64-bit words); one wave per row
+__global__ __launch_bounds__(kThreads) void row_popcount_kernel(const uint64_t* B, int64_t rows, int64_t words, int32_t* cnt) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+  for (int64_t i = wave; i < rows; i += nwaves) {
+    int c = 0;
+    for (int64_t wd = lane; wd < words; wd += 64) c += __popcll(B[i * words + wd]);
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+    if (lane == 0) cnt[i] = c;
+  }
+}
+
+constexpr int64_t kHybridMinPlayers = 4096;  // below this the plain bit walk is already cheap
+
 }  // namespace
 
 size_t ds_cgls_arena_bytes(int64_t n, int64_t k) {
   const int64_t KW = (k + 63) / 64;
-  return ds_align((size_t)n * KW * 8) + 2 * ds_align(k * 4) + 7 * ds_align(k * 8) + 4 * ds_align(n * 8) + 16384;
+  // the hybrid storage (index lists both ways for the sparse rows + transposed bitmap of the dense rows)
+  // never exceeds twice the plain transposed bitmap, and building it needs one more as a temporary;
+  // plus offsets and table-product scratch
+  const size_t hybrid = 3 * ds_align((size_t)n * KW * 8) + 4 * ds_align((n + 2) * 4) + 2 * ds_align((k + 2) * 4) +
+                        ds_align(8 * (size_t)(n > k ? n : k) * 64) + 4 * ds_scan_arena_bytes(n > k ? n + 1 : k + 1);
+  return hybrid + 2 * ds_align(k * 4) + 7 * ds_align(k * 8) + 4 * ds_align(n * 8) + 65536;
 }
 
 int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y, int paired,
@@ -202,7 +233,6 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   if (tol <= 0) tol = 1e-6;
   if (max_iter <= 0) max_iter = (int)(n < 10000 ? n : 10000);
 
-  uint64_t* Zt = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * RW * 8);
   int32_t* sz = (int32_t*)ds_arena_alloc(ctx, k * 4);
   float* wc = (float*)ds_arena_alloc(ctx, k * 4);
   double* t = (double*)ds_arena_alloc(ctx, k * 8);
@@ -219,11 +249,81 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   a.s = (double*)ds_arena_alloc(ctx, n * 8);
   a.scal = (double*)ds_arena_alloc(ctx, 64);
   a.part = (double*)ds_arena_alloc(ctx, 2 * kRed * 8);
-  if (!Zt || !sz || !wc || !t || !sqw || !a.r || !a.v || !a.d || !a.h || !a.x || !a.u || !a.s || !a.scal || !a.part)
+  if (!sz || !wc || !t || !sqw || !a.r || !a.v || !a.d || !a.h || !a.x || !a.u || !a.s || !a.scal || !a.part)
     return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
 
   DS_TRY(ds_row_prep(ctx, Z, k, n, w, y, sz, t, sqw, wc));
-  DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, Zt));
+
+  // ---- storage for the two products ----
+  // Paired, size-sorted rows of a large game: the small members with at most n/32 players become
+  // index lists (4 B per set bit is less than their n/8-byte bitmap rows) in both orientations,
+  // the denser tail stays a bitmap (rows of Z itself, plus a transposed copy) and is multiplied
+  // through byte tables. Otherwise: plain bitmap and its transpose, set bits walked one by one.
+  bool hybrid = false;
+  int64_t Rs = 0, Rd = 0, RdW = 0, nnz_s = 0;
+  int32_t *csr_off = nullptr, *csr_idx = nullptr, *csc_off = nullptr, *csc_row = nullptr;
+  uint64_t *Zt = nullptr, *Ztd = nullptr;
+  double* tab_ws = nullptr;
+  if (paired && n >= kHybridMinPlayers) {
+    int32_t* cnt = (int32_t*)ds_arena_alloc(ctx, (R + 1) * 4);
+    if (!cnt) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
+    DS_HIP(ctx, hipMemsetAsync(ctx->d_mail, 0, 4 * sizeof(int64_t), st));
+    hipLaunchKernelGGL(pair_sizes_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, sz, R, (int32_t)(n / 32), cnt, ctx->d_mail);
+    DS_TRY(ds_mail_fetch(ctx, 4));
+    if (ctx->h_mail[1] == 0) {
+      hybrid = true;
+      Rs = ctx->h_mail[0];
+      Rd = R - Rs;
+      RdW = (Rd + 63) / 64;
+      csr_off = (int32_t*)ds_arena_alloc(ctx, (Rs + 2) * 4);
+      if (!csr_off) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
+      DS_HIP(ctx, hipMemsetAsync(cnt + Rs, 0, 4, st));  // the scan's last slot: total
+      DS_TRY(ds_scan_exclusive_i32(ctx, cnt, csr_off, Rs + 1, ctx->d_mail + 2));
+      DS_TRY(ds_mail_fetch(ctx, 4));
+      nnz_s = ctx->h_mail[2];
+      if (nnz_s > 0x7fffff00LL) return ds_fail(ctx, DS_EINTERNAL, "cgls: too many set bits in the sparse rows (%lld)", (long long)nnz_s);
+      csr_idx = (int32_t*)ds_arena_alloc(ctx, (nnz_s + 1) * 4);
+      csc_row = (int32_t*)ds_arena_alloc(ctx, (nnz_s + 1) * 4);
+      csc_off = (int32_t*)ds_arena_alloc(ctx, (n + 2) * 4);
+      int32_t* cursor = (int32_t*)ds_arena_alloc(ctx, (n + 2) * 4);
+      Ztd = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * (RdW > 0 ? RdW : 1) * 8);
+      const size_t wsd = ds_bit_spmv_tab_ws_doubles(ctx, Rd, n), wsd2 = ds_bit_spmv_tab_ws_doubles(ctx, n, Rd);
+      tab_ws = (double*)ds_arena_alloc(ctx, 8 * (wsd > wsd2 ? wsd : wsd2) + 8);
+      if (!csr_idx || !csc_row || !csc_off || !cursor || !Ztd || !tab_ws) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
+      DS_TRY(ds_rows_to_csr(ctx, Z, Rs, n, W, 0, 2, csr_off, csr_idx));
+      // column lists of the sparse rows = row lists of their transposed bitmap (a temporary): built by
+      // the same ordered kernel, so every list is ascending and the sums are reproducible
+      DS_HIP(ctx, hipMemsetAsync(csc_off, 0, (n + 2) * 4, st));
+      if (Rs > 0) {
+        const int64_t RsW = (Rs + 63) / 64;
+        uint64_t* Zts = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * RsW * 8);
+        if (!Zts) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
+        DS_TRY(ds_bit_transpose(ctx, Z, Rs, n, W, 0, 2, Zts));
+        hipLaunchKernelGGL(row_popcount_kernel, dim3(ctx->num_cus * 8), dim3(kThreads), 0, st, Zts, n, RsW, csc_off);
+        DS_TRY(ds_scan_exclusive_i32(ctx, csc_off, csc_off, n + 1, nullptr));
+        DS_TRY(ds_rows_to_csr(ctx, Zts, n, Rs, RsW, 0, 1, csc_off, csc_row));
+      }
+      (void)cursor;
+      if (Rd > 0) DS_TRY(ds_bit_transpose(ctx, Z, Rd, n, W, 2 * Rs, 2, Ztd));
+      DS_HIP(ctx, hipGetLastError());
+    }
+  }
+  if (!hybrid) {
+    Zt = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * RW * 8);
+    if (!Zt) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
+    DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, Zt));
+  }
+  auto forward = [&](const double* u, double* d) -> int {  // d = (rows) . u
+    if (!hybrid) return ds_bit_spmv(ctx, Z, R, n, W, 0, paired ? 2 : 1, u, d);
+    DS_TRY(ds_csr_gather(ctx, csr_off, csr_idx, Rs, u, d));
+    return ds_bit_spmv_tab(ctx, Z, Rd, n, W, 2 * Rs, 2, u, nullptr, d + Rs, tab_ws);
+  };
+  auto adjoint = [&](const double* h, double* sv) -> int {  // s = (rows)^T . h
+    if (!hybrid) return ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, h, sv);
+    if (Rs > 0) DS_TRY(ds_csr_gather(ctx, csc_off, csc_row, n, h, sv));
+    if (Rd > 0) return ds_bit_spmv_tab(ctx, Ztd, n, Rd, RdW, 0, 1, h + Rs, Rs > 0 ? sv : nullptr, sv, tab_ws);
+    return DS_OK;
+  };
   DS_HIP(ctx, hipMemsetAsync(a.x, 0, n * 8, st));
   DS_HIP(ctx, hipMemsetAsync(a.u, 0, n * 8, st));
   DS_HIP(ctx, hipMemsetAsync(a.scal, 0, 64, st));
@@ -234,7 +334,7 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   // s_0 = P A^T r_0, u_0 = s_0
   hipLaunchKernelGGL(init_r_kernel, dim3(nblocks(k, 256)), dim3(256), 0, st, a, t);
   hipLaunchKernelGGL(make_h_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
-  DS_TRY(ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, a.h, a.s));
+  DS_TRY(adjoint(a.h, a.s));
   hipLaunchKernelGGL(s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
   hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
   hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
@@ -250,11 +350,11 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   bool converged = !(gamma0 > 0);
   DS_TRY(ds_kernel_mark(ctx, 3, 0));
   while (!converged && it < max_iter) {
-    DS_TRY(ds_bit_spmv(ctx, Z, R, n, W, 0, paired ? 2 : 1, a.u, a.d));
+    DS_TRY(forward(a.u, a.d));
     hipLaunchKernelGGL(make_v_kernel, dim3(red_r), dim3(kThreads), 0, st, a);
     hipLaunchKernelGGL(fin_delta_kernel, dim3(1), dim3(1), 0, st, a, (int)red_r);
     hipLaunchKernelGGL(update_r_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
-    DS_TRY(ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, a.h, a.s));
+    DS_TRY(adjoint(a.h, a.s));
     hipLaunchKernelGGL(s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
     hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
     hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);

@@ -12,3 +12,12 @@ int ds_bit_transpose(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols
 // out[i] = sum of x[j] over the set bits j < cols of row (row_first + i*row_step) of B, i < rows (fp64)
 int ds_bit_spmv(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
                 int64_t row_step, const double* x, double* out);
+// same product for dense rows through per-byte partial-sum tables in LDS; out = (addend or 0) + result.
+// ws: ds_bit_spmv_tab_ws_doubles(ctx, rows, cols) doubles of scratch
+size_t ds_bit_spmv_tab_ws_doubles(const ds_ctx* ctx, int64_t rows, int64_t cols);
+int ds_bit_spmv_tab(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
+                    int64_t row_step, const double* x, const double* addend, double* out, double* ws);
+// index lists of the set bits of rows (off = exclusive prefix sums of the row sizes), and the gather-sum over them
+int ds_rows_to_csr(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
+                   int64_t row_step, const int32_t* off, int32_t* idx);
+int ds_csr_gather(ds_ctx* ctx, const int32_t* off, const int32_t* idx, int64_t rows, const double* x, double* out);

@@ -252,7 +252,9 @@ def test_gram_cholesky_matches_oracle_least_squares(ctx_tiny, n, ns):
 
 
 @pytest.mark.parametrize("n,ns,paired", [(12, 4096, 1), (40, 2000, 0), (40, 2000, 1), (333, 6000, 1),
-                                         (1000, 20000, 1), (1000, 20000, 0), (3000, 1000, 1), (3000, 1000, 0)])
+                                         (1000, 20000, 1), (1000, 20000, 0), (3000, 1000, 1), (3000, 1000, 0),
+                                         # >= 4096 players and paired: index lists + byte tables
+                                         (4100, 3000, 1), (6000, 14000, 1), (4097, 130, 1), (5000, 2000, 0)])
 def test_cgls_matches_oracle(ctx_tiny, n, ns, paired):
     from paper_2506_22668_amd import Options, DS_SOLVER_CGLS
     ctx, _ = ctx_tiny
