@@ -146,10 +146,11 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_kernel(const uint64_t* B, i
 constexpr int kTabCols = 512;
 constexpr int kTabWords = kTabCols / 64;
 constexpr int kTabGroups = kTabCols / 8;
-constexpr int kTabRpt = 8;  // rows per thread
-constexpr int kTabRows = kThreads * kTabRpt;
+constexpr int kTabThreads = 1024;  // 16 waves hide the LDS and memory latency of the look-ups
+constexpr int kTabRpt = 2;         // rows per thread
+constexpr int kTabRows = kTabThreads * kTabRpt;
 
-__global__ __launch_bounds__(kThreads) void bit_spmv_tab_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
+__global__ __launch_bounds__(kTabThreads) void bit_spmv_tab_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
                                                                 int64_t row_first, int64_t row_step, const double* x,
                                                                 double* partial, int64_t chunks_per_group, int64_t n_chunks) {
   extern __shared__ double tab_smem[];
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_tab_kernel(const uint64_t* 
   const int64_t c_end = c_begin + chunks_per_group < n_chunks ? c_begin + chunks_per_group : n_chunks;
   for (int64_t c = c_begin; c < c_end; ++c) {
     __syncthreads();
-    for (int e = tid; e < kTabGroups * 32; e += kThreads) {
+    for (int e = tid; e < kTabGroups * 32; e += kTabThreads) {
       const int g = e >> 5, half = (e >> 4) & 1, m = e & 15;
       const int64_t col0 = c * kTabCols + g * 8 + half * 4;
       double sum = 0.0;
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_tab_kernel(const uint64_t* 
       nib[e] = sum;
     }
     __syncthreads();
-    for (int e = tid; e < kTabGroups * 256; e += kThreads) {
+    for (int e = tid; e < kTabGroups * 256; e += kTabThreads) {
       const int g = e >> 8, byte = e & 255;
       tab[e] = nib[g * 32 + (byte & 15)] + nib[g * 32 + 16 + (byte >> 4)];
     }
@@ -187,7 +188,7 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_tab_kernel(const uint64_t* 
     uint64_t wv[kTabRpt][kTabWords];
 #pragma unroll
     for (int i = 0; i < kTabRpt; ++i) {
-      const int64_t r = rbase + (int64_t)i * kThreads + tid;
+      const int64_t r = rbase + (int64_t)i * kTabThreads + tid;
       const uint64_t* p = B + (row_first + (r < rows ? r : 0) * row_step) * stride + c * kTabWords;
 #pragma unroll
       for (int q = 0; q < kTabWords; ++q) {
@@ -219,7 +220,7 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_tab_kernel(const uint64_t* 
   }
 #pragma unroll
   for (int i = 0; i < kTabRpt; ++i) {
-    const int64_t r = rbase + (int64_t)i * kThreads + tid;
+    const int64_t r = rbase + (int64_t)i * kTabThreads + tid;
     if (r < rows) partial[(int64_t)blockIdx.y * rows + r] = acc[i];
   }
 }
@@ -346,7 +347,7 @@ int ds_bit_spmv_tab(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, 
     DS_HIP(ctx, hipFuncSetAttribute((const void*)bit_spmv_tab_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL(bit_spmv_tab_kernel, dim3((unsigned)row_groups, (unsigned)groups), dim3(kThreads), lds, ctx->stream, B,
+  hipLaunchKernelGGL(bit_spmv_tab_kernel, dim3((unsigned)row_groups, (unsigned)groups), dim3(kTabThreads), lds, ctx->stream, B,
                      rows, cols, stride, row_first, row_step, x, ws, cpg, n_chunks);
   hipLaunchKernelGGL(tab_reduce_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, ctx->stream, ws, rows,
                      (int)groups, addend, out);

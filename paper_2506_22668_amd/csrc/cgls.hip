@@ -87,11 +87,20 @@ __global__ __launch_bounds__(kThreads) void make_v_kernel(Vecs a) {
   block_reduce2(acc, 0.0, &a.part[blockIdx.x], &dummy);
 }
 
+// sum of nparts (<= kRed) partials by one wave, in a fixed order; every lane gets the result
+__device__ __forceinline__ double wave_sum_partials(const double* part, int nparts) {
+  double s = 0.0;
+  for (int i = threadIdx.x; i < nparts; i += 64) s += part[i];
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  return s;
+}
+
 __global__ void fin_delta_kernel(Vecs a, int nparts) {
-  double s = 0;
-  for (int i = 0; i < nparts; ++i) s += a.part[i];
-  a.scal[1] = s;
-  a.scal[2] = s > 0.0 ? a.scal[0] / s : 0.0;
+  const double s = wave_sum_partials(a.part, nparts);
+  if (threadIdx.x == 0) {
+    a.scal[1] = s;
+    a.scal[2] = s > 0.0 ? a.scal[0] / s : 0.0;
+  }
 }
 
 // r -= theta v, then h
@@ -120,9 +129,8 @@ __global__ __launch_bounds__(kThreads) void s_sum_kernel(Vecs a) {
 }
 
 __global__ void fin_mean_kernel(Vecs a, int nparts) {
-  double s1 = 0;
-  for (int i = 0; i < nparts; ++i) s1 += a.part[i];
-  a.scal[5] = s1 / (double)a.n;
+  const double s1 = wave_sum_partials(a.part, nparts);
+  if (threadIdx.x == 0) a.scal[5] = s1 / (double)a.n;
 }
 
 // s <- P s (subtract the mean in place) and partial |P s|^2. Two passes on purpose:
@@ -141,8 +149,8 @@ __global__ __launch_bounds__(kThreads) void s_center_kernel(Vecs a) {
 
 // gamma_new = |P s|^2 and beta; the first call sets gamma0 and beta = theta = 0
 __global__ void fin_gamma_kernel(Vecs a, int nparts, int first) {
-  double g = 0;
-  for (int i = 0; i < nparts; ++i) g += a.part[i];
+  const double g = wave_sum_partials(a.part, nparts);
+  if (threadIdx.x != 0) return;
   a.scal[6] = g;
   if (first) {
     a.scal[7] = g;
@@ -169,10 +177,11 @@ __global__ __launch_bounds__(kThreads) void update_xu_kernel(Vecs a) {
 }
 
 __global__ void fin_u_kernel(Vecs a, int nparts) {
-  double s = 0;
-  for (int i = 0; i < nparts; ++i) s += a.part[i];
-  a.scal[4] = s;
-  a.scal[0] = a.scal[6];
+  const double s = wave_sum_partials(a.part, nparts);
+  if (threadIdx.x == 0) {
+    a.scal[4] = s;
+    a.scal[0] = a.scal[6];
+  }
 }
 
 // x += theta u only (last step, u not needed any more)
@@ -336,11 +345,11 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   hipLaunchKernelGGL(make_h_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
   DS_TRY(adjoint(a.h, a.s));
   hipLaunchKernelGGL(s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
-  hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
+  hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n);
   hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
-  hipLaunchKernelGGL(fin_gamma_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n, 1);
+  hipLaunchKernelGGL(fin_gamma_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n, 1);
   hipLaunchKernelGGL(update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a);  // theta = beta = 0: u = s
-  hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
+  hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n);
   DS_HIP(ctx, hipGetLastError());
   DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, a.scal, 64, hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipStreamSynchronize(st));
@@ -352,13 +361,13 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   while (!converged && it < max_iter) {
     DS_TRY(forward(a.u, a.d));
     hipLaunchKernelGGL(make_v_kernel, dim3(red_r), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(fin_delta_kernel, dim3(1), dim3(1), 0, st, a, (int)red_r);
+    hipLaunchKernelGGL(fin_delta_kernel, dim3(1), dim3(64), 0, st, a, (int)red_r);
     hipLaunchKernelGGL(update_r_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
     DS_TRY(adjoint(a.h, a.s));
     hipLaunchKernelGGL(s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
+    hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n);
     hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(fin_gamma_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n, 0);
+    hipLaunchKernelGGL(fin_gamma_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n, 0);
     DS_HIP(ctx, hipGetLastError());
     DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, a.scal, 64, hipMemcpyDeviceToHost, st));
     DS_HIP(ctx, hipStreamSynchronize(st));
@@ -369,7 +378,7 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
     if (rel <= tol) { converged = true; break; }
     if (it >= max_iter) break;
     hipLaunchKernelGGL(update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(1), 0, st, a, (int)red_n);
+    hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n);
   }
   DS_TRY(ds_kernel_mark(ctx, 3, 1));
   // the last step's x += theta u is folded into the output (theta is 0 if no step was taken)
