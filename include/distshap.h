@@ -183,6 +183,13 @@ int ds_cgraph_free(ds_ctx* ctx, ds_cgraph* cg);
  * k = 2*floor(n_samples/2) otherwise. [host] outputs. */
 int ds_sample_plan(int64_t n, int64_t n_samples, int64_t* k_out, int32_t* enumerated_out);
 
+/* The size-stratified allocation behind ds_sample (paper, sample-distribution equation: the samples of
+ * size s are proportional to rho_s = (n-1)/(s(n-s)); complementary pairing). Pure host function, all
+ * [host]: for pair classes s = 1..H, H = floor(n/2), writes the cumulative pair boundaries b[0..H]
+ * (pair r in [1, K] has small size min{s : b[s] >= r}; all zero under enumeration) and the per-row
+ * regression weight wtab[0..H] of a row of size s or n-s. Either output may be NULL. n >= 2. */
+int ds_plan_tables(int64_t n, int64_t n_samples, int64_t* b, float* wtab);
+
 /* Sampler (paper, "Distributed Subgraph Sampling": size-stratified allocation by
  * the kernel mass of each size, complementary pairs, one mask row per coalition).
  * Row 0 is the empty and row 1 the full coalition (weight 0: they are imposed as

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "ds_create", "ds_destroy", "ds_last_error", "ds_set_graph", "ds_set_features", "ds_set_gcn",
     "ds_explain", "ds_explain_batch", "ds_extract", "ds_cgraph_get_info", "ds_cgraph_edges",
     "ds_cgraph_nodes", "ds_cgraph_first_transform", "ds_cgraph_free", "ds_sample_plan", "ds_sample",
-    "ds_sample_range", "ds_eval", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
+    "ds_plan_tables", "ds_sample_range", "ds_eval", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
 ]
 
 
@@ -87,6 +87,7 @@ def load_library():
         "ds_cgraph_free": [p, p],
         "ds_sample_plan": [i64, i64, C.POINTER(i64), C.POINTER(i32)],
         "ds_sample": [p, i64, i64, u64, u32, p, p, p, C.POINTER(i64)],
+        "ds_plan_tables": [i64, i64, p, p],
         "ds_sample_range": [p, i64, i64, u64, u32, i64, i64, p, p, p],
         "ds_eval": [p, p, p, i64, i32, p, C.POINTER(i32)],
         "ds_solve": [p, i64, i64, p, p, p, C.POINTER(Options), p, C.POINTER(Report)],
@@ -113,6 +114,19 @@ def sample_plan(n, n_samples):
     if rc != DS_OK:
         raise DistShapError(rc, "ds_sample_plan: bad arguments")
     return k.value, bool(e.value)
+
+
+def plan_tables(n, n_samples):
+    """(b int64[H+1], wtab float32[H+1]) of the sampling plan (host-only call)."""
+    import numpy as np
+    lib = load_library()
+    H = n // 2
+    b = np.zeros(H + 1, dtype=np.int64)
+    wtab = np.zeros(H + 1, dtype=np.float32)
+    rc = lib.ds_plan_tables(n, n_samples, b.ctypes.data_as(C.c_void_p), wtab.ctypes.data_as(C.c_void_p))
+    if rc != DS_OK:
+        raise DistShapError(rc, "ds_plan_tables: bad arguments")
+    return b, wtab
 
 
 def _ptr(t):

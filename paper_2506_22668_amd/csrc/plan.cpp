@@ -70,3 +70,15 @@ int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan) {
   }
   return DS_OK;
 }
+
+extern "C" int ds_plan_tables(int64_t n, int64_t n_samples, int64_t* b, float* wtab) {
+  if (n < 2 || n > 0x7fffffffLL || n_samples < 0) return DS_EINVAL;
+  ds_plan plan;
+  int rc = ds_make_plan(nullptr, n, n_samples, &plan);
+  if (rc != DS_OK) return rc;
+  for (int64_t s = 0; s <= plan.H; ++s) {
+    if (b) b[s] = plan.b[s];
+    if (wtab) wtab[s] = plan.wtab[s];
+  }
+  return DS_OK;
+}

@@ -48,3 +48,20 @@ def test_product_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".cpp", ".h")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src.replace("no oracle", ""), f
+
+
+def test_host_plan_tables_equal_the_oracle_bit_for_bit():
+    import numpy as np
+    from oracle import sampling
+    from paper_2506_22668_amd import binding
+    for n, ns in [(2, 4), (12, 4096), (24, 1 << 24), (25, 1000), (30, 25000), (1010, 20000), (4097, 131),
+                  (99981, 200000), (1000175, 400000)]:
+        b, wtab = binding.plan_tables(n, ns)
+        plan = sampling.allocation(n, ns)
+        assert np.array_equal(wtab.view(np.uint32), plan["wtab"].view(np.uint32)), (n, ns)
+        if not plan["enumerate"]:
+            assert np.array_equal(b, plan["b"]), (n, ns)
+    with pytest.raises(binding.DistShapError):
+        binding.plan_tables(1, 10)
+    with pytest.raises(binding.DistShapError):
+        binding.plan_tables(100, 3)
