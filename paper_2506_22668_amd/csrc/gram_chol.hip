@@ -292,6 +292,27 @@ __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t 
     }
 }
 
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
+// acc (+)= A[64 x 64] * B[64 x 64]^T for 64x64 tiles held in LDS with row pitch NB+1, on the fp64
+// matrix cores. Each of the four waves owns a 32x32 quadrant = 2x2 tiles of v_mfma_f64_16x16x4f64:
+// lane l supplies A[i = l%16][k = l/16] and B^T[k = l/16][j = l%16] = B[j][k]; its four results are
+// D[4*r + l/16][l%16], r = 0..3.
+__device__ __forceinline__ void tile_nt_mfma(const double (*A)[NB + 1], const double (*B)[NB + 1], double4_t (&acc)[2][2]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
+  const int l16 = lane & 15, lk = lane >> 4;
+#pragma unroll 4
+  for (int k0 = 0; k0 < NB; k0 += 4) {
+    const double a0 = A[wi + l16][k0 + lk], a1 = A[wi + 16 + l16][k0 + lk];
+    const double b0 = B[wj + l16][k0 + lk], b1 = B[wj + 16 + l16][k0 + lk];
+    acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+    acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+    acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+  }
+}
+
 // rows below the diagonal block: X = A21 L11^-T = A21 Linv^T, a 64x64 product per workgroup
 __global__ __launch_bounds__(kThreads) void chol_panel_kernel(double* M, int64_t ld, int64_t rows_total, int64_t j0,
                                                               int nb, const double* linv) {
@@ -304,28 +325,26 @@ __global__ __launch_bounds__(kThreads) void chol_panel_kernel(double* M, int64_t
     Ls[r][c] = linv[idx];
   }
   __syncthreads();
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-  double acc[4][4];
-  for (int i = 0; i < 4; ++i)
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
-  for (int m = 0; m < NB; ++m) {
-    double a[4], b[4];
+  double4_t acc[2][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      a[i] = As[ty + 16 * i][m];
-      b[i] = Ls[tx + 16 * i][m];
-    }
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 2; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
+  tile_nt_mfma(As, Ls, acc);
+  {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int64_t r = i0 + wi + 16 * i + 4 * r4 + (lane >> 4);
+          const int c = wj + 16 * j + (lane & 15);
+          if (r < rows_total && c < nb) M[r * ld + j0 + c] = acc[i][j][r4];
+        }
   }
-  for (int i = 0; i < 4; ++i)
-    for (int j = 0; j < 4; ++j) {
-      const int64_t r = i0 + ty + 16 * i;
-      const int c = tx + 16 * j;
-      if (r < rows_total && c < nb) M[r * ld + j0 + c] = acc[i][j];
-    }
 }
 
 // trailing update A22 -= L21 L21^T on the lower tiles (rows up to rows_total, columns below n)
@@ -343,27 +362,26 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_
     Lj[r][c] = (c0 + r < n && c < nb) ? M[(c0 + r) * ld + j0 + c] : 0.0;
   }
   __syncthreads();
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-  double acc[4][4];
-  for (int i = 0; i < 4; ++i)
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
-  for (int m = 0; m < NB; ++m) {
-    double a[4], b[4];
+  double4_t acc[2][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      a[i] = Li[ty + 16 * i][m];
-      b[i] = Lj[tx + 16 * i][m];
-    }
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 2; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
+  tile_nt_mfma(Li, Lj, acc);
+  {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int64_t r = i0 + wi + 16 * i + 4 * r4 + (lane >> 4);
+          const int64_t c = c0 + wj + 16 * j + (lane & 15);
+          if (r < rows_total && c < n && c <= r) M[r * ld + c] -= acc[i][j][r4];
+        }
   }
-  for (int i = 0; i < 4; ++i)
-    for (int j = 0; j < 4; ++j) {
-      const int64_t r = i0 + ty + 16 * i, c = c0 + tx + 16 * j;
-      if (r < rows_total && c < n && c <= r) M[r * ld + c] -= acc[i][j];
-    }
 }
 
 // L^T psi = y (y = row n of M after the factorisation), block by block from the end, using
