@@ -21,9 +21,35 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 # plain integer/fp32 VALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 FP64_PEAK_TFLOPS = 78.6
+FP32_PEAK_TFLOPS = 157.3
 
 
-def cpu_baseline(w, budget_s=15.0):
+def inference_flops_per_coalition(ctx, cg, dims):
+    """Algorithmic flops of one masked GCN evaluation of the target: aggregation over the entries
+    that can reach the target (half of them active on average over a complementary pair, one
+    multiply-add per feature) plus the per-coalition dense transforms of layers >= 2."""
+    import numpy as np
+    info = ctx.cgraph_info(cg)
+    L = len(dims) - 1
+    gid, hop = ctx.cgraph_nodes(cg)
+    es, ed = ctx.cgraph_edges(cg)
+    gid, hop = gid.cpu().numpy(), hop.cpu().numpy()
+    hop_of = dict(zip(gid.tolist(), hop.tolist()))
+    hs = np.array([hop_of[int(x)] for x in es.cpu().numpy()])
+    hd = np.array([hop_of[int(x)] for x in ed.cpu().numpy()])
+    flops = 0.0
+    for l in range(1, L + 1):
+        radius = min(L - l, info.hops)
+        entries = int((hs <= radius).sum() + (hd <= radius).sum())     # directed entries into rows of that ball
+        width = dims[1] if l == 1 else dims[l - 1]
+        flops += 0.5 * entries * width * 2
+        if l >= 2:
+            flops += 2.0 * info.ball[radius] * dims[l - 1] * dims[l]
+    return flops
+
+
+
+def cpu_baseline(w, budget_s=20.0):
     """The oracle's masked inference, as it stands, on a bounded prefix of the same
     coalitions (rows of the same mask matrix), timed on this machine's host cores."""
     import numpy as np
@@ -35,6 +61,7 @@ def cpu_baseline(w, budget_s=15.0):
     probe = 64
     Z, wt, sz = sampling.sample(n, w.n_samples, w.seed, target & 0xFFFFFFFF, pair_range=(0, probe // 2))
     bits = sampling.unpack_rows(Z, n)
+    f.batch(bits[:8])                       # first calls pay one-off costs
     t0, c0 = time.perf_counter(), time.process_time()
     f.batch(bits)
     per = (time.perf_counter() - t0) / probe
@@ -98,6 +125,7 @@ def main():
     cg = ctx.extract(targets[0], opts)
     info = ctx.cgraph_info(cg)
     capacity = max(ctx.cgraph_info(c).num_players for c in [cg])
+    eval_flops = inference_flops_per_coalition(ctx, cg, list(w.dims))
     ctx.cgraph_free(cg)
     if len(targets) > 1:
         caps = []
@@ -132,9 +160,12 @@ def main():
     KW = (rows + 63) // 64
     # per-kernel durations (HIP events on the library's stream, recorded inside the timed region)
     kernels = {
-        "masked_gcn_eval": {"ms": mean("ms_k_eval"), "bound": "hbm",
-                            # compulsory HBM bytes per coalition: its mask row in, one float out
-                            "alg": rows * (W64 * 8 + 4) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"},
+        # small graphs (one coalition per lane, everything but the mask on chip): arithmetic-bound;
+        # large ones stream the mask matrix: compulsory HBM bytes per coalition = its mask row in, one float out
+        "masked_gcn_eval": ({"ms": mean("ms_k_eval"), "bound": "alu", "alg": rows * eval_flops / 1e12,
+                             "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s"} if n <= 2048 else
+                            {"ms": mean("ms_k_eval"), "bound": "hbm", "alg": rows * (W64 * 8 + 4) / 1e9,
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s"}),
         "gram_popcount": {"ms": mean("ms_k_gram"), "bound": "alu",
                           # lower triangle of n^2 column pairs x KW 64-row words x (AND, popcount, weighted add)
                           "alg": 3.0 * (n * (n + 1) / 2) * KW / 1e12, "peak": ALU_PEAK_TOPS, "unit": "Top/s"},

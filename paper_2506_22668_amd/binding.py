@@ -65,6 +65,9 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own HIP runtime: it has to be the one already in the process when this
+    # library (linked against libamdhip64) is loaded, or two runtimes end up side by side
+    import torch  # noqa: F401
     path = library_path()
     if not os.path.exists(path):
         raise FileNotFoundError(f"{path} is missing: run `python -m paper_2506_22668_amd.build` first")

@@ -100,6 +100,9 @@ int ds_create(ds_ctx** out, int device, void* stream) {
   ctx->h_stage_bytes = 0;
   ctx->stage_busy = false;
   if (hipEventCreate(&ctx->stage_ev) != hipSuccess) { delete ctx; return DS_EDEVICE; }
+  if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->join_ev, hipEventDisableTiming) != hipSuccess) { delete ctx; return DS_EDEVICE; }
   if (hipMemset(ctx->d_mail, 0, 64 * sizeof(int64_t)) != hipSuccess) { delete ctx; return DS_EDEVICE; }
   *out = ctx;
   return DS_OK;
@@ -118,6 +121,10 @@ int ds_destroy(ds_ctx* ctx) {
   if (ctx->cg_spare) hipFree(ctx->cg_spare);
   if (ctx->h_stage) hipHostFree(ctx->h_stage);
   hipEventDestroy(ctx->stage_ev);
+  hipStreamSynchronize(ctx->side);
+  hipStreamDestroy(ctx->side);
+  hipEventDestroy(ctx->fork_ev);
+  hipEventDestroy(ctx->join_ev);
   if (ctx->d_mail) hipFree(ctx->d_mail);
   if (ctx->h_mail) hipHostFree(ctx->h_mail);
   for (int i = 0; i < 6; ++i) hipEventDestroy(ctx->ev[i]);
@@ -395,7 +402,7 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   DS_TRY(ds_extract(ctx, target, &o, &cg));
   struct Guard {
     ds_ctx* c; ds_cgraph* g;
-    ~Guard() { ds_cgraph_free(c, g); ds_arena_reset(c); }
+    ~Guard() { (void)hipStreamSynchronize(c->side); ds_cgraph_free(c, g); ds_arena_reset(c); }
   } guard{ctx, cg};
   const int64_t n = cg->info.num_players;
   rep.num_players = n;
@@ -424,7 +431,7 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   rep.num_rows = k;
   rep.enumerated = n >= 2 ? plan.enumerate : 1;
   // workspace: Z, w, sz, y live for the whole call; stage temporaries follow them
-  size_t persistent = ds_align((size_t)k * W * 8) + ds_align(k * 4) * 3 + 1024;
+  size_t persistent = ds_align((size_t)k * W * 8) + ds_align(k * 4) * 3 + 1024 + ds_eval_arena_bytes(ctx, cg, 1);
   size_t stage = n >= 2 ? ds_sample_arena_bytes(plan) : 0;
   size_t e = ds_eval_arena_bytes(ctx, cg, k);
   if (e > stage) stage = e;
@@ -439,6 +446,17 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   int32_t* sz = (int32_t*)ds_arena_alloc(ctx, k * 4);
   float* y = (float*)ds_arena_alloc(ctx, k * 4);
   if (!Z || !w || !sz || !y) return ds_fail(ctx, DS_EINTERNAL, "explain: arena exhausted");
+  // The shared first transform and the predicted class depend only on the computational graph:
+  // they run on the side stream while the main stream draws the coalitions.
+  DS_HIP(ctx, hipEventRecord(ctx->fork_ev, st));
+  DS_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->fork_ev, 0));
+  {
+    ctx->stream = ctx->side;
+    const int prc = ds_prepare_model(ctx, cg);  // its temporaries stay allocated below `mark`
+    ctx->stream = st;
+    DS_TRY(prc);
+    DS_HIP(ctx, hipEventRecord(ctx->join_ev, ctx->side));
+  }
   const size_t mark = ctx->arena_used;
 
   if (n == 1) {
@@ -450,6 +468,7 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   }
   ctx->arena_used = mark;
   DS_HIP(ctx, hipEventRecord(ctx->ev[2], st));
+  DS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_ev, 0));
 
   DS_TRY(ds_eval_impl(ctx, cg, Z, k, o.score, y, o.batch_rows));
   ctx->arena_used = mark;

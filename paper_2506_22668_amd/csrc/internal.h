@@ -70,6 +70,9 @@ struct ds_ctx {
   size_t h_stage_bytes;
   hipEvent_t stage_ev;
   bool stage_busy;
+  // a second stream (default priority) for work that does not depend on what the main stream is doing
+  hipStream_t side;
+  hipEvent_t fork_ev, join_ev;
 };
 
 int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...);
