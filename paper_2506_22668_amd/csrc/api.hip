@@ -102,7 +102,9 @@ int ds_create(ds_ctx** out, int device, void* stream) {
   if (hipEventCreate(&ctx->stage_ev) != hipSuccess) { delete ctx; return DS_EDEVICE; }
   if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
       hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->join_ev, hipEventDisableTiming) != hipSuccess) { delete ctx; return DS_EDEVICE; }
+      hipEventCreateWithFlags(&ctx->join_ev, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->fork2_ev, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->join2_ev, hipEventDisableTiming) != hipSuccess) { delete ctx; return DS_EDEVICE; }
   if (hipMemset(ctx->d_mail, 0, 64 * sizeof(int64_t)) != hipSuccess) { delete ctx; return DS_EDEVICE; }
   *out = ctx;
   return DS_OK;
@@ -125,6 +127,8 @@ int ds_destroy(ds_ctx* ctx) {
   hipStreamDestroy(ctx->side);
   hipEventDestroy(ctx->fork_ev);
   hipEventDestroy(ctx->join_ev);
+  hipEventDestroy(ctx->fork2_ev);
+  hipEventDestroy(ctx->join2_ev);
   if (ctx->d_mail) hipFree(ctx->d_mail);
   if (ctx->h_mail) hipHostFree(ctx->h_mail);
   for (int i = 0; i < 6; ++i) hipEventDestroy(ctx->ev[i]);
@@ -438,6 +442,8 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   if (n >= 2) {
     size_t s = solve_arena_bytes(n, k, o.solver);
     if (s > stage) stage = s;
+    // the direct solver's buffers are live during the inference, and a fall-back CGLS comes on top of them
+    if (o.solver == DS_SOLVER_GRAM_CHOL || (o.solver == DS_SOLVER_AUTO && n <= 16384)) persistent += ds_gram_arena_bytes(n, k);
   }
   ds_arena_reset(ctx);
   DS_TRY(ds_arena_reserve(ctx, persistent + stage));
@@ -468,15 +474,42 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   }
   ctx->arena_used = mark;
   DS_HIP(ctx, hipEventRecord(ctx->ev[2], st));
-  DS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_ev, 0));
 
+  // The Gram matrix and the system matrix of the direct solver need the masks and weights but not
+  // the model outputs: they are built on the side stream while the main stream runs the inference.
+  const bool direct = n >= 2 && (o.solver == DS_SOLVER_GRAM_CHOL || (o.solver == DS_SOLVER_AUTO && n <= 16384));
+  ds_gram_state gs;
+  if (direct) {
+    DS_HIP(ctx, hipEventRecord(ctx->fork2_ev, st));
+    DS_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->fork2_ev, 0));
+    ctx->stream = ctx->side;
+    const int grc = ds_gram_begin(ctx, n, k, Z, w, 1, &gs);  // its buffers stay allocated below `mark2`
+    ctx->stream = st;
+    DS_TRY(grc);
+    DS_HIP(ctx, hipEventRecord(ctx->join2_ev, ctx->side));
+  }
+  const size_t mark2 = ctx->arena_used;
+
+  DS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_ev, 0));
   DS_TRY(ds_eval_impl(ctx, cg, Z, k, o.score, y, o.batch_rows));
-  ctx->arena_used = mark;
+  ctx->arena_used = mark2;
   DS_HIP(ctx, hipEventRecord(ctx->ev[3], st));
 
   int rc = DS_OK;
   if (n == 1) {
     hipLaunchKernelGGL(single_player_kernel, dim3(1), dim3(1), 0, st, y, phi);
+  } else if (direct) {
+    DS_HIP(ctx, hipStreamWaitEvent(st, ctx->join2_ev, 0));
+    rc = ds_gram_finish(ctx, &gs, Z, w, y, phi);
+    rep.solver_used = DS_SOLVER_GRAM_CHOL;
+    if (rc == DS_ESINGULAR && o.solver == DS_SOLVER_AUTO) {  // rank-deficient: the minimum-norm solve instead
+      int iters = 0;
+      double rel = 0.0;
+      rc = ds_solve_cgls_impl(ctx, n, k, Z, w, y, 1, o.tol, o.max_iter, phi, &iters, &rel);
+      rep.solver_used = DS_SOLVER_CGLS;
+      rep.cgls_iterations = iters;
+      rep.cgls_rel_residual = rel;
+    }
   } else {
     rc = solve_dispatch(ctx, n, k, Z, w, y, o, 1, phi, &rep);
   }

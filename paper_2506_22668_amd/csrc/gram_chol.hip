@@ -24,16 +24,18 @@ constexpr int kChunk = 32;  // 64-row words per LDS chunk
 // Paired rows (2r, 2r+1 complementary, one weight w): z z^T + zc zc^T = 2 z z^T - z 1^T - 1 z^T + 11^T and
 // t z + tc zc = (t - tc) z + tc 1; the terms with 1 vanish under the projection P, so only the small
 // member is used, with weight 2w and coefficient w (t_2r - t_2r+1). Otherwise every row is used.
-__global__ void used_rows_kernel(const float* wc, const double* t, int64_t R, int paired, float* gw, double* gc) {
+__global__ void used_row_weights_kernel(const float* w, int64_t R, int paired, float* gw) {
   const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= R) return;
-  if (paired) {
-    gw[r] = 2.0f * wc[2 * r];
-    gc[r] = (double)wc[2 * r] * (t[2 * r] - t[2 * r + 1]);
-  } else {
-    gw[r] = wc[r];
-    gc[r] = (double)wc[r] * t[r];
-  }
+  const int64_t i = paired ? 2 * r : r;
+  const float wi = i < 2 ? 0.f : w[i];  // the two constraint rows carry no weight
+  gw[r] = paired ? 2.0f * wi : wi;
+}
+
+__global__ void used_row_rhs_kernel(const float* wc, const double* t, int64_t R, int paired, double* gc) {
+  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= R) return;
+  gc[r] = paired ? (double)wc[2 * r] * (t[2 * r] - t[2 * r + 1]) : (double)wc[r] * t[r];
 }
 
 // per word of 64 rows: the common weight, or non-uniform
@@ -152,49 +154,58 @@ __global__ __launch_bounds__(kThreads) void sum_slices_row_mean_kernel(double* G
   }
 }
 
-// single block: stats[0] = mu (grand mean), stats[1] = trace(G), stats[2] = mean(c)
-__global__ __launch_bounds__(kThreads) void stats_kernel(const double* G, const double* m, const double* c, int64_t n,
-                                                         double* stats) {
-  __shared__ double sh[3][kThreads];
-  double a = 0, b = 0, d = 0;
+// single block: stats[0] = mu (grand mean of G), stats[1] = trace(G)
+__global__ __launch_bounds__(kThreads) void stats_kernel(const double* G, const double* m, int64_t n, double* stats) {
+  __shared__ double sh[2][kThreads];
+  double a = 0, b = 0;
   for (int64_t i = threadIdx.x; i < n; i += kThreads) {
     a += m[i];
     b += G[i * n + i];
-    d += c[i];
   }
   sh[0][threadIdx.x] = a;
   sh[1][threadIdx.x] = b;
-  sh[2][threadIdx.x] = d;
   __syncthreads();
   if (threadIdx.x == 0) {
-    double x = 0, yv = 0, z = 0;
+    double x = 0, yv = 0;
     for (int i = 0; i < kThreads; ++i) {
       x += sh[0][i];
       yv += sh[1][i];
-      z += sh[2][i];
     }
     stats[0] = x / (double)n;
     stats[1] = yv;
-    stats[2] = z / (double)n;
   }
 }
 
-// The system in one (n+1) x ld array M: rows 0..n-1 = A = P G P + gamma 11^T / n (lower triangle is
-// what the factorisation reads), row n = the right-hand side c - mean(c). Factorising with row n carried
-// along as an ordinary sub-diagonal row leaves L^-1 rhs in it (the forward solve comes for free).
+// The system lives in one (n+1) x ld array M: rows 0..n-1 = A = P G P + gamma 11^T / n (lower triangle
+// is what the factorisation reads), row n = the right-hand side c - mean(c). Factorising with row n
+// carried along as an ordinary sub-diagonal row leaves L^-1 rhs in it (the forward solve comes for free).
 // gamma = trace(PGP)/(n-1) keeps the added direction at the scale of the other eigenvalues.
-__global__ void build_system_kernel(const double* G, const double* m, const double* c, const double* stats, int64_t n,
-                                    int64_t ld, double* M) {
+__global__ void build_matrix_kernel(const double* G, const double* m, const double* stats, int64_t n, int64_t ld, double* M) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n * n) return;
   const double mu = stats[0];
   const double tr = stats[1] - (double)n * mu;
   double gamma = tr / (double)(n > 1 ? n - 1 : 1);
   if (!(gamma > 0.0)) gamma = 1.0;
-  if (idx < n * n) {
-    const int64_t a = idx / n, b = idx - a * n;
-    M[a * ld + b] = G[idx] - m[a] - m[b] + mu + gamma / (double)n;
+  const int64_t a = idx / n, b = idx - a * n;
+  M[a * ld + b] = G[idx] - m[a] - m[b] + mu + gamma / (double)n;
+}
+
+// row n of M = c - mean(c); single block
+__global__ __launch_bounds__(kThreads) void build_rhs_kernel(const double* c, int64_t n, int64_t ld, double* M) {
+  __shared__ double sh[kThreads];
+  double a = 0;
+  for (int64_t i = threadIdx.x; i < n; i += kThreads) a += c[i];
+  sh[threadIdx.x] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double x = 0;
+    for (int i = 0; i < kThreads; ++i) x += sh[i];
+    sh[0] = x / (double)n;
   }
-  if (idx < n) M[n * ld + idx] = c[idx] - stats[2];
+  __syncthreads();
+  const double mean = sh[0];
+  for (int64_t i = threadIdx.x; i < n; i += kThreads) M[n * ld + i] = c[i] - mean;
 }
 
 // ---------------- blocked Cholesky (lower, in place, fp64) ----------------
@@ -465,54 +476,70 @@ size_t ds_gram_arena_bytes(int64_t n, int64_t k) {
          ds_align(k * 8) + ds_align(d.RW * 4) * 2 + 4 * ds_align(n * 8) + 8192;
 }
 
-int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y, int paired,
-                       float* phi) {
+// Part 1: everything that does not need the model outputs y (Gram matrix, projection, system matrix).
+// It may run on another stream than part 2, concurrently with the masked inference.
+int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, int paired, ds_gram_state* gs) {
   hipStream_t st = ctx->stream;
   if (paired && (k & 1)) return ds_fail(ctx, DS_EINVAL, "paired rows need an even row count");
   const int64_t W = (n + 63) / 64;
   const GramDims d = gram_dims(n, k, paired, ctx->num_cus);
   const int64_t R = d.R, RW = d.RW, ld = d.ld;
-  uint64_t* Zt = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * RW * 8);
+  gs->n = n; gs->k = k; gs->R = R; gs->RW = RW; gs->ld = ld; gs->nblk = d.nblk; gs->paired = paired;
+  gs->Zt = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * RW * 8);
   double* Gp = (double*)ds_arena_alloc(ctx, (size_t)d.slices * n * n * 8);
-  double* M = (double*)ds_arena_alloc(ctx, (size_t)(n + 1) * ld * 8);
-  double* linv = (double*)ds_arena_alloc(ctx, (size_t)d.nblk * NB * NB * 8);
-  int32_t* sz = (int32_t*)ds_arena_alloc(ctx, k * 4);
-  float* wc = (float*)ds_arena_alloc(ctx, k * 4);
-  double* t = (double*)ds_arena_alloc(ctx, k * 8);
-  double* sqw = (double*)ds_arena_alloc(ctx, k * 8);
+  gs->M = (double*)ds_arena_alloc(ctx, (size_t)(n + 1) * ld * 8);
+  gs->linv = (double*)ds_arena_alloc(ctx, (size_t)d.nblk * NB * NB * 8);
   float* gw = (float*)ds_arena_alloc(ctx, R * 4);
-  double* gc = (double*)ds_arena_alloc(ctx, R * 8);
   float* wu = (float*)ds_arena_alloc(ctx, RW * 4);
   int32_t* uni = (int32_t*)ds_arena_alloc(ctx, RW * 4);
-  double* c = (double*)ds_arena_alloc(ctx, n * 8);
   double* m = (double*)ds_arena_alloc(ctx, n * 8);
-  double* yv = (double*)ds_arena_alloc(ctx, n * 8);
   double* stats = (double*)ds_arena_alloc(ctx, 64);
-  int* flag = (int*)ds_arena_alloc(ctx, 64);
-  if (!Zt || !Gp || !M || !linv || !sz || !wc || !t || !sqw || !gw || !gc || !wu || !uni || !c || !m || !yv || !stats || !flag)
+  // buffers of part 2, reserved here so that both parts draw from one contiguous region
+  gs->sz = (int32_t*)ds_arena_alloc(ctx, k * 4);
+  gs->wc = (float*)ds_arena_alloc(ctx, k * 4);
+  gs->t = (double*)ds_arena_alloc(ctx, k * 8);
+  gs->sqw = (double*)ds_arena_alloc(ctx, k * 8);
+  gs->gc = (double*)ds_arena_alloc(ctx, R * 8);
+  gs->c = (double*)ds_arena_alloc(ctx, n * 8);
+  gs->yv = (double*)ds_arena_alloc(ctx, n * 8);
+  gs->flag = (int*)ds_arena_alloc(ctx, 64);
+  if (!gs->Zt || !Gp || !gs->M || !gs->linv || !gw || !wu || !uni || !m || !stats || !gs->sz || !gs->wc || !gs->t ||
+      !gs->sqw || !gs->gc || !gs->c || !gs->yv || !gs->flag)
     return ds_fail(ctx, DS_EINTERNAL, "gram: arena exhausted");
-  DS_HIP(ctx, hipMemsetAsync(flag, 0, sizeof(int), st));
-  DS_TRY(ds_row_prep(ctx, Z, k, n, w, y, sz, t, sqw, wc));
-  hipLaunchKernelGGL(used_rows_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, wc, t, R, paired, gw, gc);
-  DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, Zt));
+  hipLaunchKernelGGL(used_row_weights_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, w, R, paired, gw);
+  DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, gs->Zt));
   hipLaunchKernelGGL(word_weights_kernel, dim3(nblocks(RW, 256)), dim3(256), 0, st, gw, R, RW, wu, uni);
   const unsigned tiles = nblocks(n, kTile);
   DS_TRY(ds_kernel_mark(ctx, 1, 0));
-  hipLaunchKernelGGL(gram_kernel, dim3(tiles, tiles, d.slices), dim3(kThreads), 0, st, Zt, n, R, RW, gw, wu, uni, Gp,
+  hipLaunchKernelGGL(gram_kernel, dim3(tiles, tiles, d.slices), dim3(kThreads), 0, st, gs->Zt, n, R, RW, gw, wu, uni, Gp,
                      d.words_per_slice);
   DS_TRY(ds_kernel_mark(ctx, 1, 1));
-  DS_TRY(ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, gc, c));  // c_j = sum over the rows containing j of gc
   const unsigned wblocks = (unsigned)(((n * 64 + kThreads - 1) / kThreads) < (int64_t)ctx->num_cus * 8 ? ((n * 64 + kThreads - 1) / kThreads) : (int64_t)ctx->num_cus * 8);
   hipLaunchKernelGGL(sum_slices_row_mean_kernel, dim3(wblocks), dim3(kThreads), 0, st, Gp, n, d.slices, m);
-  hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(kThreads), 0, st, Gp, m, c, n, stats);
-  hipLaunchKernelGGL(build_system_kernel, dim3(nblocks(n * n, 256)), dim3(256), 0, st, Gp, m, c, stats, n, ld, M);
+  hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(kThreads), 0, st, Gp, m, n, stats);
+  hipLaunchKernelGGL(build_matrix_kernel, dim3(nblocks(n * n, 256)), dim3(256), 0, st, Gp, m, stats, n, ld, gs->M);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
+
+// Part 2: right-hand side from y, factorisation (the right-hand side rides along as row n), back substitution.
+int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, const float* w, const float* y, float* phi) {
+  hipStream_t st = ctx->stream;
+  const int64_t n = gs->n, k = gs->k, R = gs->R, RW = gs->RW, ld = gs->ld;
+  double* M = gs->M;
+  double* linv = gs->linv;
+  DS_HIP(ctx, hipMemsetAsync(gs->flag, 0, sizeof(int), st));
+  DS_TRY(ds_row_prep(ctx, Z, k, n, w, y, gs->sz, gs->t, gs->sqw, gs->wc));
+  hipLaunchKernelGGL(used_row_rhs_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, gs->wc, gs->t, R, gs->paired, gs->gc);
+  DS_TRY(ds_bit_spmv(ctx, gs->Zt, n, R, RW, 0, 1, gs->gc, gs->c));  // c_j = sum over the rows containing j of gc
+  hipLaunchKernelGGL(build_rhs_kernel, dim3(1), dim3(kThreads), 0, st, gs->c, n, ld, M);
   DS_HIP(ctx, hipGetLastError());
   DS_TRY(ds_kernel_mark(ctx, 2, 0));
   const int64_t rows_total = n + 1;  // row n carries the right-hand side
   for (int64_t j0 = 0; j0 < n; j0 += NB) {
     const int nb = (int)(n - j0 < NB ? n - j0 : NB);
     double* li = linv + (size_t)(j0 / NB) * NB * NB;
-    hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, j0, nb, li, flag);
+    hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, j0, nb, li, gs->flag);
     const int64_t rest = rows_total - j0 - nb;
     hipLaunchKernelGGL(chol_panel_kernel, dim3(nblocks(rest, kTile)), dim3(kThreads), 0, st, M, ld, rows_total, j0, nb, li);
     if (n - j0 - nb > 0) {
@@ -521,11 +548,18 @@ int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
     }
   }
   DS_TRY(ds_kernel_mark(ctx, 2, 1));
-  hipLaunchKernelGGL(chol_back_solve_kernel, dim3(1), dim3(kSolveThreads), 0, st, M, ld, n, linv, yv, y, phi);
+  hipLaunchKernelGGL(chol_back_solve_kernel, dim3(1), dim3(kSolveThreads), 0, st, M, ld, n, linv, gs->yv, y, phi);
   DS_HIP(ctx, hipGetLastError());
-  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, flag, sizeof(int), hipMemcpyDeviceToHost, st));
+  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, gs->flag, sizeof(int), hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipStreamSynchronize(st));
   if (*(int*)ctx->h_mail != 0)
     return ds_fail(ctx, DS_ESINGULAR, "Cholesky met a non-positive pivot: the sampled rows do not determine all %lld players", (long long)n);
   return DS_OK;
+}
+
+int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y, int paired,
+                       float* phi) {
+  ds_gram_state gs;
+  DS_TRY(ds_gram_begin(ctx, n, k, Z, w, paired, &gs));
+  return ds_gram_finish(ctx, &gs, Z, w, y, phi);
 }

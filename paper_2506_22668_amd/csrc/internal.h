@@ -72,7 +72,7 @@ struct ds_ctx {
   bool stage_busy;
   // a second stream (default priority) for work that does not depend on what the main stream is doing
   hipStream_t side;
-  hipEvent_t fork_ev, join_ev;
+  hipEvent_t fork_ev, join_ev, fork2_ev, join2_ev;
 };
 
 int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...);
@@ -128,6 +128,18 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
 int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg);  // shared first transform + predicted class
 size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
 
+// the direct solver in two parts: the first needs only the masks and weights
+struct ds_gram_state {
+  int64_t n, k, R, RW, ld, nblk;
+  int paired;
+  uint64_t* Zt;
+  double *M, *linv, *t, *sqw, *gc, *c, *yv;
+  int32_t* sz;
+  float* wc;
+  int* flag;
+};
+int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, int paired, ds_gram_state* gs);
+int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, const float* w, const float* y, float* phi);
 int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
                        int paired, float* phi);
 size_t ds_gram_arena_bytes(int64_t n, int64_t k);
