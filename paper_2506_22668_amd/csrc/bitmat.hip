@@ -135,6 +135,40 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_kernel(const uint64_t* B, i
 }
 
 
+// Few rows (the tiled kernel above would leave most of the GPU idle): one wave per row, lanes over words.
+__global__ __launch_bounds__(kThreads) void bit_spmv_rows_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
+                                                                 int64_t row_first, int64_t row_step, const double* x,
+                                                                 double* out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+  const int64_t Wc = (cols + 63) / 64;
+  const uint64_t tail = (cols & 63) ? ((1ull << (cols & 63)) - 1ull) : ~0ull;
+  for (int64_t i = wave; i < rows; i += nwaves) {
+    const uint64_t* row = B + (row_first + i * row_step) * stride;
+    double acc = 0.0;
+    for (int64_t wd = lane; wd < Wc; wd += 128) {
+      uint64_t w0 = row[wd] & (wd == Wc - 1 ? tail : ~0ull);
+      uint64_t w1 = wd + 64 < Wc ? (row[wd + 64] & (wd + 64 == Wc - 1 ? tail : ~0ull)) : 0ull;
+      const double* x0 = x + wd * 64;
+      const double* x1 = x0 + 64 * 64;
+      double a0 = 0.0, a1 = 0.0;
+      while (w0 | w1) {
+        const bool l0 = w0 != 0ull, l1 = w1 != 0ull;
+        const double v0 = x0[l0 ? __ffsll((long long)w0) - 1 : 0];
+        const double v1 = l1 ? x1[__ffsll((long long)w1) - 1] : 0.0;
+        a0 += l0 ? v0 : 0.0;
+        a1 += v1;
+        w0 &= w0 - 1;
+        w1 &= w1 - 1;
+      }
+      acc += a0 + a1;
+    }
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (lane == 0) out[i] = acc;
+  }
+}
+
 // ---- dense rows: byte-table product -------------------------------------------------------
 // out[i] = sum over set bits j of row i of x[j], for rows that are dense enough that walking
 // bits one by one costs more than it should. For a chunk of 512 columns the workgroup builds,
@@ -294,6 +328,12 @@ int ds_bit_spmv(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int6
   if (rows <= 0) return DS_OK;
   const int64_t rows_per_block = kSpmvRowsPerWave * (kThreads / 64);
   const int64_t blocks = (rows + rows_per_block - 1) / rows_per_block;
+  if (blocks < (int64_t)ctx->num_cus) {
+    hipLaunchKernelGGL(bit_spmv_rows_kernel, dim3((unsigned)((rows * 64 + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                       ctx->stream, B, rows, cols, stride, row_first, row_step, x, out);
+    DS_HIP(ctx, hipGetLastError());
+    return DS_OK;
+  }
   hipLaunchKernelGGL(bit_spmv_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, B, rows, cols, stride,
                      row_first, row_step, x, out);
   DS_HIP(ctx, hipGetLastError());
