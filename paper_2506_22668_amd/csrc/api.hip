@@ -213,20 +213,21 @@ int ds_cgraph_get_info(const ds_cgraph* cg, ds_cgraph_info* info) {
 }
 
 // local ids -> global ids for the player list
-__global__ void export_edges_kernel(const int32_t* pl_src, const int32_t* pl_dst, const int64_t* node_gid, int64_t n,
+__global__ void export_edges_kernel(const int2* pl, const int64_t* node_gid, int64_t n,
                                     int64_t* es, int64_t* ed) {
   const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= n) return;
-  if (es) es[p] = node_gid[pl_src[p]];
-  if (ed) ed[p] = node_gid[pl_dst[p]];
+  const int2 e = pl[p];
+  if (es) es[p] = node_gid[e.x];
+  if (ed) ed[p] = node_gid[e.y];
 }
 
 int ds_cgraph_edges(ds_ctx* ctx, const ds_cgraph* cg, int64_t* edge_src, int64_t* edge_dst) {
   if (!ctx || !cg) return DS_EINVAL;
   const int64_t n = cg->info.num_players;
   if (n == 0 || (!edge_src && !edge_dst)) return DS_OK;
-  hipLaunchKernelGGL(export_edges_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, cg->pl_src,
-                     cg->pl_dst, cg->node_gid, n, edge_src, edge_dst);
+  hipLaunchKernelGGL(export_edges_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, cg->pl,
+                     cg->node_gid, n, edge_src, edge_dst);
   DS_HIP(ctx, hipGetLastError());
   DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
   return DS_OK;

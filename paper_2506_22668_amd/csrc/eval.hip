@@ -30,7 +30,8 @@ struct EvalArgs {
   int32_t dims[DS_MAX_LAYERS + 1];
   int32_t rows_out[DS_MAX_LAYERS + 1];  // rows produced by layer l (1..L)
   int64_t W, k;
-  const int32_t *row_ptr, *col, *eid, *pl_src, *pl_dst;
+  const int32_t *row_ptr, *col, *eid;
+  const int2* pl;  // player end points (local ids)
   const float* P;
   const float* Wl[DS_MAX_LAYERS];
   const float* bias[DS_MAX_LAYERS];
@@ -69,16 +70,21 @@ __device__ __forceinline__ float readlane_f(float v, int l) {
 // bits together and the set bits of the ballot are walked in order.
 __device__ __forceinline__ void aggregate_rows(const EvalArgs& a, const uint64_t* z, const float* rs,
                                                const float* src, int stride, int rows, int width,
-                                               float* dst, const float* bias, bool relu) {
+                                               float* dst, const float* bias, bool relu, float* part) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int t = wave; t < rows; t += kWaves) {
+  for (int t = 0; t < rows; ++t) {
     const int e0 = a.row_ptr[t], e1 = a.row_ptr[t + 1];
+    // a long row (a hub) is shared by all waves of the workgroup, 64 entries at a time each, and its
+    // partial sums meet in LDS; short rows go to one wave each
+    const bool coop = e1 - e0 > 2 * 64;
+    const int owner = t % kWaves;
+    if (!coop && owner != wave) continue;
     const float rst = rs[t];
     for (int f0 = 0; f0 < width; f0 += 256) {
       const int f = f0 + lane;
       float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
       const bool h0 = f < width, h1 = f + 64 < width, h2 = f + 128 < width, h3 = f + 192 < width;
-      for (int base = e0; base < e1; base += 64) {
+      for (int base = e0 + (coop ? wave * 64 : 0); base < e1; base += (coop ? kWaves * 64 : 64)) {
         const int e = base + lane;
         int srcn = 0;
         float coef = 0.f;
@@ -120,13 +126,35 @@ __device__ __forceinline__ void aggregate_rows(const EvalArgs& a, const uint64_t
           }
         }
       }
-      const float* sp = src + (size_t)t * stride + f;
-      float* dp = dst + (size_t)t * width + f;
-      float v;
-      if (h0) { v = rst * (acc0 + rst * sp[0]);   if (bias) v += bias[f];       dp[0]   = relu ? fmaxf(v, 0.f) : v; }
-      if (h1) { v = rst * (acc1 + rst * sp[64]);  if (bias) v += bias[f + 64];  dp[64]  = relu ? fmaxf(v, 0.f) : v; }
-      if (h2) { v = rst * (acc2 + rst * sp[128]); if (bias) v += bias[f + 128]; dp[128] = relu ? fmaxf(v, 0.f) : v; }
-      if (h3) { v = rst * (acc3 + rst * sp[192]); if (bias) v += bias[f + 192]; dp[192] = relu ? fmaxf(v, 0.f) : v; }
+      if (coop) {
+        float* mine = part + wave * 256 + lane;
+        mine[0] = acc0;
+        mine[64] = acc1;
+        mine[128] = acc2;
+        mine[192] = acc3;
+        __syncthreads();
+        if (wave == owner) {
+          acc0 = acc1 = acc2 = acc3 = 0.f;
+#pragma unroll
+          for (int w = 0; w < kWaves; ++w) {  // fixed order: the sum does not depend on timing
+            const float* o = part + w * 256 + lane;
+            acc0 += o[0];
+            acc1 += o[64];
+            acc2 += o[128];
+            acc3 += o[192];
+          }
+        }
+      }
+      if (wave == owner) {
+        const float* sp = src + (size_t)t * stride + f;
+        float* dp = dst + (size_t)t * width + f;
+        float v;
+        if (h0) { v = rst * (acc0 + rst * sp[0]);   if (bias) v += bias[f];       dp[0]   = relu ? fmaxf(v, 0.f) : v; }
+        if (h1) { v = rst * (acc1 + rst * sp[64]);  if (bias) v += bias[f + 64];  dp[64]  = relu ? fmaxf(v, 0.f) : v; }
+        if (h2) { v = rst * (acc2 + rst * sp[128]); if (bias) v += bias[f + 128]; dp[128] = relu ? fmaxf(v, 0.f) : v; }
+        if (h3) { v = rst * (acc3 + rst * sp[192]); if (bias) v += bias[f + 192]; dp[192] = relu ? fmaxf(v, 0.f) : v; }
+      }
+      if (coop) __syncthreads();
     }
   }
 }
@@ -151,12 +179,13 @@ __device__ __forceinline__ void transform_rows(const float* q, int rows, int din
 template <bool RS_LDS, bool BUF_LDS>
 __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
   extern __shared__ float smem[];
-  int* red = (int*)smem;  // 16 ints of reduction scratch
+  int* red = (int*)smem;  // 16 ints of reduction scratch, then the per-wave partial sums of shared rows
+  float* part = smem + 16;
   float* rs;
   float* bufA;
   float* bufB;
   {
-    float* lds = smem + 16;
+    float* lds = smem + 16 + kWaves * 256;
     float* g = a.gws + (size_t)blockIdx.x * a.gws_stride;
     if (RS_LDS) { rs = lds; lds += a.V; } else { rs = g; g += a.V; }
     if (BUF_LDS) { bufA = lds; bufB = lds + a.bufA_floats; } else { bufA = g; bufB = g + a.bufA_floats; }
@@ -176,15 +205,36 @@ __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
     int* deg = (int*)rs;
     for (int i = tid; i < a.V; i += kThreads) deg[i] = dense ? (a.row_ptr[i + 1] - a.row_ptr[i] + 1) : 1;
     __syncthreads();
-    for (int64_t w = tid; w < W; w += kThreads) {
-      uint64_t bits = dense ? ~z[w] : z[w];
-      if (w == W - 1) bits &= tail_mask;  // padding bits never name a player
-      while (bits) {
-        const int j = __ffsll((long long)bits) - 1;
-        bits &= bits - 1;
-        const int64_t p = w * 64 + j;
-        atomicAdd(&deg[a.pl_dst[p]], step);
-        if (!a.directed) atomicAdd(&deg[a.pl_src[p]], step);
+    // every thread walks four words at a time, so that four end-point look-ups are in flight
+    for (int64_t w0 = tid; w0 < W; w0 += 4 * kThreads) {
+      uint64_t bits[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int64_t w = w0 + (int64_t)q * kThreads;
+        uint64_t b = 0ull;
+        if (w < W) {
+          b = dense ? ~z[w] : z[w];
+          if (w == W - 1) b &= tail_mask;  // padding bits never name a player
+        }
+        bits[q] = b;
+      }
+      while (bits[0] | bits[1] | bits[2] | bits[3]) {
+        int2 e[4];
+        bool live[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          live[q] = bits[q] != 0ull;
+          const int64_t p = (w0 + (int64_t)q * kThreads) * 64 + (live[q] ? __ffsll((long long)bits[q]) - 1 : 0);
+          e[q] = live[q] ? a.pl[p] : make_int2(0, 0);
+          bits[q] &= bits[q] - 1;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (live[q]) {
+            atomicAdd(&deg[e[q].y], step);
+            if (!a.directed) atomicAdd(&deg[e[q].x], step);
+          }
+        }
       }
     }
     __syncthreads();
@@ -195,10 +245,10 @@ __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
     __syncthreads();
 
     // layer 1: aggregate the shared product P = X_c W_1
-    aggregate_rows(a, z, rs, a.P, a.dims[1], a.rows_out[1], a.dims[1], bufA, a.bias[0], a.L > 1);
+    aggregate_rows(a, z, rs, a.P, a.dims[1], a.rows_out[1], a.dims[1], bufA, a.bias[0], a.L > 1, part);
     __syncthreads();
     for (int l = 2; l <= a.L; ++l) {
-      aggregate_rows(a, z, rs, bufA, a.dims[l - 1], a.rows_out[l], a.dims[l - 1], bufB, nullptr, false);
+      aggregate_rows(a, z, rs, bufA, a.dims[l - 1], a.rows_out[l], a.dims[l - 1], bufB, nullptr, false, part);
       __syncthreads();
       transform_rows(bufB, a.rows_out[l], a.dims[l - 1], a.dims[l], a.Wl[l - 1], a.bias[l - 1], l < a.L,
                      a.bf16 != 0, bufA);
@@ -703,7 +753,7 @@ EvalLayout make_layout(const ds_ctx* ctx, const ds_cgraph* cg) {
   EvalLayout lay;
   lay.bufA = (int32_t)A;
   lay.bufB = (int32_t)B;
-  const size_t rs_b = (size_t)cg->info.num_nodes * 4, buf_b = (size_t)(A + B) * 4, fix = 64;
+  const size_t rs_b = (size_t)cg->info.num_nodes * 4, buf_b = (size_t)(A + B) * 4, fix = 64 + kWaves * 256 * 4;
   if (fix + rs_b + buf_b <= kLdsLimit) { lay.rs_lds = true; lay.buf_lds = true; }
   else if (fix + buf_b <= kLdsLimit && buf_b <= rs_b) { lay.rs_lds = false; lay.buf_lds = true; }
   else if (fix + rs_b <= kLdsLimit) { lay.rs_lds = true; lay.buf_lds = false; }
@@ -718,7 +768,7 @@ EvalLayout make_layout(const ds_ctx* ctx, const ds_cgraph* cg) {
 int grid_for(const ds_ctx* ctx, const EvalLayout& lay, int64_t k) {
   int occ = (int)(kLdsLimit / (lay.lds_bytes ? lay.lds_bytes : 1));
   if (occ < 1) occ = 1;
-  if (occ > 8) occ = 8;
+  if (occ > 2048 / kThreads) occ = 2048 / kThreads;  // resident threads per CU
   int64_t g = (int64_t)ctx->num_cus * occ;
   if (g > k) g = k;
   if (g < 1) g = 1;
@@ -758,8 +808,7 @@ void fill_args(const ds_ctx* ctx, const ds_cgraph* cg, const EvalLayout& lay, Ev
   a->row_ptr = cg->row_ptr;
   a->col = cg->col;
   a->eid = cg->eid;
-  a->pl_src = cg->pl_src;
-  a->pl_dst = cg->pl_dst;
+  a->pl = cg->pl;
   a->P = cg->P;
   for (int l = 0; l < ctx->L; ++l) {
     a->Wl[l] = ctx->W[l];

@@ -181,8 +181,7 @@ struct GraphOut {
   int32_t* row_ptr;
   int32_t* col;
   int32_t* eid;
-  int32_t* pl_src;
-  int32_t* pl_dst;
+  int2* pl;
   int64_t* node_gid;
   int32_t* hop;
 };
@@ -264,8 +263,7 @@ __global__ __launch_bounds__(kThreads) void fill_entries(const int64_t* row_ptr,
         int32_t p = -1;
         if (own) {
           p = ppos + __popcll(m_own & lt);
-          out.pl_src[p] = directed ? jl : lid;
-          out.pl_dst[p] = directed ? lid : jl;
+          out.pl[p] = directed ? make_int2(jl, lid) : make_int2(lid, jl);
         }
         out.eid[at] = p;
       }
@@ -293,7 +291,7 @@ __global__ void backfill_entries(GraphOut out, const int32_t* rank_scan, const i
       int32_t found = -1;
       while (lo < hi) {
         const int32_t mid = (lo + hi) >> 1;
-        const int64_t bg = out.node_gid[out.pl_dst[mid]];
+        const int64_t bg = out.node_gid[out.pl[mid].y];
         if (bg == g) {
           found = mid;
           break;
@@ -425,7 +423,7 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off += ds_align(bytes); return o; };
   const size_t o_rp = carve((V + 1) * 4), o_col = carve(nnz_c * 4 + 4), o_eid = carve(nnz_c * 4 + 4);
-  const size_t o_ps = carve(n * 4 + 4), o_pd = carve(n * 4 + 4), o_gid = carve(V * 8), o_hop = carve(V * 4);
+  const size_t o_pl = carve(n * 8 + 8), o_gid = carve(V * 8), o_hop = carve(V * 4);
   const size_t o_x = carve((size_t)V * d0 * 4), o_p = carve((size_t)V * (d1 > 0 ? d1 : 1) * 4);
   const size_t o_pred = carve(256);
   if (ctx->cg_spare && ctx->cg_spare_bytes >= off) {
@@ -445,8 +443,7 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
   cg->row_ptr = (int32_t*)(base + o_rp);
   cg->col = (int32_t*)(base + o_col);
   cg->eid = (int32_t*)(base + o_eid);
-  cg->pl_src = (int32_t*)(base + o_ps);
-  cg->pl_dst = (int32_t*)(base + o_pd);
+  cg->pl = (int2*)(base + o_pl);
   cg->node_gid = (int64_t*)(base + o_gid);
   cg->hop = (int32_t*)(base + o_hop);
   cg->Xc = (float*)(base + o_x);
@@ -468,7 +465,7 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
   DS_HIP(ctx, hipMemcpyAsync(cg->row_ptr, rowptr_tmp, (V + 1) * 4, hipMemcpyDeviceToDevice, st));
   DS_HIP(ctx, hipMemcpyAsync(cg->node_gid, node_gid_tmp, V * 8, hipMemcpyDeviceToDevice, st));
   DS_HIP(ctx, hipMemcpyAsync(cg->hop, hop_tmp, V * 4, hipMemcpyDeviceToDevice, st));
-  GraphOut go{cg->row_ptr, cg->col, cg->eid, cg->pl_src, cg->pl_dst, cg->node_gid, cg->hop};
+  GraphOut go{cg->row_ptr, cg->col, cg->eid, cg->pl, cg->node_gid, cg->hop};
   hipLaunchKernelGGL(fill_entries, dim3(wave_blocks), dim3(kThreads), 0, st, ctx->row_ptr, ctx->col, dist, lid_scan, N, lid_of_rank, player_start, V, directed, go);
   if (!directed && nnz_c > 0)
     hipLaunchKernelGGL(backfill_entries, dim3(wave_blocks), dim3(kThreads), 0, st, go, rank_scan, player_start, V, mail);

@@ -22,8 +22,8 @@ struct ds_cgraph {
   int32_t* row_ptr;       // [V+1] local CSR, row t lists local in-neighbours
   int32_t* col;           // [nnz]
   int32_t* eid;           // [nnz] CSR entry -> player
-  int32_t* pl_src;        // [n] local id of a (undirected: smaller global id) / message source
-  int32_t* pl_dst;        // [n] local id of b / message destination
+  int2* pl;               // [n] player end points as local ids: x = a (undirected: the smaller global id) or the
+                          // message source, y = b or the message destination
   int64_t* node_gid;      // [V]
   int32_t* hop;           // [V]
   float* Xc;              // [V x d0] gathered feature rows
