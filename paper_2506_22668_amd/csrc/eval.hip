@@ -96,21 +96,21 @@ __device__ __forceinline__ void aggregate_rows(const EvalArgs& a, const uint64_t
           coef = rs[srcn];
         }
         unsigned long long mask = __ballot(bit);
-        // four active entries per step: their row loads are independent and issue back to back
+        // eight active entries per step: their row loads are independent and issue back to back
         while (mask) {
-          int idx[4];
-          float cf[4];
+          int idx[8];
+          float cf[8];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
+          for (int u = 0; u < 8; ++u) {
             const bool live = mask != 0ull;
             const int i = live ? __ffsll((long long)mask) - 1 : 0;
             if (live) mask &= mask - 1;
             idx[u] = readlane_i(srcn, i);
             cf[u] = live ? readlane_f(coef, i) : 0.f;
           }
-          float v0[4], v1[4], v2[4], v3[4];
+          float v0[8], v1[8], v2[8], v3[8];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
+          for (int u = 0; u < 8; ++u) {
             const float* sp = src + (size_t)idx[u] * stride + f;
             v0[u] = h0 ? sp[0] : 0.f;
             v1[u] = h1 ? sp[64] : 0.f;
@@ -118,7 +118,7 @@ __device__ __forceinline__ void aggregate_rows(const EvalArgs& a, const uint64_t
             v3[u] = h3 ? sp[192] : 0.f;
           }
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
+          for (int u = 0; u < 8; ++u) {
             acc0 += cf[u] * v0[u];
             acc1 += cf[u] * v1[u];
             acc2 += cf[u] * v2[u];
@@ -198,7 +198,16 @@ __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
     const uint64_t* z = a.Z + row * W;
     // coalition size decides which polarity is cheaper to walk
     int c = 0;
-    for (int64_t w = tid; w < W; w += kThreads) c += __popcll(z[w] & (w == W - 1 ? tail_mask : ~0ull));
+    for (int64_t w0 = tid; w0 < W; w0 += 8 * kThreads) {  // eight independent loads per thread and step
+      uint64_t v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int64_t w = w0 + (int64_t)q * kThreads;
+        v[q] = w < W ? (z[w] & (w == W - 1 ? tail_mask : ~0ull)) : 0ull;
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) c += __popcll(v[q]);
+    }
     const int total = block_sum_int(c, red);
     const bool dense = 2 * (int64_t)total > a.n;
     const int step = dense ? -1 : 1;
