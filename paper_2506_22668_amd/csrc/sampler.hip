@@ -8,9 +8,15 @@
 // A row of size s is the set of the s columns with the smallest (key, column),
 // where key(r, j) is word j%4 of Philox4x32-10 (Salmon et al., SC'11) under key =
 // seed and counter = (j/4, r_lo, r_hi, tag). One workgroup builds one pair: it finds
-// the s-th smallest (key, column) by a radix select over regenerated keys
-// (12 + 12 bits by LDS histograms, then an explicit candidate list for the last 8
-// bits and the column tie-break), then emits both rows with wave ballots.
+// the s-th smallest (key, column) by a radix select over regenerated keys, then emits
+// both rows with wave ballots. Usually two passes over the keys are enough: the first
+// histograms the top 12 bits and, at the same time, keeps the keys whose top bits fall
+// in a window around the expected position of the threshold (s/n of the key range,
+// +- 3 standard deviations); if the threshold bin is inside the window the exact
+// threshold comes from those kept keys. Otherwise two more passes refine it
+// (next 12 bits by histogram, last 8 bits + column tie-break from a candidate list).
+#include <math.h>
+
 #include "internal.h"
 
 namespace {
@@ -73,6 +79,7 @@ struct SampleArgs {
   float* w;
   int32_t* sz;
   int* error_flag;
+  uint32_t window_cap;  // entries of the dynamic-LDS window list
 };
 
 __global__ __launch_bounds__(kThreads) void sample_pairs_kernel(SampleArgs a) {
@@ -81,7 +88,9 @@ __global__ __launch_bounds__(kThreads) void sample_pairs_kernel(SampleArgs a) {
   __shared__ uint32_t res[2];
   __shared__ unsigned long long cand[kCandMax];
   __shared__ uint32_t cand_count;
+  __shared__ uint32_t window_count;
   __shared__ unsigned long long threshold;
+  extern __shared__ unsigned long long window[];  // (key << 32 | column) of the keys near the expected threshold
 
   const int t = threadIdx.x;
   const int lane = t & 63, wave = t >> 6;
@@ -114,9 +123,22 @@ __global__ __launch_bounds__(kThreads) void sample_pairs_kernel(SampleArgs a) {
     const uint32_t s = (uint32_t)lo;
     const uint32_t r_lo = (uint32_t)r, r_hi = (uint32_t)((uint64_t)r >> 32);
 
-    // pass A: histogram of the top 12 key bits
+    // window of top-12-bit bins around the expected position of the s-th smallest key
+    uint32_t win_lo, win_hi;
+    {
+      const float fs = (float)s, fn = (float)n;
+      const float sigma = sqrtf(fs * (fn - fs) / fn);  // of the number of keys below a fixed quantile
+      const uint32_t pred = (uint32_t)(((uint64_t)s << 12) / (uint64_t)n);
+      const uint32_t delta = 2u + (uint32_t)ceilf(3.0f * sigma * 4096.0f / fn);
+      win_lo = pred > delta ? pred - delta : 0u;
+      win_hi = pred + delta < (uint32_t)kBins - 1u ? pred + delta : (uint32_t)kBins - 1u;
+    }
+    // pass A: histogram of the top 12 key bits; keys in the window are kept
     for (int i = t; i < kBins; i += kThreads) hist[i] = 0;
-    if (t == 0) cand_count = 0;
+    if (t == 0) {
+      cand_count = 0;
+      window_count = 0;
+    }
     __syncthreads();
     for (int64_t q = t; q < nq; q += kThreads) {
       uint32_t key[4];
@@ -124,44 +146,71 @@ __global__ __launch_bounds__(kThreads) void sample_pairs_kernel(SampleArgs a) {
       const int64_t j0 = q << 2;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        if (j0 + i < n) atomicAdd(&hist[key[i] >> 20], 1u);
+        if (j0 + i < n) {
+          const uint32_t bin = key[i] >> 20;
+          atomicAdd(&hist[bin], 1u);
+          if (bin >= win_lo && bin <= win_hi) {
+            const uint32_t pos = atomicAdd(&window_count, 1u);
+            if (pos < a.window_cap) window[pos] = ((unsigned long long)key[i] << 32) | (uint32_t)(j0 + i);
+          }
+        }
     }
     __syncthreads();
     select_bin(hist, part, s, res);
     const uint32_t bin1 = res[0];
     const uint32_t want2 = s - res[1];
+    uint32_t want3 = 0;
+    const bool in_window = bin1 >= win_lo && bin1 <= win_hi && window_count <= a.window_cap;
     __syncthreads();
-
-    // pass B: next 12 bits among keys in bin1
-    for (int i = t; i < kBins; i += kThreads) hist[i] = 0;
-    __syncthreads();
-    for (int64_t q = t; q < nq; q += kThreads) {
-      uint32_t key[4];
-      philox4x32_10((uint32_t)q, r_lo, r_hi, a.tag, a.seed_lo, a.seed_hi, key);
-      const int64_t j0 = q << 2;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (j0 + i < n && (key[i] >> 20) == bin1) atomicAdd(&hist[(key[i] >> 8) & 0xFFFu], 1u);
-    }
-    __syncthreads();
-    select_bin(hist, part, want2, res);
-    const uint32_t prefix24 = (bin1 << 12) | res[0];
-    const uint32_t want3 = want2 - res[1];  // 1-based rank among the candidates
-    __syncthreads();
-
-    // pass C: list the keys sharing the 24-bit prefix, as (key, column) composites
-    for (int64_t q = t; q < nq; q += kThreads) {
-      uint32_t key[4];
-      philox4x32_10((uint32_t)q, r_lo, r_hi, a.tag, a.seed_lo, a.seed_hi, key);
-      const int64_t j0 = q << 2;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (j0 + i < n && (key[i] >> 8) == prefix24) {
-          uint32_t pos = atomicAdd(&cand_count, 1u);
-          if (pos < kCandMax) cand[pos] = ((unsigned long long)key[i] << 32) | (uint32_t)(j0 + i);
+    bool have_candidates = false;
+    if (in_window) {
+      // the keys of the threshold bin are among the kept ones: move them to the candidate list
+      const uint32_t wc = window_count;
+      for (uint32_t i = t; i < wc; i += kThreads) {
+        const unsigned long long c = window[i];
+        if ((uint32_t)(c >> 52) == bin1) {
+          const uint32_t pos = atomicAdd(&cand_count, 1u);
+          if (pos < kCandMax) cand[pos] = c;
         }
+      }
+      __syncthreads();
+      have_candidates = cand_count <= kCandMax;
+      want3 = want2;  // 1-based rank inside the threshold bin
+      __syncthreads();
+      if (!have_candidates && t == 0) cand_count = 0;
+      __syncthreads();
     }
-    __syncthreads();
+    if (!have_candidates) {
+      // pass B: next 12 bits among keys in bin1
+      for (int i = t; i < kBins; i += kThreads) hist[i] = 0;
+      __syncthreads();
+      for (int64_t q = t; q < nq; q += kThreads) {
+        uint32_t key[4];
+        philox4x32_10((uint32_t)q, r_lo, r_hi, a.tag, a.seed_lo, a.seed_hi, key);
+        const int64_t j0 = q << 2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (j0 + i < n && (key[i] >> 20) == bin1) atomicAdd(&hist[(key[i] >> 8) & 0xFFFu], 1u);
+      }
+      __syncthreads();
+      select_bin(hist, part, want2, res);
+      const uint32_t prefix24 = (bin1 << 12) | res[0];
+      want3 = want2 - res[1];  // 1-based rank among the candidates
+      __syncthreads();
+      // pass C: list the keys sharing the 24-bit prefix, as (key, column) composites
+      for (int64_t q = t; q < nq; q += kThreads) {
+        uint32_t key[4];
+        philox4x32_10((uint32_t)q, r_lo, r_hi, a.tag, a.seed_lo, a.seed_hi, key);
+        const int64_t j0 = q << 2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (j0 + i < n && (key[i] >> 8) == prefix24) {
+            uint32_t pos = atomicAdd(&cand_count, 1u);
+            if (pos < kCandMax) cand[pos] = ((unsigned long long)key[i] << 32) | (uint32_t)(j0 + i);
+          }
+      }
+      __syncthreads();
+    }
     uint32_t nc = cand_count;
     if (nc > kCandMax) {  // never in practice (needs > 2048 of n keys in one 2^-24 slice)
       if (t == 0) atomicExch(a.error_flag, 1);
@@ -293,6 +342,15 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
   a.w = w;
   a.sz = sz;
   a.error_flag = d_err;
+  // window list capacity: bins within 3 sigma of the expected threshold position at the widest size (s = n/2)
+  {
+    const double nn = (double)plan.n, sigma = sqrt(nn / 4.0);
+    const double bins = 2.0 * (2.0 + ceil(3.0 * sigma * 4096.0 / nn)) + 1.0;
+    double cap = bins * nn / 4096.0 * 1.5 + 64.0;
+    if (cap < 256.0) cap = 256.0;
+    if (cap > 4096.0) cap = 4096.0;  // the widest classes of huge games overflow it and take the four-pass route
+    a.window_cap = (uint32_t)cap;
+  }
   const int64_t pairs = pair_end - pair_begin;
   if (plan.enumerate) {
     const int threads = 256;
@@ -300,7 +358,7 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
     hipLaunchKernelGGL(enumerate_pairs_kernel, dim3((unsigned)blocks), dim3(threads), 0, ctx->stream, a);
   } else {
     const int64_t blocks = pairs < (int64_t)ctx->num_cus * 64 ? pairs : (int64_t)ctx->num_cus * 64;
-    hipLaunchKernelGGL(sample_pairs_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, a);
+    hipLaunchKernelGGL(sample_pairs_kernel, dim3((unsigned)blocks), dim3(kThreads), (size_t)a.window_cap * 8, ctx->stream, a);
   }
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
