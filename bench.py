@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=16,
+                    help="also time ds_explain_batch on this many targets (0 = skip); reported under \"batch\"")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB first (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -203,6 +205,19 @@ def main():
         "kernels": {name: {kk: v[kk] for kk in ("ms", "bound", "achieved", "peak", "unit", "frac")}
                     for name, v in kernels.items()},
     }
+    # several explanations in flight (ds_explain_batch runs up to four at a time on worker contexts)
+    if args.batch > 0:
+        tg = [targets[i % len(targets)] for i in range(args.batch)]
+        ctx.explain_batch(tg, w.n_samples, w.seed, opts, capacity=capacity * args.batch)   # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps_b = 3
+        for _ in range(reps_b):
+            ctx.explain_batch(tg, w.n_samples, w.seed, opts, capacity=capacity * args.batch)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        out["batch"] = {"targets_per_call": args.batch, "sec_per_explained_node": dt / (reps_b * args.batch),
+                        "coalition_evals_per_sec": reps_b * args.batch * rows / dt}
     ctx.close()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

@@ -151,12 +151,15 @@ int ds_set_gcn(ds_ctx* ctx, int32_t num_layers, const int32_t* dims, const void*
 int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, const ds_options* opts,
                float* phi, int64_t* M_inout, int64_t* edge_src, int64_t* edge_dst, ds_report* report);
 
-/* Explain T targets one after another (each exactly as ds_explain would).
+/* Explain T targets (paper's protocol: a set of test nodes per run). Every target gets exactly the result
+ * ds_explain would give it; up to four explanations are in flight at a time, each on an internal worker
+ * context with its own stream, workspace and host thread, which fills the GPU better than one explanation
+ * at a time. The call returns when all are done.
  *   targets [host]: int64[T]; phi_concat: float[capacity] out, target t's scores at
  *   offsets[t] .. offsets[t+1]-1; M_out [host]: int64[T]; offsets [host]: int64[T+1];
  *   edge_src/edge_dst: int64[capacity] or NULL; reports [host]: ds_report[T] or NULL.
- * If the total exceeds `capacity`, DS_ECAPACITY is returned, offsets[T] holds the
- * needed total and the targets that fitted are complete. */
+ * If the total exceeds `capacity`, DS_ECAPACITY is returned, M_out and offsets are complete
+ * (offsets[T] is the needed total) and the targets whose range fits are explained. */
 int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, int64_t n_samples,
                      uint64_t seed, const ds_options* opts, float* phi_concat, int64_t* M_out,
                      int64_t* offsets, int64_t* edge_src, int64_t* edge_dst, int64_t capacity,

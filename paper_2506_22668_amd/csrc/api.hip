@@ -1,6 +1,8 @@
 // C ABI entry points: argument checks, workspace, and the end-to-end explanation.
 #include "internal.h"
 
+#include <thread>
+
 int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...) {
   if (ctx) {
     va_list ap;
@@ -94,6 +96,7 @@ int ds_create(ds_ctx** out, int device, void* stream) {
   for (int i = 0; i < 8; ++i)
     if (hipEventCreate(&ctx->kev[i]) != hipSuccess) { delete ctx; return DS_EDEVICE; }
   for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
+  ctx->owns_stream = false;
   ctx->cg_spare = nullptr;
   ctx->cg_spare_bytes = 0;
   ctx->h_stage = nullptr;
@@ -113,6 +116,8 @@ int ds_create(ds_ctx** out, int device, void* stream) {
 int ds_destroy(ds_ctx* ctx) {
   if (!ctx) return DS_OK;
   hipSetDevice(ctx->device);
+  for (ds_ctx* w : ctx->workers) ds_destroy(w);
+  ctx->workers.clear();
   hipStreamSynchronize(ctx->stream);
   for (ds_cgraph* g : ctx->graphs) {
     if (g->block) hipFree(g->block);
@@ -133,6 +138,7 @@ int ds_destroy(ds_ctx* ctx) {
   if (ctx->h_mail) hipHostFree(ctx->h_mail);
   for (int i = 0; i < 6; ++i) hipEventDestroy(ctx->ev[i]);
   for (int i = 0; i < 8; ++i) hipEventDestroy(ctx->kev[i]);
+  if (ctx->owns_stream) hipStreamDestroy(ctx->stream);
   delete ctx;
   return DS_OK;
 }
@@ -538,30 +544,89 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   return rc;
 }
 
+// worker contexts of a batch: same graph, features and model as the parent, own stream and workspace
+static int ensure_workers(ds_ctx* ctx, int count) {
+  while ((int)ctx->workers.size() < count) {
+    hipStream_t st;
+    DS_HIP(ctx, hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+    ds_ctx* w = nullptr;
+    if (ds_create(&w, ctx->device, (void*)st) != DS_OK) {
+      (void)hipStreamDestroy(st);
+      return ds_fail(ctx, DS_EDEVICE, "cannot create a worker context");
+    }
+    w->owns_stream = true;
+    ctx->workers.push_back(w);
+  }
+  for (ds_ctx* w : ctx->workers) {
+    w->N = ctx->N; w->nnz = ctx->nnz; w->row_ptr = ctx->row_ptr; w->col = ctx->col;
+    w->X = ctx->X; w->d0 = ctx->d0;
+    w->L = ctx->L;
+    for (int l = 0; l <= DS_MAX_LAYERS; ++l) w->dims[l] = ctx->dims[l];
+    for (int l = 0; l < DS_MAX_LAYERS; ++l) { w->W[l] = ctx->W[l]; w->bias[l] = ctx->bias[l]; }
+    w->transform_dtype = ctx->transform_dtype;
+    w->model_version = ctx->model_version;
+  }
+  return DS_OK;
+}
+
 int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, int64_t n_samples, uint64_t seed,
                      const ds_options* opts, float* phi_concat, int64_t* M_out, int64_t* offsets, int64_t* edge_src,
                      int64_t* edge_dst, int64_t capacity, ds_report* reports) {
   if (!ctx || !targets || num_targets < 0 || !M_out || !offsets) return DS_EINVAL;
-  int64_t off = 0;
-  int worst = DS_OK;
-  bool full = false;
+  DS_HIP(ctx, hipSetDevice(ctx->device));
   offsets[0] = 0;
+  if (num_targets == 0) return DS_OK;
+  // Up to four explanations are in flight at a time, each on its own worker context and host
+  // thread: a single explanation leaves much of the GPU idle in its latency-bound stages.
+  const int nw = num_targets < 4 ? num_targets : 4;
+  DS_TRY(ensure_workers(ctx, nw));
+  DS_HIP(ctx, hipStreamSynchronize(ctx->stream));  // whatever the caller queued before is visible to the workers
+  std::vector<int> status(num_targets, DS_OK);
+  auto run = [&](int phase) {
+    std::vector<std::thread> pool;
+    for (int wi = 0; wi < nw; ++wi)
+      pool.emplace_back([&, wi]() {
+        ds_ctx* w = ctx->workers[wi];
+        (void)hipSetDevice(w->device);
+        for (int32_t t = wi; t < num_targets; t += nw) {
+          if (phase == 0) {  // sizes: only the computational graph
+            ds_cgraph* cg = nullptr;
+            int rc = ds_extract(w, targets[t], opts, &cg);
+            if (rc == DS_OK) {
+              M_out[t] = cg->info.num_players;
+              ds_cgraph_free(w, cg);
+            }
+            status[t] = rc;
+          } else if (status[t] == DS_OK && offsets[t + 1] <= capacity) {
+            int64_t m = M_out[t];
+            const int64_t off = offsets[t];
+            status[t] = ds_explain(w, targets[t], n_samples, seed, opts, phi_concat ? phi_concat + off : nullptr, &m,
+                                   edge_src ? edge_src + off : nullptr, edge_dst ? edge_dst + off : nullptr,
+                                   reports ? reports + t : nullptr);
+          }
+        }
+      });
+    for (auto& th : pool) th.join();
+  };
+  run(0);
   for (int32_t t = 0; t < num_targets; ++t) {
-    int64_t m = full ? 0 : capacity - off;
-    int rc = ds_explain(ctx, targets[t], n_samples, seed, opts, phi_concat ? phi_concat + off : nullptr, &m,
-                        edge_src ? edge_src + off : nullptr, edge_dst ? edge_dst + off : nullptr,
-                        reports ? reports + t : nullptr);
-    if (rc == DS_ECAPACITY) {
-      full = true;
-      worst = DS_ECAPACITY;
-    } else if (rc != DS_OK && rc != DS_ENOTCONV) {
-      return rc;
-    } else if (rc == DS_ENOTCONV && worst == DS_OK) {
-      worst = rc;
+    if (status[t] != DS_OK) {
+      strncpy(ctx->err, ctx->workers[t % nw]->err, sizeof(ctx->err) - 1);
+      return status[t];
     }
-    M_out[t] = m;
-    off += m;
-    offsets[t + 1] = off;
+    offsets[t + 1] = offsets[t] + M_out[t];
+  }
+  run(1);
+  int worst = offsets[num_targets] > capacity ? DS_ECAPACITY : DS_OK;
+  if (worst == DS_ECAPACITY)
+    ds_fail(ctx, DS_ECAPACITY, "the batch needs %lld entries, the buffers hold %lld", (long long)offsets[num_targets], (long long)capacity);
+  for (int32_t t = 0; t < num_targets; ++t) {
+    if (status[t] == DS_ENOTCONV) {
+      if (worst == DS_OK) worst = DS_ENOTCONV;
+    } else if (status[t] != DS_OK) {
+      strncpy(ctx->err, ctx->workers[t % nw]->err, sizeof(ctx->err) - 1);
+      return status[t];
+    }
   }
   return worst;
 }

@@ -382,11 +382,7 @@ int ds_bit_spmv_tab(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, 
   const int64_t cpg = (n_chunks + groups - 1) / groups;
   groups = (n_chunks + cpg - 1) / cpg;
   const size_t lds = (size_t)(kTabGroups * 256 + kTabGroups * 32) * sizeof(double);
-  static bool attr_set = false;
-  if (!attr_set) {
-    DS_HIP(ctx, hipFuncSetAttribute((const void*)bit_spmv_tab_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  DS_HIP(ctx, hipFuncSetAttribute((const void*)bit_spmv_tab_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   hipLaunchKernelGGL(bit_spmv_tab_kernel, dim3((unsigned)row_groups, (unsigned)groups), dim3(kTabThreads), lds, ctx->stream, B,
                      rows, cols, stride, row_first, row_step, x, ws, cpg, n_chunks);
   hipLaunchKernelGGL(tab_reduce_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, ctx->stream, ws, rows,

@@ -73,6 +73,9 @@ struct ds_ctx {
   // a second stream (default priority) for work that does not depend on what the main stream is doing
   hipStream_t side;
   hipEvent_t fork_ev, join_ev, fork2_ev, join2_ev;
+  // ds_explain_batch runs several targets at once on worker contexts (own stream, own workspace)
+  std::vector<ds_ctx*> workers;
+  bool owns_stream;
 };
 
 int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...);
