@@ -201,7 +201,10 @@ int ds_plan_tables(int64_t n, int64_t n_samples, int64_t* b, float* wtab);
  * counter (column/4, r, tag), so any pair range can be regenerated alone.
  *   Z: uint64[k*W] out; w: float[k] out (per-row regression weight);
  *   sz: int32[k] out (coalition sizes); k_out [host]. tag: stream id (the
- *   explanation uses the low 32 bits of the target's global id). */
+ *   explanation uses the low 32 bits of the target's global id).
+ * Diagnostic: the environment variable DISTSHAP_SAMPLER_WINDOW=<entries> shrinks the list of keys the
+ * first pass keeps around the expected threshold (0 = keep none), which forces the slower four-pass
+ * selection; the masks are the same either way. */
 int ds_sample(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, uint64_t* Z,
               float* w, int32_t* sz, int64_t* k_out);
 /* Only pairs pair_begin <= r < pair_end: writes rows 2*pair_begin .. 2*pair_end-1

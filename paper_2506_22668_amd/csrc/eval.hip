@@ -289,18 +289,18 @@ __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
 // arithmetic, not the mask stream, and gathering a feature row per active edge per coalition
 // keeps L2 busy instead of the ALUs. Here a workgroup takes 64 coalitions, one per lane, and every
 // loop (over nodes, CSR entries, features) is uniform across the wave:
-//   * the mask words of the 64 coalitions sit in LDS as zs[word][lane];
+//   * the mask words of the 64 coalitions sit in LDS as zs[word][lane]; the local CSR sits in LDS too;
 //   * degrees: for node v, each lane counts the set bits of its coalition among the row's
-//     entries (no atomics), rs[v][lane] = d^-1/2 goes to a per-workgroup scratch in global memory;
-//   * aggregation of row t: per entry, each lane forms coef = bit ? rs[src][lane] : 0 and adds
-//     coef * H[src][f] for 64 features held in registers. For layer 1 the operand H = P is the
-//     same for all coalitions: its rows are staged in LDS and read as broadcasts, so one row load
-//     serves 64 coalitions. For later layers H is per coalition, laid out [row][feature][lane].
-//   * transforms: out[j] += q[f] * W[f][j] with W rows broadcast from LDS in the same way.
-// The four waves of the workgroup split the nodes and rows among them (same 64 coalitions), and
-// meet at barriers between layers. All per-coalition intermediates are [..][64 lanes] arrays.
+//     entries (no atomics), kept as u16 in LDS (or as d^-1/2 in a global scratch for larger graphs);
+//   * layer 1, row t: H1[f][c] = sum_e P[src_e][f] * coef[e][c] with coef = bit ? d_src^-1/2 : 0 is a
+//     (features x entries) . (entries x coalitions) product and runs on the matrix cores;
+//   * later layers work on per-coalition operands laid out [row][feature][lane] in a global scratch;
+//     they are cut into (row, 16-feature) items so that all waves stay busy, the weight matrix is
+//     broadcast from LDS.
+// The eight waves of the workgroup split nodes, rows and items among them (same 64 coalitions) and
+// meet at barriers between the stages.
 constexpr int kBW = 32;        // mask words per coalition held in LDS
-constexpr int kStageRows = 16; // operand rows staged per step
+constexpr int kStageRows = 16; // entries per matrix-core batch; also sizes the shared weight buffer
 constexpr int kBThreads = 512; // eight waves share the 64 coalitions of a workgroup
 constexpr int kBWaves = kBThreads / 64;
 constexpr int kDegLdsMaxNodes = 640;  // degrees as u16[V][64] in LDS up to this many nodes (80 KB)
@@ -313,59 +313,11 @@ struct BatchedArgs {
   int32_t csr_lds_offset;  // byte offset of the LDS copy of the local CSR (if used)
 };
 
-// acc[f] += coef_i * row_i[f] for the staged rows; rows live in this wave's LDS stage area
-__device__ __forceinline__ void fma_staged_rows(float (&acc)[64], const float* stage, const float (&coef)[kStageRows], int cnt) {
-#pragma unroll
-  for (int i = 0; i < kStageRows; ++i) {
-    if (i < cnt) {
-      const float c = coef[i];
-      const float4* r4 = (const float4*)(stage + i * 64);
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const float4 v = r4[j];
-        acc[4 * j + 0] += c * v.x;
-        acc[4 * j + 1] += c * v.y;
-        acc[4 * j + 2] += c * v.z;
-        acc[4 * j + 3] += c * v.w;
-      }
-    }
-  }
-}
-
-// stage `cnt` rows into LDS: row i = base + rowid_i * stride + f0 .. +63 (zero beyond width), where
-// rowid_i is held by lane i of `rowv`. Four rows per load instruction, 16 lanes x float4 each.
-__device__ __forceinline__ void stage_rows(float* stage, const float* base, int rowv, int cnt, int stride, int f0, int width,
-                                           bool bf16) {
-  const int lane = threadIdx.x & 63;
-  const int sub = lane >> 4, c4 = (lane & 15) * 4;
-#pragma unroll
-  for (int q = 0; q < kStageRows / 4; ++q) {
-    const int i = q * 4 + sub;
-    const int r = __shfl(rowv, i, 64);
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < cnt) {
-      const float* p = base + (size_t)r * stride + f0 + c4;
-      if (f0 + c4 + 3 < width && ((stride | f0) & 3) == 0) {
-        v = *(const float4*)p;
-      } else {
-        if (f0 + c4 + 0 < width) v.x = p[0];
-        if (f0 + c4 + 1 < width) v.y = p[1];
-        if (f0 + c4 + 2 < width) v.z = p[2];
-        if (f0 + c4 + 3 < width) v.w = p[3];
-      }
-      if (bf16) {
-        v.x = bf16_round(v.x); v.y = bf16_round(v.y); v.z = bf16_round(v.z); v.w = bf16_round(v.w);
-      }
-    }
-    *(float4*)(stage + i * 64 + c4) = v;
-  }
-}
-
 template <bool DEG_LDS, bool CSR_LDS>
 __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(BatchedArgs b) {
   const EvalArgs& a = b.e;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  // LDS: zs[kBW][64] u64 | stage[waves][16][64] f32 | deg[V][64] u16 (optional) | local CSR (optional)
+  // LDS: zs[kBW][64] u64 | weight-matrix buffer f32[waves*16*64] | deg[V][64] u16 (optional) | local CSR (optional)
   uint64_t* zs = (uint64_t*)smem_raw;
   float* stage_all = (float*)(smem_raw + kBW * 64 * 8);
   unsigned short* degs = (unsigned short*)(smem_raw + kBW * 64 * 8 + kBWaves * kStageRows * 64 * 4);
@@ -389,7 +341,6 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
   const int32_t* const rp_ = g_rp;
   const int32_t* const col_ = g_col;
   const int32_t* const eid_ = g_eid;
-  float* stage = stage_all + wave * kStageRows * 64;
   float* S = b.scratch + (size_t)blockIdx.x * b.scratch_stride;
   float* rs = S;
   float* bufA = rs + b.rs_floats;

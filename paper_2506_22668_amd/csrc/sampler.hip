@@ -16,6 +16,7 @@
 // threshold comes from those kept keys. Otherwise two more passes refine it
 // (next 12 bits by histogram, last 8 bits + column tie-break from a candidate list).
 #include <math.h>
+#include <stdlib.h>
 
 #include "internal.h"
 
@@ -350,6 +351,11 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
     if (cap < 256.0) cap = 256.0;
     if (cap > 4096.0) cap = 4096.0;  // the widest classes of huge games overflow it and take the four-pass route
     a.window_cap = (uint32_t)cap;
+    // diagnostic knob: a smaller list forces the four-pass route (the result must not change)
+    if (const char* env = getenv("DISTSHAP_SAMPLER_WINDOW")) {
+      const long v = strtol(env, nullptr, 10);
+      if (v >= 0 && v < (long)a.window_cap) a.window_cap = (uint32_t)v;
+    }
   }
   const int64_t pairs = pair_end - pair_begin;
   if (plan.enumerate) {

@@ -108,8 +108,9 @@ def _stage_check(key, pair_stride, y_rows, check_residual=True):
             # phi is rounded to fp32 on output: allow that rounding on top of tol
             assert res <= 2.0 * w.tol
     else:
-        ref, it, rel = cfast.cgls(n, Zh, wt.cpu().numpy(), yh, tol=1e-12, max_iter=2000)
-        assert rel <= 1e-12
+        # 1e-11 is safely above where fp64 round-off stalls the recurrence on this size
+        ref, it, rel = cfast.cgls(n, Zh, wt.cpu().numpy(), yh, tol=1e-11, max_iter=2000)
+        assert rel <= 1e-11
         err = np.abs(got - ref).max()
         say(f"{key}: max |phi - oracle| = {err:.3e}")
         assert err <= 1e-4 * np.abs(ref).max()

@@ -37,6 +37,18 @@ def test_sampler_bit_exact(ctx_tiny, n, ns, seed, tag):
     assert np.array_equal(sz.cpu().numpy(), szo)
 
 
+@pytest.mark.parametrize("window", ["0", "3"])
+def test_sampler_four_pass_route_gives_the_same_masks(ctx_tiny, window, monkeypatch):
+    ctx, _ = ctx_tiny
+    say(f"sampler forced fallback window={window}")
+    monkeypatch.setenv("DISTSHAP_SAMPLER_WINDOW", window)
+    for n, ns in [(300, 2000), (5000, 600)]:
+        Z, w, sz = ctx.sample(n, ns, 31, 8)
+        Zo, wo, szo = sampling.sample(n, ns, 31, 8)
+        assert np.array_equal(to_u64(Z), Zo)
+        assert np.array_equal(sz.cpu().numpy(), szo)
+
+
 def test_sampler_pair_ranges_equal_the_full_run(ctx_tiny):
     ctx, _ = ctx_tiny
     n, ns, seed, tag = 333, 5000, 99, 3
