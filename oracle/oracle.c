@@ -15,6 +15,7 @@
  *   oc_normal_residual |P Z^T W (t - Z psi)| / |P Z^T W t| for a given phi (property check at any size)
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -279,29 +280,39 @@ static void fwd(int64_t n, int64_t k, const uint64_t* Z, const double* sq, const
   }
 }
 
-/* s = P Z^T (sq .* r) */
+/* s = P Z^T (sq .* r). Rows are split statically over the threads and the per-thread sums are added in
+ * thread order, so the result does not change from run to run on one machine. */
 static void adj(int64_t n, int64_t k, const uint64_t* Z, const double* sq, const double* r, double* s) {
   const int64_t W64 = (n + 63) / 64;
-  memset(s, 0, (size_t)n * sizeof(double));
+  int nthreads = 1;
 #pragma omp parallel
   {
-    double* loc = (double*)calloc((size_t)n, sizeof(double));
-#pragma omp for schedule(dynamic, 64)
+#pragma omp single
+    nthreads = omp_get_num_threads();
+  }
+  double* loc = (double*)calloc((size_t)nthreads * (size_t)n, sizeof(double));
+#pragma omp parallel num_threads(nthreads)
+  {
+    double* mine = loc + (size_t)omp_get_thread_num() * (size_t)n;
+#pragma omp for schedule(static)
     for (int64_t i = 0; i < k; ++i) {
       const double g = sq[i] * r[i];
       if (g == 0.0) continue;
       for (int64_t wd = 0; wd < W64; ++wd) {
         uint64_t word = Z[i * W64 + wd];
         while (word) {
-          loc[wd * 64 + __builtin_ctzll(word)] += g;
+          mine[wd * 64 + __builtin_ctzll(word)] += g;
           word &= word - 1;
         }
       }
     }
-#pragma omp critical
-    for (int64_t j = 0; j < n; ++j) s[j] += loc[j];
-    free(loc);
   }
+  for (int64_t j = 0; j < n; ++j) {
+    double acc = 0.0;
+    for (int t = 0; t < nthreads; ++t) acc += loc[(size_t)t * (size_t)n + j];
+    s[j] = acc;
+  }
+  free(loc);
   double mean = 0.0;
   for (int64_t j = 0; j < n; ++j) mean += s[j];
   mean /= (double)n;

@@ -67,9 +67,14 @@ def test_c_cgls_and_residual_equal_numpy():
         for tol in (1e-6, 1e-11):
             ref, it, rel = solve.solve_cgls(bits, w, y, tol=tol)
             phi, itc, relc = cfast.cgls(n, Z, w, y, tol=tol)
-            assert abs(itc - it) <= 1
-            # different summation orders separate the two Krylov sequences slightly before they converge
-            assert np.abs(phi - ref).max() < max(tol, 1e-9) * max(1.0, np.abs(ref).max())
+            assert relc <= tol and abs(itc - it) <= 1
+            # the two sum in different orders; near a loose threshold they may stop one iteration apart,
+            # so the iterates are compared tightly only when both are converged far below it
+            bound = 1e-9 if tol < 1e-9 else 1e-4
+            assert np.abs(phi - ref).max() < bound * max(1.0, np.abs(ref).max())
             # the explicitly recomputed residual equals the recursively updated one up to round-off
             assert cfast.normal_residual(n, Z, w, y, phi) == pytest.approx(relc, rel=1e-3, abs=1e-9)
+        # the C version is reproducible from run to run
+        again = cfast.cgls(n, Z, w, y, tol=1e-6)[0]
+        assert np.array_equal(again, cfast.cgls(n, Z, w, y, tol=1e-6)[0])
         assert cfast.normal_residual(n, Z, w, y, np.full(n, (y[1] - y[0]) / n)) == pytest.approx(1.0)
