@@ -69,7 +69,7 @@ typedef struct ds_options {
   int32_t solver;     /* ds_solver; AUTO picks GRAM_CHOL for n <= 16384, else CGLS */
   double tol;         /* CGLS: stop when |s_i| / |s_0| <= tol; 0 -> 1e-6 */
   int32_t max_iter;   /* CGLS: 0 -> min(n, 10000) */
-  int32_t batch_rows; /* coalition rows evaluated per launch; 0 -> automatic */
+  int32_t batch_rows; /* reserved (one launch covers all coalition rows); leave 0 */
   int32_t paired;     /* ds_solve only: 1 promises that rows 2r and 2r+1 are complements with
                          equal weights (the layout ds_sample writes), which lets CGLS read only
                          one member of each pair; 0 makes no assumption. ds_explain always
