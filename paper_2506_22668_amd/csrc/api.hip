@@ -1,6 +1,7 @@
 // C ABI entry points: argument checks, workspace, and the end-to-end explanation.
 #include "internal.h"
 
+#include <string>
 #include <thread>
 
 int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...) {
@@ -582,13 +583,16 @@ int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, i
   DS_TRY(ensure_workers(ctx, nw));
   DS_HIP(ctx, hipStreamSynchronize(ctx->stream));  // whatever the caller queued before is visible to the workers
   std::vector<int> status(num_targets, DS_OK);
+  std::vector<std::string> errs(num_targets);
+  int active = nw;  // worker threads of the current phase
   auto run = [&](int phase) {
     std::vector<std::thread> pool;
-    for (int wi = 0; wi < nw; ++wi)
-      pool.emplace_back([&, wi]() {
+    const int na = active;
+    for (int wi = 0; wi < na; ++wi)
+      pool.emplace_back([&, wi, na]() {
         ds_ctx* w = ctx->workers[wi];
         (void)hipSetDevice(w->device);
-        for (int32_t t = wi; t < num_targets; t += nw) {
+        for (int32_t t = wi; t < num_targets; t += na) {
           if (phase == 0) {  // sizes: only the computational graph
             ds_cgraph* cg = nullptr;
             int rc = ds_extract(w, targets[t], opts, &cg);
@@ -603,6 +607,7 @@ int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, i
             status[t] = ds_explain(w, targets[t], n_samples, seed, opts, phi_concat ? phi_concat + off : nullptr, &m,
                                    edge_src ? edge_src + off : nullptr, edge_dst ? edge_dst + off : nullptr,
                                    reports ? reports + t : nullptr);
+            if (status[t] != DS_OK && status[t] != DS_ENOTCONV) errs[t] = w->err;
           }
         }
       });
@@ -616,6 +621,12 @@ int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, i
     }
     offsets[t + 1] = offsets[t] + M_out[t];
   }
+  // Large games fill the GPU on their own (and their workspaces are large): fewer of them at a time.
+  {
+    const int64_t avg = offsets[num_targets] / num_targets;
+    if (avg > 16384) active = 1;
+    else if (avg > 4096 && active > 2) active = 2;
+  }
   run(1);
   int worst = offsets[num_targets] > capacity ? DS_ECAPACITY : DS_OK;
   if (worst == DS_ECAPACITY)
@@ -624,7 +635,7 @@ int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, i
     if (status[t] == DS_ENOTCONV) {
       if (worst == DS_OK) worst = DS_ENOTCONV;
     } else if (status[t] != DS_OK) {
-      strncpy(ctx->err, ctx->workers[t % nw]->err, sizeof(ctx->err) - 1);
+      strncpy(ctx->err, errs[t].c_str(), sizeof(ctx->err) - 1);
       return status[t];
     }
   }
