@@ -259,14 +259,14 @@ __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t 
       bad = true;
       p = 1.0;
     }
-    // 1/sqrt(p): single-precision seed, two Newton steps in double (a short dependent chain;
+    // 1/sqrt(p): single-precision seed, two Newton steps r += r (1/2 - (p/2) r^2) in double (a short dependent chain;
     // the library routine costs several times more per step of this sequential loop)
     double rinv;
     if (p > 1e-30 && p < 1e30) {
-      rinv = (double)__frsqrt_rn((float)p);
-      rinv = rinv * (1.5 - 0.5 * p * rinv * rinv);
-      rinv = rinv * (1.5 - 0.5 * p * rinv * rinv);
-      rinv = rinv * (1.5 - 0.5 * p * rinv * rinv);
+      rinv = (double)__frsqrt_rn((float)p);          // relative error about 1e-7
+      const double hp = 0.5 * p;
+      rinv = fma(rinv, fma(-hp * rinv, rinv, 0.5), rinv);  // -> 1e-14
+      rinv = fma(rinv, fma(-hp * rinv, rinv, 0.5), rinv);  // -> below one ulp
     } else {
       rinv = rsqrt(p);
     }
