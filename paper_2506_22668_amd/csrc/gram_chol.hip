@@ -219,10 +219,26 @@ constexpr int NB = 64;
 //   Y[r][c] -= S[r][kk] Y[kk][c] / p          (r > kk)       -> L^-1 = Y scaled by 1/sqrt(p) per row
 // i.e. the forward substitution L X = I rides along with the factorisation and needs no extra
 // sequential pass. Linv (NB x NB, identity-padded) goes to linv_out.
+__device__ __forceinline__ double fast_rsqrt(double p) {
+  // 1/sqrt(p): single-precision seed, two Newton steps r += r (1/2 - (p/2) r^2) in double (a short dependent
+  // chain; the library routine costs several times more per step of this sequential loop)
+  if (p > 1e-30 && p < 1e30) {
+    double r = (double)__frsqrt_rn((float)p);       // relative error about 1e-7
+    const double hp = 0.5 * p;
+    r = fma(r, fma(-hp * r, r, 0.5), r);             // -> 1e-14
+    r = fma(r, fma(-hp * r, r, 0.5), r);             // -> below one ulp
+    return r;
+  }
+  return rsqrt(p);
+}
+
+// Two columns per barrier: the owners publish columns kk, kk+1 of S and rows kk, kk+1 of Y; every thread
+// then rebuilds, for its own rows and columns, column kk+1 as it is after column kk's update, and applies
+// both rank-1 updates at once (NB is even, padding rows are identity rows).
 __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t ld, int64_t j0, int nb, double* linv_out,
                                                              int* flag) {
-  __shared__ double colbuf[2][NB];
-  __shared__ double rowbuf[2][NB];
+  __shared__ double colA[2][NB], colB[2][NB];
+  __shared__ double rowA[2][NB], rowB[2][NB];
   __shared__ double dinv[NB];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   double s[4][4], y[4][4];
@@ -235,61 +251,71 @@ __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t 
       y[i][j] = r == c ? 1.0 : 0.0;
     }
   bool bad = false;
-  for (int kk = 0; kk < NB; ++kk) {
-    const int buf = kk & 1, blk = kk >> 4, off = kk & 15;
-    if (tx == off) {
+  for (int kk = 0; kk < NB; kk += 2) {
+    const int buf = (kk >> 1) & 1, blk = kk >> 4, off = kk & 15;  // kk and kk+1 lie in the same 16-block
+    if (tx == off || tx == off + 1) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         if (j == blk) {
+          double* dst = tx == off ? colA[buf] : colB[buf];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) colbuf[buf][ty + 16 * i] = s[i][j];
+          for (int i = 0; i < 4; ++i) dst[ty + 16 * i] = s[i][j];
         }
     }
-    if (ty == off) {
+    if (ty == off || ty == off + 1) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (i == blk) {
+          double* dst = ty == off ? rowA[buf] : rowB[buf];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) rowbuf[buf][tx + 16 * j] = y[i][j];
+          for (int j = 0; j < 4; ++j) dst[tx + 16 * j] = y[i][j];
         }
     }
     __syncthreads();
-    double p = colbuf[buf][kk];
-    if (!(p > 0.0)) {
+    double pA = colA[buf][kk];
+    if (!(pA > 0.0)) {
       bad = true;
-      p = 1.0;
+      pA = 1.0;
     }
-    // 1/sqrt(p): single-precision seed, two Newton steps r += r (1/2 - (p/2) r^2) in double (a short dependent chain;
-    // the library routine costs several times more per step of this sequential loop)
-    double rinv;
-    if (p > 1e-30 && p < 1e30) {
-      rinv = (double)__frsqrt_rn((float)p);          // relative error about 1e-7
-      const double hp = 0.5 * p;
-      rinv = fma(rinv, fma(-hp * rinv, rinv, 0.5), rinv);  // -> 1e-14
-      rinv = fma(rinv, fma(-hp * rinv, rinv, 0.5), rinv);  // -> below one ulp
-    } else {
-      rinv = rsqrt(p);
+    const double rA = fast_rsqrt(pA);
+    const double ipA = rA * rA;
+    const double a1 = colA[buf][kk + 1] * ipA;               // S[kk+1][kk] / pA
+    double pB = fma(-a1, colA[buf][kk + 1], colB[buf][kk + 1]);
+    if (!(pB > 0.0)) {
+      bad = true;
+      pB = 1.0;
     }
-    const double inv_p = rinv * rinv;
-    // The guards sit on the multipliers, not on the 32 updates: columns <= kk of S must keep
-    // their value (lc = 0 there) and rows <= kk of Y likewise (ly = 0). The strict upper triangle
-    // of S holds don't-care values that never reach the lower one.
-    double lr[4], ly[4], lc[4], yr[4];
+    const double rB = fast_rsqrt(pB);
+    const double ipB = rB * rB;
+    // multipliers for this thread's rows (left) and columns (right); the guards sit here, not on the
+    // updates: columns <= kk (kk+1) of S keep their value under update A (B), rows <= kk (kk+1) of Y likewise
+    double lA[4], lB[4], lyA[4], lyB[4], cA[4], cB[4], yA[4], yB[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      lr[i] = -colbuf[buf][ty + 16 * i] * inv_p;
-      ly[i] = (ty + 16 * i > kk) ? lr[i] : 0.0;
-      lc[i] = (tx + 16 * i > kk) ? colbuf[buf][tx + 16 * i] : 0.0;
-      yr[i] = rowbuf[buf][tx + 16 * i];
+      const int r = ty + 16 * i, c = tx + 16 * i;
+      const double ar = colA[buf][r], br = fma(-a1, ar, colB[buf][r]);   // column kk+1 after update A, row r
+      lA[i] = -ar * ipA;
+      lB[i] = -br * ipB;
+      lyA[i] = r > kk ? lA[i] : 0.0;
+      lyB[i] = r > kk + 1 ? lB[i] : 0.0;
+      const double ac = colA[buf][c], bc = fma(-a1, ac, colB[buf][c]);
+      cA[i] = c > kk ? ac : 0.0;
+      cB[i] = c > kk + 1 ? bc : 0.0;
+      const double ya = rowA[buf][c];
+      yA[i] = ya;
+      yB[i] = fma(-a1, ya, rowB[buf][c]);                     // row kk+1 of Y after update A
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        s[i][j] = fma(lr[i], lc[j], s[i][j]);
-        y[i][j] = fma(ly[i], yr[j], y[i][j]);
+        s[i][j] = fma(lB[i], cB[j], fma(lA[i], cA[j], s[i][j]));
+        y[i][j] = fma(lyB[i], yB[j], fma(lyA[i], yA[j], y[i][j]));
       }
-    if (tid == 0) dinv[kk] = rinv;
+    if (tid == 0) {
+      dinv[kk] = rA;
+      dinv[kk + 1] = rB;
+    }
   }
   __syncthreads();
   if (bad && tid == 0) atomicExch(flag, 1);
