@@ -232,13 +232,17 @@ __device__ __forceinline__ double fast_rsqrt(double p) {
   return rsqrt(p);
 }
 
-// Two columns per barrier: the owners publish columns kk, kk+1 of S and rows kk, kk+1 of Y; every thread
-// then rebuilds, for its own rows and columns, column kk+1 as it is after column kk's update, and applies
-// both rank-1 updates at once (NB is even, padding rows are identity rows).
+// kCw columns per barrier: the owners publish columns kk .. kk+kCw-1 of S and the same rows of Y. Every
+// thread then eliminates the small kCw x kCw pivot block on its own (it needs the multipliers
+// a[u][w] = S'[kk+w][kk+u] / p_u of that elimination), rebuilds for its own rows and columns each
+// published column/row as it stands after the updates of the columns before it, and applies the kCw
+// rank-1 updates to its registers at once. (64 is a multiple of kCw; padding rows are identity rows.)
+constexpr int kCw = 4;
+
 __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t ld, int64_t j0, int nb, double* linv_out,
                                                              int* flag) {
-  __shared__ double colA[2][NB], colB[2][NB];
-  __shared__ double rowA[2][NB], rowB[2][NB];
+  __shared__ double cols[2][kCw][NB];
+  __shared__ double rows[2][kCw][NB];
   __shared__ double dinv[NB];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   double s[4][4], y[4][4];
@@ -251,71 +255,90 @@ __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t 
       y[i][j] = r == c ? 1.0 : 0.0;
     }
   bool bad = false;
-  for (int kk = 0; kk < NB; kk += 2) {
-    const int buf = (kk >> 1) & 1, blk = kk >> 4, off = kk & 15;  // kk and kk+1 lie in the same 16-block
-    if (tx == off || tx == off + 1) {
+  for (int kk = 0; kk < NB; kk += kCw) {
+    const int buf = (kk / kCw) & 1, blk = kk >> 4, off = kk & 15;  // the kCw columns lie in one 16-block
+    if (tx >= off && tx < off + kCw) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         if (j == blk) {
-          double* dst = tx == off ? colA[buf] : colB[buf];
+          double* dst = cols[buf][tx - off];
 #pragma unroll
           for (int i = 0; i < 4; ++i) dst[ty + 16 * i] = s[i][j];
         }
     }
-    if (ty == off || ty == off + 1) {
+    if (ty >= off && ty < off + kCw) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (i == blk) {
-          double* dst = ty == off ? rowA[buf] : rowB[buf];
+          double* dst = rows[buf][ty - off];
 #pragma unroll
           for (int j = 0; j < 4; ++j) dst[tx + 16 * j] = y[i][j];
         }
     }
     __syncthreads();
-    double pA = colA[buf][kk];
-    if (!(pA > 0.0)) {
-      bad = true;
-      pA = 1.0;
+    // pivot block: P[v][w] = S[kk+v][kk+w], eliminated column by column
+    double P[kCw][kCw], ip[kCw], rs[kCw], a[kCw][kCw];
+#pragma unroll
+    for (int w = 0; w < kCw; ++w)
+#pragma unroll
+      for (int v = 0; v < kCw; ++v) P[v][w] = cols[buf][w][kk + v];
+#pragma unroll
+    for (int w = 0; w < kCw; ++w) {
+      double pw = P[w][w];
+      if (!(pw > 0.0)) {
+        bad = true;
+        pw = 1.0;
+      }
+      rs[w] = fast_rsqrt(pw);
+      ip[w] = rs[w] * rs[w];
+#pragma unroll
+      for (int w2 = w + 1; w2 < kCw; ++w2) {
+        a[w][w2] = P[w2][w] * ip[w];
+#pragma unroll
+        for (int v = w2; v < kCw; ++v) P[v][w2] = fma(-a[w][w2], P[v][w], P[v][w2]);
+      }
     }
-    const double rA = fast_rsqrt(pA);
-    const double ipA = rA * rA;
-    const double a1 = colA[buf][kk + 1] * ipA;               // S[kk+1][kk] / pA
-    double pB = fma(-a1, colA[buf][kk + 1], colB[buf][kk + 1]);
-    if (!(pB > 0.0)) {
-      bad = true;
-      pB = 1.0;
-    }
-    const double rB = fast_rsqrt(pB);
-    const double ipB = rB * rB;
-    // multipliers for this thread's rows (left) and columns (right); the guards sit here, not on the
-    // updates: columns <= kk (kk+1) of S keep their value under update A (B), rows <= kk (kk+1) of Y likewise
-    double lA[4], lB[4], lyA[4], lyB[4], cA[4], cB[4], yA[4], yB[4];
+    // this thread's rows (left factors) and columns (right factors) of the kCw updates; the guards sit
+    // here, not on the updates: update w leaves columns <= kk+w of S and rows <= kk+w of Y alone
+    double lS[kCw][4], lY[kCw][4], cS[kCw][4], cY[kCw][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int r = ty + 16 * i, c = tx + 16 * i;
-      const double ar = colA[buf][r], br = fma(-a1, ar, colB[buf][r]);   // column kk+1 after update A, row r
-      lA[i] = -ar * ipA;
-      lB[i] = -br * ipB;
-      lyA[i] = r > kk ? lA[i] : 0.0;
-      lyB[i] = r > kk + 1 ? lB[i] : 0.0;
-      const double ac = colA[buf][c], bc = fma(-a1, ac, colB[buf][c]);
-      cA[i] = c > kk ? ac : 0.0;
-      cB[i] = c > kk + 1 ? bc : 0.0;
-      const double ya = rowA[buf][c];
-      yA[i] = ya;
-      yB[i] = fma(-a1, ya, rowB[buf][c]);                     // row kk+1 of Y after update A
+      double tr[kCw], tc[kCw], tyc[kCw];
+#pragma unroll
+      for (int w = 0; w < kCw; ++w) {
+        tr[w] = cols[buf][w][r];
+        tc[w] = cols[buf][w][c];
+        tyc[w] = rows[buf][w][c];
+#pragma unroll
+        for (int u = 0; u < w; ++u) {
+          tr[w] = fma(-a[u][w], tr[u], tr[w]);
+          tc[w] = fma(-a[u][w], tc[u], tc[w]);
+          tyc[w] = fma(-a[u][w], tyc[u], tyc[w]);
+        }
+        const double l = -tr[w] * ip[w];
+        lS[w][i] = l;
+        lY[w][i] = r > kk + w ? l : 0.0;
+        cS[w][i] = c > kk + w ? tc[w] : 0.0;
+        cY[w][i] = tyc[w];
+      }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        s[i][j] = fma(lB[i], cB[j], fma(lA[i], cA[j], s[i][j]));
-        y[i][j] = fma(lyB[i], yB[j], fma(lyA[i], yA[j], y[i][j]));
+        double sv = s[i][j], yv = y[i][j];
+#pragma unroll
+        for (int w = 0; w < kCw; ++w) {
+          sv = fma(lS[w][i], cS[w][j], sv);
+          yv = fma(lY[w][i], cY[w][j], yv);
+        }
+        s[i][j] = sv;
+        y[i][j] = yv;
       }
-    if (tid == 0) {
-      dinv[kk] = rA;
-      dinv[kk + 1] = rB;
-    }
+#pragma unroll
+    for (int w = 0; w < kCw; ++w)
+      if (tid == w) dinv[kk + w] = rs[w];
   }
   __syncthreads();
   if (bad && tid == 0) atomicExch(flag, 1);
