@@ -48,24 +48,40 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
   out[3] = c3;
 }
 
-// Smallest bin whose inclusive prefix count reaches `want` (1-based rank); returns
-// the bin and the count of elements in earlier bins. Whole block participates.
+// Smallest bin whose inclusive prefix count reaches `want` (1-based rank); returns the bin and the
+// count of elements in earlier bins. Whole block participates: every thread sums 16 bins, wave 0
+// scans the 256 partial sums with shuffles, and one lane walks the at most 4 + 16 remaining entries.
 __device__ void select_bin(const uint32_t* hist, uint32_t* part, uint32_t want, uint32_t* res) {
   const int t = threadIdx.x;
+  constexpr int kPer = kBins / kThreads;  // 16
   uint32_t s = 0;
 #pragma unroll
-  for (int i = 0; i < kBins / kThreads; ++i) s += hist[t * (kBins / kThreads) + i];
+  for (int i = 0; i < kPer; ++i) s += hist[t * kPer + i];
   part[t] = s;
   __syncthreads();
-  if (t == 0) {
-    uint32_t cum = 0;
-    int p = 0;
-    while (p < kThreads - 1 && cum + part[p] < want) cum += part[p++];
-    int b = p * (kBins / kThreads);
-    const int bend = b + (kBins / kThreads) - 1;
-    while (b < bend && cum + hist[b] < want) cum += hist[b++];
-    res[0] = (uint32_t)b;
-    res[1] = cum;
+  if (t < 64) {
+    const uint32_t v0 = part[4 * t], v1 = part[4 * t + 1], v2 = part[4 * t + 2], v3 = part[4 * t + 3];
+    const uint32_t v = v0 + v1 + v2 + v3;
+    uint32_t incl = v;
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t up = __shfl_up(incl, o, 64);
+      if (t >= o) incl += up;
+    }
+    const unsigned long long reach = __ballot(incl >= want);
+    const int lane = reach ? __ffsll((long long)reach) - 1 : 63;  // the total always reaches `want`
+    if (t == lane) {
+      uint32_t cum = incl - v;
+      int p = 4 * t;
+      const uint32_t pv[4] = {v0, v1, v2, v3};
+      int q = 0;
+      while (q < 3 && cum + pv[q] < want) cum += pv[q++];
+      p += q;
+      int b = p * kPer;
+      const int bend = b + kPer - 1;
+      while (b < bend && cum + hist[b] < want) cum += hist[b++];
+      res[0] = (uint32_t)b;
+      res[1] = cum;
+    }
   }
   __syncthreads();
 }
