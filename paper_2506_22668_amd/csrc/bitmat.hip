@@ -181,7 +181,7 @@ constexpr int kTabCols = 512;
 constexpr int kTabWords = kTabCols / 64;
 constexpr int kTabGroups = kTabCols / 8;
 constexpr int kTabThreads = 1024;  // 16 waves hide the LDS and memory latency of the look-ups
-constexpr int kTabRpt = 2;         // rows per thread
+constexpr int kTabRpt = 4;         // rows per thread
 constexpr int kTabRows = kTabThreads * kTabRpt;
 
 __global__ __launch_bounds__(kTabThreads) void bit_spmv_tab_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
@@ -190,6 +190,7 @@ __global__ __launch_bounds__(kTabThreads) void bit_spmv_tab_kernel(const uint64_
   extern __shared__ double tab_smem[];
   double* tab = tab_smem;                       // [64 groups][256]
   double* nib = tab_smem + kTabGroups * 256;    // [64 groups][2 nibbles][16]
+  double* xch = nib + kTabGroups * 32;          // [512] the chunk of x
   const int tid = threadIdx.x;
   const int64_t Wc = (cols + 63) / 64;
   const uint64_t tail = (cols & 63) ? ((1ull << (cols & 63)) - 1ull) : ~0ull;
@@ -201,13 +202,19 @@ __global__ __launch_bounds__(kTabThreads) void bit_spmv_tab_kernel(const uint64_
   const int64_t c_end = c_begin + chunks_per_group < n_chunks ? c_begin + chunks_per_group : n_chunks;
   for (int64_t c = c_begin; c < c_end; ++c) {
     __syncthreads();
+    // the chunk's 512 vector entries first (one coalesced load), then the nibble sums from LDS
+    if (tid < kTabCols) {
+      const int64_t col = c * kTabCols + tid;
+      xch[tid] = col < cols ? x[col] : 0.0;
+    }
+    __syncthreads();
     for (int e = tid; e < kTabGroups * 32; e += kTabThreads) {
       const int g = e >> 5, half = (e >> 4) & 1, m = e & 15;
-      const int64_t col0 = c * kTabCols + g * 8 + half * 4;
+      const double* xp = xch + g * 8 + half * 4;
       double sum = 0.0;
 #pragma unroll
       for (int bbit = 0; bbit < 4; ++bbit)
-        if ((m >> bbit) & 1) sum += (col0 + bbit < cols) ? x[col0 + bbit] : 0.0;
+        if ((m >> bbit) & 1) sum += xp[bbit];
       nib[e] = sum;
     }
     __syncthreads();
@@ -381,7 +388,7 @@ int ds_bit_spmv_tab(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, 
   if (groups < 1) groups = 1;
   const int64_t cpg = (n_chunks + groups - 1) / groups;
   groups = (n_chunks + cpg - 1) / cpg;
-  const size_t lds = (size_t)(kTabGroups * 256 + kTabGroups * 32) * sizeof(double);
+  const size_t lds = (size_t)(kTabGroups * 256 + kTabGroups * 32 + kTabCols) * sizeof(double);
   DS_HIP(ctx, hipFuncSetAttribute((const void*)bit_spmv_tab_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   hipLaunchKernelGGL(bit_spmv_tab_kernel, dim3((unsigned)row_groups, (unsigned)groups), dim3(kTabThreads), lds, ctx->stream, B,
                      rows, cols, stride, row_first, row_step, x, ws, cpg, n_chunks);
