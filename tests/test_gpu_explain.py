@@ -122,3 +122,35 @@ def test_degenerate_graphs_and_error_paths():
     assert e.value.code == DS_ECAPACITY
     ctx.close()
     ctx2.close()
+
+
+def test_directed_players_and_wider_extraction():
+    """Directed players (one CSR entry each) and a computational graph wider than the receptive
+    field: edges joining two nodes beyond L hops are exact null players."""
+    from paper_2506_22668_amd import Options
+    from oracle import compgraph
+    say("explain directed / hops > L")
+    w = make_workload("c1")
+    ctx = make_context(w)
+    # directed, 1-hop graph of the target: 8 players, enumerated
+    phi, es, ed, rep, rc = ctx.explain(0, 1 << 8, 3, Options(hops=1, directed=1))
+    ref = oexplain.explain(w.row_ptr, w.col, w.features, w.weights, 0, 1 << 8, 3, hops=1, undirected=False)
+    assert rep.num_players == 8 and rep.enumerated == 1
+    assert np.array_equal(es.cpu().numpy(), ref["cg"]["edge_src"]) and np.array_equal(ed.cpu().numpy(), ref["cg"]["edge_dst"])
+    assert np.abs(phi.cpu().numpy() - ref["phi"]).max() <= 1e-4 * np.abs(ref["phi"]).max()
+    ctx.close()
+    # 2-layer model on a graph extracted to 3 hops: edge (3,4) joins two nodes at distance 3
+    rp, ci = csr_from_undirected_edges(5, [0, 1, 2, 2, 3], [1, 2, 3, 4, 4])
+    from synth.workloads import Workload
+    rng = np.random.default_rng(2)
+    W = [rng.standard_normal((6, 5)).astype(np.float32), rng.standard_normal((5, 3)).astype(np.float32)]
+    wl = Workload("null", 5, rp, ci, rng.standard_normal((5, 6), dtype=np.float32), (6, 5, 3), W, [0], 32, 1, "gram_chol")
+    ctx = make_context(wl)
+    phi, es, ed, rep, rc = ctx.explain(0, 32, 1, Options(hops=3))
+    ref = oexplain.explain(rp, ci, wl.features, W, 0, 32, 1, hops=3)
+    pairs = list(zip(es.cpu().numpy().tolist(), ed.cpu().numpy().tolist()))
+    got = phi.cpu().numpy()
+    assert abs(got[pairs.index((3, 4))]) <= 1e-6
+    assert abs(got[pairs.index((2, 3))]) > 1e-4
+    assert np.abs(got - ref["phi"]).max() <= 1e-4 * np.abs(ref["phi"]).max() + 1e-7
+    ctx.close()
