@@ -444,46 +444,49 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_
   }
 }
 
-// L^T psi = y (y = row n of M after the factorisation), block by block from the end, using
-// the stored inverses of the diagonal blocks; single workgroup. psi -> out, then phi.
-constexpr int kSolveThreads = 1024;
-__global__ __launch_bounds__(kSolveThreads) void chol_back_solve_kernel(const double* M, int64_t ld, int64_t n,
-                                                                        const double* linv_all, double* yv,
-                                                                        const float* y01, float* phi) {
-  __shared__ double Xs[NB][NB + 1];
-  __shared__ double yb[NB];
+// L^T psi = y (y = row n of M after the factorisation), block by block from the end, using the stored
+// inverses of the diagonal blocks. One launch per block: every workgroup recomputes the 64 unknowns of
+// the block, psi_c = sum_{r >= c} Linv[r][c] y_r (cheap; workgroup 0 stores them), and removes their
+// contribution from its own slice of the earlier entries, y_j -= sum_r L[j0+r][j] psi_r.
+__global__ __launch_bounds__(kThreads) void chol_back_step_kernel(const double* M, int64_t ld, int64_t j0, int nb,
+                                                                  const double* linv, double* yv, double* psi) {
   __shared__ double xs[NB];
+  __shared__ double part[kThreads / NB][NB];
   const int tid = threadIdx.x;
-  for (int64_t j = tid; j < n; j += kSolveThreads) yv[j] = M[n * ld + j];
-  __syncthreads();
-  const int64_t nblk = (n + NB - 1) / NB;
-  for (int64_t bk = nblk - 1; bk >= 0; --bk) {
-    const int64_t j0 = bk * NB;
-    const int nb = (int)(n - j0 < NB ? n - j0 : NB);
-    const double* linv = linv_all + (size_t)bk * NB * NB;
-    for (int idx = tid; idx < NB * NB; idx += kSolveThreads) Xs[idx >> 6][idx & 63] = linv[idx];
-    if (tid < NB) yb[tid] = tid < nb ? yv[j0 + tid] : 0.0;
-    __syncthreads();
-    // psi_c = sum_{r >= c} Linv[r][c] y_r : 16 threads per c
-    {
-      const int c = tid >> 4, part = tid & 15;
-      double s = 0.0;
-      for (int r = c + part; r < NB; r += 16) s += Xs[r][c] * yb[r];
-      for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-      if (part == 0) xs[c] = s;
-    }
-    __syncthreads();
-    if (tid < nb) yv[j0 + tid] = xs[tid];
-    for (int64_t j = tid; j < j0; j += kSolveThreads) {
-      double s = 0.0;
-#pragma unroll 16
-      for (int r = 0; r < nb; ++r) s += M[(j0 + r) * ld + j] * xs[r];
-      yv[j] -= s;
-    }
-    __syncthreads();
+  {
+    const int c = tid & (NB - 1), q = tid / NB;  // four partial sums per unknown, added in a fixed order
+    double s = 0.0;
+    for (int r = c + q; r < nb; r += kThreads / NB) s += linv[r * NB + c] * yv[j0 + r];
+    part[q][c] = s;
   }
+  __syncthreads();
+  if (tid < NB) {
+    double s = 0.0;
+#pragma unroll
+    for (int q = 0; q < kThreads / NB; ++q) s += part[q][tid];
+    xs[tid] = s;
+    if (blockIdx.x == 0 && tid < nb) psi[j0 + tid] = s;
+  }
+  __syncthreads();
+  const int64_t j = (int64_t)blockIdx.x * kThreads + tid;
+  if (j < j0) {
+    double s = 0.0;
+#pragma unroll 16
+    for (int r = 0; r < nb; ++r) s += M[(j0 + r) * ld + j] * xs[r];
+    yv[j] -= s;
+  }
+}
+
+__global__ void copy_row_kernel(const double* M, int64_t ld, int64_t n, double* yv) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < n) yv[j] = M[n * ld + j];
+}
+
+__global__ void finish_phi_kernel(const double* psi, const float* y01, int64_t n, float* phi) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
   const double delta = (double)y01[1] - (double)y01[0];
-  for (int64_t j = tid; j < n; j += kSolveThreads) phi[j] = (float)(yv[j] + delta / (double)n);
+  phi[j] = (float)(psi[j] + delta / (double)n);
 }
 
 inline unsigned nblocks(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
@@ -597,7 +600,15 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
     }
   }
   DS_TRY(ds_kernel_mark(ctx, 2, 1));
-  hipLaunchKernelGGL(chol_back_solve_kernel, dim3(1), dim3(kSolveThreads), 0, st, M, ld, n, linv, gs->yv, y, phi);
+  hipLaunchKernelGGL(copy_row_kernel, dim3(nblocks(n, 256)), dim3(256), 0, st, M, ld, n, gs->yv);
+  for (int64_t bk = gs->nblk - 1; bk >= 0; --bk) {
+    const int64_t j0 = bk * NB;
+    const int nb = (int)(n - j0 < NB ? n - j0 : NB);
+    const unsigned wgs = j0 > 0 ? nblocks(j0, kThreads) : 1;
+    hipLaunchKernelGGL(chol_back_step_kernel, dim3(wgs), dim3(kThreads), 0, st, M, ld, j0, nb,
+                       linv + (size_t)bk * NB * NB, gs->yv, gs->c);  // c is free again: it receives psi
+  }
+  hipLaunchKernelGGL(finish_phi_kernel, dim3(nblocks(n, 256)), dim3(256), 0, st, gs->c, y, n, phi);
   DS_HIP(ctx, hipGetLastError());
   DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, gs->flag, sizeof(int), hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipStreamSynchronize(st));
