@@ -137,6 +137,28 @@ int ds_set_features(ds_ctx* ctx, const void* X, int32_t d0, int32_t dtype);
 int ds_set_gcn(ds_ctx* ctx, int32_t num_layers, const int32_t* dims, const void* const* W,
                const void* const* bias, int32_t transform_dtype);
 
+/* GAT weights (paper, "GNN Models" and the GAT scaling experiment: a two-layer
+ * graph attention network with 8 heads; layer rule of Velickovic et al., which
+ * the paper cites). Replaces the model set by ds_set_gcn (and vice versa).
+ * Layer l has heads[l-1] heads of width head_dims[l]; with Z = H^(l-1) W_l and
+ * z_i^h the h-th slice of row i, on the sub-graph of coalition S
+ *   e_ij^h = LeakyReLU(att_dst_l^h . z_i^h + att_src_l^h . z_j^h),  j in N_S(i) + {i},
+ *   alpha_ij^h = softmax_j(e_ij^h),   out_i^h = sum_j alpha_ij^h z_j^h;
+ * a hidden layer concatenates its heads, adds b_l and applies ELU, the last
+ * layer averages its heads and adds b_L. The self term is always present.
+ * head_dims [host]: int32[L+1] = d0, then the per-head width of every layer
+ * (the last is the number of classes). heads [host]: int32[L].
+ * W [host]: L device pointers, W_l row-major fp32 [in_l x heads_l*head_dims_l]
+ * with in_1 = d0 and in_l = heads_(l-1)*head_dims_(l-1). att_src, att_dst
+ * [host]: L device pointers each, fp32 [heads_l x head_dims_l] (att_dst
+ * multiplies the receiving node, att_src the neighbour). bias [host]: NULL, or
+ * L device pointers (entries may be NULL) to fp32[heads_l*head_dims_l] (hidden)
+ * or fp32[head_dims_L] (last). 1 <= L <= 7; transform widths <= 4096, classes
+ * <= 1024. fp32 arithmetic throughout. */
+int ds_set_gat(ds_ctx* ctx, int32_t num_layers, const int32_t* head_dims, const int32_t* heads,
+               const void* const* W, const void* const* att_src, const void* const* att_dst,
+               const void* const* bias, float negative_slope);
+
 /* ---- one-shot explanation --------------------------------------------------- */
 
 /* Explain the prediction for `target`: extract G_c, draw n_samples coalitions

@@ -14,7 +14,7 @@ DS_SCORE_PROB, DS_SCORE_LOGIT = 0, 1
 DS_SOLVER_AUTO, DS_SOLVER_GRAM_CHOL, DS_SOLVER_CGLS = 0, 1, 2
 
 EXPORTED_SYMBOLS = [
-    "ds_create", "ds_destroy", "ds_last_error", "ds_set_graph", "ds_set_features", "ds_set_gcn",
+    "ds_create", "ds_destroy", "ds_last_error", "ds_set_graph", "ds_set_features", "ds_set_gcn", "ds_set_gat",
     "ds_explain", "ds_explain_batch", "ds_extract", "ds_cgraph_get_info", "ds_cgraph_edges",
     "ds_cgraph_nodes", "ds_cgraph_first_transform", "ds_cgraph_free", "ds_sample_plan", "ds_sample",
     "ds_plan_tables", "ds_sample_range", "ds_eval", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
@@ -79,6 +79,8 @@ def load_library():
         "ds_set_graph": [p, i64, p, p],
         "ds_set_features": [p, p, i32, i32],
         "ds_set_gcn": [p, i32, C.POINTER(i32), C.POINTER(p), C.POINTER(p), i32],
+        "ds_set_gat": [p, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(p), C.POINTER(p), C.POINTER(p), C.POINTER(p),
+                       C.c_float],
         "ds_explain": [p, i64, i64, u64, C.POINTER(Options), p, C.POINTER(i64), p, p, C.POINTER(Report)],
         "ds_explain_batch": [p, C.POINTER(i64), i32, i64, u64, C.POINTER(Options), p, C.POINTER(i64),
                              C.POINTER(i64), p, p, i64, C.POINTER(Report)],
@@ -207,6 +209,27 @@ class Context:
         self._check(self.lib.ds_set_gcn(self.h, L, dims_c, W_c, B_c, transform_dtype))
         self._keep["model"] = (Ws, Bs)
         self.dims = dims
+        self.first_width = dims[1]
+
+    def set_gat(self, weights, att_src, att_dst, heads, biases=None, negative_slope=0.2):
+        """weights[l]: [in_l, heads_l * width_l]; att_src[l], att_dst[l]: [heads_l, width_l]."""
+        t = self.torch
+        dev = lambda a: t.as_tensor(a, dtype=t.float32).to(self.device).contiguous()
+        Ws, As, Ad = [dev(w) for w in weights], [dev(a) for a in att_src], [dev(a) for a in att_dst]
+        L = len(Ws)
+        heads = [int(h) for h in heads]
+        head_dims = [Ws[0].shape[0]] + [Ws[l].shape[1] // heads[l] for l in range(L)]
+        Bs = None
+        if biases is not None:
+            Bs = [None if b is None else dev(b) for b in biases]
+        self._sync_inputs()
+        arr = lambda ts: (C.c_void_p * L)(*[(x.data_ptr() if x is not None else 0) for x in ts])
+        self._check(self.lib.ds_set_gat(self.h, L, (C.c_int32 * (L + 1))(*head_dims), (C.c_int32 * L)(*heads),
+                                        arr(Ws), arr(As), arr(Ad), None if Bs is None else arr(Bs),
+                                        C.c_float(negative_slope)))
+        self._keep["model"] = (Ws, As, Ad, Bs)
+        self.dims = [head_dims[0]] + [heads[l] * head_dims[l + 1] for l in range(L - 1)] + [head_dims[L]]
+        self.first_width = heads[0] * head_dims[1]
 
     # -- one-shot --------------------------------------------------------------
     def explain(self, target, n_samples, seed, options=None, capacity=None, want_edges=True,
@@ -281,7 +304,7 @@ class Context:
     def cgraph_first_transform(self, cg):
         t = self.torch
         V = self.cgraph_info(cg).num_nodes
-        out = t.empty((V, self.dims[1]), dtype=t.float32, device=self.device)
+        out = t.empty((V, self.first_width), dtype=t.float32, device=self.device)
         self._check(self.lib.ds_cgraph_first_transform(self.h, cg, _ptr(out)))
         return out
 

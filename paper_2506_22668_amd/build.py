@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdistshap_hip.so")
-SOURCES = ["api.hip", "sampler.hip", "extract.hip", "eval.hip", "bitmat.hip",
+SOURCES = ["api.hip", "sampler.hip", "extract.hip", "eval.hip", "gat_eval.hip", "bitmat.hip",
            "gram_chol.hip", "cgls.hip", "fidelity.hip", "plan.cpp"]
 
 

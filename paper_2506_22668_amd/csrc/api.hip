@@ -190,6 +190,40 @@ int ds_set_gcn(ds_ctx* ctx, int32_t num_layers, const int32_t* dims, const void*
     ctx->bias[l] = bias ? (const float*)bias[l] : nullptr;
   }
   ctx->transform_dtype = transform_dtype;
+  ctx->model_kind = DS_MODEL_GCN;
+  ctx->model_version += 1;
+  return DS_OK;
+}
+
+int ds_set_gat(ds_ctx* ctx, int32_t num_layers, const int32_t* head_dims, const int32_t* heads, const void* const* W,
+               const void* const* att_src, const void* const* att_dst, const void* const* bias, float negative_slope) {
+  if (!ctx) return DS_EINVAL;
+  if (num_layers < 1 || num_layers > DS_MAX_LAYERS || !head_dims || !heads || !W || !att_src || !att_dst)
+    return ds_fail(ctx, DS_EINVAL, "the GAT needs 1..%d layers with weights and attention vectors", DS_MAX_LAYERS);
+  if (head_dims[0] < 1 || head_dims[0] > 4096) return ds_fail(ctx, DS_EINVAL, "input width %d out of range [1, 4096]", head_dims[0]);
+  for (int l = 0; l < num_layers; ++l) {
+    if (heads[l] < 1 || heads[l] > 64) return ds_fail(ctx, DS_EINVAL, "layer %d: %d heads out of range [1, 64]", l + 1, heads[l]);
+    if (head_dims[l + 1] < 1 || (int64_t)heads[l] * head_dims[l + 1] > 4096)
+      return ds_fail(ctx, DS_EINVAL, "layer %d: transform width %lld out of range [1, 4096]", l + 1, (long long)heads[l] * head_dims[l + 1]);
+    if (!W[l] || !att_src[l] || !att_dst[l]) return ds_fail(ctx, DS_EINVAL, "layer %d: null weight or attention pointer", l + 1);
+  }
+  if (head_dims[num_layers] > 1024) return ds_fail(ctx, DS_EINVAL, "at most 1024 classes");
+  if (!(negative_slope >= 0.f && negative_slope <= 1.f)) return ds_fail(ctx, DS_EINVAL, "negative_slope must lie in [0, 1]");
+  ctx->L = num_layers;
+  ctx->dims[0] = head_dims[0];
+  for (int l = 0; l < num_layers; ++l) {
+    ctx->gat.heads[l] = heads[l];
+    ctx->gat.fh[l] = head_dims[l + 1];
+    ctx->gat.zw[l] = heads[l] * head_dims[l + 1];
+    ctx->dims[l + 1] = l + 1 < num_layers ? ctx->gat.zw[l] : head_dims[l + 1];
+    ctx->W[l] = (const float*)W[l];
+    ctx->gat.att_src[l] = (const float*)att_src[l];
+    ctx->gat.att_dst[l] = (const float*)att_dst[l];
+    ctx->bias[l] = bias ? (const float*)bias[l] : nullptr;
+  }
+  ctx->gat.slope = negative_slope;
+  ctx->transform_dtype = DS_F32;
+  ctx->model_kind = DS_MODEL_GAT;
   ctx->model_version += 1;
   return DS_OK;
 }
@@ -256,7 +290,7 @@ int ds_cgraph_first_transform(ds_ctx* ctx, ds_cgraph* cg, float* out) {
   int rc = ds_prepare_model(ctx, cg);
   ds_arena_reset(ctx);
   DS_TRY(rc);
-  DS_HIP(ctx, hipMemcpyAsync(out, cg->P, (size_t)cg->info.num_nodes * ctx->dims[1] * 4, hipMemcpyDeviceToDevice, ctx->stream));
+  DS_HIP(ctx, hipMemcpyAsync(out, cg->P, (size_t)cg->info.num_nodes * ds_first_width(ctx) * 4, hipMemcpyDeviceToDevice, ctx->stream));
   DS_HIP(ctx, hipStreamSynchronize(ctx->stream));
   return DS_OK;
 }
@@ -407,7 +441,7 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   ds_report rep;
   memset(&rep, 0, sizeof(rep));
   hipStream_t st = ctx->stream;
-  if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "ds_set_gcn has not been called");
+  if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "no model is set (ds_set_gcn / ds_set_gat)");
   for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
   DS_HIP(ctx, hipEventRecord(ctx->ev[0], st));
   ds_cgraph* cg = nullptr;
@@ -566,6 +600,8 @@ static int ensure_workers(ds_ctx* ctx, int count) {
     for (int l = 0; l < DS_MAX_LAYERS; ++l) { w->W[l] = ctx->W[l]; w->bias[l] = ctx->bias[l]; }
     w->transform_dtype = ctx->transform_dtype;
     w->model_version = ctx->model_version;
+    w->model_kind = ctx->model_kind;
+    w->gat = ctx->gat;
   }
   return DS_OK;
 }

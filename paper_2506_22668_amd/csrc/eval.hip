@@ -824,7 +824,32 @@ BatchedLayout make_batched_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_
 }
 }  // namespace
 
+int ds_launch_first_transform(ds_ctx* ctx, const float* A, const float* B, float* C, int M, int K, int Nn, int bf16) {
+  const int tiles = ((M + 31) / 32) * ((Nn + 31) / 32);
+  const int blocks = (tiles + kWaves - 1) / kWaves;
+  if (bf16)
+    hipLaunchKernelGGL((first_transform_kernel<true>), dim3(blocks), dim3(kThreads), 0, ctx->stream, A, B, C, M, K, Nn);
+  else
+    hipLaunchKernelGGL((first_transform_kernel<false>), dim3(blocks), dim3(kThreads), 0, ctx->stream, A, B, C, M, K, Nn);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
+
+int ds_launch_full_mask(ds_ctx* ctx, uint64_t* z, int64_t W, int64_t n) {
+  if (W <= 0) return DS_OK;
+  hipLaunchKernelGGL(fill_full_mask, dim3((unsigned)((W + 255) / 256)), dim3(256), 0, ctx->stream, z, W, (int)n);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
+
+int ds_launch_argmax(ds_ctx* ctx, const float* logits, int C, int32_t* out) {
+  hipLaunchKernelGGL(argmax_kernel, dim3(1), dim3(64), 0, ctx->stream, logits, C, out);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
+
 size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
+  if (ctx->model_kind == DS_MODEL_GAT) return ds_gat_eval_arena_bytes(ctx, cg, k);
   const EvalLayout lay = make_layout(ctx, cg);
   const int grid = grid_for(ctx, lay, k > 1 ? k : 1);
   const size_t W = (cg->info.num_players + 63) / 64;
@@ -836,18 +861,13 @@ size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
 // Shared first transform and the class predicted on the full computational graph;
 // cached in the graph until the model changes. Uses the arena (caller reserved it).
 int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg) {
-  if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "ds_set_gcn has not been called");
+  if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "no model is set (ds_set_gcn / ds_set_gat)");
+  if (ctx->model_kind == DS_MODEL_GAT) return ds_gat_prepare_model(ctx, cg);
   if (cg->d0 != ctx->dims[0]) return ds_fail(ctx, DS_EINVAL, "feature width %d does not match the model's input width %d", cg->d0, ctx->dims[0]);
   if (cg->model_version == ctx->model_version) return DS_OK;
   if (cg->d1 != ctx->dims[1]) return ds_fail(ctx, DS_EINVAL, "the computational graph was extracted for a model with first hidden width %d (now %d): extract again", cg->d1, ctx->dims[1]);
-  const int M = (int)cg->info.num_nodes, K = ctx->dims[0], Nn = ctx->dims[1];
-  const int tiles = ((M + 31) / 32) * ((Nn + 31) / 32);
-  const int blocks = (tiles + kWaves - 1) / kWaves;
-  if (ctx->transform_dtype == DS_BF16_IN_F32_ACC)
-    hipLaunchKernelGGL((first_transform_kernel<true>), dim3(blocks), dim3(kThreads), 0, ctx->stream, cg->Xc, ctx->W[0], cg->P, M, K, Nn);
-  else
-    hipLaunchKernelGGL((first_transform_kernel<false>), dim3(blocks), dim3(kThreads), 0, ctx->stream, cg->Xc, ctx->W[0], cg->P, M, K, Nn);
-  DS_HIP(ctx, hipGetLastError());
+  DS_TRY(ds_launch_first_transform(ctx, cg->Xc, ctx->W[0], cg->P, (int)cg->info.num_nodes, ctx->dims[0], ctx->dims[1],
+                                   ctx->transform_dtype == DS_BF16_IN_F32_ACC));
   // predicted class: evaluate the full coalition once and take the first maximum
   const int64_t n = cg->info.num_players;
   const int64_t W = (n + 63) / 64;
@@ -878,6 +898,7 @@ int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg) {
 
 int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y, int batch_rows) {
   (void)batch_rows;
+  if (ctx->model_kind == DS_MODEL_GAT) return ds_gat_eval_impl(ctx, cg, Z, k, score, y);
   DS_TRY(ds_prepare_model(ctx, cg));
   if (k <= 0) return DS_OK;
   const EvalLayout lay = make_layout(ctx, cg);

@@ -419,13 +419,15 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
   ds_cgraph* cg = new ds_cgraph();
   memset(cg, 0, sizeof(*cg));
   cg->owner = ctx;
-  const int d0 = ctx->d0, d1 = ctx->L > 0 ? ctx->dims[1] : 0;
+  const int d0 = ctx->d0, d1 = ds_first_width(ctx);
+  const int att_heads = ctx->model_kind == DS_MODEL_GAT && ctx->L > 0 ? ctx->gat.heads[0] : 0;
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off += ds_align(bytes); return o; };
   const size_t o_rp = carve((V + 1) * 4), o_col = carve(nnz_c * 4 + 4), o_eid = carve(nnz_c * 4 + 4);
   const size_t o_pl = carve(n * 8 + 8), o_gid = carve(V * 8), o_hop = carve(V * 4);
   const size_t o_x = carve((size_t)V * d0 * 4), o_p = carve((size_t)V * (d1 > 0 ? d1 : 1) * 4);
   const size_t o_pred = carve(256);
+  const size_t o_att = carve((size_t)V * att_heads * 8 + 8);
   if (ctx->cg_spare && ctx->cg_spare_bytes >= off) {
     cg->block = ctx->cg_spare;
     cg->block_bytes = ctx->cg_spare_bytes;
@@ -449,9 +451,11 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
   cg->Xc = (float*)(base + o_x);
   cg->P = (float*)(base + o_p);
   cg->d_pred = (int32_t*)(base + o_pred);
+  cg->att = (float*)(base + o_att);
   cg->pred_class = -1;
   cg->d0 = d0;
   cg->d1 = d1;
+  cg->att_heads = att_heads;
   cg->info.num_players = n;
   cg->info.num_nodes = V;
   cg->info.num_entries = nnz_c;

@@ -28,10 +28,26 @@ struct ds_cgraph {
   int32_t* hop;           // [V]
   float* Xc;              // [V x d0] gathered feature rows
   float* P;               // [V x d1] shared first transform Xc * W_1 (valid if model_version matches)
+  float* att;             // GAT only: layer-1 attention scalars, neighbour part [V x heads_1] then receiver part
   int32_t* d_pred;        // device: class predicted on the full graph (valid with model_version)
   uint64_t model_version; // model the cached P / d_pred belong to (0 = none)
   int32_t pred_class;     // host copy, -1 until fetched
   int32_t d0, d1;
+  int32_t att_heads;       // heads the `att` array was sized for (0: extracted for a GCN)
+};
+
+#define DS_MODEL_GCN 0
+#define DS_MODEL_GAT 1
+
+// attention parameters of a GAT (model_kind == DS_MODEL_GAT); dims[] of the context then holds the width
+// of every layer's OUTPUT (heads * head width for a hidden layer, head width for the last one)
+struct ds_gat_params {
+  int32_t heads[DS_MAX_LAYERS];
+  int32_t fh[DS_MAX_LAYERS];  // per-head width
+  int32_t zw[DS_MAX_LAYERS];  // heads * fh: width of the layer's dense transform
+  const float* att_src[DS_MAX_LAYERS];
+  const float* att_dst[DS_MAX_LAYERS];
+  float slope;
 };
 
 struct ds_ctx {
@@ -51,6 +67,8 @@ struct ds_ctx {
   const float* bias[DS_MAX_LAYERS];
   int32_t transform_dtype;
   uint64_t model_version;
+  int32_t model_kind;
+  ds_gat_params gat;
   // bump arena for temporaries (grown only while nothing is live)
   char* arena;
   size_t arena_bytes, arena_used;
@@ -130,6 +148,19 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
                  int batch_rows);
 int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg);  // shared first transform + predicted class
 size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
+// width of the shared first transform P = X_c W_1
+static inline int32_t ds_first_width(const ds_ctx* ctx) {
+  if (ctx->L < 1) return 0;
+  return ctx->model_kind == DS_MODEL_GAT ? ctx->gat.zw[0] : ctx->dims[1];
+}
+// small launchers shared by the two model families (defined next to the GCN kernels)
+int ds_launch_first_transform(ds_ctx* ctx, const float* A, const float* B, float* C, int M, int K, int Nn, int bf16);
+int ds_launch_full_mask(ds_ctx* ctx, uint64_t* z, int64_t W, int64_t n);
+int ds_launch_argmax(ds_ctx* ctx, const float* logits, int C, int32_t* out);
+// GAT counterparts of the three functions above (same contracts)
+int ds_gat_prepare_model(ds_ctx* ctx, ds_cgraph* cg);
+int ds_gat_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y);
+size_t ds_gat_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
 
 // the direct solver in two parts: the first needs only the masks and weights
 struct ds_gram_state {

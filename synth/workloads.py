@@ -29,6 +29,7 @@ class Workload:
     transform_dtype: str = "f32"  # "f32" | "bf16"
     tol: float = 1e-6
     max_iter: int = 0            # CGLS iteration cap (0 = library default)
+    gat: dict = None             # attention model (W, a_src, a_dst, heads, slope) instead of a GCN
     info: dict = field(default_factory=dict)
 
     @property
@@ -43,6 +44,19 @@ def glorot_uniform(rng, fan_in, fan_out):
 
 def _model(rng, dims):
     return [glorot_uniform(rng, dims[i], dims[i + 1]) for i in range(len(dims) - 1)]
+
+
+def _gat_model(rng, d0, heads, widths, slope=0.2):
+    """Glorot-uniform GAT parameters: layer l maps to heads[l] heads of width widths[l]; hidden layers
+    concatenate their heads, the last one averages them."""
+    W, a_src, a_dst = [], [], []
+    din = d0
+    for h, f in zip(heads, widths):
+        W.append(glorot_uniform(rng, din, h * f))
+        a_src.append(glorot_uniform(rng, h, f))
+        a_dst.append(glorot_uniform(rng, h, f))
+        din = h * f
+    return dict(W=W, a_src=a_src, a_dst=a_dst, bias=None, heads=list(heads), widths=list(widths), slope=slope)
 
 
 def _walk_estimate(row_ptr, col, hops):
@@ -163,7 +177,27 @@ WORKLOADS = {
                                        (64, 32, 32, 8), 3_000, "gram_chol", count=4,
                                        transform_dtype="bf16", examine=300,
                                        edge_factor=3),
+    # second model family: two-layer GAT, 8 heads (hidden 8 x 8), on the 2-hop computational graph
+    "gat_c2": lambda: _gat_workload("gat_ba10k_1k_edges", 22, lambda r: graphs.barabasi_albert(10_000, 5, r), 1000,
+                                    128, (8, 1), (8, 10), 20_000, "gram_chol", min_degree=5),
+    "gat_small": lambda: _gat_workload("gat_small_ba600", 23, lambda r: graphs.barabasi_albert(600, 3, r), 200,
+                                       32, (4, 2), (8, 6), 3_000, "gram_chol", examine=200, min_degree=3),
+    "gat_rmat": lambda: _gat_workload("gat_rmat16_50k_edges", 24, lambda r: graphs.rmat(16, 16, r), 50_000,
+                                      128, (8, 1), (8, 16), 100_000, "cgls", examine=400),
 }
+
+
+def _gat_workload(name, cfg_id, graph, want, d0, heads, widths, n_samples, solver, examine=300, min_degree=1):
+    """Two-layer GAT (the paper's second model family: 8 heads) on the 2-hop computational graph."""
+    rng = _rng(cfg_id)
+    N, rp, ci = graph(rng)
+    (_, v, m, sizes), = pick_targets(rp, ci, len(heads), want, examine=examine, min_degree=min_degree)
+    X = rng.standard_normal((N, d0), dtype=np.float32)
+    model = _gat_model(rng, d0, heads, widths)
+    dims = (d0,) + tuple(h * f for h, f in zip(heads[:-1], widths[:-1])) + (widths[-1],)
+    return Workload(name=name, num_nodes=N, row_ptr=rp, col=ci, features=X, dims=dims, weights=model["W"],
+                    targets=[v], n_samples=n_samples, seed=22668_000 + cfg_id, solver=solver, gat=model,
+                    info={"players": m, "balls": sizes})
 
 
 def _with(w, **kw):
