@@ -49,15 +49,43 @@ def inference_flops_per_coalition(ctx, cg, dims):
 
 
 
+def gat_flops_per_coalition(ctx, cg, model):
+    """Algorithmic flops of one masked GAT evaluation of the target: per active entry of a needed row (half of
+    them on average) one attention logit and one weighted accumulate per feature column (4 flop), plus the dense
+    transform of layers >= 2 on the rows they read."""
+    import numpy as np
+    info = ctx.cgraph_info(cg)
+    heads, widths = model["heads"], model["widths"]
+    L = len(heads)
+    gid, hop = ctx.cgraph_nodes(cg)
+    es, ed = ctx.cgraph_edges(cg)
+    hop_of = dict(zip(gid.cpu().numpy().tolist(), hop.cpu().numpy().tolist()))
+    hs = np.array([hop_of[int(x)] for x in es.cpu().numpy()])
+    hd = np.array([hop_of[int(x)] for x in ed.cpu().numpy()])
+    flops, din = 0.0, None
+    for l in range(1, L + 1):
+        radius = min(L - l, info.hops)
+        entries = int((hs <= radius).sum() + (hd <= radius).sum())
+        zw = heads[l - 1] * widths[l - 1]
+        flops += 0.5 * entries * zw * 4
+        if l >= 2:
+            flops += 2.0 * info.ball[min(L - l + 1, info.hops)] * din * zw
+        din = zw
+    return flops
+
+
 def cpu_baseline(w, budget_s=20.0):
     """The oracle's masked inference, as it stands, on a bounded prefix of the same
     coalitions (rows of the same mask matrix), timed on this machine's host cores."""
     import numpy as np
-    from oracle import compgraph, gcn, sampling
+    from oracle import compgraph, gat, gcn, sampling
     target = w.targets[0]
     cg = compgraph.extract(w.row_ptr, w.col, target, w.num_layers)
     n = cg["num_players"]
-    f = gcn.ValueFunction(cg, w.features, w.weights, bf16=(w.transform_dtype == "bf16"))
+    if w.gat is not None:
+        f = gat.ValueFunction(cg, w.features, w.gat)
+    else:
+        f = gcn.ValueFunction(cg, w.features, w.weights, bf16=(w.transform_dtype == "bf16"))
     probe = 64
     Z, wt, sz = sampling.sample(n, w.n_samples, w.seed, target & 0xFFFFFFFF, pair_range=(0, probe // 2))
     bits = sampling.unpack_rows(Z, n)
@@ -121,13 +149,17 @@ def main():
     ctx = Context("cuda:0")
     ctx.set_graph(w.row_ptr, w.col)
     ctx.set_features(w.features)
-    ctx.set_gcn(w.weights, transform_dtype=DS_BF16_IN_F32_ACC if w.transform_dtype == "bf16" else DS_F32)
+    if w.gat is not None:
+        ctx.set_gat(w.gat["W"], w.gat["a_src"], w.gat["a_dst"], w.gat["heads"], negative_slope=w.gat["slope"])
+    else:
+        ctx.set_gcn(w.weights, transform_dtype=DS_BF16_IN_F32_ACC if w.transform_dtype == "bf16" else DS_F32)
     opts = Options(solver=DS_SOLVER_CGLS if w.solver == "cgls" else DS_SOLVER_GRAM_CHOL, tol=w.tol)
     targets = w.targets
     cg = ctx.extract(targets[0], opts)
     info = ctx.cgraph_info(cg)
     capacity = max(ctx.cgraph_info(c).num_players for c in [cg])
-    eval_flops = inference_flops_per_coalition(ctx, cg, list(w.dims))
+    eval_flops = (gat_flops_per_coalition(ctx, cg, w.gat) if w.gat is not None
+                  else inference_flops_per_coalition(ctx, cg, list(w.dims)))
     ctx.cgraph_free(cg)
     if len(targets) > 1:
         caps = []
@@ -164,8 +196,8 @@ def main():
     kernels = {
         # small graphs (one coalition per lane, everything but the mask on chip): arithmetic-bound;
         # large ones stream the mask matrix: compulsory HBM bytes per coalition = its mask row in, one float out
-        "masked_gcn_eval": ({"ms": mean("ms_k_eval"), "bound": "alu", "alg": rows * eval_flops / 1e12,
-                             "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s"} if n <= 2048 else
+        ("masked_gat_eval" if w.gat is not None else "masked_gcn_eval"): ({"ms": mean("ms_k_eval"), "bound": "alu", "alg": rows * eval_flops / 1e12,
+                             "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s"} if (n <= 2048 or w.gat is not None) else
                             {"ms": mean("ms_k_eval"), "bound": "hbm", "alg": rows * (W64 * 8 + 4) / 1e9,
                              "peak": HBM_PEAK_GBS, "unit": "GB/s"}),
         "gram_popcount": {"ms": mean("ms_k_gram"), "bound": "alu",
@@ -186,7 +218,8 @@ def main():
     dom = kernels[dom_name]
     traffic = read_traffic(dom_name, w.name)
     out = {
-        "metric": "masked-GCN coalition evals/sec; end-to-end seconds per explained node",
+        "metric": ("masked-GAT" if w.gat is not None else "masked-GCN") +
+                  " coalition evals/sec; end-to-end seconds per explained node",
         "value": k / elapsed,
         "unit": "coalition evals/s (end to end: extraction + sampling + inference + solve)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -194,7 +227,9 @@ def main():
         "dtype": "f32" if w.transform_dtype != "bf16" else "bf16 transforms, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": w.name, "graph_nodes": w.num_nodes, "players": int(n), "cg_nodes": int(V),
-                   "coalitions": int(rows), "gcn_dims": list(w.dims), "solver": w.solver,
+                   "coalitions": int(rows), "solver": w.solver,
+                   **({"gat_heads": w.gat["heads"], "gat_head_widths": w.gat["widths"]} if w.gat is not None
+                      else {"gcn_dims": list(w.dims)}),
                    "targets_cycled": len(targets)},
         "sec_per_explained_node": elapsed / args.steps,
         "inference_stage_evals_per_sec": rows / (mean("ms_eval") / 1e3) if mean("ms_eval") > 0 else None,

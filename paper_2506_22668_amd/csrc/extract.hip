@@ -341,6 +341,14 @@ int ds_validate_csr(ds_ctx* ctx) {
   return DS_OK;
 }
 
+namespace {
+struct BallSizes { int32_t v[8]; };
+// out[h] = row_ptr[ball[h]]: the CSR entries of the rows within h hops
+__global__ void ball_entries_kernel(const int32_t* row_ptr, BallSizes b, int64_t* out) {
+  if (threadIdx.x < 8) out[threadIdx.x] = row_ptr[b.v[threadIdx.x]];
+}
+}  // namespace
+
 int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgraph** out_cg) {
   if (!ctx->row_ptr) return ds_fail(ctx, DS_EINVAL, "ds_set_graph has not been called");
   if (!ctx->X) return ds_fail(ctx, DS_EINVAL, "ds_set_features has not been called");
@@ -408,6 +416,13 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
   DS_TRY(ds_scan_exclusive_i32(ctx, rowptr_tmp, rowptr_tmp, V + 1, mail + 8));
   int32_t* player_start = directed ? cnt_all_rank : cnt_up_rank;
   DS_TRY(ds_scan_exclusive_i32(ctx, player_start, player_start, V + 1, mail + 9));
+  {  // number of CSR entries in the rows of every ball (rows are ordered by hop): mailbox slots 40..47
+    BallSizes bs;
+    for (int h = 0; h < 8; ++h) bs.v[h] = (int32_t)ball[h <= hops ? h : hops];
+    hipLaunchKernelGGL(ball_entries_kernel, dim3(1), dim3(64), 0, st, rowptr_tmp, bs, mail + 40);
+    DS_HIP(ctx, hipGetLastError());
+    DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + 40, mail + 40, 8 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  }
   DS_TRY(ds_mail_fetch(ctx, 16));
   const int64_t nnz_c = ctx->h_mail[8];
   const int64_t n = ctx->h_mail[9];
@@ -456,6 +471,7 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
   cg->d0 = d0;
   cg->d1 = d1;
   cg->att_heads = att_heads;
+  for (int h = 0; h < 8; ++h) cg->ball_entries[h] = ctx->h_mail[40 + h];
   cg->info.num_players = n;
   cg->info.num_nodes = V;
   cg->info.num_entries = nnz_c;

@@ -21,6 +21,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
+constexpr int kUnroll = 8;         // active entries gathered per step
 constexpr int kColsPerPass = 256;  // feature columns a wave covers per pass over a row (4 per lane)
 
 struct GatArgs {
@@ -45,6 +46,8 @@ struct GatArgs {
   int64_t gws_stride;  // floats per workgroup
   int32_t bufH, bufZ, bufS, bufT;  // floats
   int32_t buf_lds;
+  const float* h1;      // optional: layer-1 output of every coalition [k][rows_out[1]][dims[1]] (matrix-core path)
+  const int32_t* h1_bad; // device flag: non-zero means h1 was not produced (attention range too wide)
 };
 
 __device__ __forceinline__ int readlane_i(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
@@ -58,7 +61,8 @@ __device__ __forceinline__ float elu(float x) { return x > 0.f ? x : expm1f(x); 
 //   (the caller averages them).
 // Short rows go to one wave each; a long row is shared by all waves, whose partial (max, sum, acc)
 // triples meet in LDS and are merged by the owner in a fixed order.
-__device__ __forceinline__ void gat_aggregate(const GatArgs& a, const uint64_t* z, const float* zsrc, int zw,
+template <int NQ>
+__device__ __forceinline__ void gat_aggregate_nq(const GatArgs& a, const uint64_t* z, const float* zsrc, int zw,
                                               const float* ssrc, const float* sdst, int H, int F, int rows,
                                               float* dst, const float* bias, bool concat, float* part) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -67,12 +71,12 @@ __device__ __forceinline__ void gat_aggregate(const GatArgs& a, const uint64_t* 
     const bool coop = e1 - e0 > 2 * 64;
     const int owner = t % kWaves;
     if (!coop && owner != wave) continue;
-    for (int f0 = 0; f0 < zw; f0 += kColsPerPass) {
-      bool has[4];
-      int hd[4];
-      float sd[4], m[4], l[4], acc[4];
+    for (int f0 = 0; f0 < zw; f0 += 64 * NQ) {
+      bool has[NQ];
+      int hd[NQ];
+      float sd[NQ], m[NQ], l[NQ], acc[NQ];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < NQ; ++q) {
         const int f = f0 + lane + 64 * q;
         has[q] = f < zw;
         hd[q] = has[q] ? f / F : 0;
@@ -97,31 +101,47 @@ __device__ __forceinline__ void gat_aggregate(const GatArgs& a, const uint64_t* 
           bit = (z[p >> 6] >> (p & 63)) & 1ull;
         }
         unsigned long long mask = __ballot(bit);
+        // eight active entries per step: their loads are independent and issue back to back
         while (mask) {
-          const int i = __ffsll((long long)mask) - 1;
-          mask &= mask - 1;
-          const int j = readlane_i(srcn, i);
-          float ev[4], zv[4];
+          int idx[kUnroll];
+          bool live[kUnroll];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            ev[q] = has[q] ? ssrc[(size_t)j * H + hd[q]] : 0.f;
-            zv[q] = has[q] ? zsrc[(size_t)j * zw + f0 + lane + 64 * q] : 0.f;
+          for (int u = 0; u < kUnroll; ++u) {
+            live[u] = mask != 0ull;
+            const int i = live[u] ? __ffsll((long long)mask) - 1 : 0;
+            if (live[u]) mask &= mask - 1;
+            idx[u] = readlane_i(srcn, i);
+          }
+          float ev[kUnroll][NQ], zv[kUnroll][NQ];
+#pragma unroll
+          for (int u = 0; u < kUnroll; ++u) {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+              ev[u][q] = has[q] ? ssrc[(size_t)idx[u] * H + hd[q]] : 0.f;
+              zv[u][q] = has[q] ? zsrc[(size_t)idx[u] * zw + f0 + lane + 64 * q] : 0.f;
+            }
           }
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const float ee = lrelu(ev[q] + sd[q], a.slope);
-            const float mn = fmaxf(m[q], ee);
-            const float sc = __expf(m[q] - mn), pe = __expf(ee - mn);
-            l[q] = l[q] * sc + pe;
-            acc[q] = acc[q] * sc + pe * zv[q];
-            m[q] = mn;
+          for (int u = 0; u < kUnroll; ++u) {
+            if (!live[u]) break;  // uniform across the wave
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+              // running soft-max: of the two factors exp(m - max) and exp(e - max) one is always 1
+              const float ee = lrelu(ev[u][q] + sd[q], a.slope);
+              const float d = ee - m[q];
+              const float x = __expf(-fabsf(d));
+              const float sc = d > 0.f ? x : 1.f, pe = d > 0.f ? 1.f : x;
+              l[q] = l[q] * sc + pe;
+              acc[q] = acc[q] * sc + pe * zv[u][q];
+              m[q] = fmaxf(m[q], ee);
+            }
           }
         }
       }
       if (coop) {
         float* mine = part + (size_t)wave * 3 * kColsPerPass + lane;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < NQ; ++q) {
           mine[64 * q] = m[q];
           mine[kColsPerPass + 64 * q] = l[q];
           mine[2 * kColsPerPass + 64 * q] = acc[q];
@@ -129,7 +149,7 @@ __device__ __forceinline__ void gat_aggregate(const GatArgs& a, const uint64_t* 
         __syncthreads();
         if (wave == owner) {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
+          for (int q = 0; q < NQ; ++q) {
             float mm = -INFINITY;
             for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, part[(size_t)w * 3 * kColsPerPass + lane + 64 * q]);
             float ls = 0.f, as = 0.f;
@@ -146,7 +166,7 @@ __device__ __forceinline__ void gat_aggregate(const GatArgs& a, const uint64_t* 
       }
       if (wave == owner) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < NQ; ++q) {
           if (!has[q]) continue;
           const int f = f0 + lane + 64 * q;
           float v = acc[q] / l[q];
@@ -162,6 +182,15 @@ __device__ __forceinline__ void gat_aggregate(const GatArgs& a, const uint64_t* 
   }
 }
 
+// the number of 64-column groups a lane carries is fixed at compile time (1, 2 or 4)
+__device__ __forceinline__ void gat_aggregate(const GatArgs& a, const uint64_t* z, const float* zsrc, int zw,
+                                              const float* ssrc, const float* sdst, int H, int F, int rows,
+                                              float* dst, const float* bias, bool concat, float* part) {
+  if (zw <= 64) gat_aggregate_nq<1>(a, z, zsrc, zw, ssrc, sdst, H, F, rows, dst, bias, concat, part);
+  else if (zw <= 128) gat_aggregate_nq<2>(a, z, zsrc, zw, ssrc, sdst, H, F, rows, dst, bias, concat, part);
+  else gat_aggregate_nq<4>(a, z, zsrc, zw, ssrc, sdst, H, F, rows, dst, bias, concat, part);
+}
+
 __global__ __launch_bounds__(kThreads) void masked_gat_eval_kernel(GatArgs a) {
   extern __shared__ float smem[];
   float* part = smem;  // [kWaves][3][kColsPerPass]
@@ -175,8 +204,13 @@ __global__ __launch_bounds__(kThreads) void masked_gat_eval_kernel(GatArgs a) {
 
   for (int64_t row = blockIdx.x; row < a.k; row += gridDim.x) {
     const uint64_t* z = a.Z + row * a.W;
-    // layer 1 on the shared transform
-    {
+    // layer 1: already produced for all coalitions on the matrix cores, or aggregated here
+    if (a.h1 && *a.h1_bad == 0) {
+      const int cnt = a.rows_out[1] * a.dims[1];
+      const float* src = a.h1 + (size_t)row * cnt;
+      for (int i = tid; i < cnt; i += kThreads) bufH[i] = src[i];
+      __syncthreads();
+    } else {
       const int H = a.heads[0];
       const bool last = L == 1;
       gat_aggregate(a, z, a.P, a.zw[0], a.att1, a.att1 + (size_t)a.V * H, H, a.fh[0], a.rows_out[1],
@@ -259,6 +293,193 @@ __global__ void gat_att_scalars_kernel(const float* P, const float* asrc, const 
   out[(size_t)V * H + idx] = s1;
 }
 
+
+// ---------------- layer 1 of all coalitions at once on the matrix cores ----------------
+//
+// The attention logits of layer 1, e_tj^h, do not depend on the coalition: only the set of
+// neighbours the soft-max runs over does. With M_t^h the maximum of e_tj^h over the whole row (self
+// included) and p_tj^h = exp(e_tj^h - M_t^h),
+//   out_t^h[f] = ( sum_{j active} p_tj^h z_j^h[f] ) / ( sum_{j active} p_tj^h ),
+// so numerator and denominator of row t are products of a coalition-independent matrix
+// (columns x entries) with the 0/1 matrix (entries x coalitions): dense contractions.
+//   Az[e][0 .. zw)        = p_e^{h(f)} * z_{src e}[f]       (entry e of a needed row; the self term of row t
+//   Az[e][zwr .. zwr + H) = p_e^h                             is stored as row E1 + t)
+// zwr = zw rounded up to 32; the row stride is zwr + 32. The self term is always active, so the
+// denominator is at least p_tt > 0; if some p would fall below exp(-70) the flag is raised and the
+// per-coalition kernel computes layer 1 itself with a running maximum.
+typedef float float16_t __attribute__((ext_vector_type(16)));
+constexpr float kAttRange = 70.f;
+
+struct GatL1Args {
+  int32_t V, R1, E1, H, F, zw, zwr, zwp, concat_elu;
+  int64_t W, k;
+  const int32_t *row_ptr, *col, *eid;
+  const float* P;
+  const float* att1;
+  const float* bias;
+  float slope;
+  float* Az;      // [(E1 + R1) x zwp]
+  int32_t* bad;   // device flag
+  const uint64_t* Z;
+  float* h1;      // [k][R1][zw]
+};
+
+// one workgroup per needed row t
+__global__ __launch_bounds__(kThreads) void gat_entry_weights_kernel(GatL1Args g) {
+  __shared__ float Mh[64];
+  __shared__ float red[kWaves];
+  const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int e0 = g.row_ptr[t], e1 = g.row_ptr[t + 1];
+  const float* ssrc = g.att1;
+  const float* sdst = g.att1 + (size_t)g.V * g.H;
+  for (int h = 0; h < g.H; ++h) {
+    const float sd = sdst[(size_t)t * g.H + h];
+    float m = lrelu(ssrc[(size_t)t * g.H + h] + sd, g.slope);
+    float lo = m;
+    for (int e = e0 + tid; e < e1; e += kThreads) {
+      const float v = lrelu(ssrc[(size_t)g.col[e] * g.H + h] + sd, g.slope);
+      m = fmaxf(m, v);
+      lo = fminf(lo, v);
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      m = fmaxf(m, __shfl_xor(m, o, 64));
+      lo = fminf(lo, __shfl_xor(lo, o, 64));
+    }
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    float mm = red[0];
+    for (int w = 1; w < kWaves; ++w) mm = fmaxf(mm, red[w]);
+    if (tid == 0) Mh[h] = mm;
+    if (lane == 0 && !(mm - lo <= kAttRange)) atomicOr(g.bad, 1);  // also catches NaN
+    __syncthreads();
+  }
+  for (int ei = e0 + wave; ei <= e1; ei += kWaves) {  // ei == e1: the self term
+    const bool self = ei == e1;
+    const int src = self ? t : g.col[ei];
+    float* out = g.Az + (size_t)(self ? g.E1 + t : ei) * g.zwp;
+    for (int c = lane; c < g.zwp; c += 64) {
+      float v = 0.f;
+      int h = -1;
+      if (c < g.zw) h = c / g.F;
+      else if (c >= g.zwr && c < g.zwr + g.H) h = c - g.zwr;
+      if (h >= 0) {
+        const float e = lrelu(ssrc[(size_t)src * g.H + h] + sdst[(size_t)t * g.H + h], g.slope);
+        v = __expf(e - Mh[h]);
+        if (c < g.zw) v *= g.P[(size_t)src * g.zw + c];
+      }
+      out[c] = v;
+    }
+  }
+}
+
+// A workgroup takes 64 coalitions (lane = coalition); its waves share the (row, 32-column tile) items.
+// v_mfma_f32_32x32x2f32: lane l supplies A[m = l%32][k = l/32] and B[k = l/32][n = l%32]; accumulator
+// register i of lane l is D[8*(i/4) + 4*(l/32) + i%4][l%32].
+constexpr int kL1Stage = 16;  // entries per step
+__global__ __launch_bounds__(kThreads) void masked_gat_layer1_mfma_kernel(GatL1Args g) {
+  if (*g.bad != 0) return;
+  extern __shared__ float smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
+  float* den_w = smem + (size_t)wave * (32 * 64 + 2 * 32 * 33);  // [32 heads][64 coalitions]
+  float* T_w = den_w + 32 * 64;                                    // two tiles [32 coalitions][33]
+  const int FT = g.zwr / 32;
+  const int items = g.R1 * FT;
+  const int rounds = (items + kWaves - 1) / kWaves;
+  const int64_t blocks = (g.k + 63) / 64;
+  const size_t h1_stride = (size_t)g.R1 * g.zw;
+  for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
+    const int64_t row = blk * 64 + lane;
+    const uint64_t* zrow = g.Z + (row < g.k ? row : 0) * g.W;  // lanes past the end read row 0 and store nothing
+    for (int r = 0; r < rounds; ++r) {
+      const int item = r * kWaves + wave;
+      const bool live = item < items;
+      const int t = live ? item % g.R1 : 0, ft = live ? item / g.R1 : 0;
+      float16_t num0, num1, den0, den1;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { num0[i] = 0.f; num1[i] = 0.f; den0[i] = 0.f; den1[i] = 0.f; }
+      if (live) {
+        const int e0 = g.row_ptr[t], e1 = g.row_ptr[t + 1];  // index e1 stands for the self term
+        for (int eb = e0; eb <= e1; eb += kL1Stage) {
+          const int cnt = e1 + 1 - eb < kL1Stage ? e1 + 1 - eb : kL1Stage;
+          int pv = 0;
+          if (lane < cnt && eb + lane < e1) pv = g.eid[eb + lane];
+          float an[kL1Stage / 2], ad[kL1Stage / 2];
+#pragma unroll
+          for (int q = 0; q < kL1Stage / 2; ++q) {
+            const int ee = eb + 2 * q + half;
+            const bool ok = 2 * q + half < cnt;
+            const float* ap = g.Az + (size_t)(ee < e1 ? ee : g.E1 + t) * g.zwp;
+            an[q] = ok ? ap[ft * 32 + l32] : 0.f;
+            ad[q] = ok ? ap[g.zwr + l32] : 0.f;
+          }
+          float coef[kL1Stage];
+#pragma unroll
+          for (int i = 0; i < kL1Stage; ++i) {
+            coef[i] = 0.f;
+            if (i < cnt) {
+              const bool self = eb + i == e1;
+              const int p = readlane_i(pv, i);
+              const bool bit = self || ((zrow[p >> 6] >> (p & 63)) & 1ull);
+              coef[i] = bit ? 1.f : 0.f;
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < kL1Stage / 2; ++q) {
+            if (2 * q < cnt) {
+              const float x = coef[2 * q], y = coef[2 * q + 1];
+              const float xs = __shfl_xor(x, 32, 64), ys = __shfl_xor(y, 32, 64);
+              const float b0 = half ? ys : x;  // coalitions 0..31
+              const float b1 = half ? y : xs;  // coalitions 32..63
+              num0 = __builtin_amdgcn_mfma_f32_32x32x2f32(an[q], b0, num0, 0, 0, 0);
+              num1 = __builtin_amdgcn_mfma_f32_32x32x2f32(an[q], b1, num1, 0, 0, 0);
+              den0 = __builtin_amdgcn_mfma_f32_32x32x2f32(ad[q], b0, den0, 0, 0, 0);
+              den1 = __builtin_amdgcn_mfma_f32_32x32x2f32(ad[q], b1, den1, 0, 0, 0);
+            }
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int rr = 8 * (i / 4) + 4 * half + (i % 4);
+          den_w[rr * 64 + l32] = den0[i];
+          den_w[rr * 64 + 32 + l32] = den1[i];
+        }
+      }
+      __syncthreads();
+      if (live) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int fl = 8 * (i / 4) + 4 * half + (i % 4);
+          const int f = ft * 32 + fl;
+          float v0 = 0.f, v1 = 0.f;
+          if (f < g.zw) {
+            const int h = f / g.F;
+            v0 = num0[i] / den_w[h * 64 + l32];
+            v1 = num1[i] / den_w[h * 64 + 32 + l32];
+            if (g.concat_elu) {
+              const float bb = g.bias ? g.bias[f] : 0.f;
+              v0 = elu(v0 + bb);
+              v1 = elu(v1 + bb);
+            }
+          }
+          T_w[l32 * 33 + fl] = v0;
+          T_w[32 * 33 + l32 * 33 + fl] = v1;
+        }
+      }
+      __syncthreads();
+      if (live && ft * 32 + l32 < g.zw) {
+#pragma unroll 4
+        for (int cc = 0; cc < 32; ++cc) {
+          const int c = 2 * cc + half;  // coalition within the block: tile c / 32, column c % 32
+          const int64_t rw = blk * 64 + c;
+          if (rw < g.k) g.h1[(size_t)rw * h1_stride + (size_t)t * g.zw + ft * 32 + l32] = T_w[(c >> 5) * 32 * 33 + (c & 31) * 33 + l32];
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
 constexpr size_t kLdsBufLimit = 64 * 1024;  // buffers beyond this go to global scratch (keeps several workgroups per CU)
 
 struct GatLayout {
@@ -309,6 +530,37 @@ GatLayout gat_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
   return g;
 }
 
+// the matrix-core path for layer 1 applies to models with at least two layers and enough coalitions
+struct GatL1Layout {
+  bool use;
+  int32_t R1, E1, zwr, zwp;
+  size_t az_bytes, h1_bytes, lds_bytes;
+  int grid;
+};
+
+GatL1Layout gat_l1_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
+  GatL1Layout q;
+  memset(&q, 0, sizeof(q));
+  const int L = ctx->L, hops = cg->info.hops;
+  if (L < 2 || k < 256 || cg->info.num_players < 1 || ctx->gat.heads[0] > 32) return q;
+  const int h = L - 1 < hops ? L - 1 : hops;
+  q.R1 = (int32_t)cg->info.ball[h];
+  const int64_t E1 = cg->ball_entries[h];
+  if (E1 < 0 || E1 > 0x7fffff00LL) return q;
+  q.E1 = (int32_t)E1;
+  q.zwr = (ctx->gat.zw[0] + 31) & ~31;
+  q.zwp = q.zwr + 32;
+  q.az_bytes = ((size_t)E1 + q.R1) * q.zwp * 4;
+  q.h1_bytes = (size_t)k * q.R1 * ctx->gat.zw[0] * 4;
+  if (q.az_bytes > ((size_t)256 << 20) || q.h1_bytes > ((size_t)2 << 30)) return q;
+  q.lds_bytes = (size_t)kWaves * (32 * 64 + 2 * 32 * 33) * 4;
+  const int64_t blocks = (k + 63) / 64;
+  const int64_t cap = (int64_t)ctx->num_cus * 2;
+  q.grid = (int)(blocks < cap ? blocks : cap);
+  q.use = true;
+  return q;
+}
+
 void gat_fill(const ds_ctx* ctx, const ds_cgraph* cg, const GatLayout& g, GatArgs* a) {
   memset(a, 0, sizeof(*a));
   a->V = (int32_t)cg->info.num_nodes;
@@ -353,7 +605,8 @@ int gat_launch(ds_ctx* ctx, const GatArgs& a, const GatLayout& g, int grid) {
 size_t ds_gat_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
   const GatLayout g = gat_layout(ctx, cg, k > 1 ? k : 1);
   const size_t W = (cg->info.num_players + 63) / 64;
-  return ds_align((size_t)g.gws_floats * 4 * g.grid) + ds_align((size_t)g.gws_floats * 4) + ds_align(W * 8 + 8) +
+  const GatL1Layout q = gat_l1_layout(ctx, cg, k);
+  return (q.use ? ds_align(q.az_bytes) + ds_align(q.h1_bytes) + 512 : 0) + ds_align((size_t)g.gws_floats * 4 * g.grid) + ds_align((size_t)g.gws_floats * 4) + ds_align(W * 8 + 8) +
          ds_align(ctx->dims[ctx->L] * 4 + 8) + 1024;
 }
 
@@ -413,7 +666,33 @@ int ds_gat_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, i
   a.gws = gws;
   a.score = score;
   a.pred_ptr = cg->d_pred;
+  const GatL1Layout q = gat_l1_layout(ctx, cg, k);
+  GatL1Args l1;
+  if (q.use) {
+    float* Az = (float*)ds_arena_alloc(ctx, q.az_bytes);
+    float* h1 = (float*)ds_arena_alloc(ctx, q.h1_bytes);
+    int32_t* bad = (int32_t*)ds_arena_alloc(ctx, 256);
+    if (!Az || !h1 || !bad) return ds_fail(ctx, DS_EINTERNAL, "eval: arena exhausted");
+    memset(&l1, 0, sizeof(l1));
+    l1.V = a.V; l1.R1 = q.R1; l1.E1 = q.E1; l1.H = a.heads[0]; l1.F = a.fh[0]; l1.zw = a.zw[0];
+    l1.zwr = q.zwr; l1.zwp = q.zwp; l1.concat_elu = 1;
+    l1.W = a.W; l1.k = k;
+    l1.row_ptr = a.row_ptr; l1.col = a.col; l1.eid = a.eid;
+    l1.P = a.P; l1.att1 = a.att1; l1.bias = a.bias[0]; l1.slope = a.slope;
+    l1.Az = Az; l1.bad = bad; l1.Z = Z; l1.h1 = h1;
+    a.h1 = h1;
+    a.h1_bad = bad;
+  }
   DS_TRY(ds_kernel_mark(ctx, 0, 0));
+  if (q.use) {
+    DS_HIP(ctx, hipMemsetAsync(l1.bad, 0, sizeof(int32_t), ctx->stream));
+    hipLaunchKernelGGL(gat_entry_weights_kernel, dim3(q.R1), dim3(kThreads), 0, ctx->stream, l1);
+    DS_HIP(ctx, hipGetLastError());
+    if (q.lds_bytes > 48 * 1024)
+      DS_HIP(ctx, hipFuncSetAttribute((const void*)masked_gat_layer1_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)q.lds_bytes));
+    hipLaunchKernelGGL(masked_gat_layer1_mfma_kernel, dim3(q.grid), dim3(kThreads), q.lds_bytes, ctx->stream, l1);
+    DS_HIP(ctx, hipGetLastError());
+  }
   DS_TRY(gat_launch(ctx, a, g, g.grid));
   return ds_kernel_mark(ctx, 0, 1);
 }

@@ -33,6 +33,7 @@ struct ds_cgraph {
   uint64_t model_version; // model the cached P / d_pred belong to (0 = none)
   int32_t pred_class;     // host copy, -1 until fetched
   int32_t d0, d1;
+  int64_t ball_entries[8]; // row_ptr[ball[h]]: CSR entries of the rows within h hops
   int32_t att_heads;       // heads the `att` array was sized for (0: extracted for a GCN)
 };
 

@@ -66,7 +66,10 @@ def test_masked_gat_inference_matches_oracle(key, hops, directed, score, with_bi
     if with_bias:
         outs = [w.gat["heads"][0] * w.gat["widths"][0], w.gat["widths"][1]]
         biases = [0.1 * rng.standard_normal(o).astype(np.float32) for o in outs]
+    # 96 rows: every layer in the one-workgroup-per-coalition kernel; 333 rows (five blocks of 64 and a ragged
+    # tail): layer 1 of all coalitions on the matrix cores first
     _eval_case(w, w.gat, hops, directed, score, 96, rng, biases)
+    _eval_case(w, w.gat, hops, directed, score, 333, rng, biases)
 
 
 @pytest.mark.parametrize("heads,widths", [
@@ -82,6 +85,25 @@ def test_masked_gat_shapes(heads, widths):
     model = _gat_model(rng, w.dims[0], heads, widths)
     say(f"gat eval shapes heads={heads} widths={widths}")
     _eval_case(w, model, len(heads), False, 0, 40, rng)
+    _eval_case(w, model, len(heads), False, 0, 270, rng)
+
+
+def test_masked_gat_wide_attention_range_falls_back_to_the_running_maximum():
+    """Attention vectors scaled up until the logits of one row span more than exp() can hold in fp32 relative
+    to the row maximum: the matrix-core path for layer 1 must step aside (its weights would underflow) and the
+    per-coalition kernel with the running maximum gives the answer."""
+    w = make_workload("gat_small")
+    rng = np.random.default_rng(13)
+    model = _gat_model(rng, w.dims[0], (4, 2), (8, 6))
+    model["a_src"] = [a * 60.0 for a in model["a_src"]]
+    model["a_dst"] = [a * 60.0 for a in model["a_dst"]]
+    cgo = compgraph.extract(w.row_ptr, w.col, w.targets[0], 2)
+    Xc = w.features[cgo["node_gid"]].astype(np.float64)
+    Zf = Xc @ model["W"][0].astype(np.float64)
+    s = (Zf.reshape(len(Zf), 4, 8) * model["a_src"][0][None]).sum(-1)
+    assert s.max() - s.min() > 200.0          # the premise of the test
+    say("gat eval wide attention range")
+    _eval_case(w, model, 2, False, 0, 300, rng, tol=1e-4)
 
 
 def test_masked_gat_long_rows_shared_by_the_workgroup():
@@ -107,6 +129,16 @@ def test_masked_gat_long_rows_shared_by_the_workgroup():
     err = np.abs(y.cpu().numpy().astype(np.float64) - ref).max()
     say(f"  n={n} V={cgo['num_nodes']} err={err:.2e}")
     assert pc == f.pred_class and err <= 2e-5
+    # the same rows inside a batch large enough for the matrix-core path of layer 1 (its hub row spans dozens
+    # of 16-entry steps): the first 24 against the oracle, the rest against the per-coalition kernel
+    more = _random_rows(n, 320, rng)
+    more[:24] = bits
+    Zm = torch.from_numpy(sampling.pack_rows(more).view(np.int64)).cuda()
+    ym = ctx.eval(cg, Zm)[0].cpu().numpy().astype(np.float64)
+    assert np.abs(ym[:24] - ref).max() <= 2e-5
+    parts = np.concatenate([ctx.eval(cg, Zm[i:i + 80].contiguous())[0].cpu().numpy() for i in range(0, 320, 80)])
+    say(f"  matrix-core layer 1 vs per-coalition kernel: {np.abs(ym - parts).max():.2e}")
+    assert np.abs(ym - parts).max() <= 5e-6
     ctx.cgraph_free(cg)
     ctx.close()
 
