@@ -16,6 +16,7 @@
 #include <algorithm>
 
 #include "internal.h"
+#include "solve_common.h"
 
 namespace {
 
@@ -61,15 +62,16 @@ __device__ __forceinline__ float elu(float x) { return x > 0.f ? x : expm1f(x); 
 //   (the caller averages them).
 // Short rows go to one wave each; a long row is shared by all waves, whose partial (max, sum, acc)
 // triples meet in LDS and are merged by the owner in a fixed order.
-template <int NQ>
+template <int NQ, int WAVES>
 __device__ __forceinline__ void gat_aggregate_nq(const GatArgs& a, const uint64_t* z, const float* zsrc, int zw,
                                               const float* ssrc, const float* sdst, int H, int F, int rows,
                                               float* dst, const float* bias, bool concat, float* part) {
+  constexpr int UNROLL = WAVES == 1 ? 4 : kUnroll;  // the one-wave variant trades gather depth for occupancy
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int t = 0; t < rows; ++t) {
     const int e0 = a.row_ptr[t], e1 = a.row_ptr[t + 1];
     const bool coop = e1 - e0 > 2 * 64;
-    const int owner = t % kWaves;
+    const int owner = t % WAVES;
     if (!coop && owner != wave) continue;
     for (int f0 = 0; f0 < zw; f0 += 64 * NQ) {
       bool has[NQ];
@@ -91,7 +93,7 @@ __device__ __forceinline__ void gat_aggregate_nq(const GatArgs& a, const uint64_
           acc[q] = 0.f;
         }
       }
-      for (int base = e0 + (coop ? wave * 64 : 0); base < e1; base += (coop ? kWaves * 64 : 64)) {
+      for (int base = e0 + (coop ? wave * 64 : 0); base < e1; base += (coop ? WAVES * 64 : 64)) {
         const int e = base + lane;
         int srcn = 0;
         bool bit = false;
@@ -103,18 +105,18 @@ __device__ __forceinline__ void gat_aggregate_nq(const GatArgs& a, const uint64_
         unsigned long long mask = __ballot(bit);
         // eight active entries per step: their loads are independent and issue back to back
         while (mask) {
-          int idx[kUnroll];
-          bool live[kUnroll];
+          int idx[UNROLL];
+          bool live[UNROLL];
 #pragma unroll
-          for (int u = 0; u < kUnroll; ++u) {
+          for (int u = 0; u < UNROLL; ++u) {
             live[u] = mask != 0ull;
             const int i = live[u] ? __ffsll((long long)mask) - 1 : 0;
             if (live[u]) mask &= mask - 1;
             idx[u] = readlane_i(srcn, i);
           }
-          float ev[kUnroll][NQ], zv[kUnroll][NQ];
+          float ev[UNROLL][NQ], zv[UNROLL][NQ];
 #pragma unroll
-          for (int u = 0; u < kUnroll; ++u) {
+          for (int u = 0; u < UNROLL; ++u) {
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
               ev[u][q] = has[q] ? ssrc[(size_t)idx[u] * H + hd[q]] : 0.f;
@@ -122,7 +124,7 @@ __device__ __forceinline__ void gat_aggregate_nq(const GatArgs& a, const uint64_
             }
           }
 #pragma unroll
-          for (int u = 0; u < kUnroll; ++u) {
+          for (int u = 0; u < UNROLL; ++u) {
             if (!live[u]) break;  // uniform across the wave
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
@@ -151,9 +153,9 @@ __device__ __forceinline__ void gat_aggregate_nq(const GatArgs& a, const uint64_
 #pragma unroll
           for (int q = 0; q < NQ; ++q) {
             float mm = -INFINITY;
-            for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, part[(size_t)w * 3 * kColsPerPass + lane + 64 * q]);
+            for (int w = 0; w < WAVES; ++w) mm = fmaxf(mm, part[(size_t)w * 3 * kColsPerPass + lane + 64 * q]);
             float ls = 0.f, as = 0.f;
-            for (int w = 0; w < kWaves; ++w) {  // fixed order: the sum does not depend on timing
+            for (int w = 0; w < WAVES; ++w) {  // fixed order: the sum does not depend on timing
               const float* o = part + (size_t)w * 3 * kColsPerPass + lane + 64 * q;
               const float sc = __expf(o[0] - mm);  // exp(-inf) = 0 for a wave that saw nothing
               ls += o[kColsPerPass] * sc;
@@ -183,18 +185,24 @@ __device__ __forceinline__ void gat_aggregate_nq(const GatArgs& a, const uint64_
 }
 
 // the number of 64-column groups a lane carries is fixed at compile time (1, 2 or 4)
+template <int WAVES>
 __device__ __forceinline__ void gat_aggregate(const GatArgs& a, const uint64_t* z, const float* zsrc, int zw,
                                               const float* ssrc, const float* sdst, int H, int F, int rows,
                                               float* dst, const float* bias, bool concat, float* part) {
-  if (zw <= 64) gat_aggregate_nq<1>(a, z, zsrc, zw, ssrc, sdst, H, F, rows, dst, bias, concat, part);
-  else if (zw <= 128) gat_aggregate_nq<2>(a, z, zsrc, zw, ssrc, sdst, H, F, rows, dst, bias, concat, part);
-  else gat_aggregate_nq<4>(a, z, zsrc, zw, ssrc, sdst, H, F, rows, dst, bias, concat, part);
+  if (zw <= 64) gat_aggregate_nq<1, WAVES>(a, z, zsrc, zw, ssrc, sdst, H, F, rows, dst, bias, concat, part);
+  else if (zw <= 128 || WAVES == 1)  // the one-wave variant walks wide rows in passes of 128 columns: fewer registers
+    gat_aggregate_nq<2, WAVES>(a, z, zsrc, zw, ssrc, sdst, H, F, rows, dst, bias, concat, part);
+  else gat_aggregate_nq<4, WAVES>(a, z, zsrc, zw, ssrc, sdst, H, F, rows, dst, bias, concat, part);
 }
 
-__global__ __launch_bounds__(kThreads) void masked_gat_eval_kernel(GatArgs a) {
+// THREADS = 256: a workgroup per coalition (every layer here); THREADS = 64: a wave per coalition, used when
+// layer 1 comes precomputed and only the small later layers are left.
+template <int THREADS>
+__device__ __forceinline__ void masked_gat_eval_body(const GatArgs& a) {
+  constexpr int WAVES = THREADS / 64;
   extern __shared__ float smem[];
-  float* part = smem;  // [kWaves][3][kColsPerPass]
-  float* buf = a.buf_lds ? smem + kWaves * 3 * kColsPerPass : a.gws + (size_t)blockIdx.x * a.gws_stride;
+  float* part = smem;  // [WAVES][3][kColsPerPass]
+  float* buf = a.buf_lds ? smem + WAVES * 3 * kColsPerPass : a.gws + (size_t)blockIdx.x * a.gws_stride;
   float* bufH = buf;
   float* bufZ = bufH + a.bufH;
   float* bufS = bufZ + a.bufZ;
@@ -208,19 +216,19 @@ __global__ __launch_bounds__(kThreads) void masked_gat_eval_kernel(GatArgs a) {
     if (a.h1 && *a.h1_bad == 0) {
       const int cnt = a.rows_out[1] * a.dims[1];
       const float* src = a.h1 + (size_t)row * cnt;
-      for (int i = tid; i < cnt; i += kThreads) bufH[i] = src[i];
+      for (int i = tid; i < cnt; i += THREADS) bufH[i] = src[i];
       __syncthreads();
     } else {
       const int H = a.heads[0];
       const bool last = L == 1;
-      gat_aggregate(a, z, a.P, a.zw[0], a.att1, a.att1 + (size_t)a.V * H, H, a.fh[0], a.rows_out[1],
+      gat_aggregate<WAVES>(a, z, a.P, a.zw[0], a.att1, a.att1 + (size_t)a.V * H, H, a.fh[0], a.rows_out[1],
                     last ? bufT : bufH, a.bias[0], !last, part);
       __syncthreads();
     }
     for (int l = 2; l <= L; ++l) {
       const int rin = a.rows_out[l - 1], din = a.dims[l - 1], zw = a.zw[l - 1], H = a.heads[l - 1], F = a.fh[l - 1];
       const float* Wm = a.Wl[l - 1];
-      for (int idx = tid; idx < rin * zw; idx += kThreads) {
+      for (int idx = tid; idx < rin * zw; idx += THREADS) {
         const int r = idx / zw, j = idx - r * zw;
         const float* hr = bufH + (size_t)r * din;
         float s = 0.f;
@@ -228,7 +236,7 @@ __global__ __launch_bounds__(kThreads) void masked_gat_eval_kernel(GatArgs a) {
         bufZ[idx] = s;
       }
       __syncthreads();
-      for (int idx = tid; idx < rin * H; idx += kThreads) {
+      for (int idx = tid; idx < rin * H; idx += THREADS) {
         const int r = idx / H, h = idx - r * H;
         const float* zr = bufZ + (size_t)r * zw + h * F;
         const float *as = a.asrc[l - 1] + h * F, *ad = a.adst[l - 1] + h * F;
@@ -242,14 +250,14 @@ __global__ __launch_bounds__(kThreads) void masked_gat_eval_kernel(GatArgs a) {
       }
       __syncthreads();
       const bool last = l == L;
-      gat_aggregate(a, z, bufZ, zw, bufS, bufS + rin * H, H, F, a.rows_out[l], last ? bufT : bufH, a.bias[l - 1],
+      gat_aggregate<WAVES>(a, z, bufZ, zw, bufS, bufS + rin * H, H, F, a.rows_out[l], last ? bufT : bufH, a.bias[l - 1],
                     !last, part);
       __syncthreads();
     }
     // last layer: average the heads of the target's row, add the bias
     {
       const int H = a.heads[L - 1], C = a.fh[L - 1];
-      for (int c = tid; c < C; c += kThreads) {
+      for (int c = tid; c < C; c += THREADS) {
         float s = 0.f;
         for (int h = 0; h < H; ++h) s += bufT[h * C + c];
         s = s / (float)H;
@@ -275,6 +283,16 @@ __global__ __launch_bounds__(kThreads) void masked_gat_eval_kernel(GatArgs a) {
     }
     __syncthreads();
   }
+}
+
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void masked_gat_eval_kernel(GatArgs a) {
+  masked_gat_eval_body<THREADS>(a);
+}
+
+// the wave-per-coalition variant lives on latency hiding: ask for at least six waves per SIMD
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(6, 8))) void masked_gat_eval_wave_kernel(GatArgs a) {
+  masked_gat_eval_body<64>(a);
 }
 
 // s_src[v, h] = a_src^h . z_v^h and s_dst[v, h] = a_dst^h . z_v^h for the shared first transform
@@ -309,6 +327,7 @@ __global__ void gat_att_scalars_kernel(const float* P, const float* asrc, const 
 // per-coalition kernel computes layer 1 itself with a running maximum.
 typedef float float16_t __attribute__((ext_vector_type(16)));
 constexpr float kAttRange = 70.f;
+__device__ __forceinline__ bool ft_in_range(int ft, int l32, int zw) { return ft * 32 + l32 < zw; }
 
 struct GatL1Args {
   int32_t V, R1, E1, H, F, zw, zwr, zwp, concat_elu;
@@ -319,14 +338,15 @@ struct GatL1Args {
   const float* bias;
   float slope;
   float* Az;      // [(E1 + R1) x zwp]
+  float* rowmax;  // [R1 x H]
   int32_t* bad;   // device flag
-  const uint64_t* Z;
+  const uint64_t* Zt;  // optional: transposed masks [n][KW], word blk of row p = bit p of coalitions 64 blk ..
+  int64_t KW;
   float* h1;      // [k][R1][zw]
 };
 
-// one workgroup per needed row t
-__global__ __launch_bounds__(kThreads) void gat_entry_weights_kernel(GatL1Args g) {
-  __shared__ float Mh[64];
+// row maxima M[t][h] over the whole row (self included); one workgroup per needed row t
+__global__ __launch_bounds__(kThreads) void gat_row_max_kernel(GatL1Args g) {
   __shared__ float red[kWaves];
   const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int e0 = g.row_ptr[t], e1 = g.row_ptr[t + 1];
@@ -349,133 +369,172 @@ __global__ __launch_bounds__(kThreads) void gat_entry_weights_kernel(GatL1Args g
     __syncthreads();
     float mm = red[0];
     for (int w = 1; w < kWaves; ++w) mm = fmaxf(mm, red[w]);
-    if (tid == 0) Mh[h] = mm;
+    if (tid == 0) g.rowmax[t * g.H + h] = mm;
     if (lane == 0 && !(mm - lo <= kAttRange)) atomicOr(g.bad, 1);  // also catches NaN
     __syncthreads();
   }
-  for (int ei = e0 + wave; ei <= e1; ei += kWaves) {  // ei == e1: the self term
-    const bool self = ei == e1;
-    const int src = self ? t : g.col[ei];
-    float* out = g.Az + (size_t)(self ? g.E1 + t : ei) * g.zwp;
-    for (int c = lane; c < g.zwp; c += 64) {
-      float v = 0.f;
-      int h = -1;
-      if (c < g.zw) h = c / g.F;
-      else if (c >= g.zwr && c < g.zwr + g.H) h = c - g.zwr;
-      if (h >= 0) {
-        const float e = lrelu(ssrc[(size_t)src * g.H + h] + sdst[(size_t)t * g.H + h], g.slope);
-        v = __expf(e - Mh[h]);
-        if (c < g.zw) v *= g.P[(size_t)src * g.zw + c];
-      }
-      out[c] = v;
+}
+
+// one wave per entry of the needed rows (the self terms come after the E1 entries)
+__global__ __launch_bounds__(kThreads) void gat_entry_weights_kernel(GatL1Args g) {
+  const int lane = threadIdx.x & 63;
+  const int ei = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  if (ei >= g.E1 + g.R1) return;
+  int t, src;
+  if (ei >= g.E1) {
+    t = ei - g.E1;
+    src = t;
+  } else {
+    int lo = 0, hi = g.R1 - 1;  // last row whose first entry is <= ei
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (g.row_ptr[mid] <= ei) lo = mid; else hi = mid - 1;
     }
+    t = lo;
+    src = g.col[ei];
+  }
+  const float* ssrc = g.att1;
+  const float* sdst = g.att1 + (size_t)g.V * g.H;
+  float* out = g.Az + (size_t)ei * g.zwp;
+  for (int c = lane; c < g.zwp; c += 64) {
+    float v = 0.f;
+    int h = -1;
+    if (c < g.zw) h = c / g.F;
+    else if (c >= g.zwr && c < g.zwr + g.H) h = c - g.zwr;
+    if (h >= 0) {
+      const float e = lrelu(ssrc[(size_t)src * g.H + h] + sdst[(size_t)t * g.H + h], g.slope);
+      v = __expf(e - g.rowmax[t * g.H + h]);
+      if (c < g.zw) v *= g.P[(size_t)src * g.zw + c];
+    }
+    out[c] = v;
   }
 }
 
-// A workgroup takes 64 coalitions (lane = coalition); its waves share the (row, 32-column tile) items.
+// A workgroup takes 128 coalitions, 32 per wave, and every wave walks all needed rows for its own
+// coalitions, so the waves carry identical work whatever the row lengths are (a hub row is no imbalance).
 // v_mfma_f32_32x32x2f32: lane l supplies A[m = l%32][k = l/32] and B[k = l/32][n = l%32]; accumulator
-// register i of lane l is D[8*(i/4) + 4*(l/32) + i%4][l%32].
-constexpr int kL1Stage = 16;  // entries per step
+// register i of lane l is D[8*(i/4) + 4*(l/32) + i%4][l%32]. Per row a wave accumulates up to three
+// 32-column tiles of the numerator plus the denominator tile (one row per head).
+// The 0/1 operand comes from the transposed mask matrix: a word of player p holds the bits of 64
+// coalitions, so the words of the needed entries (staged in LDS once per block of coalitions) serve every
+// lane and no cross-lane traffic is needed: lane l takes bit (32 (wave%2) + l%32) of the word of entry
+// 2q + l/32. The A operand of the next step is loaded while the current step multiplies.
+constexpr int kL1Stage = 16;        // entries per step
+constexpr int kL1Tiles = 3;         // numerator tiles per pass
+constexpr int kL1MaxEntries = 4096; // entries of the needed rows whose mask words fit the LDS stage
+constexpr int kL1WaveFloats = 32 * 33 + 32 * 33;
 __global__ __launch_bounds__(kThreads) void masked_gat_layer1_mfma_kernel(GatL1Args g) {
   if (*g.bad != 0) return;
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_l1[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, l32 = lane & 31;
-  float* den_w = smem + (size_t)wave * (32 * 64 + 2 * 32 * 33);  // [32 heads][64 coalitions]
-  float* T_w = den_w + 32 * 64;                                    // two tiles [32 coalitions][33]
+  const int wsel_word = wave >> 1, wsel_shift = 32 * (wave & 1) + l32;
+  uint64_t* bitsL = (uint64_t*)smem_l1;  // [2][E1 + 2]: mask words of the needed entries, then all-ones, then zero
+  const int bstride = g.E1 + 2;
+  float* den_w = (float*)(smem_l1 + (((size_t)2 * bstride * 8 + 15) & ~(size_t)15)) + (size_t)wave * kL1WaveFloats;
+  float* T_w = den_w + 32 * 33;  // one tile [32 coalitions][33]
+  const uint64_t* my_bits = bitsL + (size_t)wsel_word * bstride;
   const int FT = g.zwr / 32;
-  const int items = g.R1 * FT;
-  const int rounds = (items + kWaves - 1) / kWaves;
-  const int64_t blocks = (g.k + 63) / 64;
+  const int64_t blocks = (g.k + 127) / 128;
   const size_t h1_stride = (size_t)g.R1 * g.zw;
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
-    const int64_t row = blk * 64 + lane;
-    const uint64_t* zrow = g.Z + (row < g.k ? row : 0) * g.W;  // lanes past the end read row 0 and store nothing
-    for (int r = 0; r < rounds; ++r) {
-      const int item = r * kWaves + wave;
-      const bool live = item < items;
-      const int t = live ? item % g.R1 : 0, ft = live ? item / g.R1 : 0;
-      float16_t num0, num1, den0, den1;
+    __syncthreads();
+    for (int i = tid; i < 2 * g.E1; i += kThreads) {
+      const int wd = i >= g.E1 ? 1 : 0, e = i - wd * g.E1;
+      const int64_t kw = 2 * blk + wd;
+      bitsL[(size_t)wd * bstride + e] = kw < g.KW ? g.Zt[(size_t)g.eid[e] * g.KW + kw] : 0ull;
+    }
+    if (tid < 2) {
+      bitsL[(size_t)tid * bstride + g.E1] = ~0ull;    // the self term is always active
+      bitsL[(size_t)tid * bstride + g.E1 + 1] = 0ull; // past the end of a row
+    }
+    __syncthreads();
+    const int64_t row_base = blk * 128 + wave * 32;
+    for (int t = 0; t < g.R1; ++t) {
+      const int e0 = g.row_ptr[t], e1 = g.row_ptr[t + 1];  // index e1 stands for the self term
+      const size_t self_row = (size_t)(g.E1 + t) * g.zwp;
+      for (int fg = 0; fg < FT; fg += kL1Tiles) {
+        const int nt = FT - fg < kL1Tiles ? FT - fg : kL1Tiles;
+        float16_t num[kL1Tiles], den;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) { num0[i] = 0.f; num1[i] = 0.f; den0[i] = 0.f; den1[i] = 0.f; }
-      if (live) {
-        const int e0 = g.row_ptr[t], e1 = g.row_ptr[t + 1];  // index e1 stands for the self term
+        for (int i = 0; i < 16; ++i) {
+          den[i] = 0.f;
+#pragma unroll
+          for (int j = 0; j < kL1Tiles; ++j) num[j][i] = 0.f;
+        }
+        const float* az = g.Az + l32;
+        float an[kL1Stage / 2][kL1Tiles], ad[kL1Stage / 2];
+#pragma unroll
+        for (int q = 0; q < kL1Stage / 2; ++q) {  // rows past the end are clamped to the self row and masked by B = 0
+          const int ee = e0 + 2 * q + half;
+          const float* ap = az + (ee < e1 ? (size_t)ee * g.zwp : self_row);
+#pragma unroll
+          for (int j = 0; j < kL1Tiles; ++j) an[q][j] = ap[(fg + (j < nt ? j : 0)) * 32];
+          ad[q] = ap[g.zwr];
+        }
         for (int eb = e0; eb <= e1; eb += kL1Stage) {
-          const int cnt = e1 + 1 - eb < kL1Stage ? e1 + 1 - eb : kL1Stage;
-          int pv = 0;
-          if (lane < cnt && eb + lane < e1) pv = g.eid[eb + lane];
-          float an[kL1Stage / 2], ad[kL1Stage / 2];
+          float an2[kL1Stage / 2][kL1Tiles], ad2[kL1Stage / 2];
+#pragma unroll
+          for (int q = 0; q < kL1Stage / 2; ++q) {
+            const int ee = eb + kL1Stage + 2 * q + half;
+            const float* ap = az + (ee < e1 ? (size_t)ee * g.zwp : self_row);
+#pragma unroll
+            for (int j = 0; j < kL1Tiles; ++j) an2[q][j] = ap[(fg + (j < nt ? j : 0)) * 32];
+            ad2[q] = ap[g.zwr];
+          }
 #pragma unroll
           for (int q = 0; q < kL1Stage / 2; ++q) {
             const int ee = eb + 2 * q + half;
-            const bool ok = 2 * q + half < cnt;
-            const float* ap = g.Az + (size_t)(ee < e1 ? ee : g.E1 + t) * g.zwp;
-            an[q] = ok ? ap[ft * 32 + l32] : 0.f;
-            ad[q] = ok ? ap[g.zwr + l32] : 0.f;
-          }
-          float coef[kL1Stage];
-#pragma unroll
-          for (int i = 0; i < kL1Stage; ++i) {
-            coef[i] = 0.f;
-            if (i < cnt) {
-              const bool self = eb + i == e1;
-              const int p = readlane_i(pv, i);
-              const bool bit = self || ((zrow[p >> 6] >> (p & 63)) & 1ull);
-              coef[i] = bit ? 1.f : 0.f;
-            }
+            const uint64_t wsel = my_bits[ee < e1 ? ee : (ee == e1 ? g.E1 : g.E1 + 1)];
+            const float bq = (float)((uint32_t)(wsel >> wsel_shift) & 1u);
+            den = __builtin_amdgcn_mfma_f32_32x32x2f32(ad[q], bq, den, 0, 0, 0);
+            num[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(an[q][0], bq, num[0], 0, 0, 0);
+            if (nt > 1) num[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(an[q][1], bq, num[1], 0, 0, 0);
+            if (nt > 2) num[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(an[q][2], bq, num[2], 0, 0, 0);
           }
 #pragma unroll
           for (int q = 0; q < kL1Stage / 2; ++q) {
-            if (2 * q < cnt) {
-              const float x = coef[2 * q], y = coef[2 * q + 1];
-              const float xs = __shfl_xor(x, 32, 64), ys = __shfl_xor(y, 32, 64);
-              const float b0 = half ? ys : x;  // coalitions 0..31
-              const float b1 = half ? y : xs;  // coalitions 32..63
-              num0 = __builtin_amdgcn_mfma_f32_32x32x2f32(an[q], b0, num0, 0, 0, 0);
-              num1 = __builtin_amdgcn_mfma_f32_32x32x2f32(an[q], b1, num1, 0, 0, 0);
-              den0 = __builtin_amdgcn_mfma_f32_32x32x2f32(ad[q], b0, den0, 0, 0, 0);
-              den1 = __builtin_amdgcn_mfma_f32_32x32x2f32(ad[q], b1, den1, 0, 0, 0);
-            }
+            ad[q] = ad2[q];
+#pragma unroll
+            for (int j = 0; j < kL1Tiles; ++j) an[q][j] = an2[q][j];
           }
         }
+        // denominators to LDS as [head][coalition], so that every column finds its head's
+        __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int rr = 8 * (i / 4) + 4 * half + (i % 4);
-          den_w[rr * 64 + l32] = den0[i];
-          den_w[rr * 64 + 32 + l32] = den1[i];
-        }
-      }
-      __syncthreads();
-      if (live) {
+        for (int i = 0; i < 16; ++i) den_w[(8 * (i / 4) + 4 * half + (i % 4)) * 33 + l32] = den[i];
+        __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int fl = 8 * (i / 4) + 4 * half + (i % 4);
-          const int f = ft * 32 + fl;
-          float v0 = 0.f, v1 = 0.f;
-          if (f < g.zw) {
-            const int h = f / g.F;
-            v0 = num0[i] / den_w[h * 64 + l32];
-            v1 = num1[i] / den_w[h * 64 + 32 + l32];
-            if (g.concat_elu) {
-              const float bb = g.bias ? g.bias[f] : 0.f;
-              v0 = elu(v0 + bb);
-              v1 = elu(v1 + bb);
+        for (int j = 0; j < kL1Tiles; ++j) {
+          if (j < nt) {
+            const int ft = fg + j;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int fl = 8 * (i / 4) + 4 * half + (i % 4);
+              const int f = ft * 32 + fl;
+              float v = 0.f;
+              if (f < g.zw) {
+                v = num[j][i] * __frcp_rn(den_w[(f / g.F) * 33 + l32]);
+                if (g.concat_elu) {
+                  v += g.bias ? g.bias[f] : 0.f;
+                  v = v > 0.f ? v : __expf(v) - 1.f;
+                }
+              }
+              T_w[l32 * 33 + fl] = v;
             }
           }
-          T_w[l32 * 33 + fl] = v0;
-          T_w[32 * 33 + l32 * 33 + fl] = v1;
-        }
-      }
-      __syncthreads();
-      if (live && ft * 32 + l32 < g.zw) {
+          __syncthreads();
+          if (j < nt && ft_in_range(fg + j, l32, g.zw)) {
 #pragma unroll 4
-        for (int cc = 0; cc < 32; ++cc) {
-          const int c = 2 * cc + half;  // coalition within the block: tile c / 32, column c % 32
-          const int64_t rw = blk * 64 + c;
-          if (rw < g.k) g.h1[(size_t)rw * h1_stride + (size_t)t * g.zw + ft * 32 + l32] = T_w[(c >> 5) * 32 * 33 + (c & 31) * 33 + l32];
+            for (int cc = 0; cc < 16; ++cc) {
+              const int c = 2 * cc + half;  // coalition of this wave
+              const int64_t rw = row_base + c;
+              if (rw < g.k) g.h1[(size_t)rw * h1_stride + (size_t)t * g.zw + (fg + j) * 32 + l32] = T_w[c * 33 + l32];
+            }
+          }
+          __syncthreads();
         }
       }
-      __syncthreads();
     }
   }
 }
@@ -484,6 +543,7 @@ constexpr size_t kLdsBufLimit = 64 * 1024;  // buffers beyond this go to global 
 
 struct GatLayout {
   int32_t bufH, bufZ, bufS, bufT;
+  int threads;
   bool buf_lds;
   size_t lds_bytes;
   int64_t gws_floats;
@@ -500,7 +560,7 @@ void gat_rows(const ds_ctx* ctx, const ds_cgraph* cg, int32_t rows_out[DS_MAX_LA
   }
 }
 
-GatLayout gat_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
+GatLayout gat_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int threads = kThreads) {
   int32_t rows_out[DS_MAX_LAYERS + 1];
   gat_rows(ctx, cg, rows_out);
   const int L = ctx->L;
@@ -516,12 +576,13 @@ GatLayout gat_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
   g.bufS = (int32_t)Sm;
   g.bufT = (int32_t)((int64_t)rows_out[L] * ctx->gat.zw[L - 1]);
   const size_t buf_bytes = ((size_t)Hm + Zm + Sm + g.bufT) * 4;
-  const size_t fix = (size_t)kWaves * 3 * kColsPerPass * 4;
+  const size_t fix = (size_t)(threads / 64) * 3 * kColsPerPass * 4;
+  g.threads = threads;
   g.buf_lds = buf_bytes <= kLdsBufLimit;
   g.lds_bytes = fix + (g.buf_lds ? buf_bytes : 0);
   g.gws_floats = g.buf_lds ? 0 : (int64_t)((buf_bytes / 4 + 63) & ~(size_t)63);
   int occ = (int)((160 * 1024 - 512) / g.lds_bytes);
-  if (occ > 2048 / kThreads) occ = 2048 / kThreads;
+  if (occ > 2048 / threads) occ = 2048 / threads;
   if (occ < 1) occ = 1;
   int64_t grid = (int64_t)ctx->num_cus * occ;
   if (grid > k) grid = k;
@@ -532,9 +593,10 @@ GatLayout gat_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
 
 // the matrix-core path for layer 1 applies to models with at least two layers and enough coalitions
 struct GatL1Layout {
-  bool use;
+  bool use, transpose;
   int32_t R1, E1, zwr, zwp;
-  size_t az_bytes, h1_bytes, lds_bytes;
+  int64_t KW;
+  size_t az_bytes, h1_bytes, zt_bytes, lds_bytes;
   int grid;
 };
 
@@ -553,8 +615,15 @@ GatL1Layout gat_l1_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
   q.az_bytes = ((size_t)E1 + q.R1) * q.zwp * 4;
   q.h1_bytes = (size_t)k * q.R1 * ctx->gat.zw[0] * 4;
   if (q.az_bytes > ((size_t)256 << 20) || q.h1_bytes > ((size_t)2 << 30)) return q;
-  q.lds_bytes = (size_t)kWaves * (32 * 64 + 2 * 32 * 33) * 4;
-  const int64_t blocks = (k + 63) / 64;
+  // the 0/1 operand is read from a transposed copy of the mask matrix (one word = one player for 64
+  // coalitions); when that copy would be out of proportion the per-coalition kernel does every layer
+  const size_t W = (size_t)(cg->info.num_players + 63) / 64;
+  q.KW = (k + 63) / 64;
+  q.transpose = true;
+  if ((size_t)k * W * 8 > ((size_t)1 << 30) || q.E1 > kL1MaxEntries) return q;
+  q.zt_bytes = (size_t)cg->info.num_players * q.KW * 8;
+  q.lds_bytes = (((size_t)2 * (q.E1 + 2) * 8 + 15) & ~(size_t)15) + (size_t)kWaves * kL1WaveFloats * 4;
+  const int64_t blocks = (k + 127) / 128;
   const int64_t cap = (int64_t)ctx->num_cus * 2;
   q.grid = (int)(blocks < cap ? blocks : cap);
   q.use = true;
@@ -593,9 +662,15 @@ void gat_fill(const ds_ctx* ctx, const ds_cgraph* cg, const GatLayout& g, GatArg
 }
 
 int gat_launch(ds_ctx* ctx, const GatArgs& a, const GatLayout& g, int grid) {
-  if (g.lds_bytes > 48 * 1024)
-    DS_HIP(ctx, hipFuncSetAttribute((const void*)masked_gat_eval_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes));
-  hipLaunchKernelGGL(masked_gat_eval_kernel, dim3(grid), dim3(kThreads), g.lds_bytes, ctx->stream, a);
+  if (g.threads == 64) {
+    if (g.lds_bytes > 48 * 1024)
+      DS_HIP(ctx, hipFuncSetAttribute((const void*)masked_gat_eval_wave_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes));
+    hipLaunchKernelGGL(masked_gat_eval_wave_kernel, dim3(grid), dim3(64), g.lds_bytes, ctx->stream, a);
+  } else {
+    if (g.lds_bytes > 48 * 1024)
+      DS_HIP(ctx, hipFuncSetAttribute((const void*)masked_gat_eval_kernel<kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes));
+    hipLaunchKernelGGL(masked_gat_eval_kernel<kThreads>, dim3(grid), dim3(kThreads), g.lds_bytes, ctx->stream, a);
+  }
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }
@@ -603,10 +678,12 @@ int gat_launch(ds_ctx* ctx, const GatArgs& a, const GatLayout& g, int grid) {
 }  // namespace
 
 size_t ds_gat_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
-  const GatLayout g = gat_layout(ctx, cg, k > 1 ? k : 1);
-  const size_t W = (cg->info.num_players + 63) / 64;
   const GatL1Layout q = gat_l1_layout(ctx, cg, k);
-  return (q.use ? ds_align(q.az_bytes) + ds_align(q.h1_bytes) + 512 : 0) + ds_align((size_t)g.gws_floats * 4 * g.grid) + ds_align((size_t)g.gws_floats * 4) + ds_align(W * 8 + 8) +
+  const GatLayout g = gat_layout(ctx, cg, k > 1 ? k : 1, q.use ? 64 : kThreads);
+  const GatLayout g1 = gat_layout(ctx, cg, 1);
+  const size_t W = (cg->info.num_players + 63) / 64;
+  return (q.use ? ds_align(q.az_bytes) + ds_align(q.h1_bytes) + ds_align(q.zt_bytes + 8) + ds_align((size_t)q.R1 * 32 * 4) + 1024 : 0) +
+         ds_align((size_t)g1.gws_floats * 4) + ds_align((size_t)g.gws_floats * 4 * g.grid) + ds_align((size_t)g.gws_floats * 4) + ds_align(W * 8 + 8) +
          ds_align(ctx->dims[ctx->L] * 4 + 8) + 1024;
 }
 
@@ -651,7 +728,8 @@ int ds_gat_prepare_model(ds_ctx* ctx, ds_cgraph* cg) {
 int ds_gat_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y) {
   DS_TRY(ds_gat_prepare_model(ctx, cg));
   if (k <= 0) return DS_OK;
-  const GatLayout g = gat_layout(ctx, cg, k);
+  const GatL1Layout q = gat_l1_layout(ctx, cg, k);
+  const GatLayout g = gat_layout(ctx, cg, k, q.use ? 64 : kThreads);
   float* gws = nullptr;
   if (g.gws_floats) {
     gws = (float*)ds_arena_alloc(ctx, (size_t)g.gws_floats * 4 * g.grid);
@@ -666,28 +744,34 @@ int ds_gat_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, i
   a.gws = gws;
   a.score = score;
   a.pred_ptr = cg->d_pred;
-  const GatL1Layout q = gat_l1_layout(ctx, cg, k);
   GatL1Args l1;
+  uint64_t* Zt_w = nullptr;
   if (q.use) {
     float* Az = (float*)ds_arena_alloc(ctx, q.az_bytes);
     float* h1 = (float*)ds_arena_alloc(ctx, q.h1_bytes);
     int32_t* bad = (int32_t*)ds_arena_alloc(ctx, 256);
-    if (!Az || !h1 || !bad) return ds_fail(ctx, DS_EINTERNAL, "eval: arena exhausted");
+    float* rowmax = (float*)ds_arena_alloc(ctx, (size_t)q.R1 * 32 * 4);
+    uint64_t* Zt = q.transpose ? (uint64_t*)ds_arena_alloc(ctx, q.zt_bytes + 8) : nullptr;
+    if (!Az || !h1 || !bad || !rowmax || (q.transpose && !Zt)) return ds_fail(ctx, DS_EINTERNAL, "eval: arena exhausted");
     memset(&l1, 0, sizeof(l1));
     l1.V = a.V; l1.R1 = q.R1; l1.E1 = q.E1; l1.H = a.heads[0]; l1.F = a.fh[0]; l1.zw = a.zw[0];
     l1.zwr = q.zwr; l1.zwp = q.zwp; l1.concat_elu = 1;
     l1.W = a.W; l1.k = k;
     l1.row_ptr = a.row_ptr; l1.col = a.col; l1.eid = a.eid;
     l1.P = a.P; l1.att1 = a.att1; l1.bias = a.bias[0]; l1.slope = a.slope;
-    l1.Az = Az; l1.bad = bad; l1.Z = Z; l1.h1 = h1;
+    l1.Az = Az; l1.bad = bad; l1.h1 = h1;
+    l1.rowmax = rowmax; l1.Zt = Zt; l1.KW = q.KW;
+    Zt_w = Zt;
     a.h1 = h1;
     a.h1_bad = bad;
   }
   DS_TRY(ds_kernel_mark(ctx, 0, 0));
   if (q.use) {
     DS_HIP(ctx, hipMemsetAsync(l1.bad, 0, sizeof(int32_t), ctx->stream));
-    hipLaunchKernelGGL(gat_entry_weights_kernel, dim3(q.R1), dim3(kThreads), 0, ctx->stream, l1);
+    hipLaunchKernelGGL(gat_row_max_kernel, dim3(q.R1), dim3(kThreads), 0, ctx->stream, l1);
+    hipLaunchKernelGGL(gat_entry_weights_kernel, dim3((q.E1 + q.R1 + kWaves - 1) / kWaves), dim3(kThreads), 0, ctx->stream, l1);
     DS_HIP(ctx, hipGetLastError());
+    if (q.transpose) DS_TRY(ds_bit_transpose(ctx, Z, k, cg->info.num_players, a.W, 0, 1, Zt_w));
     if (q.lds_bytes > 48 * 1024)
       DS_HIP(ctx, hipFuncSetAttribute((const void*)masked_gat_layer1_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)q.lds_bytes));
     hipLaunchKernelGGL(masked_gat_layer1_mfma_kernel, dim3(q.grid), dim3(kThreads), q.lds_bytes, ctx->stream, l1);
