@@ -477,6 +477,68 @@ __global__ __launch_bounds__(kThreads) void chol_back_step_kernel(const double* 
   }
 }
 
+// The same back substitution for small systems (n <= kBackSmallMax) in ONE launch: a single workgroup of
+// 512 threads keeps the right-hand side in LDS and walks the blocks from the end; per block the 64 unknowns
+// come from the stored inverse (8 partial sums each, added in a fixed order), then every earlier entry
+// drops their contribution. At this size the chain of per-block launches costs more than the arithmetic.
+constexpr int kBackSmallMax = 2048;
+constexpr int kBackThreads = 512;
+__global__ __launch_bounds__(kBackThreads) void chol_back_small_kernel(const double* M, int64_t ld, int64_t n, int nblk,
+                                                                       const double* linv, const float* y01, float* phi) {
+  __shared__ double ys[kBackSmallMax];
+  __shared__ double xs[NB];
+  __shared__ double part[kBackThreads / NB][NB];
+  const int tid = threadIdx.x;
+  for (int j = tid; j < n; j += kBackThreads) ys[j] = M[n * ld + j];
+  const double shift = ((double)y01[1] - (double)y01[0]) / (double)n;
+  __syncthreads();
+  // entries of the block inverse this thread multiplies: column c, rows c + q + 16 i (fetched one block ahead,
+  // so that the only memory wait inside a step is the update's own)
+  constexpr int kLi = NB / (kBackThreads / NB);
+  const int c = tid & (NB - 1), q = tid / NB;
+  double lv[kLi];
+  auto fetch_li = [&](int bk) {
+    const double* li = linv + (size_t)bk * NB * NB;
+#pragma unroll
+    for (int i = 0; i < kLi; ++i) {
+      const int r = c + q + (kBackThreads / NB) * i;
+      lv[i] = r < NB ? li[r * NB + c] : 0.0;  // rows past a short last block are skipped in the product
+    }
+  };
+  fetch_li(nblk - 1);
+  for (int bk = nblk - 1; bk >= 0; --bk) {
+    const int j0 = bk * NB;
+    const int nb = (int)(n - j0 < NB ? n - j0 : NB);
+    {
+      double s = 0.0;
+#pragma unroll
+      for (int i = 0; i < kLi; ++i) {
+        const int r = c + q + (kBackThreads / NB) * i;
+        if (r < nb) s += lv[i] * ys[j0 + r];
+      }
+      part[q][c] = s;
+    }
+    if (bk > 0) fetch_li(bk - 1);
+    __syncthreads();
+    if (tid < NB) {
+      double s = 0.0;
+#pragma unroll
+      for (int qq = 0; qq < kBackThreads / NB; ++qq) s += part[qq][tid];
+      xs[tid] = s;
+      if (tid < nb) phi[j0 + tid] = (float)(s + shift);
+    }
+    __syncthreads();
+    for (int j = tid; j < j0; j += kBackThreads) {
+      double s = 0.0;
+      const double* mp = M + (size_t)j0 * ld + j;
+#pragma unroll 32
+      for (int r = 0; r < NB; ++r) s += (r < nb ? mp[(size_t)r * ld] : 0.0) * xs[r];
+      ys[j] -= s;
+    }
+    __syncthreads();
+  }
+}
+
 __global__ void copy_row_kernel(const double* M, int64_t ld, int64_t n, double* yv) {
   const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (j < n) yv[j] = M[n * ld + j];
@@ -600,6 +662,9 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
     }
   }
   DS_TRY(ds_kernel_mark(ctx, 2, 1));
+  if (n <= kBackSmallMax) {
+    hipLaunchKernelGGL(chol_back_small_kernel, dim3(1), dim3(kBackThreads), 0, st, M, ld, n, (int)gs->nblk, linv, y, phi);
+  } else {
   hipLaunchKernelGGL(copy_row_kernel, dim3(nblocks(n, 256)), dim3(256), 0, st, M, ld, n, gs->yv);
   for (int64_t bk = gs->nblk - 1; bk >= 0; --bk) {
     const int64_t j0 = bk * NB;
@@ -609,6 +674,7 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
                        linv + (size_t)bk * NB * NB, gs->yv, gs->c);  // c is free again: it receives psi
   }
   hipLaunchKernelGGL(finish_phi_kernel, dim3(nblocks(n, 256)), dim3(256), 0, st, gs->c, y, n, phi);
+  }
   DS_HIP(ctx, hipGetLastError());
   DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, gs->flag, sizeof(int), hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipStreamSynchronize(st));
