@@ -239,8 +239,10 @@ __device__ __forceinline__ double fast_rsqrt(double p) {
 // rank-1 updates to its registers at once. (64 is a multiple of kCw; padding rows are identity rows.)
 constexpr int kCw = 4;
 
-__global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t ld, int64_t j0, int nb, double* linv_out,
-                                                             int* flag) {
+// `pend`: optional 64 x 64 tile (LDS, pitch NB+1) holding the rows of this block in the panel just finished;
+// its outer product is the one trailing update the block has not received yet and is subtracted first.
+__device__ __forceinline__ void chol_diag_body(double* M, int64_t ld, int64_t j0, int nb, double* linv_out, int* flag,
+                                               const double (*pend)[NB + 1]) {
   __shared__ double cols[2][kCw][NB];
   __shared__ double rows[2][kCw][NB];
   __shared__ double dinv[NB];
@@ -254,6 +256,21 @@ __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t 
       s[i][j] = (r < nb && c < nb) ? M[(j0 + r) * ld + j0 + c] : (r == c ? 1.0 : 0.0);
       y[i][j] = r == c ? 1.0 : 0.0;
     }
+  if (pend) {  // rows past nb of the tile are zero, so the identity padding stays as it is
+#pragma unroll 4
+    for (int k = 0; k < NB; ++k) {
+      double pr[4], pc[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        pr[i] = pend[ty + 16 * i][k];
+        pc[i] = pend[tx + 16 * i][k];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s[i][j] = fma(-pr[i], pc[j], s[i][j]);
+    }
+  }
   bool bad = false;
   for (int kk = 0; kk < NB; kk += kCw) {
     const int buf = (kk / kCw) & 1, blk = kk >> 4, off = kk & 15;  // the kCw columns lie in one 16-block
@@ -352,6 +369,11 @@ __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t 
     }
 }
 
+__global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t ld, int64_t j0, int nb, double* linv_out,
+                                                             int* flag) {
+  chol_diag_body(M, ld, j0, nb, linv_out, flag, nullptr);
+}
+
 typedef double double4_t __attribute__((ext_vector_type(4)));
 
 // acc (+)= A[64 x 64] * B[64 x 64]^T for 64x64 tiles held in LDS with row pitch NB+1, on the fp64
@@ -407,9 +429,15 @@ __global__ __launch_bounds__(kThreads) void chol_panel_kernel(double* M, int64_t
   }
 }
 
-// trailing update A22 -= L21 L21^T on the lower tiles (rows up to rows_total, columns below n)
+// trailing update A22 -= L21 L21^T on the lower tiles (rows up to rows_total, columns below n).
+// The workgroup of the first diagonal tile does more: that tile is the next diagonal block, so it applies the
+// tile's update in registers and factorises it straight away (and stores its inverse), while the other
+// workgroups are still updating the rest of the trailing matrix. The next step then starts at its panel.
+// (FUSE = false: plain update of every tile; used while the trailing matrix is large, where the registers of
+// the factorisation would halve the number of resident update workgroups for no gain.)
+template <bool FUSE>
 __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_t ld, int64_t rows_total, int64_t n,
-                                                               int64_t j0, int nb) {
+                                                               int64_t j0, int nb, double* linv_next, int* flag) {
   const int ti = blockIdx.y, tj = blockIdx.x;
   if (tj > ti) return;
   __shared__ double Li[kTile][NB + 1];
@@ -422,6 +450,17 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_
     Lj[r][c] = (c0 + r < n && c < nb) ? M[(c0 + r) * ld + j0 + c] : 0.0;
   }
   __syncthreads();
+  if (FUSE && ti == 0 && tj == 0) {  // Lj holds the rows of the next diagonal block in this panel (zero past column n)
+    // a short last block shares its tile with the right-hand-side row, which still needs this update
+    if (n - base < NB && (int64_t)threadIdx.x < n - base) {
+      const int rr = (int)(n - base), c = threadIdx.x;
+      double sum = 0.0;
+      for (int k = 0; k < NB; ++k) sum += Li[rr][k] * Lj[c][k];
+      M[n * ld + base + c] -= sum;
+    }
+    chol_diag_body(M, ld, base, (int)(n - base < NB ? n - base : NB), linv_next, flag, Lj);
+    return;
+  }
   double4_t acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -482,6 +521,7 @@ __global__ __launch_bounds__(kThreads) void chol_back_step_kernel(const double* 
 // come from the stored inverse (8 partial sums each, added in a fixed order), then every earlier entry
 // drops their contribution. At this size the chain of per-block launches costs more than the arithmetic.
 constexpr int kBackSmallMax = 2048;
+constexpr int64_t kFuseMaxRows = 2048;  // trailing rows up to which the update also factorises the next block
 constexpr int kBackThreads = 512;
 __global__ __launch_bounds__(kBackThreads) void chol_back_small_kernel(const double* M, int64_t ld, int64_t n, int nblk,
                                                                        const double* linv, const float* y01, float* phi) {
@@ -650,15 +690,25 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
   DS_HIP(ctx, hipGetLastError());
   DS_TRY(ds_kernel_mark(ctx, 2, 0));
   const int64_t rows_total = n + 1;  // row n carries the right-hand side
+  bool diag_done = false;
   for (int64_t j0 = 0; j0 < n; j0 += NB) {
     const int nb = (int)(n - j0 < NB ? n - j0 : NB);
     double* li = linv + (size_t)(j0 / NB) * NB * NB;
-    hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, j0, nb, li, gs->flag);
+    // a diagonal block has a launch of its own only if the update before it did not factorise it already
+    if (!diag_done) hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, j0, nb, li, gs->flag);
+    diag_done = false;
     const int64_t rest = rows_total - j0 - nb;
     hipLaunchKernelGGL(chol_panel_kernel, dim3(nblocks(rest, kTile)), dim3(kThreads), 0, st, M, ld, rows_total, j0, nb, li);
     if (n - j0 - nb > 0) {
       const unsigned tt = nblocks(rest, kTile);
-      hipLaunchKernelGGL(chol_update_kernel, dim3(tt, tt), dim3(kThreads), 0, st, M, ld, rows_total, n, j0, nb);
+      if (rest <= kFuseMaxRows) {
+        hipLaunchKernelGGL(chol_update_kernel<true>, dim3(tt, tt), dim3(kThreads), 0, st, M, ld, rows_total, n, j0, nb,
+                           li + (size_t)NB * NB, gs->flag);
+        diag_done = true;
+      } else {
+        hipLaunchKernelGGL(chol_update_kernel<false>, dim3(tt, tt), dim3(kThreads), 0, st, M, ld, rows_total, n, j0, nb,
+                           (double*)nullptr, gs->flag);
+      }
     }
   }
   DS_TRY(ds_kernel_mark(ctx, 2, 1));
