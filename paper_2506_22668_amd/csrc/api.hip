@@ -542,16 +542,8 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
     hipLaunchKernelGGL(single_player_kernel, dim3(1), dim3(1), 0, st, y, phi);
   } else if (direct) {
     DS_HIP(ctx, hipStreamWaitEvent(st, ctx->join2_ev, 0));
-    rc = ds_gram_finish(ctx, &gs, Z, w, y, phi);
+    rc = ds_gram_finish(ctx, &gs, Z, w, y, phi, 1);  // the pivot flag comes back with the final read-back
     rep.solver_used = DS_SOLVER_GRAM_CHOL;
-    if (rc == DS_ESINGULAR && o.solver == DS_SOLVER_AUTO) {  // rank-deficient: the minimum-norm solve instead
-      int iters = 0;
-      double rel = 0.0;
-      rc = ds_solve_cgls_impl(ctx, n, k, Z, w, y, 1, o.tol, o.max_iter, phi, &iters, &rel);
-      rep.solver_used = DS_SOLVER_CGLS;
-      rep.cgls_iterations = iters;
-      rep.cgls_rel_residual = rel;
-    }
   } else {
     rc = solve_dispatch(ctx, n, k, Z, w, y, o, 1, phi, &rep);
   }
@@ -562,9 +554,25 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   DS_HIP(ctx, hipMemcpyAsync(f01, y, 2 * sizeof(float), hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + 34, cg->d_pred, sizeof(int32_t), hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + DS_MAIL_SAMPLER, ctx->d_mail + DS_MAIL_SAMPLER, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  ctx->h_mail[36] = 0;
+  if (direct) DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + 36, gs.flag, sizeof(int), hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipStreamSynchronize(st));
   if (n >= 2 && ctx->h_mail[DS_MAIL_SAMPLER] != 0)
     return ds_fail(ctx, DS_EINTERNAL, "sampler: candidate list overflow (too many keys share a 24-bit prefix)");
+  if (direct && *(int*)(ctx->h_mail + 36) != 0) {
+    if (o.solver != DS_SOLVER_AUTO)
+      return ds_fail(ctx, DS_ESINGULAR, "Cholesky met a non-positive pivot: the sampled rows do not determine all %lld players", (long long)n);
+    // rank-deficient: the minimum-norm solve instead
+    int iters = 0;
+    double rel = 0.0;
+    rc = ds_solve_cgls_impl(ctx, n, k, Z, w, y, 1, o.tol, o.max_iter, phi, &iters, &rel);
+    rep.solver_used = DS_SOLVER_CGLS;
+    rep.cgls_iterations = iters;
+    rep.cgls_rel_residual = rel;
+    if (rc != DS_OK && rc != DS_ENOTCONV) return rc;
+    DS_HIP(ctx, hipEventRecord(ctx->ev[4], st));
+    DS_HIP(ctx, hipStreamSynchronize(st));
+  }
   rep.f_empty = f01[0];
   rep.f_full = f01[1];
   rep.pred_class = *(int32_t*)(ctx->h_mail + 34);

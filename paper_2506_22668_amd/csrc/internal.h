@@ -174,7 +174,9 @@ struct ds_gram_state {
   int* flag;
 };
 int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, int paired, ds_gram_state* gs);
-int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, const float* w, const float* y, float* phi);
+// defer_check != 0: the non-positive-pivot flag (gs->flag, device int) is left for the caller to read back
+int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, const float* w, const float* y, float* phi,
+                    int defer_check);
 int ds_solve_gram_chol(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y,
                        int paired, float* phi);
 size_t ds_gram_arena_bytes(int64_t n, int64_t k);
