@@ -10,7 +10,9 @@
 //
 // G[a][b] = sum_i w_i z_ia z_ib is computed from the transposed bit matrix: a
 // 64-row word whose rows share one weight contributes w * popcount(col_a & col_b);
-// a word that straddles weight classes walks the set bits of the AND.
+// a word that straddles weight classes is a dense 64-row contraction on the matrix cores.
+#include <stdlib.h>
+
 #include "internal.h"
 #include "solve_common.h"
 
@@ -38,8 +40,14 @@ __global__ void used_row_rhs_kernel(const float* wc, const double* t, int64_t R,
   gc[r] = paired ? (double)wc[2 * r] * (t[2 * r] - t[2 * r + 1]) : (double)wc[r] * t[r];
 }
 
-// per word of 64 rows: the common weight, or non-uniform
-__global__ void word_weights_kernel(const float* w, int64_t k, int64_t KW, float* wu, int32_t* uni) {
+// per word of 64 rows: the common weight and how the Gram kernel treats the word:
+// 1 = one weight (popcount), 0 = mixed weights and sparse rows (walk the set bits of the AND),
+// 2 = mixed weights and dense rows (matrix cores). The density is read off the first row of the word
+// (rows are ordered by size): with a fraction p of the columns set, a pair of columns shares about 64 p^2
+// rows of the word, and walking them costs more than the fixed-price contraction from p of about 0.08 on (measured).
+constexpr float kDenseFraction = 0.08f;
+__global__ void word_weights_kernel(const float* w, int64_t k, int64_t KW, const uint64_t* Z, int64_t W, int64_t n,
+                                    int64_t row_step, float dense_fraction, float* wu, int32_t* uni) {
   const int64_t wd = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (wd >= KW) return;
   const int64_t i0 = wd * 64;
@@ -50,29 +58,55 @@ __global__ void word_weights_kernel(const float* w, int64_t k, int64_t KW, float
     if (i < k && w[i] != first) same = 0;
   }
   wu[wd] = first;
-  uni[wd] = same;
+  int mode = same;
+  if (!same) {
+    const uint64_t* zr = Z + i0 * row_step * W;
+    int64_t c = 0;
+    for (int64_t x = 0; x < W; ++x) c += __popcll(zr[x]);
+    if ((float)c > dense_fraction * (float)n) mode = 2;
+  }
+  uni[wd] = mode;
 }
 
 // One 64x64 tile of G per workgroup and slice of the row words (split-K); each slice
 // writes its own full symmetric partial matrix, summed later in a fixed order.
+// A word of 64 rows that share one weight costs an AND and a popcount per pair of columns. A word that
+// straddles weight classes (most words past the first few classes: a class soon has fewer than 64 rows)
+// either walks the set bits of the AND (sparse rows) or, when its rows are dense, is treated as the small
+// dense contraction it is, sum_r (w_r z_ra) z_rb, on the fp32 matrix cores:
+// v_mfma_f32_32x32x2f32, lane l supplies A[m = l%32][k = l/32] = w_r * bit r of column m's word and
+// B[k][n = l%32] = bit r of column n's word, r = 2q + l/32; each wave owns a 32x32 quadrant of the tile
+// (accumulator register i of lane l is D[8*(i/4) + 4*(l/32) + i%4][l%32]). Both paths add up in fp32
+// within a chunk of 32 words and in fp64 across chunks.
+typedef float gram_f16_t __attribute__((ext_vector_type(16)));
+
 __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int64_t n, int64_t k, int64_t KW,
                                                         const float* w, const float* wu, const int32_t* uni,
                                                         double* Gp, int64_t words_per_slice) {
   const int ta = blockIdx.y, tb = blockIdx.x;
   if (tb > ta) return;
-  __shared__ uint64_t As[kTile][kChunk + 1];
-  __shared__ uint64_t Bs[kTile][kChunk + 1];
+  // As | Bs during the accumulation; reused as one 64 x 65 fp64 tile when the two paths are merged
+  __shared__ __attribute__((aligned(16))) uint64_t raw[2 * kTile * (kChunk + 1)];
+  static_assert(sizeof(uint64_t) * 2 * kTile * (kChunk + 1) >= sizeof(double) * kTile * (kTile + 1), "merge tile must fit");
+  uint64_t (*As)[kChunk + 1] = (uint64_t (*)[kChunk + 1])raw;
+  uint64_t (*Bs)[kChunk + 1] = (uint64_t (*)[kChunk + 1])(raw + kTile * (kChunk + 1));
   __shared__ float wrow[kChunk * 64];
   __shared__ float wus[kChunk];
   __shared__ int unis[kChunk];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+  const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
   const int64_t a0 = (int64_t)ta * kTile, b0 = (int64_t)tb * kTile;
   double* G = Gp + (size_t)blockIdx.z * n * n;
   const int64_t wbeg = (int64_t)blockIdx.z * words_per_slice;
   const int64_t wend = wbeg + words_per_slice < KW ? wbeg + words_per_slice : KW;
-  double acc[4][4];
+  double acc[4][4];   // popcount path: elements (ty + 16 i, tx + 16 j)
+  double accm[16];    // matrix-core path: elements (wi + 8*(i/4) + 4*half + i%4, wj + l32)
   for (int i = 0; i < 4; ++i)
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+    for (int j = 0; j < 4; ++j) {
+      acc[i][j] = 0.0;
+      accm[4 * i + j] = 0.0;
+    }
   for (int64_t wd0 = wbeg; wd0 < wend; wd0 += kChunk) {
     __syncthreads();
     for (int idx = tid; idx < kTile * kChunk; idx += kThreads) {
@@ -94,44 +128,74 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
     float f[4][4];
     for (int i = 0; i < 4; ++i)
       for (int j = 0; j < 4; ++j) f[i][j] = 0.f;
-    for (int c = 0; c < kChunk; ++c) {
-      uint64_t av[4], bv[4];
+    gram_f16_t fm0, fm1;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        av[i] = As[ty + 16 * i][c];
-        bv[i] = Bs[tx + 16 * i][c];
-      }
-      if (unis[c]) {
+    for (int i = 0; i < 16; ++i) { fm0[i] = 0.f; fm1[i] = 0.f; }
+    for (int c = 0; c < kChunk; ++c) {
+      if (unis[c] == 1) {
+        uint64_t av[4], bv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          av[i] = As[ty + 16 * i][c];
+          bv[i] = Bs[tx + 16 * i][c];
+        }
         const float wv = wus[c];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
           for (int j = 0; j < 4; ++j) f[i][j] += wv * (float)__popcll(av[i] & bv[j]);
+      } else if (unis[c] == 2) {
+        const uint64_t aw = As[wi + l32][c] >> half, bw = Bs[wj + l32][c] >> half;  // bit 2q of these = row 2q + half
+        const float* wr = wrow + c * 64 + half;
+#pragma unroll
+        for (int q = 0; q < 32; q += 2) {
+          const float a0v = ((aw >> (2 * q)) & 1ull) ? wr[2 * q] : 0.f;
+          const float b0v = (float)((uint32_t)(bw >> (2 * q)) & 1u);
+          const float a1v = ((aw >> (2 * q + 2)) & 1ull) ? wr[2 * q + 2] : 0.f;
+          const float b1v = (float)((uint32_t)(bw >> (2 * q + 2)) & 1u);
+          fm0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b0v, fm0, 0, 0, 0);
+          fm1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b1v, fm1, 0, 0, 0);
+        }
       } else {
+        uint64_t av[4], bv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          av[i] = As[ty + 16 * i][c];
+          bv[i] = Bs[tx + 16 * i][c];
+        }
         const float* wr = wrow + c * 64;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             uint64_t m = av[i] & bv[j];
-            float s = 0.f;
+            float sum = 0.f;
             while (m) {
-              s += wr[__ffsll((long long)m) - 1];
+              sum += wr[__ffsll((long long)m) - 1];
               m &= m - 1;
             }
-            f[i][j] += s;
+            f[i][j] += sum;
           }
       }
     }
     for (int i = 0; i < 4; ++i)
       for (int j = 0; j < 4; ++j) acc[i][j] += (double)f[i][j];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) accm[i] += (double)fm0[i] + (double)fm1[i];
   }
+  // merge: the matrix-core quadrants pass through LDS into the popcount path's element order
+  __syncthreads();
+  double (*Ts)[kTile + 1] = (double (*)[kTile + 1])raw;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) Ts[wi + 8 * (i / 4) + 4 * half + (i % 4)][wj + l32] = accm[i];
+  __syncthreads();
   for (int i = 0; i < 4; ++i)
     for (int j = 0; j < 4; ++j) {
       const int64_t a = a0 + ty + 16 * i, b = b0 + tx + 16 * j;
       if (a < n && b < n) {
-        G[a * n + b] = acc[i][j];
-        G[b * n + a] = acc[i][j];
+        const double v = acc[i][j] + Ts[ty + 16 * i][tx + 16 * j];
+        G[a * n + b] = v;
+        G[b * n + a] = v;
       }
     }
 }
@@ -591,6 +655,15 @@ __global__ void finish_phi_kernel(const double* psi, const float* y01, int64_t n
   phi[j] = (float)(psi[j] + delta / (double)n);
 }
 
+// tuning knob: DISTSHAP_GRAM_DENSE overrides the density from which mixed-weight words use the matrix cores
+inline float dense_fraction() {
+  static const float v = [] {
+    const char* e = getenv("DISTSHAP_GRAM_DENSE");
+    return e ? (float)atof(e) : kDenseFraction;
+  }();
+  return v;
+}
+
 inline unsigned nblocks(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
 struct GramDims {
@@ -662,7 +735,8 @@ int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const fl
     return ds_fail(ctx, DS_EINTERNAL, "gram: arena exhausted");
   hipLaunchKernelGGL(used_row_weights_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, w, R, paired, gw);
   DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, gs->Zt));
-  hipLaunchKernelGGL(word_weights_kernel, dim3(nblocks(RW, 256)), dim3(256), 0, st, gw, R, RW, wu, uni);
+  hipLaunchKernelGGL(word_weights_kernel, dim3(nblocks(RW, 256)), dim3(256), 0, st, gw, R, RW, Z, W, n,
+                     (int64_t)(paired ? 2 : 1), dense_fraction(), wu, uni);
   const unsigned tiles = nblocks(n, kTile);
   DS_TRY(ds_kernel_mark(ctx, 1, 0));
   hipLaunchKernelGGL(gram_kernel, dim3(tiles, tiles, d.slices), dim3(kThreads), 0, st, gs->Zt, n, R, RW, gw, wu, uni, Gp,

@@ -70,6 +70,26 @@ def test_small_underdetermined_config_cgls_minimum_norm():
     _explain_case("c4_small", 1e-4, oracle_solver="cgls")
 
 
+def test_underdetermined_config_direct_solver_reports_and_auto_falls_back():
+    """Fewer rows than players: the direct solver inside ds_explain must report the singular system (its pivot
+    flag only reaches the host with the final read-back), and solver AUTO must then give the minimum-norm
+    solution of CGLS."""
+    from paper_2506_22668_amd import DistShapError, DS_ESINGULAR, DS_SOLVER_CGLS, Options
+    w = make_workload("c4_small")
+    ctx = make_context(w)
+    target = w.targets[0]
+    say(f"explain c4_small target={target} with the direct solver and with AUTO")
+    with pytest.raises(DistShapError) as e:
+        ctx.explain(target, w.n_samples, w.seed, Options(solver=1))
+    assert e.value.code == DS_ESINGULAR
+    phi, es, ed, rep, rc = ctx.explain(target, w.n_samples, w.seed, Options(solver=0, tol=w.tol))
+    assert rep.solver_used == DS_SOLVER_CGLS and rep.cgls_iterations > 0
+    ref = oexplain.explain(w.row_ptr, w.col, w.features, w.weights, target, w.n_samples, w.seed, solver="cgls", tol=w.tol)
+    scale = np.abs(ref["phi"]).max()
+    assert np.abs(phi.cpu().numpy() - ref["phi"]).max() <= 1e-4 * scale
+    ctx.close()
+
+
 def test_small_batched_bf16_config():
     # oracle in the same reduced-precision reading: transform operands rounded to bf16
     _explain_case("c5_small", 1e-2)
