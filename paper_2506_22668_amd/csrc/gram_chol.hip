@@ -200,21 +200,27 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
     }
 }
 
-// G = sum of the slices (into slice 0) and the row means of G; one wave per row
+// G = sum of the slices (into slice 0) and the row means of G; one workgroup per row (grid-stride)
 __global__ __launch_bounds__(kThreads) void sum_slices_row_mean_kernel(double* Gp, int64_t n, int slices, double* m) {
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-  for (int64_t a = wave; a < n; a += nwaves) {
+  __shared__ double red[kThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int64_t a = blockIdx.x; a < n; a += gridDim.x) {
     double s = 0.0;
-    for (int64_t b = lane; b < n; b += 64) {
+    for (int64_t b = threadIdx.x; b < n; b += kThreads) {
       double g = Gp[a * n + b];
       for (int z = 1; z < slices; ++z) g += Gp[(size_t)z * n * n + a * n + b];
       Gp[a * n + b] = g;
       s += g;
     }
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    if (lane == 0) m[a] = s / (double)n;
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      for (int w = 0; w < kThreads / 64; ++w) t += red[w];  // fixed order
+      m[a] = t / (double)n;
+    }
+    __syncthreads();
   }
 }
 
@@ -742,7 +748,7 @@ int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const fl
   hipLaunchKernelGGL(gram_kernel, dim3(tiles, tiles, d.slices), dim3(kThreads), 0, st, gs->Zt, n, R, RW, gw, wu, uni, Gp,
                      d.words_per_slice);
   DS_TRY(ds_kernel_mark(ctx, 1, 1));
-  const unsigned wblocks = (unsigned)(((n * 64 + kThreads - 1) / kThreads) < (int64_t)ctx->num_cus * 8 ? ((n * 64 + kThreads - 1) / kThreads) : (int64_t)ctx->num_cus * 8);
+  const unsigned wblocks = (unsigned)(n < (int64_t)ctx->num_cus * 16 ? n : (int64_t)ctx->num_cus * 16);
   hipLaunchKernelGGL(sum_slices_row_mean_kernel, dim3(wblocks), dim3(kThreads), 0, st, Gp, n, d.slices, m);
   hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(kThreads), 0, st, Gp, m, n, stats);
   hipLaunchKernelGGL(build_matrix_kernel, dim3(nblocks(n * n, 256)), dim3(256), 0, st, Gp, m, stats, n, ld, gs->M);
