@@ -59,6 +59,13 @@ enum ds_dtype {
 
 enum ds_score { DS_SCORE_PROB = 0, DS_SCORE_LOGIT = 1 };
 enum ds_solver { DS_SOLVER_AUTO = 0, DS_SOLVER_GRAM_CHOL = 1, DS_SOLVER_CGLS = 2 };
+/* Regression weight of a sampled row (paper, "Shapley value" / sample-distribution equation: rho_s is the
+ * total kernel weight of the coalitions of size s and the rows are allocated in proportion to it).
+ * CLASS_MASS: a row of size s weighs rho_s / (rows of size s), so every represented size carries its whole
+ * mass. UNIFORM: every sampled row weighs 1, the importance-sampling form of the same estimator (the two
+ * differ through the rounding of the allocation and the classes that received no row). Enumerated
+ * explanations always use the exact kernel weights. */
+enum ds_weighting { DS_WEIGHT_CLASS_MASS = 0, DS_WEIGHT_UNIFORM = 1 };
 
 /* Options of an explanation. Zero-initialise for the defaults. */
 typedef struct ds_options {
@@ -74,6 +81,8 @@ typedef struct ds_options {
                          equal weights (the layout ds_sample writes), which lets CGLS read only
                          one member of each pair; 0 makes no assumption. ds_explain always
                          uses its own paired rows. */
+  int32_t weighting;  /* ds_weighting, honoured by ds_explain and ds_explain_batch (the stage-wise
+                         ds_sample / ds_plan_tables always use CLASS_MASS) */
 } ds_options;
 
 /* What an explanation did (all [host]). Times are wall-clock milliseconds measured

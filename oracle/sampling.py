@@ -43,9 +43,17 @@ def rho(n, s):
     return float(n - 1) / (float(s) * float(n - s))
 
 
-def allocation(n, n_samples):
+def allocation(n, n_samples, weighting="class"):
     """Class boundaries b[0..H], pairs per class q[1..H], weight table
-    wtab[1..H] (float32; entry 0 unused and zero)."""
+    wtab[1..H] (float32; entry 0 unused and zero).
+
+    weighting="class" (default): a row of size s weighs rho_s / (rows of that size).
+    weighting="uniform": every sampled row weighs 1 -- the rows are already allocated in
+    proportion to rho_s, so this is the importance-sampling form of the same estimator (it
+    differs from the default only through the rounding of the allocation and through classes
+    that received no row).  Enumerated plans keep the exact kernel weights."""
+    if weighting not in ("class", "uniform"):
+        raise ValueError("weighting must be 'class' or 'uniform'")
     k, enum = row_count(n, n_samples)
     H = n // 2
     out = {"n": n, "k": k, "enumerate": enum, "H": H}
@@ -74,7 +82,7 @@ def allocation(n, n_samples):
     for s in range(1, H + 1):
         m = int(q[s]) * (2 if 2 * s == n else 1)
         if m > 0:
-            wtab[s] = np.float32(rho(n, s) / float(m))
+            wtab[s] = np.float32(1.0) if weighting == "uniform" else np.float32(rho(n, s) / float(m))
     out.update(K=K, b=b, q=q, wtab=wtab, T=T)
     return out
 
@@ -114,11 +122,11 @@ def unpack_rows(Z, n):
     return np.unpackbits(by, axis=1, bitorder="little")[:, :n].astype(bool)
 
 
-def sample(n, n_samples, seed, tag, pair_range=None, chunk_elems=1 << 22):
+def sample(n, n_samples, seed, tag, pair_range=None, chunk_elems=1 << 22, weighting="class"):
     """Mask matrix Z (uint64[k, W]), weights w (float32[k]) and sizes sz
     (int32[k]).  With pair_range=(r0, r1) only the rows of pairs r0 <= r < r1
     are produced (rows 2*r0 .. 2*r1-1), identical to those of the full run."""
-    plan = allocation(n, n_samples)
+    plan = allocation(n, n_samples, weighting)
     k, K, wtab = plan["k"], plan["K"], plan["wtab"]
     r0, r1 = (0, k // 2) if pair_range is None else pair_range
     npairs = r1 - r0

@@ -12,6 +12,7 @@ DS_OK, DS_EINVAL, DS_ECAPACITY, DS_ENOMEM, DS_ENOTCONV, DS_EDEVICE, DS_ESINGULAR
 DS_F32, DS_BF16_IN_F32_ACC = 0, 1
 DS_SCORE_PROB, DS_SCORE_LOGIT = 0, 1
 DS_SOLVER_AUTO, DS_SOLVER_GRAM_CHOL, DS_SOLVER_CGLS = 0, 1, 2
+DS_WEIGHT_CLASS_MASS, DS_WEIGHT_UNIFORM = 0, 1
 
 EXPORTED_SYMBOLS = [
     "ds_create", "ds_destroy", "ds_last_error", "ds_set_graph", "ds_set_features", "ds_set_gcn", "ds_set_gat",
@@ -24,7 +25,7 @@ EXPORTED_SYMBOLS = [
 class Options(C.Structure):
     _fields_ = [("hops", C.c_int32), ("directed", C.c_int32), ("score", C.c_int32),
                 ("solver", C.c_int32), ("tol", C.c_double), ("max_iter", C.c_int32),
-                ("batch_rows", C.c_int32), ("paired", C.c_int32)]
+                ("batch_rows", C.c_int32), ("paired", C.c_int32), ("weighting", C.c_int32)]
 
 
 class Report(C.Structure):

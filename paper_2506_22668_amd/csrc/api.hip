@@ -471,7 +471,9 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   if (n == 1) {
     k = 2;
   } else {
-    DS_TRY(ds_make_plan(ctx, n, n_samples, &plan));
+    if (o.weighting != DS_WEIGHT_CLASS_MASS && o.weighting != DS_WEIGHT_UNIFORM)
+      return ds_fail(ctx, DS_EINVAL, "unknown weighting %d", o.weighting);
+    DS_TRY(ds_make_plan(ctx, n, n_samples, &plan, o.weighting));
     k = plan.k;
   }
   rep.num_rows = k;

@@ -8,7 +8,8 @@
 // classes sum to K exactly and pairs are laid out by ascending size. A row of
 // size s weighs rho_s / (number of emitted rows of size s), so each represented
 // size carries its whole kernel mass; under enumeration this is the Shapley
-// kernel weight itself.
+// kernel weight itself. (Option: every sampled row weighs 1 instead, the
+// importance-sampling form, since the allocation already follows rho_s.)
 //
 // Every operation that decides an integer is a single IEEE double + * / or floor
 // (no fused multiply-add: build with -ffp-contract=off), so the boundaries are
@@ -30,7 +31,7 @@ extern "C" int ds_sample_plan(int64_t n, int64_t n_samples, int64_t* k_out, int3
   return DS_OK;
 }
 
-int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan) {
+int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan, int weighting) {
   if (n < 2) return ds_fail(ctx, DS_EINVAL, "sampling needs at least 2 players (n=%lld)", (long long)n);
   if (n > 0x7fffffffLL) return ds_fail(ctx, DS_EINVAL, "too many players (n=%lld)", (long long)n);
   int32_t enumerate;
@@ -66,7 +67,7 @@ int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan) {
   plan->b[H] = K;
   for (int64_t s = 1; s <= H; ++s) {
     int64_t m = (plan->b[s] - plan->b[s - 1]) * ((2 * s == n) ? 2 : 1);
-    if (m > 0) plan->wtab[s] = (float)(rho_mass(n, s) / (double)m);
+    if (m > 0) plan->wtab[s] = weighting == DS_WEIGHT_UNIFORM ? 1.0f : (float)(rho_mass(n, s) / (double)m);
   }
   return DS_OK;
 }
@@ -74,7 +75,7 @@ int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan) {
 extern "C" int ds_plan_tables(int64_t n, int64_t n_samples, int64_t* b, float* wtab) {
   if (n < 2 || n > 0x7fffffffLL || n_samples < 0) return DS_EINVAL;
   ds_plan plan;
-  int rc = ds_make_plan(nullptr, n, n_samples, &plan);
+  int rc = ds_make_plan(nullptr, n, n_samples, &plan, DS_WEIGHT_CLASS_MASS);
   if (rc != DS_OK) return rc;
   for (int64_t s = 0; s <= plan.H; ++s) {
     if (b) b[s] = plan.b[s];

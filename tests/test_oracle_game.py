@@ -248,6 +248,56 @@ def test_sampled_estimate_approaches_exact_shapley():
     assert errs[1] < 0.05 * np.abs(exact).max() + 1e-3
 
 
+def test_uniform_weighting_is_the_importance_sampling_form_of_the_same_estimator():
+    """weighting="uniform": rows are already allocated in proportion to rho_s, so weight 1 per row is the
+    importance-sampling estimator. Pins: the allocation is untouched and the table is 1 on every class
+    that has rows; a linear game is still recovered exactly; the estimate approaches exact Shapley at
+    the same rate as the default; enumerated plans keep the exact kernel weights."""
+    a = sampling.allocation(30, 2000)
+    u = sampling.allocation(30, 2000, "uniform")
+    assert np.array_equal(a["b"], u["b"])
+    has_rows = np.diff(u["b"], prepend=0)[1:] > 0
+    assert np.array_equal(u["wtab"][1:], has_rows.astype(np.float32))
+    # where the allocation is exact the default weight is the same constant T / (2K) for every class
+    # (a pair class of mass 2 rho_s gets K 2 rho_s / T pairs, each with one row of size s; the middle class
+    # of an even n has mass rho_s and two rows per pair): uniform
+    # weights differ from it only by that common factor and by the rounding of the allocation
+    K = a["K"]
+    ratio = a["wtab"][1:][has_rows] * 2 * K / a["T"]
+    q = np.diff(a["b"], prepend=0)[1:][has_rows]
+    assert np.all(np.abs(ratio - 1.0) <= 1.2 / q + 1e-6)
+    e = sampling.allocation(10, 1 << 10, "uniform")
+    assert e["enumerate"] and np.array_equal(e["wtab"], sampling.allocation(10, 1 << 10)["wtab"])
+    with pytest.raises(ValueError):
+        sampling.allocation(30, 2000, "other")
+
+    rng = np.random.default_rng(0)
+    coef = rng.normal(size=14)
+    Z, wt, sz = sampling.sample(14, 400, 3, 0, weighting="uniform")
+    bits = sampling.unpack_rows(Z, 14)
+    assert set(np.unique(wt[2:])) == {np.float32(1.0)} and wt[0] == 0 and wt[1] == 0
+    phi = solve.solve_lstsq(bits, wt, 0.3 + bits @ coef)
+    assert np.abs(phi - coef).max() < 1e-10
+
+    w = make_workload("c1")
+    cg = compgraph.extract(w.row_ptr, w.col, 0, 2)
+    f = gcn.ValueFunction(cg, w.features, w.weights, dense=True)
+    vals = shapley.all_values(f, 12)
+    exact = shapley.exact_shapley(vals, 12)
+    err = {}
+    for mode in ("class", "uniform"):
+        for ns in (64, 1024):
+            e = []
+            for seed in range(6):
+                Z, wt, sz = sampling.sample(12, ns, seed, 0, weighting=mode)
+                bits = sampling.unpack_rows(Z, 12)
+                idx = (bits.astype(np.int64) << np.arange(12)).sum(axis=1)
+                e.append(np.abs(solve.solve_lstsq(bits, wt, vals[idx]) - exact).max())
+            err[mode, ns] = np.mean(e)
+    assert err["uniform", 1024] < 0.5 * err["uniform", 64]
+    assert 0.5 < err["uniform", 1024] / err["class", 1024] < 2.0
+
+
 def test_bf16_rounding_is_nearest_even():
     # bfloat16 keeps 8 significand bits: spacing 2^-7 in [1, 2)
     assert gcn.round_bf16(1.0) == 1.0
