@@ -553,6 +553,61 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_
   }
 }
 
+// Trailing update of a whole super-panel: A22 -= L21 L21^T with L21 = the kw (a multiple of 64) columns
+// starting at J, on the lower 64x64 tiles of the matrix from row/column `base` = J + kw on. The tile stays in
+// registers across the kw/64 column chunks, so it is read and written once per super-panel instead of once
+// per 64 columns; the next chunk of the two operands is fetched into registers while the matrix cores work on
+// the current one.
+__global__ __launch_bounds__(kThreads) void chol_update_wide_kernel(double* M, int64_t ld, int64_t rows_total, int64_t n,
+                                                                    int64_t J, int kw, int64_t base) {
+  const int ti = blockIdx.y, tj = blockIdx.x;
+  if (tj > ti) return;
+  __shared__ double Li[kTile][NB + 1];
+  __shared__ double Lj[kTile][NB + 1];
+  const int tid = threadIdx.x;
+  const int64_t i0 = base + (int64_t)ti * kTile, c0 = base + (int64_t)tj * kTile;
+  constexpr int kPer = kTile * NB / kThreads;
+  double pi[kPer], pj[kPer];
+  auto fetch = [&](int kc) {
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const int idx = tid + u * kThreads, r = idx >> 6, c = idx & 63;
+      pi[u] = i0 + r < rows_total ? M[(i0 + r) * ld + J + kc + c] : 0.0;
+      pj[u] = c0 + r < n ? M[(c0 + r) * ld + J + kc + c] : 0.0;
+    }
+  };
+  double4_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
+  fetch(0);
+  for (int kc = 0; kc < kw; kc += NB) {
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const int idx = tid + u * kThreads, r = idx >> 6, c = idx & 63;
+      Li[r][c] = pi[u];
+      Lj[r][c] = pj[u];
+    }
+    __syncthreads();
+    if (kc + NB < kw) fetch(kc + NB);
+    tile_nt_mfma(Li, Lj, acc);
+  }
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int64_t r = i0 + wi + 16 * i + 4 * r4 + (lane >> 4);
+        const int64_t c = c0 + wj + 16 * j + (lane & 15);
+        if (r < rows_total && c < n && c <= r) M[r * ld + c] -= acc[i][j][r4];
+      }
+}
+
 // L^T psi = y (y = row n of M after the factorisation), block by block from the end, using the stored
 // inverses of the diagonal blocks. One launch per block: every workgroup recomputes the 64 unknowns of
 // the block, psi_c = sum_{r >= c} Linv[r][c] y_r (cheap; workgroup 0 stores them), and removes their
@@ -591,7 +646,8 @@ __global__ __launch_bounds__(kThreads) void chol_back_step_kernel(const double* 
 // come from the stored inverse (8 partial sums each, added in a fixed order), then every earlier entry
 // drops their contribution. At this size the chain of per-block launches costs more than the arithmetic.
 constexpr int kBackSmallMax = 2048;
-constexpr int64_t kFuseMaxRows = 2048;  // trailing rows up to which the update also factorises the next block
+constexpr int64_t kFuseMaxRows = 2048;
+constexpr int64_t kSuperCols = 256;     // columns of a super-panel (large trailing matrices)  // trailing rows up to which the update also factorises the next block
 constexpr int kBackThreads = 512;
 __global__ __launch_bounds__(kBackThreads) void chol_back_small_kernel(const double* M, int64_t ld, int64_t n, int nblk,
                                                                        const double* linv, const float* y01, float* phi) {
@@ -771,8 +827,35 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
   DS_HIP(ctx, hipGetLastError());
   DS_TRY(ds_kernel_mark(ctx, 2, 0));
   const int64_t rows_total = n + 1;  // row n carries the right-hand side
+  // While the trailing matrix is large the blocks are taken four at a time (a super-panel of 256 columns):
+  // inside it the updates reach only the super-panel's own columns, and the rest of the trailing matrix is
+  // updated once with all 256 columns. Below kFuseMaxRows trailing rows: one block per step, the update
+  // factorising the next diagonal block on the way.
   bool diag_done = false;
-  for (int64_t j0 = 0; j0 < n; j0 += NB) {
+  int64_t j0 = 0;
+  while (j0 < n) {
+    const bool super = rows_total - j0 - kSuperCols > kFuseMaxRows && n - j0 >= kSuperCols + NB;
+    if (super) {
+      for (int b = 0; b < kSuperCols / NB; ++b) {
+        const int64_t jb = j0 + (int64_t)b * NB;
+        double* li = linv + (size_t)(jb / NB) * NB * NB;
+        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, jb, NB, li, gs->flag);
+        const int64_t rest = rows_total - jb - NB;
+        const unsigned tt = nblocks(rest, kTile);
+        hipLaunchKernelGGL(chol_panel_kernel, dim3(tt), dim3(kThreads), 0, st, M, ld, rows_total, jb, NB, li);
+        const unsigned inside = (unsigned)(kSuperCols / NB - 1 - b);  // block columns of the super-panel still ahead
+        if (inside > 0)
+          hipLaunchKernelGGL(chol_update_kernel<false>, dim3(inside, tt), dim3(kThreads), 0, st, M, ld, rows_total, n, jb,
+                             NB, (double*)nullptr, gs->flag);
+      }
+      const int64_t base = j0 + kSuperCols;
+      const unsigned tw = nblocks(rows_total - base, kTile);
+      hipLaunchKernelGGL(chol_update_wide_kernel, dim3(tw, tw), dim3(kThreads), 0, st, M, ld, rows_total, n, j0,
+                         (int)kSuperCols, base);
+      j0 += kSuperCols;
+      diag_done = false;
+      continue;
+    }
     const int nb = (int)(n - j0 < NB ? n - j0 : NB);
     double* li = linv + (size_t)(j0 / NB) * NB * NB;
     // a diagonal block has a launch of its own only if the update before it did not factorise it already
@@ -791,6 +874,7 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
                            (double*)nullptr, gs->flag);
       }
     }
+    j0 += nb;
   }
   DS_TRY(ds_kernel_mark(ctx, 2, 1));
   if (n <= kBackSmallMax) {

@@ -305,6 +305,24 @@ def test_cgls_reports_non_convergence(ctx_tiny):
     assert np.abs(phi.cpu().numpy() - ref2).max() <= 1e-4 * np.abs(ref2).max()
 
 
+def test_gram_cholesky_mid_size_crosses_every_factorisation_regime(ctx_tiny):
+    """2,700 players: the factorisation starts with super-panels of 256 columns (one wide trailing update each),
+    continues with single blocks and ends with the steps whose update factorises the next diagonal block; the
+    back substitution takes one launch per block."""
+    from paper_2506_22668_amd import Options, DS_SOLVER_GRAM_CHOL
+    ctx, _ = ctx_tiny
+    n, ns = 2700, 9000
+    say(f"gram+chol n={n} n_samples={ns}")
+    Z, w, bits, y = _solve_inputs(n, ns, 77)
+    ref = solve.solve_lstsq(bits, w, y)
+    phi, rep, rc = ctx.solve(n, torch.from_numpy(Z.view(np.int64)).cuda(), torch.from_numpy(w).cuda(),
+                             torch.from_numpy(y).cuda(), Options(solver=DS_SOLVER_GRAM_CHOL, paired=1))
+    got = phi.cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref).max()
+    say(f"  err={err:.2e} max|phi|={np.abs(ref).max():.2e}")
+    assert err <= 1e-4 * np.abs(ref).max()
+
+
 def test_rank_deficient_gram_is_reported_and_auto_falls_back(ctx_tiny):
     from paper_2506_22668_amd import Options, DistShapError, DS_SOLVER_GRAM_CHOL, DS_SOLVER_CGLS, DS_ESINGULAR
     ctx, _ = ctx_tiny
