@@ -47,25 +47,150 @@ __global__ void used_row_rhs_kernel(const float* wc, const double* t, int64_t R,
 // rows of the word, and walking them costs more than the fixed-price contraction from p of about 0.08 on (measured).
 constexpr float kDenseFraction = 0.08f;
 __global__ void word_weights_kernel(const float* w, int64_t k, int64_t KW, const uint64_t* Z, int64_t W, int64_t n,
-                                    int64_t row_step, float dense_fraction, float* wu, int32_t* uni) {
+                                    int64_t row_step, float dense_fraction, const uint64_t* keep, float* wu,
+                                    int32_t* uni) {
   const int64_t wd = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (wd >= KW) return;
   const int64_t i0 = wd * 64;
-  const float first = w[i0];
+  const uint64_t km = keep[wd];  // rows of this word that are left to the column-wise kernel
+  if (km == 0ull) {
+    wu[wd] = 0.f;
+    uni[wd] = 3;  // nothing to do
+    return;
+  }
+  const int fb = __ffsll((long long)km) - 1;
+  const float first = w[i0 + fb];
   int same = 1;
-  for (int b = 1; b < 64; ++b) {
+  for (int b = fb + 1; b < 64; ++b) {
     const int64_t i = i0 + b;
-    if (i < k && w[i] != first) same = 0;
+    if (((km >> b) & 1ull) && i < k && w[i] != first) same = 0;
   }
   wu[wd] = first;
   int mode = same;
   if (!same) {
-    const uint64_t* zr = Z + i0 * row_step * W;
+    const uint64_t* zr = Z + (i0 + fb) * row_step * W;
     int64_t c = 0;
     for (int64_t x = 0; x < W; ++x) c += __popcll(zr[x]);
     if ((float)c > dense_fraction * (float)n) mode = 2;
   }
   uni[wd] = mode;
+}
+
+// ---- sparse rows: row-wise outer products -------------------------------------------------------
+// A row with s of n columns set touches s^2 entries of G, while the column-wise kernel pays for all
+// n^2/2 pairs of columns whatever the row holds; up to a density of about 1/8 the row-wise form is the
+// cheaper one, and in a Kernel-SHAP sample most rows are far sparser than that. Rows are split by their
+// own popcount: sparse ones go to gram_rows_kernel, the others stay with the column-wise kernel
+// (`keep` holds their bits per 64-row word).
+//   Zc[cb][r] = word cb of row r (zero for a kept row): the 64 columns of a tile side for all rows, contiguous.
+//   wq[r]     = weight of row r in fixed point, w_r * 2^e with e chosen so that the sum of all weights stays
+//               below 2^62: every entry of G is a sum over a subset of the rows, so the integer sums cannot
+//               overflow, they are exact, and they do not depend on the order of the atomic additions.
+constexpr int kSparseDivisor = 8;  // rows with at most n / 8 columns set are sparse
+
+// scale[0] = 2^e (0 if the weights are not all finite and non-negative: then every row is kept)
+__global__ __launch_bounds__(kThreads) void gram_scale_kernel(const float* gw, int64_t R, double* scale) {
+  __shared__ double sh[kThreads];
+  __shared__ int bad[kThreads];
+  double a = 0.0;
+  int b = 0;
+  for (int64_t i = threadIdx.x; i < R; i += kThreads) {
+    const float v = gw[i];
+    if (!(v >= 0.f) || v > 3.0e38f) b = 1;
+    a += (double)v;
+  }
+  sh[threadIdx.x] = a;
+  bad[threadIdx.x] = b;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double x = 0.0;
+    int anyb = 0;
+    for (int i = 0; i < kThreads; ++i) {
+      x += sh[i];
+      anyb |= bad[i];
+    }
+    double sc = 0.0;
+    if (!anyb && x > 0.0 && x < 1e300) {
+      int e;
+      frexp(x, &e);  // x < 2^e
+      sc = ldexp(1.0, 61 - e);
+    }
+    scale[0] = sc;
+  }
+}
+
+// one wave per used row
+__global__ __launch_bounds__(kThreads) void gram_row_class_kernel(const uint64_t* Z, int64_t R, int64_t W, int64_t n,
+                                                                  int64_t row_step, const float* gw, const double* scale,
+                                                                  uint64_t* Zc, unsigned long long* keep,
+                                                                  unsigned long long* wq) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+  const double sc = scale[0];
+  for (int64_t r = wave; r < R; r += nwaves) {
+    const uint64_t* zr = Z + r * row_step * W;
+    int c = 0;
+    for (int64_t x = lane; x < W; x += 64) c += __popcll(zr[x]);
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+    const bool sparse = sc > 0.0 && (int64_t)c * kSparseDivisor <= n;
+    for (int64_t x = lane; x < W; x += 64) Zc[x * R + r] = sparse ? zr[x] : 0ull;
+    if (lane == 0) {
+      wq[r] = sparse ? (unsigned long long)llrint((double)gw[r] * sc) : 0ull;
+      if (!sparse) atomicOr(&keep[r >> 6], 1ull << (r & 63));
+    }
+  }
+}
+
+// One 64x64 tile of G per workgroup (lower tiles); streams the two column-block words of every row.
+__global__ __launch_bounds__(kThreads) void gram_rows_kernel(const uint64_t* Zc, const unsigned long long* wq, int64_t R,
+                                                             int64_t n, const double* scale, double* G) {
+  const int ta = blockIdx.y, tb = blockIdx.x;
+  if (tb > ta) return;
+  __shared__ unsigned long long acc[kTile * kTile];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < kTile * kTile; i += kThreads) acc[i] = 0ull;
+  __syncthreads();
+  const uint64_t* Ac = Zc + (size_t)ta * R;
+  const uint64_t* Bc = Zc + (size_t)tb * R;
+  for (int64_t r0 = tid; r0 < R; r0 += 4 * kThreads) {  // four rows per step: their loads are in flight together
+    uint64_t av[4], bv[4];
+    unsigned long long wvv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t r = r0 + (int64_t)u * kThreads;
+      av[u] = r < R ? Ac[r] : 0ull;
+      bv[u] = r < R ? Bc[r] : 0ull;
+      wvv[u] = r < R ? wq[r] : 0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (av[u] == 0ull || bv[u] == 0ull) continue;
+      const unsigned long long wv = wvv[u];
+      uint64_t am = av[u];
+      while (am) {
+        const int a = __ffsll((long long)am) - 1;
+        am &= am - 1;
+        uint64_t bm = bv[u];
+        while (bm) {
+          const int b = __ffsll((long long)bm) - 1;
+          bm &= bm - 1;
+          atomicAdd(&acc[a * kTile + b], wv);
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const double sc = scale[0];
+  const double inv = sc > 0.0 ? 1.0 / sc : 0.0;
+  for (int i = tid; i < kTile * kTile; i += kThreads) {
+    const int64_t a = (int64_t)ta * kTile + (i >> 6), b = (int64_t)tb * kTile + (i & 63);
+    if (a < n && b < n) {
+      const double v = (double)acc[i] * inv;
+      G[a * n + b] = v;
+      if (ta != tb) G[b * n + a] = v;
+    }
+  }
 }
 
 // One 64x64 tile of G per workgroup and slice of the row words (split-K); each slice
@@ -82,7 +207,7 @@ typedef float gram_f16_t __attribute__((ext_vector_type(16)));
 
 __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int64_t n, int64_t k, int64_t KW,
                                                         const float* w, const float* wu, const int32_t* uni,
-                                                        double* Gp, int64_t words_per_slice) {
+                                                        const uint64_t* keep, double* Gp, int64_t words_per_slice) {
   const int ta = blockIdx.y, tb = blockIdx.x;
   if (tb > ta) return;
   // As | Bs during the accumulation; reused as one 64 x 65 fp64 tile when the two paths are merged
@@ -108,11 +233,15 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
       accm[4 * i + j] = 0.0;
     }
   for (int64_t wd0 = wbeg; wd0 < wend; wd0 += kChunk) {
-    __syncthreads();
+    {  // a chunk none of whose rows is kept (all sparse: done by the row-wise kernel) is not even loaded
+      const int64_t wd = wd0 + (tid & (kChunk - 1));
+      const bool any = wd < wend && keep[wd] != 0ull;
+      if (!__syncthreads_or(any)) continue;
+    }
     for (int idx = tid; idx < kTile * kChunk; idx += kThreads) {
       const int r = idx / kChunk, c = idx - r * kChunk;
       const int64_t wd = wd0 + c;
-      As[r][c] = (a0 + r < n && wd < wend) ? Zt[(a0 + r) * KW + wd] : 0ull;
+      As[r][c] = (a0 + r < n && wd < wend) ? (Zt[(a0 + r) * KW + wd] & keep[wd]) : 0ull;  // kept rows only
       Bs[r][c] = (b0 + r < n && wd < wend) ? Zt[(b0 + r) * KW + wd] : 0ull;
     }
     for (int idx = tid; idx < kChunk * 64; idx += kThreads) {
@@ -144,15 +273,21 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
         for (int i = 0; i < 4; ++i)
 #pragma unroll
           for (int j = 0; j < 4; ++j) f[i][j] += wv * (float)__popcll(av[i] & bv[j]);
+      } else if (unis[c] == 3) {
+        // no kept row in this word
       } else if (unis[c] == 2) {
-        const uint64_t aw = As[wi + l32][c] >> half, bw = Bs[wj + l32][c] >> half;  // bit 2q of these = row 2q + half
+        // rows 2q + half, q < 32: bits of the two 32-bit halves of the column words, pre-shifted by `half`
+        const uint64_t aw = As[wi + l32][c] >> half, bw = Bs[wj + l32][c] >> half;
+        const uint32_t alo = (uint32_t)aw, ahi = (uint32_t)(aw >> 32), blo = (uint32_t)bw, bhi = (uint32_t)(bw >> 32);
         const float* wr = wrow + c * 64 + half;
 #pragma unroll
         for (int q = 0; q < 32; q += 2) {
-          const float a0v = ((aw >> (2 * q)) & 1ull) ? wr[2 * q] : 0.f;
-          const float b0v = (float)((uint32_t)(bw >> (2 * q)) & 1u);
-          const float a1v = ((aw >> (2 * q + 2)) & 1ull) ? wr[2 * q + 2] : 0.f;
-          const float b1v = (float)((uint32_t)(bw >> (2 * q + 2)) & 1u);
+          const uint32_t ax = q < 16 ? alo : ahi, bx = q < 16 ? blo : bhi;
+          const int sh = (2 * q) & 31;
+          const float a0v = (ax & (1u << sh)) ? wr[2 * q] : 0.f;
+          const float b0v = (float)((bx >> sh) & 1u);
+          const float a1v = (ax & (1u << (sh + 2))) ? wr[2 * q + 2] : 0.f;
+          const float b1v = (float)((bx >> (sh + 2)) & 1u);
           fm0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b0v, fm0, 0, 0, 0);
           fm1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b1v, fm1, 0, 0, 0);
         }
@@ -193,9 +328,10 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
     for (int j = 0; j < 4; ++j) {
       const int64_t a = a0 + ty + 16 * i, b = b0 + tx + 16 * j;
       if (a < n && b < n) {
-        const double v = acc[i][j] + Ts[ty + 16 * i][tx + 16 * j];
+        double v = acc[i][j] + Ts[ty + 16 * i][tx + 16 * j];
+        if (blockIdx.z == 0) v += G[a * n + b];  // slice 0 already holds the sparse rows' part (both triangles)
         G[a * n + b] = v;
-        G[b * n + a] = v;
+        if (ta != tb) G[b * n + a] = v;  // a diagonal tile computes both of its triangles itself
       }
     }
 }
@@ -762,7 +898,8 @@ size_t ds_gram_arena_bytes(int64_t n, int64_t k) {
   const size_t slices = (size_t)(d.slices > dp.slices ? d.slices : dp.slices) + 1;  // +1: CU counts differ a little
   return ds_align((size_t)n * d.RW * 8) + ds_align(slices * (size_t)n * n * 8) + ds_align((size_t)(n + 1) * d.ld * 8) +
          ds_align((size_t)d.nblk * NB * NB * 8) + 2 * ds_align(k * 4) + 2 * ds_align(k * 8) + ds_align(k * 4) +
-         ds_align(k * 8) + ds_align(d.RW * 4) * 2 + 4 * ds_align(n * 8) + 8192;
+         ds_align(k * 8) + ds_align(d.RW * 4) * 2 + 4 * ds_align(n * 8) + 8192 +
+         ds_align((size_t)((n + 63) / 64) * d.R * 8 + 8) + ds_align((size_t)d.RW * 8 + 8) + ds_align((size_t)d.R * 8 + 8) + 256;
 }
 
 // Part 1: everything that does not need the model outputs y (Gram matrix, projection, system matrix).
@@ -783,6 +920,10 @@ int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const fl
   int32_t* uni = (int32_t*)ds_arena_alloc(ctx, RW * 4);
   double* m = (double*)ds_arena_alloc(ctx, n * 8);
   double* stats = (double*)ds_arena_alloc(ctx, 64);
+  uint64_t* Zc = (uint64_t*)ds_arena_alloc(ctx, (size_t)W * R * 8 + 8);
+  uint64_t* keep = (uint64_t*)ds_arena_alloc(ctx, (size_t)RW * 8 + 8);
+  uint64_t* wq = (uint64_t*)ds_arena_alloc(ctx, (size_t)R * 8 + 8);
+  double* gscale = (double*)ds_arena_alloc(ctx, 64);
   // buffers of part 2, reserved here so that both parts draw from one contiguous region
   gs->sz = (int32_t*)ds_arena_alloc(ctx, k * 4);
   gs->wc = (float*)ds_arena_alloc(ctx, k * 4);
@@ -792,17 +933,29 @@ int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const fl
   gs->c = (double*)ds_arena_alloc(ctx, n * 8);
   gs->yv = (double*)ds_arena_alloc(ctx, n * 8);
   gs->flag = (int*)ds_arena_alloc(ctx, 64);
-  if (!gs->Zt || !Gp || !gs->M || !gs->linv || !gw || !wu || !uni || !m || !stats || !gs->sz || !gs->wc || !gs->t ||
+  if (!gs->Zt || !Gp || !gs->M || !gs->linv || !gw || !wu || !uni || !m || !stats || !Zc || !keep || !wq || !gscale || !gs->sz || !gs->wc || !gs->t ||
       !gs->sqw || !gs->gc || !gs->c || !gs->yv || !gs->flag)
     return ds_fail(ctx, DS_EINTERNAL, "gram: arena exhausted");
   hipLaunchKernelGGL(used_row_weights_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, w, R, paired, gw);
   DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, gs->Zt));
-  hipLaunchKernelGGL(word_weights_kernel, dim3(nblocks(RW, 256)), dim3(256), 0, st, gw, R, RW, Z, W, n,
-                     (int64_t)(paired ? 2 : 1), dense_fraction(), wu, uni);
+  // sparse rows: row-wise outer products into slice 0; the rest (bits in `keep`) column-wise on top of it
+  const int64_t row_step = paired ? 2 : 1;
+  DS_HIP(ctx, hipMemsetAsync(keep, 0, (size_t)RW * 8, st));
+  hipLaunchKernelGGL(gram_scale_kernel, dim3(1), dim3(kThreads), 0, st, gw, R, gscale);
+  {
+    int64_t blocks = (R * 64 + kThreads - 1) / kThreads;
+    if (blocks > (int64_t)ctx->num_cus * 16) blocks = (int64_t)ctx->num_cus * 16;
+    hipLaunchKernelGGL(gram_row_class_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, Z, R, W, n, row_step, gw,
+                       gscale, Zc, (unsigned long long*)keep, (unsigned long long*)wq);
+  }
+  hipLaunchKernelGGL(word_weights_kernel, dim3(nblocks(RW, 256)), dim3(256), 0, st, gw, R, RW, Z, W, n, row_step,
+                     dense_fraction(), keep, wu, uni);
   const unsigned tiles = nblocks(n, kTile);
   DS_TRY(ds_kernel_mark(ctx, 1, 0));
-  hipLaunchKernelGGL(gram_kernel, dim3(tiles, tiles, d.slices), dim3(kThreads), 0, st, gs->Zt, n, R, RW, gw, wu, uni, Gp,
-                     d.words_per_slice);
+  hipLaunchKernelGGL(gram_rows_kernel, dim3(tiles, tiles), dim3(kThreads), 0, st, Zc, (const unsigned long long*)wq, R, n,
+                     gscale, Gp);
+  hipLaunchKernelGGL(gram_kernel, dim3(tiles, tiles, d.slices), dim3(kThreads), 0, st, gs->Zt, n, R, RW, gw, wu, uni, keep,
+                     Gp, d.words_per_slice);
   DS_TRY(ds_kernel_mark(ctx, 1, 1));
   const unsigned wblocks = (unsigned)(n < (int64_t)ctx->num_cus * 16 ? n : (int64_t)ctx->num_cus * 16);
   hipLaunchKernelGGL(sum_slices_row_mean_kernel, dim3(wblocks), dim3(kThreads), 0, st, Gp, n, d.slices, m);
