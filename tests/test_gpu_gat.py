@@ -229,3 +229,35 @@ def test_switching_model_family_on_one_context():
     phi_b = ctx.explain(target, 2000, 5, Options(solver=1))[0].cpu().numpy()
     assert np.array_equal(phi_a, phi_b)
     ctx.close()
+
+
+def test_gat_batch_equals_single_explanations_and_fidelity_matches_oracle():
+    """The other entry points with a GAT set: ds_explain_batch (worker contexts take the attention model along) gives
+    exactly the single-call results, and ds_fidelity evaluates the GAT on the top-k sub-graphs like the oracle."""
+    from oracle import fidelity
+    from paper_2506_22668_amd import Options
+    w = make_workload("gat_small")
+    ctx = _context(w, w.gat)
+    rng = np.random.default_rng(2)
+    deg = np.diff(w.row_ptr)
+    targets = [w.targets[0]] + [int(t) for t in rng.choice(np.flatnonzero(deg >= 3), size=5, replace=False)]
+    say(f"gat batch targets={targets}")
+    singles = [ctx.explain(t, 2000, w.seed, Options(solver=1))[0] for t in targets]
+    total = sum(len(x) for x in singles)
+    phi, M, off, es, ed, reps, rc = ctx.explain_batch(targets, 2000, w.seed, Options(solver=1), capacity=total)
+    assert rc == 0 and M == [len(x) for x in singles]
+    for i, x in enumerate(singles):
+        assert torch.equal(phi[off[i]:off[i + 1]], x)
+    target = targets[0]
+    cg = ctx.extract(target, Options(hops=2))
+    cgo = compgraph.extract(w.row_ptr, w.col, target, 2)
+    n = cgo["num_players"]
+    ks = [0, 1, 3, 10, n // 2, n]
+    plus, minus, masks = ctx.fidelity(cg, singles[0], ks, 0, want_masks=True)
+    f = ogat.ValueFunction(cgo, w.features, w.gat)
+    ph = singles[0].cpu().numpy()
+    assert np.array_equal(to_u64(masks), sampling.pack_rows(fidelity.top_k_masks(ph, ks)))
+    rp, rm = fidelity.fidelity(f, ph, ks)
+    assert np.abs(np.array(plus) - rp).max() <= 2e-5 and np.abs(np.array(minus) - rm).max() <= 2e-5
+    ctx.cgraph_free(cg)
+    ctx.close()
