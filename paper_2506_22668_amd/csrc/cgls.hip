@@ -45,14 +45,17 @@ __device__ __forceinline__ void block_reduce2(double a, double b, double* pa, do
   __syncthreads();
 }
 
-// scalars (device doubles): 0 gamma, 1 delta, 2 theta, 3 beta, 4 sum(u), 5 mean(s_raw), 6 gamma_new, 7 gamma0
+// scalars (device doubles): 0 gamma, 1 delta, 2 theta, 3 beta, 4 sum(u), 5 mean(s_raw), 6 gamma_new, 7 gamma0,
+// 8 done (0/1), 9 iterations completed, 10 relative residual at the last test
+// partial sums: four arrays of kRed doubles, one per reduction of the loop (|v|^2, sum(s), |Ps|^2, sum(u)), so
+// that a kernel can read the partials of the reduction before it while writing those of its own
 struct Vecs {
   int64_t n, k, R;   // R = rows of the forward matrix (pairs or rows)
   int paired;
   const double* sqw; // [k]
   double *x, *u, *s, *r, *v, *d, *h;  // n, n, n, k, k, R, R
   double* scal;
-  double* part;      // [2 * kRed]
+  double* part;      // [4 * kRed]
 };
 
 // r = sqrt(w) t ; h from r
@@ -66,58 +69,12 @@ __global__ void make_h_kernel(Vecs a) {
   a.h[i] = a.paired ? a.sqw[2 * i] * (a.r[2 * i] - a.r[2 * i + 1]) : a.sqw[i] * a.r[i];
 }
 
-// v from d; partial |v|^2
-__global__ __launch_bounds__(kThreads) void make_v_kernel(Vecs a) {
-  const double U = a.scal[4];
-  double acc = 0.0;
-  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < a.R; i += (int64_t)gridDim.x * kThreads) {
-    if (a.paired) {
-      const double w = a.sqw[2 * i], d = a.d[i];
-      const double v0 = w * d, v1 = w * (U - d);
-      a.v[2 * i] = v0;
-      a.v[2 * i + 1] = v1;
-      acc += v0 * v0 + v1 * v1;
-    } else {
-      const double v0 = a.sqw[i] * a.d[i];
-      a.v[i] = v0;
-      acc += v0 * v0;
-    }
-  }
-  double dummy;
-  block_reduce2(acc, 0.0, &a.part[blockIdx.x], &dummy);
-}
-
 // sum of nparts (<= kRed) partials by one wave, in a fixed order; every lane gets the result
 __device__ __forceinline__ double wave_sum_partials(const double* part, int nparts) {
   double s = 0.0;
   for (int i = threadIdx.x; i < nparts; i += 64) s += part[i];
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
   return s;
-}
-
-__global__ void fin_delta_kernel(Vecs a, int nparts) {
-  const double s = wave_sum_partials(a.part, nparts);
-  if (threadIdx.x == 0) {
-    a.scal[1] = s;
-    a.scal[2] = s > 0.0 ? a.scal[0] / s : 0.0;
-  }
-}
-
-// r -= theta v, then h
-__global__ void update_r_kernel(Vecs a) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= a.R) return;
-  const double th = a.scal[2];
-  if (a.paired) {
-    const double r0 = a.r[2 * i] - th * a.v[2 * i], r1 = a.r[2 * i + 1] - th * a.v[2 * i + 1];
-    a.r[2 * i] = r0;
-    a.r[2 * i + 1] = r1;
-    a.h[i] = a.sqw[2 * i] * (r0 - r1);
-  } else {
-    const double r0 = a.r[i] - th * a.v[i];
-    a.r[i] = r0;
-    a.h[i] = a.sqw[i] * r0;
-  }
 }
 
 // partial sums of the raw adjoint (for its mean)
@@ -182,6 +139,133 @@ __global__ void fin_u_kernel(Vecs a, int nparts) {
     a.scal[4] = s;
     a.scal[0] = a.scal[6];
   }
+}
+
+// ---- the loop's kernels: every reduction is finished by the kernel that needs its result (each workgroup
+// adds the same partials in the same order, workgroup 0 records the scalar), and the stopping rule of the
+// iteration is evaluated on the device, so that the host only looks every few iterations. Once `done` is set
+// the state that the result is made of (x, u, theta) is left alone by everything that still runs. ----
+constexpr int kPartV = 0, kPartS = 1, kPartG = 2, kPartU = 3;
+
+// all threads of the workgroup get the sum of the nparts partials of array `which`
+__device__ __forceinline__ double block_sum_partials(const Vecs& a, int which, int nparts) {
+  __shared__ double bs;
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const double s = wave_sum_partials(a.part + which * kRed, nparts);
+    if (threadIdx.x == 0) bs = s;
+  }
+  __syncthreads();
+  return bs;
+}
+
+// v from d (after finishing sum(u) and moving gamma_new to gamma); partial |v|^2
+__global__ __launch_bounds__(kThreads) void loop_make_v_kernel(Vecs a, int parts_u) {
+  const double U = block_sum_partials(a, kPartU, parts_u);
+  if (blockIdx.x == 0 && threadIdx.x == 0 && a.scal[8] == 0.0) {
+    a.scal[4] = U;
+    a.scal[0] = a.scal[6];
+  }
+  double acc = 0.0;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < a.R; i += (int64_t)gridDim.x * kThreads) {
+    if (a.paired) {
+      const double w = a.sqw[2 * i], d = a.d[i];
+      const double v0 = w * d, v1 = w * (U - d);
+      a.v[2 * i] = v0;
+      a.v[2 * i + 1] = v1;
+      acc += v0 * v0 + v1 * v1;
+    } else {
+      const double v0 = a.sqw[i] * a.d[i];
+      a.v[i] = v0;
+      acc += v0 * v0;
+    }
+  }
+  double dummy;
+  block_reduce2(acc, 0.0, &a.part[kPartV * kRed + blockIdx.x], &dummy);
+}
+
+// delta = |v|^2, theta = gamma / delta; r -= theta v, then h. A direction in the null space (delta = 0)
+// ends the iteration with theta = 0.
+__global__ __launch_bounds__(kThreads) void loop_update_r_kernel(Vecs a, int parts_v) {
+  const double delta = block_sum_partials(a, kPartV, parts_v);
+  const bool done = a.scal[8] != 0.0;
+  const double gamma = a.scal[0];
+  const bool null_dir = !(delta > 0.0);
+  const double th = null_dir ? 0.0 : gamma / delta;
+  if (done) return;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    a.scal[1] = delta;
+    a.scal[2] = th;
+    if (null_dir) {
+      a.scal[8] = 1.0;
+      a.scal[9] += 1.0;
+    }
+  }
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < a.R; i += (int64_t)gridDim.x * kThreads) {
+    if (a.paired) {
+      const double r0 = a.r[2 * i] - th * a.v[2 * i], r1 = a.r[2 * i + 1] - th * a.v[2 * i + 1];
+      a.r[2 * i] = r0;
+      a.r[2 * i + 1] = r1;
+      a.h[i] = a.sqw[2 * i] * (r0 - r1);
+    } else {
+      const double r0 = a.r[i] - th * a.v[i];
+      a.r[i] = r0;
+      a.h[i] = a.sqw[i] * r0;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void loop_s_sum_kernel(Vecs a) {
+  double s1 = 0;
+  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) s1 += a.s[j];
+  double dummy;
+  block_reduce2(s1, 0.0, &a.part[kPartS * kRed + blockIdx.x], &dummy);
+}
+
+// s <- P s and partial |P s|^2 (two passes on purpose, see s_center_kernel)
+__global__ __launch_bounds__(kThreads) void loop_s_center_kernel(Vecs a, int parts_s) {
+  const double mean = block_sum_partials(a, kPartS, parts_s) / (double)a.n;
+  double s2 = 0;
+  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) {
+    const double v = a.s[j] - mean;
+    a.s[j] = v;
+    s2 += v * v;
+  }
+  double dummy;
+  block_reduce2(s2, 0.0, &a.part[kPartG * kRed + blockIdx.x], &dummy);
+}
+
+// end of an iteration: gamma_new = |P s|^2, the stopping rule, and (if the iteration goes on and do_update)
+// x += theta u, u = s + beta u with the partial sums of the new u
+__global__ __launch_bounds__(kThreads) void loop_update_xu_kernel(Vecs a, int parts_g, double tol, int do_update) {
+  const double g = block_sum_partials(a, kPartG, parts_g);
+  if (a.scal[8] != 0.0) return;
+  const double gamma = a.scal[0], gamma0 = a.scal[7];
+  const double rel = sqrt(g) / sqrt(gamma0);
+  const bool stop = rel <= tol;
+  const double beta = gamma > 0.0 ? g / gamma : 0.0;
+  const double th = a.scal[2];
+  __syncthreads();  // every thread has read the scalars before workgroup 0 changes them
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    a.scal[9] += 1.0;
+    a.scal[10] = rel;
+    if (stop) a.scal[8] = 1.0;
+    else if (do_update) {
+      a.scal[3] = beta;
+      a.scal[6] = g;
+    }
+  }
+  if (stop || !do_update) return;
+  double acc = 0;
+  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) {
+    const double uo = a.u[j];
+    a.x[j] += th * uo;
+    const double un = a.s[j] + beta * uo;
+    a.u[j] = un;
+    acc += un;
+  }
+  double dummy;
+  block_reduce2(acc, 0.0, &a.part[kPartU * kRed + blockIdx.x], &dummy);
 }
 
 // x += theta u only (last step, u not needed any more)
@@ -256,8 +340,8 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   a.x = (double*)ds_arena_alloc(ctx, n * 8);
   a.u = (double*)ds_arena_alloc(ctx, n * 8);
   a.s = (double*)ds_arena_alloc(ctx, n * 8);
-  a.scal = (double*)ds_arena_alloc(ctx, 64);
-  a.part = (double*)ds_arena_alloc(ctx, 2 * kRed * 8);
+  a.scal = (double*)ds_arena_alloc(ctx, 128);
+  a.part = (double*)ds_arena_alloc(ctx, 4 * kRed * 8);
   if (!sz || !wc || !t || !sqw || !a.r || !a.v || !a.d || !a.h || !a.x || !a.u || !a.s || !a.scal || !a.part)
     return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
 
@@ -335,7 +419,7 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   };
   DS_HIP(ctx, hipMemsetAsync(a.x, 0, n * 8, st));
   DS_HIP(ctx, hipMemsetAsync(a.u, 0, n * 8, st));
-  DS_HIP(ctx, hipMemsetAsync(a.scal, 0, 64, st));
+  DS_HIP(ctx, hipMemsetAsync(a.scal, 0, 128, st));
 
   const unsigned red_n = nblocks(n, kThreads) < (unsigned)kRed ? nblocks(n, kThreads) : (unsigned)kRed;
   const unsigned red_r = nblocks(R, kThreads) < (unsigned)kRed ? nblocks(R, kThreads) : (unsigned)kRed;
@@ -348,8 +432,12 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n);
   hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
   hipLaunchKernelGGL(fin_gamma_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n, 1);
-  hipLaunchKernelGGL(update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a);  // theta = beta = 0: u = s
-  hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n);
+  {
+    Vecs au = a;  // the partial sums of u live in their own array (the loop's first kernel adds them up)
+    au.part = a.part + kPartU * kRed;
+    hipLaunchKernelGGL(update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, au);  // theta = beta = 0: u = s
+    hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(64), 0, st, au, (int)red_n);
+  }
   DS_HIP(ctx, hipGetLastError());
   DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, a.scal, 64, hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipStreamSynchronize(st));
@@ -358,27 +446,31 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   double rel = gamma0 > 0 ? 1.0 : 0.0;
   bool converged = !(gamma0 > 0);
   DS_TRY(ds_kernel_mark(ctx, 3, 0));
-  while (!converged && it < max_iter) {
-    DS_TRY(forward(a.u, a.d));
-    hipLaunchKernelGGL(make_v_kernel, dim3(red_r), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(fin_delta_kernel, dim3(1), dim3(64), 0, st, a, (int)red_r);
-    hipLaunchKernelGGL(update_r_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
-    DS_TRY(adjoint(a.h, a.s));
-    hipLaunchKernelGGL(s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n);
-    hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(fin_gamma_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n, 0);
+  // The stopping rule runs on the device; the host reads the scalars back every kCheckEvery iterations
+  // (kernels queued after the iteration that stopped leave the result alone).
+  constexpr int kCheckEvery = 8;
+  int launched = 0;
+  while (!converged && launched < max_iter) {
+    const int burst = max_iter - launched < kCheckEvery ? max_iter - launched : kCheckEvery;
+    for (int b = 0; b < burst; ++b) {
+      DS_TRY(forward(a.u, a.d));
+      hipLaunchKernelGGL(loop_make_v_kernel, dim3(red_r), dim3(kThreads), 0, st, a, (int)red_n);
+      hipLaunchKernelGGL(loop_update_r_kernel, dim3(red_r), dim3(kThreads), 0, st, a, (int)red_r);
+      DS_TRY(adjoint(a.h, a.s));
+      hipLaunchKernelGGL(loop_s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
+      hipLaunchKernelGGL(loop_s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a, (int)red_n);
+      // the last iteration allowed takes no further step: it only evaluates the stopping rule
+      hipLaunchKernelGGL(loop_update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a, (int)red_n, tol,
+                         launched + b + 1 < max_iter ? 1 : 0);
+    }
+    launched += burst;
     DS_HIP(ctx, hipGetLastError());
-    DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, a.scal, 64, hipMemcpyDeviceToHost, st));
+    DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail, a.scal, 128, hipMemcpyDeviceToHost, st));
     DS_HIP(ctx, hipStreamSynchronize(st));
     const double* sc = (const double*)ctx->h_mail;
-    ++it;
-    if (!(sc[1] > 0.0)) { converged = true; break; }  // u in the null space: nothing left to gain
-    rel = sqrt(sc[6]) / sqrt(gamma0);
-    if (rel <= tol) { converged = true; break; }
-    if (it >= max_iter) break;
-    hipLaunchKernelGGL(update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(fin_u_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n);
+    it = (int)sc[9];
+    if (sc[10] > 0.0 || it > 0) rel = sc[10] > 0.0 ? sc[10] : rel;
+    if (sc[8] != 0.0) converged = true;
   }
   DS_TRY(ds_kernel_mark(ctx, 3, 1));
   // the last step's x += theta u is folded into the output (theta is 0 if no step was taken)
