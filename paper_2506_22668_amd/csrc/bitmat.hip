@@ -269,8 +269,17 @@ __global__ __launch_bounds__(kTabThreads) void bit_spmv_tab_kernel(const uint64_
 __global__ void tab_reduce_kernel(const double* partial, int64_t rows, int groups, const double* addend, double* out) {
   const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= rows) return;
+  // eight loads in flight; the partial sums are added in the order of their groups whatever the count is
   double s = addend ? addend[r] : 0.0;
-  for (int g = 0; g < groups; ++g) s += partial[(int64_t)g * rows + r];
+  int g = 0;
+  for (; g + 8 <= groups; g += 8) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(g + u) * rows + r];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; g < groups; ++g) s += partial[(int64_t)g * rows + r];
   out[r] = s;
 }
 
@@ -379,7 +388,8 @@ size_t ds_bit_spmv_tab_ws_doubles(const ds_ctx* ctx, int64_t rows, int64_t cols)
 }
 
 int ds_bit_spmv_tab(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
-                    int64_t row_step, const double* x, const double* addend, double* out, double* ws) {
+                    int64_t row_step, const double* x, const double* addend, double* out, double* ws,
+                    hipEvent_t addend_ready) {
   if (rows <= 0) return DS_OK;
   const int64_t row_groups = (rows + kTabRows - 1) / kTabRows;
   const int64_t n_chunks = (cols + kTabCols - 1) / kTabCols;
@@ -392,6 +402,7 @@ int ds_bit_spmv_tab(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, 
   DS_HIP(ctx, hipFuncSetAttribute((const void*)bit_spmv_tab_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   hipLaunchKernelGGL(bit_spmv_tab_kernel, dim3((unsigned)row_groups, (unsigned)groups), dim3(kTabThreads), lds, ctx->stream, B,
                      rows, cols, stride, row_first, row_step, x, ws, cpg, n_chunks);
+  if (addend_ready) DS_HIP(ctx, hipStreamWaitEvent(ctx->stream, addend_ready, 0));  // the addend comes from another stream
   hipLaunchKernelGGL(tab_reduce_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, ctx->stream, ws, rows,
                      (int)groups, addend, out);
   DS_HIP(ctx, hipGetLastError());

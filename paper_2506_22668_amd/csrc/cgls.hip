@@ -406,13 +406,37 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
     if (!Zt) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
     DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, Zt));
   }
+  // In the hybrid layout the index-list product (sparse rows) and the table product (dense rows) are
+  // independent: the former runs on the context's second stream while the latter runs here (worth the two
+  // cross-stream waits per product only when the index lists are long).
+  const bool overlap = hybrid && Rs > 0 && Rd > 0 && nnz_s >= ((int64_t)1 << 22);
+  auto gather_on_side = [&](const int32_t* off, const int32_t* idx, int64_t rows, const double* x, double* out) -> int {
+    DS_HIP(ctx, hipEventRecord(ctx->fork_ev, st));
+    DS_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->fork_ev, 0));
+    ctx->stream = ctx->side;
+    const int rc = ds_csr_gather(ctx, off, idx, rows, x, out);
+    ctx->stream = st;
+    DS_TRY(rc);
+    DS_HIP(ctx, hipEventRecord(ctx->join_ev, ctx->side));
+    return DS_OK;
+  };
   auto forward = [&](const double* u, double* d) -> int {  // d = (rows) . u
     if (!hybrid) return ds_bit_spmv(ctx, Z, R, n, W, 0, paired ? 2 : 1, u, d);
+    if (overlap) {
+      DS_TRY(gather_on_side(csr_off, csr_idx, Rs, u, d));
+      DS_TRY(ds_bit_spmv_tab(ctx, Z, Rd, n, W, 2 * Rs, 2, u, nullptr, d + Rs, tab_ws));
+      DS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_ev, 0));
+      return DS_OK;
+    }
     DS_TRY(ds_csr_gather(ctx, csr_off, csr_idx, Rs, u, d));
     return ds_bit_spmv_tab(ctx, Z, Rd, n, W, 2 * Rs, 2, u, nullptr, d + Rs, tab_ws);
   };
   auto adjoint = [&](const double* h, double* sv) -> int {  // s = (rows)^T . h
     if (!hybrid) return ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, h, sv);
+    if (overlap) {  // the table product's final summation adds the index-list result: it waits for it
+      DS_TRY(gather_on_side(csc_off, csc_row, n, h, sv));
+      return ds_bit_spmv_tab(ctx, Ztd, n, Rd, RdW, 0, 1, h + Rs, sv, sv, tab_ws, ctx->join_ev);
+    }
     if (Rs > 0) DS_TRY(ds_csr_gather(ctx, csc_off, csc_row, n, h, sv));
     if (Rd > 0) return ds_bit_spmv_tab(ctx, Ztd, n, Rd, RdW, 0, 1, h + Rs, Rs > 0 ? sv : nullptr, sv, tab_ws);
     return DS_OK;

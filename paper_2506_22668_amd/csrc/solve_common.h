@@ -15,8 +15,10 @@ int ds_bit_spmv(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int6
 // same product for dense rows through per-byte partial-sum tables in LDS; out = (addend or 0) + result.
 // ws: ds_bit_spmv_tab_ws_doubles(ctx, rows, cols) doubles of scratch
 size_t ds_bit_spmv_tab_ws_doubles(const ds_ctx* ctx, int64_t rows, int64_t cols);
+// addend_ready: optional event the final summation waits for (an addend produced on another stream)
 int ds_bit_spmv_tab(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
-                    int64_t row_step, const double* x, const double* addend, double* out, double* ws);
+                    int64_t row_step, const double* x, const double* addend, double* out, double* ws,
+                    hipEvent_t addend_ready = nullptr);
 // index lists of the set bits of rows (off = exclusive prefix sums of the row sizes), and the gather-sum over them
 int ds_rows_to_csr(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
                    int64_t row_step, const int32_t* off, int32_t* idx);
