@@ -168,7 +168,8 @@ def main():
         ctx.set_gat(w.gat["W"], w.gat["a_src"], w.gat["a_dst"], w.gat["heads"], negative_slope=w.gat["slope"])
     else:
         ctx.set_gcn(w.weights, transform_dtype=DS_BF16_IN_F32_ACC if w.transform_dtype == "bf16" else DS_F32)
-    opts = Options(solver=DS_SOLVER_CGLS if w.solver == "cgls" else DS_SOLVER_GRAM_CHOL, tol=w.tol)
+    opts = Options(solver=DS_SOLVER_CGLS if w.solver == "cgls" else DS_SOLVER_GRAM_CHOL, tol=w.tol,
+                   max_iter=w.max_iter)
     targets = w.targets
     cg = ctx.extract(targets[0], opts)
     info = ctx.cgraph_info(cg)
