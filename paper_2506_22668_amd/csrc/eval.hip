@@ -299,7 +299,8 @@ __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
 //     broadcast from LDS.
 // The eight waves of the workgroup split nodes, rows and items among them (same 64 coalitions) and
 // meet at barriers between the stages.
-constexpr int kBW = 32;        // mask words per coalition held in LDS
+constexpr int kBW = 32;        // mask words per coalition held in LDS (at least; more for wider masks, see the layout)
+constexpr int kBWMax = 192;    // ... up to this many (12,288 players) when the rest of the LDS budget allows
 constexpr int kStageRows = 16; // entries per matrix-core batch; also sizes the shared weight buffer
 constexpr int kBThreads = 512; // eight waves share the 64 coalitions of a workgroup
 constexpr int kBWaves = kBThreads / 64;
@@ -311,16 +312,17 @@ struct BatchedArgs {
   int64_t scratch_stride;  // floats per workgroup
   int64_t rs_floats, a_floats, b_floats, q_floats;  // region sizes (floats, already x64)
   int32_t csr_lds_offset;  // byte offset of the LDS copy of the local CSR (if used)
+  int32_t zs_words;        // mask words per coalition reserved in LDS (>= W)
 };
 
 template <bool DEG_LDS, bool CSR_LDS>
 __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(BatchedArgs b) {
   const EvalArgs& a = b.e;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  // LDS: zs[kBW][64] u64 | weight-matrix buffer f32[waves*16*64] | deg[V][64] u16 (optional) | local CSR (optional)
+  // LDS: zs[zs_words][64] u64 | weight-matrix buffer f32[waves*16*64] | deg[V][64] u16 (optional) | local CSR (optional)
   uint64_t* zs = (uint64_t*)smem_raw;
-  float* stage_all = (float*)(smem_raw + kBW * 64 * 8);
-  unsigned short* degs = (unsigned short*)(smem_raw + kBW * 64 * 8 + kBWaves * kStageRows * 64 * 4);
+  float* stage_all = (float*)(smem_raw + (size_t)b.zs_words * 64 * 8);
+  unsigned short* degs = (unsigned short*)(smem_raw + (size_t)b.zs_words * 64 * 8 + kBWaves * kStageRows * 64 * 4);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t *g_rp = a.row_ptr, *g_col = a.col, *g_eid = a.eid;
   if (CSR_LDS) {  // the graph structure is read many times per coalition block: keep it on chip
@@ -782,7 +784,7 @@ void fill_args(const ds_ctx* ctx, const ds_cgraph* cg, const EvalLayout& lay, Ev
 
 struct BatchedLayout {
   bool use, deg_lds, csr_lds;
-  int csr_off;
+  int csr_off, zs_words;
   int grid;
   size_t lds_bytes;
   int64_t rs_floats, a_floats, b_floats, q_floats, stride;
@@ -793,8 +795,10 @@ BatchedLayout make_batched_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_
   BatchedLayout bl;
   memset(&bl, 0, sizeof(bl));
   const int64_t n = cg->info.num_players;
-  bl.use = n >= 1 && n <= (int64_t)kBW * 64 && k >= 256;
+  const int64_t Wn = (n + 63) / 64;
+  bl.use = n >= 1 && Wn <= kBWMax && k >= 256;
   if (!bl.use) return bl;
+  bl.zs_words = (int)(Wn > kBW ? Wn : kBW);
   int32_t rows_out[DS_MAX_LAYERS + 1];
   fill_rows(ctx, cg, rows_out);
   const int L = ctx->L;
@@ -807,11 +811,15 @@ BatchedLayout make_batched_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_
   bl.a_floats = A * 64;
   bl.b_floats = (B > 0 ? B : 1) * 64;
   bl.q_floats = (dq > 0 ? dq : 1) * 64;
-  bl.deg_lds = cg->info.num_nodes <= kDegLdsMaxNodes;
+  const size_t fixed = (size_t)bl.zs_words * 64 * 8 + (size_t)kBWaves * kStageRows * 64 * 4;
+  bl.deg_lds = cg->info.num_nodes <= kDegLdsMaxNodes && fixed + (size_t)cg->info.num_nodes * 64 * 2 + 16 <= kLdsLimit;
   bl.rs_floats = bl.deg_lds ? 0 : cg->info.num_nodes * 64;
-  bl.lds_bytes = (size_t)kBW * 64 * 8 + (size_t)kBWaves * kStageRows * 64 * 4 +
-                 (bl.deg_lds ? (size_t)cg->info.num_nodes * 64 * 2 : 0);
+  bl.lds_bytes = fixed + (bl.deg_lds ? (size_t)cg->info.num_nodes * 64 * 2 : 0);
   bl.lds_bytes = (bl.lds_bytes + 15) & ~(size_t)15;
+  if (bl.lds_bytes > kLdsLimit) {  // wide masks and no room left: the one-workgroup-per-coalition kernel takes over
+    bl.use = false;
+    return bl;
+  }
   const size_t csr_bytes = 4 * (((size_t)cg->info.num_nodes + 4) & ~(size_t)3) + 8 * (((size_t)cg->info.num_entries + 3) & ~(size_t)3);
   bl.csr_lds = bl.lds_bytes + csr_bytes <= kLdsLimit;
   bl.csr_off = (int)bl.lds_bytes;
@@ -922,6 +930,7 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
     b.b_floats = bl.b_floats;
     b.q_floats = bl.q_floats;
     b.csr_lds_offset = bl.csr_off;
+    b.zs_words = bl.zs_words;
     DS_TRY(ds_kernel_mark(ctx, 0, 0));
     const void* fn;
     if (bl.deg_lds && bl.csr_lds) fn = (const void*)masked_gcn_eval_batched_kernel<true, true>;
