@@ -769,10 +769,13 @@ __global__ __launch_bounds__(kThreads) void chol_back_step_kernel(const double* 
   }
   __syncthreads();
   const int64_t j = (int64_t)blockIdx.x * kThreads + tid;
-  if (j < j0) {
+  if (j < j0) {  // all NB loads of the column are in flight together (rows past a short block are skipped)
+    double mv[NB];
+#pragma unroll
+    for (int r = 0; r < NB; ++r) mv[r] = r < nb ? M[(j0 + r) * ld + j] : 0.0;
     double s = 0.0;
-#pragma unroll 16
-    for (int r = 0; r < nb; ++r) s += M[(j0 + r) * ld + j] * xs[r];
+#pragma unroll
+    for (int r = 0; r < NB; ++r) s += mv[r] * xs[r];
     yv[j] -= s;
   }
 }
