@@ -198,12 +198,28 @@ __global__ __launch_bounds__(kThreads) void gram_rows_kernel(const uint64_t* Zc,
 // A word of 64 rows that share one weight costs an AND and a popcount per pair of columns. A word that
 // straddles weight classes (most words past the first few classes: a class soon has fewer than 64 rows)
 // either walks the set bits of the AND (sparse rows) or, when its rows are dense, is treated as the small
-// dense contraction it is, sum_r (w_r z_ra) z_rb, on the fp32 matrix cores:
-// v_mfma_f32_32x32x2f32, lane l supplies A[m = l%32][k = l/32] = w_r * bit r of column m's word and
-// B[k][n = l%32] = bit r of column n's word, r = 2q + l/32; each wave owns a 32x32 quadrant of the tile
-// (accumulator register i of lane l is D[8*(i/4) + 4*(l/32) + i%4][l%32]). Both paths add up in fp32
+// dense contraction it is, sum_r (w_r z_ra) z_rb, on the matrix cores. The fp32 weight is split into three
+// bfloat16 pieces (w = w1 + w2 + w3 to 24 bits; a bit is exactly 0 or 1 in bfloat16), so the contraction runs
+// as three v_mfma_f32_32x32x8bf16_1k per 8 rows with fp32 accumulation, several times the rate of the fp32
+// instruction: lane l supplies A[m = l%32][k = 4*(l/32) + j] = piece of row r * bit r of column m's word and
+// B[k][n = l%32] = bit r of column n's word, r = 8 kb + k, j < 4 (two values per register). Operands are
+// made with look-ups: a 16-entry LDS table turns four bits into the two registers of 16-bit masks (or of
+// bfloat16 ones for B), which the packed weight pieces are ANDed with. Each wave owns a 32x32 quadrant of the
+// tile (accumulator register i of lane l is D[8*(i/4) + 4*(l/32) + i%4][l%32]). Both paths add up in fp32
 // within a chunk of 32 words and in fp64 across chunks.
 typedef float gram_f16_t __attribute__((ext_vector_type(16)));
+typedef short gram_s4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int gram_u2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t bf16_bits_rn(float x) {  // nearest-even bfloat16 of a finite float, as 16 bits
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+// 16-bit lane masks of two bits: bit 0 -> low half, bit 1 -> high half
+__device__ __forceinline__ uint32_t pair_mask(uint32_t two_bits) {
+  return ((0u - (two_bits & 1u)) & 0xFFFFu) | ((0u - ((two_bits >> 1) & 1u)) & 0xFFFF0000u);
+}
 
 __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int64_t n, int64_t k, int64_t KW,
                                                         const float* w, const float* wu, const int32_t* uni,
@@ -216,10 +232,17 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
   uint64_t (*As)[kChunk + 1] = (uint64_t (*)[kChunk + 1])raw;
   uint64_t (*Bs)[kChunk + 1] = (uint64_t (*)[kChunk + 1])(raw + kTile * (kChunk + 1));
   __shared__ float wrow[kChunk * 64];
+  __shared__ gram_u2_t wpk[3][kChunk * 16];  // weight pieces as bfloat16, rows 4j..4j+3 of a word per entry
+  __shared__ gram_u2_t tabA[16], tabB[16];   // four bits -> 16-bit masks / bfloat16 ones (two registers)
   __shared__ float wus[kChunk];
   __shared__ int unis[kChunk];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const int lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+  if (tid < 16) {
+    const gram_u2_t m = {pair_mask(tid & 3u), pair_mask((uint32_t)tid >> 2)};
+    tabA[tid] = m;
+    tabB[tid] = gram_u2_t{m.x & 0x3F803F80u, m.y & 0x3F803F80u};
+  }
   const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
   const int64_t a0 = (int64_t)ta * kTile, b0 = (int64_t)tb * kTile;
   double* G = Gp + (size_t)blockIdx.z * n * n;
@@ -247,6 +270,21 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
     for (int idx = tid; idx < kChunk * 64; idx += kThreads) {
       const int64_t i = wd0 * 64 + idx;
       wrow[idx] = i < k ? w[i] : 0.f;
+    }
+    for (int idx = tid; idx < kChunk * 16; idx += kThreads) {  // rows 4 idx .. 4 idx + 3 of the chunk
+      uint32_t pc[3][4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int64_t i = wd0 * 64 + 4 * (int64_t)idx + j;
+        float rest = i < k ? w[i] : 0.f;
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+          pc[p][j] = bf16_bits_rn(rest);
+          rest -= __uint_as_float(pc[p][j] << 16);  // exact: the piece shares the leading bits of `rest`
+        }
+      }
+#pragma unroll
+      for (int p = 0; p < 3; ++p) wpk[p][idx] = gram_u2_t{pc[p][0] | (pc[p][1] << 16), pc[p][2] | (pc[p][3] << 16)};
     }
     if (tid < kChunk) {
       const int64_t wd = wd0 + tid;
@@ -276,20 +314,22 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
       } else if (unis[c] == 3) {
         // no kept row in this word
       } else if (unis[c] == 2) {
-        // rows 2q + half, q < 32: bits of the two 32-bit halves of the column words, pre-shifted by `half`
-        const uint64_t aw = As[wi + l32][c] >> half, bw = Bs[wj + l32][c] >> half;
-        const uint32_t alo = (uint32_t)aw, ahi = (uint32_t)(aw >> 32), blo = (uint32_t)bw, bhi = (uint32_t)(bw >> 32);
-        const float* wr = wrow + c * 64 + half;
+        // rows 8 kb + 4 half + j, j < 4: a nibble of each column word per step (pre-shifted by 4 half)
+        const uint64_t aw = As[wi + l32][c] >> (4 * half), bw = Bs[wj + l32][c] >> (4 * half);
+        const gram_u2_t* w1 = wpk[0] + c * 16 + half;
+        const gram_u2_t* w2 = wpk[1] + c * 16 + half;
+        const gram_u2_t* w3 = wpk[2] + c * 16 + half;
 #pragma unroll
-        for (int q = 0; q < 32; q += 2) {
-          const uint32_t ax = q < 16 ? alo : ahi, bx = q < 16 ? blo : bhi;
-          const int sh = (2 * q) & 31;
-          const float a0v = (ax & (1u << sh)) ? wr[2 * q] : 0.f;
-          const float b0v = (float)((bx >> sh) & 1u);
-          const float a1v = (ax & (1u << (sh + 2))) ? wr[2 * q + 2] : 0.f;
-          const float b1v = (float)((bx >> (sh + 2)) & 1u);
-          fm0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0v, b0v, fm0, 0, 0, 0);
-          fm1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1v, b1v, fm1, 0, 0, 0);
+        for (int kb = 0; kb < 8; ++kb) {
+          const gram_u2_t am = tabA[(uint32_t)(aw >> (8 * kb)) & 15u];
+          const gram_s4_t bo = __builtin_bit_cast(gram_s4_t, tabB[(uint32_t)(bw >> (8 * kb)) & 15u]);
+          const gram_u2_t p1 = w1[2 * kb], p2 = w2[2 * kb], p3 = w3[2 * kb];
+          const gram_s4_t a1 = __builtin_bit_cast(gram_s4_t, gram_u2_t{p1.x & am.x, p1.y & am.y});
+          const gram_s4_t a2 = __builtin_bit_cast(gram_s4_t, gram_u2_t{p2.x & am.x, p2.y & am.y});
+          const gram_s4_t a3 = __builtin_bit_cast(gram_s4_t, gram_u2_t{p3.x & am.x, p3.y & am.y});
+          fm0 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a1, bo, fm0, 0, 0, 0);
+          fm1 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a2, bo, fm1, 0, 0, 0);
+          fm1 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a3, bo, fm1, 0, 0, 0);
         }
       } else {
         uint64_t av[4], bv[4];
