@@ -78,7 +78,7 @@ __global__ void word_weights_kernel(const float* w, int64_t k, int64_t KW, const
 
 // ---- sparse rows: row-wise outer products -------------------------------------------------------
 // A row with s of n columns set touches s^2 entries of G, while the column-wise kernel pays for all
-// n^2/2 pairs of columns whatever the row holds; up to a density of about 1/8 the row-wise form is the
+// n^2/2 pairs of columns whatever the row holds; up to a density of about a tenth the row-wise form is the
 // cheaper one, and in a Kernel-SHAP sample most rows are far sparser than that. Rows are split by their
 // own popcount: sparse ones go to gram_rows_kernel, the others stay with the column-wise kernel
 // (`keep` holds their bits per 64-row word).
@@ -86,7 +86,7 @@ __global__ void word_weights_kernel(const float* w, int64_t k, int64_t KW, const
 //   wq[r]     = weight of row r in fixed point, w_r * 2^e with e chosen so that the sum of all weights stays
 //               below 2^62: every entry of G is a sum over a subset of the rows, so the integer sums cannot
 //               overflow, they are exact, and they do not depend on the order of the atomic additions.
-constexpr int kSparseDivisor = 8;  // rows with at most n / 8 columns set are sparse
+constexpr int kSparseDivisor = 12;  // rows with at most n / 12 columns set are sparse (measured optimum: flat from 8 to 16)
 
 // scale[0] = 2^e (0 if the weights are not all finite and non-negative: then every row is kept)
 __global__ __launch_bounds__(kThreads) void gram_scale_kernel(const float* gw, int64_t R, double* scale) {
@@ -122,8 +122,8 @@ __global__ __launch_bounds__(kThreads) void gram_scale_kernel(const float* gw, i
 // one wave per used row
 __global__ __launch_bounds__(kThreads) void gram_row_class_kernel(const uint64_t* Z, int64_t R, int64_t W, int64_t n,
                                                                   int64_t row_step, const float* gw, const double* scale,
-                                                                  uint64_t* Zc, unsigned long long* keep,
-                                                                  unsigned long long* wq) {
+                                                                  int sparse_divisor, uint64_t* Zc,
+                                                                  unsigned long long* keep, unsigned long long* wq) {
   const int lane = threadIdx.x & 63;
   const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void gram_row_class_kernel(const uint64_t
     int c = 0;
     for (int64_t x = lane; x < W; x += 64) c += __popcll(zr[x]);
     for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
-    const bool sparse = sc > 0.0 && (int64_t)c * kSparseDivisor <= n;
+    const bool sparse = sc > 0.0 && (int64_t)c * sparse_divisor <= n;
     for (int64_t x = lane; x < W; x += 64) Zc[x * R + r] = sparse ? zr[x] : 0ull;
     if (lane == 0) {
       wq[r] = sparse ? (unsigned long long)llrint((double)gw[r] * sc) : 0ull;
@@ -905,6 +905,16 @@ inline float dense_fraction() {
   return v;
 }
 
+// tuning knob: DISTSHAP_GRAM_SPARSE_DIV overrides the divisor d of the rule "at most n / d columns set = sparse row"
+inline int sparse_divisor() {
+  static const int v = [] {
+    const char* e = getenv("DISTSHAP_GRAM_SPARSE_DIV");
+    const int x = e ? atoi(e) : kSparseDivisor;
+    return x >= 1 ? x : kSparseDivisor;
+  }();
+  return v;
+}
+
 inline unsigned nblocks(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
 struct GramDims {
@@ -989,7 +999,7 @@ int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const fl
     int64_t blocks = (R * 64 + kThreads - 1) / kThreads;
     if (blocks > (int64_t)ctx->num_cus * 16) blocks = (int64_t)ctx->num_cus * 16;
     hipLaunchKernelGGL(gram_row_class_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, Z, R, W, n, row_step, gw,
-                       gscale, Zc, (unsigned long long*)keep, (unsigned long long*)wq);
+                       gscale, sparse_divisor(), Zc, (unsigned long long*)keep, (unsigned long long*)wq);
   }
   hipLaunchKernelGGL(word_weights_kernel, dim3(nblocks(RW, 256)), dim3(256), 0, st, gw, R, RW, Z, W, n, row_step,
                      dense_fraction(), keep, wu, uni);
