@@ -74,18 +74,25 @@ def gat_flops_per_coalition(ctx, cg, model):
     return flops
 
 
-def cholesky_launches(n, block=64, fuse_rows=2048):
-    """Kernel launches of the blocked factorisation: per 64-column block a panel and a trailing update; a
-    diagonal block gets a launch of its own unless the update before it factorised it (trailing matrix of at
-    most `fuse_rows` rows, the library's rule)."""
-    count, done = 0, False
-    for j0 in range(0, n, block):
+def cholesky_launches(n, block=64, fuse_rows=2048, super_cols=256):
+    """Kernel launches of the blocked factorisation (the library's rules): while more than `fuse_rows` rows
+    trail a super-panel of 256 columns, 4 panels + 3 narrow updates (each factorising the next diagonal block) +
+    1 diagonal block + 1 wide update; afterwards per 64-column block a panel and a trailing update, a diagonal
+    block having a launch of its own unless the update before it factorised it."""
+    count, done, j0 = 0, False, 0
+    while j0 < n:
+        if (n + 1) - j0 - super_cols > fuse_rows and n - j0 >= super_cols + block:
+            count += 1 + 4 + 3 + 1
+            j0 += super_cols
+            done = False
+            continue
         nb = min(block, n - j0)
         count += (0 if done else 1) + 1
         done = False
         if n - j0 - nb > 0:
             count += 1
             done = (n + 1 - j0 - nb) <= fuse_rows
+        j0 += nb
     return count
 
 

@@ -1045,14 +1045,15 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
       for (int b = 0; b < kSuperCols / NB; ++b) {
         const int64_t jb = j0 + (int64_t)b * NB;
         double* li = linv + (size_t)(jb / NB) * NB * NB;
-        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, jb, NB, li, gs->flag);
+        // inside the super-panel the narrow update factorises the next diagonal block on the way
+        if (b == 0) hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, jb, NB, li, gs->flag);
         const int64_t rest = rows_total - jb - NB;
         const unsigned tt = nblocks(rest, kTile);
         hipLaunchKernelGGL(chol_panel_kernel, dim3(tt), dim3(kThreads), 0, st, M, ld, rows_total, jb, NB, li);
         const unsigned inside = (unsigned)(kSuperCols / NB - 1 - b);  // block columns of the super-panel still ahead
         if (inside > 0)
-          hipLaunchKernelGGL(chol_update_kernel<false>, dim3(inside, tt), dim3(kThreads), 0, st, M, ld, rows_total, n, jb,
-                             NB, (double*)nullptr, gs->flag);
+          hipLaunchKernelGGL(chol_update_kernel<true>, dim3(inside, tt), dim3(kThreads), 0, st, M, ld, rows_total, n, jb,
+                             NB, li + (size_t)NB * NB, gs->flag);
       }
       const int64_t base = j0 + kSuperCols;
       const unsigned tw = nblocks(rows_total - base, kTile);
