@@ -91,6 +91,36 @@ __global__ __launch_bounds__(kThreads) void scan_apply(const int32_t* in, int32_
   }
 }
 
+// short inputs: the whole exclusive scan in one launch. Every thread owns a contiguous run of items: it sums
+// them, the 1024 run sums are scanned in LDS, and the thread then walks its run again (out may alias in: a
+// run is read and written by its owner only, after every first pass is over).
+constexpr int kSmallScanThreads = 1024;
+constexpr int64_t kSmallScanMax = 4096;  // beyond a few items per thread the strided runs cost more than two extra launches
+__global__ __launch_bounds__(kSmallScanThreads) void scan_small_kernel(const int32_t* in, int32_t* out, int64_t count,
+                                                                       int64_t* total_out) {
+  __shared__ int sh[kSmallScanThreads];
+  const int tid = threadIdx.x;
+  const int64_t per = (count + kSmallScanThreads - 1) / kSmallScanThreads;
+  const int64_t b = (int64_t)tid * per, e = b + per < count ? b + per : count;
+  int s = 0;
+  for (int64_t i = b; i < e; ++i) s += in[i];
+  sh[tid] = s;
+  __syncthreads();
+  for (int o = 1; o < kSmallScanThreads; o <<= 1) {  // Hillis-Steele inclusive scan of the run sums
+    const int add = tid >= o ? sh[tid - o] : 0;
+    __syncthreads();
+    sh[tid] += add;
+    __syncthreads();
+  }
+  int run = sh[tid] - s;
+  for (int64_t i = b; i < e; ++i) {
+    const int v = in[i];
+    out[i] = run;
+    run += v;
+  }
+  if (tid == kSmallScanThreads - 1 && total_out) *total_out = sh[tid];
+}
+
 }  // namespace
 
 size_t ds_scan_arena_bytes(int64_t count) {
@@ -102,6 +132,11 @@ size_t ds_scan_arena_bytes(int64_t count) {
 int ds_scan_exclusive_i32(ds_ctx* ctx, const int32_t* in, int32_t* out, int64_t count, int64_t* total_mail_slot) {
   if (count <= 0) {
     if (total_mail_slot) DS_HIP(ctx, hipMemsetAsync(total_mail_slot, 0, sizeof(int64_t), ctx->stream));
+    return DS_OK;
+  }
+  if (count <= kSmallScanMax) {
+    hipLaunchKernelGGL(scan_small_kernel, dim3(1), dim3(kSmallScanThreads), 0, ctx->stream, in, out, count, total_mail_slot);
+    DS_HIP(ctx, hipGetLastError());
     return DS_OK;
   }
   const int64_t tiles = (count + kScanTile - 1) / kScanTile;
@@ -342,6 +377,23 @@ int ds_validate_csr(ds_ctx* ctx) {
 }
 
 namespace {
+__global__ void zero_three_kernel(int32_t* a, int32_t* b, int32_t* c) {
+  if (threadIdx.x == 0) {
+    *a = 0;
+    *b = 0;
+    *c = 0;
+  }
+}
+// the three per-node arrays of the computational graph in one launch (row_ptr has V + 1 entries)
+__global__ void copy_node_arrays_kernel(const int32_t* rp, const int64_t* gid, const int32_t* hop, int64_t V, int32_t* rp_out,
+                                        int64_t* gid_out, int32_t* hop_out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i <= V) rp_out[i] = rp[i];
+  if (i < V) {
+    gid_out[i] = gid[i];
+    hop_out[i] = hop[i];
+  }
+}
 struct BallSizes { int32_t v[8]; };
 // out[h] = row_ptr[ball[h]]: the CSR entries of the rows within h hops
 __global__ void ball_entries_kernel(const int32_t* row_ptr, BallSizes b, int64_t* out) {
@@ -407,9 +459,7 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
     return ds_fail(ctx, DS_EINTERNAL, "extract: arena exhausted (phase 2)");
   }
   hipLaunchKernelGGL(assign_nodes, dim3(blocks_for(N)), dim3(kThreads), 0, st, dist, lid_scan, rank_scan, N, node_gid_tmp, hop_tmp, lid_of_rank);
-  DS_HIP(ctx, hipMemsetAsync(rowptr_tmp + V, 0, 4, st));
-  DS_HIP(ctx, hipMemsetAsync(cnt_all_rank + V, 0, 4, st));
-  DS_HIP(ctx, hipMemsetAsync(cnt_up_rank + V, 0, 4, st));
+  hipLaunchKernelGGL(zero_three_kernel, dim3(1), dim3(64), 0, st, rowptr_tmp + V, cnt_all_rank + V, cnt_up_rank + V);
   const unsigned wave_blocks = (unsigned)((V * 64 + kThreads - 1) / kThreads < (int64_t)ctx->num_cus * 8 ? (V * 64 + kThreads - 1) / kThreads : (int64_t)ctx->num_cus * 8);
   hipLaunchKernelGGL(count_entries, dim3(wave_blocks), dim3(kThreads), 0, st, ctx->row_ptr, ctx->col, dist, node_gid_tmp, lid_of_rank, V, rowptr_tmp, cnt_all_rank, cnt_up_rank);
   DS_HIP(ctx, hipGetLastError());
@@ -482,9 +532,8 @@ int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgra
   ctx->graphs.push_back(cg);
   *out_cg = cg;
 
-  DS_HIP(ctx, hipMemcpyAsync(cg->row_ptr, rowptr_tmp, (V + 1) * 4, hipMemcpyDeviceToDevice, st));
-  DS_HIP(ctx, hipMemcpyAsync(cg->node_gid, node_gid_tmp, V * 8, hipMemcpyDeviceToDevice, st));
-  DS_HIP(ctx, hipMemcpyAsync(cg->hop, hop_tmp, V * 4, hipMemcpyDeviceToDevice, st));
+  hipLaunchKernelGGL(copy_node_arrays_kernel, dim3((unsigned)((V + 1 + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
+                     rowptr_tmp, node_gid_tmp, hop_tmp, V, cg->row_ptr, cg->node_gid, cg->hop);
   GraphOut go{cg->row_ptr, cg->col, cg->eid, cg->pl, cg->node_gid, cg->hop};
   hipLaunchKernelGGL(fill_entries, dim3(wave_blocks), dim3(kThreads), 0, st, ctx->row_ptr, ctx->col, dist, lid_scan, N, lid_of_rank, player_start, V, directed, go);
   if (!directed && nnz_c > 0)
