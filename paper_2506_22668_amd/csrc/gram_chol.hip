@@ -457,167 +457,14 @@ __global__ __launch_bounds__(kThreads) void build_rhs_kernel(const double* c, in
 // ---------------- blocked Cholesky (lower, in place, fp64) ----------------
 constexpr int NB = 64;
 
-// Factor the nb x nb diagonal block at j0 and invert the factor in the same sweep.
-// 16x16 threads; thread (ty, tx) keeps the elements (ty+16i, tx+16j), i, j < 4, of the block S
-// and of Y (initially I) in registers. Right-looking step kk: the owners publish column kk of S
-// and row kk of Y in LDS (double-buffered, so ONE barrier per step), then everyone updates
-//   S[r][c] -= S[r][kk] S[c][kk] / p          (c > kk)       -> L = S scaled by 1/sqrt(p) per column
-//   Y[r][c] -= S[r][kk] Y[kk][c] / p          (r > kk)       -> L^-1 = Y scaled by 1/sqrt(p) per row
-// i.e. the forward substitution L X = I rides along with the factorisation and needs no extra
-// sequential pass. Linv (NB x NB, identity-padded) goes to linv_out.
+// 1/sqrt(p) for 1e-30 < p < 1e30: single-precision seed, two Newton steps r += r (1/2 - (p/2) r^2) in double (a
+// short dependent chain; the library routine costs several times more per step of a sequential loop)
 __device__ __forceinline__ double fast_rsqrt(double p) {
-  // 1/sqrt(p): single-precision seed, two Newton steps r += r (1/2 - (p/2) r^2) in double (a short dependent
-  // chain; the library routine costs several times more per step of this sequential loop)
-  if (p > 1e-30 && p < 1e30) {
-    double r = (double)__frsqrt_rn((float)p);       // relative error about 1e-7
-    const double hp = 0.5 * p;
-    r = fma(r, fma(-hp * r, r, 0.5), r);             // -> 1e-14
-    r = fma(r, fma(-hp * r, r, 0.5), r);             // -> below one ulp
-    return r;
-  }
-  return rsqrt(p);
-}
-
-// kCw columns per barrier: the owners publish columns kk .. kk+kCw-1 of S and the same rows of Y. Every
-// thread then eliminates the small kCw x kCw pivot block on its own (it needs the multipliers
-// a[u][w] = S'[kk+w][kk+u] / p_u of that elimination), rebuilds for its own rows and columns each
-// published column/row as it stands after the updates of the columns before it, and applies the kCw
-// rank-1 updates to its registers at once. (64 is a multiple of kCw; padding rows are identity rows.)
-constexpr int kCw = 4;
-
-// `pend`: optional 64 x 64 tile (LDS, pitch NB+1) holding the rows of this block in the panel just finished;
-// its outer product is the one trailing update the block has not received yet and is subtracted first.
-__device__ __forceinline__ void chol_diag_body(double* M, int64_t ld, int64_t j0, int nb, double* linv_out, int* flag,
-                                               const double (*pend)[NB + 1]) {
-  __shared__ double cols[2][kCw][NB];
-  __shared__ double rows[2][kCw][NB];
-  __shared__ double dinv[NB];
-  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-  double s[4][4], y[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int r = ty + 16 * i, c = tx + 16 * j;
-      s[i][j] = (r < nb && c < nb) ? M[(j0 + r) * ld + j0 + c] : (r == c ? 1.0 : 0.0);
-      y[i][j] = r == c ? 1.0 : 0.0;
-    }
-  if (pend) {  // rows past nb of the tile are zero, so the identity padding stays as it is
-#pragma unroll 4
-    for (int k = 0; k < NB; ++k) {
-      double pr[4], pc[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        pr[i] = pend[ty + 16 * i][k];
-        pc[i] = pend[tx + 16 * i][k];
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) s[i][j] = fma(-pr[i], pc[j], s[i][j]);
-    }
-  }
-  bool bad = false;
-  for (int kk = 0; kk < NB; kk += kCw) {
-    const int buf = (kk / kCw) & 1, blk = kk >> 4, off = kk & 15;  // the kCw columns lie in one 16-block
-    if (tx >= off && tx < off + kCw) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (j == blk) {
-          double* dst = cols[buf][tx - off];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) dst[ty + 16 * i] = s[i][j];
-        }
-    }
-    if (ty >= off && ty < off + kCw) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (i == blk) {
-          double* dst = rows[buf][ty - off];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) dst[tx + 16 * j] = y[i][j];
-        }
-    }
-    __syncthreads();
-    // pivot block: P[v][w] = S[kk+v][kk+w], eliminated column by column
-    double P[kCw][kCw], ip[kCw], rs[kCw], a[kCw][kCw];
-#pragma unroll
-    for (int w = 0; w < kCw; ++w)
-#pragma unroll
-      for (int v = 0; v < kCw; ++v) P[v][w] = cols[buf][w][kk + v];
-#pragma unroll
-    for (int w = 0; w < kCw; ++w) {
-      double pw = P[w][w];
-      if (!(pw > 0.0)) {
-        bad = true;
-        pw = 1.0;
-      }
-      rs[w] = fast_rsqrt(pw);
-      ip[w] = rs[w] * rs[w];
-#pragma unroll
-      for (int w2 = w + 1; w2 < kCw; ++w2) {
-        a[w][w2] = P[w2][w] * ip[w];
-#pragma unroll
-        for (int v = w2; v < kCw; ++v) P[v][w2] = fma(-a[w][w2], P[v][w], P[v][w2]);
-      }
-    }
-    // this thread's rows (left factors) and columns (right factors) of the kCw updates; the guards sit
-    // here, not on the updates: update w leaves columns <= kk+w of S and rows <= kk+w of Y alone
-    double lS[kCw][4], lY[kCw][4], cS[kCw][4], cY[kCw][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = ty + 16 * i, c = tx + 16 * i;
-      double tr[kCw], tc[kCw], tyc[kCw];
-#pragma unroll
-      for (int w = 0; w < kCw; ++w) {
-        tr[w] = cols[buf][w][r];
-        tc[w] = cols[buf][w][c];
-        tyc[w] = rows[buf][w][c];
-#pragma unroll
-        for (int u = 0; u < w; ++u) {
-          tr[w] = fma(-a[u][w], tr[u], tr[w]);
-          tc[w] = fma(-a[u][w], tc[u], tc[w]);
-          tyc[w] = fma(-a[u][w], tyc[u], tyc[w]);
-        }
-        const double l = -tr[w] * ip[w];
-        lS[w][i] = l;
-        lY[w][i] = r > kk + w ? l : 0.0;
-        cS[w][i] = c > kk + w ? tc[w] : 0.0;
-        cY[w][i] = tyc[w];
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        double sv = s[i][j], yv = y[i][j];
-#pragma unroll
-        for (int w = 0; w < kCw; ++w) {
-          sv = fma(lS[w][i], cS[w][j], sv);
-          yv = fma(lY[w][i], cY[w][j], yv);
-        }
-        s[i][j] = sv;
-        y[i][j] = yv;
-      }
-#pragma unroll
-    for (int w = 0; w < kCw; ++w)
-      if (tid == w) dinv[kk + w] = rs[w];
-  }
-  __syncthreads();
-  if (bad && tid == 0) atomicExch(flag, 1);
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int r = ty + 16 * i, c = tx + 16 * j;
-      if (r < nb && c <= r) M[(j0 + r) * ld + j0 + c] = s[i][j] * dinv[c];
-      linv_out[r * NB + c] = (c <= r) ? y[i][j] * dinv[r] : 0.0;
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t ld, int64_t j0, int nb, double* linv_out,
-                                                             int* flag) {
-  chol_diag_body(M, ld, j0, nb, linv_out, flag, nullptr);
+  double r = (double)__frsqrt_rn((float)p);  // relative error about 1e-7
+  const double hp = 0.5 * p;
+  r = fma(r, fma(-hp * r, r, 0.5), r);        // -> 1e-14
+  r = fma(r, fma(-hp * r, r, 0.5), r);        // -> below one ulp
+  return r;
 }
 
 typedef double double4_t __attribute__((ext_vector_type(4)));
@@ -639,6 +486,192 @@ __device__ __forceinline__ void tile_nt_mfma(const double (*A)[NB + 1], const do
     acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
     acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
   }
+}
+
+// value of `v` in lane `src` (a compile-time constant after unrolling) for the whole wave, through two scalar registers
+__device__ __forceinline__ double wave_bcast(double v, int src) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+  return __hiloint2double(hi, lo);
+}
+
+constexpr int kSub = 16;  // sub-block of the diagonal block: one matrix-core tile
+
+// One wave factorises the 16 x 16 block D = S[o.., o..] in place (lower factor) and writes its inverse to Ld.
+// Lane l < 16 keeps row l of D (columns up to l matter) and column l of the inverse X in registers (the other
+// lanes repeat them). Step j: every lane puts its entry of column j, as updated so far, into `col` (LDS), the
+// pivot d goes to all lanes through scalar registers, and with p = 1/d, L[i][j] L[k][j] = S[i][j] S[k][j] p: lane i
+// subtracts (S[i][j] p) col[k] from its entry of column k > j; the same column moves the forward substitution
+// L X = I on, X[k][c] -= col[k] (X[j][c] p). Only then are column j and row j of X scaled by 1/sqrt(d). The
+// column travels through LDS while the reciprocal square root is computed; reads of one address by all lanes are
+// a broadcast.
+__device__ __forceinline__ void factor_sub_block(double (*S)[NB + 1], int o, double (*Ld)[kSub + 1], double* col, int* flag) {
+  const int l = threadIdx.x & 15;
+  double a[kSub], x[kSub];
+#pragma unroll
+  for (int k = 0; k < kSub; ++k) {
+    a[k] = S[o + l][o + k];
+    x[k] = l == k ? 1.0 : 0.0;
+  }
+#pragma unroll
+  for (int j = 0; j < kSub; ++j) {
+    if (j + 1 < kSub) col[l] = a[j];
+    double d = wave_bcast(a[j], j);
+    if (!(d > 1e-30 && d < 1e30)) {  // not positive (or not a number, or out of the seed's range): report, carry on
+      if ((threadIdx.x & 63) == 0) atomicExch(flag, 1);
+      d = 1.0;
+    }
+    const double r = fast_rsqrt(d), ip = r * r;
+    const double t = a[j] * ip, u = x[j] * ip;
+    a[j] *= r;
+    x[j] *= r;
+    double c[kSub];
+#pragma unroll
+    for (int k = j + 1; k < kSub; ++k) c[k] = col[k];
+#pragma unroll
+    for (int k = j + 1; k < kSub; ++k) {
+      a[k] = fma(-t, c[k], a[k]);
+      x[k] = fma(-c[k], u, x[k]);
+    }
+    // pin the updates to this step: left to itself the compiler defers the updates of a column until the
+    // column's own step and holds every earlier column in registers for them
+#pragma unroll
+    for (int k = j + 1; k < kSub; ++k) asm volatile("" : "+v"(a[k]), "+v"(x[k]));
+  }
+  if ((threadIdx.x & 63) < kSub) {
+#pragma unroll
+    for (int k = 0; k < kSub; ++k) {
+      if (k <= l) S[o + l][o + k] = a[k];
+      Ld[k][l] = x[k];
+    }
+  }
+}
+
+// 16 x 16 product on the fp64 matrix cores: acc + sign * A B with A(m, k) = Ap[m * ars + k * acs] and
+// B(k, n) = Bp[k * brs + n * bcs]; lane l holds D[4 r + l / 16][l % 16], r = 0..3.
+__device__ __forceinline__ double4_t sub_block_mma(const double* Ap, int ars, int acs, const double* Bp, int brs, int bcs,
+                                                   double sign, double4_t acc) {
+  const int lane = threadIdx.x & 63, l16 = lane & 15, lk = lane >> 4;
+#pragma unroll
+  for (int kk = 0; kk < kSub; kk += 4) {
+    const double av = sign * Ap[l16 * ars + (kk + lk) * acs];
+    const double bv = Bp[(kk + lk) * brs + l16 * bcs];
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+  }
+  return acc;
+}
+__device__ __forceinline__ double4_t sub_block_load(const double (*T)[NB + 1], int r0, int c0) {
+  const int lane = threadIdx.x & 63, l16 = lane & 15, lk = lane >> 4;
+  double4_t v;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) v[r] = T[r0 + 4 * r + lk][c0 + l16];
+  return v;
+}
+__device__ __forceinline__ void sub_block_store(double (*T)[NB + 1], int r0, int c0, double4_t v) {
+  const int lane = threadIdx.x & 63, l16 = lane & 15, lk = lane >> 4;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) T[r0 + 4 * r + lk][c0 + l16] = v[r];
+}
+
+// Factor the nb x nb diagonal block at j0 (lower factor L, in place) and invert the factor: Linv (NB x NB,
+// identity-padded) goes to linv_out. One workgroup of four waves; the block S and the inverse Y live in the two
+// LDS tiles the caller hands over. The block is taken as 4 x 4 sub-blocks of 16: for each block column b
+//   1. one wave factorises the diagonal sub-block and inverts its factor (the only sequential part: 16 columns),
+//   2. the sub-blocks below become L_ib = S_ib Linv_bb^T, and row b of Y becomes Linv_bb Y_b (Y starts as I and
+//      follows the forward substitution L Y = I block row by block row),
+//   3. S_ij -= L_ib L_jb^T on the lower sub-blocks behind, and Y_i -= L_ib Y_b on the block rows below,
+// steps 2 and 3 as 16 x 16 x 16 products on the fp64 matrix cores, shared out over the waves.
+// `pend`: optional 64 x 64 tile (LDS, pitch NB+1; may be the tile Y) holding the rows of this block in the panel
+// just finished; its outer product is the one trailing update the block has not received yet and is subtracted
+// first.
+__device__ __forceinline__ void chol_diag_body(double* M, int64_t ld, int64_t j0, int nb, double* linv_out, int* flag,
+                                               const double (*pend)[NB + 1], double (*S)[NB + 1], double (*Y)[NB + 1]) {
+  __shared__ double Ld[kSub][kSub + 1];
+  __shared__ __align__(16) double col[kSub];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  {
+    double4_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
+    if (pend) {  // rows past nb of the tile are zero, so the identity padding stays as it is
+      tile_nt_mfma(pend, pend, acc);
+      __syncthreads();  // every wave has read `pend` before Y (possibly the same tile) is cleared
+    }
+    const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int r = wi + 16 * i + 4 * r4 + (lane >> 4), c = wj + 16 * j + (lane & 15);
+          const double m = (r < nb && c < nb) ? M[(j0 + r) * ld + j0 + c] : (r == c ? 1.0 : 0.0);
+          S[r][c] = m - acc[i][j][r4];
+        }
+    for (int idx = tid; idx < NB * NB; idx += kThreads) Y[idx >> 6][idx & 63] = 0.0;
+  }
+  __syncthreads();
+  constexpr int nsb = NB / kSub;
+  for (int b = 0; b < nsb; ++b) {
+    const int o = b * kSub;
+    if (wave == 0) factor_sub_block(S, o, Ld, col, flag);
+    __syncthreads();
+    {  // step 2: (nsb - 1 - b) sub-blocks of the panel, b sub-blocks of Y's row b, and Y_bb = Linv_bb
+      int t = 0;
+      for (int i = b + 1; i < nsb; ++i, ++t)
+        if ((t & 3) == wave) {
+          const double4_t z = double4_t{0.0, 0.0, 0.0, 0.0};
+          // X(m, n) = sum_k S_ib(m, k) Ld(n, k)
+          const double4_t xv = sub_block_mma(&S[i * kSub][o], NB + 1, 1, &Ld[0][0], 1, kSub + 1, 1.0, z);
+          sub_block_store(S, i * kSub, o, xv);
+        }
+      for (int j = 0; j < b; ++j, ++t)
+        if ((t & 3) == wave) {
+          const double4_t z = double4_t{0.0, 0.0, 0.0, 0.0};
+          const double4_t yv = sub_block_mma(&Ld[0][0], kSub + 1, 1, &Y[o][j * kSub], NB + 1, 1, 1.0, z);
+          sub_block_store(Y, o, j * kSub, yv);
+        }
+      if ((t & 3) == wave) {
+        const int l16 = lane & 15, lk = lane >> 4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Y[o + 4 * r + lk][o + l16] = Ld[4 * r + lk][l16];
+      }
+    }
+    __syncthreads();
+    {  // step 3
+      int t = 0;
+      for (int i = b + 1; i < nsb; ++i)
+        for (int j = b + 1; j <= i; ++j, ++t)
+          if ((t & 3) == wave) {
+            const double4_t cur = sub_block_load(S, i * kSub, j * kSub);
+            // S_ij(m, n) -= sum_k L_ib(m, k) L_jb(n, k)
+            const double4_t nv = sub_block_mma(&S[i * kSub][o], NB + 1, 1, &S[j * kSub][o], 1, NB + 1, -1.0, cur);
+            sub_block_store(S, i * kSub, j * kSub, nv);
+          }
+      for (int i = b + 1; i < nsb; ++i)
+        for (int j = 0; j <= b; ++j, ++t)
+          if ((t & 3) == wave) {
+            const double4_t cur = sub_block_load(Y, i * kSub, j * kSub);
+            const double4_t nv = sub_block_mma(&S[i * kSub][o], NB + 1, 1, &Y[o][j * kSub], NB + 1, 1, -1.0, cur);
+            sub_block_store(Y, i * kSub, j * kSub, nv);
+          }
+    }
+    __syncthreads();
+  }
+  for (int idx = tid; idx < NB * NB; idx += kThreads) {
+    const int r = idx >> 6, c = idx & 63;
+    if (r < nb && c <= r) M[(j0 + r) * ld + j0 + c] = S[r][c];
+    linv_out[idx] = c <= r ? Y[r][c] : 0.0;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t ld, int64_t j0, int nb, double* linv_out,
+                                                             int* flag) {
+  __shared__ double S[kTile][NB + 1];
+  __shared__ double Y[kTile][NB + 1];
+  chol_diag_body(M, ld, j0, nb, linv_out, flag, nullptr, S, Y);
 }
 
 // rows below the diagonal block: X = A21 L11^-T = A21 Linv^T, a 64x64 product per workgroup
@@ -704,7 +737,8 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_
       for (int k = 0; k < NB; ++k) sum += Li[rr][k] * Lj[c][k];
       M[n * ld + base + c] -= sum;
     }
-    chol_diag_body(M, ld, base, (int)(n - base < NB ? n - base : NB), linv_next, flag, Lj);
+    __syncthreads();  // the row above has read Li, which becomes the block's tile
+    chol_diag_body(M, ld, base, (int)(n - base < NB ? n - base : NB), linv_next, flag, Lj, Li, Lj);
     return;
   }
   double4_t acc[2][2];
