@@ -467,6 +467,14 @@ __device__ __forceinline__ double fast_rsqrt(double p) {
   return r;
 }
 
+// 1/p for 1e-30 < p < 1e30: hardware seed (about 24 bits), two Newton steps x += x (1 - p x)
+__device__ __forceinline__ double fast_rcp(double p) {
+  double x = __builtin_amdgcn_rcp(p);
+  x = fma(x, fma(-p, x, 1.0), x);
+  x = fma(x, fma(-p, x, 1.0), x);
+  return x;
+}
+
 typedef double double4_t __attribute__((ext_vector_type(4)));
 
 // acc (+)= A[64 x 64] * B[64 x 64]^T for 64x64 tiles held in LDS with row pitch NB+1, on the fp64
@@ -497,64 +505,86 @@ __device__ __forceinline__ double wave_bcast(double v, int src) {
 
 constexpr int kSub = 16;  // sub-block of the diagonal block: one matrix-core tile
 
-// One wave factorises the 16 x 16 block D = S[o.., o..] in place (lower factor) and writes its inverse to Ld.
-// Lane l < 16 keeps row l of D (columns up to l matter) and column l of the inverse X in registers (the other
-// lanes repeat them). Step j: every lane puts its entry of column j, as updated so far, into `col` (LDS), the
-// pivot d goes to all lanes through scalar registers, and with p = 1/d, L[i][j] L[k][j] = S[i][j] S[k][j] p: lane i
-// subtracts (S[i][j] p) col[k] from its entry of column k > j; the same column moves the forward substitution
-// L X = I on, X[k][c] -= col[k] (X[j][c] p). Only then are column j and row j of X scaled by 1/sqrt(d). The
-// column travels through LDS while the reciprocal square root is computed; reads of one address by all lanes are
-// a broadcast.
-__device__ __forceinline__ void factor_sub_block(double (*S)[NB + 1], int o, double (*Ld)[kSub + 1], double* col, int* flag) {
-  const int l = threadIdx.x & 15;
-  double a[kSub], x[kSub];
+// One wave eliminates the 16 x 16 block D = S[o.., o..] and, alongside, the identity: what it leaves is the factor
+// and its inverse up to the scaling by 1/sqrt(pivot), which the other waves apply where they use them,
+//   L[i][k] = S[o+i][o+k] r_k,   Linv[k][c] = XT[c][k] r_k,   r_k = 1/sqrt(d_k),   d_k = S[o+k][o+k].
+// A lone wave issues one instruction every few cycles whatever the instruction is, so the loop holds nothing that
+// can be done elsewhere: no square root, no pivot check, no stores to global memory.
+// Lane l < 16 keeps row l of D (columns up to l matter), lane 16 + l keeps column l of the inverse (the upper half
+// of the wave repeats the lower). With d the pivot of column j and p = 1/d, L[i][j] L[k][j] = S[i][j] S[k][j] p:
+// lane i subtracts (S[i][j] p) col[k] from its entry of column k > j, where col[] is column j as updated so far,
+// which every lane has put into LDS (entry j of it is the pivot's own lane's); the same column moves the forward substitution L X = I on,
+// X[k][c] -= col[k] (X[j][c] p), so one multiply-add per k serves both halves. The pivot reaches all lanes through
+// scalar registers; the column travels through LDS (two buffers; reads of one address by all lanes are a
+// broadcast) under the updates of the step before. I16 is a 16 x 16 identity.
+__device__ __forceinline__ void eliminate_sub_block(double (*S)[NB + 1], int o, double (*XT)[kSub + 1],
+                                                    const double (*I16)[kSub + 1], double* col) {
+  const int lane = threadIdx.x & 63, l = lane & 15, slot = lane & 31;
+  const bool inv = (lane & 16) != 0;
+  double* mine = inv ? &XT[l][0] : &S[o + l][o];
+  const double* init = inv ? &I16[l][0] : mine;
+  double v[kSub];
 #pragma unroll
-  for (int k = 0; k < kSub; ++k) {
-    a[k] = S[o + l][o + k];
-    x[k] = l == k ? 1.0 : 0.0;
+  for (int k = 0; k < kSub; ++k) v[k] = init[k];
+  // The column's store and loads are written as instructions: the loads of the next column have to be issued right
+  // behind its store, so that they return under the remaining updates of this column, and the compiler's scheduler
+  // puts them next to their first use instead. LDS answers a wave in order, so the compiler's own counting of its
+  // LDS accesses stays on the safe side.
+  typedef double pair_t __attribute__((ext_vector_type(2)));
+  const unsigned col_lds = (unsigned)(size_t)(__attribute__((address_space(3))) double*)col;  // byte address in LDS
+  const unsigned slot_lds = col_lds + 8u * slot;
+  pair_t q[kSub / 2];
+  asm volatile("ds_write_b64 %0, %1" ::"v"(slot_lds), "v"(v[0]) : "memory");
+#pragma unroll
+  for (int h = 0; h < kSub / 2; ++h) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(q[h]) : "v"(col_lds), "n"(16 * h));
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]), "+v"(q[4]), "+v"(q[5]), "+v"(q[6]), "+v"(q[7]));
+  double c[kSub];
+#pragma unroll
+  for (int h = 0; h < kSub / 2; ++h) {
+    c[2 * h] = q[h].x;
+    c[2 * h + 1] = q[h].y;
   }
 #pragma unroll
-  for (int j = 0; j < kSub; ++j) {
-    if (j + 1 < kSub) col[l] = a[j];
-    double d = wave_bcast(a[j], j);
-    if (!(d > 1e-30 && d < 1e30)) {  // not positive (or not a number, or out of the seed's range): report, carry on
-      if ((threadIdx.x & 63) == 0) atomicExch(flag, 1);
-      d = 1.0;
+  for (int j = 0; j + 1 < kSub; ++j) {
+    const double p = v[j] * fast_rcp(wave_bcast(v[j], j));
+    v[j + 1] = fma(-p, c[j + 1], v[j + 1]);
+    if (j + 2 < kSub) {  // the next column is complete: send it on its way before the other updates
+      asm volatile("ds_write_b64 %0, %1 offset:%2" ::"v"(slot_lds), "v"(v[j + 1]), "n"(((j + 1) & 1) * 256) : "memory");
+#pragma unroll
+      for (int h = (j + 2) / 2; h < kSub / 2; ++h)
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(q[h]) : "v"(col_lds), "n"(((j + 1) & 1) * 256 + 16 * h));
     }
-    const double r = fast_rsqrt(d), ip = r * r;
-    const double t = a[j] * ip, u = x[j] * ip;
-    a[j] *= r;
-    x[j] *= r;
-    double c[kSub];
 #pragma unroll
-    for (int k = j + 1; k < kSub; ++k) c[k] = col[k];
+    for (int k = j + 2; k < kSub; ++k) v[k] = fma(-p, c[k], v[k]);
+    // pin the updates to this step: left to itself the compiler defers the updates of a column until the column's
+    // own step and holds every earlier column in registers for them
 #pragma unroll
-    for (int k = j + 1; k < kSub; ++k) {
-      a[k] = fma(-t, c[k], a[k]);
-      x[k] = fma(-c[k], u, x[k]);
-    }
-    // pin the updates to this step: left to itself the compiler defers the updates of a column until the
-    // column's own step and holds every earlier column in registers for them
+    for (int k = j + 2; k < kSub; ++k) asm volatile("" : "+v"(v[k]));
+    if (j + 2 < kSub) {
+      // q[h] for h below (j + 2) / 2 were not loaded again and pass through unchanged
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]), "+v"(q[4]), "+v"(q[5]), "+v"(q[6]), "+v"(q[7]));
 #pragma unroll
-    for (int k = j + 1; k < kSub; ++k) asm volatile("" : "+v"(a[k]), "+v"(x[k]));
-  }
-  if ((threadIdx.x & 63) < kSub) {
-#pragma unroll
-    for (int k = 0; k < kSub; ++k) {
-      if (k <= l) S[o + l][o + k] = a[k];
-      Ld[k][l] = x[k];
+      for (int h = (j + 2) / 2; h < kSub / 2; ++h) {
+        c[2 * h] = q[h].x;
+        c[2 * h + 1] = q[h].y;
+      }
     }
   }
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int k = 0; k < kSub; ++k) mine[k] = v[k];
 }
 
-// 16 x 16 product on the fp64 matrix cores: acc + sign * A B with A(m, k) = Ap[m * ars + k * acs] and
-// B(k, n) = Bp[k * brs + n * bcs]; lane l holds D[4 r + l / 16][l % 16], r = 0..3.
+// sum_k A(m, k) B(k, n) over a 16 x 16 x 16 product on the fp64 matrix cores, added to acc: A(m, k) = Ap[m * ars + k * acs]
+// and B(k, n) = Bp[k * brs + n * bcs]; lane l holds D[4 r + l / 16][l % 16], r = 0..3.
 __device__ __forceinline__ double4_t sub_block_mma(const double* Ap, int ars, int acs, const double* Bp, int brs, int bcs,
-                                                   double sign, double4_t acc) {
+                                                   double4_t acc) {
   const int lane = threadIdx.x & 63, l16 = lane & 15, lk = lane >> 4;
 #pragma unroll
   for (int kk = 0; kk < kSub; kk += 4) {
-    const double av = sign * Ap[l16 * ars + (kk + lk) * acs];
+    const double av = Ap[l16 * ars + (kk + lk) * acs];
     const double bv = Bp[(kk + lk) * brs + l16 * bcs];
     acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
   }
@@ -575,20 +605,24 @@ __device__ __forceinline__ void sub_block_store(double (*T)[NB + 1], int r0, int
 
 // Factor the nb x nb diagonal block at j0 (lower factor L, in place) and invert the factor: Linv (NB x NB,
 // identity-padded) goes to linv_out. One workgroup of four waves; the block S and the inverse Y live in the two
-// LDS tiles the caller hands over. The block is taken as 4 x 4 sub-blocks of 16: for each block column b
-//   1. one wave factorises the diagonal sub-block and inverts its factor (the only sequential part: 16 columns),
-//   2. the sub-blocks below become L_ib = S_ib Linv_bb^T, and row b of Y becomes Linv_bb Y_b (Y starts as I and
-//      follows the forward substitution L Y = I block row by block row),
-//   3. S_ij -= L_ib L_jb^T on the lower sub-blocks behind, and Y_i -= L_ib Y_b on the block rows below,
-// steps 2 and 3 as 16 x 16 x 16 products on the fp64 matrix cores, shared out over the waves.
+// LDS tiles the caller hands over. The block is taken as 4 x 4 sub-blocks of 16, left-looking; for block column b
+//   A. S_ib -= sum_{k<b} L_ik L_bk^T for i >= b, and T_bj = sum_{j<=k<b} L_bk Y_kj for j < b   (4 tasks, one a wave),
+//   B. one wave eliminates S_bb and the identity beside it (the only sequential part: 16 columns),
+//   C. L_ib = S_ib Linv_bb^T for i > b, Y_bj = -Linv_bb T_bj for j < b, and the scaled L_bb and Y_bb = Linv_bb
+//      (4 tasks, one a wave; this is where the square roots are taken and the pivots are checked),
+// where Y follows the forward substitution L Y = I block row by block row. A and C are 16 x 16 x 16 products on the
+// fp64 matrix cores; results go to global memory as they appear. A pivot that is not positive (or not a number, or
+// outside 1e-30 .. 1e30) raises the flag; nothing is repaired, the caller discards a flagged factorisation.
 // `pend`: optional 64 x 64 tile (LDS, pitch NB+1; may be the tile Y) holding the rows of this block in the panel
 // just finished; its outer product is the one trailing update the block has not received yet and is subtracted
 // first.
 __device__ __forceinline__ void chol_diag_body(double* M, int64_t ld, int64_t j0, int nb, double* linv_out, int* flag,
                                                const double (*pend)[NB + 1], double (*S)[NB + 1], double (*Y)[NB + 1]) {
-  __shared__ double Ld[kSub][kSub + 1];
-  __shared__ __align__(16) double col[kSub];
+  __shared__ double XT[kSub][kSub + 1];
+  __shared__ double I16[kSub][kSub + 1];
+  __shared__ __align__(16) double col[2 * 32];  // two buffers for the column in flight
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, lk = lane >> 4;
   {
     double4_t acc[2][2];
 #pragma unroll
@@ -597,7 +631,7 @@ __device__ __forceinline__ void chol_diag_body(double* M, int64_t ld, int64_t j0
       for (int j = 0; j < 2; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
     if (pend) {  // rows past nb of the tile are zero, so the identity padding stays as it is
       tile_nt_mfma(pend, pend, acc);
-      __syncthreads();  // every wave has read `pend` before Y (possibly the same tile) is cleared
+      __syncthreads();  // every wave has read `pend` before Y (possibly the same tile) is written
     }
     const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
 #pragma unroll
@@ -606,64 +640,72 @@ __device__ __forceinline__ void chol_diag_body(double* M, int64_t ld, int64_t j0
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
-          const int r = wi + 16 * i + 4 * r4 + (lane >> 4), c = wj + 16 * j + (lane & 15);
+          const int r = wi + 16 * i + 4 * r4 + lk, c = wj + 16 * j + l16;
           const double m = (r < nb && c < nb) ? M[(j0 + r) * ld + j0 + c] : (r == c ? 1.0 : 0.0);
           S[r][c] = m - acc[i][j][r4];
         }
-    for (int idx = tid; idx < NB * NB; idx += kThreads) Y[idx >> 6][idx & 63] = 0.0;
+    I16[tid >> 4][tid & 15] = (tid >> 4) == (tid & 15) ? 1.0 : 0.0;
+    // the sub-blocks of Linv above the diagonal are zero; the others are written as they are computed
+    for (int idx = tid; idx < NB * NB; idx += kThreads)
+      if (((idx & 63) >> 4) > (idx >> 10)) linv_out[idx] = 0.0;
   }
   __syncthreads();
   constexpr int nsb = NB / kSub;
+  const double4_t zero = double4_t{0.0, 0.0, 0.0, 0.0};
   for (int b = 0; b < nsb; ++b) {
     const int o = b * kSub;
-    if (wave == 0) factor_sub_block(S, o, Ld, col, flag);
+    if (b > 0) {  // A
+      if (wave < nsb - b) {
+        const int i = b + wave;
+        double4_t acc = zero;
+        for (int k = 0; k < b; ++k)  // (m, n): sum_kk S[16 i + m][16 k + kk] S[16 b + n][16 k + kk]
+          acc = sub_block_mma(&S[i * kSub][k * kSub], NB + 1, 1, &S[o][k * kSub], 1, NB + 1, acc);
+        sub_block_store(S, i * kSub, o, sub_block_load(S, i * kSub, o) - acc);
+      } else {
+        const int j = wave - (nsb - b);
+        double4_t acc = zero;
+        for (int k = j; k < b; ++k)  // (m, n): sum_kk S[o + m][16 k + kk] Y[16 k + kk][16 j + n]
+          acc = sub_block_mma(&S[o][k * kSub], NB + 1, 1, &Y[k * kSub][j * kSub], NB + 1, 1, acc);
+        sub_block_store(Y, o, j * kSub, acc);
+      }
+      __syncthreads();
+    }
+    if (wave == 0) eliminate_sub_block(S, o, XT, I16, col);  // B
     __syncthreads();
-    {  // step 2: (nsb - 1 - b) sub-blocks of the panel, b sub-blocks of Y's row b, and Y_bb = Linv_bb
-      int t = 0;
-      for (int i = b + 1; i < nsb; ++i, ++t)
-        if ((t & 3) == wave) {
-          const double4_t z = double4_t{0.0, 0.0, 0.0, 0.0};
-          // X(m, n) = sum_k S_ib(m, k) Ld(n, k)
-          const double4_t xv = sub_block_mma(&S[i * kSub][o], NB + 1, 1, &Ld[0][0], 1, kSub + 1, 1.0, z);
-          sub_block_store(S, i * kSub, o, xv);
-        }
-      for (int j = 0; j < b; ++j, ++t)
-        if ((t & 3) == wave) {
-          const double4_t z = double4_t{0.0, 0.0, 0.0, 0.0};
-          const double4_t yv = sub_block_mma(&Ld[0][0], kSub + 1, 1, &Y[o][j * kSub], NB + 1, 1, 1.0, z);
-          sub_block_store(Y, o, j * kSub, yv);
-        }
-      if ((t & 3) == wave) {
-        const int l16 = lane & 15, lk = lane >> 4;
+    {  // C
+      const double d = S[o + l16][o + l16];
+      const double rl = fast_rsqrt(d);  // r of this lane's column; r of row m is lane m's
+      if (wave < nsb - 1 - b) {
+        const int i = b + 1 + wave;  // L_ib(m, n) = r_n sum_k S_ib(m, k) XT(k, n)
+        const double4_t xv = sub_block_mma(&S[i * kSub][o], NB + 1, 1, &XT[0][0], kSub + 1, 1, zero) * rl;
+        sub_block_store(S, i * kSub, o, xv);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) Y[o + 4 * r + lk][o + l16] = Ld[4 * r + lk][l16];
+        for (int r = 0; r < 4; ++r) {
+          const int row = i * kSub + 4 * r + lk;
+          if (row < nb) M[(j0 + row) * ld + j0 + o + l16] = xv[r];
+        }
+      } else if (wave < nsb - 1) {
+        const int j = wave - (nsb - 1 - b);  // Y_bj(m, n) = -r_m sum_k XT(k, m) T(k, n)
+        const double4_t tv = sub_block_mma(&XT[0][0], 1, kSub + 1, &Y[o][j * kSub], NB + 1, 1, zero);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const double yv = -tv[r] * __shfl(rl, 4 * r + lk);
+          Y[o + 4 * r + lk][j * kSub + l16] = yv;
+          linv_out[(o + 4 * r + lk) * NB + j * kSub + l16] = yv;
+        }
+      } else {
+        if (!(d > 1e-30 && d < 1e30)) atomicExch(flag, 1);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int m = 4 * r + lk;  // row of the sub-block, column l16
+          const double x = XT[l16][m] * __shfl(rl, m);
+          Y[o + m][o + l16] = x;
+          linv_out[(o + m) * NB + o + l16] = x;
+          if (l16 <= m && o + m < nb) M[(j0 + o + m) * ld + j0 + o + l16] = S[o + m][o + l16] * rl;
+        }
       }
     }
     __syncthreads();
-    {  // step 3
-      int t = 0;
-      for (int i = b + 1; i < nsb; ++i)
-        for (int j = b + 1; j <= i; ++j, ++t)
-          if ((t & 3) == wave) {
-            const double4_t cur = sub_block_load(S, i * kSub, j * kSub);
-            // S_ij(m, n) -= sum_k L_ib(m, k) L_jb(n, k)
-            const double4_t nv = sub_block_mma(&S[i * kSub][o], NB + 1, 1, &S[j * kSub][o], 1, NB + 1, -1.0, cur);
-            sub_block_store(S, i * kSub, j * kSub, nv);
-          }
-      for (int i = b + 1; i < nsb; ++i)
-        for (int j = 0; j <= b; ++j, ++t)
-          if ((t & 3) == wave) {
-            const double4_t cur = sub_block_load(Y, i * kSub, j * kSub);
-            const double4_t nv = sub_block_mma(&S[i * kSub][o], NB + 1, 1, &Y[o][j * kSub], NB + 1, 1, -1.0, cur);
-            sub_block_store(Y, i * kSub, j * kSub, nv);
-          }
-    }
-    __syncthreads();
-  }
-  for (int idx = tid; idx < NB * NB; idx += kThreads) {
-    const int r = idx >> 6, c = idx & 63;
-    if (r < nb && c <= r) M[(j0 + r) * ld + j0 + c] = S[r][c];
-    linv_out[idx] = c <= r ? Y[r][c] : 0.0;
   }
 }
 
