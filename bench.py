@@ -77,9 +77,11 @@ def gat_flops_per_coalition(ctx, cg, model):
 def cholesky_launches(n, block=64, fuse_rows=2048, super_cols=256):
     """Kernel launches of the blocked factorisation (the library's rules): while more than `fuse_rows` rows
     trail a super-panel of 256 columns, 4 panels + 3 narrow updates (each factorising the next diagonal block) +
-    1 diagonal block + 1 wide update; afterwards per 64-column block a panel and a trailing update, a diagonal
-    block having a launch of its own unless the update before it factorised it."""
-    count, done, j0 = 0, False, 0
+    1 diagonal block + 1 wide update; afterwards one launch per full 64-column block that has columns behind it
+    (panel solve, trailing update and the next diagonal block together, plus one copy of the panel before the
+    first of them), and a panel launch for the last block; a diagonal block has a launch of its own only if
+    the launch before it did not factorise it."""
+    count, done, j0, panel_ready = 0, False, 0, False
     while j0 < n:
         if (n + 1) - j0 - super_cols > fuse_rows and n - j0 >= super_cols + block:
             count += 1 + 4 + 3 + 1
@@ -87,11 +89,16 @@ def cholesky_launches(n, block=64, fuse_rows=2048, super_cols=256):
             done = False
             continue
         nb = min(block, n - j0)
-        count += (0 if done else 1) + 1
+        count += 0 if done else 1
         done = False
-        if n - j0 - nb > 0:
+        rest = n + 1 - j0 - nb
+        if n - j0 - nb > 0 and rest <= fuse_rows:
+            count += (0 if panel_ready else 1) + 1
+            panel_ready, done = True, True
+        else:
             count += 1
-            done = (n + 1 - j0 - nb) <= fuse_rows
+            if n - j0 - nb > 0:
+                count += 1
         j0 += nb
     return count
 

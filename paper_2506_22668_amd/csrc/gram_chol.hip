@@ -616,8 +616,25 @@ __device__ __forceinline__ void sub_block_store(double (*T)[NB + 1], int r0, int
 // `pend`: optional 64 x 64 tile (LDS, pitch NB+1; may be the tile Y) holding the rows of this block in the panel
 // just finished; its outer product is the one trailing update the block has not received yet and is subtracted
 // first.
+// the block's entries as chol_diag_body wants them (identity beyond nb): each wave's 32 x 32 quadrant, matrix-core
+// layout. A caller with other work to do first loads them early, so that they arrive under that work.
+__device__ __forceinline__ void load_diag_block(const double* M, int64_t ld, int64_t j0, int nb, double4_t (&mt)[2][2]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int r = wi + 16 * i + 4 * r4 + (lane >> 4), c = wj + 16 * j + (lane & 15);
+        mt[i][j][r4] = (r < nb && c < nb) ? M[(j0 + r) * ld + j0 + c] : (r == c ? 1.0 : 0.0);
+      }
+}
+
 __device__ __forceinline__ void chol_diag_body(double* M, int64_t ld, int64_t j0, int nb, double* linv_out, int* flag,
-                                               const double (*pend)[NB + 1], double (*S)[NB + 1], double (*Y)[NB + 1]) {
+                                               const double (*pend)[NB + 1], double (*S)[NB + 1], double (*Y)[NB + 1],
+                                               const double4_t (&mt)[2][2]) {
   __shared__ double XT[kSub][kSub + 1];
   __shared__ double I16[kSub][kSub + 1];
   __shared__ __align__(16) double col[2 * 32];  // two buffers for the column in flight
@@ -641,8 +658,7 @@ __device__ __forceinline__ void chol_diag_body(double* M, int64_t ld, int64_t j0
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
           const int r = wi + 16 * i + 4 * r4 + lk, c = wj + 16 * j + l16;
-          const double m = (r < nb && c < nb) ? M[(j0 + r) * ld + j0 + c] : (r == c ? 1.0 : 0.0);
-          S[r][c] = m - acc[i][j][r4];
+          S[r][c] = mt[i][j][r4] - acc[i][j][r4];
         }
     I16[tid >> 4][tid & 15] = (tid >> 4) == (tid & 15) ? 1.0 : 0.0;
     // the sub-blocks of Linv above the diagonal are zero; the others are written as they are computed
@@ -713,7 +729,9 @@ __global__ __launch_bounds__(kThreads) void chol_diag_kernel(double* M, int64_t 
                                                              int* flag) {
   __shared__ double S[kTile][NB + 1];
   __shared__ double Y[kTile][NB + 1];
-  chol_diag_body(M, ld, j0, nb, linv_out, flag, nullptr, S, Y);
+  double4_t mt[2][2];
+  load_diag_block(M, ld, j0, nb, mt);
+  chol_diag_body(M, ld, j0, nb, linv_out, flag, nullptr, S, Y, mt);
 }
 
 // rows below the diagonal block: X = A21 L11^-T = A21 Linv^T, a 64x64 product per workgroup
@@ -780,7 +798,9 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_
       M[n * ld + base + c] -= sum;
     }
     __syncthreads();  // the row above has read Li, which becomes the block's tile
-    chol_diag_body(M, ld, base, (int)(n - base < NB ? n - base : NB), linv_next, flag, Lj, Li, Lj);
+    double4_t mt[2][2];
+    load_diag_block(M, ld, base, (int)(n - base < NB ? n - base : NB), mt);
+    chol_diag_body(M, ld, base, (int)(n - base < NB ? n - base : NB), linv_next, flag, Lj, Li, Lj, mt);
     return;
   }
   double4_t acc[2][2];
@@ -803,6 +823,99 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_
           if (r < rows_total && c < n && c <= r) M[r * ld + c] -= acc[i][j][r4];
         }
   }
+}
+
+// One launch per 64-column step while the trailing matrix is small (at most kFuseMaxRows rows): panel solve,
+// trailing update and factorisation of the next diagonal block together. Every workgroup (ti, tj), tj <= ti, first
+// solves its own two 64-row pieces of the panel, X = A Linv^T, instead of waiting for a launch that does so
+// (twice the arithmetic of the update itself, on workgroups that would otherwise be idle), then updates its tile;
+// the workgroup of the first diagonal tile factorises that tile instead, as in chol_update_kernel<true>.
+// The rows of the panel as the step before left them come from Pcur (row r of the matrix at Pcur[r * 64 ..]), not
+// from M: the workgroups of tile column 0 store the solved panel to M while others may still be reading, and they
+// store their updated tile, the next step's panel, to Pnext as well.
+__global__ __launch_bounds__(kThreads) void chol_step_kernel(double* M, int64_t ld, int64_t rows_total, int64_t n, int64_t j0,
+                                                             const double* linv, double* linv_next, int* flag,
+                                                             const double* Pcur, double* Pnext) {
+  const int ti = blockIdx.y, tj = blockIdx.x;
+  if (tj > ti) return;
+  __shared__ double Li[kTile][NB + 1];
+  __shared__ double Lj[kTile][NB + 1];
+  __shared__ double Ls[NB][NB + 1];
+  const int64_t base = j0 + NB;
+  const int64_t i0 = base + (int64_t)ti * kTile, c0 = base + (int64_t)tj * kTile;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
+  double4_t mt[2][2];  // the next diagonal block (first diagonal tile only), on its way while the panel is solved
+  if (ti == 0) load_diag_block(M, ld, base, (int)(n - base < NB ? n - base : NB), mt);
+  for (int idx = threadIdx.x; idx < kTile * NB; idx += kThreads) {
+    const int r = idx >> 6, c = idx & 63;
+    Li[r][c] = i0 + r < rows_total ? Pcur[(i0 + r) * NB + c] : 0.0;
+    if (ti != tj) Lj[r][c] = Pcur[(c0 + r) * NB + c];  // tj < ti: all 64 rows lie above row i0 <= n
+    Ls[r][c] = linv[idx];
+  }
+  __syncthreads();
+  double4_t xi[2][2], xj[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) xi[i][j] = xj[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
+  tile_nt_mfma(Li, Ls, xi);
+  if (ti != tj) tile_nt_mfma(Lj, Ls, xj);
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int r = wi + 16 * i + 4 * r4 + (lane >> 4), c = wj + 16 * j + (lane & 15);
+        const double x = xi[i][j][r4];
+        Li[r][c] = x;
+        // on a diagonal tile Lj is the same piece without the right-hand-side row (row n of the matrix)
+        Lj[r][c] = ti != tj ? xj[i][j][r4] : (c0 + r < n ? x : 0.0);
+        if (tj == 0 && i0 + r < rows_total) M[(i0 + r) * ld + j0 + c] = x;
+      }
+  __syncthreads();
+  if (ti == 0) {  // tj == 0 too: the next diagonal block
+    // a short last block shares its tile with the right-hand-side row, which still needs this update
+    if (n - base < NB && (int64_t)threadIdx.x < n - base) {
+      const int rr = (int)(n - base), c = threadIdx.x;
+      double sum = 0.0;
+      for (int k = 0; k < NB; ++k) sum += Li[rr][k] * Lj[c][k];
+      M[n * ld + base + c] -= sum;
+    }
+    __syncthreads();  // the row above has read Li, which becomes the block's tile
+    chol_diag_body(M, ld, base, (int)(n - base < NB ? n - base : NB), linv_next, flag, Lj, Li, Ls, mt);
+    return;
+  }
+  double4_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
+  tile_nt_mfma(Li, Lj, acc);
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int64_t r = i0 + wi + 16 * i + 4 * r4 + (lane >> 4);
+        const int64_t c = c0 + wj + 16 * j + (lane & 15);
+        if (r < rows_total && c < n && c <= r) {
+          const double v = M[r * ld + c] - acc[i][j][r4];
+          M[r * ld + c] = v;
+          if (tj == 0) Pnext[r * NB + (c - c0)] = v;
+        }
+      }
+}
+
+// rows [row0, rows_total) of the 64 columns at j0 -> P (row r at P[r * 64 ..]): the panel of the first fused step
+__global__ void copy_panel_kernel(const double* M, int64_t ld, int64_t rows_total, int64_t row0, int64_t j0, int64_t n, double* P) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t r = row0 + (idx >> 6);
+  const int c = (int)(idx & 63);
+  if (r < rows_total) P[r * NB + c] = j0 + c < n ? M[r * ld + j0 + c] : 0.0;
 }
 
 // Trailing update of a whole super-panel: A22 -= L21 L21^T with L21 = the kw (a multiple of 64) columns
@@ -1021,12 +1134,15 @@ GramDims gram_dims(int64_t n, int64_t k, int paired, int num_cus) {
 
 }  // namespace
 
+// rows of a 64-column panel, one buffer (the fused steps of the factorisation keep two)
+static size_t panel_bytes(int64_t n) { return (size_t)(n + 1) * NB * 8; }
+
 size_t ds_gram_arena_bytes(int64_t n, int64_t k) {
   const GramDims d = gram_dims(n, k, 0, 256);  // the unpaired layout is the larger one
   const GramDims dp = gram_dims(n, k, 1, 256);
   const size_t slices = (size_t)(d.slices > dp.slices ? d.slices : dp.slices) + 1;  // +1: CU counts differ a little
   return ds_align((size_t)n * d.RW * 8) + ds_align(slices * (size_t)n * n * 8) + ds_align((size_t)(n + 1) * d.ld * 8) +
-         ds_align((size_t)d.nblk * NB * NB * 8) + 2 * ds_align(k * 4) + 2 * ds_align(k * 8) + ds_align(k * 4) +
+         ds_align((size_t)d.nblk * NB * NB * 8) + 2 * ds_align(panel_bytes(n)) + 2 * ds_align(k * 4) + 2 * ds_align(k * 8) + ds_align(k * 4) +
          ds_align(k * 8) + ds_align(d.RW * 4) * 2 + 4 * ds_align(n * 8) + 8192 +
          ds_align((size_t)((n + 63) / 64) * d.R * 8 + 8) + ds_align((size_t)d.RW * 8 + 8) + ds_align((size_t)d.R * 8 + 8) + 256;
 }
@@ -1044,6 +1160,8 @@ int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const fl
   double* Gp = (double*)ds_arena_alloc(ctx, (size_t)d.slices * n * n * 8);
   gs->M = (double*)ds_arena_alloc(ctx, (size_t)(n + 1) * ld * 8);
   gs->linv = (double*)ds_arena_alloc(ctx, (size_t)d.nblk * NB * NB * 8);
+  gs->panel[0] = (double*)ds_arena_alloc(ctx, panel_bytes(n));
+  gs->panel[1] = (double*)ds_arena_alloc(ctx, panel_bytes(n));
   float* gw = (float*)ds_arena_alloc(ctx, R * 4);
   float* wu = (float*)ds_arena_alloc(ctx, RW * 4);
   int32_t* uni = (int32_t*)ds_arena_alloc(ctx, RW * 4);
@@ -1062,7 +1180,7 @@ int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const fl
   gs->c = (double*)ds_arena_alloc(ctx, n * 8);
   gs->yv = (double*)ds_arena_alloc(ctx, n * 8);
   gs->flag = (int*)ds_arena_alloc(ctx, 64);
-  if (!gs->Zt || !Gp || !gs->M || !gs->linv || !gw || !wu || !uni || !m || !stats || !Zc || !keep || !wq || !gscale || !gs->sz || !gs->wc || !gs->t ||
+  if (!gs->Zt || !Gp || !gs->M || !gs->linv || !gs->panel[0] || !gs->panel[1] || !gw || !wu || !uni || !m || !stats || !Zc || !keep || !wq || !gscale || !gs->sz || !gs->wc || !gs->t ||
       !gs->sqw || !gs->gc || !gs->c || !gs->yv || !gs->flag)
     return ds_fail(ctx, DS_EINTERNAL, "gram: arena exhausted");
   hipLaunchKernelGGL(used_row_weights_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, w, R, paired, gw);
@@ -1114,6 +1232,8 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
   // updated once with all 256 columns. Below kFuseMaxRows trailing rows: one block per step, the update
   // factorising the next diagonal block on the way.
   bool diag_done = false;
+  bool panel_ready = false;  // gs->panel[pbuf] holds the rows of the current panel (fused steps only)
+  int pbuf = 0;
   int64_t j0 = 0;
   while (j0 < n) {
     const bool super = rows_total - j0 - kSuperCols > kFuseMaxRows && n - j0 >= kSuperCols + NB;
@@ -1145,6 +1265,20 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
     if (!diag_done) hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, j0, nb, li, gs->flag);
     diag_done = false;
     const int64_t rest = rows_total - j0 - nb;
+    if (n - j0 - nb > 0 && rest <= kFuseMaxRows) {  // nb == NB here
+      const unsigned tt = nblocks(rest, kTile);
+      if (!panel_ready) {
+        hipLaunchKernelGGL(copy_panel_kernel, dim3(nblocks(rest * NB, 256)), dim3(256), 0, st, M, ld, rows_total, j0 + NB, j0, n,
+                           gs->panel[pbuf]);
+        panel_ready = true;
+      }
+      hipLaunchKernelGGL(chol_step_kernel, dim3(tt, tt), dim3(kThreads), 0, st, M, ld, rows_total, n, j0, li,
+                         li + (size_t)NB * NB, gs->flag, gs->panel[pbuf], gs->panel[pbuf ^ 1]);
+      pbuf ^= 1;
+      diag_done = true;
+      j0 += nb;
+      continue;
+    }
     hipLaunchKernelGGL(chol_panel_kernel, dim3(nblocks(rest, kTile)), dim3(kThreads), 0, st, M, ld, rows_total, j0, nb, li);
     if (n - j0 - nb > 0) {
       const unsigned tt = nblocks(rest, kTile);

@@ -169,6 +169,7 @@ struct ds_gram_state {
   int paired;
   uint64_t* Zt;
   double *M, *linv, *t, *sqw, *gc, *c, *yv;
+  double* panel[2];  // rows of the current and of the next 64-column panel (fused steps of the factorisation)
   int32_t* sz;
   float* wc;
   int* flag;
