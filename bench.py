@@ -272,7 +272,7 @@ def main():
         "kernels": {name: {kk: v[kk] for kk in ("ms", "bound", "achieved", "peak", "unit", "frac")}
                     for name, v in kernels.items()},
     }
-    # several explanations in flight (ds_explain_batch runs up to four at a time on worker contexts)
+    # several explanations in flight (ds_explain_batch runs up to eight at a time on worker contexts)
     if args.batch > 0:
         tg = [targets[i % len(targets)] for i in range(args.batch)]
         ctx.explain_batch(tg, w.n_samples, w.seed, opts, capacity=capacity * args.batch)   # warm-up

@@ -183,7 +183,7 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
                float* phi, int64_t* M_inout, int64_t* edge_src, int64_t* edge_dst, ds_report* report);
 
 /* Explain T targets (paper's protocol: a set of test nodes per run). Every target gets exactly the result
- * ds_explain would give it; up to four explanations are in flight at a time (two when the games average more
+ * ds_explain would give it; up to eight explanations are in flight at a time (two when the games average more
  * than 4096 players, one above 16384), each on an internal worker context with its own stream, workspace and
  * host thread, which fills the GPU better than one small explanation at a time. The call returns when all are done.
  *   targets [host]: int64[T]; phi_concat: float[capacity] out, target t's scores at
