@@ -496,6 +496,40 @@ __device__ __forceinline__ void tile_nt_mfma(const double (*A)[NB + 1], const do
   }
 }
 
+// M[r][c] -= acc over a wave's NI x NJ matrix-core tiles at (i0 + wi, c0 + wj), lower triangle and in-bounds
+// entries only; P, if not null, also receives the new values of the tile's column block (row r at P[r * 64 ..]).
+// All loads of a tile row are issued before the first store: written as `M[..] -= acc` under its bounds check,
+// every entry becomes a load, a wait and a store of its own, one memory latency each. The loads are made safe
+// by clamping the address instead of skipping them.
+template <int NI, int NJ>
+__device__ __forceinline__ void tile_sub_store(double* M, int64_t ld, int64_t rows_total, int64_t n, int64_t i0, int64_t c0,
+                                               int wi, int wj, const double4_t (&acc)[NI][NJ], double* P) {
+  const int lane = threadIdx.x & 63, l16 = lane & 15, lk = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    double cur[NJ][4];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int64_t r = i0 + wi + 16 * i + 4 * r4 + lk, c = c0 + wj + 16 * j + l16;
+        const int64_t rs = r < rows_total ? r : rows_total - 1, cs = c < n ? c : n - 1;
+        cur[j][r4] = M[rs * ld + cs];
+      }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int64_t r = i0 + wi + 16 * i + 4 * r4 + lk, c = c0 + wj + 16 * j + l16;
+        if (r < rows_total && c < n && c <= r) {
+          const double v = cur[j][r4] - acc[i][j][r4];
+          M[r * ld + c] = v;
+          if (P) P[r * NB + (c - c0)] = v;
+        }
+      }
+  }
+}
+
 // value of `v` in lane `src` (a compile-time constant after unrolling) for the whole wave, through two scalar registers
 __device__ __forceinline__ double wave_bcast(double v, int src) {
   const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
@@ -810,18 +844,8 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_
     for (int j = 0; j < 2; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
   tile_nt_mfma(Li, Lj, acc);
   {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int64_t r = i0 + wi + 16 * i + 4 * r4 + (lane >> 4);
-          const int64_t c = c0 + wj + 16 * j + (lane & 15);
-          if (r < rows_total && c < n && c <= r) M[r * ld + c] -= acc[i][j][r4];
-        }
+    const int wave = threadIdx.x >> 6;
+    tile_sub_store<2, 2>(M, ld, rows_total, n, i0, c0, (wave >> 1) * 32, (wave & 1) * 32, acc, nullptr);
   }
 }
 
@@ -894,20 +918,7 @@ __global__ __launch_bounds__(kThreads) void chol_step_kernel(double* M, int64_t 
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
   tile_nt_mfma(Li, Lj, acc);
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int64_t r = i0 + wi + 16 * i + 4 * r4 + (lane >> 4);
-        const int64_t c = c0 + wj + 16 * j + (lane & 15);
-        if (r < rows_total && c < n && c <= r) {
-          const double v = M[r * ld + c] - acc[i][j][r4];
-          M[r * ld + c] = v;
-          if (tj == 0) Pnext[r * NB + (c - c0)] = v;
-        }
-      }
+  tile_sub_store<2, 2>(M, ld, rows_total, n, i0, c0, wi, wj, acc, tj == 0 ? Pnext : nullptr);
 }
 
 // rows [row0, rows_total) of the 64 columns at j0 -> P (row r at P[r * 64 ..]): the panel of the first fused step
@@ -959,19 +970,10 @@ __global__ __launch_bounds__(kThreads) void chol_update_wide_kernel(double* M, i
     if (kc + NB < kw) fetch(kc + NB);
     tile_nt_mfma(Li, Lj, acc);
   }
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int64_t r = i0 + wi + 16 * i + 4 * r4 + (lane >> 4);
-        const int64_t c = c0 + wj + 16 * j + (lane & 15);
-        if (r < rows_total && c < n && c <= r) M[r * ld + c] -= acc[i][j][r4];
-      }
+  const int wave = tid >> 6;
+  tile_sub_store<2, 2>(M, ld, rows_total, n, i0, c0, (wave >> 1) * 32, (wave & 1) * 32, acc, nullptr);
 }
+
 
 // L^T psi = y (y = row n of M after the factorisation), block by block from the end, using the stored
 // inverses of the diagonal blocks. One launch per block: every workgroup recomputes the 64 unknowns of
