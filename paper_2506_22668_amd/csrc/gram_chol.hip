@@ -364,12 +364,23 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
 #pragma unroll
   for (int i = 0; i < 16; ++i) Ts[wi + 8 * (i / 4) + 4 * half + (i % 4)][wj + l32] = accm[i];
   __syncthreads();
+  // slice 0 already holds the sparse rows' part (both triangles): all of a thread's entries are fetched before the
+  // first store (one memory latency instead of sixteen; addresses clamped instead of skipped)
+  double prev[4][4];
+#pragma unroll
   for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t a = a0 + ty + 16 * i, b = b0 + tx + 16 * j;
+      prev[i][j] = blockIdx.z == 0 ? G[(a < n ? a : n - 1) * n + (b < n ? b : n - 1)] : 0.0;
+    }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int64_t a = a0 + ty + 16 * i, b = b0 + tx + 16 * j;
       if (a < n && b < n) {
-        double v = acc[i][j] + Ts[ty + 16 * i][tx + 16 * j];
-        if (blockIdx.z == 0) v += G[a * n + b];  // slice 0 already holds the sparse rows' part (both triangles)
+        const double v = acc[i][j] + Ts[ty + 16 * i][tx + 16 * j] + prev[i][j];
         G[a * n + b] = v;
         if (ta != tb) G[b * n + a] = v;  // a diagonal tile computes both of its triangles itself
       }
