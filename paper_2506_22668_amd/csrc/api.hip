@@ -2,6 +2,8 @@
 #include "internal.h"
 
 #include <string>
+#include <condition_variable>
+#include <mutex>
 #include <thread>
 
 int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...) {
@@ -433,19 +435,30 @@ int ds_copy_probe(ds_ctx* ctx, void* dst, const void* src, int64_t bytes) {
   return DS_OK;
 }
 
+static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t n_samples, uint64_t seed, const ds_options& o,
+                             float* phi, int64_t* M_inout, int64_t* edge_src, int64_t* edge_dst, ds_report* report);
+
 int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, const ds_options* opts, float* phi,
                int64_t* M_inout, int64_t* edge_src, int64_t* edge_dst, ds_report* report) {
   if (!ctx || !M_inout) return DS_EINVAL;
   DS_HIP(ctx, hipSetDevice(ctx->device));
   ds_options o = default_options(opts);
-  ds_report rep;
-  memset(&rep, 0, sizeof(rep));
   hipStream_t st = ctx->stream;
   if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "no model is set (ds_set_gcn / ds_set_gat)");
   for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
   DS_HIP(ctx, hipEventRecord(ctx->ev[0], st));
   ds_cgraph* cg = nullptr;
   DS_TRY(ds_extract(ctx, target, &o, &cg));
+  return explain_extracted(ctx, cg, target, n_samples, seed, o, phi, M_inout, edge_src, edge_dst, report);
+}
+
+// Everything after the extraction; takes over (and frees) the computational graph. ctx->ev[0] has been recorded
+// before the extraction.
+static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t n_samples, uint64_t seed, const ds_options& o,
+                             float* phi, int64_t* M_inout, int64_t* edge_src, int64_t* edge_dst, ds_report* report) {
+  ds_report rep;
+  memset(&rep, 0, sizeof(rep));
+  hipStream_t st = ctx->stream;
   struct Guard {
     ds_ctx* c; ds_cgraph* g;
     ~Guard() { (void)hipStreamSynchronize(c->side); ds_cgraph_free(c, g); ds_arena_reset(c); }
@@ -637,55 +650,81 @@ int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, i
   // context and host thread: a single explanation leaves much of the GPU idle in its latency-bound stages.
   // (Measured on 1,010-player games: 1.53 / 1.21 / 1.00 / 0.96 ms per explanation with 1 / 2 / 4 / 8 in flight; the
   // launches of all workers go through one runtime, which is what the curve runs into.)
-  const int nw = num_targets < batch_workers() ? num_targets : batch_workers();
+  // A target's place in the outputs depends on the sizes of all targets before it. Every worker extracts its
+  // target's computational graph, publishes the size, waits until the sizes before it are known (their workers
+  // publish right after their own extraction, so the wait is short and the lowest unpublished target never waits)
+  // and goes on with the graph it already holds.
+  if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "no model is set (ds_set_gcn / ds_set_gat)");
+  int nw = num_targets < batch_workers() ? num_targets : batch_workers();
   DS_TRY(ensure_workers(ctx, nw));
   DS_HIP(ctx, hipStreamSynchronize(ctx->stream));  // whatever the caller queued before is visible to the workers
+  const ds_options o = default_options(opts);
   std::vector<int> status(num_targets, DS_OK);
   std::vector<std::string> errs(num_targets);
-  int active = nw;  // worker threads of the current phase
-  auto run = [&](int phase) {
+  // The first graph is extracted up front: large games fill the GPU on their own (and their workspaces are large),
+  // so fewer of them are taken at a time, and the first target's size stands for the batch.
+  ds_cgraph* first_cg = nullptr;
+  {
+    ds_ctx* w0 = ctx->workers[0];
+    for (int i = 0; i < 4; ++i) w0->kev_set[i] = false;
+    DS_HIP(ctx, hipEventRecord(w0->ev[0], w0->stream));
+    const int rc = ds_extract(w0, targets[0], &o, &first_cg);
+    if (rc != DS_OK) {
+      strncpy(ctx->err, w0->err, sizeof(ctx->err) - 1);
+      return rc;
+    }
+    const int64_t m0 = first_cg->info.num_players;
+    if (m0 > 16384) nw = 1;
+    else if (m0 > 4096 && nw > 2) nw = 2;
+  }
+  std::mutex mu;
+  std::condition_variable cv;
+  std::vector<char> published(num_targets, 0);
+  int32_t prefix = 0;  // offsets[0 .. prefix] are final
+  {
     std::vector<std::thread> pool;
-    const int na = active;
-    for (int wi = 0; wi < na; ++wi)
-      pool.emplace_back([&, wi, na]() {
+    for (int wi = 0; wi < nw; ++wi)
+      pool.emplace_back([&, wi]() {
         ds_ctx* w = ctx->workers[wi];
         (void)hipSetDevice(w->device);
-        for (int32_t t = wi; t < num_targets; t += na) {
-          if (phase == 0) {  // sizes: only the computational graph
-            ds_cgraph* cg = nullptr;
-            int rc = ds_extract(w, targets[t], opts, &cg);
-            if (rc == DS_OK) {
-              M_out[t] = cg->info.num_players;
-              ds_cgraph_free(w, cg);
-            }
-            status[t] = rc;
-          } else if (status[t] == DS_OK && offsets[t + 1] <= capacity) {
-            int64_t m = M_out[t];
-            const int64_t off = offsets[t];
-            status[t] = ds_explain(w, targets[t], n_samples, seed, opts, phi_concat ? phi_concat + off : nullptr, &m,
-                                   edge_src ? edge_src + off : nullptr, edge_dst ? edge_dst + off : nullptr,
-                                   reports ? reports + t : nullptr);
-            if (status[t] != DS_OK && status[t] != DS_ENOTCONV) errs[t] = w->err;
+        for (int32_t t = wi; t < num_targets; t += nw) {
+          ds_cgraph* cg = nullptr;
+          int rc = DS_OK;
+          if (t == 0) {
+            cg = first_cg;
+          } else {
+            for (int i = 0; i < 4; ++i) w->kev_set[i] = false;
+            rc = hipEventRecord(w->ev[0], w->stream) == hipSuccess ? DS_OK : DS_EDEVICE;
+            if (rc == DS_OK) rc = ds_extract(w, targets[t], &o, &cg);
           }
+          status[t] = rc;
+          if (rc != DS_OK) errs[t] = w->err;
+          M_out[t] = rc == DS_OK ? cg->info.num_players : 0;
+          {
+            std::unique_lock<std::mutex> lk(mu);
+            published[t] = 1;
+            while (prefix < num_targets && published[prefix]) {
+              offsets[prefix + 1] = offsets[prefix] + M_out[prefix];
+              ++prefix;
+            }
+            cv.notify_all();
+            cv.wait(lk, [&] { return prefix > t; });
+          }
+          if (rc != DS_OK) continue;
+          if (offsets[t + 1] > capacity) {  // no room for this one: its size is reported, nothing is written
+            ds_cgraph_free(w, cg);
+            continue;
+          }
+          int64_t m = M_out[t];
+          const int64_t off = offsets[t];
+          status[t] = explain_extracted(w, cg, targets[t], n_samples, seed, o, phi_concat ? phi_concat + off : nullptr, &m,
+                                        edge_src ? edge_src + off : nullptr, edge_dst ? edge_dst + off : nullptr,
+                                        reports ? reports + t : nullptr);
+          if (status[t] != DS_OK && status[t] != DS_ENOTCONV) errs[t] = w->err;
         }
       });
     for (auto& th : pool) th.join();
-  };
-  run(0);
-  for (int32_t t = 0; t < num_targets; ++t) {
-    if (status[t] != DS_OK) {
-      strncpy(ctx->err, ctx->workers[t % nw]->err, sizeof(ctx->err) - 1);
-      return status[t];
-    }
-    offsets[t + 1] = offsets[t] + M_out[t];
   }
-  // Large games fill the GPU on their own (and their workspaces are large): fewer of them at a time.
-  {
-    const int64_t avg = offsets[num_targets] / num_targets;
-    if (avg > 16384) active = 1;
-    else if (avg > 4096 && active > 2) active = 2;
-  }
-  run(1);
   int worst = offsets[num_targets] > capacity ? DS_ECAPACITY : DS_OK;
   if (worst == DS_ECAPACITY)
     ds_fail(ctx, DS_ECAPACITY, "the batch needs %lld entries, the buffers hold %lld", (long long)offsets[num_targets], (long long)capacity);
