@@ -248,7 +248,10 @@ def _solve_inputs(n, ns, seed):
     return Z, w, bits, y
 
 
-@pytest.mark.parametrize("n,ns", [(12, 4096), (40, 2000), (65, 3000), (200, 3000), (333, 6000), (1000, 20000)])
+# sizes around the factorisation's block edges too: one block exactly (64), a block and one column (65), whole blocks
+# only (128, 192: the last fused step is followed by a full last block), a last block of one column (129)
+@pytest.mark.parametrize("n,ns", [(12, 4096), (40, 2000), (63, 3000), (64, 3000), (65, 3000), (128, 4000), (129, 4000),
+                                  (192, 4000), (200, 3000), (333, 6000), (1000, 20000)])
 def test_gram_cholesky_matches_oracle_least_squares(ctx_tiny, n, ns):
     from paper_2506_22668_amd import Options, DS_SOLVER_GRAM_CHOL
     ctx, _ = ctx_tiny
