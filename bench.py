@@ -81,7 +81,7 @@ def cholesky_launches(n, block=64, fuse_rows=2048, super_cols=256):
     (panel solve, trailing update and the next diagonal block together, plus one copy of the panel before the
     first of them), and a panel launch for the last block; a diagonal block has a launch of its own only if
     the launch before it did not factorise it."""
-    count, done, j0, panel_ready = 0, False, 0, False
+    count, done, j0, panel_ready = 0, True, 0, False   # the first diagonal block is factorised with the system matrix
     while j0 < n:
         if (n + 1) - j0 - super_cols > fuse_rows and n - j0 >= super_cols + block:
             count += 1 + 4 + 3 + 1

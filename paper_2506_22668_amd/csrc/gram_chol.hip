@@ -1221,6 +1221,11 @@ int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const fl
   hipLaunchKernelGGL(sum_slices_row_mean_kernel, dim3(wblocks), dim3(kThreads), 0, st, Gp, n, d.slices, m);
   hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(kThreads), 0, st, Gp, m, n, stats);
   hipLaunchKernelGGL(build_matrix_kernel, dim3(nblocks(n * n, 256)), dim3(256), 0, st, Gp, m, stats, n, ld, gs->M);
+  // the first diagonal block does not involve the right-hand side either: factorised here, off the path that waits
+  // for the model outputs
+  DS_HIP(ctx, hipMemsetAsync(gs->flag, 0, sizeof(int), st));
+  hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, gs->M, ld, (int64_t)0, (int)(n < NB ? n : NB), gs->linv,
+                     gs->flag);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }
@@ -1232,7 +1237,6 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
   const int64_t n = gs->n, k = gs->k, R = gs->R, RW = gs->RW, ld = gs->ld;
   double* M = gs->M;
   double* linv = gs->linv;
-  DS_HIP(ctx, hipMemsetAsync(gs->flag, 0, sizeof(int), st));
   DS_TRY(ds_row_prep(ctx, Z, k, n, w, y, gs->sz, gs->t, gs->sqw, gs->wc));
   hipLaunchKernelGGL(used_row_rhs_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, gs->wc, gs->t, R, gs->paired, gs->gc);
   DS_TRY(ds_bit_spmv(ctx, gs->Zt, n, R, RW, 0, 1, gs->gc, gs->c));  // c_j = sum over the rows containing j of gc
@@ -1244,7 +1248,7 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
   // inside it the updates reach only the super-panel's own columns, and the rest of the trailing matrix is
   // updated once with all 256 columns. Below kFuseMaxRows trailing rows: one block per step, the update
   // factorising the next diagonal block on the way.
-  bool diag_done = false;
+  bool diag_done = true;  // the first diagonal block was factorised with the system matrix (ds_gram_begin)
   bool panel_ready = false;  // gs->panel[pbuf] holds the rows of the current panel (fused steps only)
   int pbuf = 0;
   int64_t j0 = 0;
@@ -1255,7 +1259,7 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
         const int64_t jb = j0 + (int64_t)b * NB;
         double* li = linv + (size_t)(jb / NB) * NB * NB;
         // inside the super-panel the narrow update factorises the next diagonal block on the way
-        if (b == 0) hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, jb, NB, li, gs->flag);
+        if (b == 0 && jb > 0) hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(kThreads), 0, st, M, ld, jb, NB, li, gs->flag);
         const int64_t rest = rows_total - jb - NB;
         const unsigned tt = nblocks(rest, kTile);
         hipLaunchKernelGGL(chol_panel_kernel, dim3(tt), dim3(kThreads), 0, st, M, ld, rows_total, jb, NB, li);
