@@ -77,14 +77,15 @@ def gat_flops_per_coalition(ctx, cg, model):
 def cholesky_launches(n, block=64, fuse_rows=2048, super_cols=256):
     """Kernel launches of the blocked factorisation (the library's rules): while more than `fuse_rows` rows
     trail a super-panel of 256 columns, 4 panels + 3 narrow updates (each factorising the next diagonal block) +
-    1 diagonal block + 1 wide update; afterwards one launch per full 64-column block that has columns behind it
+    1 diagonal block (not the very first: that one is factorised when the system matrix is built, outside the
+    timed group) + 1 wide update; afterwards one launch per full 64-column block that has columns behind it
     (panel solve, trailing update and the next diagonal block together, plus one copy of the panel before the
     first of them), and a panel launch for the last block; a diagonal block has a launch of its own only if
     the launch before it did not factorise it."""
     count, done, j0, panel_ready = 0, True, 0, False   # the first diagonal block is factorised with the system matrix
     while j0 < n:
         if (n + 1) - j0 - super_cols > fuse_rows and n - j0 >= super_cols + block:
-            count += 1 + 4 + 3 + 1
+            count += (0 if j0 == 0 else 1) + 4 + 3 + 1
             j0 += super_cols
             done = False
             continue
