@@ -137,6 +137,33 @@ def test_explain_batch_equals_single_explanations():
     ctx.close()
 
 
+def test_explain_batch_more_targets_than_workers_and_a_bad_target():
+    """Targets outnumber the worker contexts (each worker takes several, sizes are published out of order and
+    every result still lands at its offset); a target outside the graph anywhere in the batch is an error of the
+    call, reported after the workers have drained (none of them may be left waiting for its size)."""
+    from paper_2506_22668_amd import DistShapError, DS_EINVAL
+    w = make_workload("c2_small")
+    say("explain_batch 21 targets, then one bad target")
+    ctx = make_context(w)
+    rng = np.random.default_rng(5)
+    targets = [int(t) for t in rng.choice(w.num_nodes, size=21, replace=False)]
+    ns = 600
+    singles = [ctx.explain(t, ns, w.seed)[0] for t in targets]
+    total = sum(len(x) for x in singles)
+    phi, M, off, es, ed, reps, rc = ctx.explain_batch(targets, ns, w.seed, capacity=total)
+    assert rc == 0 and M == [len(x) for x in singles] and off[-1] == total
+    for i, x in enumerate(singles):
+        assert torch.equal(phi[off[i]:off[i + 1]], x)
+    bad = targets[:5] + [w.num_nodes + 7] + targets[5:9]
+    with pytest.raises(DistShapError) as e:
+        ctx.explain_batch(bad, ns, w.seed, capacity=total)
+    assert e.value.code == DS_EINVAL
+    # the context is still usable
+    again = ctx.explain(targets[0], ns, w.seed)[0]
+    assert torch.equal(again, singles[0])
+    ctx.close()
+
+
 def test_degenerate_graphs_and_error_paths():
     from paper_2506_22668_amd import DistShapError, Options, DS_ECAPACITY, DS_EINVAL
     from synth.workloads import Workload
