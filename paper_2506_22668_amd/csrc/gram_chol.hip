@@ -496,14 +496,54 @@ __device__ __forceinline__ void tile_nt_mfma(const double (*A)[NB + 1], const do
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
   const int l16 = lane & 15, lk = lane >> 4;
-#pragma unroll 4
+  const double* pa0 = &A[wi + l16][lk];
+  const double* pa1 = &A[wi + 16 + l16][lk];
+  const double* pb0 = &B[wj + l16][lk];
+  const double* pb1 = &B[wj + 16 + l16][lk];
+  // the operands of the next step are read from LDS before this step's products are issued
+  double a0 = pa0[0], a1 = pa1[0], b0 = pb0[0], b1 = pb1[0];
+#pragma unroll
   for (int k0 = 0; k0 < NB; k0 += 4) {
-    const double a0 = A[wi + l16][k0 + lk], a1 = A[wi + 16 + l16][k0 + lk];
-    const double b0 = B[wj + l16][k0 + lk], b1 = B[wj + 16 + l16][k0 + lk];
+    double na0 = 0.0, na1 = 0.0, nb0 = 0.0, nb1 = 0.0;
+    if (k0 + 4 < NB) {
+      na0 = pa0[k0 + 4];
+      na1 = pa1[k0 + 4];
+      nb0 = pb0[k0 + 4];
+      nb1 = pb1[k0 + 4];
+    }
     acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
     acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
     acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
     acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+    a0 = na0;
+    a1 = na1;
+    b0 = nb0;
+    b1 = nb1;
+  }
+}
+
+// A 64 x 64 tile from global memory into LDS (row pitch NB+1) in two halves, so that a kernel can have the loads of
+// all its tiles in flight before the first LDS store: written as one loop that loads and stores element by element
+// (the bounds checks make every load a branch of its own), each of a thread's 16 elements costs a memory latency.
+// Element (r, c) is src[(row0 + r) * stride + col0 + c], valid for row0 + r < row_limit and c < ncols, zero otherwise;
+// out-of-range elements are read from a clamped address. row_limit and ncols are at least 1.
+struct TileRegs {
+  double v[kTile * NB / kThreads];
+};
+__device__ __forceinline__ void tile_fetch(TileRegs& t, const double* src, int64_t stride, int64_t row0, int64_t row_limit,
+                                           int64_t col0, int ncols) {
+#pragma unroll
+  for (int u = 0; u < kTile * NB / kThreads; ++u) {
+    const int idx = threadIdx.x + u * kThreads, r = idx >> 6, c = idx & 63;
+    const int64_t rr = row0 + r < row_limit ? row0 + r : row_limit - 1;
+    t.v[u] = src[rr * stride + col0 + (c < ncols ? c : ncols - 1)];
+  }
+}
+__device__ __forceinline__ void tile_put(double (*T)[NB + 1], const TileRegs& t, int64_t row0, int64_t row_limit, int ncols) {
+#pragma unroll
+  for (int u = 0; u < kTile * NB / kThreads; ++u) {
+    const int idx = threadIdx.x + u * kThreads, r = idx >> 6, c = idx & 63;
+    T[r][c] = (row0 + r < row_limit && c < ncols) ? t.v[u] : 0.0;
   }
 }
 
@@ -785,10 +825,12 @@ __global__ __launch_bounds__(kThreads) void chol_panel_kernel(double* M, int64_t
   __shared__ double As[kTile][NB + 1];
   __shared__ double Ls[NB][NB + 1];
   const int64_t i0 = j0 + nb + (int64_t)blockIdx.x * kTile;
-  for (int idx = threadIdx.x; idx < kTile * NB; idx += kThreads) {
-    const int r = idx >> 6, c = idx & 63;
-    As[r][c] = (i0 + r < rows_total && c < nb) ? M[(i0 + r) * ld + j0 + c] : 0.0;
-    Ls[r][c] = linv[idx];
+  {
+    TileRegs ta, tl;
+    tile_fetch(ta, M, ld, i0, rows_total, j0, nb);
+    tile_fetch(tl, linv, NB, 0, NB, 0, NB);
+    tile_put(As, ta, i0, rows_total, nb);
+    tile_put(Ls, tl, 0, NB, NB);
   }
   __syncthreads();
   double4_t acc[2][2];
@@ -828,10 +870,12 @@ __global__ __launch_bounds__(kThreads) void chol_update_kernel(double* M, int64_
   __shared__ double Lj[kTile][NB + 1];
   const int64_t base = j0 + nb;
   const int64_t i0 = base + (int64_t)ti * kTile, c0 = base + (int64_t)tj * kTile;
-  for (int idx = threadIdx.x; idx < kTile * NB; idx += kThreads) {
-    const int r = idx >> 6, c = idx & 63;
-    Li[r][c] = (i0 + r < rows_total && c < nb) ? M[(i0 + r) * ld + j0 + c] : 0.0;
-    Lj[r][c] = (c0 + r < n && c < nb) ? M[(c0 + r) * ld + j0 + c] : 0.0;
+  {
+    TileRegs ta, tb;
+    tile_fetch(ta, M, ld, i0, rows_total, j0, nb);
+    tile_fetch(tb, M, ld, c0, n, j0, nb);
+    tile_put(Li, ta, i0, rows_total, nb);
+    tile_put(Lj, tb, c0, n, nb);
   }
   __syncthreads();
   if (FUSE && ti == 0 && tj == 0) {  // Lj holds the rows of the next diagonal block in this panel (zero past column n)
@@ -882,11 +926,14 @@ __global__ __launch_bounds__(kThreads) void chol_step_kernel(double* M, int64_t 
   const int wi = (wave >> 1) * 32, wj = (wave & 1) * 32;
   double4_t mt[2][2];  // the next diagonal block (first diagonal tile only), on its way while the panel is solved
   if (ti == 0) load_diag_block(M, ld, base, (int)(n - base < NB ? n - base : NB), mt);
-  for (int idx = threadIdx.x; idx < kTile * NB; idx += kThreads) {
-    const int r = idx >> 6, c = idx & 63;
-    Li[r][c] = i0 + r < rows_total ? Pcur[(i0 + r) * NB + c] : 0.0;
-    if (ti != tj) Lj[r][c] = Pcur[(c0 + r) * NB + c];  // tj < ti: all 64 rows lie above row i0 <= n
-    Ls[r][c] = linv[idx];
+  {
+    TileRegs ta, tb, tl;
+    tile_fetch(ta, Pcur, NB, i0, rows_total, 0, NB);
+    tile_fetch(tl, linv, NB, 0, NB, 0, NB);
+    if (ti != tj) tile_fetch(tb, Pcur, NB, c0, rows_total, 0, NB);  // tj < ti: all 64 rows lie above row i0 <= n
+    tile_put(Li, ta, i0, rows_total, NB);
+    tile_put(Ls, tl, 0, NB, NB);
+    if (ti != tj) tile_put(Lj, tb, c0, rows_total, NB);
   }
   __syncthreads();
   double4_t xi[2][2], xj[2][2];
