@@ -221,7 +221,7 @@ __device__ __forceinline__ uint32_t pair_mask(uint32_t two_bits) {
   return ((0u - (two_bits & 1u)) & 0xFFFFu) | ((0u - ((two_bits >> 1) & 1u)) & 0xFFFF0000u);
 }
 
-__global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int64_t n, int64_t k, int64_t KW,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 4))) void gram_kernel(const uint64_t* Zt, int64_t n, int64_t k, int64_t KW,
                                                         const float* w, const float* wu, const int32_t* uni,
                                                         const uint64_t* keep, double* Gp, int64_t words_per_slice) {
   const int ta = blockIdx.y, tb = blockIdx.x;
@@ -261,30 +261,67 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const uint64_t* Zt, int6
       const bool any = wd < wend && keep[wd] != 0ull;
       if (!__syncthreads_or(any)) continue;
     }
-    for (int idx = tid; idx < kTile * kChunk; idx += kThreads) {
-      const int r = idx / kChunk, c = idx - r * kChunk;
-      const int64_t wd = wd0 + c;
-      As[r][c] = (a0 + r < n && wd < wend) ? (Zt[(a0 + r) * KW + wd] & keep[wd]) : 0ull;  // kept rows only
-      Bs[r][c] = (b0 + r < n && wd < wend) ? Zt[(b0 + r) * KW + wd] : 0ull;
-    }
-    for (int idx = tid; idx < kChunk * 64; idx += kThreads) {
-      const int64_t i = wd0 * 64 + idx;
-      wrow[idx] = i < k ? w[i] : 0.f;
-    }
-    for (int idx = tid; idx < kChunk * 16; idx += kThreads) {  // rows 4 idx .. 4 idx + 3 of the chunk
-      uint32_t pc[3][4];
+    // Everything the chunk needs from global memory is fetched into registers first (addresses clamped instead of
+    // skipped) and only then stored to LDS: a loop that loads and stores element by element pays one memory latency
+    // per element, about twenty per chunk.
+    {
+      constexpr int kZ = kTile * kChunk / kThreads;  // mask words per thread and operand
+      constexpr int kWr = kChunk * 64 / kThreads;    // row weights per thread
+      constexpr int kWp = kChunk * 16 / kThreads;    // groups of four rows per thread
+      static_assert(kThreads % kChunk == 0, "a thread stays in one word column of the chunk");
+      uint64_t za[kZ], zb[kZ];
+      float wr_[kWr], w4[kWp][4];
+      const int cz = tid % kChunk;  // this thread's word of the chunk (the same for all its elements)
+      const int64_t wdz = wd0 + cz < wend ? wd0 + cz : wend - 1;
+      const uint64_t kp = keep[wdz];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int64_t i = wd0 * 64 + 4 * (int64_t)idx + j;
-        float rest = i < k ? w[i] : 0.f;
-#pragma unroll
-        for (int p = 0; p < 3; ++p) {
-          pc[p][j] = bf16_bits_rn(rest);
-          rest -= __uint_as_float(pc[p][j] << 16);  // exact: the piece shares the leading bits of `rest`
-        }
+      for (int u = 0; u < kZ; ++u) {
+        const int r = (tid + u * kThreads) / kChunk;
+        const int64_t ra = a0 + r < n ? a0 + r : n - 1, rb = b0 + r < n ? b0 + r : n - 1;
+        za[u] = Zt[ra * KW + wdz];
+        zb[u] = Zt[rb * KW + wdz];
       }
 #pragma unroll
-      for (int p = 0; p < 3; ++p) wpk[p][idx] = gram_u2_t{pc[p][0] | (pc[p][1] << 16), pc[p][2] | (pc[p][3] << 16)};
+      for (int u = 0; u < kWr; ++u) {
+        const int64_t i = wd0 * 64 + tid + u * kThreads;
+        wr_[u] = w[i < k ? i : k - 1];
+      }
+#pragma unroll
+      for (int u = 0; u < kWp; ++u)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int64_t i = wd0 * 64 + 4 * (int64_t)(tid + u * kThreads) + j;
+          w4[u][j] = w[i < k ? i : k - 1];
+        }
+#pragma unroll
+      for (int u = 0; u < kZ; ++u) {
+        const int idx = tid + u * kThreads, r = idx / kChunk, c = idx - r * kChunk;
+        const bool in = wd0 + c < wend;
+        As[r][c] = (a0 + r < n && in) ? (za[u] & kp) : 0ull;  // kept rows only
+        Bs[r][c] = (b0 + r < n && in) ? zb[u] : 0ull;
+      }
+#pragma unroll
+      for (int u = 0; u < kWr; ++u) {
+        const int idx = tid + u * kThreads;
+        wrow[idx] = wd0 * 64 + idx < k ? wr_[u] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < kWp; ++u) {  // rows 4 idx .. 4 idx + 3 of the chunk
+        const int idx = tid + u * kThreads;
+        uint32_t pc[3][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int64_t i = wd0 * 64 + 4 * (int64_t)idx + j;
+          float rest = i < k ? w4[u][j] : 0.f;
+#pragma unroll
+          for (int p = 0; p < 3; ++p) {
+            pc[p][j] = bf16_bits_rn(rest);
+            rest -= __uint_as_float(pc[p][j] << 16);  // exact: the piece shares the leading bits of `rest`
+          }
+        }
+#pragma unroll
+        for (int p = 0; p < 3; ++p) wpk[p][idx] = gram_u2_t{pc[p][0] | (pc[p][1] << 16), pc[p][2] | (pc[p][3] << 16)};
+      }
     }
     if (tid < kChunk) {
       const int64_t wd = wd0 + tid;
