@@ -153,19 +153,20 @@ __global__ __launch_bounds__(kThreads) void gram_rows_kernel(const uint64_t* Zc,
   __syncthreads();
   const uint64_t* Ac = Zc + (size_t)ta * R;
   const uint64_t* Bc = Zc + (size_t)tb * R;
-  for (int64_t r0 = tid; r0 < R; r0 += 4 * kThreads) {  // four rows per step: their loads are in flight together
-    uint64_t av[4], bv[4];
-    unsigned long long wvv[4];
+  constexpr int kRowsPerStep = 8;  // rows per step: their loads are in flight together (addresses clamped, not skipped)
+  for (int64_t r0 = tid; r0 < R; r0 += kRowsPerStep * kThreads) {
+    uint64_t av[kRowsPerStep], bv[kRowsPerStep];
+    unsigned long long wvv[kRowsPerStep];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int64_t r = r0 + (int64_t)u * kThreads;
-      av[u] = r < R ? Ac[r] : 0ull;
-      bv[u] = r < R ? Bc[r] : 0ull;
-      wvv[u] = r < R ? wq[r] : 0ull;
+    for (int u = 0; u < kRowsPerStep; ++u) {
+      const int64_t r = r0 + (int64_t)u * kThreads, rc = r < R ? r : R - 1;
+      av[u] = Ac[rc];
+      bv[u] = Bc[rc];
+      wvv[u] = wq[rc];
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (av[u] == 0ull || bv[u] == 0ull) continue;
+    for (int u = 0; u < kRowsPerStep; ++u) {
+      if (r0 + (int64_t)u * kThreads >= R || av[u] == 0ull || bv[u] == 0ull) continue;
       const unsigned long long wv = wvv[u];
       uint64_t am = av[u];
       while (am) {
