@@ -438,6 +438,19 @@ int ds_copy_probe(ds_ctx* ctx, void* dst, const void* src, int64_t bytes) {
 static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t n_samples, uint64_t seed, const ds_options& o,
                              float* phi, int64_t* M_inout, int64_t* edge_src, int64_t* edge_dst, ds_report* report);
 
+// what ds_explain reads back at its end, in mailbox slots out[0..4]: (y[0], y[1]) as two floats | unused | predicted
+// class | sampler overflow flag | pivot flag of the factorisation (0 without one)
+__global__ void final_mail_kernel(const float* y, const int32_t* pred, const int64_t* sampler_flag, const int* pivot_flag,
+                                  int64_t* out) {
+  float* f = (float*)out;
+  f[0] = y[0];
+  f[1] = y[1];
+  out[1] = 0;
+  out[2] = (int64_t)*pred;
+  out[3] = *sampler_flag;
+  out[4] = pivot_flag ? (int64_t)*pivot_flag : 0;
+}
+
 int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, const ds_options* opts, float* phi,
                int64_t* M_inout, int64_t* edge_src, int64_t* edge_dst, ds_report* report) {
   if (!ctx || !M_inout) return DS_EINVAL;
@@ -564,15 +577,15 @@ static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t
   }
   if (rc != DS_OK && rc != DS_ENOTCONV) return rc;
   DS_HIP(ctx, hipEventRecord(ctx->ev[4], st));
-  // one round trip for everything the host still needs: f(empty), f(full), predicted class, sampler flag
+  // one round trip for everything the host still needs: f(empty), f(full), predicted class, sampler flag, pivot
+  // flag, gathered into consecutive mailbox slots by one small kernel and copied once
   float* f01 = (float*)(ctx->h_mail + 32);
-  DS_HIP(ctx, hipMemcpyAsync(f01, y, 2 * sizeof(float), hipMemcpyDeviceToHost, st));
-  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + 34, cg->d_pred, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + DS_MAIL_SAMPLER, ctx->d_mail + DS_MAIL_SAMPLER, sizeof(int64_t), hipMemcpyDeviceToHost, st));
-  ctx->h_mail[36] = 0;
-  if (direct) DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + 36, gs.flag, sizeof(int), hipMemcpyDeviceToHost, st));
+  hipLaunchKernelGGL(final_mail_kernel, dim3(1), dim3(1), 0, st, y, cg->d_pred, ctx->d_mail + DS_MAIL_SAMPLER,
+                     direct ? gs.flag : (const int*)nullptr, ctx->d_mail + 32);
+  DS_HIP(ctx, hipGetLastError());
+  DS_HIP(ctx, hipMemcpyAsync(ctx->h_mail + 32, ctx->d_mail + 32, 5 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
   DS_HIP(ctx, hipStreamSynchronize(st));
-  if (n >= 2 && ctx->h_mail[DS_MAIL_SAMPLER] != 0)
+  if (n >= 2 && ctx->h_mail[35] != 0)
     return ds_fail(ctx, DS_EINTERNAL, "sampler: candidate list overflow (too many keys share a 24-bit prefix)");
   if (direct && *(int*)(ctx->h_mail + 36) != 0) {
     if (o.solver != DS_SOLVER_AUTO)
