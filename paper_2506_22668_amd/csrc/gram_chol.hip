@@ -652,7 +652,8 @@ __device__ __forceinline__ void eliminate_sub_block(double (*S)[NB + 1], int o, 
   // The column's store and loads are written as instructions: the loads of the next column have to be issued right
   // behind its store, so that they return under the remaining updates of this column, and the compiler's scheduler
   // puts them next to their first use instead. LDS answers a wave in order, so the compiler's own counting of its
-  // LDS accesses stays on the safe side.
+  // LDS accesses stays on the safe side. Between a load and the wait below its destination registers are in flight,
+  // which the compiler does not know: tests/test_isa_lds_reads.py checks the generated code for any use in between.
   typedef double pair_t __attribute__((ext_vector_type(2)));
   const unsigned col_lds = (unsigned)(size_t)(__attribute__((address_space(3))) double*)col;  // byte address in LDS
   const unsigned slot_lds = col_lds + 8u * slot;
