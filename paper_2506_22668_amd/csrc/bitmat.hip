@@ -153,14 +153,23 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_rows_kernel(const uint64_t*
       const double* x0 = x + wd * 64;
       const double* x1 = x0 + 64 * 64;
       double a0 = 0.0, a1 = 0.0;
-      while (w0 | w1) {
-        const bool l0 = w0 != 0ull, l1 = w1 != 0ull;
-        const double v0 = x0[l0 ? __ffsll((long long)w0) - 1 : 0];
-        const double v1 = l1 ? x1[__ffsll((long long)w1) - 1] : 0.0;
-        a0 += l0 ? v0 : 0.0;
-        a1 += v1;
-        w0 &= w0 - 1;
-        w1 &= w1 - 1;
+      while (w0 | w1) {  // four bits of either word per step: eight gathers in flight (same order of additions)
+        double v0[4], v1[4];
+        bool l0[4], l1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          l0[u] = w0 != 0ull;
+          l1[u] = w1 != 0ull;
+          v0[u] = x0[l0[u] ? __ffsll((long long)w0) - 1 : 0];
+          v1[u] = *(l1[u] ? x1 + (__ffsll((long long)w1) - 1) : x0);  // x1 may lie past the end when w1 is empty
+          w0 &= w0 - 1;
+          w1 &= w1 - 1;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          a0 += l0[u] ? v0[u] : 0.0;
+          a1 += l1[u] ? v1[u] : 0.0;
+        }
       }
       acc += a0 + a1;
     }
