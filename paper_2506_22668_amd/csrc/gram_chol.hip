@@ -1041,12 +1041,21 @@ __global__ __launch_bounds__(kThreads) void chol_update_wide_kernel(double* M, i
   const int64_t i0 = base + (int64_t)ti * kTile, c0 = base + (int64_t)tj * kTile;
   constexpr int kPer = kTile * NB / kThreads;
   double pi[kPer], pj[kPer];
+  // Rows past the end of the matrix are read from the last valid row instead of being zeroed: such a row of an
+  // operand only reaches rows (or columns) of the tile that are never stored. The row addresses are formed once.
+  const double* rowi[kPer];
+  const double* rowj[kPer];
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const int idx = tid + u * kThreads, r = idx >> 6, c = idx & 63;
+    rowi[u] = M + (i0 + r < rows_total ? i0 + r : rows_total - 1) * ld + J + c;
+    rowj[u] = M + (c0 + r < n ? c0 + r : n - 1) * ld + J + c;
+  }
   auto fetch = [&](int kc) {
 #pragma unroll
     for (int u = 0; u < kPer; ++u) {
-      const int idx = tid + u * kThreads, r = idx >> 6, c = idx & 63;
-      pi[u] = i0 + r < rows_total ? M[(i0 + r) * ld + J + kc + c] : 0.0;
-      pj[u] = c0 + r < n ? M[(c0 + r) * ld + J + kc + c] : 0.0;
+      pi[u] = rowi[u][kc];
+      pj[u] = rowj[u][kc];
     }
   };
   double4_t acc[2][2];
