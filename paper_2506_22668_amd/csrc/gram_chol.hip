@@ -505,6 +505,7 @@ __global__ __launch_bounds__(kThreads) void build_rhs_kernel(const double* c, in
 
 // ---------------- blocked Cholesky (lower, in place, fp64) ----------------
 constexpr int NB = 64;
+constexpr int64_t kSuperCols = 256;  // columns of a super-panel (large trailing matrices)
 
 // 1/sqrt(p) for 1e-30 < p < 1e30: single-precision seed, two Newton steps r += r (1/2 - (p/2) r^2) in double (a
 // short dependent chain; the library routine costs several times more per step of a sequential loop)
@@ -1031,8 +1032,11 @@ __global__ void copy_panel_kernel(const double* M, int64_t ld, int64_t rows_tota
 // registers across the kw/64 column chunks, so it is read and written once per super-panel instead of once
 // per 64 columns; the next chunk of the two operands is fetched into registers while the matrix cores work on
 // the current one.
+template <int KW>  // columns of the super-panel: known at compile time, so that the chunk loop unrolls (column offsets
+                   // become immediates and the accumulators stay where the matrix cores want them)
 __global__ __launch_bounds__(kThreads) void chol_update_wide_kernel(double* M, int64_t ld, int64_t rows_total, int64_t n,
-                                                                    int64_t J, int kw, int64_t base) {
+                                                                    int64_t J, int64_t base) {
+  constexpr int kw = KW;
   const int ti = blockIdx.y, tj = blockIdx.x;
   if (tj > ti) return;
   __shared__ double Li[kTile][NB + 1];
@@ -1064,6 +1068,7 @@ __global__ __launch_bounds__(kThreads) void chol_update_wide_kernel(double* M, i
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
   fetch(0);
+#pragma unroll
   for (int kc = 0; kc < kw; kc += NB) {
     __syncthreads();
 #pragma unroll
@@ -1123,7 +1128,6 @@ __global__ __launch_bounds__(kThreads) void chol_back_step_kernel(const double* 
 // drops their contribution. At this size the chain of per-block launches costs more than the arithmetic.
 constexpr int kBackSmallMax = 2048;
 constexpr int64_t kFuseMaxRows = 2048;
-constexpr int64_t kSuperCols = 256;     // columns of a super-panel (large trailing matrices)  // trailing rows up to which the update also factorises the next block
 constexpr int kBackThreads = 512;
 __global__ __launch_bounds__(kBackThreads) void chol_back_small_kernel(const double* M, int64_t ld, int64_t n, int nblk,
                                                                        const double* linv, const float* y01, float* phi) {
@@ -1365,8 +1369,8 @@ int ds_gram_finish(ds_ctx* ctx, const ds_gram_state* gs, const uint64_t* Z, cons
       }
       const int64_t base = j0 + kSuperCols;
       const unsigned tw = nblocks(rows_total - base, kTile);
-      hipLaunchKernelGGL(chol_update_wide_kernel, dim3(tw, tw), dim3(kThreads), 0, st, M, ld, rows_total, n, j0,
-                         (int)kSuperCols, base);
+      hipLaunchKernelGGL(chol_update_wide_kernel<(int)kSuperCols>, dim3(tw, tw), dim3(kThreads), 0, st, M, ld, rows_total, n,
+                         j0, base);
       j0 += kSuperCols;
       diag_done = false;
       continue;
