@@ -16,14 +16,14 @@ SRC = os.path.join(ROOT, "paper_2506_22668_amd", "csrc", "gram_chol.hip")
 KERNELS = ("chol_diag_kernel", "chol_step_kernel", "chol_update_kernelILb1")
 
 
-@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="no hipcc")
 def test_no_use_of_an_in_flight_lds_destination_before_its_wait():
-    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    # exactly the flags of the shipped library (one list, in build.py), so that the code inspected here is the
+    # code that runs; a machine without the compiler fails this test rather than passing it unseen
+    from paper_2506_22668_amd.build import COMPILE_FLAGS, HIPCC
+    assert os.path.exists(HIPCC) or shutil.which(HIPCC), "hipcc is needed to inspect the generated code"
     with tempfile.TemporaryDirectory() as tmp:
         out = os.path.join(tmp, "gram_chol.s")
-        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-               "-packed-fp32-ops", "-I" + os.path.join(ROOT, "include"),
-               "-I" + os.path.join(ROOT, "paper_2506_22668_amd", "csrc"), "-S", "--cuda-device-only", SRC, "-o", out]
+        cmd = [HIPCC] + COMPILE_FLAGS + ["-S", "--cuda-device-only", SRC, "-o", out]
         subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
         lines = open(out).read().split("\n")
     name, pending, reads, seen = "", {}, 0, set()
