@@ -54,7 +54,8 @@ enum ds_status {
 
 enum ds_dtype {
   DS_F32 = 0,            /* fp32 storage and arithmetic */
-  DS_BF16_IN_F32_ACC = 1 /* dense transforms round their inputs to bf16, accumulate in fp32 */
+  DS_BF16_IN_F32_ACC = 1 /* the per-coalition dense transforms (layers 2..L) round both operands to bf16 and
+                            accumulate in fp32; the product X_c W_1, formed once per target, stays fp32 */
 };
 
 enum ds_score { DS_SCORE_PROB = 0, DS_SCORE_LOGIT = 1 };

@@ -55,21 +55,19 @@ def round_bf16(x):
 def forward(Ahat, X, weights, biases=None, bf16=False):
     """Logits of every node. X float64[n, d0].
 
-    bf16=True is the reduced-precision configuration: the two operands of every
-    dense transform are rounded to bfloat16 and the products are accumulated
-    exactly.  Layer 1 is then taken as A^ (X W_1) (equal to (A^ X) W_1 in real
-    arithmetic), so the rounded operands are X and W_1; for the later layers
-    they are the aggregated activations A^ H and W_l."""
+    bf16=True is a DIAGNOSTIC mode (parity of the reduced-precision configuration is
+    judged against bf16=False): in layers 2..L the two operands of the dense
+    transform, the aggregated activations A^ H and W_l, are rounded to bfloat16 and
+    the products are accumulated exactly; layer 1 (whose product with W_1 does not
+    depend on the coalition) is left unrounded."""
     H = np.asarray(X, dtype=np.float64)
     L = len(weights)
     for l, W in enumerate(weights):
         W = np.asarray(W, dtype=np.float64)
-        if not bf16:
-            H = (Ahat @ H) @ W
-        elif l == 0:
-            H = Ahat @ (round_bf16(H) @ round_bf16(W))
-        else:
+        if bf16 and l >= 1:
             H = round_bf16(Ahat @ H) @ round_bf16(W)
+        else:
+            H = (Ahat @ H) @ W
         if biases is not None and biases[l] is not None:
             H = H + np.asarray(biases[l], dtype=np.float64)
         if l < L - 1:

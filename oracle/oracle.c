@@ -152,7 +152,8 @@ static double round_bf16(double x) {
  * Wcat: the L weight matrices one after another (row-major d_{l-1} x d_l); bias_cat: NULL or the L bias
  * vectors one after another. score: 0 softmax probability, 1 logit, of class pred_class.
  * Every layer is evaluated on every node: A~ = A_S + I, A^ = D^-1/2 A~ D^-1/2, H <- act(A^ H W + b).
- * bf16 != 0: operands of the dense transforms rounded to bfloat16 (layer 1 as A^ (X W_1)).
+ * bf16 != 0 (a diagnostic mode, not what parity is judged against): in layers 2..L both operands of the dense
+ * transform (A^ H and W_l) are rounded to bfloat16 and the products summed exactly; layer 1 is not rounded.
  */
 int oc_gcn_values(int32_t V, int64_t n, const int32_t* psrc, const int32_t* pdst, int32_t directed, const double* X,
                   int32_t L, const int32_t* dims, const double* Wcat, const double* bias_cat, int32_t bf16, int32_t score,
@@ -183,47 +184,34 @@ int oc_gcn_values(int32_t V, int64_t n, const int32_t* psrc, const int32_t* pdst
       const double* bl = bias_cat;
       for (int l = 1; l <= L; ++l) {
         const int din = dims[l - 1], dout = dims[l];
+        const int round_ops = bf16 && l >= 2; /* the first product is shared by all coalitions and stays unrounded */
         const double* Wuse = Wl;
-        if (bf16) {
+        if (round_ops) {
           for (int q = 0; q < din * dout; ++q) Wr[q] = round_bf16(Wl[q]);
           Wuse = Wr;
         }
-        int width = din;
-        const double* src = H;
-        if (bf16 && l == 1) { /* transform first: T = bf16(X) bf16(W_1), then aggregate T */
-          for (int v = 0; v < V; ++v)
-            for (int j = 0; j < dout; ++j) {
-              double s = 0.0;
-              for (int q = 0; q < din; ++q) s += round_bf16(H[(size_t)v * din + q]) * Wuse[(size_t)q * dout + j];
-              T[(size_t)v * dout + j] = s;
-            }
-          src = T;
-          width = dout;
-        }
-        /* A = A^ src */
+        /* A = A^ H */
         for (int v = 0; v < V; ++v)
-          for (int q = 0; q < width; ++q) A[(size_t)v * width + q] = dinv[v] * dinv[v] * src[(size_t)v * width + q];
+          for (int q = 0; q < din; ++q) A[(size_t)v * din + q] = dinv[v] * dinv[v] * H[(size_t)v * din + q];
         for (int64_t p = 0; p < n; ++p)
           if ((z[p >> 6] >> (p & 63)) & 1ull) {
             const int s = psrc[p], d = pdst[p];
             const double c = dinv[s] * dinv[d];
-            for (int q = 0; q < width; ++q) A[(size_t)d * width + q] += c * src[(size_t)s * width + q];
+            for (int q = 0; q < din; ++q) A[(size_t)d * din + q] += c * H[(size_t)s * din + q];
             if (!directed)
-              for (int q = 0; q < width; ++q) A[(size_t)s * width + q] += c * src[(size_t)d * width + q];
+              for (int q = 0; q < din; ++q) A[(size_t)s * din + q] += c * H[(size_t)d * din + q];
           }
-        if (bf16 && l == 1) {
-          memcpy(H, A, (size_t)V * dout * sizeof(double));
-        } else {
-          for (int v = 0; v < V; ++v)
-            for (int j = 0; j < dout; ++j) {
-              double s = 0.0;
-              for (int q = 0; q < din; ++q) {
-                const double a = bf16 ? round_bf16(A[(size_t)v * din + q]) : A[(size_t)v * din + q];
-                s += a * Wuse[(size_t)q * dout + j];
-              }
-              H[(size_t)v * dout + j] = s;
+        /* T = A W (operands rounded to bfloat16 in the reduced-precision layers), then H = T */
+        for (int v = 0; v < V; ++v)
+          for (int j = 0; j < dout; ++j) {
+            double s = 0.0;
+            for (int q = 0; q < din; ++q) {
+              const double a = round_ops ? round_bf16(A[(size_t)v * din + q]) : A[(size_t)v * din + q];
+              s += a * Wuse[(size_t)q * dout + j];
             }
-        }
+            T[(size_t)v * dout + j] = s;
+          }
+        memcpy(H, T, (size_t)V * dout * sizeof(double));
         for (int v = 0; v < V; ++v)
           for (int j = 0; j < dout; ++j) {
             double s = H[(size_t)v * dout + j] + (bl ? bl[j] : 0.0);

@@ -876,8 +876,9 @@ int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg) {
   if (cg->d0 != ctx->dims[0]) return ds_fail(ctx, DS_EINVAL, "feature width %d does not match the model's input width %d", cg->d0, ctx->dims[0]);
   if (cg->model_version == ctx->model_version) return DS_OK;
   if (cg->d1 != ctx->dims[1]) return ds_fail(ctx, DS_EINVAL, "the computational graph was extracted for a model with first hidden width %d (now %d): extract again", cg->d1, ctx->dims[1]);
-  DS_TRY(ds_launch_first_transform(ctx, cg->Xc, ctx->W[0], cg->P, (int)cg->info.num_nodes, ctx->dims[0], ctx->dims[1],
-                                   ctx->transform_dtype == DS_BF16_IN_F32_ACC));
+  // The shared product is formed once per target and feeds every coalition: it stays in fp32 also in the
+  // reduced-precision configuration (only the per-coalition transforms round their operands to bfloat16).
+  DS_TRY(ds_launch_first_transform(ctx, cg->Xc, ctx->W[0], cg->P, (int)cg->info.num_nodes, ctx->dims[0], ctx->dims[1], 0));
   // predicted class: evaluate the full coalition once and take the first maximum
   const int64_t n = cg->info.num_players;
   const int64_t W = (n + 63) / 64;

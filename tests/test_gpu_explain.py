@@ -24,8 +24,9 @@ def _explain_case(key, tol, solver=None, oracle_solver="lstsq", targets=None):
         phi, es, ed, rep, rc = ctx.explain(target, w.n_samples, w.seed, opts)
         # an iterative solve is compared at the same stopping rule on both sides: the
         # truncation error of CGLS at tol is part of the method, not of the arithmetic
+        # the gate is always the plain fp64 oracle, also for the reduced-precision configuration
         ref = oexplain.explain(w.row_ptr, w.col, w.features, w.weights, target, w.n_samples, w.seed,
-                               solver=oracle_solver, tol=w.tol, bf16=(dtype == 1))
+                               solver=oracle_solver, tol=w.tol)
         assert rep.num_players == ref["n"] and rep.num_rows == ref["k"]
         assert rep.pred_class == ref["pred_class"]
         assert np.array_equal(es.cpu().numpy(), ref["cg"]["edge_src"])
@@ -36,6 +37,14 @@ def _explain_case(key, tol, solver=None, oracle_solver="lstsq", targets=None):
         say(f"  n={ref['n']} k={ref['k']} max|phi|={scale:.3e} err={err:.3e} iters={rep.cgls_iterations} "
             f"ms: ext={rep.ms_extract:.2f} smp={rep.ms_sample:.2f} eval={rep.ms_eval:.2f} solve={rep.ms_solve:.2f}")
         assert err <= tol * scale
+        if dtype == 1:
+            # diagnostic beside the gate: against the oracle's bfloat16-emulating mode (per-coalition transforms
+            # round both operands) only accumulation order is left
+            diag = oexplain.explain(w.row_ptr, w.col, w.features, w.weights, target, w.n_samples, w.seed,
+                                    solver=oracle_solver, tol=w.tol, bf16=True)
+            derr = np.abs(got - diag["phi"]).max()
+            say(f"  diagnostic: err vs the bf16-emulating oracle mode = {derr:.3e} ({derr / scale:.1e} of max|phi|)")
+            assert derr <= 1e-3 * scale
         if oracle_solver == "cgls":
             # the residual creeps over the threshold slowly near the end, so round-off can move the
             # stopping iteration by a few steps; phi above is what has to agree
@@ -113,7 +122,7 @@ def test_uniform_weighting_option_matches_the_oracle():
 
 
 def test_small_batched_bf16_config():
-    # oracle in the same reduced-precision reading: transform operands rounded to bf16
+    # bf16 per-coalition transforms against the plain fp64 oracle, at the tolerance stated for this configuration
     _explain_case("c5_small", 1e-2)
 
 
@@ -135,6 +144,30 @@ def test_explain_batch_equals_single_explanations():
     phi, M, off, es, ed, reps, rc = ctx.explain_batch(w.targets, w.n_samples, w.seed, capacity=len(singles[0]))
     assert rc == DS_ECAPACITY and off[-1] == total
     ctx.close()
+
+
+def test_explain_batch_matches_the_oracle():
+    """The batch entry point against the oracle itself (not against single HIP calls): fp32 transforms at 1e-4 of
+    max|phi|, and the reduced-precision configuration at its 1e-2, every target of the batch."""
+    w = make_workload("c5_small")
+    for dtype, tol in ((0, 1e-4), (1, 1e-2)):
+        say(f"explain_batch c5_small vs oracle, transform dtype {dtype}")
+        ctx = make_context(w, transform_dtype=dtype)
+        refs = [oexplain.explain(w.row_ptr, w.col, w.features, w.weights, t, w.n_samples, w.seed) for t in w.targets]
+        total = sum(r["n"] for r in refs)
+        phi, M, off, es, ed, reps, rc = ctx.explain_batch(w.targets, w.n_samples, w.seed, capacity=total)
+        assert rc == 0 and M == [r["n"] for r in refs]
+        for i, r in enumerate(refs):
+            got = phi[off[i]:off[i + 1]].cpu().numpy().astype(np.float64)
+            scale = np.abs(r["phi"]).max()
+            err = np.abs(got - r["phi"]).max()
+            say(f"  target {w.targets[i]}: n={r['n']} err={err:.3e} ({err / scale:.1e} of max|phi|)")
+            assert err <= tol * scale
+            assert np.array_equal(es[off[i]:off[i + 1]].cpu().numpy(), r["cg"]["edge_src"])
+            assert np.array_equal(ed[off[i]:off[i + 1]].cpu().numpy(), r["cg"]["edge_dst"])
+            assert reps[i].pred_class == r["pred_class"]
+            assert abs(got.sum() - (reps[i].f_full - reps[i].f_empty)) <= 1e-5
+        ctx.close()
 
 
 def test_explain_batch_more_targets_than_workers_and_a_bad_target():

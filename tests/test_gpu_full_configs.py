@@ -1,16 +1,26 @@
 """Configs 3, 4 and 5 at their full sizes, in the launch configuration bench.py uses.
 
 The numpy oracle cannot finish these, so the plain-C restatement (oracle/oracle.c, itself tested
-against the numpy oracle) is used, and only on what it can compute in seconds:
+against the numpy oracle) is used, on what it can compute within minutes:
   * masks / weights / sizes: bit-exact on a stratified sample of pairs taken from the full mask
     matrix the GPU wrote, plus popcount and complement invariants on every row;
-  * y: sampled rows, element by element;
-  * phi: efficiency, and the normal-equation residual |P Z^T W (t - Z psi)| / |P Z^T W t| recomputed
-    by the oracle from the GPU's phi (what CGLS must have driven below tol) for the CGLS configs;
-    for the Gram+Cholesky config the oracle's converged CGLS solution on the same y (the
-    least-squares solution is unique there). phi checks use the GPU's y (validated on samples),
-    because the oracle needs hours for all rows.
+  * y: element by element on at least 1 % of the rows, spread evenly over the pairs (pairs ascend by
+    size, so every size class is sampled in proportion to its rows), both members of each pair;
+  * phi, CGLS configs (3, 4): the conjugate-gradient iteration is deterministic, so the iterate after a
+    fixed number of steps is compared element by element with the oracle's iterate after the same
+    number of steps on the same y (this exercises the full-size products with Z and its transpose;
+    for the under-determined config 4 it also pins the minimum-norm trajectory, which a small
+    residual alone would not). The converged one-shot explanation is then checked for efficiency,
+    its reported residual, and (config 3) the residual recomputed by the oracle;
+  * phi, config 5: all 64 targets through ds_explain_batch; efficiency on every target; on eight
+    targets spread over the range of game sizes phi against the oracle's converged solve on the
+    GPU's y (unique there), y on 1 % of the rows; and on the smallest game the whole explanation
+    against the plain fp64 oracle (its own y on every row) at the 1e-2 of the bf16 configuration.
+phi checks other than the last use the GPU's y (validated on the samples), because the oracle needs
+hours for all rows.
 """
+import time
+
 import numpy as np
 import pytest
 
@@ -37,11 +47,56 @@ def _popcount_rows(Z):
     return out
 
 
-def _stage_check(key, pair_stride, y_rows, check_residual=True):
-    from paper_2506_22668_amd import Options, DS_SOLVER_CGLS, DS_SOLVER_GRAM_CHOL
+def _stratified_rows(k, count):
+    """About `count` rows: rows 0/1 and both members of pairs spread evenly over the pair index."""
+    pairs = np.unique(np.linspace(1, k // 2 - 1, max(count // 2, 2)).astype(np.int64))
+    return np.concatenate([[0, 1], np.stack([2 * pairs, 2 * pairs + 1], axis=1).ravel()])
+
+
+def _check_masks(ctx, w, key, n, target, Z, wt, sz, pair_stride):
+    k = Z.shape[0]
+    K1 = k // 2
+    pc = _popcount_rows(Z)
+    assert torch.equal(pc, sz.to(torch.int64))
+    assert torch.equal(pc[0::2] + pc[1::2], torch.full((K1,), n, dtype=torch.int64, device=pc.device))
+    tail = (1 << (n % 64)) - 1 if n % 64 else -1
+    full = torch.full((Z.shape[1],), -1, dtype=torch.int64, device=Z.device)
+    full[-1] = tail
+    step = max(1, (1 << 25) // Z.shape[1])
+    for a in range(0, K1, step):
+        assert torch.equal(Z[2 * a:2 * (a + step):2] ^ Z[2 * a + 1:2 * (a + step):2],
+                           full.expand(min(step, K1 - a), -1))
+    assert torch.all(sz[2::2][1:] >= sz[2::2][:-1])          # pairs ascending by size
+    pairs = np.unique(np.concatenate([np.arange(0, K1, pair_stride), [1, K1 - 1]]))
+    say(f"{key}: oracle masks for {len(pairs)} pairs")
+    rows = np.stack([2 * pairs, 2 * pairs + 1], axis=1).ravel()
+    Zg = to_u64(Z[torch.from_numpy(rows).cuda()])
+    wg, szg = wt.cpu().numpy()[rows], sz.cpu().numpy()[rows]
+    for i, r in enumerate(pairs):
+        Zo, wo, szo = cfast.sample(n, w.n_samples, w.seed, target, pair_range=(int(r), int(r) + 1))
+        assert np.array_equal(Zo, Zg[2 * i:2 * i + 2]), f"pair {r}"
+        assert np.array_equal(wo.view(np.uint32), wg[2 * i:2 * i + 2].view(np.uint32))
+        assert np.array_equal(szo, szg[2 * i:2 * i + 2])
+
+
+def _check_y(key, w, cgo, Z, y, pcl, count, bf16):
+    k = Z.shape[0]
+    sel = _stratified_rows(k, count)
+    assert len(sel) >= 0.01 * k
+    t0 = time.time()
+    Zs = to_u64(Z[torch.from_numpy(sel).cuda()])
+    yo, pco, _ = cfast.gcn_values(cgo, w.features, w.weights, Zs, bf16=bf16)
+    assert pcl == pco
+    err = np.abs(y.cpu().numpy()[sel].astype(np.float64) - yo).max()
+    say(f"{key}: max |y - oracle| on {len(sel)} of {k} rows = {err:.3e} ({time.time() - t0:.0f} s of oracle)")
+    assert err <= (1e-5 if not bf16 else 2e-5)
+    return sel, Zs
+
+
+def _cgls_config(key, pair_stride, iterations, check_residual):
+    from paper_2506_22668_amd import Options, DS_SOLVER_CGLS, DS_ENOTCONV
     w = make_workload(key)
-    bf16 = w.transform_dtype == "bf16"
-    ctx = make_context(w, transform_dtype=1 if bf16 else 0)
+    ctx = make_context(w)
     target = w.targets[0]
     say(f"{key}: extract target={target}")
     cg = ctx.extract(target)
@@ -55,85 +110,115 @@ def _stage_check(key, pair_stride, y_rows, check_residual=True):
     say(f"{key}: sample n={n} k={w.n_samples}")
     Z, wt, sz = ctx.sample(n, w.n_samples, w.seed, target)
     k = Z.shape[0]
-    K1 = k // 2
-    # invariants on every row
-    pc = _popcount_rows(Z)
-    assert torch.equal(pc, sz.to(torch.int64))
-    assert torch.equal(pc[0::2] + pc[1::2], torch.full((K1,), n, dtype=torch.int64, device=pc.device))
-    tail = (1 << (n % 64)) - 1 if n % 64 else -1
-    full = torch.full((Z.shape[1],), -1, dtype=torch.int64, device=Z.device)
-    full[-1] = tail
-    step = max(1, (1 << 25) // Z.shape[1])
-    for a in range(0, K1, step):
-        assert torch.equal(Z[2 * a:2 * (a + step):2] ^ Z[2 * a + 1:2 * (a + step):2],
-                           full.expand(min(step, K1 - a), -1))
-    assert torch.all(sz[2::2][1:] >= sz[2::2][:-1])          # pairs ascending by size
-    # bit-exact against the oracle on a stratified sample of pairs
-    pairs = np.unique(np.concatenate([np.arange(0, K1, pair_stride), [1, K1 - 1]]))
-    say(f"{key}: oracle masks for {len(pairs)} pairs")
-    rows = np.stack([2 * pairs, 2 * pairs + 1], axis=1).ravel()
-    Zg = to_u64(Z[torch.from_numpy(rows).cuda()])
-    wg, szg = wt.cpu().numpy()[rows], sz.cpu().numpy()[rows]
-    for i, r in enumerate(pairs):
-        Zo, wo, szo = cfast.sample(n, w.n_samples, w.seed, target, pair_range=(int(r), int(r) + 1))
-        assert np.array_equal(Zo, Zg[2 * i:2 * i + 2]), f"pair {r}"
-        assert np.array_equal(wo.view(np.uint32), wg[2 * i:2 * i + 2].view(np.uint32))
-        assert np.array_equal(szo, szg[2 * i:2 * i + 2])
+    _check_masks(ctx, w, key, n, target, Z, wt, sz, pair_stride)
 
-    say(f"{key}: eval all rows, oracle on {y_rows} of them")
+    say(f"{key}: eval all rows")
     y, pcl = ctx.eval(cg, Z)
-    sel = np.unique(np.concatenate([[0, 1, 2, 3, k - 2, k - 1],
-                                    np.random.default_rng(1).integers(0, k, size=y_rows)]))
-    yo, pco, _ = cfast.gcn_values(cgo, w.features, w.weights, to_u64(Z[torch.from_numpy(sel).cuda()]), bf16=bf16)
-    assert pcl == pco
-    err = np.abs(y.cpu().numpy()[sel].astype(np.float64) - yo).max()
-    say(f"{key}: max |y - oracle| on sampled rows = {err:.3e}")
-    assert err <= (1e-5 if not bf16 else 2e-5)
+    _check_y(key, w, cgo, Z, y, pcl, int(0.01 * k) + 2, False)
 
-    say(f"{key}: solve")
-    opts = Options(solver=DS_SOLVER_CGLS if w.solver == "cgls" else DS_SOLVER_GRAM_CHOL, tol=w.tol,
-                   max_iter=w.max_iter, paired=1)
-    phi, rep, rc = ctx.solve(n, Z, wt, y, opts)
+    # the iterate after `iterations` steps, element by element (tol far below anything reachable: never met)
+    say(f"{key}: {iterations} CGLS steps on both sides")
+    phi, rep, rc = ctx.solve(n, Z, wt, y, Options(solver=DS_SOLVER_CGLS, tol=1e-300, max_iter=iterations, paired=1),
+                             allow_not_converged=True)
+    assert rc == DS_ENOTCONV and rep.cgls_iterations == iterations
     got = phi.cpu().numpy().astype(np.float64)
     yh = y.cpu().numpy().astype(np.float64)
-    assert abs(got.sum() - (yh[1] - yh[0])) <= 1e-5
-    say(f"{key}: solver={rep.solver_used} iterations={rep.cgls_iterations} rel={rep.cgls_rel_residual:.3e} "
-        f"max|phi|={np.abs(got).max():.3e}")
     Zh = to_u64(Z)
-    if w.solver == "cgls":
-        assert rep.cgls_rel_residual <= w.tol
-        if check_residual:
-            res = cfast.normal_residual(n, Zh, wt.cpu().numpy(), yh, got)
-            say(f"{key}: oracle-side residual of the GPU solution = {res:.3e}")
-            # phi is rounded to fp32 on output: allow that rounding on top of tol
-            assert res <= 2.0 * w.tol
-    else:
-        # 1e-11 is safely above where fp64 round-off stalls the recurrence on this size
-        ref, it, rel = cfast.cgls(n, Zh, wt.cpu().numpy(), yh, tol=1e-11, max_iter=2000)
-        assert rel <= 1e-11
-        err = np.abs(got - ref).max()
-        say(f"{key}: max |phi - oracle| = {err:.3e}")
-        assert err <= 1e-4 * np.abs(ref).max()
+    t0 = time.time()
+    ref, it, rel = cfast.cgls(n, Zh, wt.cpu().numpy(), yh, tol=0.0, max_iter=iterations)
+    assert it == iterations
+    err, scale = np.abs(got - ref).max(), np.abs(ref).max()
+    say(f"{key}: iterate {iterations}: max |phi - oracle| = {err:.3e}, max|phi| = {scale:.3e}, residual gpu {rep.cgls_rel_residual:.6e} "
+        f"oracle {rel:.6e} ({time.time() - t0:.0f} s of oracle)")
+    assert err <= 1e-4 * scale
+    assert abs(rep.cgls_rel_residual - rel) <= 1e-4 * rel
+    assert abs(got.sum() - (yh[1] - yh[0])) <= 1e-5
 
-    # the one-shot call gives the same answer as the stages
+    # the converged one-shot explanation
     say(f"{key}: one-shot explain")
     phi2, _, _, rep2, _ = ctx.explain(target, w.n_samples, w.seed,
-                                      Options(solver=opts.solver, tol=w.tol, max_iter=w.max_iter), capacity=n,
+                                      Options(solver=DS_SOLVER_CGLS, tol=w.tol, max_iter=w.max_iter), capacity=n,
                                       want_edges=False)
-    assert torch.equal(phi2, phi)
-    say(f"{key}: ms extract={rep2.ms_extract:.2f} sample={rep2.ms_sample:.2f} eval={rep2.ms_eval:.2f} "
-        f"solve={rep2.ms_solve:.2f}")
+    got2 = phi2.cpu().numpy().astype(np.float64)
+    say(f"{key}: iterations={rep2.cgls_iterations} rel={rep2.cgls_rel_residual:.3e} max|phi|={np.abs(got2).max():.3e} "
+        f"ms extract={rep2.ms_extract:.2f} sample={rep2.ms_sample:.2f} eval={rep2.ms_eval:.2f} solve={rep2.ms_solve:.2f}")
+    assert rep2.cgls_rel_residual <= w.tol
+    assert abs(got2.sum() - (rep2.f_full - rep2.f_empty)) <= 1e-5
+    assert abs(rep2.f_full - yh[1]) <= 1e-6 and abs(rep2.f_empty - yh[0]) <= 1e-6
+    if check_residual:
+        res = cfast.normal_residual(n, Zh, wt.cpu().numpy(), yh, got2)
+        say(f"{key}: oracle-side residual of the converged GPU solution = {res:.3e}")
+        assert res <= 2.0 * w.tol          # phi is rounded to fp32 on output: allow that on top of tol
     ctx.cgraph_free(cg)
     ctx.close()
 
 
 def test_config3_rmat18_100k_players_cgls():
-    _stage_check("c3", pair_stride=400, y_rows=48)
-
-
-def test_config5_batched_bf16_gram_cholesky_first_target():
-    _stage_check("c5", pair_stride=100, y_rows=48)
+    _cgls_config("c3", pair_stride=400, iterations=25, check_residual=True)
 
 
 def test_config4_rmat20_1m_players_underdetermined_cgls():
-    _stage_check("c4", pair_stride=5000, y_rows=16)
+    _cgls_config("c4", pair_stride=5000, iterations=3, check_residual=False)
+
+
+def test_config5_all_64_targets_bf16_gram_cholesky():
+    from paper_2506_22668_amd import Options, DS_SOLVER_GRAM_CHOL, DS_ECAPACITY
+    w = make_workload("c5")
+    assert len(w.targets) == 64
+    ctx = make_context(w, transform_dtype=1)
+    opts = Options(solver=DS_SOLVER_GRAM_CHOL)
+    say("c5: sizes of the 64 games")
+    _, M, off, _, _, _, rc = ctx.explain_batch(w.targets, w.n_samples, w.seed, opts, capacity=0)
+    assert rc == DS_ECAPACITY
+    say(f"c5: explain_batch, {off[-1]} players in all, games of {min(M)} .. {max(M)} players")
+    t0 = time.time()
+    phi, M2, off, es, ed, reps, rc = ctx.explain_batch(w.targets, w.n_samples, w.seed, opts, capacity=off[-1])
+    say(f"c5: batch of 64 done in {time.time() - t0:.2f} s")
+    assert rc == 0 and M2 == M
+    for i in range(64):
+        got = phi[off[i]:off[i + 1]].cpu().numpy().astype(np.float64)
+        assert reps[i].num_players == M[i] and reps[i].num_rows == 50_000
+        assert abs(got.sum() - (reps[i].f_full - reps[i].f_empty)) <= 1e-5, i
+    order = np.argsort(M, kind="stable")
+    picked = [int(order[j]) for j in np.unique(np.linspace(0, 63, 8).round().astype(int))]
+    for rank, i in enumerate(picked):
+        target, n = w.targets[i], M[i]
+        say(f"c5: target {target} ({n} players): stages")
+        cg = ctx.extract(target)
+        cgo = compgraph.extract(w.row_ptr, w.col, target, w.num_layers)
+        assert cgo["num_players"] == n
+        assert np.array_equal(es[off[i]:off[i + 1]].cpu().numpy(), cgo["edge_src"])
+        assert np.array_equal(ed[off[i]:off[i + 1]].cpu().numpy(), cgo["edge_dst"])
+        Z, wt, sz = ctx.sample(n, w.n_samples, w.seed, target)
+        k = Z.shape[0]
+        if rank in (0, len(picked) - 1):
+            _check_masks(ctx, w, f"c5[{target}]", n, target, Z, wt, sz, 250)
+        y, pcl = ctx.eval(cg, Z)
+        assert pcl == reps[i].pred_class
+        # y against the oracle's bf16-emulating diagnostic mode (same rounding points, so only the order of the
+        # fp32 sums is left), and how far that is from the plain fp64 value function
+        sel, Zs = _check_y(f"c5[{target}]", w, cgo, Z, y, pcl, int(0.01 * k) + 2, True)
+        yp, _, _ = cfast.gcn_values(cgo, w.features, w.weights, Zs, bf16=False)
+        say(f"c5[{target}]: max |y - plain fp64 oracle| on the same rows = {np.abs(y.cpu().numpy()[sel] - yp).max():.3e}")
+        got = phi[off[i]:off[i + 1]].cpu().numpy().astype(np.float64)
+        yh = y.cpu().numpy().astype(np.float64)
+        t0 = time.time()
+        # 1e-11 is safely above where fp64 round-off stalls the recurrence on these sizes
+        ref, it, rel = cfast.cgls(n, to_u64(Z), wt.cpu().numpy(), yh, tol=1e-11, max_iter=4000)
+        assert rel <= 1e-11
+        err, scale = np.abs(got - ref).max(), np.abs(ref).max()
+        say(f"c5[{target}]: max |phi - oracle solve on the GPU's y| = {err:.3e} (max|phi| {scale:.3e}, {it} oracle "
+            f"iterations, {time.time() - t0:.0f} s)")
+        assert err <= 1e-4 * scale
+        if rank == 0:
+            # the smallest game end to end against the plain fp64 oracle: its own y on every row, its own solve
+            t0 = time.time()
+            yo, pco, _ = cfast.gcn_values(cgo, w.features, w.weights, to_u64(Z), bf16=False)
+            refp, it, rel = cfast.cgls(n, to_u64(Z), wt.cpu().numpy(), yo, tol=1e-11, max_iter=4000)
+            errp, scalep = np.abs(got - refp).max(), np.abs(refp).max()
+            say(f"c5[{target}]: max |phi - plain fp64 oracle| = {errp:.3e} = {errp / scalep:.2e} of max|phi| "
+                f"({time.time() - t0:.0f} s of oracle)")
+            assert pco == pcl and rel <= 1e-11
+            assert errp <= 1e-2 * scalep
+        ctx.cgraph_free(cg)
+    ctx.close()

@@ -321,3 +321,30 @@ def test_bf16_mode_stays_close_to_full_precision():
         m = rng.random(cg["num_players"]) < 0.5
         assert abs(f64(m) - f16(m)) < 2e-2
         assert f64(m) != f16(m)
+
+
+def test_bf16_diagnostic_mode_operand_placement_hand_worked():
+    """Two nodes joined by one edge, widths 1 -> 1 -> 1, X = (1, 2), W_1 = 1 + 2^-6 + 2^-8, W_2 = 3 + 2^-7 + 2^-12.
+    Full coalition: A^ = [[1/2, 1/2], [1/2, 1/2]]. Layer 1 is NOT rounded: A^ X = 1.5 at both nodes,
+    h = 1.5 * 1.01953125 = 1.529296875. Layer 2 rounds both operands: bfloat16 spacing is 2^-7 in [1, 2), so
+    A^ H = h -> 1.53125 (0.00195 away; 1.5234375 is 0.00586 away); spacing 2^-6 in [2, 4), so
+    W_2 = 3.00805664 -> 3.015625 (0.00757 away; 3.0 is 0.00806 away); logit = 1.53125 * 3.015625 = 4.61767578125.
+    Rounding layer 1 as well would give 4.5941162109375, leaving the activations unrounded 4.611785888671875,
+    leaving W_2 unrounded 4.606086730957031, no rounding 4.6002116203308105: each misplacement fails.
+    Empty coalition: A^ = I, h = 1.01953125 = 1 + 2.5 * 2^-7, a tie that goes to the even neighbour 1.015625;
+    logit = 1.015625 * 3.015625 = 3.062744140625."""
+    from oracle import cfast
+    row_ptr = np.array([0, 1, 2], dtype=np.int64)
+    col = np.array([1, 0], dtype=np.int32)
+    X = np.array([[1.0], [2.0]])
+    weights = [np.array([[1.0 + 2.0 ** -6 + 2.0 ** -8]]), np.array([[3.0 + 2.0 ** -7 + 2.0 ** -12]])]
+    cg = compgraph.extract(row_ptr, col, 0, 2)
+    assert cg["num_players"] == 1 and cg["num_nodes"] == 2
+    f = gcn.ValueFunction(cg, X, weights, score="logit", bf16=True)
+    assert f(np.array([True])) == 4.61767578125
+    assert f(np.array([False])) == 3.062744140625
+    plain = gcn.ValueFunction(cg, X, weights, score="logit")
+    assert abs(plain(np.array([True])) - 4.6002116203308105) < 1e-14
+    Z = np.array([[1], [0]], dtype=np.uint64)
+    y, _, _ = cfast.gcn_values(cg, X, weights, Z, score="logit", bf16=True)
+    assert y[0] == 4.61767578125 and y[1] == 3.062744140625
