@@ -1,11 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the whole hot path on one MI355X.
 
-A step is one complete explanation (extraction -> sampling -> masked GCN inference
-of every coalition -> weighted least squares) of one target of the workload, with
-the graph, features and weights already resident in HBM. Prints ONE JSON line.
+A step is one complete pass of the hot path over one batch of synthetic input: one explanation
+(extraction -> sampling -> masked GCN inference of every coalition -> weighted least squares) of the
+workload's target, or, for the 64-target configuration, one ds_explain_batch call over all 64 targets.
+Graph, features and weights are resident in HBM before the timed region. Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4] [--others c2,c3,c5]
+
+The headline workload is the largest single-GPU configuration (config 4: one million players, 400,000
+coalitions, a 50 GB mask matrix). Short runs of the other configurations are reported under
+"other_workloads", each with its own roofline. A step of config 4 takes seconds, so the warm-up is
+cut short once it has taken `--warmup-budget-s` seconds (at least one warm-up step always runs; the
+JSON states how many ran), and the extra workloads and the CPU baseline are skipped when the process
+is about to run out of `--time-budget-s`.
 """
 import argparse
 import json
@@ -13,6 +21,7 @@ import os
 import sys
 import time
 
+T_START = time.perf_counter()
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -34,9 +43,9 @@ def inference_flops_per_coalition(ctx, cg, dims):
     gid, hop = ctx.cgraph_nodes(cg)
     es, ed = ctx.cgraph_edges(cg)
     gid, hop = gid.cpu().numpy(), hop.cpu().numpy()
-    hop_of = dict(zip(gid.tolist(), hop.tolist()))
-    hs = np.array([hop_of[int(x)] for x in es.cpu().numpy()])
-    hd = np.array([hop_of[int(x)] for x in ed.cpu().numpy()])
+    order = np.argsort(gid)
+    hs = hop[order][np.searchsorted(gid[order], es.cpu().numpy())]
+    hd = hop[order][np.searchsorted(gid[order], ed.cpu().numpy())]
     flops = 0.0
     for l in range(1, L + 1):
         radius = min(L - l, info.hops)
@@ -46,7 +55,6 @@ def inference_flops_per_coalition(ctx, cg, dims):
         if l >= 2:
             flops += 2.0 * info.ball[radius] * dims[l - 1] * dims[l]
     return flops
-
 
 
 def gat_flops_per_coalition(ctx, cg, model):
@@ -59,9 +67,10 @@ def gat_flops_per_coalition(ctx, cg, model):
     L = len(heads)
     gid, hop = ctx.cgraph_nodes(cg)
     es, ed = ctx.cgraph_edges(cg)
-    hop_of = dict(zip(gid.cpu().numpy().tolist(), hop.cpu().numpy().tolist()))
-    hs = np.array([hop_of[int(x)] for x in es.cpu().numpy()])
-    hd = np.array([hop_of[int(x)] for x in ed.cpu().numpy()])
+    gid, hop = gid.cpu().numpy(), hop.cpu().numpy()
+    order = np.argsort(gid)
+    hs = hop[order][np.searchsorted(gid[order], es.cpu().numpy())]
+    hd = hop[order][np.searchsorted(gid[order], ed.cpu().numpy())]
     flops, din = 0.0, None
     for l in range(1, L + 1):
         radius = min(L - l, info.hops)
@@ -74,108 +83,94 @@ def gat_flops_per_coalition(ctx, cg, model):
     return flops
 
 
-def cholesky_launches(n, block=64, fuse_rows=2048, super_cols=256):
-    """Kernel launches of the blocked factorisation (the library's rules): while more than `fuse_rows` rows
-    trail a super-panel of 256 columns, 4 panels + 3 narrow updates (each factorising the next diagonal block) +
-    1 diagonal block (not the very first: that one is factorised when the system matrix is built, outside the
-    timed group) + 1 wide update; afterwards one launch per full 64-column block that has columns behind it
-    (panel solve, trailing update and the next diagonal block together, plus one copy of the panel before the
-    first of them), and a panel launch for the last block; a diagonal block has a launch of its own only if
-    the launch before it did not factorise it."""
-    count, done, j0, panel_ready = 0, True, 0, False   # the first diagonal block is factorised with the system matrix
-    while j0 < n:
-        if (n + 1) - j0 - super_cols > fuse_rows and n - j0 >= super_cols + block:
-            count += (0 if j0 == 0 else 1) + 4 + 3 + 1
-            j0 += super_cols
-            done = False
-            continue
-        nb = min(block, n - j0)
-        count += 0 if done else 1
-        done = False
-        rest = n + 1 - j0 - nb
-        if n - j0 - nb > 0 and rest <= fuse_rows:
-            count += (0 if panel_ready else 1) + 1
-            panel_ready, done = True, True
-        else:
-            count += 1
-            if n - j0 - nb > 0:
-                count += 1
-        j0 += nb
-    return count
-
-
-def cpu_baseline(w, budget_s=20.0):
-    """The oracle's masked inference, as it stands, on a bounded prefix of the same
-    coalitions (rows of the same mask matrix), timed on this machine's host cores."""
+def cpu_baseline(w, gpu_iterations, budget_s=20.0):
+    """The C oracle (OpenMP, one coalition per thread, fp64, every layer on every node) as it stands, timed on
+    this machine's host cores on a bounded sample of the same workload: the first rows of the same mask matrix
+    (rows 0/1 and whole complementary pairs, which ascend by size, so the sample is also spread over the sizes).
+    Inference is timed on the sample; the solve is timed as one conjugate-gradient step on the sample's rows and
+    scaled to all rows and to the number of steps the GPU run needed (config 3/4), or as the oracle's dense
+    least-squares solve on the sample (small configs). Both are extrapolated linearly to one explanation."""
     import numpy as np
-    from oracle import compgraph, gat, gcn, sampling
+    from oracle import cfast, compgraph
+    if w.gat is not None:
+        return None
     target = w.targets[0]
     cg = compgraph.extract(w.row_ptr, w.col, target, w.num_layers)
     n = cg["num_players"]
-    if w.gat is not None:
-        f = gat.ValueFunction(cg, w.features, w.gat)
-    else:
-        f = gcn.ValueFunction(cg, w.features, w.weights, bf16=(w.transform_dtype == "bf16"))
-    probe = 64
-    Z, wt, sz = sampling.sample(n, w.n_samples, w.seed, target & 0xFFFFFFFF, pair_range=(0, probe // 2))
-    bits = sampling.unpack_rows(Z, n)
-    f.batch(bits[:8])                       # first calls pay one-off costs
-    t0, c0 = time.perf_counter(), time.process_time()
-    f.batch(bits)
-    per = (time.perf_counter() - t0) / probe
-    rows = int(max(probe, min(w.n_samples, budget_s / max(per, 1e-9))))
-    rows -= rows % 2
-    Z, wt, sz = sampling.sample(n, w.n_samples, w.seed, target & 0xFFFFFFFF, pair_range=(0, rows // 2))
-    bits = sampling.unpack_rows(Z, n)
-    t0, c0 = time.perf_counter(), time.process_time()
-    f.batch(bits)
-    wall, cpu = time.perf_counter() - t0, time.process_time() - c0
-    return {"value": rows / wall, "unit": "coalition evals/s", "cores": max(1, int(round(cpu / wall))),
-            "kind": "oracle", "sample": f"first {rows} rows (pairs 0..{rows // 2 - 1}) of the same mask matrix, "
-            f"masked inference only, {wall:.1f} s"}
+    k = w.n_samples - w.n_samples % 2
+    threads = cfast.threads()
+    K1 = k // 2
+
+    def rows_spread(count):
+        per = max(count // 16, 1)                        # pairs per block; eight blocks spread over the pair index
+        starts = np.unique(np.linspace(1, max(K1 - per, 1), 8).astype(np.int64))
+        parts = [cfast.sample(n, w.n_samples, w.seed, target & 0xFFFFFFFF, pair_range=(0, 1))]
+        parts += [cfast.sample(n, w.n_samples, w.seed, target & 0xFFFFFFFF, pair_range=(int(s), int(min(s + per, K1))))
+                  for s in starts]
+        return np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts])
+
+    probe = 2 * threads
+    Z, wt = rows_spread(probe)
+    t0 = time.perf_counter()
+    cfast.gcn_values(cg, w.features, w.weights, Z)
+    per = (time.perf_counter() - t0) / len(Z)
+    rows = int(max(probe, min(k, 0.7 * budget_s / max(per, 1e-9))))
+    Z, wt = rows_spread(rows)
+    t0 = time.perf_counter()
+    y, _, _ = cfast.gcn_values(cg, w.features, w.weights, Z)
+    t_inf = time.perf_counter() - t0
+    evals_per_s = len(Z) / t_inf
+    # one conjugate-gradient step = one product with Z and one with its transpose, whose cost is proportional to
+    # the rows walked, plus vector work that is not: the step is timed on the sample repeated to a few thousand
+    # rows and on four rows, and the difference is scaled to all k rows
+    def step_seconds(Zr, wr, yr):
+        t0 = time.perf_counter()
+        cfast.cgls(n, Zr, wr, yr, tol=0.0, max_iter=1)
+        t1 = time.perf_counter()
+        cfast.cgls(n, Zr, wr, yr, tol=0.0, max_iter=3)
+        return max((time.perf_counter() - t1) - (t1 - t0), 0.0) / 2.0
+    reps = int(max(1, min(4000 // len(Z), (1 << 30) // max(Z.nbytes, 1))))
+    Zr, wr, yr = np.tile(Z, (reps, 1)), np.tile(wt, reps), np.tile(y, reps)
+    t_fixed = step_seconds(Z[:4], wt[:4], y[:4])
+    t_rows = step_seconds(Zr, wr, yr)
+    t_step = t_fixed + max(t_rows - t_fixed, 0.0) * (k / len(Zr))
+    iters = gpu_iterations if gpu_iterations > 0 else 100.0   # direct-solver configs: a nominal 100 steps
+    solve_s = t_step * iters
+    e2e = k / evals_per_s + solve_s
+    return {"value": evals_per_s, "unit": "coalition evals/s (masked inference)", "cores": threads, "kind": "oracle",
+            "sec_per_explained_node_extrapolated": e2e,
+            "sample": f"{len(Z)} rows (rows 0/1 and eight blocks of pairs spread evenly over the {K1 - 1} sampled pairs) of the same mask "
+                      f"matrix: inference {t_inf:.1f} s measured; end to end = all {k} rows at that rate + "
+                      f"{iters:.0f} conjugate-gradient steps ({'the count of the GPU run' if gpu_iterations > 0 else 'nominal: the GPU run solved directly'}) at {t_step:.2f} s each (a step timed on "
+                      f"{len(Zr)} rows, the sample repeated, and scaled by rows)"}
 
 
 def read_traffic(kernel, workload):
-    """HBM bytes per launch of `kernel` on `workload`, from the committed rocprofv3 --pmc summary
+    """HBM bytes per launch of `kernel` on `workload`, from the committed rocprofv3 --pmc summaries
     (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a plain copy of known
     size). None if no summary covers it."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+    pdir = os.path.join(ROOT, "profiles")
     try:
-        for line in open(path):
-            parts = line.split()
-            if len(parts) >= 4 and parts[0] == "traffic_bytes" and parts[1] == workload and parts[2] == kernel:
-                return float(parts[3])
+        for fn in sorted(os.listdir(pdir)):
+            for line in open(os.path.join(pdir, fn)):
+                parts = line.split()
+                if len(parts) >= 4 and parts[0] == "traffic_bytes" and parts[1] == workload and parts[2] == kernel:
+                    return float(parts[3])
     except OSError:
         pass
     return None
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--batch", type=int, default=16,
-                    help="also time ds_explain_batch on this many targets (0 = skip); reported under \"batch\"")
-    ap.add_argument("--copy-probe-mib", type=int, default=0,
-                    help="also run a plain device copy of this many MiB first (calibrates rocprofv3 byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs one GPU's share on one GPU; --gpus must be 1 "
-              "(no collectives or sharding are part of it)", file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(key, steps, warmup, warmup_budget_s, batch, copy_probe_mib=0):
+    """Time `steps` steps of workload `key`; returns (result dict, workload, mean CGLS iterations)."""
     import numpy as np
     import torch
     from paper_2506_22668_amd import Context, Options, DS_SOLVER_CGLS, DS_SOLVER_GRAM_CHOL, DS_BF16_IN_F32_ACC, DS_F32
     from synth import make_workload
 
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(1)
-    w = make_workload(args.workload)
+    t_gen = time.perf_counter()
+    w = make_workload(key)
+    t_gen = time.perf_counter() - t_gen
     ctx = Context("cuda:0")
     ctx.set_graph(w.row_ptr, w.col)
     ctx.set_features(w.features)
@@ -186,109 +181,170 @@ def main():
     opts = Options(solver=DS_SOLVER_CGLS if w.solver == "cgls" else DS_SOLVER_GRAM_CHOL, tol=w.tol,
                    max_iter=w.max_iter)
     targets = w.targets
+    many = len(targets) > 1                      # the 64-target configuration: a step is one batch call
     cg = ctx.extract(targets[0], opts)
-    info = ctx.cgraph_info(cg)
-    capacity = max(ctx.cgraph_info(c).num_players for c in [cg])
     eval_flops = (gat_flops_per_coalition(ctx, cg, w.gat) if w.gat is not None
                   else inference_flops_per_coalition(ctx, cg, list(w.dims)))
+    capacity = ctx.cgraph_info(cg).num_players
     ctx.cgraph_free(cg)
-    if len(targets) > 1:
-        caps = []
-        for t in targets:
-            c = ctx.extract(t, opts)
-            caps.append(ctx.cgraph_info(c).num_players)
-            ctx.cgraph_free(c)
-        capacity = max(caps)
+    if many:
+        _, M, off, _, _, _, _ = ctx.explain_batch(targets, w.n_samples, w.seed, opts, capacity=0)
+        capacity = off[-1]
 
-    def step(i):
-        return ctx.explain(targets[i % len(targets)], w.n_samples, w.seed, opts, capacity=capacity,
-                           want_edges=False)
+    def step():
+        if many:
+            return ctx.explain_batch(targets, w.n_samples, w.seed, opts, capacity=capacity)[5]
+        return [ctx.explain(targets[0], w.n_samples, w.seed, opts, capacity=capacity, want_edges=False)[3]]
 
-    if args.copy_probe_mib > 0:
-        ctx.copy_probe(args.copy_probe_mib << 20)
-    for i in range(args.warmup):
-        step(i)
+    if copy_probe_mib > 0:
+        ctx.copy_probe(copy_probe_mib << 20)
+    warm_done, t0 = 0, time.perf_counter()
+    for i in range(max(warmup, 1)):
+        step()
+        warm_done += 1
+        if time.perf_counter() - t0 > warmup_budget_s:
+            break
     torch.cuda.synchronize()
     reports = []
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        reports.append(step(i)[3])
+    for i in range(steps):
+        reports.extend(step())
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    k = sum(r.num_rows for r in reports)
-    ms_per_step = 1e3 * elapsed / args.steps
+    k_total = sum(r.num_rows for r in reports)
+    per_step = len(reports) // steps
     mean = lambda name: float(np.mean([getattr(r, name) for r in reports]))
-    rep = reports[0]
-    n, V, W64 = rep.num_players, rep.num_nodes, (rep.num_players + 63) // 64
-    rows = rep.num_rows
+    rep = max(reports[:per_step], key=lambda r: r.num_players)
+    n, V, W64, rows = rep.num_players, rep.num_nodes, (rep.num_players + 63) // 64, rep.num_rows
     KW = (rows + 63) // 64
-    # per-kernel durations (HIP events on the library's stream, recorded inside the timed region)
+    iters = mean("cgls_iterations")
+    # per-kernel-group durations: HIP events recorded by the library on its own stream inside the timed region
+    # (means over all explanations of the run); algorithmic work per explanation from the library's report
+    stream_eval = n > 12288 and w.gat is None          # the mask-streaming inference kernel
     kernels = {
-        # small graphs (one coalition per lane, everything but the mask on chip): arithmetic-bound;
-        # large ones stream the mask matrix: compulsory HBM bytes per coalition = its mask row in, one float out
-        ("masked_gat_eval" if w.gat is not None else "masked_gcn_eval"): ({"ms": mean("ms_k_eval"), "bound": "alu", "alg": rows * eval_flops / 1e12,
-                             "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s"} if (n <= 2048 or w.gat is not None) else
-                            {"ms": mean("ms_k_eval"), "bound": "hbm", "alg": rows * (W64 * 8 + 4) / 1e9,
-                             "peak": HBM_PEAK_GBS, "unit": "GB/s"}),
+        ("masked_gat_eval" if w.gat is not None else "masked_gcn_eval"):
+            ({"ms": mean("ms_k_eval"), "bound": "hbm", "alg": mean("bytes_eval") / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+             if stream_eval else
+             {"ms": mean("ms_k_eval"), "bound": "alu", "alg": rows * eval_flops / 1e12, "peak": FP32_PEAK_TFLOPS,
+              "unit": "TFLOP/s"}),
         "gram_popcount": {"ms": mean("ms_k_gram"), "bound": "alu",
                           # lower triangle of n^2 column pairs x KW 64-row words x (AND, popcount, weighted add)
                           "alg": 3.0 * (n * (n + 1) / 2) * KW / 1e12, "peak": ALU_PEAK_TOPS, "unit": "Top/s"},
-        # the factorisation is a group of launches (per 64-column block: panel, then the trailing update that also
-        # factorises the next diagonal block; the first diagonal block has a launch of its own)
-        "cholesky_fp64": {"ms": mean("ms_k_chol"), "bound": "alu", "launches": cholesky_launches(n),
-                          "alg": (n ** 3 / 3.0) / 1e12, "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s"},
-        "cgls_loop": {"ms": mean("ms_k_cgls"), "bound": "hbm",
-                      # per iteration: the small member of every pair once, plus its transposed copy once
-                      "alg": mean("cgls_iterations") * 2 * (rows // 2) * W64 * 8 / 1e9, "peak": HBM_PEAK_GBS,
-                      "unit": "GB/s"},
+        "cholesky_fp64": {"ms": mean("ms_k_chol"), "bound": "mfma", "alg": (n ** 3 / 3.0) / 1e12,
+                          "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s"},
+        # all iterations of the conjugate-gradient loop; per iteration the small member of every pair once for
+        # Z u and once for Z^T r
+        "cgls_loop": {"ms": mean("ms_k_cgls"), "bound": "hbm", "alg": mean("bytes_solve") / 1e9 if iters > 0 else 0.0,
+                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "launches": max(int(round(iters)), 1)},
     }
     for v in kernels.values():
         v["achieved"] = (v["alg"] / (v["ms"] / 1e3)) if v["ms"] > 0 else 0.0
         v["frac"] = v["achieved"] / v["peak"]
     dom_name = max(kernels, key=lambda name: kernels[name]["ms"])
     dom = kernels[dom_name]
-    traffic = read_traffic(dom_name, w.name)
+    launches = dom.get("launches", 1)
     out = {
-        "metric": ("masked-GAT" if w.gat is not None else "masked-GCN") +
-                  " coalition evals/sec; end-to-end seconds per explained node",
-        "value": k / elapsed,
-        "unit": "coalition evals/s (end to end: extraction + sampling + inference + solve)",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if w.transform_dtype != "bf16" else "bf16 transforms, f32 accumulate",
-        "data": "synthetic",
+        "value": k_total / elapsed,
+        "ms_per_step": 1e3 * elapsed / steps,
+        "steps": steps, "warmup": warm_done,
+        "dtype": "f32" if w.transform_dtype != "bf16" else "bf16 per-coalition transforms, f32 accumulate",
         "config": {"workload": w.name, "graph_nodes": w.num_nodes, "players": int(n), "cg_nodes": int(V),
-                   "coalitions": int(rows), "solver": w.solver,
+                   "coalitions": int(rows), "pairs_sampled": int(rep.num_pairs), "solver": w.solver,
                    **({"gat_heads": w.gat["heads"], "gat_head_widths": w.gat["widths"]} if w.gat is not None
                       else {"gcn_dims": list(w.dims)}),
-                   "targets_cycled": len(targets)},
-        "sec_per_explained_node": elapsed / args.steps,
+                   "targets_per_step": per_step},
+        "sec_per_explained_node": elapsed / len(reports),
         "inference_stage_evals_per_sec": rows / (mean("ms_eval") / 1e3) if mean("ms_eval") > 0 else None,
         "stage_ms": {s: mean("ms_" + s) for s in ("extract", "sample", "eval", "solve", "total")},
-        "cgls_iterations": mean("cgls_iterations"),
+        "algorithmic_bytes": {s: mean("bytes_" + s) for s in ("sample", "eval", "solve")},
+        "cgls_iterations": iters,
         "roofline": {"kernel": dom_name, "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                     "unit": dom["unit"], "frac": dom["frac"], "traffic": traffic,
-                     "avg_launch_ms": dom["ms"], "launches": dom.get("launches", 1)},
+                     "unit": dom["unit"], "frac": dom["frac"], "traffic": read_traffic(dom_name, w.name),
+                     "avg_launch_ms": dom["ms"] / launches, "launches": launches},
         "kernels": {name: {kk: v[kk] for kk in ("ms", "bound", "achieved", "peak", "unit", "frac")}
                     for name, v in kernels.items()},
+        "generation_s": t_gen,
     }
-    # several explanations in flight (ds_explain_batch runs up to eight at a time on worker contexts)
-    if args.batch > 0:
-        tg = [targets[i % len(targets)] for i in range(args.batch)]
-        ctx.explain_batch(tg, w.n_samples, w.seed, opts, capacity=capacity * args.batch)   # warm-up
+    if many:
+        out["games_players_min_max"] = [int(min(r.num_players for r in reports)), int(max(r.num_players for r in reports))]
+    # several explanations of one target in flight (ds_explain_batch keeps up to eight on worker contexts)
+    if batch > 0 and not many:
+        tg = [targets[0]] * batch
+        ctx.explain_batch(tg, w.n_samples, w.seed, opts, capacity=capacity * batch)   # warm-up
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         reps_b = 3
         for _ in range(reps_b):
-            ctx.explain_batch(tg, w.n_samples, w.seed, opts, capacity=capacity * args.batch)
+            ctx.explain_batch(tg, w.n_samples, w.seed, opts, capacity=capacity * batch)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        out["batch"] = {"targets_per_call": args.batch, "sec_per_explained_node": dt / (reps_b * args.batch),
-                        "coalition_evals_per_sec": reps_b * args.batch * rows / dt}
+        out["batch"] = {"targets_per_call": batch, "sec_per_explained_node": dt / (reps_b * batch),
+                        "coalition_evals_per_sec": reps_b * batch * rows / dt}
     ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+    return out, w, iters
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c4")
+    ap.add_argument("--others", default="c2,c3,c5",
+                    help="comma-separated workloads timed briefly after the headline one (\"\" = none)")
+    ap.add_argument("--other-steps", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=16,
+                    help="small workloads: also time ds_explain_batch on this many copies of the target (0 = skip)")
+    ap.add_argument("--warmup-budget-s", type=float, default=12.0)
+    ap.add_argument("--time-budget-s", type=float, default=480.0,
+                    help="wall-clock budget of the process: optional parts are skipped when it is nearly spent")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB first (calibrates rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs one GPU's share on one GPU; --gpus must be 1 "
+              "(no collectives or sharding are part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    small = args.workload in ("c1", "c2", "c2_small", "gat_c2", "gat_small", "c5_small", "c3_small", "c4_small")
+    head, w, iters = run_workload(args.workload, args.steps, args.warmup, args.warmup_budget_s,
+                                  args.batch if small else 0, args.copy_probe_mib)
+    out = {
+        "metric": ("masked-GAT" if w.gat is not None else "masked-GCN") +
+                  " coalition evals/sec; end-to-end seconds per explained node",
+        "value": head.pop("value"),
+        "unit": "coalition evals/s (end to end: extraction + sampling + inference + solve)",
+        "n_gpus": 1, "steps": head.pop("steps"), "warmup": head.pop("warmup"), "warmup_requested": args.warmup,
+        "ms_per_step": head.pop("ms_per_step"),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head.pop("dtype"), "data": "synthetic",
+    }
+    out.update(head)
+    left = lambda: args.time_budget_s - (time.perf_counter() - T_START)
+    others = {}
+    # rough cost of a short run of each (generation + warm-up + steps), seconds
+    cost = {"c2": 15, "c3": 50, "c5": 25, "c4": 80, "gat_c2": 15, "gat_rmat": 20}
+    for key in [s for s in args.others.split(",") if s and s != args.workload]:
+        need = cost.get(key, 30) + (0 if args.no_cpu_baseline else 35)
+        if left() < need:
+            others[key] = {"skipped": f"{left():.0f} s of the process's time budget left, about {need} s needed"}
+            continue
+        r, _, _ = run_workload(key, args.other_steps, 1, 5.0, args.batch if key in ("c2", "gat_c2") else 0)
+        others[key] = r
+    if others:
+        out["other_workloads"] = others
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w)
+        budget = min(20.0, max(5.0, left() - 15.0))
+        out["cpu_baseline"] = cpu_baseline(w, iters, budget)
+    out["wall_s"] = time.perf_counter() - T_START
     print(json.dumps(out))
 
 

@@ -105,6 +105,16 @@ typedef struct ds_report {
    * the masked-inference kernel over all k rows, the popcount Gram kernel, the
    * Cholesky factorisation launches, and the CGLS loop (all iterations). */
   float ms_k_eval, ms_k_gram, ms_k_chol, ms_k_cgls;
+  int64_t num_pairs;      /* K: sampled complementary pairs (rows 2..k-1 are K pairs; 2^(n-1) - 1 when enumerated) */
+  /* Algorithmic bytes of each stage: what the step has to move whatever the kernel does, the basis of the
+   * roofline fractions (W = ceil(n/64) words per mask row).
+   *   sample: k*W*8 mask bytes + k*8 bytes of weights and sizes written;
+   *   eval:   one member of every complementary pair read (the other is its complement and needs no second
+   *           look), (k/2)*W*8, plus k*4 bytes of outputs;
+   *   solve:  CGLS: per iteration the small member of every pair once for Z u and once for Z^T r,
+   *           iterations * 2 * (k/2)*W*8; Gram + Cholesky: (k/2)*W*8 mask bytes read, n*n*4 bytes of Gram
+   *           matrix written. */
+  double bytes_sample, bytes_eval, bytes_solve;
 } ds_report;
 
 typedef struct ds_cgraph_info {
@@ -126,6 +136,19 @@ int ds_create(ds_ctx** out, int device, void* stream);
 int ds_destroy(ds_ctx* ctx);
 /* Message of the last failing call on this context (static storage, [host]). */
 const char* ds_last_error(const ds_ctx* ctx);
+
+/* Tuning of a context (none of it changes a result). Zero in a field keeps the built-in value, which is the
+ * measured optimum; pass NULL to restore all of them. Worker contexts of ds_explain_batch inherit the values. */
+typedef struct ds_tuning {
+  int32_t batch_workers;      /* explanations in flight in ds_explain_batch, 1..16 (default 8) */
+  int32_t gram_sparse_div;    /* Gram: rows with at most n / div set columns are accumulated row-wise (default 12) */
+  float gram_dense_fraction;  /* Gram: density from which a 64-row word with mixed weights goes to the matrix
+                                 cores (default 0.08) */
+  int32_t sampler_window;     /* sampler: capacity (entries) of the list of keys the first pass keeps around the
+                                 expected threshold; -1 keeps none. A small list forces the slower four-pass
+                                 selection (a test hook: the masks are the same either way) */
+} ds_tuning;
+int ds_set_tuning(ds_ctx* ctx, const ds_tuning* tuning /* [host] or NULL */);
 
 /* Graph G(V, E) as a CSR adjacency (paper, "Background & Related Work"): row i
  * lists the in-neighbours j of node i (messages flow j -> i), strictly ascending,
@@ -234,9 +257,7 @@ int ds_plan_tables(int64_t n, int64_t n_samples, int64_t* b, float* wtab);
  *   Z: uint64[k*W] out; w: float[k] out (per-row regression weight);
  *   sz: int32[k] out (coalition sizes); k_out [host]. tag: stream id (the
  *   explanation uses the low 32 bits of the target's global id).
- * Diagnostic: the environment variable DISTSHAP_SAMPLER_WINDOW=<entries> shrinks the list of keys the
- * first pass keeps around the expected threshold (0 = keep none), which forces the slower four-pass
- * selection; the masks are the same either way. */
+ */
 int ds_sample(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, uint64_t* Z,
               float* w, int32_t* sz, int64_t* k_out);
 /* Only pairs pair_begin <= r < pair_end: writes rows 2*pair_begin .. 2*pair_end-1

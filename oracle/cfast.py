@@ -33,6 +33,11 @@ def lib():
     return _lib
 
 
+def threads():
+    """OpenMP threads the C oracle's parallel loops run on."""
+    return int(lib().oc_threads())
+
+
 def _p(a):
     return a.ctypes.data_as(C.c_void_p)
 

@@ -238,6 +238,9 @@ int oc_gcn_values(int32_t V, int64_t n, const int32_t* psrc, const int32_t* pdst
   return 0;
 }
 
+/* threads the parallel loops of this file use (reported beside timings of the oracle) */
+int oc_threads(void) { return omp_get_max_threads(); }
+
 /* ------------------------------------------------------------------ least squares */
 static void row_targets(int64_t n, int64_t k, const uint64_t* Z, const float* w, const double* y, double* t, double* sq) {
   const int64_t W64 = (n + 63) / 64;

@@ -15,7 +15,7 @@ DS_SOLVER_AUTO, DS_SOLVER_GRAM_CHOL, DS_SOLVER_CGLS = 0, 1, 2
 DS_WEIGHT_CLASS_MASS, DS_WEIGHT_UNIFORM = 0, 1
 
 EXPORTED_SYMBOLS = [
-    "ds_create", "ds_destroy", "ds_last_error", "ds_set_graph", "ds_set_features", "ds_set_gcn", "ds_set_gat",
+    "ds_create", "ds_destroy", "ds_last_error", "ds_set_tuning", "ds_set_graph", "ds_set_features", "ds_set_gcn", "ds_set_gat",
     "ds_explain", "ds_explain_batch", "ds_extract", "ds_cgraph_get_info", "ds_cgraph_edges",
     "ds_cgraph_nodes", "ds_cgraph_first_transform", "ds_cgraph_free", "ds_sample_plan", "ds_sample",
     "ds_plan_tables", "ds_sample_range", "ds_eval", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
@@ -28,6 +28,11 @@ class Options(C.Structure):
                 ("batch_rows", C.c_int32), ("paired", C.c_int32), ("weighting", C.c_int32)]
 
 
+class Tuning(C.Structure):
+    _fields_ = [("batch_workers", C.c_int32), ("gram_sparse_div", C.c_int32), ("gram_dense_fraction", C.c_float),
+                ("sampler_window", C.c_int32)]
+
+
 class Report(C.Structure):
     _fields_ = [("num_players", C.c_int64), ("num_nodes", C.c_int64), ("num_entries", C.c_int64),
                 ("num_rows", C.c_int64), ("enumerated", C.c_int32), ("pred_class", C.c_int32),
@@ -36,7 +41,9 @@ class Report(C.Structure):
                 ("ms_extract", C.c_float), ("ms_sample", C.c_float), ("ms_eval", C.c_float),
                 ("ms_solve", C.c_float), ("ms_total", C.c_float),
                 ("ms_k_eval", C.c_float), ("ms_k_gram", C.c_float), ("ms_k_chol", C.c_float),
-                ("ms_k_cgls", C.c_float)]
+                ("ms_k_cgls", C.c_float),
+                ("num_pairs", C.c_int64), ("bytes_sample", C.c_double), ("bytes_eval", C.c_double),
+                ("bytes_solve", C.c_double)]
 
     def as_dict(self):
         return {name: getattr(self, name) for name, _ in self._fields_}
@@ -77,6 +84,7 @@ def load_library():
     sigs = {
         "ds_create": [C.POINTER(p), C.c_int, p],
         "ds_destroy": [p],
+        "ds_set_tuning": [p, C.POINTER(Tuning)],
         "ds_set_graph": [p, i64, p, p],
         "ds_set_features": [p, p, i32, i32],
         "ds_set_gcn": [p, i32, C.POINTER(i32), C.POINTER(p), C.POINTER(p), i32],
@@ -176,6 +184,9 @@ class Context:
     def _sync_inputs(self):
         # inputs were produced on torch's current stream; the library runs on its own
         self.torch.cuda.current_stream(self.device).synchronize()
+
+    def set_tuning(self, tuning=None):
+        self._check(self.lib.ds_set_tuning(self.h, C.byref(tuning) if tuning is not None else None))
 
     # -- registration --------------------------------------------------------
     def set_graph(self, row_ptr, col):

@@ -100,6 +100,7 @@ int ds_create(ds_ctx** out, int device, void* stream) {
     if (hipEventCreate(&ctx->kev[i]) != hipSuccess) { delete ctx; return DS_EDEVICE; }
   for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
   ctx->owns_stream = false;
+  memset(&ctx->tuning, 0, sizeof(ctx->tuning));
   ctx->cg_spare = nullptr;
   ctx->cg_spare_bytes = 0;
   ctx->h_stage = nullptr;
@@ -163,6 +164,19 @@ int ds_set_graph(ds_ctx* ctx, int64_t num_nodes, const int64_t* row_ptr, const i
     ctx->N = 0;
   }
   return rc;
+}
+
+int ds_set_tuning(ds_ctx* ctx, const ds_tuning* tuning) {
+  if (!ctx) return DS_EINVAL;
+  if (!tuning) {
+    memset(&ctx->tuning, 0, sizeof(ctx->tuning));
+    return DS_OK;
+  }
+  if (tuning->batch_workers < 0 || tuning->batch_workers > 16 || tuning->gram_sparse_div < 0 ||
+      !(tuning->gram_dense_fraction >= 0.f && tuning->gram_dense_fraction <= 1.f) || tuning->sampler_window < -1)
+    return ds_fail(ctx, DS_EINVAL, "tuning value out of range");
+  ctx->tuning = *tuning;
+  return DS_OK;
 }
 
 int ds_set_features(ds_ctx* ctx, const void* X, int32_t d0, int32_t dtype) {
@@ -611,19 +625,22 @@ static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t
   hipEventElapsedTime(&rep.ms_solve, ctx->ev[3], ctx->ev[4]);
   hipEventElapsedTime(&rep.ms_total, ctx->ev[0], ctx->ev[4]);
   kernel_times(ctx, &rep);
+  rep.num_pairs = k / 2 - 1;
+  {
+    const double row_bytes = (double)W * 8.0, half = (double)(k / 2);
+    rep.bytes_sample = (double)k * row_bytes + (double)k * 8.0;
+    rep.bytes_eval = half * row_bytes + (double)k * 4.0;
+    rep.bytes_solve = rep.solver_used == DS_SOLVER_CGLS ? (double)rep.cgls_iterations * 2.0 * half * row_bytes
+                                                        : half * row_bytes + (double)n * (double)n * 4.0;
+  }
   if (report) *report = rep;
   return rc;
 }
 
 // worker contexts of a batch: same graph, features and model as the parent, own stream and workspace
-// explanations in flight in ds_explain_batch (tuning knob DISTSHAP_BATCH_WORKERS, 1..16)
-static int batch_workers() {
-  static const int v = [] {
-    const char* e = getenv("DISTSHAP_BATCH_WORKERS");
-    const int x = e ? atoi(e) : 8;
-    return x < 1 ? 1 : (x > 16 ? 16 : x);
-  }();
-  return v;
+static int batch_workers(const ds_ctx* ctx) {
+  const int x = ctx->tuning.batch_workers > 0 ? ctx->tuning.batch_workers : 8;
+  return x > 16 ? 16 : x;
 }
 
 static int ensure_workers(ds_ctx* ctx, int count) {
@@ -648,6 +665,7 @@ static int ensure_workers(ds_ctx* ctx, int count) {
     w->model_version = ctx->model_version;
     w->model_kind = ctx->model_kind;
     w->gat = ctx->gat;
+    w->tuning = ctx->tuning;
   }
   return DS_OK;
 }
@@ -668,7 +686,7 @@ int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, i
   // publish right after their own extraction, so the wait is short and the lowest unpublished target never waits)
   // and goes on with the graph it already holds.
   if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "no model is set (ds_set_gcn / ds_set_gat)");
-  int nw = num_targets < batch_workers() ? num_targets : batch_workers();
+  int nw = num_targets < batch_workers(ctx) ? num_targets : batch_workers(ctx);
   DS_TRY(ensure_workers(ctx, nw));
   DS_HIP(ctx, hipStreamSynchronize(ctx->stream));  // whatever the caller queued before is visible to the workers
   const ds_options o = default_options(opts);

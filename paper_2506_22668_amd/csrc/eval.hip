@@ -865,7 +865,9 @@ size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
   const size_t W = (cg->info.num_players + 63) / 64;
   const BatchedLayout bl = make_batched_layout(ctx, cg, k);
   const size_t batched = bl.use ? ds_align((size_t)bl.stride * 4 * bl.grid) : 0;
-  return ds_align((size_t)lay.gws_floats * 4 * grid) + batched + ds_align(W * 8 + 8) + ds_align(ctx->dims[ctx->L] * 4 + 8) + 1024;
+  // the last three terms: what ds_prepare_model allocates (full mask row, logits, one workgroup's scratch)
+  return ds_align((size_t)lay.gws_floats * 4 * grid) + batched + ds_align(W * 8 + 8) + ds_align(ctx->dims[ctx->L] * 4 + 8) +
+         ds_align((size_t)lay.gws_floats * 4) + 1024;
 }
 
 // Shared first transform and the class predicted on the full computational graph;

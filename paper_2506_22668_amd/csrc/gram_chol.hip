@@ -475,13 +475,19 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(const double* G, const 
 // is what the factorisation reads), row n = the right-hand side c - mean(c). Factorising with row n
 // carried along as an ordinary sub-diagonal row leaves L^-1 rhs in it (the forward solve comes for free).
 // gamma = trace(PGP)/(n-1) keeps the added direction at the scale of the other eigenvalues.
-__global__ void build_matrix_kernel(const double* G, const double* m, const double* stats, int64_t n, int64_t ld, double* M) {
+// pivot_floor: the smallest pivot the factorisation accepts, relative to the mean diagonal entry of A: a pivot
+// that exact arithmetic would make zero (a direction the sampled rows do not determine) comes out of fp64
+// as about n * 2^-52 times the scale, with either sign; 256 n 2^-52 sits well above that and far below the
+// pivots of a determined system.
+__global__ void build_matrix_kernel(const double* G, const double* m, const double* stats, int64_t n, int64_t ld, double* M,
+                                    double* pivot_floor) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n * n) return;
   const double mu = stats[0];
   const double tr = stats[1] - (double)n * mu;
   double gamma = tr / (double)(n > 1 ? n - 1 : 1);
   if (!(gamma > 0.0)) gamma = 1.0;
+  if (idx == 0) *pivot_floor = 256.0 * (double)n * 0x1p-52 * ((tr > 0.0 ? tr : 0.0) + gamma) / (double)n;
   const int64_t a = idx / n, b = idx - a * n;
   M[a * ld + b] = G[idx] - m[a] - m[b] + mu + gamma / (double)n;
 }
@@ -737,7 +743,7 @@ __device__ __forceinline__ void sub_block_store(double (*T)[NB + 1], int r0, int
 //      (4 tasks, one a wave; this is where the square roots are taken and the pivots are checked),
 // where Y follows the forward substitution L Y = I block row by block row. A and C are 16 x 16 x 16 products on the
 // fp64 matrix cores; results go to global memory as they appear. A pivot that is not positive (or not a number, or
-// outside 1e-30 .. 1e30) raises the flag; nothing is repaired, the caller discards a flagged factorisation.
+// below the relative floor stored next to the flag, or above 1e30) raises the flag; nothing is repaired, the caller discards a flagged factorisation.
 // `pend`: optional 64 x 64 tile (LDS, pitch NB+1; may be the tile Y) holding the rows of this block in the panel
 // just finished; its outer product is the one trailing update the block has not received yet and is subtracted
 // first.
@@ -835,7 +841,7 @@ __device__ __forceinline__ void chol_diag_body(double* M, int64_t ld, int64_t j0
           linv_out[(o + 4 * r + lk) * NB + j * kSub + l16] = yv;
         }
       } else {
-        if (!(d > 1e-30 && d < 1e30)) atomicExch(flag, 1);
+        if (!(d > *(const double*)(flag + 2) && d < 1e30)) atomicExch(flag, 1);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int m = 4 * r + lk;  // row of the sub-block, column l16
@@ -1197,23 +1203,11 @@ __global__ void finish_phi_kernel(const double* psi, const float* y01, int64_t n
   phi[j] = (float)(psi[j] + delta / (double)n);
 }
 
-// tuning knob: DISTSHAP_GRAM_DENSE overrides the density from which mixed-weight words use the matrix cores
-inline float dense_fraction() {
-  static const float v = [] {
-    const char* e = getenv("DISTSHAP_GRAM_DENSE");
-    return e ? (float)atof(e) : kDenseFraction;
-  }();
-  return v;
+inline float dense_fraction(const ds_ctx* ctx) {
+  return ctx->tuning.gram_dense_fraction > 0.f ? ctx->tuning.gram_dense_fraction : kDenseFraction;
 }
-
-// tuning knob: DISTSHAP_GRAM_SPARSE_DIV overrides the divisor d of the rule "at most n / d columns set = sparse row"
-inline int sparse_divisor() {
-  static const int v = [] {
-    const char* e = getenv("DISTSHAP_GRAM_SPARSE_DIV");
-    const int x = e ? atoi(e) : kSparseDivisor;
-    return x >= 1 ? x : kSparseDivisor;
-  }();
-  return v;
+inline int sparse_divisor(const ds_ctx* ctx) {
+  return ctx->tuning.gram_sparse_div >= 1 ? ctx->tuning.gram_sparse_div : kSparseDivisor;
 }
 
 inline unsigned nblocks(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
@@ -1305,10 +1299,10 @@ int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const fl
     int64_t blocks = (R * 64 + kThreads - 1) / kThreads;
     if (blocks > (int64_t)ctx->num_cus * 16) blocks = (int64_t)ctx->num_cus * 16;
     hipLaunchKernelGGL(gram_row_class_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, Z, R, W, n, row_step, gw,
-                       gscale, sparse_divisor(), Zc, (unsigned long long*)keep, (unsigned long long*)wq);
+                       gscale, sparse_divisor(ctx), Zc, (unsigned long long*)keep, (unsigned long long*)wq);
   }
   hipLaunchKernelGGL(word_weights_kernel, dim3(nblocks(RW, 256)), dim3(256), 0, st, gw, R, RW, Z, W, n, row_step,
-                     dense_fraction(), keep, wu, uni);
+                     dense_fraction(ctx), keep, wu, uni);
   const unsigned tiles = nblocks(n, kTile);
   DS_TRY(ds_kernel_mark(ctx, 1, 0));
   hipLaunchKernelGGL(gram_rows_kernel, dim3(tiles, tiles), dim3(kThreads), 0, st, Zc, (const unsigned long long*)wq, R, n,
@@ -1319,7 +1313,8 @@ int ds_gram_begin(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const fl
   const unsigned wblocks = (unsigned)(n < (int64_t)ctx->num_cus * 16 ? n : (int64_t)ctx->num_cus * 16);
   hipLaunchKernelGGL(sum_slices_row_mean_kernel, dim3(wblocks), dim3(kThreads), 0, st, Gp, n, d.slices, m);
   hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(kThreads), 0, st, Gp, m, n, stats);
-  hipLaunchKernelGGL(build_matrix_kernel, dim3(nblocks(n * n, 256)), dim3(256), 0, st, Gp, m, stats, n, ld, gs->M);
+  hipLaunchKernelGGL(build_matrix_kernel, dim3(nblocks(n * n, 256)), dim3(256), 0, st, Gp, m, stats, n, ld, gs->M,
+                     (double*)(gs->flag + 2));
   // the first diagonal block does not involve the right-hand side either: factorised here, off the path that waits
   // for the model outputs
   DS_HIP(ctx, hipMemsetAsync(gs->flag, 0, sizeof(int), st));

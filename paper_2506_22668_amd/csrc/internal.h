@@ -95,6 +95,7 @@ struct ds_ctx {
   // ds_explain_batch runs several targets at once on worker contexts (own stream, own workspace)
   std::vector<ds_ctx*> workers;
   bool owns_stream;
+  ds_tuning tuning;  // zero fields = built-in values
 };
 
 int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...);

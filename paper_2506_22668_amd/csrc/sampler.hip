@@ -367,11 +367,10 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
     if (cap < 256.0) cap = 256.0;
     if (cap > 4096.0) cap = 4096.0;  // the widest classes of huge games overflow it and take the four-pass route
     a.window_cap = (uint32_t)cap;
-    // diagnostic knob: a smaller list forces the four-pass route (the result must not change)
-    if (const char* env = getenv("DISTSHAP_SAMPLER_WINDOW")) {
-      const long v = strtol(env, nullptr, 10);
-      if (v >= 0 && v < (long)a.window_cap) a.window_cap = (uint32_t)v;
-    }
+    // test hook: a smaller list forces the four-pass route (the result must not change)
+    const int32_t tw = ctx->tuning.sampler_window;
+    if (tw == -1) a.window_cap = 0;
+    else if (tw > 0 && (uint32_t)tw < a.window_cap) a.window_cap = (uint32_t)tw;
   }
   const int64_t pairs = pair_end - pair_begin;
   if (plan.enumerate) {

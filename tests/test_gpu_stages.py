@@ -37,16 +37,20 @@ def test_sampler_bit_exact(ctx_tiny, n, ns, seed, tag):
     assert np.array_equal(sz.cpu().numpy(), szo)
 
 
-@pytest.mark.parametrize("window", ["0", "3"])
-def test_sampler_four_pass_route_gives_the_same_masks(ctx_tiny, window, monkeypatch):
+@pytest.mark.parametrize("window", [-1, 3])
+def test_sampler_four_pass_route_gives_the_same_masks(ctx_tiny, window):
+    from paper_2506_22668_amd import Tuning
     ctx, _ = ctx_tiny
     say(f"sampler forced fallback window={window}")
-    monkeypatch.setenv("DISTSHAP_SAMPLER_WINDOW", window)
-    for n, ns in [(300, 2000), (5000, 600)]:
-        Z, w, sz = ctx.sample(n, ns, 31, 8)
-        Zo, wo, szo = sampling.sample(n, ns, 31, 8)
-        assert np.array_equal(to_u64(Z), Zo)
-        assert np.array_equal(sz.cpu().numpy(), szo)
+    ctx.set_tuning(Tuning(sampler_window=window))
+    try:
+        for n, ns in [(300, 2000), (5000, 600)]:
+            Z, w, sz = ctx.sample(n, ns, 31, 8)
+            Zo, wo, szo = sampling.sample(n, ns, 31, 8)
+            assert np.array_equal(to_u64(Z), Zo)
+            assert np.array_equal(sz.cpu().numpy(), szo)
+    finally:
+        ctx.set_tuning(None)
 
 
 def test_sampler_pair_ranges_equal_the_full_run(ctx_tiny):
@@ -339,3 +343,28 @@ def test_rank_deficient_gram_is_reported_and_auto_falls_back(ctx_tiny):
     assert rep.solver_used == DS_SOLVER_CGLS
     ref = solve.solve_lstsq(bits, w, y)
     assert np.abs(phi.cpu().numpy() - ref).max() <= 1e-4 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("n,ns", [(150, 1000), (400, 3000)])
+def test_gram_with_one_lost_direction_is_reported_and_auto_falls_back(ctx_tiny, n, ns):
+    """Nullity one: two players that appear together in every sampled row (column n-1 is made a copy of column
+    n-2). Exact arithmetic gives one zero pivot; in fp64 it comes out as round-off of either sign, which only a
+    relative test catches. The direct solver must report the singular system, AUTO must return the minimum-norm
+    solution (the oracle's projected least-squares solution)."""
+    from paper_2506_22668_amd import Options, DistShapError, DS_SOLVER_GRAM_CHOL, DS_SOLVER_CGLS, DS_ESINGULAR
+    ctx, _ = ctx_tiny
+    say(f"gram nullity 1 n={n}")
+    Z, w, bits, y = _solve_inputs(n, ns, 300 + n)
+    bits = bits.copy()
+    bits[2:, n - 1] = bits[2:, n - 2]
+    Z = sampling.pack_rows(bits)
+    args = (n, torch.from_numpy(Z.view(np.int64)).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(y).cuda())
+    with pytest.raises(DistShapError) as e:
+        ctx.solve(*args, Options(solver=DS_SOLVER_GRAM_CHOL))
+    assert e.value.code == DS_ESINGULAR
+    phi, rep, rc = ctx.solve(*args, Options(tol=1e-11))
+    assert rep.solver_used == DS_SOLVER_CGLS
+    ref = solve.solve_lstsq(bits, w, y)
+    got = phi.cpu().numpy().astype(np.float64)
+    assert abs(ref[n - 1] - ref[n - 2]) <= 1e-9            # minimum norm splits the pair's share evenly
+    assert np.abs(got - ref).max() <= 1e-4 * np.abs(ref).max()
