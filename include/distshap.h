@@ -272,6 +272,19 @@ int ds_sample_range(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, ui
 int ds_eval(ds_ctx* ctx, const ds_cgraph* cg, const uint64_t* Z, int64_t k, int32_t score, float* y,
             int32_t* pred_class_out);
 
+/* ds_eval for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc. Same kernels and results as ds_eval, but every byte of scratch memory comes
+ * from an array of 32 MiB that is part of the library's device image (each GPU the library runs on holds its own
+ * copy until the process ends; its address is looked up once per device in ds_create). The call allocates and
+ * frees nothing and does not synchronise: work is queued on the context's stream and y is valid once that
+ * stream has reached it. GCN only. When the scratch of one workgroup does not fit the array the launch uses
+ * fewer workgroups; when not even one fits (or the mask row itself is too wide: beyond about 2.6e8 players)
+ * DS_ECAPACITY is returned and nothing runs. All calls on one GPU share the one array, from any context or
+ * thread: calls that overlap in time on a GPU race on it, so the caller serialises them (one stream, or events).
+ * Nothing in the array has to start at zero. The class whose score is returned is the one predicted on the
+ * full graph, as in ds_eval; it is not copied to the host here (ds_eval does that). */
+int ds_eval_noalloc(ds_ctx* ctx, const ds_cgraph* cg, const uint64_t* Z, int64_t k, int32_t score, float* y);
+
 /* Constrained weighted least squares (paper, Eq. for Kernel-SHAP regression, the
  * efficiency decomposition, and Alg. 1): rows 0/1 of Z must be the empty/full
  * coalitions; phi minimises sum_{i>=2} w_i (y_i - y_0 - z_i.phi)^2 subject to

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "ds_create", "ds_destroy", "ds_last_error", "ds_set_tuning", "ds_set_graph", "ds_set_features", "ds_set_gcn", "ds_set_gat",
     "ds_explain", "ds_explain_batch", "ds_extract", "ds_cgraph_get_info", "ds_cgraph_edges",
     "ds_cgraph_nodes", "ds_cgraph_first_transform", "ds_cgraph_free", "ds_sample_plan", "ds_sample",
-    "ds_plan_tables", "ds_sample_range", "ds_eval", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
+    "ds_plan_tables", "ds_sample_range", "ds_eval", "ds_eval_noalloc", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
 ]
 
 
@@ -104,6 +104,7 @@ def load_library():
         "ds_plan_tables": [i64, i64, p, p],
         "ds_sample_range": [p, i64, i64, u64, u32, i64, i64, p, p, p],
         "ds_eval": [p, p, p, i64, i32, p, C.POINTER(i32)],
+        "ds_eval_noalloc": [p, p, p, i64, i32, p],
         "ds_solve": [p, i64, i64, p, p, p, C.POINTER(Options), p, C.POINTER(Report)],
         "ds_copy_probe": [p, p, p, i64],
         "ds_fidelity": [p, p, p, C.POINTER(i64), i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), p],
@@ -358,6 +359,18 @@ class Context:
         self._sync_inputs()
         self._check(self.lib.ds_eval(self.h, cg, _ptr(Z), k, score, _ptr(y), C.byref(pc)))
         return y[:k], pc.value
+
+    def eval_noalloc(self, cg, Z, y, score=DS_SCORE_PROB):
+        """ds_eval_noalloc into the caller's y (float32[k]); queued on the context's stream, no synchronisation."""
+        self._sync_inputs()
+        self._check(self.lib.ds_eval_noalloc(self.h, cg, _ptr(Z), Z.shape[0], score, _ptr(y)))
+
+    def synchronize(self):
+        """Wait for the library's stream (the one given at creation, else the default stream)."""
+        if self._stream is not None:
+            self._stream.synchronize()
+        else:
+            self.torch.cuda.synchronize(self.device)
 
     def fidelity(self, cg, phi, ks, score=DS_SCORE_PROB, want_masks=False):
         """(fid_plus, fid_minus[, masks]) for the top-k sub-graphs, k in ks."""

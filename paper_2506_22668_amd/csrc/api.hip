@@ -113,6 +113,7 @@ int ds_create(ds_ctx** out, int device, void* stream) {
       hipEventCreateWithFlags(&ctx->fork2_ev, hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&ctx->join2_ev, hipEventDisableTiming) != hipSuccess) { delete ctx; return DS_EDEVICE; }
   if (hipMemset(ctx->d_mail, 0, 64 * sizeof(int64_t)) != hipSuccess) { delete ctx; return DS_EDEVICE; }
+  if (ds_static_scratch_init(device) != DS_OK) { delete ctx; return DS_EDEVICE; }
   *out = ctx;
   return DS_OK;
 }
@@ -381,6 +382,35 @@ int ds_eval(ds_ctx* ctx, const ds_cgraph* cg_in, const uint64_t* Z, int64_t k, i
     rc = ds_fetch_pred_class(ctx, cg);
     *pred_class_out = cg->pred_class;
   }
+  return rc;
+}
+
+int ds_eval_noalloc(ds_ctx* ctx, const ds_cgraph* cg_in, const uint64_t* Z, int64_t k, int32_t score, float* y) {
+  if (!ctx || !cg_in) return DS_EINVAL;
+  if (k < 0 || (k > 0 && (!Z || !y))) return ds_fail(ctx, DS_EINVAL, "bad eval arguments");
+  if (score != DS_SCORE_PROB && score != DS_SCORE_LOGIT) return ds_fail(ctx, DS_EINVAL, "unknown score %d", score);
+  if (ctx->model_kind != DS_MODEL_GCN) return ds_fail(ctx, DS_EINVAL, "ds_eval_noalloc covers the GCN only");
+  DS_HIP(ctx, hipSetDevice(ctx->device));
+  void* ptr = ds_static_scratch(ctx->device);
+  if (!ptr) return ds_fail(ctx, DS_EINTERNAL, "the static scratch array of device %d was not initialised", ctx->device);
+  ds_cgraph* cg = const_cast<ds_cgraph*>(cg_in);
+  // the same host driver and kernels as ds_eval, with the workspace pointed at the static array for this call
+  char* const own = ctx->arena;
+  const size_t own_bytes = ctx->arena_bytes, own_used = ctx->arena_used;
+  ctx->arena = (char*)ptr;
+  ctx->arena_bytes = DS_EVAL_NOALLOC_SCRATCH_BYTES;
+  ctx->arena_used = 0;
+  int rc = DS_OK;
+  const size_t W = (size_t)((cg->info.num_players + 63) / 64);
+  const size_t fixed = ds_align(W * 8 + 8) + ds_align((size_t)ctx->dims[ctx->L] * 4 + 8) + 4096;
+  if (fixed > DS_EVAL_NOALLOC_SCRATCH_BYTES)
+    rc = ds_fail(ctx, DS_ECAPACITY, "ds_eval_noalloc: %lld players need %zu bytes of scratch, the static array holds %u",
+                 (long long)cg->info.num_players, fixed, DS_EVAL_NOALLOC_SCRATCH_BYTES);
+  if (rc == DS_OK) rc = ds_eval_impl(ctx, cg, Z, k, score, y, -1);
+  if (rc == DS_EINTERNAL) rc = DS_ECAPACITY;  // the bounded workspace ran out: a size limit, not a fault
+  ctx->arena = own;
+  ctx->arena_bytes = own_bytes;
+  ctx->arena_used = own_used;
   return rc;
 }
 

@@ -675,6 +675,8 @@ __global__ void argmax_kernel(const float* logits, int C, int32_t* out) {
   if (lane == 0) *out = arg == 0x7fffffff ? 0 : arg;
 }
 
+__global__ void store_i32_kernel(int32_t* p, int32_t v) { *p = v; }
+
 __global__ void fill_full_mask(uint64_t* z, int64_t W, int n) {
   const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (w >= W) return;
@@ -834,6 +836,27 @@ BatchedLayout make_batched_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_
 }
 }  // namespace
 
+// ---------------- scratch memory for the entry point that may not allocate ----------------
+// A file-scope device array: every GPU the library runs on holds its own copy at its own address until the
+// process ends. In host code the array's name is only a stand-in for the symbol; the address on a device is
+// looked up once per device (below) and that pointer is what kernels, and the workspace logic, receive.
+static __device__ __align__(256) unsigned char scratch[DS_EVAL_NOALLOC_SCRATCH_BYTES];
+static void* g_scratch_ptr[DS_MAX_DEVICES] = {nullptr};
+
+int ds_static_scratch_init(int device) {
+  if (device < 0 || device >= DS_MAX_DEVICES) return DS_EINVAL;
+  if (g_scratch_ptr[device]) return DS_OK;
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {  // `device` is current (ds_create set it)
+    (void)hipGetLastError();
+    return DS_EDEVICE;
+  }
+  g_scratch_ptr[device] = ptr;
+  return DS_OK;
+}
+
+void* ds_static_scratch(int device) { return device >= 0 && device < DS_MAX_DEVICES ? g_scratch_ptr[device] : nullptr; }
+
 int ds_launch_first_transform(ds_ctx* ctx, const float* A, const float* B, float* C, int M, int K, int Nn, int bf16) {
   const int tiles = ((M + 31) / 32) * ((Nn + 31) / 32);
   const int blocks = (tiles + kWaves - 1) / kWaves;
@@ -899,7 +922,7 @@ int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg) {
   a.logits_out = logits;
   a.gws = gws;
   a.score = DS_SCORE_LOGIT;
-  DS_HIP(ctx, hipMemsetAsync(cg->d_pred, 0, sizeof(int32_t), ctx->stream));
+  hipLaunchKernelGGL(store_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, cg->d_pred, 0);  // a kernel, not a memset node
   a.pred_ptr = cg->d_pred;
   DS_TRY(launch_eval(ctx, a, lay, 1));
   hipLaunchKernelGGL(argmax_kernel, dim3(1), dim3(64), 0, ctx->stream, logits, C, cg->d_pred);
@@ -909,15 +932,23 @@ int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg) {
   return DS_OK;
 }
 
+// batch_rows < 0: the workspace is bounded (it is not the context's own arena): fit the launch into it
 int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y, int batch_rows) {
-  (void)batch_rows;
   if (ctx->model_kind == DS_MODEL_GAT) return ds_gat_eval_impl(ctx, cg, Z, k, score, y);
   DS_TRY(ds_prepare_model(ctx, cg));
   if (k <= 0) return DS_OK;
   const EvalLayout lay = make_layout(ctx, cg);
   const BatchedLayout bl = make_batched_layout(ctx, cg, k);
+  // a bounded workspace (the entry point that may not allocate) runs fewer workgroups at a time instead of failing
+  const size_t avail = ctx->arena_bytes - ctx->arena_used > 512 ? ctx->arena_bytes - ctx->arena_used - 512 : 0;
   if (bl.use) {
-    float* scratch = (float*)ds_arena_alloc(ctx, (size_t)bl.stride * 4 * bl.grid);
+    int bgrid = bl.grid;
+    if (batch_rows < 0) {
+      const size_t fit = avail / ((size_t)bl.stride * 4);
+      if (fit < 1) return ds_fail(ctx, DS_ECAPACITY, "eval: one workgroup needs %zu bytes of scratch, %zu are left", (size_t)bl.stride * 4, avail);
+      if ((size_t)bgrid > fit) bgrid = (int)fit;
+    }
+    float* scratch = (float*)ds_arena_alloc(ctx, (size_t)bl.stride * 4 * bgrid);
     if (!scratch) return ds_fail(ctx, DS_EINTERNAL, "eval: arena exhausted");
     BatchedArgs b;
     fill_args(ctx, cg, lay, &b.e);
@@ -945,19 +976,24 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
     if (bl.lds_bytes > 48 * 1024)
       DS_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bl.lds_bytes));
     if (bl.deg_lds && bl.csr_lds)
-      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, true>), dim3(bl.grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, true>), dim3(bgrid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
     else if (bl.deg_lds)
-      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, false>), dim3(bl.grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, false>), dim3(bgrid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
     else if (bl.csr_lds)
-      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, true>), dim3(bl.grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, true>), dim3(bgrid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
     else
-      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, false>), dim3(bl.grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, false>), dim3(bgrid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
     DS_HIP(ctx, hipGetLastError());
     return ds_kernel_mark(ctx, 0, 1);
   }
-  const int grid = grid_for(ctx, lay, k);
+  int grid = grid_for(ctx, lay, k);
   float* gws = nullptr;
   if (lay.gws_floats) {
+    if (batch_rows < 0) {
+      const size_t fit = avail / ((size_t)lay.gws_floats * 4);
+      if (fit < 1) return ds_fail(ctx, DS_ECAPACITY, "eval: one workgroup needs %zu bytes of scratch, %zu are left", (size_t)lay.gws_floats * 4, avail);
+      if ((size_t)grid > fit) grid = (int)fit;
+    }
     gws = (float*)ds_arena_alloc(ctx, (size_t)lay.gws_floats * 4 * grid);
     if (!gws) return ds_fail(ctx, DS_EINTERNAL, "eval: arena exhausted");
   }

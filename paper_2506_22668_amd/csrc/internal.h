@@ -13,6 +13,8 @@
 #define DS_MAX_HOPS 7
 #define DS_ENUM_MAX_PLAYERS 24
 #define DS_WAVE 64
+#define DS_MAX_DEVICES 64
+#define DS_EVAL_NOALLOC_SCRATCH_BYTES (32u << 20)
 
 struct ds_cgraph {
   ds_ctx* owner;
@@ -149,6 +151,10 @@ int ds_validate_csr(ds_ctx* ctx);
 int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y,
                  int batch_rows);
 int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg);  // shared first transform + predicted class
+// the file-scope device array behind ds_eval_noalloc: address look-up (once per device, that device current)
+// and the pointer found
+int ds_static_scratch_init(int device);
+void* ds_static_scratch(int device);
 size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
 // width of the shared first transform P = X_c W_1
 static inline int32_t ds_first_width(const ds_ctx* ctx) {
