@@ -608,6 +608,120 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
   }
 }
 
+// ---------------- large computational graphs: the mask matrix is streamed once ----------------
+//
+// When a mask row is long (more than 12,288 players) everything a coalition's evaluation needs from its
+// row is (a) the degree of every node and (b) the bits of the CSR entries of the rows layer 1 has to
+// produce (the nodes within L-1 hops of the target; their entries are a prefix of the local CSR). A first
+// kernel streams the rows and reduces each to exactly that, a few KB per coalition; the layers then run
+// on 64 coalitions per workgroup from those compact arrays (the one-coalition-per-lane kernel in its
+// external-input mode), with the shared first product on the matrix cores.
+//
+// Complementary pairs (rows 2r, 2r+1 as the sampler writes them): only row 2r, the smaller member, is read.
+// Its complement has d'(v) = deg_full(v) + 2 - d(v) and the opposite entry bits, which the second kernel
+// derives itself, so the stream is half of the mask matrix.
+struct StreamArgs {
+  int32_t V, n, directed, E_need;
+  int64_t W, rows, row_stride;  // rows handled by this launch; words between consecutive handled rows
+  const uint64_t* Z;
+  const uint32_t* pab;          // [n] end points of player p as local ids: a in the low, b in the high 16 bits
+  const int32_t *row_ptr, *eid;
+  uint16_t* deg_out;            // [rows][deg_stride] d(v) = 1 + active entries of row v
+  uint32_t* ebits_out;          // [rows][eb_stride] bit e = mask bit of the player of CSR entry e, e < E_need
+  int64_t deg_stride, eb_stride;
+};
+
+__global__ void pack_endpoints_kernel(const int2* pl, int64_t n, uint32_t* pab) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= n) return;
+  const int2 e = pl[p];
+  pab[p] = (uint32_t)e.x | ((uint32_t)e.y << 16);
+}
+
+// PAIRED: the row is known to be the smaller member of its pair (at most n/2 bits): its set bits are
+// walked. Otherwise the row's popcount decides whether the set or the cleared bits are walked.
+template <bool PAIRED>
+__global__ __launch_bounds__(kThreads) void stream_degrees_kernel(StreamArgs a) {
+  extern __shared__ int sdeg[];  // V counters, then 16 ints of reduction scratch
+  int* red = sdeg + a.V;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t W = a.W;
+  const uint64_t tail_mask = (a.n & 63) ? ((1ull << (a.n & 63)) - 1ull) : ~0ull;
+  for (int64_t r = blockIdx.x; r < a.rows; r += gridDim.x) {
+    const uint64_t* z = a.Z + r * a.row_stride;
+    bool dense = false;
+    if (!PAIRED) {
+      int c = 0;
+      for (int64_t w0 = tid; w0 < W; w0 += 8 * kThreads) {
+        uint64_t v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const int64_t w = w0 + (int64_t)q * kThreads;
+          v[q] = w < W ? (z[w] & (w == W - 1 ? tail_mask : ~0ull)) : 0ull;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) c += __popcll(v[q]);
+      }
+      dense = 2 * (int64_t)block_sum_int(c, red) > a.n;
+    }
+    for (int i = tid; i < a.V; i += kThreads) sdeg[i] = 0;
+    __syncthreads();
+    for (int64_t w0 = tid; w0 < W; w0 += 4 * kThreads) {
+      uint64_t bits[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int64_t w = w0 + (int64_t)q * kThreads;
+        uint64_t b = 0ull;
+        if (w < W) {
+          b = dense ? ~z[w] : z[w];
+          if (w == W - 1) b &= tail_mask;  // padding bits never name a player
+        }
+        bits[q] = b;
+      }
+      while (bits[0] | bits[1] | bits[2] | bits[3]) {
+        uint32_t e[4];
+        bool live[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          live[q] = bits[q] != 0ull;
+          const int64_t p = (w0 + (int64_t)q * kThreads) * 64 + (live[q] ? __ffsll((long long)bits[q]) - 1 : 0);
+          e[q] = live[q] ? a.pab[p] : 0u;
+          bits[q] &= bits[q] - 1;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (live[q]) {
+            atomicAdd(&sdeg[e[q] >> 16], 1);
+            if (!a.directed) atomicAdd(&sdeg[e[q] & 0xFFFFu], 1);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    uint16_t* dout = a.deg_out + r * a.deg_stride;
+    for (int i = tid; i < a.V; i += kThreads) {
+      const int c = sdeg[i];
+      dout[i] = (uint16_t)(dense ? a.row_ptr[i + 1] - a.row_ptr[i] - c + 1 : c + 1);
+    }
+    // the bits of the entries layer 1 reads, 64 at a time per wave
+    uint32_t* eout = a.ebits_out + r * a.eb_stride;
+    for (int e0 = wave * 64; e0 < a.E_need; e0 += kWaves * 64) {
+      const int e = e0 + lane;
+      bool bit = false;
+      if (e < a.E_need) {
+        const int p = a.eid[e];
+        bit = (z[p >> 6] >> (p & 63)) & 1ull;
+      }
+      const unsigned long long m = __ballot(bit);
+      if (lane == 0) {
+        eout[e0 >> 5] = (uint32_t)m;
+        eout[(e0 >> 5) + 1] = (uint32_t)(m >> 32);
+      }
+    }
+    __syncthreads();
+  }
+}
+
 // ---------------- shared first transform P = X_c W_1 on the matrix cores ----------------
 
 __device__ __forceinline__ short bf16_bits(float x) {
