@@ -115,6 +115,7 @@ typedef struct ds_report {
    *           iterations * 2 * (k/2)*W*8; Gram + Cholesky: (k/2)*W*8 mask bytes read, n*n*4 bytes of Gram
    *           matrix written. */
   double bytes_sample, bytes_eval, bytes_solve;
+  float ms_k_stream;      /* the mask-streaming kernel alone (long mask rows; part of ms_k_eval), else 0 */
 } ds_report;
 
 typedef struct ds_cgraph_info {
@@ -147,6 +148,11 @@ typedef struct ds_tuning {
   int32_t sampler_window;     /* sampler: capacity (entries) of the list of keys the first pass keeps around the
                                  expected threshold; -1 keeps none. A small list forces the slower four-pass
                                  selection (a test hook: the masks are the same either way) */
+  int32_t eval_path;          /* masked GCN inference kernel: 0 = chosen by size; 1 = one workgroup per coalition;
+                                 2 = one coalition per lane, masks on chip (short mask rows); 3 = the mask-streaming
+                                 kernel followed by the one-coalition-per-lane layers (long mask rows). 2 and 3 need
+                                 256 rows or more and fall back to 1 where they do not apply (a test hook: the
+                                 results agree to rounding) */
 } ds_tuning;
 int ds_set_tuning(ds_ctx* ctx, const ds_tuning* tuning /* [host] or NULL */);
 
@@ -271,6 +277,13 @@ int ds_sample_range(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, ui
  * NULL. */
 int ds_eval(ds_ctx* ctx, const ds_cgraph* cg, const uint64_t* Z, int64_t k, int32_t score, float* y,
             int32_t* pred_class_out);
+
+/* ds_eval for rows that come in complementary pairs, the layout ds_sample writes (paper, "Distributed Subgraph
+ * Sampling": paired sampling): row 2r+1 must be the complement of row 2r on the n players; k even. Only row 2r of
+ * each pair is read (the complement's degrees and entry bits follow from it), which halves the mask traffic of
+ * long rows. Results equal ds_eval's. Rows that are not complements give undefined y for the odd rows. */
+int ds_eval_pairs(ds_ctx* ctx, const ds_cgraph* cg, const uint64_t* Z, int64_t k, int32_t score, float* y,
+                  int32_t* pred_class_out);
 
 /* ds_eval for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc. Same kernels and results as ds_eval, but every byte of scratch memory comes

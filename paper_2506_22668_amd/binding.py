@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "ds_create", "ds_destroy", "ds_last_error", "ds_set_tuning", "ds_set_graph", "ds_set_features", "ds_set_gcn", "ds_set_gat",
     "ds_explain", "ds_explain_batch", "ds_extract", "ds_cgraph_get_info", "ds_cgraph_edges",
     "ds_cgraph_nodes", "ds_cgraph_first_transform", "ds_cgraph_free", "ds_sample_plan", "ds_sample",
-    "ds_plan_tables", "ds_sample_range", "ds_eval", "ds_eval_noalloc", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
+    "ds_plan_tables", "ds_sample_range", "ds_eval", "ds_eval_pairs", "ds_eval_noalloc", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
 ]
 
 
@@ -30,7 +30,7 @@ class Options(C.Structure):
 
 class Tuning(C.Structure):
     _fields_ = [("batch_workers", C.c_int32), ("gram_sparse_div", C.c_int32), ("gram_dense_fraction", C.c_float),
-                ("sampler_window", C.c_int32)]
+                ("sampler_window", C.c_int32), ("eval_path", C.c_int32)]
 
 
 class Report(C.Structure):
@@ -43,7 +43,7 @@ class Report(C.Structure):
                 ("ms_k_eval", C.c_float), ("ms_k_gram", C.c_float), ("ms_k_chol", C.c_float),
                 ("ms_k_cgls", C.c_float),
                 ("num_pairs", C.c_int64), ("bytes_sample", C.c_double), ("bytes_eval", C.c_double),
-                ("bytes_solve", C.c_double)]
+                ("bytes_solve", C.c_double), ("ms_k_stream", C.c_float)]
 
     def as_dict(self):
         return {name: getattr(self, name) for name, _ in self._fields_}
@@ -104,6 +104,7 @@ def load_library():
         "ds_plan_tables": [i64, i64, p, p],
         "ds_sample_range": [p, i64, i64, u64, u32, i64, i64, p, p, p],
         "ds_eval": [p, p, p, i64, i32, p, C.POINTER(i32)],
+        "ds_eval_pairs": [p, p, p, i64, i32, p, C.POINTER(i32)],
         "ds_eval_noalloc": [p, p, p, i64, i32, p],
         "ds_solve": [p, i64, i64, p, p, p, C.POINTER(Options), p, C.POINTER(Report)],
         "ds_copy_probe": [p, p, p, i64],
@@ -350,14 +351,16 @@ class Context:
                                              int(pair_end), _ptr(Z), _ptr(w), _ptr(sz)))
         return Z[:rows], w[:rows], sz[:rows]
 
-    def eval(self, cg, Z, score=DS_SCORE_PROB):
+    def eval(self, cg, Z, score=DS_SCORE_PROB, pairs=False):
+        """ds_eval, or ds_eval_pairs when `pairs` (rows 2r, 2r+1 complementary)."""
         t = self.torch
         Z = Z.contiguous()
         k = Z.shape[0]
         y = t.empty(max(k, 1), dtype=t.float32, device=self.device)
         pc = C.c_int32()
         self._sync_inputs()
-        self._check(self.lib.ds_eval(self.h, cg, _ptr(Z), k, score, _ptr(y), C.byref(pc)))
+        fn = self.lib.ds_eval_pairs if pairs else self.lib.ds_eval
+        self._check(fn(self.h, cg, _ptr(Z), k, score, _ptr(y), C.byref(pc)))
         return y[:k], pc.value
 
     def eval_noalloc(self, cg, Z, y, score=DS_SCORE_PROB):

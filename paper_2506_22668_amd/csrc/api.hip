@@ -49,8 +49,8 @@ int ds_kernel_mark(ds_ctx* ctx, int slot, int end) {
 }
 
 static void kernel_times(ds_ctx* ctx, ds_report* rep) {
-  float* out[4] = {&rep->ms_k_eval, &rep->ms_k_gram, &rep->ms_k_chol, &rep->ms_k_cgls};
-  for (int s = 0; s < 4; ++s) {
+  float* out[5] = {&rep->ms_k_eval, &rep->ms_k_gram, &rep->ms_k_chol, &rep->ms_k_cgls, &rep->ms_k_stream};
+  for (int s = 0; s < 5; ++s) {
     *out[s] = 0.f;
     if (ctx->kev_set[s]) (void)hipEventElapsedTime(out[s], ctx->kev[2 * s], ctx->kev[2 * s + 1]);
   }
@@ -96,9 +96,9 @@ int ds_create(ds_ctx** out, int device, void* stream) {
   }
   for (int i = 0; i < 6; ++i)
     if (hipEventCreate(&ctx->ev[i]) != hipSuccess) { delete ctx; return DS_EDEVICE; }
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < 10; ++i)
     if (hipEventCreate(&ctx->kev[i]) != hipSuccess) { delete ctx; return DS_EDEVICE; }
-  for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
+  for (int i = 0; i < 5; ++i) ctx->kev_set[i] = false;
   ctx->owns_stream = false;
   memset(&ctx->tuning, 0, sizeof(ctx->tuning));
   ctx->cg_spare = nullptr;
@@ -142,7 +142,7 @@ int ds_destroy(ds_ctx* ctx) {
   if (ctx->d_mail) hipFree(ctx->d_mail);
   if (ctx->h_mail) hipHostFree(ctx->h_mail);
   for (int i = 0; i < 6; ++i) hipEventDestroy(ctx->ev[i]);
-  for (int i = 0; i < 8; ++i) hipEventDestroy(ctx->kev[i]);
+  for (int i = 0; i < 10; ++i) hipEventDestroy(ctx->kev[i]);
   if (ctx->owns_stream) hipStreamDestroy(ctx->stream);
   delete ctx;
   return DS_OK;
@@ -174,7 +174,8 @@ int ds_set_tuning(ds_ctx* ctx, const ds_tuning* tuning) {
     return DS_OK;
   }
   if (tuning->batch_workers < 0 || tuning->batch_workers > 16 || tuning->gram_sparse_div < 0 ||
-      !(tuning->gram_dense_fraction >= 0.f && tuning->gram_dense_fraction <= 1.f) || tuning->sampler_window < -1)
+      !(tuning->gram_dense_fraction >= 0.f && tuning->gram_dense_fraction <= 1.f) || tuning->sampler_window < -1 ||
+      tuning->eval_path < 0 || tuning->eval_path > 3)
     return ds_fail(ctx, DS_EINVAL, "tuning value out of range");
   ctx->tuning = *tuning;
   return DS_OK;
@@ -366,8 +367,22 @@ int ds_sample_range(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, ui
   return sample_checked(ctx, n, n_samples, seed, tag, pair_begin, pair_end, false, Z, w, sz, nullptr);
 }
 
+static int eval_checked(ds_ctx* ctx, const ds_cgraph* cg_in, const uint64_t* Z, int64_t k, int32_t score, float* y,
+                        int32_t* pred_class_out, int flags);
+
 int ds_eval(ds_ctx* ctx, const ds_cgraph* cg_in, const uint64_t* Z, int64_t k, int32_t score, float* y,
             int32_t* pred_class_out) {
+  return eval_checked(ctx, cg_in, Z, k, score, y, pred_class_out, 0);
+}
+
+int ds_eval_pairs(ds_ctx* ctx, const ds_cgraph* cg_in, const uint64_t* Z, int64_t k, int32_t score, float* y,
+                  int32_t* pred_class_out) {
+  if (ctx && (k & 1)) return ds_fail(ctx, DS_EINVAL, "ds_eval_pairs needs an even number of rows (k=%lld)", (long long)k);
+  return eval_checked(ctx, cg_in, Z, k, score, y, pred_class_out, DS_EVAL_PAIRED);
+}
+
+static int eval_checked(ds_ctx* ctx, const ds_cgraph* cg_in, const uint64_t* Z, int64_t k, int32_t score, float* y,
+                        int32_t* pred_class_out, int flags) {
   if (!ctx || !cg_in) return DS_EINVAL;
   if (k < 0 || (k > 0 && (!Z || !y))) return ds_fail(ctx, DS_EINVAL, "bad eval arguments");
   if (score != DS_SCORE_PROB && score != DS_SCORE_LOGIT) return ds_fail(ctx, DS_EINVAL, "unknown score %d", score);
@@ -375,7 +390,8 @@ int ds_eval(ds_ctx* ctx, const ds_cgraph* cg_in, const uint64_t* Z, int64_t k, i
   ds_cgraph* cg = const_cast<ds_cgraph*>(cg_in);
   ds_arena_reset(ctx);
   DS_TRY(ds_arena_reserve(ctx, ds_eval_arena_bytes(ctx, cg, k)));
-  int rc = ds_eval_impl(ctx, cg, Z, k, score, y, 0);
+  for (int i = 0; i < 5; ++i) ctx->kev_set[i] = false;
+  int rc = ds_eval_impl(ctx, cg, Z, k, score, y, flags);
   if (rc == DS_OK && hipStreamSynchronize(ctx->stream) != hipSuccess) rc = ds_fail(ctx, DS_EDEVICE, "eval kernel failed");
   ds_arena_reset(ctx);
   if (rc == DS_OK && pred_class_out) {
@@ -406,7 +422,7 @@ int ds_eval_noalloc(ds_ctx* ctx, const ds_cgraph* cg_in, const uint64_t* Z, int6
   if (fixed > DS_EVAL_NOALLOC_SCRATCH_BYTES)
     rc = ds_fail(ctx, DS_ECAPACITY, "ds_eval_noalloc: %lld players need %zu bytes of scratch, the static array holds %u",
                  (long long)cg->info.num_players, fixed, DS_EVAL_NOALLOC_SCRATCH_BYTES);
-  if (rc == DS_OK) rc = ds_eval_impl(ctx, cg, Z, k, score, y, -1);
+  if (rc == DS_OK) rc = ds_eval_impl(ctx, cg, Z, k, score, y, DS_EVAL_BOUNDED);
   if (rc == DS_EINTERNAL) rc = DS_ECAPACITY;  // the bounded workspace ran out: a size limit, not a fault
   ctx->arena = own;
   ctx->arena_bytes = own_bytes;
@@ -451,7 +467,7 @@ int ds_solve(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* 
   if (report) memset(report, 0, sizeof(*report));
   ds_arena_reset(ctx);
   DS_TRY(ds_arena_reserve(ctx, solve_arena_bytes(n, k, o.solver)));
-  for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
+  for (int i = 0; i < 5; ++i) ctx->kev_set[i] = false;
   int rc = solve_dispatch(ctx, n, k, Z, w, y, o, o.paired ? 1 : 0, phi, report);
   hipStreamSynchronize(ctx->stream);
   ds_arena_reset(ctx);
@@ -502,7 +518,7 @@ int ds_explain(ds_ctx* ctx, int64_t target, int64_t n_samples, uint64_t seed, co
   ds_options o = default_options(opts);
   hipStream_t st = ctx->stream;
   if (ctx->L < 1) return ds_fail(ctx, DS_EINVAL, "no model is set (ds_set_gcn / ds_set_gat)");
-  for (int i = 0; i < 4; ++i) ctx->kev_set[i] = false;
+  for (int i = 0; i < 5; ++i) ctx->kev_set[i] = false;
   DS_HIP(ctx, hipEventRecord(ctx->ev[0], st));
   ds_cgraph* cg = nullptr;
   DS_TRY(ds_extract(ctx, target, &o, &cg));
@@ -605,7 +621,7 @@ static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t
   const size_t mark2 = ctx->arena_used;
 
   DS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_ev, 0));
-  DS_TRY(ds_eval_impl(ctx, cg, Z, k, o.score, y, o.batch_rows));
+  DS_TRY(ds_eval_impl(ctx, cg, Z, k, o.score, y, DS_EVAL_PAIRED, n >= 2 ? sz : nullptr));  // the sampler's rows are complementary pairs
   ctx->arena_used = mark2;
   DS_HIP(ctx, hipEventRecord(ctx->ev[3], st));
 
@@ -727,7 +743,7 @@ int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, i
   ds_cgraph* first_cg = nullptr;
   {
     ds_ctx* w0 = ctx->workers[0];
-    for (int i = 0; i < 4; ++i) w0->kev_set[i] = false;
+    for (int i = 0; i < 5; ++i) w0->kev_set[i] = false;
     DS_HIP(ctx, hipEventRecord(w0->ev[0], w0->stream));
     const int rc = ds_extract(w0, targets[0], &o, &first_cg);
     if (rc != DS_OK) {
@@ -754,7 +770,7 @@ int ds_explain_batch(ds_ctx* ctx, const int64_t* targets, int32_t num_targets, i
           if (t == 0) {
             cg = first_cg;
           } else {
-            for (int i = 0; i < 4; ++i) w->kev_set[i] = false;
+            for (int i = 0; i < 5; ++i) w->kev_set[i] = false;
             rc = hipEventRecord(w->ev[0], w->stream) == hipSuccess ? DS_OK : DS_EDEVICE;
             if (rc == DS_OK) rc = ds_extract(w, targets[t], &o, &cg);
           }

@@ -312,17 +312,29 @@ struct BatchedArgs {
   EvalArgs e;
   float* scratch;          // per workgroup: rs[V][64] (if not in LDS) | bufA | bufB | q[waves][dmax][64]
   int64_t scratch_stride;  // floats per workgroup
-  int64_t rs_floats, a_floats, b_floats, q_floats;  // region sizes (floats, already x64)
+  int64_t rs_floats, a_floats, b_floats, q_floats;  // region sizes (floats, already x64); then kBWaves x 64 x 64
+                                                    // floats of partial sums (rows shared by all waves)
   int32_t csr_lds_offset;  // byte offset of the LDS copy of the local CSR (if used)
   int32_t zs_words;        // mask words per coalition reserved in LDS (>= W)
+  // external-input mode (long mask rows): degrees and entry bits as the streaming kernel wrote them, one record
+  // per complementary pair (ext_paired: lanes 0..31 take the pairs' stored members, lanes 32..63 their
+  // complements) or per row
+  const uint16_t* ext_deg;
+  const uint32_t* ext_bits;   // [record][eb_stride]: bit r = mask bit of the needed player of rank r
+  const int32_t* erank;       // [E_need]: rank of the player of CSR entry e among the needed players
+  int64_t eb_stride;
+  int32_t ext_paired, eb_words;  // ext_deg is [block][node][32 or 64 records]
 };
 
-template <bool DEG_LDS, bool CSR_LDS>
+constexpr int kSharedRow = 256;  // a row with more entries than this is shared by all waves of the workgroup
+
+template <bool DEG_LDS, bool CSR_LDS, bool EXT>
 __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(BatchedArgs b) {
   const EvalArgs& a = b.e;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   // LDS: zs[zs_words][64] u64 | weight-matrix buffer f32[waves*16*64] | deg[V][64] u16 (optional) | local CSR (optional)
   uint64_t* zs = (uint64_t*)smem_raw;
+  const uint32_t* ebs = (const uint32_t*)smem_raw;  // EXT: entry bits as ebs[word][lane]
   float* stage_all = (float*)(smem_raw + (size_t)b.zs_words * 64 * 8);
   unsigned short* degs = (unsigned short*)(smem_raw + (size_t)b.zs_words * 64 * 8 + kBWaves * kStageRows * 64 * 4);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -353,33 +365,63 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
   const uint64_t tail_mask = (a.n & 63) ? ((1ull << (a.n & 63)) - 1ull) : ~0ull;
   const int64_t blocks = (a.k + 63) / 64;
 
+  const uint16_t* ext_deg_lane = nullptr;  // EXT: this lane's record in the current block of the transposed degrees
+  int ext_member = 0, ext_slots = 64;
   auto rs_of = [&](int v) -> float {
+    if (EXT) {
+      int d = ext_deg_lane[(size_t)v * ext_slots];
+      if (ext_member) d = rp_[v + 1] - rp_[v] + 2 - d;  // the complement: d'(v) = deg_full(v) + 2 - d(v)
+      return __frsqrt_rn((float)d);
+    }
     if (DEG_LDS) return __frsqrt_rn((float)degs[v * 64 + lane]);
     return rs[(size_t)v * 64 + lane];
   };
   auto bit_of = [&](int p) -> bool { return (zs[(p >> 6) * 64 + lane] >> (p & 63)) & 1ull; };
+  // mask bit of CSR entry e (of a row layer 1 produces) in this lane's coalition
+  // (x: the player of the entry, or, with external inputs, the rank of that player among the needed ones)
+  auto entry_bit = [&](int x) -> bool {
+    if (EXT) return (ebs[(x >> 5) * 64 + lane] >> (x & 31)) & 1u;
+    return bit_of(x);
+  };
+  const int32_t* const key_ = EXT ? b.erank : eid_;  // per CSR entry: what entry_bit takes
 
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
-    const int64_t row = blk * 64 + lane;
+    // EXT and paired records: lanes 0..31 are the stored members of 32 pairs, lanes 32..63 their complements
+    const int member = (EXT && b.ext_paired) ? (lane >> 5) : 0;
+    const int64_t rec = (EXT && b.ext_paired) ? blk * 32 + (lane & 31) : blk * 64 + lane;
+    const int64_t row = (EXT && b.ext_paired) ? 2 * rec + member : rec;
     const bool valid = row < a.k;
     __syncthreads();
-    for (int w = wave; w < W; w += kBWaves) {
-      uint64_t word = valid ? a.Z[row * W + w] : 0ull;
-      if (w == W - 1) word &= tail_mask;
-      zs[w * 64 + lane] = word;
-    }
-    __syncthreads();
-    // degrees: node v's entries are fetched 64 at a time by the lanes and broadcast one by one
-    for (int v = wave; v < a.V; v += kBWaves) {
-      const int e0 = rp_[v], e1 = rp_[v + 1];
-      int cnt = 1;
-      for (int eb = e0; eb < e1; eb += 64) {
-        const int m = e1 - eb < 64 ? e1 - eb : 64;
-        const int pv = lane < m ? eid_[eb + lane] : 0;
-        for (int i = 0; i < m; ++i) cnt += bit_of(readlane_i(pv, i)) ? 1 : 0;
+    if (!EXT) {
+      for (int w = wave; w < W; w += kBWaves) {
+        uint64_t word = valid ? a.Z[row * W + w] : 0ull;
+        if (w == W - 1) word &= tail_mask;
+        zs[w * 64 + lane] = word;
       }
-      if (DEG_LDS) degs[v * 64 + lane] = (unsigned short)cnt;
-      else rs[(size_t)v * 64 + lane] = 1.0f / sqrtf((float)cnt);
+      __syncthreads();
+      // degrees: node v's entries are fetched 64 at a time by the lanes and broadcast one by one
+      for (int v = wave; v < a.V; v += kBWaves) {
+        const int e0 = rp_[v], e1 = rp_[v + 1];
+        int cnt = 1;
+        for (int eb = e0; eb < e1; eb += 64) {
+          const int m = e1 - eb < 64 ? e1 - eb : 64;
+          const int pv = lane < m ? eid_[eb + lane] : 0;
+          for (int i = 0; i < m; ++i) cnt += bit_of(readlane_i(pv, i)) ? 1 : 0;
+        }
+        if (DEG_LDS) degs[v * 64 + lane] = (unsigned short)cnt;
+        else rs[(size_t)v * 64 + lane] = 1.0f / sqrtf((float)cnt);
+      }
+    } else {
+      // entry bits of this lane's record (complemented for the second member; bits past the last entry are
+      // never looked at)
+      uint32_t* ebw = (uint32_t*)smem_raw;
+      for (int j = wave; j < b.eb_words; j += kBWaves) {
+        uint32_t wd = valid ? b.ext_bits[rec * b.eb_stride + j] : 0u;
+        ebw[j * 64 + lane] = member ? ~wd : wd;
+      }
+      ext_member = member;
+      ext_slots = b.ext_paired ? 32 : 64;
+      ext_deg_lane = b.ext_deg + (size_t)blk * a.V * ext_slots + (b.ext_paired ? (lane & 31) : lane);
     }
     __syncthreads();
 
@@ -394,8 +436,25 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
       const int d1 = a.dims[1];
       const bool relu = a.L > 1;
       const int half = lane >> 5, l32 = lane & 31;
-      for (int t = wave; t < a.rows_out[1]; t += kBWaves) {
+      const int rows1 = a.rows_out[1];
+      // One loop over the rows layer 1 produces. A row of ordinary length belongs to one wave (round-robin). A long
+      // row (a hub within L-1 hops of the target) is shared: the waves split its entries, leave their partial
+      // tiles in the workgroup's scratch and add them up in wave order (a fixed order: results do not depend on
+      // timing).
+      int ordinary = 0;
+      for (int t = 0; t < rows1; ++t) {
         const int e0 = rp_[t], e1 = rp_[t + 1];  // entry e1 stands for the self-loop
+        const bool shared = e1 - e0 > kSharedRow;  // the same for every wave
+        if (!shared && (ordinary++ % kBWaves) != wave) continue;
+        int s0 = e0, s1 = e1 + 1;
+        if (shared) {
+          int per = (e1 - e0 + 1 + kBWaves - 1) / kBWaves;
+          per = (per + kStageRows - 1) / kStageRows * kStageRows;
+          s0 = e0 + wave * per;
+          s1 = s0 + per;
+          if (s0 > e1 + 1) s0 = e1 + 1;
+          if (s1 > e1 + 1) s1 = e1 + 1;
+        }
         const float rst = rs_of(t);
         const float rst_sw = __shfl_xor(rst, 32, 64);
         for (int f0 = 0; f0 < d1; f0 += 64) {
@@ -404,18 +463,18 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
           for (int i = 0; i < 16; ++i) {
             acc[0][0][i] = 0.f; acc[0][1][i] = 0.f; acc[1][0][i] = 0.f; acc[1][1][i] = 0.f;
           }
-          for (int eb = e0; eb <= e1; eb += kStageRows) {
-            const int cnt = e1 + 1 - eb < kStageRows ? e1 + 1 - eb : kStageRows;
+          for (int eb = s0; eb < s1; eb += kStageRows) {
+            const int cnt = s1 - eb < kStageRows ? s1 - eb : kStageRows;
             int pv = 0, sv = t;
             if (lane < cnt && eb + lane < e1) {
-              pv = eid_[eb + lane];
+              pv = key_[eb + lane];
               sv = col_[eb + lane];
             }
             float av[kStageRows / 2][2];
 #pragma unroll
             for (int q = 0; q < kStageRows / 2; ++q) {
-              const int s0 = readlane_i(sv, 2 * q), s1 = readlane_i(sv, 2 * q + 1);
-              const int src = half ? s1 : s0;
+              const int s0q = readlane_i(sv, 2 * q), s1q = readlane_i(sv, 2 * q + 1);
+              const int src = half ? s1q : s0q;
               const bool ok = 2 * q + half < cnt;
               const float* pr = a.P + (size_t)src * d1 + f0 + l32;
               av[q][0] = (ok && f0 + l32 < d1) ? pr[0] : 0.f;
@@ -429,7 +488,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
                 const bool self = eb + i == e1;
                 const int p = readlane_i(pv, i), src = readlane_i(sv, i);
                 const float r = rs_of(src);
-                coef[i] = (self || bit_of(p)) ? r : 0.f;
+                coef[i] = (self || entry_bit(p)) ? r : 0.f;
               }
             }
 #pragma unroll
@@ -447,21 +506,51 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
             }
           }
           // accumulator register i of lane l is D[feature 8*(i/4) + 4*(l/32) + i%4][coalition l%32]
+          if (!shared) {
 #pragma unroll
-          for (int ft = 0; ft < 2; ++ft)
+            for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-              const float scale = (nb == half) ? rst : rst_sw;  // d^-1/2 of row t in coalition nb*32 + l32
+              for (int nb = 0; nb < 2; ++nb) {
+                const float scale = (nb == half) ? rst : rst_sw;  // d^-1/2 of row t in coalition nb*32 + l32
 #pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                const int fr = f0 + ft * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-                if (fr < d1) {
-                  float v = scale * acc[ft][nb][i];
-                  if (a.bias[0]) v += a.bias[0][fr];
-                  bufA[((size_t)t * d1 + fr) * 64 + nb * 32 + l32] = relu ? fmaxf(v, 0.f) : v;
+                for (int i = 0; i < 16; ++i) {
+                  const int fr = f0 + ft * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                  if (fr < d1) {
+                    float v = scale * acc[ft][nb][i];
+                    if (a.bias[0]) v += a.bias[0][fr];
+                    bufA[((size_t)t * d1 + fr) * 64 + nb * 32 + l32] = relu ? fmaxf(v, 0.f) : v;
+                  }
                 }
               }
+          } else {
+            // the waves add their tiles into one LDS tile, one wave at a time in wave order
+            float* tl = stage_all + (4 * half) * 64 + l32;  // the staging area is idle during layer 1
+            for (int w = 0; w < kBWaves; ++w) {
+              if (wave == w) {
+#pragma unroll
+                for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+                  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                      float* dst = tl + (ft * 32 + 8 * (i / 4) + (i % 4)) * 64 + nb * 32;
+                      *dst = w == 0 ? acc[ft][nb][i] : *dst + acc[ft][nb][i];
+                    }
+              }
+              __syncthreads();
             }
+#pragma unroll 1
+            for (int j = 0; j < 4096 / kBThreads; ++j) {
+              const int idx = tid + j * kBThreads;  // feature idx / 64 of the tile, coalition idx % 64 == lane
+              const int fr = f0 + (idx >> 6);
+              if (fr < d1) {
+                float v = rst * stage_all[idx];
+                if (a.bias[0]) v += a.bias[0][fr];
+                bufA[((size_t)t * d1 + fr) * 64 + lane] = relu ? fmaxf(v, 0.f) : v;
+              }
+            }
+            __syncthreads();
+          }
         }
       }
     }
@@ -495,7 +584,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
             c[u] = 0.f;
             if (e < e1) {
               src = col_[e];
-              c[u] = bit_of(eid_[e]) ? rs_of(src) : 0.f;
+              c[u] = entry_bit(key_[e]) ? rs_of(src) : 0.f;
             } else if (e == e1) {
               c[u] = rst;
             }
@@ -622,101 +711,388 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
 // derives itself, so the stream is half of the mask matrix.
 struct StreamArgs {
   int32_t V, n, directed, E_need;
+  int32_t lr;         // log2 of the rows a workgroup takes together (1..3)
+  int32_t cnt_words;  // u32 words of the group's packed 16-bit counters: V x R / 2 (node-major: a node's R counters are consecutive)
+  int32_t slots;      // records per block of the transposed degree array: 32 (pairs) or 64 (single rows)
+  int32_t size_step;  // row r's coalition size is sizes[r * size_step]
   int64_t W, rows, row_stride;  // rows handled by this launch; words between consecutive handled rows
   const uint64_t* Z;
+  const int32_t* sizes;
   const uint32_t* pab;          // [n] end points of player p as local ids: a in the low, b in the high 16 bits
-  const int32_t *row_ptr, *eid;
-  uint16_t* deg_out;            // [rows][deg_stride] d(v) = 1 + active entries of row v
-  uint32_t* ebits_out;          // [rows][eb_stride] bit e = mask bit of the player of CSR entry e, e < E_need
-  int64_t deg_stride, eb_stride;
+  const int32_t* a_end;         // [V] one past the last player whose first end point is node v (players with equal a are consecutive)
+  const int32_t* row_ptr;
+  const uint64_t* nmask;        // [W] bits of the players whose CSR entries layer 1 reads ("needed" players)
+  const int32_t* nbase;         // [W] number of needed players before word w: a needed player's rank = nbase + rank in word
+  int32_t eb_words;             // u32 words of a row's needed bits (rank order)
+  uint16_t* deg_out;            // [block][V][slots]: d(v) = 1 + active entries of row v, record = block*slots + slot
+  uint32_t* ebits_out;          // [rows][eb_stride] bit r = mask bit of the needed player of rank r
+  int64_t eb_stride;
 };
 
-__global__ void pack_endpoints_kernel(const int2* pl, int64_t n, uint32_t* pab) {
+__global__ void pack_endpoints_kernel(const int2* pl, int64_t n, uint32_t* pab, int32_t* a_end) {
   const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= n) return;
   const int2 e = pl[p];
   pab[p] = (uint32_t)e.x | ((uint32_t)e.y << 16);
+  if (p == n - 1 || pl[p + 1].x != e.x) a_end[e.x] = (int32_t)(p + 1);
 }
 
-// PAIRED: the row is known to be the smaller member of its pair (at most n/2 bits): its set bits are
-// walked. Otherwise the row's popcount decides whether the set or the cleared bits are walked.
-template <bool PAIRED>
-__global__ __launch_bounds__(kThreads) void stream_degrees_kernel(StreamArgs a) {
-  extern __shared__ int sdeg[];  // V counters, then 16 ints of reduction scratch
-  int* red = sdeg + a.V;
+// coalition size of every handled row, one wave per row (only when the caller has no sizes at hand)
+__global__ __launch_bounds__(kThreads) void row_popcount_kernel(const uint64_t* Z, int64_t rows, int64_t row_stride, int64_t W,
+                                                                int32_t* sizes) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6, nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+  for (int64_t r = wave; r < rows; r += nwaves) {
+    const uint64_t* z = Z + r * row_stride;
+    int c = 0;
+    for (int64_t w = lane; w < W; w += 64) c += __popcll(z[w]);  // padding bits are zero
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+    if (lane == 0) sizes[r] = c;
+  }
+}
+
+// needed players: mark, (scan of the per-word counts on the host side), rank of every needed CSR entry's player
+__global__ void zero_u64_kernel(uint64_t* x, int64_t count) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) x[i] = 0ull;
+}
+__global__ void need_mark_kernel(const int32_t* eid, int E_need, unsigned long long* nmask) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E_need) return;
+  const int p = eid[e];
+  atomicOr(&nmask[p >> 6], 1ull << (p & 63));
+}
+__global__ void need_count_kernel(const uint64_t* nmask, int64_t W, int32_t* cnt) {
+  const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w < W) cnt[w] = __popcll(nmask[w]);
+}
+__global__ void need_rank_kernel(const int32_t* eid, int E_need, const uint64_t* nmask, const int32_t* nbase, int32_t* erank) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E_need) return;
+  const int p = eid[e];
+  erank[e] = nbase[p >> 6] + __popcll(nmask[p >> 6] & ((1ull << (p & 63)) - 1ull));
+}
+
+constexpr int kSThreads = 512;
+constexpr int kSWaves = kSThreads / 64;
+constexpr int kQueueCap = 768;  // players a wave lists before it looks their end points up
+constexpr int kDenseShift = 4;    // a row walks player by player (not bit by bit) from n / 16 bits to count ...
+constexpr int kDenseMinBits = 64;  // ... and this many
+
+// A workgroup takes R = 2^lr consecutive rows together and counts, for every row, the set bits (or, when more than
+// half are set, the cleared ones) incident to every node, with LDS atomics on 16-bit counters packed in pairs, one
+// array per row. Rows with few bits to count are walked bit by bit: a wave's 64 lanes are R rows x 64/R consecutive
+// words, so the lanes of one word column look up the end points of the same 64 players. Rows with many bits are
+// walked player by player instead: a lane holds the end points of one player of the word (one coalesced load
+// for all dense rows of the group), the row's mask word becomes the execution mask of one atomic add for the
+// second end points; the first end points of consecutive players are equal, so they are counted by the
+// popcount of each run in a separate sweep over the row's words. Degrees go out transposed ([node][record]) so
+// that the layers kernel reads one node's degrees of all its coalitions with one coalesced load.
+// `val` in the lanes whose bit is set in the (wave-uniform) 64-bit mask, 0 in the others: one select on the mask
+__device__ __forceinline__ uint32_t lanes_of_mask(unsigned long long mask, uint32_t val) {
+  uint32_t r;
+  asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(r) : "v"(val), "s"(mask));
+  return r;
+}
+
+template <bool PAIRED, int LR>
+__global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a) {
+  extern __shared__ uint32_t ssm[];  // V x R packed 16-bit counters, 8 mode words, the waves' player queues
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int R = 1 << LR, wpw = 64 >> LR;  // rows per workgroup, words per wave and row
+  const int q = lane >> (6 - LR), wl = lane & (wpw - 1);
+  uint32_t* cnt_all = ssm;
+  int* modes = (int*)(ssm + a.cnt_words);  // bit 0: the cleared bits are walked, bit 1: player by player
+  uint32_t* queue = ssm + a.cnt_words + 8;  // kSWaves queues of kQueueCap players
+  uint32_t* nb_all = queue + kSWaves * kQueueCap;       // R x eb_words needed bits
+  constexpr int lrh = LR - 1;  // a node's counters are 2^lrh u32 words; row r sits in word r >> 1, half r & 1
+  auto count_one = [&](uint32_t node, int row) { atomicAdd(&cnt_all[(node << lrh) + (row >> 1)], 1u << ((row & 1) << 4)); };
   const int64_t W = a.W;
   const uint64_t tail_mask = (a.n & 63) ? ((1ull << (a.n & 63)) - 1ull) : ~0ull;
-  for (int64_t r = blockIdx.x; r < a.rows; r += gridDim.x) {
-    const uint64_t* z = a.Z + r * a.row_stride;
-    bool dense = false;
-    if (!PAIRED) {
-      int c = 0;
-      for (int64_t w0 = tid; w0 < W; w0 += 8 * kThreads) {
-        uint64_t v[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          const int64_t w = w0 + (int64_t)q * kThreads;
-          v[q] = w < W ? (z[w] & (w == W - 1 ? tail_mask : ~0ull)) : 0ull;
-        }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) c += __popcll(v[q]);
+  const int64_t groups = (a.rows + R - 1) / R;
+  for (int64_t g = blockIdx.x; g < groups; g += gridDim.x) {
+    for (int i = tid; i < a.cnt_words; i += kSThreads) cnt_all[i] = 0u;
+    for (int i = tid; i < R * a.eb_words; i += kSThreads) nb_all[i] = 0u;
+    if (tid < R) {
+      const int64_t rr = g * R + tid;
+      int mode = 0;
+      if (rr < a.rows) {
+        const int64_t sz = a.sizes[rr * a.size_step];
+        const bool flip = !PAIRED && 2 * sz > a.n;
+        const int64_t walk = flip ? a.n - sz : sz;
+        mode = (flip ? 1 : 0) | (((walk << kDenseShift) >= a.n && walk >= kDenseMinBits) ? 2 : 0);
       }
-      dense = 2 * (int64_t)block_sum_int(c, red) > a.n;
+      modes[tid] = mode;
     }
-    for (int i = tid; i < a.V; i += kThreads) sdeg[i] = 0;
     __syncthreads();
-    for (int64_t w0 = tid; w0 < W; w0 += 4 * kThreads) {
-      uint64_t bits[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int64_t w = w0 + (int64_t)q * kThreads;
-        uint64_t b = 0ull;
-        if (w < W) {
-          b = dense ? ~z[w] : z[w];
-          if (w == W - 1) b &= tail_mask;  // padding bits never name a player
-        }
-        bits[q] = b;
+    int any_dense = 0;
+    for (int i = 0; i < R; ++i) any_dense |= modes[i] & 2;
+    // the needed players' bits of mask word `word` (true bits, word index w) of group row `row`, in rank order
+    auto take_needed = [&](uint64_t word, uint64_t nm, int r0, int row) {  // r0: needed players before this word
+      uint64_t x = word & nm;
+      if (x == 0ull) return;
+      uint32_t* nb = nb_all + (size_t)row * a.eb_words;
+      if (nm == ~0ull) {  // a run of needed players (the players of a hub come one after another)
+        const int sh = r0 & 31;
+        atomicOr(&nb[r0 >> 5], (uint32_t)(x << sh));
+        atomicOr(&nb[(r0 >> 5) + 1], (uint32_t)(x >> (32 - sh)));
+        if (sh) atomicOr(&nb[(r0 >> 5) + 2], (uint32_t)(x >> (64 - sh)));
+        return;
       }
-      while (bits[0] | bits[1] | bits[2] | bits[3]) {
-        uint32_t e[4];
-        bool live[4];
+      while (x) {
+        const int j = __ffsll((long long)x) - 1;
+        x &= x - 1;
+        const int r = r0 + __popcll(nm & ((1ull << j) - 1ull));
+        atomicOr(&nb[r >> 5], 1u << (r & 31));
+      }
+    };
+    // ---- rows walked bit by bit. Looking up a player's end points right where its bit is found makes every step
+    // wait for a memory round trip that serves a few bits; instead the wave first only lists the players (the bit
+    // positions, with the row in the top three bits) in a queue of its own in LDS, and empties the queue when it
+    // is nearly full: then every lane has four independent look-ups in flight, whatever word they came from.
+    {
+      const int64_t r = g * R + q;
+      const int mode = modes[q];
+      const bool active = r < a.rows && !(mode & 2);
+      const bool flip = mode & 1;
+      const uint64_t* z = a.Z + (r < a.rows ? r : 0) * a.row_stride;
+      uint32_t* myq = queue + wave * kQueueCap;
+      int qfill = 0;  // the same in every lane
+      auto drain = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        for (int i0 = 0; i0 < qfill; i0 += 256) {
+          uint32_t ent[4], e[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          live[q] = bits[q] != 0ull;
-          const int64_t p = (w0 + (int64_t)q * kThreads) * 64 + (live[q] ? __ffsll((long long)bits[q]) - 1 : 0);
-          e[q] = live[q] ? a.pab[p] : 0u;
-          bits[q] &= bits[q] - 1;
+          for (int u = 0; u < 4; ++u) {
+            const int idx = i0 + u * 64 + lane;
+            ent[u] = idx < qfill ? myq[idx] : 0xFFFFFFFFu;
+            e[u] = ent[u] != 0xFFFFFFFFu ? a.pab[ent[u] & 0x0FFFFFFFu] : 0u;
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            if (ent[u] != 0xFFFFFFFFu) {
+              const int row = (int)(ent[u] >> 28);
+              count_one(e[u] >> 16, row);
+              if (!a.directed) count_one(e[u] & 0xFFFFu, row);
+            }
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        qfill = 0;
+      };
+      // eight word columns per lane are fetched together (the row's words and the needed-player masks: sixteen
+      // independent loads), then handled two at a time
+      for (int64_t wc0 = (int64_t)wave * wpw; wc0 < W; wc0 += 8 * kSWaves * wpw) {
+        uint64_t tw[8], nm[8];
+        int nr[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int64_t w = wc0 + (int64_t)u * kSWaves * wpw + wl;
+          const bool in = active && w < W;
+          tw[u] = in ? z[w] : 0ull;
+          nm[u] = in ? a.nmask[w] : 0ull;
+          nr[u] = in ? a.nbase[w] : 0;
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if (live[q]) {
-            atomicAdd(&sdeg[e[q] >> 16], 1);
-            if (!a.directed) atomicAdd(&sdeg[e[q] & 0xFFFFu], 1);
+        for (int uu = 0; uu < 4; ++uu) {
+        const int64_t wc = wc0 + (int64_t)(2 * uu) * kSWaves * wpw;
+        if (wc >= W) break;
+        uint64_t bits[2];
+        int64_t base[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int64_t w = wc + (int64_t)u * kSWaves * wpw + wl;
+          uint64_t bw = 0ull;
+          if (active && w < W) {
+            take_needed(tw[2 * uu + u], nm[2 * uu + u], nr[2 * uu + u], q);
+            bw = flip ? ~tw[2 * uu + u] : tw[2 * uu + u];
+            if (w == W - 1) bw &= tail_mask;  // padding bits never name a player
+          }
+          bits[u] = bw;
+          base[u] = w * 64;
+        }
+        const int c = __popcll(bits[0]) + __popcll(bits[1]);
+        if (__ballot(c != 0) == 0ull) continue;
+        int incl = c;  // inclusive prefix sum over the lanes
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int t = __shfl_up(incl, o, 64);
+          if (lane >= o) incl += t;
+        }
+        const int total = __shfl(incl, 63, 64);
+        if (total > kQueueCap) {  // does not happen for rows below the dense threshold; counted directly
+          if (qfill) drain();
+#pragma unroll
+          for (int u = 0; u < 2; ++u)
+            while (bits[u]) {
+              const uint32_t e = a.pab[base[u] + (__ffsll((long long)bits[u]) - 1)];
+              bits[u] &= bits[u] - 1;
+              count_one(e >> 16, q);
+              if (!a.directed) count_one(e & 0xFFFFu, q);
+            }
+          continue;
+        }
+        if (qfill + total > kQueueCap) drain();
+        int pos = qfill + incl - c;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+          while (bits[u]) {
+            myq[pos++] = (uint32_t)(base[u] + (__ffsll((long long)bits[u]) - 1)) | ((uint32_t)q << 28);
+            bits[u] &= bits[u] - 1;
+          }
+        qfill += total;
+        }
+      }
+      if (qfill) drain();
+    }
+    // ---- rows walked player by player (uniform control flow from here to the barrier: every lane of every wave
+    // is active, which the execution-mask atomics below rely on)
+    if (any_dense) {
+      int dmode[8];  // per row of the group: -1 = not walked this way, else bit 0 of its mode (wave-uniform values)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int m = i < R ? __builtin_amdgcn_readfirstlane(modes[i < R ? i : 0]) : 0;
+        dmode[i] = (m & 2) ? (m & 1) : -1;
+      }
+      const int64_t per = ((W + kSWaves - 1) / kSWaves + 63) & ~(int64_t)63;
+      const int64_t w_begin = (int64_t)__builtin_amdgcn_readfirstlane(wave) * per;
+      const int64_t w_end = w_begin + per < W ? w_begin + per : W;
+      // lane l holds word wb + l of every dense row of the current block of 64 words (and, one block ahead, of the
+      // next); the words are handed to all lanes one at a time below
+      uint64_t mw[8], mw_next[8];
+      auto load_words = [&](int64_t wb, uint64_t (&dst)[8]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          uint64_t m = 0ull;
+          if (dmode[i] >= 0 && wb + lane < w_end) m = a.Z[(g * R + i) * a.row_stride + wb + lane];
+          dst[i] = m;
+        }
+      };
+      auto load_players = [&](int64_t w0, uint32_t (&dst)[8]) {  // end points of player `lane` of eight consecutive words
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int64_t p = (w0 + u) * 64 + lane;
+          dst[u] = p < a.n ? a.pab[p] : 0u;
+        }
+      };
+      if (w_begin < w_end) load_words(w_begin, mw_next);
+      for (int64_t wb = w_begin; wb < w_end; wb += 64) {
+        const uint64_t nmw = wb + lane < w_end ? a.nmask[wb + lane] : 0ull;
+        const int nrw = wb + lane < w_end ? a.nbase[wb + lane] : 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          uint64_t m = mw_next[i];
+          if (dmode[i] >= 0 && wb + lane < w_end) {
+            take_needed(m, nmw, nrw, i);
+            if (dmode[i]) m = ~m;
+            if (wb + lane == W - 1) m &= tail_mask;
+          }
+          mw[i] = m;
+        }
+        if (wb + 64 < w_end) load_words(wb + 64, mw_next);
+        uint32_t e[8], e_next[8];
+        load_players(wb, e_next);
+        for (int j0 = 0; j0 < 64 && wb + j0 < w_end; j0 += 8) {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) e[u] = e_next[u];
+          if (j0 + 8 < 64 && wb + j0 + 8 < w_end) load_players(wb + j0 + 8, e_next);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            // this lane's player of word wb + j0 + u: one increment word per four rows (a 16-bit field per row:
+            // the row's bit of this player), added to the player's second end point with one 64-bit atomic.
+            // Rows that are not walked this way hold zero words here.
+            uint32_t* cb = cnt_all + ((e[u] >> 16) << lrh);
+#pragma unroll
+            for (int h = 0; h < (R + 3) / 4; ++h) {
+              uint32_t inc[2] = {0u, 0u};
+#pragma unroll
+              for (int i2 = 0; i2 < 4; ++i2) {
+                const int i = 4 * h + i2;
+                if (i >= R) break;
+                const unsigned long long ms =
+                    ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(mw[i] >> 32), j0 + u) << 32) |
+                    (uint32_t)__builtin_amdgcn_readlane((int)mw[i], j0 + u);
+                inc[i2 >> 1] |= lanes_of_mask(ms, (i2 & 1) ? 0x10000u : 1u);
+              }
+              if (R == 2) {
+                if (inc[0]) atomicAdd(cb, inc[0]);
+              } else if (inc[0] | inc[1]) {
+                atomicAdd((unsigned long long*)cb + h, (unsigned long long)inc[0] | ((unsigned long long)inc[1] << 32));
+              }
+            }
+          }
+        }
+      }
+      // first end points of the dense rows (undirected players only): players with the same first end point are
+      // consecutive, so a word is a few runs of equal a; a run's count in a row is one popcount. The runs of a
+      // word are found once (a chain of dependent look-ups) and applied to every dense row of the group.
+      if (!a.directed) {
+        for (int64_t w = tid; w < W; w += kSThreads) {
+          uint64_t mr[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            uint64_t m = 0ull;
+            if (dmode[i] >= 0) {
+              m = a.Z[(g * R + i) * a.row_stride + w];
+              if (dmode[i]) m = ~m;
+              if (w == W - 1) m &= tail_mask;
+            }
+            mr[i] = m;
+          }
+          int64_t p = w * 64;
+          const int64_t p_end = p + 64 < a.n ? p + 64 : a.n;
+          while (p < p_end) {
+            const uint32_t ha = a.pab[p] & 0xFFFFu;
+            int64_t run_end = a.a_end[ha];
+            if (run_end > p_end) run_end = p_end;
+            const int lo = (int)(p - w * 64), hi = (int)(run_end - w * 64);  // bits lo .. hi-1 of the word
+            const uint64_t seg = (hi >= 64 ? ~0ull : ((1ull << hi) - 1ull)) & ~((1ull << lo) - 1ull);
+            uint32_t* cb = cnt_all + (ha << lrh);
+#pragma unroll
+            for (int h = 0; h < (R + 3) / 4; ++h) {
+              uint32_t inc[2] = {0u, 0u};
+#pragma unroll
+              for (int i2 = 0; i2 < 4; ++i2) {
+                const int i = 4 * h + i2;
+                if (i >= R) break;
+                inc[i2 >> 1] |= (uint32_t)__popcll(mr[i] & seg) << ((i2 & 1) << 4);  // zero words for the other rows
+              }
+              if (R == 2) {
+                if (inc[0]) atomicAdd(cb, inc[0]);
+              } else if (inc[0] | inc[1]) {
+                atomicAdd((unsigned long long*)cb + h, (unsigned long long)inc[0] | ((unsigned long long)inc[1] << 32));
+              }
+            }
+            p = run_end;
           }
         }
       }
     }
     __syncthreads();
-    uint16_t* dout = a.deg_out + r * a.deg_stride;
-    for (int i = tid; i < a.V; i += kThreads) {
-      const int c = sdeg[i];
-      dout[i] = (uint16_t)(dense ? a.row_ptr[i + 1] - a.row_ptr[i] - c + 1 : c + 1);
+    // degrees, transposed: the R records of this workgroup are R consecutive slots of one block
+    {
+      const int64_t rec0 = g * R;
+      const int64_t blk = rec0 / a.slots;
+      const int slot0 = (int)(rec0 - blk * a.slots);
+      uint16_t* dst = a.deg_out + ((size_t)blk * a.V) * a.slots + slot0;
+      for (int v = tid; v < a.V; v += kSThreads) {
+        const int full1 = a.row_ptr[v + 1] - a.row_ptr[v] + 1;
+        uint32_t* d32 = (uint32_t*)(dst + (size_t)v * a.slots);
+        for (int q2 = 0; q2 < R; q2 += 2) {
+          const uint32_t cw = cnt_all[(v << lrh) + (q2 >> 1)];
+          int c0 = cw & 0xFFFF, c1 = cw >> 16;
+          if (!PAIRED) {
+            if (modes[q2] & 1) c0 = full1 - 1 - c0;
+            if (modes[q2 + 1] & 1) c1 = full1 - 1 - c1;
+          }
+          d32[q2 >> 1] = (uint32_t)(c0 + 1) | ((uint32_t)(c1 + 1) << 16);
+        }
+      }
     }
-    // the bits of the entries layer 1 reads, 64 at a time per wave
-    uint32_t* eout = a.ebits_out + r * a.eb_stride;
-    for (int e0 = wave * 64; e0 < a.E_need; e0 += kWaves * 64) {
-      const int e = e0 + lane;
-      bool bit = false;
-      if (e < a.E_need) {
-        const int p = a.eid[e];
-        bit = (z[p >> 6] >> (p & 63)) & 1ull;
-      }
-      const unsigned long long m = __ballot(bit);
-      if (lane == 0) {
-        eout[e0 >> 5] = (uint32_t)m;
-        eout[(e0 >> 5) + 1] = (uint32_t)(m >> 32);
-      }
+    // the needed players' bits
+    for (int i = tid; i < R * a.eb_words; i += kSThreads) {
+      const int row = i / a.eb_words, j = i - row * a.eb_words;
+      if (g * R + row < a.rows) a.ebits_out[(g * R + row) * a.eb_stride + j] = nb_all[i];
     }
     __syncthreads();
   }
@@ -901,12 +1277,33 @@ void fill_args(const ds_ctx* ctx, const ds_cgraph* cg, const EvalLayout& lay, Ev
 
 
 struct BatchedLayout {
-  bool use, deg_lds, csr_lds;
-  int csr_off, zs_words;
+  bool use, deg_lds, csr_lds, ext;
+  int csr_off, zs_words, eb_words;
   int grid;
   size_t lds_bytes;
   int64_t rs_floats, a_floats, b_floats, q_floats, stride;
+  // external-input mode: the streaming kernel's launch and its outputs
+  int64_t records, deg_blocks, eb_stride;
+  int32_t E_need, stream_grid, stream_lr, cnt_words, slots;
+  size_t stream_lds;
 };
+
+constexpr int64_t kPartFloats = 0;
+
+void batched_buffers(const ds_ctx* ctx, const ds_cgraph* cg, BatchedLayout* bl) {
+  int32_t rows_out[DS_MAX_LAYERS + 1];
+  fill_rows(ctx, cg, rows_out);
+  const int L = ctx->L;
+  int64_t A = 0, B = 0, dq = 0;
+  for (int l = 1; l <= L; ++l) {
+    const int64_t out = (int64_t)rows_out[l] * ctx->dims[l];
+    if (l & 1) { if (out > A) A = out; } else { if (out > B) B = out; }
+    if (l >= 2 && (int64_t)rows_out[l] * ctx->dims[l - 1] > dq) dq = (int64_t)rows_out[l] * ctx->dims[l - 1];
+  }
+  bl->a_floats = A * 64;
+  bl->b_floats = (B > 0 ? B : 1) * 64;
+  bl->q_floats = (dq > 0 ? dq : 1) * 64;
+}
 
 // the one-coalition-per-lane kernel applies to short mask rows and enough coalitions to fill lanes
 BatchedLayout make_batched_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
@@ -917,24 +1314,13 @@ BatchedLayout make_batched_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_
   bl.use = n >= 1 && Wn <= kBWMax && k >= 256;
   if (!bl.use) return bl;
   bl.zs_words = (int)(Wn > kBW ? Wn : kBW);
-  int32_t rows_out[DS_MAX_LAYERS + 1];
-  fill_rows(ctx, cg, rows_out);
-  const int L = ctx->L;
-  int64_t A = 0, B = 0, dq = 0;
-  for (int l = 1; l <= L; ++l) {
-    const int64_t out = (int64_t)rows_out[l] * ctx->dims[l];
-    if (l & 1) { if (out > A) A = out; } else { if (out > B) B = out; }
-    if (l >= 2 && (int64_t)rows_out[l] * ctx->dims[l - 1] > dq) dq = (int64_t)rows_out[l] * ctx->dims[l - 1];
-  }
-  bl.a_floats = A * 64;
-  bl.b_floats = (B > 0 ? B : 1) * 64;
-  bl.q_floats = (dq > 0 ? dq : 1) * 64;
+  batched_buffers(ctx, cg, &bl);
   const size_t fixed = (size_t)bl.zs_words * 64 * 8 + (size_t)kBWaves * kStageRows * 64 * 4;
   bl.deg_lds = cg->info.num_nodes <= kDegLdsMaxNodes && fixed + (size_t)cg->info.num_nodes * 64 * 2 + 16 <= kLdsLimit;
   bl.rs_floats = bl.deg_lds ? 0 : cg->info.num_nodes * 64;
   bl.lds_bytes = fixed + (bl.deg_lds ? (size_t)cg->info.num_nodes * 64 * 2 : 0);
   bl.lds_bytes = (bl.lds_bytes + 15) & ~(size_t)15;
-  if (bl.lds_bytes > kLdsLimit) {  // wide masks and no room left: the one-workgroup-per-coalition kernel takes over
+  if (bl.lds_bytes > kLdsLimit) {  // wide masks and no room left: the other kernels take over
     bl.use = false;
     return bl;
   }
@@ -942,11 +1328,87 @@ BatchedLayout make_batched_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_
   bl.csr_lds = bl.lds_bytes + csr_bytes <= kLdsLimit;
   bl.csr_off = (int)bl.lds_bytes;
   if (bl.csr_lds) bl.lds_bytes += csr_bytes;
-  bl.stride = bl.rs_floats + bl.a_floats + bl.b_floats + bl.q_floats;
+  bl.stride = bl.rs_floats + bl.a_floats + bl.b_floats + bl.q_floats + kPartFloats;
   const int64_t blocks = (k + 63) / 64;
   int64_t g = (int64_t)ctx->num_cus * 2;
   bl.grid = (int)(blocks < g ? blocks : g);
   return bl;
+}
+
+// Long mask rows: the streaming kernel reduces every row (or complementary pair) to degrees and entry bits, and the
+// one-coalition-per-lane kernel runs the layers from those. Needs 16-bit degrees and local ids and the entry bits
+// of 64 coalitions in LDS.
+BatchedLayout make_stream_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int paired) {
+  BatchedLayout bl;
+  memset(&bl, 0, sizeof(bl));
+  const int64_t n = cg->info.num_players, V = cg->info.num_nodes;
+  if (n < 1 || n > (1 << 28) || k < 256 || V > 65000 || ctx->L < 1) return bl;
+  if (paired && (k & 1)) return bl;
+  int h = ctx->L - 1;
+  if (h > cg->info.hops) h = cg->info.hops;
+  const int64_t E_need = cg->ball_entries[h];
+  if (E_need > (1 << 20)) return bl;
+  bl.E_need = (int32_t)E_need;
+  bl.eb_words = (int)((E_need + 63) / 64 * 2);  // whole 64-entry groups (one ballot each)
+  if (bl.eb_words < 2) bl.eb_words = 2;
+  bl.zs_words = bl.eb_words / 2;
+  bl.lds_bytes = (size_t)bl.zs_words * 64 * 8 + (size_t)kBWaves * kStageRows * 64 * 4;
+  if (bl.lds_bytes > kLdsLimit) return bl;
+  // the streaming kernel: R = 8 rows per workgroup if their packed 16-bit counters fit LDS, else 4 or 2
+  bl.stream_lr = 3;
+  const size_t stream_fixed = 32 + (size_t)kSWaves * kQueueCap * 4 + 64;
+  const size_t stream_row = (size_t)((V + 3) & ~(int64_t)3) * 2 + (size_t)bl.eb_words * 4;  // 16-bit counters, needed bits
+  while (bl.stream_lr > 1 && (stream_row << bl.stream_lr) + stream_fixed > kLdsLimit) --bl.stream_lr;
+  bl.stream_lds = (stream_row << bl.stream_lr) + stream_fixed;
+  if (bl.stream_lds > kLdsLimit) return bl;
+  bl.cnt_words = (int32_t)((((V + 3) & ~(int64_t)3) << bl.stream_lr) / 2);
+  bl.use = true;
+  bl.ext = true;
+  batched_buffers(ctx, cg, &bl);
+  bl.rs_floats = 0;
+  bl.stride = bl.a_floats + bl.b_floats + bl.q_floats;
+  const int64_t blocks = (k + 63) / 64;
+  int64_t g = (int64_t)ctx->num_cus * 2;
+  bl.grid = (int)(blocks < g ? blocks : g);
+  bl.records = paired ? k / 2 : k;
+  bl.slots = paired ? 32 : 64;
+  bl.deg_blocks = (bl.records + bl.slots - 1) / bl.slots;
+  bl.eb_stride = bl.eb_words;
+  int occ = (int)(kLdsLimit / bl.stream_lds);
+  if (occ > 2048 / kSThreads) occ = 2048 / kSThreads;
+  if (occ < 1) occ = 1;
+  const int64_t groups = (bl.records + (1 << bl.stream_lr) - 1) >> bl.stream_lr;
+  int64_t sg = (int64_t)ctx->num_cus * occ;
+  bl.stream_grid = (int)(groups < sg ? groups : sg);
+  return bl;
+}
+
+size_t stream_bytes(const BatchedLayout& bl, const ds_cgraph* cg) {
+  const size_t Wn = (size_t)(cg->info.num_players + 63) / 64;
+  return ds_align((size_t)cg->info.num_players * 4) + ds_align((size_t)cg->info.num_nodes * 4) + ds_align((size_t)bl.records * 4) +
+         ds_align(Wn * 8) + ds_align(Wn * 4) + ds_align((size_t)bl.E_need * 4 + 4) + ds_scan_arena_bytes((int64_t)Wn) +
+         ds_align((size_t)bl.deg_blocks * cg->info.num_nodes * bl.slots * 2) + ds_align((size_t)bl.records * bl.eb_stride * 4);
+}
+
+template <bool EXT>
+int launch_batched(ds_ctx* ctx, const BatchedLayout& bl, const BatchedArgs& b, int grid) {
+  const void* fn;
+  if (bl.deg_lds && bl.csr_lds) fn = (const void*)masked_gcn_eval_batched_kernel<true, true, EXT>;
+  else if (bl.deg_lds) fn = (const void*)masked_gcn_eval_batched_kernel<true, false, EXT>;
+  else if (bl.csr_lds) fn = (const void*)masked_gcn_eval_batched_kernel<false, true, EXT>;
+  else fn = (const void*)masked_gcn_eval_batched_kernel<false, false, EXT>;
+  if (bl.lds_bytes > 48 * 1024)
+    DS_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bl.lds_bytes));
+  if (bl.deg_lds && bl.csr_lds)
+    hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, true, EXT>), dim3(grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+  else if (bl.deg_lds)
+    hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, false, EXT>), dim3(grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+  else if (bl.csr_lds)
+    hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, true, EXT>), dim3(grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+  else
+    hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, false, EXT>), dim3(grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
 }
 }  // namespace
 
@@ -1000,8 +1462,15 @@ size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
   const EvalLayout lay = make_layout(ctx, cg);
   const int grid = grid_for(ctx, lay, k > 1 ? k : 1);
   const size_t W = (cg->info.num_players + 63) / 64;
-  const BatchedLayout bl = make_batched_layout(ctx, cg, k);
-  const size_t batched = bl.use ? ds_align((size_t)bl.stride * 4 * bl.grid) : 0;
+  const int path = ctx->tuning.eval_path;
+  BatchedLayout bl;
+  memset(&bl, 0, sizeof(bl));
+  if (path == 0 || path == 2) bl = make_batched_layout(ctx, cg, k);
+  size_t batched = bl.use ? ds_align((size_t)bl.stride * 4 * bl.grid) : 0;
+  if (!bl.use && (path == 0 || path == 3)) {
+    bl = make_stream_layout(ctx, cg, k, 0);  // the unpaired form is the larger one
+    if (bl.use) batched = ds_align((size_t)bl.stride * 4 * bl.grid) + stream_bytes(bl, cg);
+  }
   // the last three terms: what ds_prepare_model allocates (full mask row, logits, one workgroup's scratch)
   return ds_align((size_t)lay.gws_floats * 4 * grid) + batched + ds_align(W * 8 + 8) + ds_align(ctx->dims[ctx->L] * 4 + 8) +
          ds_align((size_t)lay.gws_floats * 4) + 1024;
@@ -1046,26 +1515,115 @@ int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg) {
   return DS_OK;
 }
 
-// batch_rows < 0: the workspace is bounded (it is not the context's own arena): fit the launch into it
-int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y, int batch_rows) {
+// flags: DS_EVAL_BOUNDED: the workspace is bounded (it is not the context's own arena): fit the launch into it;
+// DS_EVAL_PAIRED: rows 2r and 2r+1 are complementary pairs (the sampler's layout)
+int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y, int flags, const int32_t* sz) {
   if (ctx->model_kind == DS_MODEL_GAT) return ds_gat_eval_impl(ctx, cg, Z, k, score, y);
   DS_TRY(ds_prepare_model(ctx, cg));
   if (k <= 0) return DS_OK;
+  const bool bounded = (flags & DS_EVAL_BOUNDED) != 0;
+  const int paired = (flags & DS_EVAL_PAIRED) != 0 && (k & 1) == 0;
   const EvalLayout lay = make_layout(ctx, cg);
-  const BatchedLayout bl = make_batched_layout(ctx, cg, k);
-  // a bounded workspace (the entry point that may not allocate) runs fewer workgroups at a time instead of failing
-  const size_t avail = ctx->arena_bytes - ctx->arena_used > 512 ? ctx->arena_bytes - ctx->arena_used - 512 : 0;
+  // which kernel: short mask rows -> one coalition per lane with everything on chip; long rows -> the streaming
+  // kernel + the same kernel on its compact output; otherwise (few rows, very wide graphs) one workgroup per
+  // coalition. ds_tuning.eval_path forces one of them where it applies (a test hook).
+  const int path = ctx->tuning.eval_path;
+  BatchedLayout bl;
+  memset(&bl, 0, sizeof(bl));
+  if (path == 0 || path == 2) bl = make_batched_layout(ctx, cg, k);
+  if (!bl.use && (path == 0 || path == 3)) bl = make_stream_layout(ctx, cg, k, paired);
   if (bl.use) {
+    const int64_t n = cg->info.num_players;
+    BatchedArgs b;
+    memset(&b, 0, sizeof(b));
+    fill_args(ctx, cg, lay, &b.e);
+    DS_TRY(ds_kernel_mark(ctx, 0, 0));
+    if (bl.ext) {
+      uint32_t* pab = (uint32_t*)ds_arena_alloc(ctx, (size_t)n * 4);
+      int32_t* a_end = (int32_t*)ds_arena_alloc(ctx, (size_t)cg->info.num_nodes * 4);
+      const int64_t Wn = (n + 63) / 64;
+      uint64_t* nmask = (uint64_t*)ds_arena_alloc(ctx, (size_t)Wn * 8);
+      int32_t* nbase = (int32_t*)ds_arena_alloc(ctx, (size_t)Wn * 4);
+      int32_t* erank = (int32_t*)ds_arena_alloc(ctx, (size_t)(bl.E_need > 0 ? bl.E_need : 1) * 4);
+      int32_t* sizes = sz ? nullptr : (int32_t*)ds_arena_alloc(ctx, (size_t)bl.records * 4);
+      uint16_t* deg = (uint16_t*)ds_arena_alloc(ctx, (size_t)bl.deg_blocks * cg->info.num_nodes * bl.slots * 2);
+      uint32_t* ebits = (uint32_t*)ds_arena_alloc(ctx, (size_t)bl.records * bl.eb_stride * 4);
+      if (!pab || !a_end || !nmask || !nbase || !erank || (!sz && !sizes) || !deg || !ebits)
+        return ds_fail(ctx, bounded ? DS_ECAPACITY : DS_EINTERNAL, "eval: workspace exhausted (%lld records of %lld bytes)",
+                       (long long)bl.records, (long long)(cg->info.num_nodes * 2 + bl.eb_stride * 4));
+      hipLaunchKernelGGL(pack_endpoints_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, cg->pl, n, pab, a_end);
+      // the players whose bits layer 1 reads: their words' masks, the rank of every such player, the rank per entry
+      hipLaunchKernelGGL(zero_u64_kernel, dim3((unsigned)((Wn + 255) / 256)), dim3(256), 0, ctx->stream, nmask, Wn);
+      if (bl.E_need > 0)
+        hipLaunchKernelGGL(need_mark_kernel, dim3((unsigned)((bl.E_need + 255) / 256)), dim3(256), 0, ctx->stream, cg->eid, bl.E_need,
+                           (unsigned long long*)nmask);
+      hipLaunchKernelGGL(need_count_kernel, dim3((unsigned)((Wn + 255) / 256)), dim3(256), 0, ctx->stream, nmask, Wn, nbase);
+      DS_TRY(ds_scan_exclusive_i32(ctx, nbase, nbase, Wn, nullptr));
+      if (bl.E_need > 0)
+        hipLaunchKernelGGL(need_rank_kernel, dim3((unsigned)((bl.E_need + 255) / 256)), dim3(256), 0, ctx->stream, cg->eid, bl.E_need,
+                           nmask, nbase, erank);
+      StreamArgs sa;
+      memset(&sa, 0, sizeof(sa));
+      sa.V = (int32_t)cg->info.num_nodes;
+      sa.n = (int32_t)n;
+      sa.directed = cg->info.directed;
+      sa.E_need = bl.E_need;
+      sa.W = (n + 63) / 64;
+      sa.rows = bl.records;
+      sa.row_stride = paired ? 2 * sa.W : sa.W;
+      sa.Z = Z;
+      sa.pab = pab;
+      sa.a_end = a_end;
+      sa.row_ptr = cg->row_ptr;
+      sa.nmask = nmask;
+      sa.nbase = nbase;
+      sa.eb_words = bl.eb_words;
+      sa.deg_out = deg;
+      sa.ebits_out = ebits;
+      sa.lr = bl.stream_lr;
+      sa.cnt_words = bl.cnt_words;
+      sa.slots = bl.slots;
+      sa.eb_stride = bl.eb_stride;
+      DS_TRY(ds_kernel_mark(ctx, 4, 0));
+      if (sz) {  // the sampler's sizes: row r of this launch is row r (or 2r) of the mask matrix
+        sa.sizes = sz;
+        sa.size_step = paired ? 2 : 1;
+      } else {
+        int64_t pg = (bl.records * 64 + kThreads - 1) / kThreads;
+        if (pg > (int64_t)ctx->num_cus * 32) pg = (int64_t)ctx->num_cus * 32;
+        hipLaunchKernelGGL(row_popcount_kernel, dim3((unsigned)pg), dim3(kThreads), 0, ctx->stream, Z, bl.records, sa.row_stride, sa.W, sizes);
+        sa.sizes = sizes;
+        sa.size_step = 1;
+      }
+      {
+        const void* fn;
+        void (*kern)(StreamArgs);
+        if (paired) kern = bl.stream_lr == 3 ? stream_degrees_kernel<true, 3> : bl.stream_lr == 2 ? stream_degrees_kernel<true, 2> : stream_degrees_kernel<true, 1>;
+        else kern = bl.stream_lr == 3 ? stream_degrees_kernel<false, 3> : bl.stream_lr == 2 ? stream_degrees_kernel<false, 2> : stream_degrees_kernel<false, 1>;
+        fn = (const void*)kern;
+        if (bl.stream_lds > 48 * 1024)
+          DS_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bl.stream_lds));
+        hipLaunchKernelGGL(kern, dim3(bl.stream_grid), dim3(kSThreads), bl.stream_lds, ctx->stream, sa);
+      }
+      DS_HIP(ctx, hipGetLastError());
+      DS_TRY(ds_kernel_mark(ctx, 4, 1));
+      b.ext_deg = deg;
+      b.ext_bits = ebits;
+      b.erank = erank;
+      b.eb_stride = bl.eb_stride;
+      b.ext_paired = paired;
+      b.eb_words = bl.eb_words;
+    }
+    // a bounded workspace (the entry point that may not allocate) runs fewer workgroups at a time instead of failing
+    const size_t avail = ctx->arena_bytes - ctx->arena_used > 512 ? ctx->arena_bytes - ctx->arena_used - 512 : 0;
     int bgrid = bl.grid;
-    if (batch_rows < 0) {
+    if (bounded) {
       const size_t fit = avail / ((size_t)bl.stride * 4);
       if (fit < 1) return ds_fail(ctx, DS_ECAPACITY, "eval: one workgroup needs %zu bytes of scratch, %zu are left", (size_t)bl.stride * 4, avail);
       if ((size_t)bgrid > fit) bgrid = (int)fit;
     }
     float* scratch = (float*)ds_arena_alloc(ctx, (size_t)bl.stride * 4 * bgrid);
     if (!scratch) return ds_fail(ctx, DS_EINTERNAL, "eval: arena exhausted");
-    BatchedArgs b;
-    fill_args(ctx, cg, lay, &b.e);
     b.e.Z = Z;
     b.e.k = k;
     b.e.y = y;
@@ -1081,29 +1639,15 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
     b.q_floats = bl.q_floats;
     b.csr_lds_offset = bl.csr_off;
     b.zs_words = bl.zs_words;
-    DS_TRY(ds_kernel_mark(ctx, 0, 0));
-    const void* fn;
-    if (bl.deg_lds && bl.csr_lds) fn = (const void*)masked_gcn_eval_batched_kernel<true, true>;
-    else if (bl.deg_lds) fn = (const void*)masked_gcn_eval_batched_kernel<true, false>;
-    else if (bl.csr_lds) fn = (const void*)masked_gcn_eval_batched_kernel<false, true>;
-    else fn = (const void*)masked_gcn_eval_batched_kernel<false, false>;
-    if (bl.lds_bytes > 48 * 1024)
-      DS_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bl.lds_bytes));
-    if (bl.deg_lds && bl.csr_lds)
-      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, true>), dim3(bgrid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
-    else if (bl.deg_lds)
-      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, false>), dim3(bgrid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
-    else if (bl.csr_lds)
-      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, true>), dim3(bgrid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
-    else
-      hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, false>), dim3(bgrid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
-    DS_HIP(ctx, hipGetLastError());
+    if (bl.ext) DS_TRY(launch_batched<true>(ctx, bl, b, bgrid));
+    else DS_TRY(launch_batched<false>(ctx, bl, b, bgrid));
     return ds_kernel_mark(ctx, 0, 1);
   }
+  const size_t avail = ctx->arena_bytes - ctx->arena_used > 512 ? ctx->arena_bytes - ctx->arena_used - 512 : 0;
   int grid = grid_for(ctx, lay, k);
   float* gws = nullptr;
   if (lay.gws_floats) {
-    if (batch_rows < 0) {
+    if (bounded) {
       const size_t fit = avail / ((size_t)lay.gws_floats * 4);
       if (fit < 1) return ds_fail(ctx, DS_ECAPACITY, "eval: one workgroup needs %zu bytes of scratch, %zu are left", (size_t)lay.gws_floats * 4, avail);
       if ((size_t)grid > fit) grid = (int)fit;

@@ -80,8 +80,8 @@ struct ds_ctx {
   int64_t* h_mail;  // pinned host int64[64]
   int num_cus;
   hipEvent_t ev[6];
-  hipEvent_t kev[8];   // begin/end pairs: 0 masked inference, 1 Gram, 2 Cholesky, 3 CGLS loop
-  bool kev_set[4];
+  hipEvent_t kev[10];  // begin/end pairs: 0 masked inference, 1 Gram, 2 Cholesky, 3 CGLS loop, 4 mask-streaming kernel
+  bool kev_set[5];
   std::vector<ds_cgraph*> graphs;
   // one released computational-graph block is kept for the next extraction (no malloc/free per explanation)
   void* cg_spare;
@@ -148,8 +148,11 @@ size_t ds_scan_arena_bytes(int64_t count);
 int ds_extract_impl(ds_ctx* ctx, int64_t target, int hops, int directed, ds_cgraph** out);
 int ds_validate_csr(ds_ctx* ctx);
 
-int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y,
-                 int batch_rows);
+#define DS_EVAL_BOUNDED 1  // the workspace is not the context's own arena: fit the launch into what is there
+#define DS_EVAL_PAIRED 2   // rows 2r, 2r+1 are complementary pairs: only row 2r of each is read
+// sz: coalition size of every row (the sampler's output) or nullptr
+int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y, int flags,
+                 const int32_t* sz = nullptr);
 int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg);  // shared first transform + predicted class
 // the file-scope device array behind ds_eval_noalloc: address look-up (once per device, that device current)
 // and the pointer found

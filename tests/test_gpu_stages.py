@@ -197,12 +197,28 @@ def _eval_case(w, hops, directed, score, biases, rows, rng, tol=1e-5, layers=Non
         bits[i] = rng.random(n) < rng.random() ** 2
     bits[rows - 1] = ~bits[rows - 2]
     Z = torch.from_numpy(sampling.pack_rows(bits).view(np.int64)).cuda()
-    y, pc = ctx.eval(cg, Z, score)
     ref = f.batch(bits)
-    assert pc == f.pred_class
-    err = np.abs(y.cpu().numpy().astype(np.float64) - ref).max()
     scale = max(1.0, np.abs(ref).max())
-    assert err <= tol * scale, f"max |y - oracle| = {err}"
+    # every inference kernel on the same rows: the size-based choice, then each kernel forced (one workgroup per
+    # coalition; one coalition per lane with the masks on chip; the mask-streaming kernel + layers on its output)
+    from paper_2506_22668_amd import Tuning
+    for path in (0, 1, 2, 3):
+        ctx.set_tuning(Tuning(eval_path=path))
+        y, pc = ctx.eval(cg, Z, score)
+        assert pc == f.pred_class
+        err = np.abs(y.cpu().numpy().astype(np.float64) - ref).max()
+        assert err <= tol * scale, f"path {path}: max |y - oracle| = {err}"
+    # rows as complementary pairs (only the even rows are read): masks 2r+1 = complement of 2r
+    if rows % 2 == 0 and n > 0:
+        pbits = bits.copy()
+        pbits[1::2] = ~pbits[0::2]
+        Zp = torch.from_numpy(sampling.pack_rows(pbits).view(np.int64)).cuda()
+        refp = f.batch(pbits)
+        for path in (0, 3):
+            ctx.set_tuning(Tuning(eval_path=path))
+            y, pc = ctx.eval(cg, Zp, score, pairs=True)
+            err = np.abs(y.cpu().numpy().astype(np.float64) - refp).max()
+            assert err <= tol * max(1.0, np.abs(refp).max()), f"pairs, path {path}: max |y - oracle| = {err}"
     ctx.cgraph_free(cg)
     ctx.close()
 
