@@ -3,9 +3,15 @@
 // Paper, "Distributed Model Prediction": the GNN is evaluated once per sampled
 // sub-graph; the paper batches by stacking block-diagonal copies of the adjacency
 // and multiplying element-wise with a block-diagonal mask. Here the mask bits are
-// read in place: one workgroup evaluates one coalition at a time with every
-// per-coalition intermediate in LDS, so nothing but the mask row is streamed from
-// HBM and nothing but one float is written back.
+// read in place by one of three kernels, chosen by the size of the problem:
+//   * few coalitions, or graphs too wide for the others: one workgroup per coalition, every per-coalition
+//     intermediate in LDS (masked_gcn_eval_kernel);
+//   * short mask rows (up to 12,288 players): one coalition per lane, 64 per workgroup, masks, degrees and the
+//     local CSR on chip, the first layer on the matrix cores; per-coalition activations of later layers go
+//     through a per-workgroup scratch in global memory (masked_gcn_eval_batched_kernel);
+//   * long mask rows: a streaming kernel reads each row once (of a complementary pair: only one member) and
+//     reduces it to node degrees and the bits of the entries layer 1 reads (stream_degrees_kernel); the
+//     one-coalition-per-lane kernel then runs the layers from those compact arrays.
 //
 // GCN layer under a coalition S (Kipf & Welling, as cited by the paper; degrees
 // renormalised per coalition):  A~ = A_S + I, d_i = row sum of A~,
@@ -321,6 +327,7 @@ struct BatchedArgs {
   // complements) or per row
   const uint16_t* ext_deg;
   const uint32_t* ext_bits;   // [record][eb_stride]: bit r = mask bit of the needed player of rank r
+  const uint16_t* fdeg2;      // [V]: deg_full(v) + 2
   const int32_t* erank;       // [E_need]: rank of the player of CSR entry e among the needed players
   int64_t eb_stride;
   int32_t ext_paired, eb_words;  // ext_deg is [block][node][32 or 64 records]
@@ -370,7 +377,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
   auto rs_of = [&](int v) -> float {
     if (EXT) {
       int d = ext_deg_lane[(size_t)v * ext_slots];
-      if (ext_member) d = rp_[v + 1] - rp_[v] + 2 - d;  // the complement: d'(v) = deg_full(v) + 2 - d(v)
+      if (ext_member) d = b.fdeg2[v] - d;  // the complement: d'(v) = deg_full(v) + 2 - d(v)
       return __frsqrt_rn((float)d);
     }
     if (DEG_LDS) return __frsqrt_rn((float)degs[v * 64 + lane]);
@@ -463,12 +470,19 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
           for (int i = 0; i < 16; ++i) {
             acc[0][0][i] = 0.f; acc[0][1][i] = 0.f; acc[1][0][i] = 0.f; acc[1][1][i] = 0.f;
           }
+          int pv_next = 0, sv_next = t;  // sources and keys of the step's entries, fetched one step ahead
+          if (lane < kStageRows && s0 + lane < s1 && s0 + lane < e1) {
+            pv_next = key_[s0 + lane];
+            sv_next = col_[s0 + lane];
+          }
           for (int eb = s0; eb < s1; eb += kStageRows) {
             const int cnt = s1 - eb < kStageRows ? s1 - eb : kStageRows;
-            int pv = 0, sv = t;
-            if (lane < cnt && eb + lane < e1) {
-              pv = key_[eb + lane];
-              sv = col_[eb + lane];
+            const int pv = pv_next, sv = sv_next;
+            pv_next = 0;
+            sv_next = t;
+            if (lane < kStageRows && eb + kStageRows + lane < s1 && eb + kStageRows + lane < e1) {
+              pv_next = key_[eb + kStageRows + lane];
+              sv_next = col_[eb + kStageRows + lane];
             }
             float av[kStageRows / 2][2];
 #pragma unroll
@@ -752,6 +766,10 @@ __global__ __launch_bounds__(kThreads) void row_popcount_kernel(const uint64_t* 
 }
 
 // needed players: mark, (scan of the per-word counts on the host side), rank of every needed CSR entry's player
+__global__ void full_degree_kernel(const int32_t* row_ptr, int V, uint16_t* fdeg2) {
+  const int v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v < V) fdeg2[v] = (uint16_t)(row_ptr[v + 1] - row_ptr[v] + 2);
+}
 __global__ void zero_u64_kernel(uint64_t* x, int64_t count) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < count) x[i] = 0ull;
@@ -1385,7 +1403,7 @@ BatchedLayout make_stream_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t
 
 size_t stream_bytes(const BatchedLayout& bl, const ds_cgraph* cg) {
   const size_t Wn = (size_t)(cg->info.num_players + 63) / 64;
-  return ds_align((size_t)cg->info.num_players * 4) + ds_align((size_t)cg->info.num_nodes * 4) + ds_align((size_t)bl.records * 4) +
+  return ds_align((size_t)cg->info.num_players * 4) + ds_align((size_t)cg->info.num_nodes * 4) * 2 + ds_align((size_t)bl.records * 4) +
          ds_align(Wn * 8) + ds_align(Wn * 4) + ds_align((size_t)bl.E_need * 4 + 4) + ds_scan_arena_bytes((int64_t)Wn) +
          ds_align((size_t)bl.deg_blocks * cg->info.num_nodes * bl.slots * 2) + ds_align((size_t)bl.records * bl.eb_stride * 4);
 }
@@ -1541,6 +1559,7 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
     if (bl.ext) {
       uint32_t* pab = (uint32_t*)ds_arena_alloc(ctx, (size_t)n * 4);
       int32_t* a_end = (int32_t*)ds_arena_alloc(ctx, (size_t)cg->info.num_nodes * 4);
+      uint16_t* fdeg2 = (uint16_t*)ds_arena_alloc(ctx, (size_t)cg->info.num_nodes * 2);
       const int64_t Wn = (n + 63) / 64;
       uint64_t* nmask = (uint64_t*)ds_arena_alloc(ctx, (size_t)Wn * 8);
       int32_t* nbase = (int32_t*)ds_arena_alloc(ctx, (size_t)Wn * 4);
@@ -1548,10 +1567,12 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
       int32_t* sizes = sz ? nullptr : (int32_t*)ds_arena_alloc(ctx, (size_t)bl.records * 4);
       uint16_t* deg = (uint16_t*)ds_arena_alloc(ctx, (size_t)bl.deg_blocks * cg->info.num_nodes * bl.slots * 2);
       uint32_t* ebits = (uint32_t*)ds_arena_alloc(ctx, (size_t)bl.records * bl.eb_stride * 4);
-      if (!pab || !a_end || !nmask || !nbase || !erank || (!sz && !sizes) || !deg || !ebits)
+      if (!pab || !a_end || !fdeg2 || !nmask || !nbase || !erank || (!sz && !sizes) || !deg || !ebits)
         return ds_fail(ctx, bounded ? DS_ECAPACITY : DS_EINTERNAL, "eval: workspace exhausted (%lld records of %lld bytes)",
                        (long long)bl.records, (long long)(cg->info.num_nodes * 2 + bl.eb_stride * 4));
       hipLaunchKernelGGL(pack_endpoints_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, cg->pl, n, pab, a_end);
+      hipLaunchKernelGGL(full_degree_kernel, dim3((unsigned)((cg->info.num_nodes + 255) / 256)), dim3(256), 0, ctx->stream, cg->row_ptr,
+                         (int)cg->info.num_nodes, fdeg2);
       // the players whose bits layer 1 reads: their words' masks, the rank of every such player, the rank per entry
       hipLaunchKernelGGL(zero_u64_kernel, dim3((unsigned)((Wn + 255) / 256)), dim3(256), 0, ctx->stream, nmask, Wn);
       if (bl.E_need > 0)
@@ -1610,6 +1631,7 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
       b.ext_deg = deg;
       b.ext_bits = ebits;
       b.erank = erank;
+      b.fdeg2 = fdeg2;
       b.eb_stride = bl.eb_stride;
       b.ext_paired = paired;
       b.eb_words = bl.eb_words;
