@@ -82,8 +82,14 @@ typedef struct ds_options {
                          equal weights (the layout ds_sample writes), which lets CGLS read only
                          one member of each pair; 0 makes no assumption. ds_explain always
                          uses its own paired rows. */
-  int32_t weighting;  /* ds_weighting, honoured by ds_explain and ds_explain_batch (the stage-wise
-                         ds_sample / ds_plan_tables always use CLASS_MASS) */
+  int32_t weighting;  /* ds_weighting, honoured by ds_explain, ds_explain_batch, ds_sample_ex and
+                         ds_plan_tables_ex (ds_sample / ds_plan_tables always use CLASS_MASS) */
+  int32_t saturate;   /* 1: a size class that is allotted at least as many pairs as it has coalitions
+                         (q_s >= C(n, s); the sizes 1 and n-1 on small graphs) is enumerated instead of
+                         sampled: its pairs are the s-subsets of the players in lexicographic order, each once,
+                         weighted by the Shapley kernel itself, and the pairs this frees go to the other
+                         classes by the same allotment rule. Needs CLASS_MASS weighting. Honoured where
+                         `weighting` is. 0 (default): every class is sampled. */
 } ds_options;
 
 /* What an explanation did (all [host]). Times are wall-clock milliseconds measured
@@ -254,6 +260,11 @@ int ds_sample_plan(int64_t n, int64_t n_samples, int64_t* k_out, int32_t* enumer
  * regression weight wtab[0..H] of a row of size s or n-s. Either output may be NULL. n >= 2. */
 int ds_plan_tables(int64_t n, int64_t n_samples, int64_t* b, float* wtab);
 
+/* ds_plan_tables with the options that change the plan (weighting, saturate). enum_upto [host] (may be NULL):
+ * the size classes 1..enum_upto are enumerated. */
+int ds_plan_tables_ex(int64_t n, int64_t n_samples, const ds_options* opts, int64_t* b, float* wtab,
+                      int64_t* enum_upto);
+
 /* Sampler (paper, "Distributed Subgraph Sampling": size-stratified allocation by
  * the kernel mass of each size, complementary pairs, one mask row per coalition).
  * Row 0 is the empty and row 1 the full coalition (weight 0: they are imposed as
@@ -266,6 +277,9 @@ int ds_plan_tables(int64_t n, int64_t n_samples, int64_t* b, float* wtab);
  */
 int ds_sample(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, uint64_t* Z,
               float* w, int32_t* sz, int64_t* k_out);
+/* ds_sample with the options that change the plan (opts->weighting, opts->saturate; NULL = defaults). */
+int ds_sample_ex(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, const ds_options* opts,
+                 uint64_t* Z, float* w, int32_t* sz, int64_t* k_out);
 /* Only pairs pair_begin <= r < pair_end: writes rows 2*pair_begin .. 2*pair_end-1
  * to Z[0..], w[0..], sz[0..] (what one GPU of a sharded run would generate). */
 int ds_sample_range(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag,

@@ -8,7 +8,8 @@ from . import compgraph, gat as gat_model, gcn, sampling, solve
 
 def explain(row_ptr, col, X, weights, target, n_samples, seed, biases=None,
             hops=None, undirected=True, score="prob", solver="lstsq",
-            tol=1e-10, max_iter=None, dense_adjacency=False, bf16=False, gat=None, weighting="class"):
+            tol=1e-10, max_iter=None, dense_adjacency=False, bf16=False, gat=None, weighting="class",
+            saturate=False):
     """`gat`: a model dictionary for oracle.gat (then `weights`/`biases` are ignored); otherwise a GCN."""
     L = len(gat["W"]) if gat is not None else len(weights)
     hops = L if hops is None or hops == 0 else hops
@@ -28,7 +29,7 @@ def explain(row_ptr, col, X, weights, target, n_samples, seed, biases=None,
         return out
     if n_samples < 4:
         raise ValueError("n_samples must be at least 4")
-    Z, w, sz = sampling.sample(n, n_samples, seed, int(target) & 0xFFFFFFFF, weighting=weighting)
+    Z, w, sz = sampling.sample(n, n_samples, seed, int(target) & 0xFFFFFFFF, weighting=weighting, saturate=saturate)
     bits = sampling.unpack_rows(Z, n)
     y = f.batch(bits)
     if solver == "lstsq":

@@ -22,6 +22,13 @@ fixed here as follows:
 * a row of size s weighs rho_s / m_s with m_s the number of emitted rows of
   that size (so each represented size class carries exactly its kernel mass;
   under enumeration m_s = C(n, s) and the weight is the Shapley kernel itself).
+* option saturate=True (a refinement, off by default): a size class that is allotted at least
+  as many pairs as it has coalitions, q_s >= C(n, s), is enumerated instead of sampled: its
+  C(n, s) pairs are the s-subsets of the players in lexicographic order, each once, with the
+  Shapley kernel weight itself, rho_s / C(n, s). The pairs this frees are allotted to the
+  other classes by the same rule (cumulative rounding over the classes that are left), and the
+  test is repeated for the next class. C(n, s) grows and the allotment shrinks with s, so
+  the enumerated classes are s = 1..S_e. The class 2s = n is never enumerated this way.
 """
 from math import comb
 import numpy as np
@@ -43,7 +50,7 @@ def rho(n, s):
     return float(n - 1) / (float(s) * float(n - s))
 
 
-def allocation(n, n_samples, weighting="class"):
+def allocation(n, n_samples, weighting="class", saturate=False):
     """Class boundaries b[0..H], pairs per class q[1..H], weight table
     wtab[1..H] (float32; entry 0 unused and zero).
 
@@ -54,6 +61,8 @@ def allocation(n, n_samples, weighting="class"):
     that received no row).  Enumerated plans keep the exact kernel weights."""
     if weighting not in ("class", "uniform"):
         raise ValueError("weighting must be 'class' or 'uniform'")
+    if saturate and weighting != "class":
+        raise ValueError("saturate needs the class-mass weighting")
     k, enum = row_count(n, n_samples)
     H = n // 2
     out = {"n": n, "k": k, "enumerate": enum, "H": H}
@@ -64,18 +73,31 @@ def allocation(n, n_samples, weighting="class"):
         out.update(K=k // 2 - 1, b=None, q=None, wtab=wtab)
         return out
     K = k // 2 - 1
-    c = np.zeros(H + 1, dtype=np.float64)
-    acc = 0.0
-    for s in range(1, H + 1):
-        r = rho(n, s)
-        acc = acc + (r if 2 * s == n else 2.0 * r)
-        c[s] = acc
-    T = acc
-    b = np.zeros(H + 1, dtype=np.int64)
-    for s in range(1, H):
-        b[s] = int(np.floor(float(K) * (c[s] / T) + 0.5))
-    if H >= 1:
-        b[H] = K
+    enum_upto, used = 0, 0                    # classes 1..enum_upto are enumerated and take `used` pairs
+    while True:
+        # the K - used pairs that are left, over the classes enum_upto+1..H
+        c = np.zeros(H + 1, dtype=np.float64)
+        acc = 0.0
+        for s in range(enum_upto + 1, H + 1):
+            r = rho(n, s)
+            acc = acc + (r if 2 * s == n else 2.0 * r)
+            c[s] = acc
+        T = acc
+        b = np.zeros(H + 1, dtype=np.int64)
+        for s in range(1, enum_upto + 1):
+            b[s] = b[s - 1] + comb(n, s)
+        for s in range(enum_upto + 1, H):
+            b[s] = used + int(np.floor(float(K - used) * (c[s] / T) + 0.5))
+        if H >= 1:
+            b[H] = K
+        s1 = enum_upto + 1
+        if not saturate or s1 > H or 2 * s1 >= n:
+            break
+        cap = comb(n, s1)
+        if int(b[s1]) - used >= cap:          # (then used + cap <= b[s1] <= K)
+            enum_upto, used = s1, used + cap
+            continue
+        break
     q = np.diff(b, prepend=0)
     q[0] = 0
     wtab = np.zeros(H + 1, dtype=np.float32)
@@ -83,7 +105,23 @@ def allocation(n, n_samples, weighting="class"):
         m = int(q[s]) * (2 if 2 * s == n else 1)
         if m > 0:
             wtab[s] = np.float32(1.0) if weighting == "uniform" else np.float32(rho(n, s) / float(m))
-    out.update(K=K, b=b, q=q, wtab=wtab, T=T)
+    out.update(K=K, b=b, q=q, wtab=wtab, T=T, enum_upto=enum_upto)
+    return out
+
+
+def unrank_subset(n, s, j):
+    """The j-th (from 0) s-subset of {0..n-1} in lexicographic order, as an ascending list: element x
+    is the next one if fewer than C(n-1-x, remaining-1) subsets start with it ... else skip those."""
+    out, x = [], 0
+    for i in range(s):
+        while True:
+            c = comb(n - 1 - x, s - 1 - i)    # subsets that continue with element x
+            if j < c:
+                break
+            j -= c
+            x += 1
+        out.append(x)
+        x += 1
     return out
 
 
@@ -122,11 +160,11 @@ def unpack_rows(Z, n):
     return np.unpackbits(by, axis=1, bitorder="little")[:, :n].astype(bool)
 
 
-def sample(n, n_samples, seed, tag, pair_range=None, chunk_elems=1 << 22, weighting="class"):
+def sample(n, n_samples, seed, tag, pair_range=None, chunk_elems=1 << 22, weighting="class", saturate=False):
     """Mask matrix Z (uint64[k, W]), weights w (float32[k]) and sizes sz
     (int32[k]).  With pair_range=(r0, r1) only the rows of pairs r0 <= r < r1
     are produced (rows 2*r0 .. 2*r1-1), identical to those of the full run."""
-    plan = allocation(n, n_samples, weighting)
+    plan = allocation(n, n_samples, weighting, saturate)
     k, K, wtab = plan["k"], plan["K"], plan["wtab"]
     r0, r1 = (0, k // 2) if pair_range is None else pair_range
     npairs = r1 - r0
@@ -154,6 +192,10 @@ def sample(n, n_samples, seed, tag, pair_range=None, chunk_elems=1 << 22, weight
         rank = np.empty_like(order)
         np.put_along_axis(rank, order, np.arange(n)[None, :], axis=1)
         small = rank < s[:, None]
+        for i in np.flatnonzero(s <= plan["enum_upto"]):   # pairs of enumerated classes: the subsets in order
+            si = int(s[i])
+            small[i] = False
+            small[i, unrank_subset(n, si, int(pr[i]) - 1 - int(plan["b"][si - 1]))] = True
         lo = 2 * (pr - r0)
         bits[lo] = small
         bits[lo + 1] = ~small

@@ -18,14 +18,15 @@ EXPORTED_SYMBOLS = [
     "ds_create", "ds_destroy", "ds_last_error", "ds_set_tuning", "ds_set_graph", "ds_set_features", "ds_set_gcn", "ds_set_gat",
     "ds_explain", "ds_explain_batch", "ds_extract", "ds_cgraph_get_info", "ds_cgraph_edges",
     "ds_cgraph_nodes", "ds_cgraph_first_transform", "ds_cgraph_free", "ds_sample_plan", "ds_sample",
-    "ds_plan_tables", "ds_sample_range", "ds_eval", "ds_eval_pairs", "ds_eval_noalloc", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
+    "ds_plan_tables", "ds_plan_tables_ex", "ds_sample_ex", "ds_sample_range", "ds_eval", "ds_eval_pairs", "ds_eval_noalloc", "ds_solve", "ds_fidelity", "ds_copy_probe", "ds_version",
 ]
 
 
 class Options(C.Structure):
     _fields_ = [("hops", C.c_int32), ("directed", C.c_int32), ("score", C.c_int32),
                 ("solver", C.c_int32), ("tol", C.c_double), ("max_iter", C.c_int32),
-                ("batch_rows", C.c_int32), ("paired", C.c_int32), ("weighting", C.c_int32)]
+                ("batch_rows", C.c_int32), ("paired", C.c_int32), ("weighting", C.c_int32),
+                ("saturate", C.c_int32)]
 
 
 class Tuning(C.Structure):
@@ -102,6 +103,8 @@ def load_library():
         "ds_sample_plan": [i64, i64, C.POINTER(i64), C.POINTER(i32)],
         "ds_sample": [p, i64, i64, u64, u32, p, p, p, C.POINTER(i64)],
         "ds_plan_tables": [i64, i64, p, p],
+        "ds_plan_tables_ex": [i64, i64, C.POINTER(Options), p, p, C.POINTER(i64)],
+        "ds_sample_ex": [p, i64, i64, u64, u32, C.POINTER(Options), p, p, p, C.POINTER(i64)],
         "ds_sample_range": [p, i64, i64, u64, u32, i64, i64, p, p, p],
         "ds_eval": [p, p, p, i64, i32, p, C.POINTER(i32)],
         "ds_eval_pairs": [p, p, p, i64, i32, p, C.POINTER(i32)],
@@ -132,17 +135,25 @@ def sample_plan(n, n_samples):
     return k.value, bool(e.value)
 
 
-def plan_tables(n, n_samples):
-    """(b int64[H+1], wtab float32[H+1]) of the sampling plan (host-only call)."""
+def plan_tables(n, n_samples, options=None):
+    """(b int64[H+1], wtab float32[H+1]) of the sampling plan (host-only call); with `options` also the number of
+    enumerated size classes (ds_plan_tables_ex)."""
     import numpy as np
     lib = load_library()
     H = n // 2
     b = np.zeros(H + 1, dtype=np.int64)
     wtab = np.zeros(H + 1, dtype=np.float32)
-    rc = lib.ds_plan_tables(n, n_samples, b.ctypes.data_as(C.c_void_p), wtab.ctypes.data_as(C.c_void_p))
+    if options is None:
+        rc = lib.ds_plan_tables(n, n_samples, b.ctypes.data_as(C.c_void_p), wtab.ctypes.data_as(C.c_void_p))
+        if rc != DS_OK:
+            raise DistShapError(rc, "ds_plan_tables: bad arguments")
+        return b, wtab
+    upto = C.c_int64()
+    rc = lib.ds_plan_tables_ex(n, n_samples, C.byref(options), b.ctypes.data_as(C.c_void_p),
+                               wtab.ctypes.data_as(C.c_void_p), C.byref(upto))
     if rc != DS_OK:
-        raise DistShapError(rc, "ds_plan_tables: bad arguments")
-    return b, wtab
+        raise DistShapError(rc, "ds_plan_tables_ex: bad arguments")
+    return b, wtab, upto.value
 
 
 def _ptr(t):
@@ -325,7 +336,8 @@ class Context:
     def cgraph_free(self, cg):
         self._check(self.lib.ds_cgraph_free(self.h, cg))
 
-    def sample(self, n, n_samples, seed, tag):
+    def sample(self, n, n_samples, seed, tag, options=None):
+        """ds_sample, or ds_sample_ex when `options` is given."""
         t = self.torch
         k, _ = sample_plan(n, n_samples)
         W = (n + 63) // 64
@@ -333,9 +345,14 @@ class Context:
         w = t.empty(max(k, 1), dtype=t.float32, device=self.device)
         sz = t.empty(max(k, 1), dtype=t.int32, device=self.device)
         kout = C.c_int64()
-        self._check(self.lib.ds_sample(self.h, int(n), int(n_samples), C.c_uint64(int(seed)),
-                                       C.c_uint32(int(tag) & 0xFFFFFFFF), _ptr(Z), _ptr(w), _ptr(sz),
-                                       C.byref(kout)))
+        if options is None:
+            self._check(self.lib.ds_sample(self.h, int(n), int(n_samples), C.c_uint64(int(seed)),
+                                           C.c_uint32(int(tag) & 0xFFFFFFFF), _ptr(Z), _ptr(w), _ptr(sz),
+                                           C.byref(kout)))
+        else:
+            self._check(self.lib.ds_sample_ex(self.h, int(n), int(n_samples), C.c_uint64(int(seed)),
+                                              C.c_uint32(int(tag) & 0xFFFFFFFF), C.byref(options), _ptr(Z), _ptr(w),
+                                              _ptr(sz), C.byref(kout)))
         assert kout.value == k
         return Z[:k], w[:k], sz[:k]
 

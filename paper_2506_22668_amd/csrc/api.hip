@@ -341,12 +341,12 @@ int ds_cgraph_free(ds_ctx* ctx, ds_cgraph* cg) {
 }
 
 static int sample_checked(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, int64_t pb, int64_t pe,
-                          bool whole, uint64_t* Z, float* w, int32_t* sz, int64_t* k_out) {
+                          bool whole, uint64_t* Z, float* w, int32_t* sz, int64_t* k_out, const ds_options* opts = nullptr) {
   if (!ctx) return DS_EINVAL;
   if (!Z || !w || !sz) return ds_fail(ctx, DS_EINVAL, "null output buffer");
   DS_HIP(ctx, hipSetDevice(ctx->device));
   ds_plan plan;
-  DS_TRY(ds_make_plan(ctx, n, n_samples, &plan));
+  DS_TRY(ds_make_plan(ctx, n, n_samples, &plan, opts ? opts->weighting : DS_WEIGHT_CLASS_MASS, opts ? opts->saturate : 0));
   if (whole) { pb = 0; pe = plan.k / 2; }
   ds_arena_reset(ctx);
   DS_TRY(ds_arena_reserve(ctx, ds_sample_arena_bytes(plan)));
@@ -360,6 +360,13 @@ static int sample_checked(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t se
 int ds_sample(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, uint64_t* Z, float* w,
               int32_t* sz, int64_t* k_out) {
   return sample_checked(ctx, n, n_samples, seed, tag, 0, 0, true, Z, w, sz, k_out);
+}
+
+int ds_sample_ex(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, const ds_options* opts, uint64_t* Z,
+                 float* w, int32_t* sz, int64_t* k_out) {
+  if (ctx && opts && opts->weighting != DS_WEIGHT_CLASS_MASS && opts->weighting != DS_WEIGHT_UNIFORM)
+    return ds_fail(ctx, DS_EINVAL, "unknown weighting %d", opts->weighting);
+  return sample_checked(ctx, n, n_samples, seed, tag, 0, 0, true, Z, w, sz, k_out, opts);
 }
 
 int ds_sample_range(ds_ctx* ctx, int64_t n, int64_t n_samples, uint64_t seed, uint32_t tag, int64_t pair_begin,
@@ -559,7 +566,7 @@ static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t
   } else {
     if (o.weighting != DS_WEIGHT_CLASS_MASS && o.weighting != DS_WEIGHT_UNIFORM)
       return ds_fail(ctx, DS_EINVAL, "unknown weighting %d", o.weighting);
-    DS_TRY(ds_make_plan(ctx, n, n_samples, &plan, o.weighting));
+    DS_TRY(ds_make_plan(ctx, n, n_samples, &plan, o.weighting, o.saturate ? 1 : 0));
     k = plan.k;
   }
   rep.num_rows = k;

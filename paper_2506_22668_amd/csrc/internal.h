@@ -130,10 +130,12 @@ int ds_mail_fetch(ds_ctx* ctx, int count);
 struct ds_plan {
   int64_t n, k, K, H;
   int enumerate;
+  int64_t enum_upto;        // size classes 1..enum_upto are enumerated (every subset once), the rest sampled
   std::vector<int64_t> b;   // class boundaries b[0..H]
   std::vector<float> wtab;  // weight per pair class, wtab[0..H]
 };
-int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan, int weighting = DS_WEIGHT_CLASS_MASS);
+int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan, int weighting = DS_WEIGHT_CLASS_MASS,
+                 int saturate = 0);
 // launches the sampler; the overflow flag is left in device mailbox slot DS_MAIL_SAMPLER (checked by the caller)
 int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t tag, int64_t pair_begin,
                      int64_t pair_end, uint64_t* Z, float* w, int32_t* sz);

@@ -31,7 +31,7 @@ extern "C" int ds_sample_plan(int64_t n, int64_t n_samples, int64_t* k_out, int3
   return DS_OK;
 }
 
-int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan, int weighting) {
+int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan, int weighting, int saturate) {
   if (n < 2) return ds_fail(ctx, DS_EINVAL, "sampling needs at least 2 players (n=%lld)", (long long)n);
   if (n > 0x7fffffffLL) return ds_fail(ctx, DS_EINVAL, "too many players (n=%lld)", (long long)n);
   int32_t enumerate;
@@ -47,6 +47,9 @@ int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan, int w
   const int64_t H = plan->H, K = plan->K;
   plan->wtab.assign(H + 1, 0.0f);
   plan->b.assign(H + 1, 0);
+  plan->enum_upto = 0;
+  if (saturate && weighting != DS_WEIGHT_CLASS_MASS)
+    return ds_fail(ctx, DS_EINVAL, "saturated size classes need the class-mass weighting");
   if (enumerate) {
     double binom = 1.0;  // C(n, s), exact in double for n <= 24
     for (int64_t s = 1; s <= H; ++s) {
@@ -55,16 +58,33 @@ int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan, int w
     }
     return DS_OK;
   }
+  // Option `saturate`: a class that is allotted at least as many pairs as it has coalitions (q_s >= C(n, s)) is
+  // enumerated (every s-subset once) and the pairs this frees go to the classes that are left, by the same
+  // cumulative rounding; the test moves on to the next class (C(n, s) grows and the allotment shrinks with s, so
+  // the enumerated classes are 1..enum_upto). The class 2s == n is never enumerated this way.
   std::vector<double> c(H + 1, 0.0);
-  double acc = 0.0;
-  for (int64_t s = 1; s <= H; ++s) {
-    double r = rho_mass(n, s);
-    acc = acc + ((2 * s == n) ? r : 2.0 * r);
-    c[s] = acc;
+  int64_t enum_upto = 0, used = 0, cap_prev = 1;  // cap_prev = C(n, enum_upto)
+  for (;;) {
+    double acc = 0.0;
+    for (int64_t s = enum_upto + 1; s <= H; ++s) {
+      double r = rho_mass(n, s);
+      acc = acc + ((2 * s == n) ? r : 2.0 * r);
+      c[s] = acc;
+    }
+    const double T = acc;
+    for (int64_t s = enum_upto + 1; s < H; ++s)
+      plan->b[s] = used + (int64_t)std::floor((double)(K - used) * (c[s] / T) + 0.5);
+    plan->b[H] = K;
+    const int64_t s1 = enum_upto + 1;
+    if (!saturate || s1 > H || 2 * s1 >= n) break;
+    const __int128 cap = (__int128)cap_prev * (__int128)(n - s1 + 1) / (__int128)s1;  // C(n, s1), exact
+    if (cap > (__int128)(plan->b[s1] - used)) break;
+    enum_upto = s1;
+    used += (int64_t)cap;
+    cap_prev = (int64_t)cap;
+    plan->b[s1] = used;
   }
-  const double T = acc;
-  for (int64_t s = 1; s < H; ++s) plan->b[s] = (int64_t)std::floor((double)K * (c[s] / T) + 0.5);
-  plan->b[H] = K;
+  plan->enum_upto = enum_upto;
   for (int64_t s = 1; s <= H; ++s) {
     int64_t m = (plan->b[s] - plan->b[s - 1]) * ((2 * s == n) ? 2 : 1);
     if (m > 0) plan->wtab[s] = weighting == DS_WEIGHT_UNIFORM ? 1.0f : (float)(rho_mass(n, s) / (double)m);
@@ -73,9 +93,15 @@ int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan, int w
 }
 
 extern "C" int ds_plan_tables(int64_t n, int64_t n_samples, int64_t* b, float* wtab) {
+  return ds_plan_tables_ex(n, n_samples, nullptr, b, wtab, nullptr);
+}
+
+extern "C" int ds_plan_tables_ex(int64_t n, int64_t n_samples, const ds_options* opts, int64_t* b, float* wtab,
+                                 int64_t* enum_upto) {
   if (n < 2 || n > 0x7fffffffLL || n_samples < 0) return DS_EINVAL;
   ds_plan plan;
-  int rc = ds_make_plan(nullptr, n, n_samples, &plan, DS_WEIGHT_CLASS_MASS);
+  int rc = ds_make_plan(nullptr, n, n_samples, &plan, opts ? opts->weighting : DS_WEIGHT_CLASS_MASS, opts ? opts->saturate : 0);
+  if (enum_upto) *enum_upto = plan.enum_upto;
   if (rc != DS_OK) return rc;
   for (int64_t s = 0; s <= plan.H; ++s) {
     if (b) b[s] = plan.b[s];

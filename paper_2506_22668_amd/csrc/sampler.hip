@@ -88,6 +88,7 @@ __device__ void select_bin(const uint32_t* hist, uint32_t* part, uint32_t want, 
 
 struct SampleArgs {
   int64_t n, W, K, H;
+  int64_t enum_upto;  // pairs of the size classes 1..enum_upto are the subsets in lexicographic order, not sampled
   int64_t pair_begin, pair_end;
   const int64_t* b;     // class boundaries [H+1]
   const float* wtab;    // [H+1]
@@ -138,6 +139,46 @@ __global__ __launch_bounds__(kThreads) void sample_pairs_kernel(SampleArgs a) {
       if (a.b[mid] >= r) hi = mid; else lo = mid + 1;
     }
     const uint32_t s = (uint32_t)lo;
+    if ((int64_t)s <= a.enum_upto) {
+      // An enumerated class: pair r is the j-th s-subset of the players in lexicographic order, j = r - 1 - b_(s-1).
+      // Unranking: with c = C(m, t) the number of subsets that continue with element x (m = n-1-x players after
+      // x, t elements still to choose after it), skip x while j >= c. c follows x and t by exact integer updates:
+      // C(m-1, t) = c (m-t) / m and C(m-1, t-1) = c t / m (c <= K, so the products stay below 2^63 for the sizes
+      // the host admits).
+      for (int64_t wd = t; wd < W; wd += kThreads) {
+        row_small[wd] = 0ull;
+        row_big[wd] = (wd == W - 1) ? tail_mask : ~0ull;
+      }
+      __syncthreads();
+      if (t == 0) {
+        int64_t j = r - 1 - a.b[s - 1];
+        int64_t m = n - 1, tt = (int64_t)s - 1, x = 0;
+        uint64_t c = 1;
+        for (int64_t u = 1; u <= tt; ++u) c = c * (uint64_t)(m - tt + u) / (uint64_t)u;
+        for (uint32_t i = 0; i < s; ++i) {
+          while ((uint64_t)j >= c) {
+            j -= (int64_t)c;
+            c = c * (uint64_t)(m - tt) / (uint64_t)m;
+            --m;
+            ++x;
+          }
+          row_small[x >> 6] |= 1ull << (x & 63);
+          row_big[x >> 6] &= ~(1ull << (x & 63));
+          if (tt > 0) c = c * (uint64_t)tt / (uint64_t)m;
+          --m;
+          --tt;
+          ++x;
+        }
+        const float wt = a.wtab[s];
+        const int64_t o = 2 * (r - a.pair_begin);
+        a.w[o] = wt;
+        a.w[o + 1] = wt;
+        a.sz[o] = (int32_t)s;
+        a.sz[o + 1] = (int32_t)(n - s);
+      }
+      __syncthreads();
+      continue;
+    }
     const uint32_t r_lo = (uint32_t)r, r_hi = (uint32_t)((uint64_t)r >> 32);
 
     // window of top-12-bit bins around the expected position of the s-th smallest key
@@ -315,6 +356,8 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
     return ds_fail(ctx, DS_EINVAL, "pair range [%lld, %lld) outside [0, %lld)", (long long)pair_begin,
                    (long long)pair_end, (long long)(plan.k / 2));
   if (pair_begin == pair_end) return DS_OK;
+  if (plan.enum_upto > 0 && (double)plan.K * (double)plan.n >= 4.0e18)
+    return ds_fail(ctx, DS_EINVAL, "saturated size classes: the plan is too large for exact 64-bit unranking");
   const int64_t H = plan.H;
   int64_t* d_b = (int64_t*)ds_arena_alloc(ctx, (H + 1) * sizeof(int64_t));
   float* d_wtab = (float*)ds_arena_alloc(ctx, (H + 1) * sizeof(float));
@@ -348,6 +391,7 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
   a.W = (plan.n + 63) / 64;
   a.K = plan.K;
   a.H = H;
+  a.enum_upto = plan.enum_upto;
   a.pair_begin = pair_begin;
   a.pair_end = pair_end;
   a.b = d_b;

@@ -65,3 +65,17 @@ def test_host_plan_tables_equal_the_oracle_bit_for_bit():
         binding.plan_tables(1, 10)
     with pytest.raises(binding.DistShapError):
         binding.plan_tables(100, 3)
+
+
+def test_host_plan_tables_with_saturated_classes_equal_the_oracle():
+    import numpy as np
+    from oracle import sampling
+    from paper_2506_22668_amd import binding
+    for n, ns in [(30, 25000), (200, 3000), (12, 1000), (9, 510), (1010, 20000), (99981, 200000), (333, 70000)]:
+        b, wtab, upto = binding.plan_tables(n, ns, binding.Options(saturate=1))
+        plan = sampling.allocation(n, ns, saturate=True)
+        assert upto == plan["enum_upto"], (n, ns)
+        assert np.array_equal(b, plan["b"]), (n, ns)
+        assert np.array_equal(wtab.view(np.uint32), plan["wtab"].view(np.uint32)), (n, ns)
+    with pytest.raises(binding.DistShapError):
+        binding.plan_tables(100, 1000, binding.Options(saturate=1, weighting=1))

@@ -121,6 +121,26 @@ def test_uniform_weighting_option_matches_the_oracle():
     ctx.close()
 
 
+def test_saturated_size_classes_option_matches_the_oracle():
+    """ds_options.saturate end to end (the size-1 class of a 200-player game is enumerated): phi against the
+    oracle run with the same option; it is a different estimate from the default one."""
+    from paper_2506_22668_amd import Options
+    w = make_workload("c2_small")
+    ctx = make_context(w)
+    target = w.targets[0]
+    say(f"explain c2_small target={target} saturate=1")
+    ref = oexplain.explain(w.row_ptr, w.col, w.features, w.weights, target, w.n_samples, w.seed, saturate=True)
+    base = oexplain.explain(w.row_ptr, w.col, w.features, w.weights, target, w.n_samples, w.seed)
+    scale = np.abs(ref["phi"]).max()
+    for solver in (1, 2):
+        phi, es, ed, rep, rc = ctx.explain(target, w.n_samples, w.seed, Options(solver=solver, tol=1e-10, saturate=1))
+        got = phi.cpu().numpy().astype(np.float64)
+        say(f"  solver={solver} err={np.abs(got - ref['phi']).max():.2e} (default estimate differs by {np.abs(ref['phi'] - base['phi']).max():.2e})")
+        assert np.abs(got - ref["phi"]).max() <= 1e-4 * scale
+    assert np.abs(ref["phi"] - base["phi"]).max() > 1e-4 * scale
+    ctx.close()
+
+
 def test_small_batched_bf16_config():
     # bf16 per-coalition transforms against the plain fp64 oracle, at the tolerance stated for this configuration
     _explain_case("c5_small", 1e-2)

@@ -181,8 +181,15 @@ def test_config5_all_64_targets_bf16_gram_cholesky():
         got = phi[off[i]:off[i + 1]].cpu().numpy().astype(np.float64)
         assert reps[i].num_players == M[i] and reps[i].num_rows == 50_000
         assert abs(got.sum() - (reps[i].f_full - reps[i].f_empty)) <= 1e-5, i
-    order = np.argsort(M, kind="stable")
-    picked = [int(order[j]) for j in np.unique(np.linspace(0, 63, 8).round().astype(int))]
+    # Eight games spread over the sizes up to 9,000 players get the full comparison (the oracle's conjugate-gradient
+    # solve needs thousands of steps on the larger ones, whose regressions have barely more rows than unknowns);
+    # the largest game of all gets every check but that one: the oracle recomputes the normal-equation residual of
+    # the GPU's solution instead.
+    order = [int(i) for i in np.argsort(M, kind="stable")]
+    small_enough = [i for i in order if M[i] <= 9000]
+    picked = [small_enough[j] for j in np.unique(np.linspace(0, len(small_enough) - 1, 8).round().astype(int))]
+    assert len(picked) == 8
+    picked.append(order[-1])
     for rank, i in enumerate(picked):
         target, n = w.targets[i], M[i]
         say(f"c5: target {target} ({n} players): stages")
@@ -193,7 +200,7 @@ def test_config5_all_64_targets_bf16_gram_cholesky():
         assert np.array_equal(ed[off[i]:off[i + 1]].cpu().numpy(), cgo["edge_dst"])
         Z, wt, sz = ctx.sample(n, w.n_samples, w.seed, target)
         k = Z.shape[0]
-        if rank in (0, len(picked) - 1):
+        if rank in (0, len(picked) - 2, len(picked) - 1):
             _check_masks(ctx, w, f"c5[{target}]", n, target, Z, wt, sz, 250)
         y, pcl = ctx.eval(cg, Z)
         assert pcl == reps[i].pred_class
@@ -204,6 +211,12 @@ def test_config5_all_64_targets_bf16_gram_cholesky():
         say(f"c5[{target}]: max |y - plain fp64 oracle| on the same rows = {np.abs(y.cpu().numpy()[sel] - yp).max():.3e}")
         got = phi[off[i]:off[i + 1]].cpu().numpy().astype(np.float64)
         yh = y.cpu().numpy().astype(np.float64)
+        if rank == len(picked) - 1:
+            res = cfast.normal_residual(n, to_u64(Z), wt.cpu().numpy(), yh, got)
+            say(f"c5[{target}]: largest game, oracle-side normal-equation residual of the GPU's phi = {res:.3e}")
+            assert res <= 1e-5
+            ctx.cgraph_free(cg)
+            continue
         t0 = time.time()
         # 1e-11 is safely above where fp64 round-off stalls the recurrence on these sizes
         ref, it, rel = cfast.cgls(n, to_u64(Z), wt.cpu().numpy(), yh, tol=1e-11, max_iter=4000)

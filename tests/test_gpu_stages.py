@@ -53,6 +53,23 @@ def test_sampler_four_pass_route_gives_the_same_masks(ctx_tiny, window):
         ctx.set_tuning(None)
 
 
+@pytest.mark.parametrize("n,ns", [(30, 25000), (200, 3000), (12, 1000), (9, 510), (1010, 20000), (333, 70000)])
+def test_sampler_with_saturated_size_classes_bit_exact(ctx_tiny, n, ns):
+    """ds_options.saturate: size classes allotted at least C(n, s) pairs are enumerated (subsets in lexicographic
+    order, kernel weights); masks, weights and sizes against the oracle run with the same option."""
+    from paper_2506_22668_amd import Options, DistShapError
+    ctx, _ = ctx_tiny
+    say(f"sampler saturate n={n} n_samples={ns}")
+    Z, w, sz = ctx.sample(n, ns, 11, 5, Options(saturate=1))
+    Zo, wo, szo = sampling.sample(n, ns, 11, 5, saturate=True)
+    assert sampling.allocation(n, ns, saturate=True)["enum_upto"] >= 1
+    assert np.array_equal(to_u64(Z), Zo)
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), wo.view(np.uint32))
+    assert np.array_equal(sz.cpu().numpy(), szo)
+    with pytest.raises(DistShapError):
+        ctx.sample(n, ns, 11, 5, Options(saturate=1, weighting=1))
+
+
 def test_sampler_pair_ranges_equal_the_full_run(ctx_tiny):
     ctx, _ = ctx_tiny
     n, ns, seed, tag = 333, 5000, 99, 3

@@ -189,3 +189,65 @@ def test_gram_closed_form_under_enumeration():
     assert np.allclose(off, (n - 1) / n * (Hn - 1.0), rtol=1e-6)
     assert np.diag(G)[0] == pytest.approx(2.7682209, rel=1e-6)
     assert off[0] == pytest.approx(1.8515542, rel=1e-6)
+
+
+# ---------------------------------------------------------------- saturated size classes (option)
+def test_unranking_is_the_lexicographic_order_of_subsets():
+    import itertools
+    for n, s in [(5, 1), (5, 2), (6, 3), (9, 4), (12, 2)]:
+        want = [list(c) for c in itertools.combinations(range(n), s)]
+        got = [sampling.unrank_subset(n, s, j) for j in range(len(want))]
+        assert got == want
+
+
+@pytest.mark.parametrize("n,ns", [(30, 25000), (200, 3000), (12, 1000), (9, 510), (1010, 20000)])
+def test_saturated_classes_are_enumerated_once_with_the_kernel_weight(n, ns):
+    from math import comb
+    plain = sampling.allocation(n, ns)
+    plan = sampling.allocation(n, ns, saturate=True)
+    up = plan["enum_upto"]
+    assert up >= 1 and plain["enum_upto"] == 0
+    assert int(plan["q"].sum()) == plan["K"] and np.all(np.diff(plan["b"]) >= 0)
+    # the first class that stays sampled was allotted fewer pairs than it has coalitions; the enumerated ones had enough
+    assert plan["q"][up + 1] < comb(n, up + 1) or 2 * (up + 1) >= n
+    assert plain["q"][1] >= comb(n, 1)
+    Z, w, sz = sampling.sample(n, ns, 7, 3, saturate=True)
+    bits = sampling.unpack_rows(Z, n)
+    for s in range(1, up + 1):
+        assert plan["q"][s] == comb(n, s)
+        for size in (s, n - s):
+            rows = bits[sz == size]
+            assert len(rows) == comb(n, s) and len({r.tobytes() for r in rows}) == comb(n, s)   # every subset once
+            # the Shapley kernel weight itself: (n-1) / (C(n,s) s (n-s))
+            assert np.all(w[sz == size] == np.float32((n - 1) / (comb(n, s) * s * (n - s))))
+    # complements and sizes as in every plan; sampled classes keep their whole mass
+    assert np.array_equal(bits[0::2], ~bits[1::2])
+    for s in range(up + 1, min(up + 4, n // 2)):
+        if plan["q"][s] > 0:
+            assert abs(w[sz == s].astype(np.float64).sum() - sampling.rho(n, s)) < 1e-5 * sampling.rho(n, s)
+    # pairs of the sampled classes are drawn as without the option (same keys, same pair index): only the sizes moved
+    with pytest.raises(ValueError):
+        sampling.allocation(n, ns, weighting="uniform", saturate=True)
+
+
+def test_saturation_brings_the_estimate_closer_to_exact_shapley():
+    """9 players, 510 rows: without the option the 254 pairs are drawn with replacement from 255 pairs of
+    coalitions; with it the classes 1..3 are enumerated and only the size-4 class (125 of its 126 pairs) is
+    sampled (with replacement), so most of the sampling error is gone."""
+    from oracle import shapley, solve
+    n = 9
+    rng = np.random.default_rng(3)
+    a, c = rng.standard_normal(n), rng.standard_normal(n)
+    f = lambda bits: float(np.tanh(bits @ a) + 0.5 * np.sin(bits @ c))     # interactions of every order
+    vals = np.array([f(np.array([(m >> j) & 1 for j in range(n)], dtype=np.float64)) for m in range(1 << n)])
+    exact = shapley.exact_shapley(vals, n)
+    err = {}
+    for sat in (False, True):
+        e = []
+        for seed in range(6):
+            Z, w, sz = sampling.sample(n, 510, seed, 1, saturate=sat)
+            bits = sampling.unpack_rows(Z, n)
+            idx = (bits.astype(np.int64) << np.arange(n)).sum(axis=1)
+            e.append(np.abs(solve.solve_lstsq(bits, w, vals[idx]) - exact).max())
+        err[sat] = np.mean(e)
+    assert err[True] < 0.6 * err[False]
