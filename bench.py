@@ -145,6 +145,12 @@ def cpu_baseline(w, gpu_iterations, budget_s=20.0):
                       f"{len(Zr)} rows, the sample repeated, and scaled by rows)"}
 
 
+def progress(msg):
+    """Progress goes to stderr (stdout carries the one JSON line): a step of the large workloads takes seconds, and
+    a run that prints nothing for minutes is taken to be hung."""
+    print(f"[bench {time.perf_counter() - T_START:7.1f} s] {msg}", file=sys.stderr, flush=True)
+
+
 def read_traffic(kernel, workload):
     """HBM bytes per launch of `kernel` on `workload`, from the committed rocprofv3 --pmc summaries
     (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a plain copy of known
@@ -161,7 +167,7 @@ def read_traffic(kernel, workload):
     return None
 
 
-def run_workload(key, steps, warmup, warmup_budget_s, batch, copy_probe_mib=0):
+def run_workload(key, steps, warmup, warmup_budget_s, batch, copy_probe_mib=0, max_iter=0):
     """Time `steps` steps of workload `key`; returns (result dict, workload, mean CGLS iterations)."""
     import numpy as np
     import torch
@@ -169,8 +175,10 @@ def run_workload(key, steps, warmup, warmup_budget_s, batch, copy_probe_mib=0):
     from synth import make_workload
 
     t_gen = time.perf_counter()
+    progress(f"{key}: generating the workload")
     w = make_workload(key)
     t_gen = time.perf_counter() - t_gen
+    progress(f"{key}: {w.name} generated in {t_gen:.1f} s; uploading, extracting")
     ctx = Context("cuda:0")
     ctx.set_graph(w.row_ptr, w.col)
     ctx.set_features(w.features)
@@ -179,22 +187,22 @@ def run_workload(key, steps, warmup, warmup_budget_s, batch, copy_probe_mib=0):
     else:
         ctx.set_gcn(w.weights, transform_dtype=DS_BF16_IN_F32_ACC if w.transform_dtype == "bf16" else DS_F32)
     opts = Options(solver=DS_SOLVER_CGLS if w.solver == "cgls" else DS_SOLVER_GRAM_CHOL, tol=w.tol,
-                   max_iter=w.max_iter)
+                   max_iter=max_iter if max_iter > 0 else w.max_iter)
     targets = w.targets
     many = len(targets) > 1                      # the 64-target configuration: a step is one batch call
-    cg = ctx.extract(targets[0], opts)
-    eval_flops = (gat_flops_per_coalition(ctx, cg, w.gat) if w.gat is not None
-                  else inference_flops_per_coalition(ctx, cg, list(w.dims)))
-    capacity = ctx.cgraph_info(cg).num_players
-    ctx.cgraph_free(cg)
-    if many:
-        _, M, off, _, _, _, _ = ctx.explain_batch(targets, w.n_samples, w.seed, opts, capacity=0)
-        capacity = off[-1]
+    flops_of, capacity = {}, 0      # algorithmic inference flops per coalition, per target
+    for tgt in targets:
+        cg = ctx.extract(tgt, opts)
+        flops_of[ctx.cgraph_info(cg).num_players] = (gat_flops_per_coalition(ctx, cg, w.gat) if w.gat is not None
+                                                      else inference_flops_per_coalition(ctx, cg, list(w.dims)))
+        capacity += ctx.cgraph_info(cg).num_players
+        ctx.cgraph_free(cg)
 
     def step():
         if many:
             return ctx.explain_batch(targets, w.n_samples, w.seed, opts, capacity=capacity)[5]
-        return [ctx.explain(targets[0], w.n_samples, w.seed, opts, capacity=capacity, want_edges=False)[3]]
+        return [ctx.explain(targets[0], w.n_samples, w.seed, opts, capacity=capacity, want_edges=False,
+                            allow_not_converged=max_iter > 0)[3]]
 
     if copy_probe_mib > 0:
         ctx.copy_probe(copy_probe_mib << 20)
@@ -202,42 +210,57 @@ def run_workload(key, steps, warmup, warmup_budget_s, batch, copy_probe_mib=0):
     for i in range(max(warmup, 1)):
         step()
         warm_done += 1
+        progress(f"{key}: warm-up step {warm_done} done")
         if time.perf_counter() - t0 > warmup_budget_s:
             break
     torch.cuda.synchronize()
     reports = []
     t0 = time.perf_counter()
+    t_last = t0
     for i in range(steps):
         reports.extend(step())
+        if time.perf_counter() - t_last > 20.0:      # a line now and then; never inside a step
+            t_last = time.perf_counter()
+            progress(f"{key}: timed step {i + 1} of {steps} done")
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    progress(f"{key}: {steps} steps in {elapsed:.2f} s")
 
     k_total = sum(r.num_rows for r in reports)
     per_step = len(reports) // steps
     mean = lambda name: float(np.mean([getattr(r, name) for r in reports]))
+    mean_of = lambda fn: float(np.mean([fn(r) for r in reports]))   # algorithmic work differs from game to game
     rep = max(reports[:per_step], key=lambda r: r.num_players)
     n, V, W64, rows = rep.num_players, rep.num_nodes, (rep.num_players + 63) // 64, rep.num_rows
-    KW = (rows + 63) // 64
     iters = mean("cgls_iterations")
     # per-kernel-group durations: HIP events recorded by the library on its own stream inside the timed region
     # (means over all explanations of the run); algorithmic work per explanation from the library's report
-    stream_eval = n > 12288 and w.gat is None          # the mask-streaming inference kernel
+    stream_eval = mean("ms_k_stream") > 0              # long mask rows: streaming kernel + layers kernel
+    eval_tflop = mean_of(lambda r: r.num_rows * flops_of[r.num_players]) / 1e12
     kernels = {
-        ("masked_gat_eval" if w.gat is not None else "masked_gcn_eval"):
-            ({"ms": mean("ms_k_eval"), "bound": "hbm", "alg": mean("bytes_eval") / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-             if stream_eval else
-             {"ms": mean("ms_k_eval"), "bound": "alu", "alg": rows * eval_flops / 1e12, "peak": FP32_PEAK_TFLOPS,
-              "unit": "TFLOP/s"}),
         "gram_popcount": {"ms": mean("ms_k_gram"), "bound": "alu",
-                          # lower triangle of n^2 column pairs x KW 64-row words x (AND, popcount, weighted add)
-                          "alg": 3.0 * (n * (n + 1) / 2) * KW / 1e12, "peak": ALU_PEAK_TOPS, "unit": "Top/s"},
-        "cholesky_fp64": {"ms": mean("ms_k_chol"), "bound": "mfma", "alg": (n ** 3 / 3.0) / 1e12,
+                          # lower triangle of n^2 column pairs x 64-row words x (AND, popcount, weighted add)
+                          "alg": mean_of(lambda r: 3.0 * (r.num_players * (r.num_players + 1) / 2) * ((r.num_rows + 63) // 64)) / 1e12
+                          if mean("ms_k_gram") > 0 else 0.0, "peak": ALU_PEAK_TOPS, "unit": "Top/s"},
+        "cholesky_fp64": {"ms": mean("ms_k_chol"), "bound": "mfma",
+                          "alg": mean_of(lambda r: r.num_players ** 3 / 3.0) / 1e12 if mean("ms_k_chol") > 0 else 0.0,
                           "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s"},
         # all iterations of the conjugate-gradient loop; per iteration the small member of every pair once for
         # Z u and once for Z^T r
         "cgls_loop": {"ms": mean("ms_k_cgls"), "bound": "hbm", "alg": mean("bytes_solve") / 1e9 if iters > 0 else 0.0,
                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "launches": max(int(round(iters)), 1)},
     }
+    if stream_eval:
+        # the kernel that streams the mask matrix (one member of every pair) against HBM, the layers on its compact
+        # output (first layer on the fp32 matrix cores) against the fp32 matrix-core peak
+        kernels["mask_stream"] = {"ms": mean("ms_k_stream"), "bound": "hbm", "alg": mean("bytes_eval") / 1e9,
+                                  "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+        kernels["masked_gcn_layers"] = {"ms": mean("ms_k_eval") - mean("ms_k_stream"), "bound": "mfma", "alg": eval_tflop,
+                                        "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        # short mask rows (one coalition per lane, everything but the mask on chip): arithmetic-bound
+        kernels["masked_gat_eval" if w.gat is not None else "masked_gcn_eval"] = {
+            "ms": mean("ms_k_eval"), "bound": "alu", "alg": eval_tflop, "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s"}
     for v in kernels.values():
         v["achieved"] = (v["alg"] / (v["ms"] / 1e3)) if v["ms"] > 0 else 0.0
         v["frac"] = v["achieved"] / v["peak"]
@@ -302,6 +325,9 @@ def main():
     ap.add_argument("--warmup-budget-s", type=float, default=12.0)
     ap.add_argument("--time-budget-s", type=float, default=480.0,
                     help="wall-clock budget of the process: optional parts are skipped when it is nearly spent")
+    ap.add_argument("--profile-max-iter", type=int, default=0,
+                    help="profiling runs only: stop the conjugate-gradient loop after this many steps (the result is "
+                         "then not the converged one and the line is not a benchmark)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB first (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -316,7 +342,7 @@ def main():
         sys.exit(1)
     small = args.workload in ("c1", "c2", "c2_small", "gat_c2", "gat_small", "c5_small", "c3_small", "c4_small")
     head, w, iters = run_workload(args.workload, args.steps, args.warmup, args.warmup_budget_s,
-                                  args.batch if small else 0, args.copy_probe_mib)
+                                  args.batch if small else 0, args.copy_probe_mib, args.profile_max_iter)
     out = {
         "metric": ("masked-GAT" if w.gat is not None else "masked-GCN") +
                   " coalition evals/sec; end-to-end seconds per explained node",
@@ -327,6 +353,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": head.pop("dtype"), "data": "synthetic",
     }
+    if args.profile_max_iter > 0:
+        out["profiling_run_cgls_capped_at"] = args.profile_max_iter
     out.update(head)
     left = lambda: args.time_budget_s - (time.perf_counter() - T_START)
     others = {}
@@ -342,6 +370,7 @@ def main():
     if others:
         out["other_workloads"] = others
     if not args.no_cpu_baseline:
+        progress("CPU baseline (the C oracle on a sample of the same rows)")
         budget = min(20.0, max(5.0, left() - 15.0))
         out["cpu_baseline"] = cpu_baseline(w, iters, budget)
     out["wall_s"] = time.perf_counter() - T_START

@@ -752,7 +752,7 @@ __global__ void pack_endpoints_kernel(const int2* pl, int64_t n, uint32_t* pab, 
 }
 
 // coalition size of every handled row, one wave per row (only when the caller has no sizes at hand)
-__global__ __launch_bounds__(kThreads) void row_popcount_kernel(const uint64_t* Z, int64_t rows, int64_t row_stride, int64_t W,
+__global__ __launch_bounds__(kThreads) void mask_row_sizes_kernel(const uint64_t* Z, int64_t rows, int64_t row_stride, int64_t W,
                                                                 int32_t* sizes) {
   const int lane = threadIdx.x & 63;
   const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6, nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
@@ -1612,7 +1612,7 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
       } else {
         int64_t pg = (bl.records * 64 + kThreads - 1) / kThreads;
         if (pg > (int64_t)ctx->num_cus * 32) pg = (int64_t)ctx->num_cus * 32;
-        hipLaunchKernelGGL(row_popcount_kernel, dim3((unsigned)pg), dim3(kThreads), 0, ctx->stream, Z, bl.records, sa.row_stride, sa.W, sizes);
+        hipLaunchKernelGGL(mask_row_sizes_kernel, dim3((unsigned)pg), dim3(kThreads), 0, ctx->stream, Z, bl.records, sa.row_stride, sa.W, sizes);
         sa.sizes = sizes;
         sa.size_step = 1;
       }
