@@ -159,6 +159,9 @@ typedef struct ds_tuning {
                                  kernel followed by the one-coalition-per-lane layers (long mask rows). 2 and 3 need
                                  256 rows or more and fall back to 1 where they do not apply (a test hook: the
                                  results agree to rounding) */
+  int32_t cgls_dense_div;     /* CGLS on large games: pair rows with more than n / div players stay bit-packed and
+                                 are multiplied on the int8 matrix cores, the sparser ones become index lists
+                                 (default 128: where one gather per set bit costs what streaming the row does) */
 } ds_tuning;
 int ds_set_tuning(ds_ctx* ctx, const ds_tuning* tuning /* [host] or NULL */);
 

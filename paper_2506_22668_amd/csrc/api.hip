@@ -175,7 +175,8 @@ int ds_set_tuning(ds_ctx* ctx, const ds_tuning* tuning) {
   }
   if (tuning->batch_workers < 0 || tuning->batch_workers > 16 || tuning->gram_sparse_div < 0 ||
       !(tuning->gram_dense_fraction >= 0.f && tuning->gram_dense_fraction <= 1.f) || tuning->sampler_window < -1 ||
-      tuning->eval_path < 0 || tuning->eval_path > 3)
+      tuning->eval_path < 0 || tuning->eval_path > 3 ||
+      (tuning->cgls_dense_div != 0 && (tuning->cgls_dense_div < 32 || tuning->cgls_dense_div > 65536)))
     return ds_fail(ctx, DS_EINVAL, "tuning value out of range");
   ctx->tuning = *tuning;
   return DS_OK;

@@ -178,118 +178,245 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_rows_kernel(const uint64_t*
   }
 }
 
-// ---- dense rows: byte-table product -------------------------------------------------------
-// out[i] = sum over set bits j of row i of x[j], for rows that are dense enough that walking
-// bits one by one costs more than it should. For a chunk of 512 columns the workgroup builds,
-// in LDS, the 64 tables T_g[b] = sum of x over the bits of byte value b within column group g
-// (from two 16-entry nibble tables per group), and every thread then adds eight table entries
-// per 64-bit word of its rows: one LDS read per 8 matrix bits, whatever the density. A
-// workgroup covers 2048 rows x a range of chunks; the per-range partial sums are added up in a
-// fixed order by a second kernel.
-constexpr int kTabCols = 512;
-constexpr int kTabWords = kTabCols / 64;
-constexpr int kTabGroups = kTabCols / 8;
-constexpr int kTabThreads = 1024;  // 16 waves hide the LDS and memory latency of the look-ups
-constexpr int kTabRpt = 4;         // rows per thread
-constexpr int kTabRows = kTabThreads * kTabRpt;
+// ---- dense rows: product on the int8 matrix cores ------------------------------------------
+// out[i] = sum over set bits j of row i of x[j], for rows dense enough that one look-up or one
+// gather per set bit (or per byte of mask) costs more than streaming the bits. The product is a
+// (rows x cols 0/1 matrix) . (cols x 7 matrix of base-256 digits of x): exact integer arithmetic.
+//  * x is scaled by a power of two so that max|x| < 2^54 and rounded to integers (the same 2^-54
+//    relative step for every entry); each integer is written in seven balanced base-256 digits
+//    (-128..127), one int8 plane per digit (`digit_planes_kernel`).
+//  * A operand of v_mfma_i32_16x16x64_i8 = 16 rows x 64 columns of mask bits as bytes. A lane holds
+//    16 bytes of one row; the bytes come from the lane's four 32-bit mask words by ONE AND each:
+//    word & (0x01010101 << j) puts bit j of every mask byte into a byte of its own (value 2^j), so
+//    operand j multiplies the columns {8i + j} and its accumulator carries the factor 2^(j & 3)
+//    (bits 4..7 after a shift of the word by 4), divided out exactly at the end. The digit planes
+//    are stored permuted to match: within every 128 columns, position j<<4 | v<<2 | i holds column
+//    v<<5 | i<<3 | j, so the B operand of (word group, j) is 16 contiguous bytes.
+//  * B operand = digits (7 of the 16 columns used; the eighth plane is zero and serves the idle
+//    columns). The planes of a 1024-column chunk are staged in LDS once per workgroup and read by
+//    all of its waves, one (half, nibble) group of four operands ahead of their use.
+//  * A wave owns 64 rows (four 16-row tiles); per chunk every row is visited with 128 contiguous
+//    bytes (two 16-byte loads per lane and tile), requested one chunk ahead.
+// The per-column-group partial sums are int32 (exact) and are added up, recombined
+// (sum_d 256^d S_d, as two exact integer halves) and rescaled by a second kernel, so the result does not
+// depend on the grouping.
+typedef int v4i __attribute__((ext_vector_type(4)));
+constexpr int kMmTiles = 4;                          // 16-row tiles per wave
+constexpr int kMmWaves = 4;                          // waves per workgroup
+constexpr int kMmWaveRows = 16 * kMmTiles;
+constexpr int kMmRows = kMmWaveRows * kMmWaves;      // rows per workgroup
+constexpr int kMmChunk = 1024;                       // columns per step
+constexpr int kMmHalves = kMmChunk / 512;            // 64-byte pieces of a row per chunk
+constexpr int kMmDigits = 7;
+constexpr int kMmPlanes = 8;
+constexpr int kMmPlanePitch = kMmChunk + 16;         // LDS pitch of a plane: the eight planes start 16 bytes (4 banks) apart
+constexpr int64_t kMmMaxGroupCols = 1 << 20;         // 2^20 columns * 128 * 2^3 = 2^30: the int32 accumulators cannot overflow
 
-__global__ __launch_bounds__(kTabThreads) void bit_spmv_tab_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
-                                                                int64_t row_first, int64_t row_step, const double* x,
-                                                                double* partial, int64_t chunks_per_group, int64_t n_chunks) {
-  extern __shared__ double tab_smem[];
-  double* tab = tab_smem;                       // [64 groups][256]
-  double* nib = tab_smem + kTabGroups * 256;    // [64 groups][2 nibbles][16]
-  double* xch = nib + kTabGroups * 32;          // [512] the chunk of x
-  const int tid = threadIdx.x;
-  const int64_t Wc = (cols + 63) / 64;
-  const uint64_t tail = (cols & 63) ? ((1ull << (cols & 63)) - 1ull) : ~0ull;
-  const int64_t rbase = (int64_t)blockIdx.x * kTabRows;
-  double acc[kTabRpt];
+// slot: bit pattern of max |x| over the call (0 on entry; non-negative doubles order like their bit patterns)
+__global__ __launch_bounds__(256) void absmax_kernel(const double* x, int64_t n, unsigned long long* slot) {
+  unsigned long long m = 0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x[i]) & 0x7fffffffffffffffull;
+    m = b > m ? b : m;
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned long long t = __shfl_xor(m, o, 64);
+    m = t > m ? t : m;
+  }
+  if ((threadIdx.x & 63) == 0 && m) atomicMax(slot, m);
+}
+
+// One thread per 4 plane positions (i = 0..3: columns 8 apart). scal[0] = the power of two that turns the integer
+// result back into the scale of x (NaN if x holds a non-finite value: the product is then NaN everywhere).
+__global__ __launch_bounds__(256) void digit_planes_kernel(const double* x, int64_t n, int64_t npad, const unsigned long long* slot,
+                                                           int8_t* D, double* scal) {
+  const double mx = __longlong_as_double((long long)*slot);
+  const bool finite = mx < __longlong_as_double(0x7ff0000000000000ll);
+  int e = 0;
+  if (finite && mx > 0.0) frexp(mx, &e);   // mx < 2^e
+  const int f = 54 - e;
+  const int64_t q4 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q4 == 0) scal[0] = finite ? ldexp(1.0, -f) : __longlong_as_double(0x7ff8000000000000ll);
+  const int64_t pos0 = q4 * 4;
+  if (pos0 >= npad) return;
+  const int p = (int)(pos0 & 127);
+  const int j = p >> 4, v = (p >> 2) & 3;
+  const int64_t colbase = (pos0 & ~(int64_t)127) + (v << 5 | j);
+  int32_t packed[kMmDigits] = {0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-  for (int i = 0; i < kTabRpt; ++i) acc[i] = 0.0;
-  const int64_t c_begin = (int64_t)blockIdx.y * chunks_per_group;
-  const int64_t c_end = c_begin + chunks_per_group < n_chunks ? c_begin + chunks_per_group : n_chunks;
-  for (int64_t c = c_begin; c < c_end; ++c) {
-    __syncthreads();
-    // the chunk's 512 vector entries first (one coalesced load), then the nibble sums from LDS
-    if (tid < kTabCols) {
-      const int64_t col = c * kTabCols + tid;
-      xch[tid] = col < cols ? x[col] : 0.0;
-    }
-    __syncthreads();
-    for (int e = tid; e < kTabGroups * 32; e += kTabThreads) {
-      const int g = e >> 5, half = (e >> 4) & 1, m = e & 15;
-      const double* xp = xch + g * 8 + half * 4;
-      double sum = 0.0;
+  for (int i = 0; i < 4; ++i) {
+    const int64_t col = colbase + (i << 3);
+    long long q = (finite && col < n) ? __double2ll_rn(ldexp(x[col], f)) : 0ll;
 #pragma unroll
-      for (int bbit = 0; bbit < 4; ++bbit)
-        if ((m >> bbit) & 1) sum += xp[bbit];
-      nib[e] = sum;
-    }
-    __syncthreads();
-    for (int e = tid; e < kTabGroups * 256; e += kTabThreads) {
-      const int g = e >> 8, byte = e & 255;
-      tab[e] = nib[g * 32 + (byte & 15)] + nib[g * 32 + 16 + (byte >> 4)];
-    }
-    __syncthreads();
-    // all words of the thread's rows for this chunk are requested first (their latency overlaps);
-    // then, word by word, the eight table reads are issued together and summed as a tree, so that
-    // the LDS pipeline stays full instead of waiting on one read at a time
-    uint64_t wv[kTabRpt][kTabWords];
-#pragma unroll
-    for (int i = 0; i < kTabRpt; ++i) {
-      const int64_t r = rbase + (int64_t)i * kTabThreads + tid;
-      const uint64_t* p = B + (row_first + (r < rows ? r : 0) * row_step) * stride + c * kTabWords;
-#pragma unroll
-      for (int q = 0; q < kTabWords; ++q) {
-        const int64_t wd = c * kTabWords + q;
-        uint64_t v = (r < rows && wd < Wc) ? p[q] : 0ull;
-        if (wd == Wc - 1) v &= tail;
-        wv[i][q] = v;
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < kTabRpt; ++i) {
-      double rowsum = 0.0;
-#pragma unroll
-      for (int q = 0; q < kTabWords; ++q) {
-        const uint32_t lo = (uint32_t)wv[i][q], hi = (uint32_t)(wv[i][q] >> 32);
-        const double* tq = tab + q * 8 * 256;
-        const double t0 = tq[0 * 256 + (lo & 0xFF)];
-        const double t1 = tq[1 * 256 + ((lo >> 8) & 0xFF)];
-        const double t2 = tq[2 * 256 + ((lo >> 16) & 0xFF)];
-        const double t3 = tq[3 * 256 + (lo >> 24)];
-        const double t4 = tq[4 * 256 + (hi & 0xFF)];
-        const double t5 = tq[5 * 256 + ((hi >> 8) & 0xFF)];
-        const double t6 = tq[6 * 256 + ((hi >> 16) & 0xFF)];
-        const double t7 = tq[7 * 256 + (hi >> 24)];
-        rowsum += ((t0 + t1) + (t2 + t3)) + ((t4 + t5) + (t6 + t7));
-      }
-      acc[i] += rowsum;
+    for (int d = 0; d < kMmDigits; ++d) {
+      const int di = (int)(int8_t)(q & 0xFF);
+      q = (q - di) >> 8;
+      packed[d] |= (di & 0xFF) << (8 * i);
     }
   }
 #pragma unroll
-  for (int i = 0; i < kTabRpt; ++i) {
-    const int64_t r = rbase + (int64_t)i * kTabThreads + tid;
-    if (r < rows) partial[(int64_t)blockIdx.y * rows + r] = acc[i];
+  for (int d = 0; d < kMmDigits; ++d) *(int32_t*)(D + d * npad + pos0) = packed[d];
+}
+
+__global__ __launch_bounds__(kMmWaves * 64) void bit_spmv_mm_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
+                                                                    int64_t row_first, int64_t row_step, const int8_t* D,
+                                                                    int64_t dstride, int32_t* partial, int64_t chunks_per_group,
+                                                                    int64_t n_chunks) {
+  __shared__ __align__(16) int8_t Bs[2][kMmPlanes * kMmPlanePitch];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r16 = lane & 15, g = lane >> 4;
+  const int64_t Wc = (cols + 63) / 64;
+  const int64_t wave_row0 = ((int64_t)blockIdx.x * kMmWaves + wave) * kMmWaveRows;
+  const int64_t c_begin = (int64_t)blockIdx.y * chunks_per_group;
+  const int64_t c_end = c_begin + chunks_per_group < n_chunks ? c_begin + chunks_per_group : n_chunks;
+  const int64_t row_bytes = row_step * stride * 8;
+  const char* Bb = (const char*)(B + row_first * stride);
+  const uint32_t lane_off = (uint32_t)r16 * (uint32_t)row_bytes;   // the host keeps 16 * row_bytes below 2^32
+  v4i acc[kMmTiles][4];
+#pragma unroll
+  for (int t = 0; t < kMmTiles; ++t)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[t][q] = v4i{0, 0, 0, 0};
+  uint32_t a_cur[kMmTiles][4 * kMmHalves], a_next[kMmTiles][4 * kMmHalves];
+  // Rows past the end are read from a live row and never stored; in the last chunk, words past the row's end are
+  // read from its last word and meet zero digits (the planes are zero from column `cols` on).
+  // (one 16-byte load per lane, tile and half: as two 8-byte loads the same bytes took twice the requests and the
+  // kernel ran 17 % slower)
+  typedef uint32_t u4a8 __attribute__((ext_vector_type(4), aligned(8)));   // rows are 8-byte aligned
+  auto load_a = [&](uint32_t (&a)[kMmTiles][4 * kMmHalves], int64_t c) {
+    if (c != n_chunks - 1) {
+#pragma unroll
+      for (int t = 0; t < kMmTiles; ++t) {
+        const int64_t r_t = wave_row0 + 16 * t;
+        const char* base = Bb + (r_t < rows ? r_t : rows - 1) * row_bytes;   // uniform over the wave
+        const uint32_t lo = (r_t + r16 < rows ? lane_off : 0u) + (uint32_t)(c * (kMmChunk / 8) + g * 16);
+#pragma unroll
+        for (int h = 0; h < kMmHalves; ++h) {
+          const u4a8 v = *(const u4a8*)(base + (lo + h * 64));
+          a[t][4 * h + 0] = v.x;
+          a[t][4 * h + 1] = v.y;
+          a[t][4 * h + 2] = v.z;
+          a[t][4 * h + 3] = v.w;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < kMmTiles; ++t) {
+        const int64_t r_t = wave_row0 + 16 * t;
+        const char* base = Bb + (r_t < rows ? r_t : rows - 1) * row_bytes;
+        const uint32_t lo = r_t + r16 < rows ? lane_off : 0u;
+#pragma unroll
+        for (int h = 0; h < kMmHalves; ++h) {
+          const int64_t w0 = c * (kMmChunk / 64) + h * 8 + g * 2, w1 = w0 + 1;
+          const uint32_t cb0 = (uint32_t)(w0 < Wc ? w0 : Wc - 1) * 8u, cb1 = (uint32_t)(w1 < Wc ? w1 : Wc - 1) * 8u;
+          const uint64_t v0 = *(const uint64_t*)(base + (lo + cb0)), v1 = *(const uint64_t*)(base + (lo + cb1));
+          a[t][4 * h + 0] = (uint32_t)v0;
+          a[t][4 * h + 1] = (uint32_t)(v0 >> 32);
+          a[t][4 * h + 2] = (uint32_t)v1;
+          a[t][4 * h + 3] = (uint32_t)(v1 >> 32);
+        }
+      }
+    }
+  };
+  // staging of a chunk's digit planes: thread -> (plane, 32-byte segment)
+  static_assert(kMmWaves * 64 * 32 == kMmPlanes * kMmChunk, "one 32-byte segment per thread");
+  const int st_plane = tid / (kMmChunk / 32), st_seg = tid % (kMmChunk / 32);
+  const int8_t* st_src = D + (int64_t)st_plane * dstride + st_seg * 32;
+  const int st_dst = st_plane * kMmPlanePitch + st_seg * 32;
+  v4i s0, s1;
+  auto stage_load = [&](int64_t c) {
+    s0 = *(const v4i*)(st_src + c * kMmChunk);
+    s1 = *(const v4i*)(st_src + c * kMmChunk + 16);
+  };
+  auto stage_store = [&](int buf) {
+    *(v4i*)(&Bs[buf][st_dst]) = s0;
+    *(v4i*)(&Bs[buf][st_dst + 16]) = s1;
+  };
+  const int b_off = (r16 < kMmDigits ? r16 : kMmDigits) * kMmPlanePitch + g * 128;   // plane 7 is all zero
+  stage_load(c_begin);
+  load_a(a_cur, c_begin);
+  stage_store(0);
+  __syncthreads();
+  int buf = 0;
+  for (int64_t c = c_begin; c < c_end; ++c) {
+    const int64_t cn = c + 1 < c_end ? c + 1 : c;   // (the last chunk is requested again and not used)
+    stage_load(cn);
+    load_a(a_next, cn);
+    const int8_t* bs = &Bs[buf][b_off];
+    v4i bq[2][4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) bq[0][q] = *(const v4i*)(bs + q * 16);
+#pragma unroll
+    for (int gi = 0; gi < 2 * kMmHalves; ++gi) {
+      const int h = gi >> 1, hi = gi & 1;
+      if (gi + 1 < 2 * kMmHalves) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          bq[(gi + 1) & 1][q] = *(const v4i*)(bs + ((gi + 1) >> 1) * 512 + (4 * ((gi + 1) & 1) + q) * 16);
+      }
+#pragma unroll
+      for (int t = 0; t < kMmTiles; ++t) {
+        uint32_t x0 = a_cur[t][4 * h + 0], x1 = a_cur[t][4 * h + 1], x2 = a_cur[t][4 * h + 2], x3 = a_cur[t][4 * h + 3];
+        if (hi) {
+          x0 >>= 4;
+          x1 >>= 4;
+          x2 >>= 4;
+          x3 >>= 4;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const uint32_t m = 0x01010101u << q;
+          const v4i av = {(int)(x0 & m), (int)(x1 & m), (int)(x2 & m), (int)(x3 & m)};
+          acc[t][q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bq[gi & 1][q], acc[t][q], 0, 0, 0);
+        }
+      }
+    }
+    stage_store(buf ^ 1);
+    __syncthreads();   // every wave is done with Bs[buf]; Bs[buf ^ 1] is complete
+    buf ^= 1;
+#pragma unroll
+    for (int t = 0; t < kMmTiles; ++t)
+#pragma unroll
+      for (int k = 0; k < 4 * kMmHalves; ++k) a_cur[t][k] = a_next[t][k];
+  }
+  // lane (digit r16, lane group g) holds rows 4g + v of every tile
+  if (r16 < kMmPlanes) {
+#pragma unroll
+    for (int t = 0; t < kMmTiles; ++t)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int64_t row = wave_row0 + 16 * t + 4 * g + v;
+        if (row < rows)
+          partial[((int64_t)blockIdx.y * rows + row) * kMmPlanes + r16] =
+              acc[t][0][v] + (acc[t][1][v] >> 1) + (acc[t][2][v] >> 2) + (acc[t][3][v] >> 3);
+      }
   }
 }
 
-__global__ void tab_reduce_kernel(const double* partial, int64_t rows, int groups, const double* addend, double* out) {
+// out[r] = (addend[r] or 0) + scal[0] * sum_d 256^d * (sum over the column groups of digit sum d); also clears the
+// maximum slot for the next product
+__global__ __launch_bounds__(256) void mm_reduce_kernel(const int32_t* partial, int64_t rows, int groups, const double* scal,
+                                                        const double* addend, double* out, unsigned long long* slot) {
   const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r == 0) *slot = 0ull;
   if (r >= rows) return;
-  // eight loads in flight; the partial sums are added in the order of their groups whatever the count is
-  double s = addend ? addend[r] : 0.0;
-  int g = 0;
-  for (; g + 8 <= groups; g += 8) {
-    double v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(g + u) * rows + r];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) s += v[u];
+  long long S[kMmPlanes] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int gq = 0; gq < groups; ++gq) {
+    const int4* p = (const int4*)(partial + ((int64_t)gq * rows + r) * kMmPlanes);
+    const int4 u = p[0], w = p[1];
+    S[0] += u.x;
+    S[1] += u.y;
+    S[2] += u.z;
+    S[3] += u.w;
+    S[4] += w.x;
+    S[5] += w.y;
+    S[6] += w.z;
   }
-  for (; g < groups; ++g) s += partial[(int64_t)g * rows + r];
-  out[r] = s;
+  const long long hi = ((S[6] * 256 + S[5]) * 256 + S[4]) * 256 + S[3];
+  const long long lo = (S[2] * 256 + S[1]) * 256 + S[0];
+  const double val = ((double)hi * 16777216.0 + (double)lo) * scal[0];
+  out[r] = addend ? addend[r] + val : val;
 }
 
 // ---- sparse rows: index lists ----------------------------------------------------------------
@@ -387,33 +514,60 @@ int ds_bit_transpose(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols
   return DS_OK;
 }
 
-size_t ds_bit_spmv_tab_ws_doubles(const ds_ctx* ctx, int64_t rows, int64_t cols) {
-  const int64_t row_groups = (rows + kTabRows - 1) / kTabRows;
-  const int64_t n_chunks = (cols + kTabCols - 1) / kTabCols;
-  int64_t groups = (6 * (int64_t)ctx->num_cus + row_groups - 1) / (row_groups > 0 ? row_groups : 1);
-  if (groups > n_chunks) groups = n_chunks;
+static void mm_shape(const ds_ctx* ctx, int64_t rows, int64_t cols, ds_mm_plan* p) {
+  p->rows = rows;
+  p->cols = cols;
+  p->row_groups = (rows + kMmRows - 1) / kMmRows;
+  p->n_chunks = (cols + kMmChunk - 1) / kMmChunk;
+  int64_t groups = (8 * (int64_t)ctx->num_cus + p->row_groups - 1) / (p->row_groups > 0 ? p->row_groups : 1);
+  if (groups > p->n_chunks) groups = p->n_chunks;
   if (groups < 1) groups = 1;
-  return (size_t)groups * (size_t)rows;
+  p->cpg = (p->n_chunks + groups - 1) / groups;
+  if (p->cpg > kMmMaxGroupCols / kMmChunk) p->cpg = kMmMaxGroupCols / kMmChunk;
+  p->groups = (p->n_chunks + p->cpg - 1) / p->cpg;
+  p->npad = p->n_chunks * kMmChunk;
 }
 
-int ds_bit_spmv_tab(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
-                    int64_t row_step, const double* x, const double* addend, double* out, double* ws,
-                    hipEvent_t addend_ready) {
-  if (rows <= 0) return DS_OK;
-  const int64_t row_groups = (rows + kTabRows - 1) / kTabRows;
-  const int64_t n_chunks = (cols + kTabCols - 1) / kTabCols;
-  int64_t groups = (6 * (int64_t)ctx->num_cus + row_groups - 1) / row_groups;
-  if (groups > n_chunks) groups = n_chunks;
-  if (groups < 1) groups = 1;
-  const int64_t cpg = (n_chunks + groups - 1) / groups;
-  groups = (n_chunks + cpg - 1) / cpg;
-  const size_t lds = (size_t)(kTabGroups * 256 + kTabGroups * 32 + kTabCols) * sizeof(double);
-  DS_HIP(ctx, hipFuncSetAttribute((const void*)bit_spmv_tab_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(bit_spmv_tab_kernel, dim3((unsigned)row_groups, (unsigned)groups), dim3(kTabThreads), lds, ctx->stream, B,
-                     rows, cols, stride, row_first, row_step, x, ws, cpg, n_chunks);
+size_t ds_bit_spmv_mm_ws_bytes(const ds_ctx* ctx, int64_t rows, int64_t cols) {
+  ds_mm_plan p;
+  mm_shape(ctx, rows, cols, &p);
+  return 256 + ds_align((size_t)kMmPlanes * p.npad) + ds_align((size_t)p.groups * rows * kMmPlanes * 4);
+}
+
+int ds_bit_spmv_mm_prepare(ds_ctx* ctx, int64_t rows, int64_t cols, void* ws, ds_mm_plan* plan) {
+  mm_shape(ctx, rows, cols, plan);
+  char* p = (char*)ws;
+  plan->scal = (double*)p;
+  plan->D = (int8_t*)(p + 256);
+  plan->partial = (int32_t*)(p + 256 + ds_align((size_t)kMmPlanes * plan->npad));
+  DS_HIP(ctx, hipMemsetAsync(plan->scal, 0, 256, ctx->stream));                                    // scale and maximum slot
+  DS_HIP(ctx, hipMemsetAsync(plan->D + (size_t)kMmDigits * plan->npad, 0, plan->npad, ctx->stream));  // the zero plane
+  return DS_OK;
+}
+
+int ds_bit_spmv_mm_digits(ds_ctx* ctx, const ds_mm_plan* p, const double* x) {
+  if (p->rows <= 0) return DS_OK;
+  unsigned long long* slot = (unsigned long long*)(p->scal + 1);
+  int64_t mb = (p->cols + 2047) / 2048;
+  if (mb > 2 * (int64_t)ctx->num_cus) mb = 2 * (int64_t)ctx->num_cus;
+  hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)mb), dim3(256), 0, ctx->stream, x, p->cols, slot);
+  hipLaunchKernelGGL(digit_planes_kernel, dim3((unsigned)((p->npad / 4 + 255) / 256)), dim3(256), 0, ctx->stream, x, p->cols,
+                     p->npad, slot, p->D, p->scal);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
+
+int ds_bit_spmv_mm_product(ds_ctx* ctx, const ds_mm_plan* p, const uint64_t* B, int64_t stride, int64_t row_first,
+                           int64_t row_step, const double* addend, double* out, hipEvent_t addend_ready) {
+  if (p->rows <= 0) return DS_OK;
+  if (row_step * stride * 8 * 16 >= ((int64_t)1 << 32))
+    return ds_fail(ctx, DS_EINTERNAL, "matrix-core product: rows of %lld bytes are too far apart", (long long)(row_step * stride * 8));
+  unsigned long long* slot = (unsigned long long*)(p->scal + 1);
+  hipLaunchKernelGGL(bit_spmv_mm_kernel, dim3((unsigned)p->row_groups, (unsigned)p->groups), dim3(kMmWaves * 64), 0, ctx->stream,
+                     B, p->rows, p->cols, stride, row_first, row_step, p->D, p->npad, p->partial, p->cpg, p->n_chunks);
   if (addend_ready) DS_HIP(ctx, hipStreamWaitEvent(ctx->stream, addend_ready, 0));  // the addend comes from another stream
-  hipLaunchKernelGGL(tab_reduce_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, ctx->stream, ws, rows,
-                     (int)groups, addend, out);
+  hipLaunchKernelGGL(mm_reduce_kernel, dim3((unsigned)((p->rows + 255) / 256)), dim3(256), 0, ctx->stream, p->partial, p->rows,
+                     (int)p->groups, p->scal, addend, out, slot);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }

@@ -303,6 +303,7 @@ __global__ __launch_bounds__(kThreads) void row_popcount_kernel(const uint64_t* 
 }
 
 constexpr int64_t kHybridMinPlayers = 4096;  // below this the plain bit walk is already cheap
+constexpr int32_t kDenseDiv = 128;           // pair rows with more than n / 128 players are multiplied as bitmaps
 
 }  // namespace
 
@@ -310,9 +311,9 @@ size_t ds_cgls_arena_bytes(int64_t n, int64_t k) {
   const int64_t KW = (k + 63) / 64;
   // the hybrid storage (index lists both ways for the sparse rows + transposed bitmap of the dense rows)
   // never exceeds twice the plain transposed bitmap, and building it needs one more as a temporary;
-  // plus offsets and table-product scratch
+  // plus offsets and the scratch of the two matrix-core products (digit planes, per-group digit sums)
   const size_t hybrid = 3 * ds_align((size_t)n * KW * 8) + 4 * ds_align((n + 2) * 4) + 2 * ds_align((k + 2) * 4) +
-                        ds_align(8 * (size_t)(n > k ? n : k) * 64) + 4 * ds_scan_arena_bytes(n > k ? n + 1 : k + 1);
+                        ds_align(96 * (size_t)(n > k ? n : k)) + ((size_t)80 << 20) + 4 * ds_scan_arena_bytes(n > k ? n + 1 : k + 1);
   return hybrid + 2 * ds_align(k * 4) + 7 * ds_align(k * 8) + 4 * ds_align(n * 8) + 65536;
 }
 
@@ -348,20 +349,22 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   DS_TRY(ds_row_prep(ctx, Z, k, n, w, y, sz, t, sqw, wc));
 
   // ---- storage for the two products ----
-  // Paired, size-sorted rows of a large game: the small members with at most n/32 players become
-  // index lists (4 B per set bit is less than their n/8-byte bitmap rows) in both orientations,
-  // the denser tail stays a bitmap (rows of Z itself, plus a transposed copy) and is multiplied
-  // through byte tables. Otherwise: plain bitmap and its transpose, set bits walked one by one.
+  // Paired, size-sorted rows of a large game: the small members with at most n/128 players become
+  // index lists in both orientations (one 8-byte gather per set bit: cheaper than streaming the
+  // n/8-byte bitmap row only below that density), the denser tail stays a bitmap (rows of Z itself,
+  // plus a transposed copy) and is multiplied on the int8 matrix cores. Otherwise: plain bitmap and
+  // its transpose, set bits walked one by one.
   bool hybrid = false;
   int64_t Rs = 0, Rd = 0, RdW = 0, nnz_s = 0;
   int32_t *csr_off = nullptr, *csr_idx = nullptr, *csc_off = nullptr, *csc_row = nullptr;
   uint64_t *Zt = nullptr, *Ztd = nullptr;
-  double* tab_ws = nullptr;
-  if (paired && n >= kHybridMinPlayers) {
+  ds_mm_plan mm_f = {}, mm_a = {};   // dense rows: forward (Rd x n) and adjoint (n x Rd) products
+  if (paired && n >= kHybridMinPlayers && n < ((int64_t)1 << 28)) {   // (the matrix-core product addresses rows with 32 bits)
     int32_t* cnt = (int32_t*)ds_arena_alloc(ctx, (R + 1) * 4);
     if (!cnt) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
     DS_HIP(ctx, hipMemsetAsync(ctx->d_mail, 0, 4 * sizeof(int64_t), st));
-    hipLaunchKernelGGL(pair_sizes_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, sz, R, (int32_t)(n / 32), cnt, ctx->d_mail);
+    const int32_t dense_div = ctx->tuning.cgls_dense_div >= 32 ? ctx->tuning.cgls_dense_div : kDenseDiv;   // below 32 the index lists outgrow the bitmap
+    hipLaunchKernelGGL(pair_sizes_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, sz, R, (int32_t)(n / dense_div), cnt, ctx->d_mail);
     DS_TRY(ds_mail_fetch(ctx, 4));
     if (ctx->h_mail[1] == 0) {
       hybrid = true;
@@ -380,9 +383,13 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
       csc_off = (int32_t*)ds_arena_alloc(ctx, (n + 2) * 4);
       int32_t* cursor = (int32_t*)ds_arena_alloc(ctx, (n + 2) * 4);
       Ztd = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * (RdW > 0 ? RdW : 1) * 8);
-      const size_t wsd = ds_bit_spmv_tab_ws_doubles(ctx, Rd, n), wsd2 = ds_bit_spmv_tab_ws_doubles(ctx, n, Rd);
-      tab_ws = (double*)ds_arena_alloc(ctx, 8 * (wsd > wsd2 ? wsd : wsd2) + 8);
-      if (!csr_idx || !csc_row || !csc_off || !cursor || !Ztd || !tab_ws) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
+      void* ws_f = ds_arena_alloc(ctx, ds_bit_spmv_mm_ws_bytes(ctx, Rd, n));
+      void* ws_a = ds_arena_alloc(ctx, ds_bit_spmv_mm_ws_bytes(ctx, n, Rd));
+      if (!csr_idx || !csc_row || !csc_off || !cursor || !Ztd || !ws_f || !ws_a) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
+      if (Rd > 0) {
+        DS_TRY(ds_bit_spmv_mm_prepare(ctx, Rd, n, ws_f, &mm_f));
+        DS_TRY(ds_bit_spmv_mm_prepare(ctx, n, Rd, ws_a, &mm_a));
+      }
       DS_TRY(ds_rows_to_csr(ctx, Z, Rs, n, W, 0, 2, csr_off, csr_idx));
       // column lists of the sparse rows = row lists of their transposed bitmap (a temporary): built by
       // the same ordered kernel, so every list is ascending and the sums are reproducible
@@ -406,7 +413,7 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
     if (!Zt) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
     DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, Zt));
   }
-  // In the hybrid layout the index-list product (sparse rows) and the table product (dense rows) are
+  // In the hybrid layout the index-list product (sparse rows) and the matrix-core product (dense rows) are
   // independent: the former runs on the context's second stream while the latter runs here (worth the two
   // cross-stream waits per product only when the index lists are long).
   const bool overlap = hybrid && Rs > 0 && Rd > 0 && nnz_s >= ((int64_t)1 << 22);
@@ -420,25 +427,29 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
     DS_HIP(ctx, hipEventRecord(ctx->join_ev, ctx->side));
     return DS_OK;
   };
+  // (the digits of the vector are written before the index-list product starts on the other stream: the two small
+  // kernels would otherwise queue behind its workgroups)
   auto forward = [&](const double* u, double* d) -> int {  // d = (rows) . u
     if (!hybrid) return ds_bit_spmv(ctx, Z, R, n, W, 0, paired ? 2 : 1, u, d);
+    DS_TRY(ds_bit_spmv_mm_digits(ctx, &mm_f, u));
     if (overlap) {
       DS_TRY(gather_on_side(csr_off, csr_idx, Rs, u, d));
-      DS_TRY(ds_bit_spmv_tab(ctx, Z, Rd, n, W, 2 * Rs, 2, u, nullptr, d + Rs, tab_ws));
+      DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_f, Z, W, 2 * Rs, 2, nullptr, d + Rs));
       DS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_ev, 0));
       return DS_OK;
     }
     DS_TRY(ds_csr_gather(ctx, csr_off, csr_idx, Rs, u, d));
-    return ds_bit_spmv_tab(ctx, Z, Rd, n, W, 2 * Rs, 2, u, nullptr, d + Rs, tab_ws);
+    return ds_bit_spmv_mm_product(ctx, &mm_f, Z, W, 2 * Rs, 2, nullptr, d + Rs);
   };
   auto adjoint = [&](const double* h, double* sv) -> int {  // s = (rows)^T . h
     if (!hybrid) return ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, h, sv);
-    if (overlap) {  // the table product's final summation adds the index-list result: it waits for it
+    DS_TRY(ds_bit_spmv_mm_digits(ctx, &mm_a, h + Rs));
+    if (overlap) {  // the dense product's final summation adds the index-list result: it waits for it
       DS_TRY(gather_on_side(csc_off, csc_row, n, h, sv));
-      return ds_bit_spmv_tab(ctx, Ztd, n, Rd, RdW, 0, 1, h + Rs, sv, sv, tab_ws, ctx->join_ev);
+      return ds_bit_spmv_mm_product(ctx, &mm_a, Ztd, RdW, 0, 1, sv, sv, ctx->join_ev);
     }
     if (Rs > 0) DS_TRY(ds_csr_gather(ctx, csc_off, csc_row, n, h, sv));
-    if (Rd > 0) return ds_bit_spmv_tab(ctx, Ztd, n, Rd, RdW, 0, 1, h + Rs, Rs > 0 ? sv : nullptr, sv, tab_ws);
+    if (Rd > 0) return ds_bit_spmv_mm_product(ctx, &mm_a, Ztd, RdW, 0, 1, Rs > 0 ? sv : nullptr, sv);
     return DS_OK;
   };
   DS_HIP(ctx, hipMemsetAsync(a.x, 0, n * 8, st));
