@@ -305,7 +305,7 @@ def test_gram_cholesky_matches_oracle_least_squares(ctx_tiny, n, ns):
 
 @pytest.mark.parametrize("n,ns,paired", [(12, 4096, 1), (40, 2000, 0), (40, 2000, 1), (333, 6000, 1),
                                          (1000, 20000, 1), (1000, 20000, 0), (3000, 1000, 1), (3000, 1000, 0),
-                                         # >= 4096 players and paired: index lists + byte tables
+                                         # >= 4096 players and paired: index lists + the matrix-core product of the dense rows
                                          (4100, 3000, 1), (6000, 14000, 1), (4097, 130, 1), (5000, 2000, 0)])
 def test_cgls_matches_oracle(ctx_tiny, n, ns, paired):
     from paper_2506_22668_amd import Options, DS_SOLVER_CGLS
@@ -320,6 +320,33 @@ def test_cgls_matches_oracle(ctx_tiny, n, ns, paired):
     assert np.abs(got - ref).max() <= 1e-4 * np.abs(ref).max()
     if n <= 1000:   # well-determined: also the dense least-squares answer
         assert np.abs(got - solve.solve_lstsq(bits, w, y)).max() <= 1e-4 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("dense_div", [32, 1024, 65536])
+def test_cgls_dense_row_threshold_leaves_the_solution_alone(ctx_tiny, dense_div):
+    """Which pair rows are multiplied as bitmaps on the matrix cores and which as index lists is a tuning choice:
+    nearly all dense (65536), the built-in split, nearly all sparse (32). 6,200 players: rows of 97 words, so the last
+    1024-column chunk is short and the transposed copy has an odd number of words per row."""
+    from paper_2506_22668_amd import Options, DS_SOLVER_CGLS
+    from paper_2506_22668_amd.binding import Tuning
+    ctx, _ = ctx_tiny
+    n, ns = 6200, 8250
+    say(f"cgls dense_div={dense_div}")
+    Z, w, bits, y = _solve_inputs(n, ns, 77)
+    ref, _, _ = solve.solve_cgls(bits, w, y, tol=1e-12)
+    args = (n, torch.from_numpy(Z.view(np.int64)).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(y).cuda(),
+            Options(solver=DS_SOLVER_CGLS, tol=1e-9, paired=1))
+    base, rep0, _ = ctx.solve(*args)
+    try:
+        ctx.set_tuning(Tuning(cgls_dense_div=dense_div))
+        phi, rep, _ = ctx.solve(*args)
+    finally:
+        ctx.set_tuning(None)
+    assert rep.cgls_rel_residual <= 1e-9
+    got = phi.cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref).max() <= 1e-4 * np.abs(ref).max()
+    assert np.abs(got - base.cpu().numpy()).max() <= 1e-6 * np.abs(ref).max()
+    assert abs(rep.cgls_iterations - rep0.cgls_iterations) <= 2
 
 
 def test_cgls_one_iteration_under_enumeration(ctx_tiny):
