@@ -160,8 +160,8 @@ typedef struct ds_tuning {
                                  256 rows or more and fall back to 1 where they do not apply (a test hook: the
                                  results agree to rounding) */
   int32_t cgls_dense_div;     /* CGLS on large games: pair rows with more than n / div players stay bit-packed and
-                                 are multiplied on the int8 matrix cores, the sparser ones become index lists
-                                 (default 128: where one gather per set bit costs what streaming the row does) */
+                                 are multiplied on the int8 matrix cores, the sparser ones become (row, column)
+                                 entries multiplied through LDS (default 64, the measured optimum; 32..65536) */
 } ds_tuning;
 int ds_set_tuning(ds_ctx* ctx, const ds_tuning* tuning /* [host] or NULL */);
 

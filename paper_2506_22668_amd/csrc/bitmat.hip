@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void bit_spmv_rows_kernel(const uint64_t*
 // (rows x cols 0/1 matrix) . (cols x 7 matrix of base-256 digits of x): exact integer arithmetic.
 //  * x is scaled by a power of two so that max|x| < 2^54 and rounded to integers (the same 2^-54
 //    relative step for every entry); each integer is written in seven balanced base-256 digits
-//    (-128..127), one int8 plane per digit (`digit_planes_kernel`).
+//    (-128..127), one int8 plane per digit (`quantize_kernel`).
 //  * A operand of v_mfma_i32_16x16x64_i8 = 16 rows x 64 columns of mask bits as bytes. A lane holds
 //    16 bytes of one row; the bytes come from the lane's four 32-bit mask words by ONE AND each:
 //    word & (0x01010101 << j) puts bit j of every mask byte into a byte of its own (value 2^j), so
@@ -226,10 +226,12 @@ __global__ __launch_bounds__(256) void absmax_kernel(const double* x, int64_t n,
   if ((threadIdx.x & 63) == 0 && m) atomicMax(slot, m);
 }
 
-// One thread per 4 plane positions (i = 0..3: columns 8 apart). scal[0] = the power of two that turns the integer
-// result back into the scale of x (NaN if x holds a non-finite value: the product is then NaN everywhere).
-__global__ __launch_bounds__(256) void digit_planes_kernel(const double* x, int64_t n, int64_t npad, const unsigned long long* slot,
-                                                           int8_t* D, double* scal) {
+// The fixed-point form of a vector: scal[0] = the power of two that turns integer results back into the scale of x
+// (NaN if the vector holds a non-finite value: the products are then NaN everywhere). Two roles per thread:
+//  * digit planes of xp[0..n) (npad > 0): one thread per 4 plane positions (i = 0..3: columns 8 apart);
+//  * q64[i] = round(xq[i] * 2^f) for i < qlen (the index-tile products read these): four entries per thread.
+__global__ __launch_bounds__(256) void quantize_kernel(const double* xp, int64_t n, int64_t npad, const unsigned long long* slot,
+                                                       int8_t* D, double* scal, const double* xq, int64_t qlen, long long* q64) {
   const double mx = __longlong_as_double((long long)*slot);
   const bool finite = mx < __longlong_as_double(0x7ff0000000000000ll);
   int e = 0;
@@ -238,6 +240,11 @@ __global__ __launch_bounds__(256) void digit_planes_kernel(const double* x, int6
   const int64_t q4 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (q4 == 0) scal[0] = finite ? ldexp(1.0, -f) : __longlong_as_double(0x7ff8000000000000ll);
   const int64_t pos0 = q4 * 4;
+  if (pos0 < qlen) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (pos0 + i < qlen) q64[pos0 + i] = finite ? __double2ll_rn(ldexp(xq[pos0 + i], f)) : 0ll;
+  }
   if (pos0 >= npad) return;
   const int p = (int)(pos0 & 127);
   const int j = p >> 4, v = (p >> 2) & 3;
@@ -246,7 +253,7 @@ __global__ __launch_bounds__(256) void digit_planes_kernel(const double* x, int6
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int64_t col = colbase + (i << 3);
-    long long q = (finite && col < n) ? __double2ll_rn(ldexp(x[col], f)) : 0ll;
+    long long q = (finite && col < n) ? __double2ll_rn(ldexp(xp[col], f)) : 0ll;
 #pragma unroll
     for (int d = 0; d < kMmDigits; ++d) {
       const int di = (int)(int8_t)(q & 0xFF);
@@ -394,12 +401,12 @@ __global__ __launch_bounds__(kMmWaves * 64) void bit_spmv_mm_kernel(const uint64
   }
 }
 
-// out[r] = (addend[r] or 0) + scal[0] * sum_d 256^d * (sum over the column groups of digit sum d); also clears the
-// maximum slot for the next product
+// out[r] = (addend[r] or 0) + scal[0] * sum_d 256^d * (sum over the column groups of digit sum d); clears the
+// maximum slot for the next product if asked to
 __global__ __launch_bounds__(256) void mm_reduce_kernel(const int32_t* partial, int64_t rows, int groups, const double* scal,
                                                         const double* addend, double* out, unsigned long long* slot) {
   const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (r == 0) *slot = 0ull;
+  if (r == 0 && slot) *slot = 0ull;
   if (r >= rows) return;
   long long S[kMmPlanes] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int gq = 0; gq < groups; ++gq) {
@@ -419,7 +426,7 @@ __global__ __launch_bounds__(256) void mm_reduce_kernel(const int32_t* partial, 
   out[r] = addend ? addend[r] + val : val;
 }
 
-// ---- sparse rows: index lists ----------------------------------------------------------------
+// ---- sparse rows: index lists (the input of the tile build) ------------------------------------
 // idx[off[i] .. off[i+1]) = ascending columns of the set bits of row i; one wave per row
 __global__ __launch_bounds__(kThreads) void rows_to_csr_kernel(const uint64_t* B, int64_t rows, int64_t cols, int64_t stride,
                                                                int64_t row_first, int64_t row_step, const int32_t* off,
@@ -452,27 +459,6 @@ __global__ __launch_bounds__(kThreads) void rows_to_csr_kernel(const uint64_t* B
   }
 }
 
-// out[i] = sum_{e in [off[i], off[i+1])} x[idx[e]]; one wave per row, rows taken from the long end first
-__global__ __launch_bounds__(kThreads) void csr_gather_kernel(const int32_t* off, const int32_t* idx, int64_t rows,
-                                                              const double* x, double* out) {
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-  for (int64_t w = wave; w < rows; w += nwaves) {
-    const int64_t i = rows - 1 - w;
-    const int32_t a = off[i], b = off[i + 1];
-    double s0 = 0.0, s1 = 0.0;
-    int32_t e = a + lane;
-    for (; e + 64 < b; e += 128) {
-      s0 += x[idx[e]];
-      s1 += x[idx[e + 64]];
-    }
-    if (e < b) s0 += x[idx[e]];
-    double s = s0 + s1;
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    if (lane == 0) out[i] = s;
-  }
-}
 }  // namespace
 
 int ds_bit_spmv(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
@@ -531,43 +517,43 @@ static void mm_shape(const ds_ctx* ctx, int64_t rows, int64_t cols, ds_mm_plan* 
 size_t ds_bit_spmv_mm_ws_bytes(const ds_ctx* ctx, int64_t rows, int64_t cols) {
   ds_mm_plan p;
   mm_shape(ctx, rows, cols, &p);
-  return 256 + ds_align((size_t)kMmPlanes * p.npad) + ds_align((size_t)p.groups * rows * kMmPlanes * 4);
+  return ds_align((size_t)kMmPlanes * p.npad) + ds_align((size_t)p.groups * rows * kMmPlanes * 4);
 }
 
 int ds_bit_spmv_mm_prepare(ds_ctx* ctx, int64_t rows, int64_t cols, void* ws, ds_mm_plan* plan) {
   mm_shape(ctx, rows, cols, plan);
   char* p = (char*)ws;
-  plan->scal = (double*)p;
-  plan->D = (int8_t*)(p + 256);
-  plan->partial = (int32_t*)(p + 256 + ds_align((size_t)kMmPlanes * plan->npad));
-  DS_HIP(ctx, hipMemsetAsync(plan->scal, 0, 256, ctx->stream));                                    // scale and maximum slot
+  plan->D = (int8_t*)p;
+  plan->partial = (int32_t*)(p + ds_align((size_t)kMmPlanes * plan->npad));
   DS_HIP(ctx, hipMemsetAsync(plan->D + (size_t)kMmDigits * plan->npad, 0, plan->npad, ctx->stream));  // the zero plane
   return DS_OK;
 }
 
-int ds_bit_spmv_mm_digits(ds_ctx* ctx, const ds_mm_plan* p, const double* x) {
-  if (p->rows <= 0) return DS_OK;
-  unsigned long long* slot = (unsigned long long*)(p->scal + 1);
-  int64_t mb = (p->cols + 2047) / 2048;
+int ds_vec_quantize(ds_ctx* ctx, const double* x_all, int64_t len_all, const ds_mm_plan* planes, const double* x_planes,
+                    const double* x_q, int64_t qlen, long long* q64, double* scal) {
+  unsigned long long* slot = (unsigned long long*)(scal + 1);
+  int64_t mb = (len_all + 2047) / 2048;
   if (mb > 2 * (int64_t)ctx->num_cus) mb = 2 * (int64_t)ctx->num_cus;
-  hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)mb), dim3(256), 0, ctx->stream, x, p->cols, slot);
-  hipLaunchKernelGGL(digit_planes_kernel, dim3((unsigned)((p->npad / 4 + 255) / 256)), dim3(256), 0, ctx->stream, x, p->cols,
-                     p->npad, slot, p->D, p->scal);
+  if (mb < 1) mb = 1;
+  hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)mb), dim3(256), 0, ctx->stream, x_all, len_all, slot);
+  const bool with_planes = planes && planes->rows > 0;
+  const int64_t npad = with_planes ? planes->npad : 0;
+  const int64_t span = npad > qlen ? npad : qlen;
+  hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)((span / 4 + 256) / 256)), dim3(256), 0, ctx->stream, x_planes,
+                     with_planes ? planes->cols : 0, npad, slot, with_planes ? planes->D : nullptr, scal, x_q, qlen, q64);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }
 
 int ds_bit_spmv_mm_product(ds_ctx* ctx, const ds_mm_plan* p, const uint64_t* B, int64_t stride, int64_t row_first,
-                           int64_t row_step, const double* addend, double* out, hipEvent_t addend_ready) {
+                           int64_t row_step, const double* scal, const double* addend, double* out, int clear_slot) {
   if (p->rows <= 0) return DS_OK;
   if (row_step * stride * 8 * 16 >= ((int64_t)1 << 32))
     return ds_fail(ctx, DS_EINTERNAL, "matrix-core product: rows of %lld bytes are too far apart", (long long)(row_step * stride * 8));
-  unsigned long long* slot = (unsigned long long*)(p->scal + 1);
   hipLaunchKernelGGL(bit_spmv_mm_kernel, dim3((unsigned)p->row_groups, (unsigned)p->groups), dim3(kMmWaves * 64), 0, ctx->stream,
                      B, p->rows, p->cols, stride, row_first, row_step, p->D, p->npad, p->partial, p->cpg, p->n_chunks);
-  if (addend_ready) DS_HIP(ctx, hipStreamWaitEvent(ctx->stream, addend_ready, 0));  // the addend comes from another stream
   hipLaunchKernelGGL(mm_reduce_kernel, dim3((unsigned)((p->rows + 255) / 256)), dim3(256), 0, ctx->stream, p->partial, p->rows,
-                     (int)p->groups, p->scal, addend, out, slot);
+                     (int)p->groups, scal, addend, out, clear_slot ? (unsigned long long*)(scal + 1) : (unsigned long long*)nullptr);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }
@@ -579,15 +565,6 @@ int ds_rows_to_csr(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, i
   if (blocks > (int64_t)ctx->num_cus * 16) blocks = (int64_t)ctx->num_cus * 16;
   hipLaunchKernelGGL(rows_to_csr_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, B, rows, cols, stride,
                      row_first, row_step, off, idx);
-  DS_HIP(ctx, hipGetLastError());
-  return DS_OK;
-}
-
-int ds_csr_gather(ds_ctx* ctx, const int32_t* off, const int32_t* idx, int64_t rows, const double* x, double* out) {
-  if (rows <= 0) return DS_OK;
-  int64_t blocks = (rows * 64 + kThreads - 1) / kThreads;
-  if (blocks > (int64_t)ctx->num_cus * 16) blocks = (int64_t)ctx->num_cus * 16;
-  hipLaunchKernelGGL(csr_gather_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, off, idx, rows, x, out);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }

@@ -289,31 +289,23 @@ __global__ void pair_sizes_kernel(const int32_t* sz, int64_t R, int32_t thr, int
   if (r > 0 && sz[2 * (r - 1)] > c) atomicExch((unsigned long long*)&mail[1], 1ull);
 }
 
-// cnt[i] = number of set bits of row i (rows of `words` 64-bit words); one wave per row
-__global__ __launch_bounds__(kThreads) void row_popcount_kernel(const uint64_t* B, int64_t rows, int64_t words, int32_t* cnt) {
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-  for (int64_t i = wave; i < rows; i += nwaves) {
-    int c = 0;
-    for (int64_t wd = lane; wd < words; wd += 64) c += __popcll(B[i * words + wd]);
-    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
-    if (lane == 0) cnt[i] = c;
-  }
-}
-
 constexpr int64_t kHybridMinPlayers = 4096;  // below this the plain bit walk is already cheap
-constexpr int32_t kDenseDiv = 128;           // pair rows with more than n / 128 players are multiplied as bitmaps
+constexpr int32_t kDenseDiv = 64;            // pair rows with more than n / 64 players are multiplied as bitmaps
 
 }  // namespace
 
 size_t ds_cgls_arena_bytes(int64_t n, int64_t k) {
   const int64_t KW = (k + 63) / 64;
-  // the hybrid storage (index lists both ways for the sparse rows + transposed bitmap of the dense rows)
-  // never exceeds twice the plain transposed bitmap, and building it needs one more as a temporary;
-  // plus offsets and the scratch of the two matrix-core products (digit planes, per-group digit sums)
+  // The hybrid storage never exceeds 1.5 x the plain transposed bitmap: the transposed bitmap of the dense pair rows
+  // is at most half of it, and the index lists of the sparse rows (needed while their tiles are built) and the tile
+  // entries take 4 bytes per set bit of rows with at most n/32 of them each. Plus offsets, the scratch of the two
+  // matrix-core products (digit planes, per-group digit sums) and of the tile products (per-group partial vectors,
+  // tile counters, the vectors as 64-bit integers).
+  const size_t tile_scratch = ds_align((size_t)(2 * (k / 32768) + 32) * n * 8) + ds_align((size_t)32 * k * 8) +
+                              ds_align((size_t)(k / 8192 + 160) * (n / 8192 + 2) * 8) + ds_align((size_t)(n + k) * 8);
   const size_t hybrid = 3 * ds_align((size_t)n * KW * 8) + 4 * ds_align((n + 2) * 4) + 2 * ds_align((k + 2) * 4) +
-                        ds_align(96 * (size_t)(n > k ? n : k)) + ((size_t)80 << 20) + 4 * ds_scan_arena_bytes(n > k ? n + 1 : k + 1);
+                        ds_align(96 * (size_t)(n > k ? n : k)) + ((size_t)80 << 20) + tile_scratch +
+                        4 * ds_scan_arena_bytes(n > k ? n + 1 : k + 1);
   return hybrid + 2 * ds_align(k * 4) + 7 * ds_align(k * 8) + 4 * ds_align(n * 8) + 65536;
 }
 
@@ -349,62 +341,58 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   DS_TRY(ds_row_prep(ctx, Z, k, n, w, y, sz, t, sqw, wc));
 
   // ---- storage for the two products ----
-  // Paired, size-sorted rows of a large game: the small members with at most n/128 players become
-  // index lists in both orientations (one 8-byte gather per set bit: cheaper than streaming the
-  // n/8-byte bitmap row only below that density), the denser tail stays a bitmap (rows of Z itself,
-  // plus a transposed copy) and is multiplied on the int8 matrix cores. Otherwise: plain bitmap and
-  // its transpose, set bits walked one by one.
+  // Paired, size-sorted rows of a large game: the small members with at most n/div players become
+  // (row, column) entries in 2-D tiles that serve both products through LDS, the denser tail stays a
+  // bitmap (rows of Z itself, plus a transposed copy) and is multiplied on the int8 matrix cores; both
+  // in fixed point with exact integer sums. Otherwise: plain bitmap and its transpose, set bits walked
+  // one by one in fp64.
   bool hybrid = false;
   int64_t Rs = 0, Rd = 0, RdW = 0, nnz_s = 0;
-  int32_t *csr_off = nullptr, *csr_idx = nullptr, *csc_off = nullptr, *csc_row = nullptr;
   uint64_t *Zt = nullptr, *Ztd = nullptr;
   ds_mm_plan mm_f = {}, mm_a = {};   // dense rows: forward (Rd x n) and adjoint (n x Rd) products
+  ds_tile_plan tiles = {};           // sparse rows: one entry list for both products
+  long long *q64u = nullptr, *q64h = nullptr;   // the vectors of the two products as integers (for the sparse rows)
+  double *scal_f = nullptr, *scal_a = nullptr;  // [0] scale, [1] maximum slot of the forward / adjoint product
   if (paired && n >= kHybridMinPlayers && n < ((int64_t)1 << 28)) {   // (the matrix-core product addresses rows with 32 bits)
     int32_t* cnt = (int32_t*)ds_arena_alloc(ctx, (R + 1) * 4);
     if (!cnt) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
     DS_HIP(ctx, hipMemsetAsync(ctx->d_mail, 0, 4 * sizeof(int64_t), st));
     const int32_t dense_div = ctx->tuning.cgls_dense_div >= 32 ? ctx->tuning.cgls_dense_div : kDenseDiv;   // below 32 the index lists outgrow the bitmap
-    hipLaunchKernelGGL(pair_sizes_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, sz, R, (int32_t)(n / dense_div), cnt, ctx->d_mail);
+    const int32_t thr = (int32_t)(n / dense_div);
+    hipLaunchKernelGGL(pair_sizes_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, sz, R, thr, cnt, ctx->d_mail);
     DS_TRY(ds_mail_fetch(ctx, 4));
     if (ctx->h_mail[1] == 0) {
       hybrid = true;
       Rs = ctx->h_mail[0];
       Rd = R - Rs;
       RdW = (Rd + 63) / 64;
-      csr_off = (int32_t*)ds_arena_alloc(ctx, (Rs + 2) * 4);
+      int32_t* csr_off = (int32_t*)ds_arena_alloc(ctx, (Rs + 2) * 4);
       if (!csr_off) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
       DS_HIP(ctx, hipMemsetAsync(cnt + Rs, 0, 4, st));  // the scan's last slot: total
       DS_TRY(ds_scan_exclusive_i32(ctx, cnt, csr_off, Rs + 1, ctx->d_mail + 2));
       DS_TRY(ds_mail_fetch(ctx, 4));
       nnz_s = ctx->h_mail[2];
       if (nnz_s > 0x7fffff00LL) return ds_fail(ctx, DS_EINTERNAL, "cgls: too many set bits in the sparse rows (%lld)", (long long)nnz_s);
-      csr_idx = (int32_t*)ds_arena_alloc(ctx, (nnz_s + 1) * 4);
-      csc_row = (int32_t*)ds_arena_alloc(ctx, (nnz_s + 1) * 4);
-      csc_off = (int32_t*)ds_arena_alloc(ctx, (n + 2) * 4);
-      int32_t* cursor = (int32_t*)ds_arena_alloc(ctx, (n + 2) * 4);
       Ztd = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * (RdW > 0 ? RdW : 1) * 8);
       void* ws_f = ds_arena_alloc(ctx, ds_bit_spmv_mm_ws_bytes(ctx, Rd, n));
       void* ws_a = ds_arena_alloc(ctx, ds_bit_spmv_mm_ws_bytes(ctx, n, Rd));
-      if (!csr_idx || !csc_row || !csc_off || !cursor || !Ztd || !ws_f || !ws_a) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
+      void* ws_t = ds_arena_alloc(ctx, ds_tile_ws_bytes(ctx, Rs, n, nnz_s));
+      q64u = (long long*)ds_arena_alloc(ctx, n * 8);
+      q64h = (long long*)ds_arena_alloc(ctx, (Rs + 1) * 8);
+      scal_f = (double*)ds_arena_alloc(ctx, 256);
+      int32_t* csr_idx = (int32_t*)ds_arena_alloc(ctx, (nnz_s + 1) * 4);   // (index lists; the tile build keeps the memory)
+      if (!Ztd || !ws_f || !ws_a || !ws_t || !q64u || !q64h || !scal_f || !csr_idx) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
+      scal_a = scal_f + 16;
+      DS_HIP(ctx, hipMemsetAsync(scal_f, 0, 256, st));
       if (Rd > 0) {
         DS_TRY(ds_bit_spmv_mm_prepare(ctx, Rd, n, ws_f, &mm_f));
         DS_TRY(ds_bit_spmv_mm_prepare(ctx, n, Rd, ws_a, &mm_a));
+        DS_TRY(ds_bit_transpose(ctx, Z, Rd, n, W, 2 * Rs, 2, Ztd));
       }
-      DS_TRY(ds_rows_to_csr(ctx, Z, Rs, n, W, 0, 2, csr_off, csr_idx));
-      // column lists of the sparse rows = row lists of their transposed bitmap (a temporary): built by
-      // the same ordered kernel, so every list is ascending and the sums are reproducible
-      DS_HIP(ctx, hipMemsetAsync(csc_off, 0, (n + 2) * 4, st));
       if (Rs > 0) {
-        const int64_t RsW = (Rs + 63) / 64;
-        uint64_t* Zts = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * RsW * 8);
-        if (!Zts) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
-        DS_TRY(ds_bit_transpose(ctx, Z, Rs, n, W, 0, 2, Zts));
-        hipLaunchKernelGGL(row_popcount_kernel, dim3(ctx->num_cus * 8), dim3(kThreads), 0, st, Zts, n, RsW, csc_off);
-        DS_TRY(ds_scan_exclusive_i32(ctx, csc_off, csc_off, n + 1, nullptr));
-        DS_TRY(ds_rows_to_csr(ctx, Zts, n, Rs, RsW, 0, 1, csc_off, csc_row));
+        DS_TRY(ds_rows_to_csr(ctx, Z, Rs, n, W, 0, 2, csr_off, csr_idx));
+        DS_TRY(ds_tile_build(ctx, Rs, n, nnz_s, thr > 1 ? thr : 1, csr_off, csr_idx, ws_t, &tiles));
       }
-      (void)cursor;
-      if (Rd > 0) DS_TRY(ds_bit_transpose(ctx, Z, Rd, n, W, 2 * Rs, 2, Ztd));
       DS_HIP(ctx, hipGetLastError());
     }
   }
@@ -413,43 +401,21 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
     if (!Zt) return ds_fail(ctx, DS_EINTERNAL, "cgls: arena exhausted");
     DS_TRY(ds_bit_transpose(ctx, Z, R, n, W, 0, paired ? 2 : 1, Zt));
   }
-  // In the hybrid layout the index-list product (sparse rows) and the matrix-core product (dense rows) are
-  // independent: the former runs on the context's second stream while the latter runs here (worth the two
-  // cross-stream waits per product only when the index lists are long).
-  const bool overlap = hybrid && Rs > 0 && Rd > 0 && nnz_s >= ((int64_t)1 << 22);
-  auto gather_on_side = [&](const int32_t* off, const int32_t* idx, int64_t rows, const double* x, double* out) -> int {
-    DS_HIP(ctx, hipEventRecord(ctx->fork_ev, st));
-    DS_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->fork_ev, 0));
-    ctx->stream = ctx->side;
-    const int rc = ds_csr_gather(ctx, off, idx, rows, x, out);
-    ctx->stream = st;
-    DS_TRY(rc);
-    DS_HIP(ctx, hipEventRecord(ctx->join_ev, ctx->side));
-    return DS_OK;
-  };
-  // (the digits of the vector are written before the index-list product starts on the other stream: the two small
-  // kernels would otherwise queue behind its workgroups)
+  // Hybrid layout: the vector is brought into fixed point once per product; the sparse rows' tiles and the dense
+  // rows' bitmap are multiplied one after the other (side by side on two streams they only competed for memory
+  // bandwidth and the iteration took 8 % longer), the dense product adding the sparse result in the adjoint.
   auto forward = [&](const double* u, double* d) -> int {  // d = (rows) . u
     if (!hybrid) return ds_bit_spmv(ctx, Z, R, n, W, 0, paired ? 2 : 1, u, d);
-    DS_TRY(ds_bit_spmv_mm_digits(ctx, &mm_f, u));
-    if (overlap) {
-      DS_TRY(gather_on_side(csr_off, csr_idx, Rs, u, d));
-      DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_f, Z, W, 2 * Rs, 2, nullptr, d + Rs));
-      DS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_ev, 0));
-      return DS_OK;
-    }
-    DS_TRY(ds_csr_gather(ctx, csr_off, csr_idx, Rs, u, d));
-    return ds_bit_spmv_mm_product(ctx, &mm_f, Z, W, 2 * Rs, 2, nullptr, d + Rs);
+    DS_TRY(ds_vec_quantize(ctx, u, n, &mm_f, u, u, Rs > 0 ? n : 0, q64u, scal_f));
+    if (Rs > 0) DS_TRY(ds_tile_spmv(ctx, &tiles, 0, q64u, scal_f, d, Rd > 0 ? 0 : 1));
+    if (Rd > 0) DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_f, Z, W, 2 * Rs, 2, scal_f, nullptr, d + Rs, 1));
+    return DS_OK;
   };
   auto adjoint = [&](const double* h, double* sv) -> int {  // s = (rows)^T . h
     if (!hybrid) return ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, h, sv);
-    DS_TRY(ds_bit_spmv_mm_digits(ctx, &mm_a, h + Rs));
-    if (overlap) {  // the dense product's final summation adds the index-list result: it waits for it
-      DS_TRY(gather_on_side(csc_off, csc_row, n, h, sv));
-      return ds_bit_spmv_mm_product(ctx, &mm_a, Ztd, RdW, 0, 1, sv, sv, ctx->join_ev);
-    }
-    if (Rs > 0) DS_TRY(ds_csr_gather(ctx, csc_off, csc_row, n, h, sv));
-    if (Rd > 0) return ds_bit_spmv_mm_product(ctx, &mm_a, Ztd, RdW, 0, 1, Rs > 0 ? sv : nullptr, sv);
+    DS_TRY(ds_vec_quantize(ctx, h, R, &mm_a, h + Rs, h, Rs, q64h, scal_a));
+    if (Rs > 0) DS_TRY(ds_tile_spmv(ctx, &tiles, 1, q64h, scal_a, sv, Rd > 0 ? 0 : 1));
+    if (Rd > 0) DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_a, Ztd, RdW, 0, 1, scal_a, Rs > 0 ? sv : nullptr, sv, 1));
     return DS_OK;
   };
   DS_HIP(ctx, hipMemsetAsync(a.x, 0, n * 8, st));

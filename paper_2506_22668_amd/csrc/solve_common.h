@@ -12,23 +12,47 @@ int ds_bit_transpose(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols
 // out[i] = sum of x[j] over the set bits j < cols of row (row_first + i*row_step) of B, i < rows (fp64)
 int ds_bit_spmv(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
                 int64_t row_step, const double* x, double* out);
-// The same product for dense rows on the int8 matrix cores (x split into base-256 digits: exact integer sums);
-// out = (addend or 0) + result. A plan fixes the launch shape and the scratch of one (rows, cols) shape:
-// ds_bit_spmv_mm_ws_bytes bytes at `ws`, which ds_bit_spmv_mm_prepare initialises (on ctx->stream).
+// ---- products of the CGLS matrix of a large game in fixed point (exact integer sums) ----
+// Every product starts with ds_vec_quantize: scal[1] (the bit pattern of max |x|, 0 on entry) is found over
+// x_all[0..len_all), scal[0] becomes the power of two that scales integer results back, and the vector is written as
+// digit planes for the matrix-core product (x_planes[0..planes->cols), if `planes` has rows) and/or as 64-bit
+// integers q64[i] = round(x_q[i] * 2^f), i < qlen (if qlen > 0). The product that runs last clears scal[1].
+//
+// Dense rows on the int8 matrix cores (x split into base-256 digits); out = (addend or 0) + result. A plan fixes
+// the launch shape and the scratch of one (rows, cols) shape: ds_bit_spmv_mm_ws_bytes bytes at `ws`, which
+// ds_bit_spmv_mm_prepare initialises (on ctx->stream).
 struct ds_mm_plan {
   int64_t rows, cols, row_groups, n_chunks, groups, cpg, npad;
-  double* scal;      // [0] scale of the current product, [1] bit pattern of max |x| (cleared by every product)
   int8_t* D;         // eight digit planes of npad bytes (the last one stays zero)
   int32_t* partial;  // [groups][rows][8] digit sums
 };
 size_t ds_bit_spmv_mm_ws_bytes(const ds_ctx* ctx, int64_t rows, int64_t cols);
 int ds_bit_spmv_mm_prepare(ds_ctx* ctx, int64_t rows, int64_t cols, void* ws, ds_mm_plan* plan);
-// A product is two calls: the digits of x (two small kernels), then the product proper.
-// addend_ready: optional event the final summation waits for (an addend produced on another stream)
-int ds_bit_spmv_mm_digits(ds_ctx* ctx, const ds_mm_plan* plan, const double* x);
+int ds_vec_quantize(ds_ctx* ctx, const double* x_all, int64_t len_all, const ds_mm_plan* planes, const double* x_planes,
+                    const double* x_q, int64_t qlen, long long* q64, double* scal);
 int ds_bit_spmv_mm_product(ds_ctx* ctx, const ds_mm_plan* plan, const uint64_t* B, int64_t stride, int64_t row_first,
-                           int64_t row_step, const double* addend, double* out, hipEvent_t addend_ready = nullptr);
-// index lists of the set bits of rows (off = exclusive prefix sums of the row sizes), and the gather-sum over them
+                           int64_t row_step, const double* scal, const double* addend, double* out, int clear_slot);
+
+// Sparse rows as 2-D tiles of (row, column) entries: one list serves both products. Built from the index lists of the
+// rows (off = exclusive prefix sums of the row sizes, idx = ascending columns); rows must not hold more than
+// max_row_size entries. ws: ds_tile_ws_bytes bytes. The plan keeps `idx`'s memory (the entries end up there) and
+// `off` is free after the call.
+struct ds_tile_plan {
+  int64_t rows, cols, nnz;
+  int32_t nrb, ncb, nga, gf, cpg;   // row blocks, column chunks, adjoint row-block groups, forward chunk groups (of cpg)
+  int sh_f, sh_a;                   // bits dropped (rounded) from the 2^-54-scaled integers so that the sums fit 63 bits
+  int32_t *rb_start, *ga_start, *tile_off;
+  uint32_t* ent;
+  long long* partial;
+};
+size_t ds_tile_ws_bytes(const ds_ctx* ctx, int64_t rows, int64_t cols, int64_t nnz);
+int ds_tile_build(ds_ctx* ctx, int64_t rows, int64_t cols, int64_t nnz, int64_t max_row_size, const int32_t* off,
+                  int32_t* idx, void* ws, ds_tile_plan* plan);
+// forward: out[r] = sum of x[c] over the entries of row r (q64 = the 64-bit form of x, cols entries);
+// adjoint: out[c] = sum of x[r] over the entries of column c (q64 of rows entries)
+int ds_tile_spmv(ds_ctx* ctx, const ds_tile_plan* plan, int adjoint, const long long* q64, const double* scal, double* out,
+                 int clear_slot);
+
+// index lists of the set bits of rows (off = exclusive prefix sums of the row sizes)
 int ds_rows_to_csr(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
                    int64_t row_step, const int32_t* off, int32_t* idx);
-int ds_csr_gather(ds_ctx* ctx, const int32_t* off, const int32_t* idx, int64_t rows, const double* x, double* out);
