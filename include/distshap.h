@@ -117,9 +117,10 @@ typedef struct ds_report {
    *   sample: k*W*8 mask bytes + k*8 bytes of weights and sizes written;
    *   eval:   one member of every complementary pair read (the other is its complement and needs no second
    *           look), (k/2)*W*8, plus k*4 bytes of outputs;
-   *   solve:  CGLS: per iteration the small member of every pair once for Z u and once for Z^T r,
-   *           iterations * 2 * (k/2)*W*8; Gram + Cholesky: (k/2)*W*8 mask bytes read, n*n*4 bytes of Gram
-   *           matrix written. */
+   *   solve:  CGLS: per iteration the small member of every pair once for Z u and once for Z^T r, in the storage
+   *           the solver keeps them in: iterations * 2 * (bit-packed rows * W*8 + 4 bytes per set bit of the rows
+   *           kept as (row, column) entries); all rows bit-packed for games below 4,096 players. Gram + Cholesky:
+   *           (k/2)*W*8 mask bytes read, n*n*4 bytes of Gram matrix written. */
   double bytes_sample, bytes_eval, bytes_solve;
   float ms_k_stream;      /* the mask-streaming kernel alone (long mask rows; part of ms_k_eval), else 0 */
 } ds_report;

@@ -684,7 +684,7 @@ static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t
     const double row_bytes = (double)W * 8.0, half = (double)(k / 2);
     rep.bytes_sample = (double)k * row_bytes + (double)k * 8.0;
     rep.bytes_eval = half * row_bytes + (double)k * 4.0;
-    rep.bytes_solve = rep.solver_used == DS_SOLVER_CGLS ? (double)rep.cgls_iterations * 2.0 * half * row_bytes
+    rep.bytes_solve = rep.solver_used == DS_SOLVER_CGLS ? (double)rep.cgls_iterations * ctx->cgls_bytes_per_iter
                                                         : half * row_bytes + (double)n * (double)n * 4.0;
   }
   if (report) *report = rep;

@@ -301,7 +301,7 @@ size_t ds_cgls_arena_bytes(int64_t n, int64_t k) {
   // entries take 4 bytes per set bit of rows with at most n/32 of them each. Plus offsets, the scratch of the two
   // matrix-core products (digit planes, per-group digit sums) and of the tile products (per-group partial vectors,
   // tile counters, the vectors as 64-bit integers).
-  const size_t tile_scratch = ds_align((size_t)(2 * (k / 32768) + 32) * n * 8) + ds_align((size_t)32 * k * 8) +
+  const size_t tile_scratch = ds_align((size_t)(2 * (k / 32768) + 160) * n * 8) + ds_align((size_t)32 * k * 8) +
                               ds_align((size_t)(k / 8192 + 160) * (n / 8192 + 2) * 8) + ds_align((size_t)(n + k) * 8);
   const size_t hybrid = 3 * ds_align((size_t)n * KW * 8) + 4 * ds_align((n + 2) * 4) + 2 * ds_align((k + 2) * 4) +
                         ds_align(96 * (size_t)(n > k ? n : k)) + ((size_t)80 << 20) + tile_scratch +
@@ -418,6 +418,9 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
     if (Rd > 0) DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_a, Ztd, RdW, 0, 1, scal_a, Rs > 0 ? sv : nullptr, sv, 1));
     return DS_OK;
   };
+  // what one iteration must read of the matrix: the bitmap rows of both orientations and 4 bytes per tile entry, twice
+  ctx->cgls_bytes_per_iter = hybrid ? 2.0 * ((double)Rd * (double)W * 8.0 + 4.0 * (double)nnz_s)
+                                    : 2.0 * (double)R * (double)W * 8.0;
   DS_HIP(ctx, hipMemsetAsync(a.x, 0, n * 8, st));
   DS_HIP(ctx, hipMemsetAsync(a.u, 0, n * 8, st));
   DS_HIP(ctx, hipMemsetAsync(a.scal, 0, 128, st));

@@ -98,6 +98,7 @@ struct ds_ctx {
   std::vector<ds_ctx*> workers;
   bool owns_stream;
   ds_tuning tuning;  // zero fields = built-in values
+  double cgls_bytes_per_iter;  // bytes of matrix storage the last CGLS solve read per iteration (both products)
 };
 
 int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...);

@@ -35,8 +35,11 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
       k0 += 0x9E3779B9u;
       k1 += 0xBB67AE85u;
     }
-    uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
-    uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    // one 32 x 32 -> 64 multiply per product (as a high and a low multiply the generator ran 18 % slower)
+    unsigned long long p0, p1;
+    asm("v_mad_u64_u32 %0, vcc, %1, %2, 0" : "=v"(p0) : "v"(c0), "s"(M0) : "vcc");
+    asm("v_mad_u64_u32 %0, vcc, %1, %2, 0" : "=v"(p1) : "v"(c2), "s"(M1) : "vcc");
+    const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0, hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
     c0 = hi1 ^ c1 ^ k0;
     c1 = lo1;
     c2 = hi0 ^ c3 ^ k1;
@@ -98,6 +101,8 @@ struct SampleArgs {
   int32_t* sz;
   int* error_flag;
   uint32_t window_cap;  // entries of the dynamic-LDS window list
+  int32_t* retry;          // pairs the one-pass kernel hands to the multi-pass kernel (offsets from pair_begin), or null
+  uint32_t* retry_count;
 };
 
 __global__ __launch_bounds__(kThreads) void sample_pairs_kernel(SampleArgs a) {
@@ -116,7 +121,9 @@ __global__ __launch_bounds__(kThreads) void sample_pairs_kernel(SampleArgs a) {
   const int64_t nq = (n + 3) >> 2;
   const uint64_t tail_mask = (n & 63) ? ((1ull << (n & 63)) - 1ull) : ~0ull;
 
-  for (int64_t r = a.pair_begin + blockIdx.x; r < a.pair_end; r += gridDim.x) {
+  const int64_t todo = a.retry ? (int64_t)*a.retry_count : a.pair_end - a.pair_begin;
+  for (int64_t it = blockIdx.x; it < todo; it += gridDim.x) {
+    const int64_t r = a.pair_begin + (a.retry ? (int64_t)a.retry[it] : it);
     uint64_t* row_small = a.Z + (2 * (r - a.pair_begin)) * W;
     uint64_t* row_big = row_small + W;
     if (r == 0) {  // (empty, full): the two constraint rows
@@ -326,6 +333,169 @@ __global__ __launch_bounds__(kThreads) void sample_pairs_kernel(SampleArgs a) {
   }
 }
 
+// The common case in one pass over the keys. The s-th smallest of n uniform 32-bit keys lies within a few standard
+// deviations of (s/n) 2^32; so while the keys are generated once, every column whose key falls below a window
+// around that value gets its bit at once (a lane builds one 32-bit word of the row from eight generator calls and
+// stores it), the few keys inside the window are listed, and the keys below the window are counted. The threshold
+// is then the (s - below)-th smallest of the listed (key, column) pairs, found through a histogram of the window's
+// sub-ranges and a rank count inside the threshold's sub-range, and the listed columns at or below it are added to
+// the written row with atomics. Pairs whose threshold falls outside the window (about 0.3 %) or whose lists overflow,
+// the two constraint rows and enumerated classes are left to the multi-pass kernel through the retry list.
+// Same keys, same comparison, same masks.
+constexpr int kWinBins = 1024;
+constexpr int kFastCand = 1024;
+constexpr int kFastThreads = 512;
+constexpr uint32_t kFastWindow = 4096;   // listed keys at most (32 KB of LDS)
+
+__global__ __launch_bounds__(kFastThreads) void sample_pairs_fast_kernel(SampleArgs a) {
+  __shared__ uint32_t whist[kWinBins];
+  __shared__ unsigned long long cand[kFastCand];
+  __shared__ unsigned long long window[kFastWindow];
+  __shared__ uint32_t cand_count, window_count, below_total, sel[2];
+  __shared__ unsigned long long threshold;
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int64_t n = a.n, W = a.W;
+  const int64_t D = 2 * W;   // 32-bit words of a row
+  uint32_t wcap = a.window_cap < kFastWindow ? a.window_cap : kFastWindow;
+
+  for (int64_t r = a.pair_begin + blockIdx.x; r < a.pair_end; r += gridDim.x) {
+    uint32_t* row_small = (uint32_t*)(a.Z + (2 * (r - a.pair_begin)) * W);
+    uint32_t* row_big = row_small + D;
+    int64_t lo = 1, hi = a.H;
+    while (lo < hi) {
+      int64_t mid = (lo + hi) >> 1;
+      if (a.b[mid] >= r) hi = mid; else lo = mid + 1;
+    }
+    const uint32_t s = (uint32_t)lo;
+    // window [k_lo, k_hi] of key values: expected position of the threshold +- (3 sigma + 8) ranks
+    uint32_t k_lo, k_hi;
+    {
+      const double fs = (double)s, fn = (double)n;
+      const double half = 3.0 * sqrt(fs * (fn - fs) / fn) + 8.0;
+      const double scale = 4294967296.0 / fn;
+      const double x_lo = (fs - half) * scale, x_hi = (fs + half) * scale;
+      k_lo = x_lo <= 0.0 ? 0u : (uint32_t)x_lo;
+      k_hi = x_hi >= 4294967295.0 ? 0xffffffffu : (uint32_t)x_hi;
+    }
+    const uint32_t width = k_hi - k_lo;                          // keys k with k - k_lo <= width are listed
+    const int shift = width >= (uint32_t)kWinBins ? 32 - __builtin_clz(width) - 10 : 0;   // (width >> shift) < kWinBins
+    bool give_up = r == 0 || (int64_t)s <= a.enum_upto;          // uniform over the workgroup
+    if (!give_up) {
+      const uint32_t r_lo = (uint32_t)r, r_hi = (uint32_t)((uint64_t)r >> 32);
+      for (int i = t; i < kWinBins; i += kFastThreads) whist[i] = 0;
+      if (t == 0) {
+        cand_count = 0;
+        window_count = 0;
+        below_total = 0;
+      }
+      __syncthreads();
+      uint32_t below = 0;
+      for (int64_t d = t; d < D; d += kFastThreads) {   // a wave writes 256 contiguous bytes per step
+        const int64_t c0 = d << 5;
+        const uint32_t valid = c0 + 32 <= n ? 0xffffffffu : (c0 < n ? (1u << (uint32_t)(n - c0)) - 1u : 0u);
+        uint32_t word = 0;
+        if (valid) {
+#pragma unroll 2
+          for (int i = 0; i < 8; ++i) {
+            uint32_t key[4];
+            philox4x32_10((uint32_t)(d * 8 + i), r_lo, r_hi, a.tag, a.seed_lo, a.seed_hi, key);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const uint32_t off = key[c] - k_lo;
+              if (key[c] < k_lo) {
+                word |= 1u << (4 * i + c);
+              } else if (off <= width) {
+                const int64_t col = c0 + 4 * i + c;
+                if (col < n) {
+                  atomicAdd(&whist[off >> shift], 1u);
+                  const uint32_t pos = atomicAdd(&window_count, 1u);
+                  if (pos < wcap) window[pos] = ((unsigned long long)key[c] << 32) | (uint32_t)col;
+                }
+              }
+            }
+          }
+          word &= valid;
+          below += __popc(word);
+        }
+        row_small[d] = word;
+        row_big[d] = ~word & valid;
+      }
+      for (int o = 32; o > 0; o >>= 1) below += __shfl_xor(below, o, 64);
+      if (lane == 0) atomicAdd(&below_total, below);
+      __syncthreads();   // (also: the row's words are written before any of them is patched below)
+      const uint32_t wc = window_count;
+      const int64_t want = (int64_t)s - (int64_t)below_total;   // 1-based rank of the threshold among the listed keys
+      give_up = wc > wcap || want < 1 || want > (int64_t)wc;
+      if (!give_up) {
+        if (t < 64) {  // the sub-range that holds rank `want`: wave 0 scans 16 bins per lane, one lane walks its 16
+          constexpr int kPer = kWinBins / 64;
+          uint32_t v = 0;
+#pragma unroll
+          for (int i = 0; i < kPer; ++i) v += whist[t * kPer + i];
+          uint32_t incl = v;
+          for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t up = __shfl_up(incl, o, 64);
+            if (t >= o) incl += up;
+          }
+          const unsigned long long reach = __ballot(incl >= (uint32_t)want);
+          const int owner = reach ? __ffsll((long long)reach) - 1 : 63;   // the total always reaches `want`
+          if (t == owner) {
+            uint32_t cum = incl - v;
+            int bsel = t * kPer;
+            const int bend = bsel + kPer - 1;
+            while (bsel < bend && cum + whist[bsel] < (uint32_t)want) cum += whist[bsel++];
+            sel[0] = (uint32_t)bsel;
+            sel[1] = (uint32_t)want - cum;   // 1-based rank inside that sub-range
+          }
+        }
+        __syncthreads();
+        const uint32_t bin1 = sel[0], want3 = sel[1];
+        for (uint32_t i = t; i < wc; i += kFastThreads) {
+          const unsigned long long c = window[i];
+          if ((((uint32_t)(c >> 32) - k_lo) >> shift) == bin1) {
+            const uint32_t pos = atomicAdd(&cand_count, 1u);
+            if (pos < kFastCand) cand[pos] = c;
+          }
+        }
+        __syncthreads();
+        const uint32_t nc = cand_count;
+        give_up = nc > kFastCand;
+        if (!give_up) {
+          for (uint32_t i = t; i < nc; i += kFastThreads) {
+            const unsigned long long me = cand[i];
+            uint32_t rank = 0;
+            for (uint32_t o = 0; o < nc; ++o) rank += (cand[o] < me) ? 1u : 0u;
+            if (rank == want3 - 1) threshold = me;
+          }
+          __syncthreads();
+          const unsigned long long thr = threshold;
+          for (uint32_t i = t; i < wc; i += kFastThreads) {
+            const unsigned long long c = window[i];
+            if (c <= thr) {
+              const uint32_t col = (uint32_t)c;
+              const uint32_t bit = 1u << (col & 31);
+              atomicOr(&row_small[col >> 5], bit);
+              atomicAnd(&row_big[col >> 5], ~bit);
+            }
+          }
+          if (t == 0) {
+            const float wt = a.wtab[s];
+            const int64_t o = 2 * (r - a.pair_begin);
+            a.w[o] = wt;
+            a.w[o + 1] = wt;
+            a.sz[o] = (int32_t)s;
+            a.sz[o + 1] = (int32_t)(n - s);
+          }
+        }
+      }
+    }
+    if (give_up && t == 0) a.retry[atomicAdd(a.retry_count, 1u)] = (int32_t)(r - a.pair_begin);
+    __syncthreads();
+  }
+}
+
 // Enumeration (n <= 24): pair r = (bit pattern r, its complement).
 __global__ void enumerate_pairs_kernel(SampleArgs a) {
   const int64_t r = a.pair_begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -347,7 +517,7 @@ __global__ void enumerate_pairs_kernel(SampleArgs a) {
 }  // namespace
 
 size_t ds_sample_arena_bytes(const ds_plan& plan) {
-  return ds_align((plan.H + 1) * sizeof(int64_t)) + ds_align((plan.H + 1) * sizeof(float)) + 256;
+  return ds_align((plan.H + 1) * sizeof(int64_t)) + ds_align((plan.H + 1) * sizeof(float)) + ds_align((size_t)(plan.k / 2 + 2) * 4) + 512;
 }
 
 int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t tag, int64_t pair_begin,
@@ -409,7 +579,7 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
     const double bins = 2.0 * (2.0 + ceil(3.0 * sigma * 4096.0 / nn)) + 1.0;
     double cap = bins * nn / 4096.0 * 1.5 + 64.0;
     if (cap < 256.0) cap = 256.0;
-    if (cap > 4096.0) cap = 4096.0;  // the widest classes of huge games overflow it and take the four-pass route
+    if (cap > 4096.0) cap = 4096.0;  // (32 KB of LDS; what overflows it takes more passes)
     a.window_cap = (uint32_t)cap;
     // test hook: a smaller list forces the four-pass route (the result must not change)
     const int32_t tw = ctx->tuning.sampler_window;
@@ -423,7 +593,23 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
     hipLaunchKernelGGL(enumerate_pairs_kernel, dim3((unsigned)blocks), dim3(threads), 0, ctx->stream, a);
   } else {
     const int64_t blocks = pairs < (int64_t)ctx->num_cus * 64 ? pairs : (int64_t)ctx->num_cus * 64;
-    hipLaunchKernelGGL(sample_pairs_kernel, dim3((unsigned)blocks), dim3(kThreads), (size_t)a.window_cap * 8, ctx->stream, a);
+    a.retry = nullptr;
+    a.retry_count = nullptr;
+    if (a.window_cap > 0 && pairs < 0x7fffffffLL) {
+      // one pass for the pairs whose threshold falls where it is expected, the multi-pass kernel for the rest
+      a.retry = (int32_t*)ds_arena_alloc(ctx, (size_t)(pairs + 1) * 4);
+      a.retry_count = (uint32_t*)ds_arena_alloc(ctx, 256);
+      if (!a.retry || !a.retry_count) return ds_fail(ctx, DS_EINTERNAL, "sampler: arena exhausted");
+      DS_HIP(ctx, hipMemsetAsync(a.retry_count, 0, 4, ctx->stream));
+      const int64_t fblocks = pairs < (int64_t)ctx->num_cus * 32 ? pairs : (int64_t)ctx->num_cus * 32;
+      hipLaunchKernelGGL(sample_pairs_fast_kernel, dim3((unsigned)fblocks), dim3(kFastThreads), 0, ctx->stream, a);
+      const int64_t rblocks = blocks < (int64_t)ctx->num_cus * 4 ? blocks : (int64_t)ctx->num_cus * 4;
+      if (a.window_cap > 4096) a.window_cap = 4096;   // (the multi-pass kernel holds more static LDS)
+      hipLaunchKernelGGL(sample_pairs_kernel, dim3((unsigned)rblocks), dim3(kThreads), (size_t)a.window_cap * 8, ctx->stream, a);
+    } else {
+      if (a.window_cap > 4096) a.window_cap = 4096;
+      hipLaunchKernelGGL(sample_pairs_kernel, dim3((unsigned)blocks), dim3(kThreads), (size_t)a.window_cap * 8, ctx->stream, a);
+    }
   }
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;

@@ -243,11 +243,15 @@ int ceil_log2(int64_t v) {
 
 static void tile_shape(const ds_ctx* ctx, int64_t rows, int64_t cols, int64_t nnz, int64_t* budget, int64_t* gbudget,
                        int32_t* max_blocks, int32_t* ncb) {
-  *budget = nnz / 16 > 65536 ? nnz / 16 : 65536;
-  *gbudget = nnz / 6 > 4 * *budget ? nnz / 6 : 4 * *budget;
-  *max_blocks = (int32_t)(rows / kTileSpan + 2 * (nnz / *budget) + 8);
   *ncb = (int32_t)((cols + kTileSpan - 1) / kTileSpan);
-  (void)ctx;
+  // entry-heavy row blocks: 16, or more where the matrix has few column chunks (the adjoint product runs one
+  // workgroup per chunk and group of row blocks, and wants two per compute unit)
+  int64_t parts = (2 * (int64_t)ctx->num_cus + *ncb - 1) / *ncb;
+  if (parts < 16) parts = 16;
+  if (parts > 64) parts = 64;
+  *budget = nnz / parts > 65536 ? nnz / parts : 65536;
+  *gbudget = parts > 16 ? *budget : (nnz / 6 > 4 * *budget ? nnz / 6 : 4 * *budget);
+  *max_blocks = (int32_t)(rows / kTileSpan + 2 * (nnz / *budget) + 8);
 }
 
 size_t ds_tile_ws_bytes(const ds_ctx* ctx, int64_t rows, int64_t cols, int64_t nnz) {
@@ -258,7 +262,7 @@ size_t ds_tile_ws_bytes(const ds_ctx* ctx, int64_t rows, int64_t cols, int64_t n
   // forward partials: at most 32 chunk groups of `rows`; adjoint: at most max_blocks groups, in practice
   // a few more than rows / 32768, of `cols`
   return 2 * ds_align((max_blocks + 2) * 4) + 2 * ds_align(tiles * 4) + ds_align((size_t)(nnz + 1) * 4) +
-         ds_align((size_t)32 * rows * 8) + ds_align((size_t)(2 * (rows / kAdjGroupRows) + 16) * cols * 8) + ds_scan_arena_bytes((int64_t)tiles) +
+         ds_align((size_t)32 * rows * 8) + ds_align((size_t)(2 * (rows / kAdjGroupRows) + 2 * 64 + 24) * cols * 8) + ds_scan_arena_bytes((int64_t)tiles) +
          4096;
 }
 
@@ -293,8 +297,8 @@ int ds_tile_build(ds_ctx* ctx, int64_t rows, int64_t cols, int64_t nnz, int64_t 
   if (ctx->h_mail[4] <= 0) return ds_fail(ctx, DS_EINTERNAL, "index tiles: more row blocks than planned (%d)", max_blocks);
   plan->nrb = (int32_t)ctx->h_mail[4];
   plan->nga = (int32_t)ctx->h_mail[5];
-  if (plan->nga > 2 * (rows / kAdjGroupRows) + 16)
-    return ds_fail(ctx, DS_EINTERNAL, "index tiles: %d adjoint groups, %lld planned", plan->nga, (long long)(2 * (rows / kAdjGroupRows) + 16));
+  if (plan->nga > 2 * (rows / kAdjGroupRows) + 2 * 64 + 24)
+    return ds_fail(ctx, DS_EINTERNAL, "index tiles: %d adjoint groups, %lld planned", plan->nga, (long long)(2 * (rows / kAdjGroupRows) + 152));
   const int64_t tiles = (int64_t)plan->nrb * ncb;
   // forward: (row block, chunk group) workgroups, about three per compute unit
   int32_t gf = (int32_t)((3 * (int64_t)ctx->num_cus + plan->nrb - 1) / plan->nrb);
