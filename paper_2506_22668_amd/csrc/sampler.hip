@@ -595,7 +595,7 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
     const int64_t blocks = pairs < (int64_t)ctx->num_cus * 64 ? pairs : (int64_t)ctx->num_cus * 64;
     a.retry = nullptr;
     a.retry_count = nullptr;
-    if (a.window_cap > 0 && pairs < 0x7fffffffLL) {
+    if (a.window_cap > 0 && pairs < 0x7fffffffLL && plan.n >= 4096) {   // (a lane makes 32 columns: short rows leave the one-pass kernel idle)
       // one pass for the pairs whose threshold falls where it is expected, the multi-pass kernel for the rest
       a.retry = (int32_t*)ds_arena_alloc(ctx, (size_t)(pairs + 1) * 4);
       a.retry_count = (uint32_t*)ds_arena_alloc(ctx, 256);

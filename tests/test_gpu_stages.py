@@ -26,6 +26,7 @@ def ctx_tiny():
     (30, 2000, 5, 3), (64, 1000, 11, 4), (65, 1000, 12, 5), (130, 3001, 2 ** 40 + 17, 2 ** 31 + 5),
     (255, 777, 1, 1), (256, 778, 1, 1), (257, 4, 1, 1),
     (1000, 20000, 22668002, 7965), (5000, 3000, 9, 10), (40000, 600, 13, 77),
+    (4096, 500, 21, 3), (4099, 700, 23, 4), (6241, 9000, 25, 5),   # the one-pass kernel (4,096 players and more)
 ])
 def test_sampler_bit_exact(ctx_tiny, n, ns, seed, tag):
     ctx, _ = ctx_tiny
