@@ -372,7 +372,7 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
       DS_TRY(ds_scan_exclusive_i32(ctx, cnt, csr_off, Rs + 1, ctx->d_mail + 2));
       DS_TRY(ds_mail_fetch(ctx, 4));
       nnz_s = ctx->h_mail[2];
-      if (nnz_s > 0x7fffff00LL) return ds_fail(ctx, DS_EINTERNAL, "cgls: too many set bits in the sparse rows (%lld)", (long long)nnz_s);
+      if (nnz_s > 0x7fff0000LL) return ds_fail(ctx, DS_EINTERNAL, "cgls: too many set bits in the sparse rows (%lld)", (long long)nnz_s);
       Ztd = (uint64_t*)ds_arena_alloc(ctx, (size_t)n * (RdW > 0 ? RdW : 1) * 8);
       void* ws_f = ds_arena_alloc(ctx, ds_bit_spmv_mm_ws_bytes(ctx, Rd, n));
       void* ws_a = ds_arena_alloc(ctx, ds_bit_spmv_mm_ws_bytes(ctx, n, Rd));
