@@ -307,7 +307,10 @@ def test_gram_cholesky_matches_oracle_least_squares(ctx_tiny, n, ns):
 @pytest.mark.parametrize("n,ns,paired", [(12, 4096, 1), (40, 2000, 0), (40, 2000, 1), (333, 6000, 1),
                                          (1000, 20000, 1), (1000, 20000, 0), (3000, 1000, 1), (3000, 1000, 0),
                                          # >= 4096 players and paired: index lists + the matrix-core product of the dense rows
-                                         (4100, 3000, 1), (6000, 14000, 1), (4097, 130, 1), (5000, 2000, 0)])
+                                         (4100, 3000, 1), (6000, 14000, 1), (4097, 130, 1), (5000, 2000, 0),
+                                         # exactly one 8192-column chunk / one column more; more than 8192 sparse
+                                         # rows (several row blocks of tile entries)
+                                         (8192, 3000, 1), (8193, 9000, 1), (5000, 40000, 1)])
 def test_cgls_matches_oracle(ctx_tiny, n, ns, paired):
     from paper_2506_22668_amd import Options, DS_SOLVER_CGLS
     ctx, _ = ctx_tiny
