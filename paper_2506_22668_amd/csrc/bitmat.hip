@@ -30,31 +30,62 @@ __global__ __launch_bounds__(kThreads) void row_prep_kernel(const uint64_t* Z, i
   }
 }
 
-// Transpose a bit matrix: in[rows x Win words] (row stride in_stride words, rows taken
-// as row_first + i*row_step) -> out[cols x Wout words], Wout = ceil(rows/64); bit i of
-// out row j = bit j of in row i. One wave per 64x64 block: lane l loads the word of
-// row l; ballot j collects bit j of all 64 rows, which is the word of column j.
-__global__ __launch_bounds__(kThreads) void bit_transpose_kernel(const uint64_t* in, int64_t rows, int64_t cols,
-                                                                 int64_t in_stride, int64_t row_first, int64_t row_step,
-                                                                 uint64_t* out, int64_t Wout) {
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+// Transpose a bit matrix: in[rows x Win words] (row stride in_stride words, rows taken as row_first + i*row_step)
+// -> out[cols x Wout words], Wout = ceil(rows/64); bit i of out row j = bit j of in row i.
+// A workgroup of 512 threads takes a tile of 512 rows x 512 columns through LDS: every row is read in 64 contiguous
+// bytes and every output row written in 64 contiguous bytes (one wave per 64x64 block with 8-byte accesses, the first
+// version, left most of every cache line unused: 0.3 TB/s). Each wave transposes eight of the tile's 64x64 blocks in
+// registers: lane = row, six rounds of swapping bit blocks with the lane 32, 16, ... 1 away.
+constexpr int kTrThreads = 512;
+constexpr int kTrPitch = 9;  // 64-bit words per LDS row of 8: lanes that read one word column of 64 rows spread over the banks
+
+__device__ __forceinline__ uint64_t transpose64_in_wave(uint64_t x, int lane) {
+  const uint64_t masks[6] = {0x00000000FFFFFFFFull, 0x0000FFFF0000FFFFull, 0x00FF00FF00FF00FFull,
+                             0x0F0F0F0F0F0F0F0Full, 0x3333333333333333ull, 0x5555555555555555ull};
+#pragma unroll
+  for (int s = 0; s < 6; ++s) {
+    const int j = 32 >> s;
+    const uint64_t m = masks[s];
+    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)x, j, 64), hi = (uint32_t)__shfl_xor((int)(uint32_t)(x >> 32), j, 64);
+    const uint64_t t = ((uint64_t)hi << 32) | lo;
+    // rows whose index has bit j clear keep their low bit blocks and take the partner's low blocks as their high
+    // ones; the others keep their high blocks and take the partner's high blocks as their low ones
+    x = (lane & j) ? (((t >> j) & m) | (x & ~m)) : ((x & m) | ((t & m) << j));
+  }
+  return x;
+}
+
+__global__ __launch_bounds__(kTrThreads) void bit_transpose_kernel(const uint64_t* in, int64_t rows, int64_t cols,
+                                                                   int64_t in_stride, int64_t row_first, int64_t row_step,
+                                                                   uint64_t* out, int64_t Wout, int64_t tiles_c) {
+  __shared__ uint64_t tin[512 * kTrPitch];
+  __shared__ uint64_t tout[512 * kTrPitch];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int64_t Win = (cols + 63) / 64;
-  const int64_t blocks = Wout * Win;
-  for (int64_t b = wave; b < blocks; b += nwaves) {
-    const int64_t rb = b / Win, cb = b - rb * Win;  // consecutive waves walk along a row block: coalesced reads
-    const int64_t i = rb * 64 + lane;
-    uint64_t word = 0;
-    if (i < rows) word = in[(row_first + i * row_step) * in_stride + cb];
-    uint64_t mine = 0;
-#pragma unroll 8
-    for (int j = 0; j < 64; ++j) {
-      const uint64_t col = __ballot((word >> j) & 1ull);
-      if (lane == j) mine = col;
-    }
-    const int64_t c = cb * 64 + lane;
-    if (c < cols) out[c * Wout + rb] = mine;
+  const int64_t tr = blockIdx.x / tiles_c, tc = blockIdx.x % tiles_c;   // consecutive workgroups walk along a row block
+  const int64_t r0 = tr * 512, w0 = tc * 8;
+  // load: 8 lanes per row (64 contiguous bytes), 64 rows per step
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int r = k * 64 + (t >> 3), w = t & 7;
+    uint64_t v = 0;
+    if (r0 + r < rows && w0 + w < Win) v = in[(row_first + (r0 + r) * row_step) * in_stride + w0 + w];
+    tin[r * kTrPitch + w] = v;
+  }
+  __syncthreads();
+  // wave `wave` transposes the blocks (row block rbi, word column wave) for the eight row blocks
+#pragma unroll
+  for (int rbi = 0; rbi < 8; ++rbi) {
+    const uint64_t x = transpose64_in_wave(tin[(rbi * 64 + lane) * kTrPitch + wave], lane);
+    tout[(wave * 64 + lane) * kTrPitch + rbi] = x;   // lane = column within the word column, word = row block
+  }
+  __syncthreads();
+  // store: 8 lanes per output row (64 contiguous bytes)
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int c = k * 64 + (t >> 3), w = t & 7;
+    const int64_t col = w0 * 64 + c, ow = tr * 8 + w;
+    if (col < cols && ow < Wout) out[col * Wout + ow] = tout[c * kTrPitch + w];
   }
 }
 // out[i] = sum over the set bits j of row i of x[j] (fp64).
@@ -491,11 +522,11 @@ int ds_row_prep(ds_ctx* ctx, const uint64_t* Z, int64_t k, int64_t n, const floa
 int ds_bit_transpose(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols, int64_t in_stride, int64_t row_first,
                      int64_t row_step, uint64_t* out) {
   const int64_t Wout = (rows + 63) / 64, Win = (cols + 63) / 64;
-  int64_t blocks = (Wout * Win * 64 + kThreads - 1) / kThreads;
-  if (blocks > (int64_t)ctx->num_cus * 16) blocks = (int64_t)ctx->num_cus * 16;
-  if (blocks < 1) return DS_OK;
-  hipLaunchKernelGGL(bit_transpose_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, ctx->stream, in, rows, cols,
-                     in_stride, row_first, row_step, out, Wout);
+  const int64_t tiles_r = (rows + 511) / 512, tiles_c = (Win + 7) / 8;
+  if (tiles_r < 1 || tiles_c < 1) return DS_OK;
+  if (tiles_r * tiles_c > 0x7fffffffLL) return ds_fail(ctx, DS_EINVAL, "bit matrix too large to transpose");
+  hipLaunchKernelGGL(bit_transpose_kernel, dim3((unsigned)(tiles_r * tiles_c)), dim3(kTrThreads), 0, ctx->stream, in, rows, cols,
+                     in_stride, row_first, row_step, out, Wout, tiles_c);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }
