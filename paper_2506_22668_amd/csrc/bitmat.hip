@@ -439,21 +439,7 @@ __global__ __launch_bounds__(256) void mm_reduce_kernel(const int32_t* partial, 
   const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (r == 0 && slot) *slot = 0ull;
   if (r >= rows) return;
-  long long S[kMmPlanes] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int gq = 0; gq < groups; ++gq) {
-    const int4* p = (const int4*)(partial + ((int64_t)gq * rows + r) * kMmPlanes);
-    const int4 u = p[0], w = p[1];
-    S[0] += u.x;
-    S[1] += u.y;
-    S[2] += u.z;
-    S[3] += u.w;
-    S[4] += w.x;
-    S[5] += w.y;
-    S[6] += w.z;
-  }
-  const long long hi = ((S[6] * 256 + S[5]) * 256 + S[4]) * 256 + S[3];
-  const long long lo = (S[2] * 256 + S[1]) * 256 + S[0];
-  const double val = ((double)hi * 16777216.0 + (double)lo) * scal[0];
+  const double val = ds_mm_sum(partial, rows, groups, r) * scal[0];
   out[r] = addend ? addend[r] + val : val;
 }
 
@@ -581,12 +567,12 @@ int ds_bit_spmv_mm_prepare(ds_ctx* ctx, int64_t rows, int64_t cols, void* ws, ds
 }
 
 int ds_vec_quantize(ds_ctx* ctx, const double* x_all, int64_t len_all, const ds_mm_plan* planes, const double* x_planes,
-                    const double* x_q, int64_t qlen, long long* q64, double* scal) {
+                    const double* x_q, int64_t qlen, long long* q64, double* scal, int with_absmax) {
   unsigned long long* slot = (unsigned long long*)(scal + 1);
   int64_t mb = (len_all + 2047) / 2048;
   if (mb > 2 * (int64_t)ctx->num_cus) mb = 2 * (int64_t)ctx->num_cus;
   if (mb < 1) mb = 1;
-  hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)mb), dim3(256), 0, ctx->stream, x_all, len_all, slot);
+  if (with_absmax) hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)mb), dim3(256), 0, ctx->stream, x_all, len_all, slot);
   const bool with_planes = planes && planes->rows > 0;
   const int64_t npad = with_planes ? planes->npad : 0;
   const int64_t span = npad > qlen ? npad : qlen;
@@ -603,8 +589,9 @@ int ds_bit_spmv_mm_product(ds_ctx* ctx, const ds_mm_plan* p, const uint64_t* B, 
     return ds_fail(ctx, DS_EINTERNAL, "matrix-core product: rows of %lld bytes are too far apart", (long long)(row_step * stride * 8));
   hipLaunchKernelGGL(bit_spmv_mm_kernel, dim3((unsigned)p->row_groups, (unsigned)p->groups), dim3(kMmWaves * 64), 0, ctx->stream,
                      B, p->rows, p->cols, stride, row_first, row_step, p->D, p->npad, p->partial, p->cpg, p->n_chunks);
-  hipLaunchKernelGGL(mm_reduce_kernel, dim3((unsigned)((p->rows + 255) / 256)), dim3(256), 0, ctx->stream, p->partial, p->rows,
-                     (int)p->groups, scal, addend, out, clear_slot ? (unsigned long long*)(scal + 1) : (unsigned long long*)nullptr);
+  if (out)
+    hipLaunchKernelGGL(mm_reduce_kernel, dim3((unsigned)((p->rows + 255) / 256)), dim3(256), 0, ctx->stream, p->partial, p->rows,
+                       (int)p->groups, scal, addend, out, clear_slot ? (unsigned long long*)(scal + 1) : (unsigned long long*)nullptr);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }

@@ -28,8 +28,10 @@ struct ds_mm_plan {
 };
 size_t ds_bit_spmv_mm_ws_bytes(const ds_ctx* ctx, int64_t rows, int64_t cols);
 int ds_bit_spmv_mm_prepare(ds_ctx* ctx, int64_t rows, int64_t cols, void* ws, ds_mm_plan* plan);
+// with_absmax == 0: the caller's own kernel has left the maximum in scal[1]
 int ds_vec_quantize(ds_ctx* ctx, const double* x_all, int64_t len_all, const ds_mm_plan* planes, const double* x_planes,
-                    const double* x_q, int64_t qlen, long long* q64, double* scal);
+                    const double* x_q, int64_t qlen, long long* q64, double* scal, int with_absmax = 1);
+// out == nullptr: the per-group digit sums are left for the caller's own kernel to add up (ds_mm_sum below)
 int ds_bit_spmv_mm_product(ds_ctx* ctx, const ds_mm_plan* plan, const uint64_t* B, int64_t stride, int64_t row_first,
                            int64_t row_step, const double* scal, const double* addend, double* out, int clear_slot);
 
@@ -50,8 +52,63 @@ int ds_tile_build(ds_ctx* ctx, int64_t rows, int64_t cols, int64_t nnz, int64_t 
                   int32_t* idx, void* ws, ds_tile_plan* plan);
 // forward: out[r] = sum of x[c] over the entries of row r (q64 = the 64-bit form of x, cols entries);
 // adjoint: out[c] = sum of x[r] over the entries of column c (q64 of rows entries)
+// out == nullptr: the per-group partial vectors are left for the caller's own kernel to add up (ds_tile_sum below)
 int ds_tile_spmv(ds_ctx* ctx, const ds_tile_plan* plan, int adjoint, const long long* q64, const double* scal, double* out,
                  int clear_slot);
+
+// Where the integer results of one product lie before they are added up, for kernels that consume them directly
+// (groups == 0: that part of the matrix is empty).
+struct ds_fixed_view {
+  const long long* tile_partial;  // [tile_groups][tile_len]
+  int64_t tile_len;
+  int tile_groups, tile_sh;
+  const int32_t* mm_partial;      // [mm_groups][mm_rows][8]
+  int64_t mm_rows;
+  int mm_groups;
+};
+static inline ds_fixed_view ds_fixed_view_of(const ds_tile_plan* t, const ds_mm_plan* m, int adjoint) {
+  ds_fixed_view v;
+  const bool has_t = t && t->rows > 0 && t->nnz > 0, has_m = m && m->rows > 0;
+  v.tile_partial = has_t ? t->partial : nullptr;
+  v.tile_len = has_t ? (adjoint ? t->cols : t->rows) : 0;
+  v.tile_groups = has_t ? (adjoint ? t->nga : t->gf) : 0;
+  v.tile_sh = has_t ? (adjoint ? t->sh_a : t->sh_f) : 0;
+  v.mm_partial = has_m ? m->partial : nullptr;
+  v.mm_rows = has_m ? m->rows : 0;
+  v.mm_groups = has_m ? (int)m->groups : 0;
+  return v;
+}
+#ifdef __HIPCC__
+// sum over the groups of entry i of a tile product, times 2^sh (exact up to the final rounding: the groups are added
+// as two 32-bit halves so that the total may exceed 63 bits)
+__device__ __forceinline__ double ds_tile_sum(const long long* partial, int64_t len, int groups, int sh, int64_t i) {
+  long long hi = 0, lo = 0;
+  for (int g = 0; g < groups; ++g) {
+    const long long p = partial[(int64_t)g * len + i];
+    hi += p >> 32;
+    lo += p & 0xffffffffll;
+  }
+  return ((double)hi * 4294967296.0 + (double)lo) * (double)(1ll << sh);
+}
+// sum_d 256^d * (sum over the groups of digit sum d) of row r of a matrix-core product
+__device__ __forceinline__ double ds_mm_sum(const int32_t* partial, int64_t rows, int groups, int64_t r) {
+  long long S0 = 0, S1 = 0, S2 = 0, S3 = 0, S4 = 0, S5 = 0, S6 = 0;
+  for (int g = 0; g < groups; ++g) {
+    const int4* p = (const int4*)(partial + ((int64_t)g * rows + r) * 8);
+    const int4 u = p[0], w = p[1];
+    S0 += u.x;
+    S1 += u.y;
+    S2 += u.z;
+    S3 += u.w;
+    S4 += w.x;
+    S5 += w.y;
+    S6 += w.z;
+  }
+  const long long hi = ((S6 * 256 + S5) * 256 + S4) * 256 + S3;
+  const long long lo = (S2 * 256 + S1) * 256 + S0;
+  return (double)hi * 16777216.0 + (double)lo;
+}
+#endif
 
 // index lists of the set bits of rows (off = exclusive prefix sums of the row sizes)
 int ds_rows_to_csr(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,

@@ -225,13 +225,7 @@ __global__ __launch_bounds__(256) void tile_reduce_kernel(const long long* parti
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0 && slot) *slot = 0ull;
   if (i >= len) return;
-  long long hi = 0, lo = 0;
-  for (int g = 0; g < groups; ++g) {
-    const long long p = partial[(int64_t)g * len + i];
-    hi += p >> 32;
-    lo += p & 0xffffffffll;
-  }
-  out[i] = ((double)hi * 4294967296.0 + (double)lo) * (scal[0] * (double)(1ll << sh));
+  out[i] = ds_tile_sum(partial, len, groups, sh, i) * scal[0];
 }
 
 int ceil_log2(int64_t v) {
@@ -343,7 +337,7 @@ int ds_tile_spmv(ds_ctx* ctx, const ds_tile_plan* p, int adjoint, const long lon
                  int clear_slot) {
   if (p->rows <= 0) return DS_OK;
   if (p->nnz <= 0) {  // rows without a single entry (the empty coalition of pair 0): a zero result
-    DS_HIP(ctx, hipMemsetAsync(out, 0, (size_t)(adjoint ? p->cols : p->rows) * 8, ctx->stream));
+    if (out) DS_HIP(ctx, hipMemsetAsync(out, 0, (size_t)(adjoint ? p->cols : p->rows) * 8, ctx->stream));
     if (clear_slot) DS_HIP(ctx, hipMemsetAsync((void*)(scal + 1), 0, 8, ctx->stream));
     return DS_OK;
   }
@@ -364,13 +358,15 @@ int ds_tile_spmv(ds_ctx* ctx, const ds_tile_plan* p, int adjoint, const long lon
   if (!adjoint) {
     a.sh = p->sh_f;
     hipLaunchKernelGGL(tile_spmv_kernel<false>, dim3((unsigned)p->nrb, (unsigned)p->gf), dim3(kTileThreads), lds, ctx->stream, a);
-    hipLaunchKernelGGL(tile_reduce_kernel, dim3((unsigned)((p->rows + 255) / 256)), dim3(256), 0, ctx->stream, p->partial, p->rows,
-                       (int)p->gf, scal, p->sh_f, out, slot);
+    if (out)
+      hipLaunchKernelGGL(tile_reduce_kernel, dim3((unsigned)((p->rows + 255) / 256)), dim3(256), 0, ctx->stream, p->partial,
+                         p->rows, (int)p->gf, scal, p->sh_f, out, slot);
   } else {
     a.sh = p->sh_a;
     hipLaunchKernelGGL(tile_spmv_kernel<true>, dim3((unsigned)p->ncb, (unsigned)p->nga), dim3(kTileThreads), lds, ctx->stream, a);
-    hipLaunchKernelGGL(tile_reduce_kernel, dim3((unsigned)((p->cols + 255) / 256)), dim3(256), 0, ctx->stream, p->partial, p->cols,
-                       (int)p->nga, scal, p->sh_a, out, slot);
+    if (out)
+      hipLaunchKernelGGL(tile_reduce_kernel, dim3((unsigned)((p->cols + 255) / 256)), dim3(256), 0, ctx->stream, p->partial,
+                         p->cols, (int)p->nga, scal, p->sh_a, out, slot);
   }
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
