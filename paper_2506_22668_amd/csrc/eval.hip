@@ -21,6 +21,7 @@
 // Layer 1 uses the coalition-independent product P = X_c W_1 (computed once per
 // target with MFMA) and aggregates it; layers >= 2 aggregate, then transform.
 #include "internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -53,6 +54,12 @@ __device__ __forceinline__ float bf16_round(float x) {
   uint32_t u = __float_as_uint(x);
   u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even (finite inputs)
   return __uint_as_float(u & 0xFFFF0000u);
+}
+
+__device__ __forceinline__ short bf16_bits(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (short)(u >> 16);
 }
 
 __device__ __forceinline__ int block_sum_int(int v, int* sh) {
@@ -165,20 +172,57 @@ __device__ __forceinline__ void aggregate_rows(const EvalArgs& a, const uint64_t
   }
 }
 
-// dst[t, j] = act( sum_i q[t, i] * W[i, j] + b[j] )
+// dst[t, j] = act( sum_i q[t, i] * W[i, j] + b[j] ), the per-coalition dense transform of a layer ("Distributed Model
+// Prediction": the |V_c| d^2 term), on the matrix cores: a wave takes a 32-row x 32-column tile of the result,
+// v_mfma_f32_32x32x2f32 with lane l supplying q[row l%32][i l/32] and W[i l/32][column l%32]; in the bf16 configuration
+// both operands are rounded to bfloat16 (nearest even) and v_mfma_f32_32x32x8bf16_1k accumulates in fp32.
 __device__ __forceinline__ void transform_rows(const float* q, int rows, int din, int dout, const float* Wm,
                                                const float* bias, bool relu, bool bf16, float* dst) {
-  for (int idx = threadIdx.x; idx < rows * dout; idx += kThreads) {
-    const int t = idx / dout, j = idx - t * dout;
-    const float* qr = q + (size_t)t * din;
-    float acc = 0.f;
-    if (bf16) {
-      for (int i = 0; i < din; ++i) acc += bf16_round(qr[i]) * bf16_round(Wm[(size_t)i * dout + j]);
-    } else {
-      for (int i = 0; i < din; ++i) acc += qr[i] * Wm[(size_t)i * dout + j];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r = lane & 31, half = lane >> 5;
+  const int tn = (dout + 31) / 32, tm = (rows + 31) / 32;
+  for (int tile = wave; tile < tm * tn; tile += kWaves) {
+    const int m0 = (tile / tn) * 32, n0 = (tile - (tile / tn) * tn) * 32;
+    const int am = m0 + r, bn = n0 + r;
+    const bool aok = am < rows, bok = bn < dout;
+    const float* qr = q + (size_t)(aok ? am : 0) * din;
+    const float* wc = Wm + (bok ? bn : 0);
+    float16_t acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int k0 = 0; k0 < din; k0 += 8) {
+      float x[4], w[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int kk = k0 + (bf16 ? 4 * half + u : 2 * u + half);
+        const bool ok = kk < din;
+        x[u] = (ok && aok) ? qr[kk] : 0.f;
+        w[u] = (ok && bok) ? wc[(size_t)kk * dout] : 0.f;
+      }
+      if (bf16) {
+        short4_t av, bv;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          av[u] = bf16_bits(x[u]);
+          bv[u] = bf16_bits(w[u]);
+        }
+        acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(av, bv, acc, 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[u], w[u], acc, 0, 0, 0);
+      }
     }
-    if (bias) acc += bias[j];
-    dst[idx] = relu ? fmaxf(acc, 0.f) : acc;
+    // accumulator register i of lane l is the result's [row 8*(i/4) + 4*(l/32) + i%4][column l%32]
+    if (bok) {
+      const float bj = bias ? bias[bn] : 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int t = m0 + 8 * (i / 4) + 4 * half + (i % 4);
+        if (t < rows) {
+          const float v = acc[i] + bj;
+          dst[(size_t)t * dout + bn] = relu ? fmaxf(v, 0.f) : v;
+        }
+      }
+    }
   }
 }
 
@@ -300,9 +344,10 @@ __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
 //     entries (no atomics), kept as u16 in LDS (or as d^-1/2 in a global scratch for larger graphs);
 //   * layer 1, row t: H1[f][c] = sum_e P[src_e][f] * coef[e][c] with coef = bit ? d_src^-1/2 : 0 is a
 //     (features x entries) . (entries x coalitions) product and runs on the matrix cores;
-//   * later layers work on per-coalition operands laid out [row][feature][lane] in a global scratch;
-//     they are cut into (row, 16-feature) items so that all waves stay busy, the weight matrix is
-//     broadcast from LDS.
+//   * later layers work on per-coalition operands laid out [row][feature][lane] in a global scratch: the
+//     aggregation is cut into (row, 16-feature) items so that all waves stay busy; the dense transform of a
+//     row, (features out x features in) . (features in x 64 coalitions), runs on the matrix cores with the
+//     weight matrix staged in LDS.
 // The sixteen waves of the workgroup split nodes, rows and items among them (same 64 coalitions) and
 // meet at barriers between the stages.
 constexpr int kBW = 32;        // mask words per coalition held in LDS (at least; more for wider masks, see the layout)
@@ -332,6 +377,118 @@ struct BatchedArgs {
   int64_t eb_stride;
   int32_t ext_paired, eb_words;  // ext_deg is [block][node][32 or 64 records]
 };
+
+// One wave's 64 x 64 (feature x coalition) result tile of a first-layer row: accumulator register i of lane l is
+// [feature 8*(i/4) + 4*(l/32) + i%4][coalition l%32]; `out` points at this lane's feature 4*(l/32) and coalition l%32.
+template <bool GENERAL>
+__device__ __forceinline__ void store_layer1_tile(const float16_t (&acc)[2][2], float* out, float sc0, float sc1, bool relu,
+                                                  const float* bias, int fl, int d1) {
+#pragma unroll
+  for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int fo = ft * 32 + 8 * (i / 4) + (i % 4);
+        if (!GENERAL || fl + fo < d1) {
+          float v = (nb ? sc1 : sc0) * acc[ft][nb][i];
+          if (GENERAL && bias) v += bias[fl + fo];
+          out[fo * 64 + nb * 32] = relu ? fmaxf(v, 0.f) : v;
+        }
+      }
+}
+
+// zeros in place of a layer's bias vector when it has none (layer widths are at most 4096)
+__device__ const float zero_bias[4096] = {};
+
+// The per-coalition dense transform of the one-coalition-per-lane kernel ("Distributed Model Prediction", the
+// |V_c| d^2 term): out[t][j][c] = act( sum_f W[f][j] q[t][f][c] + b[j] ) is, for
+// every row t, a (features out x features in) . (features in x coalitions) product and runs on the matrix
+// cores. A wave takes (row, 32 output features, 32 coalitions); with v_mfma_f32_32x32x2f32 lane l supplies
+// W[f + l/32][j0 + l%32] (from the LDS copy of W that the workgroup stages, in row chunks if W is large) and
+// q[t][f + l/32][c0 + l%32], a coalesced load in the [row][feature][coalition] layout. In the bf16
+// configuration both operands are already rounded to bfloat16 (q where the aggregation stored it, W where it is
+// staged) and v_mfma_f32_32x32x8bf16_1k accumulates in fp32.
+__device__ __forceinline__ void transform_coalitions(const float* qall, float* nxt, float* Ws, const float* Wg,
+                                                  const float* bias, int rows, int din, int dout, bool relu, bool isbf) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cap = kBWaves * kStageRows * 64;
+  int FB = cap / dout;
+  if (FB > din) FB = din;
+  if (FB < din && FB > 8) FB &= ~7;  // whole matrix-core steps per chunk
+  const bool single = FB == din;
+  const int jt = (dout + 31) / 32;
+  const int items = rows * jt * 2;
+  const int nit = (items + kBWaves - 1) / kBWaves;
+  const int half = lane >> 5, r = lane & 31;
+  const float* const bl = bias ? bias : zero_bias;
+  for (int it = 0; it < nit; ++it) {
+    const int item = it * kBWaves + wave;
+    const bool live = item < items;
+    const int t = live ? item / (2 * jt) : 0;
+    const int rem = live ? item - t * 2 * jt : 0;
+    const int j0 = (rem >> 1) * 32, c0 = (rem & 1) * 32;
+    const bool jok = j0 + r < dout;
+    float16_t acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    const float* qp = qall + (size_t)t * din * 64 + c0 + r;
+    for (int fb0 = 0; fb0 < din; fb0 += FB) {
+      const int fcnt = din - fb0 < FB ? din - fb0 : FB;
+      if (!(single && it > 0)) {
+        __syncthreads();
+        for (int i = tid; i < fcnt * dout; i += kBThreads) {
+          const float wv = Wg[(size_t)fb0 * dout + i];
+          Ws[i] = isbf ? bf16_round(wv) : wv;
+        }
+        __syncthreads();
+      }
+      if (live) {
+        const float* wp = Ws + (jok ? j0 + r : 0);
+        // 32 input features per step: their sixteen operand loads are in flight together
+        for (int fb = 0; fb < fcnt; fb += 32) {
+          float xa[4][4], xb[4][4];
+#pragma unroll
+          for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int f = fb + 8 * s + (isbf ? 4 * half + u : 2 * u + half);
+              const bool ok = f < fcnt;
+              xa[s][u] = (ok && jok) ? wp[f * dout] : 0.f;
+              xb[s][u] = ok ? qp[(size_t)(fb0 + f) * 64] : 0.f;
+            }
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            if (fb + 8 * s >= fcnt) break;
+            if (isbf) {
+              short4_t av, bv;
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                av[u] = (short)(__float_as_uint(xa[s][u]) >> 16);
+                bv[u] = (short)(__float_as_uint(xb[s][u]) >> 16);
+              }
+              acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(av, bv, acc, 0, 0, 0);
+            } else {
+#pragma unroll
+              for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[s][u], xb[s][u], acc, 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+    if (live) {
+      // accumulator register i of lane l is out[feature j0 + 8*(i/4) + 4*(l/32) + i%4][coalition c0 + l%32]
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int j = j0 + 8 * (i / 4) + 4 * half + (i % 4);
+        if (j < dout) {
+          const float v = acc[i] + bl[j];
+          nxt[((size_t)t * dout + j) * 64 + c0 + r] = relu ? fmaxf(v, 0.f) : v;
+        }
+      }
+    }
+  }
+}
 
 constexpr int kSharedRow = 256;  // a row with more entries than this is shared by all waves of the workgroup
 
@@ -443,6 +600,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
       const int d1 = a.dims[1];
       const bool relu = a.L > 1;
       const int half = lane >> 5, l32 = lane & 31;
+      const float* const bias1 = a.bias[0] ? a.bias[0] : zero_bias;
       const int rows1 = a.rows_out[1];
       // One loop over the rows layer 1 produces. A row of ordinary length belongs to one wave (round-robin). A long
       // row (a hub within L-1 hops of the target) is shared: the waves split its entries, leave their partial
@@ -521,21 +679,14 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
           }
           // accumulator register i of lane l is D[feature 8*(i/4) + 4*(l/32) + i%4][coalition l%32]
           if (!shared) {
-#pragma unroll
-            for (int ft = 0; ft < 2; ++ft)
-#pragma unroll
-              for (int nb = 0; nb < 2; ++nb) {
-                const float scale = (nb == half) ? rst : rst_sw;  // d^-1/2 of row t in coalition nb*32 + l32
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                  const int fr = f0 + ft * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-                  if (fr < d1) {
-                    float v = scale * acc[ft][nb][i];
-                    if (a.bias[0]) v += a.bias[0][fr];
-                    bufA[((size_t)t * d1 + fr) * 64 + nb * 32 + l32] = relu ? fmaxf(v, 0.f) : v;
-                  }
-                }
-              }
+            // a full tile without a bias (the usual case) is stored without a test or a load per element
+            const int fl = f0 + 4 * half;
+            float* out = bufA + ((size_t)t * d1 + fl) * 64 + l32;
+            const float sc0 = half ? rst_sw : rst, sc1 = half ? rst : rst_sw;  // d^-1/2 of row t in coalitions l32, 32 + l32
+            if (a.bias[0] == nullptr && f0 + 64 <= d1)
+              store_layer1_tile<false>(acc, out, sc0, sc1, relu, nullptr, fl, d1);
+            else
+              store_layer1_tile<true>(acc, out, sc0, sc1, relu, a.bias[0], fl, d1);
           } else {
             // the waves add their tiles into one LDS tile, one wave at a time in wave order
             float* tl = stage_all + (4 * half) * 64 + l32;  // the staging area is idle during layer 1
@@ -558,8 +709,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
               const int idx = tid + j * kBThreads;  // feature idx / 64 of the tile, coalition idx % 64 == lane
               const int fr = f0 + (idx >> 6);
               if (fr < d1) {
-                float v = rst * stage_all[idx];
-                if (a.bias[0]) v += a.bias[0][fr];
+                const float v = rst * stage_all[idx] + bias1[fr];
                 bufA[((size_t)t * d1 + fr) * 64 + lane] = relu ? fmaxf(v, 0.f) : v;
               }
             }
@@ -622,76 +772,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
           }
       }
       __syncthreads();
-      // phase B: out[t][j] = act( sum_f q[t][f] W[f][j] + b[j] ). W is the same for every lane:
-      // the workgroup copies it (in row chunks if it is large) into the LDS staging area once and
-      // the waves read it back as broadcasts.
-      {
-        float* Ws = stage_all;  // kBWaves * kStageRows * 64 floats
-        const int cap = kBWaves * kStageRows * 64;
-        int FB = cap / dout;
-        if (FB > din) FB = din;
-        const bool single = FB == din;
-        const int jch = (dout + 15) / 16;
-        const int nit = (rows * jch + kBWaves - 1) / kBWaves;
-        const float* Wg = a.Wl[l - 1];
-        for (int it = 0; it < nit; ++it) {
-          const int item = it * kBWaves + wave;
-          const bool live = item < rows * jch;
-          const int t = live ? item / jch : 0, j0 = live ? (item - t * jch) * 16 : 0;
-          float acc[16];
-#pragma unroll
-          for (int j = 0; j < 16; ++j) acc[j] = 0.f;
-          const float* qp = qall + (size_t)t * din * 64 + lane;
-          for (int fb0 = 0; fb0 < din; fb0 += FB) {
-            const int fcnt = din - fb0 < FB ? din - fb0 : FB;
-            if (!(single && it > 0)) {
-              __syncthreads();
-              for (int i = tid; i < fcnt * dout; i += kBThreads) {
-                const float wv = Wg[(size_t)fb0 * dout + i];
-                Ws[i] = a.bf16 ? bf16_round(wv) : wv;
-              }
-              __syncthreads();
-            }
-            if (live) {
-              for (int fb = 0; fb < fcnt; fb += 16) {
-                float q[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) q[u] = (fb + u < fcnt) ? qp[(size_t)(fb0 + fb + u) * 64] : 0.f;
-#pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                  if (fb + u < fcnt) {
-                    const float* wr = Ws + (fb + u) * dout + j0;
-                    if ((dout & 3) == 0 && j0 + 16 <= dout) {
-                      const float4* w4 = (const float4*)wr;
-#pragma unroll
-                      for (int j = 0; j < 4; ++j) {
-                        const float4 v = w4[j];
-                        acc[4 * j + 0] += q[u] * v.x;
-                        acc[4 * j + 1] += q[u] * v.y;
-                        acc[4 * j + 2] += q[u] * v.z;
-                        acc[4 * j + 3] += q[u] * v.w;
-                      }
-                    } else {
-#pragma unroll
-                      for (int j = 0; j < 16; ++j)
-                        if (j0 + j < dout) acc[j] += q[u] * wr[j];
-                    }
-                  }
-                }
-              }
-            }
-          }
-          if (live) {
-#pragma unroll
-            for (int j = 0; j < 16; ++j)
-              if (j0 + j < dout) {
-                float v = acc[j];
-                if (a.bias[l - 1]) v += a.bias[l - 1][j0 + j];
-                nxt[((size_t)t * dout + j0 + j) * 64 + lane] = relu ? fmaxf(v, 0.f) : v;
-              }
-          }
-        }
-      }
+      transform_coalitions(qall, nxt, stage_all, a.Wl[l - 1], a.bias[l - 1], rows, din, dout, relu, a.bf16 != 0);
       __syncthreads();
       float* tmp = cur; cur = nxt; nxt = tmp;
     }
@@ -1117,12 +1198,6 @@ __global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a)
 }
 
 // ---------------- shared first transform P = X_c W_1 on the matrix cores ----------------
-
-__device__ __forceinline__ short bf16_bits(float x) {
-  uint32_t u = __float_as_uint(x);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (short)(u >> 16);
-}
 
 // One wave per 32x32 tile of C = A[M x K] * B[K x Nn] (row-major, fp32 in memory).
 // MFMA 32x32x2 f32: lane l supplies A[row l%32][k l/32] and B[k l/32][col l%32]; the
