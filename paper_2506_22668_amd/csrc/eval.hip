@@ -375,7 +375,8 @@ struct BatchedArgs {
   const uint16_t* fdeg2;      // [V]: deg_full(v) + 2
   const int32_t* erank;       // [E_need]: rank of the player of CSR entry e among the needed players
   int64_t eb_stride;
-  int32_t ext_paired, eb_words;  // ext_deg is [block][node][32 or 64 records]
+  int32_t ext_paired, eb_words;
+  int32_t ext_lr;  // ext_deg is [group of 2^ext_lr records][node][record of the group]
 };
 
 // One wave's 64 x 64 (feature x coalition) result tile of a first-layer row: accumulator register i of lane l is
@@ -529,11 +530,11 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
   const uint64_t tail_mask = (a.n & 63) ? ((1ull << (a.n & 63)) - 1ull) : ~0ull;
   const int64_t blocks = (a.k + 63) / 64;
 
-  const uint16_t* ext_deg_lane = nullptr;  // EXT: this lane's record in the current block of the transposed degrees
-  int ext_member = 0, ext_slots = 64;
+  const uint16_t* ext_deg_lane = nullptr;  // EXT: this lane's record in its group's block of the degrees
+  int ext_member = 0;
   auto rs_of = [&](int v) -> float {
     if (EXT) {
-      int d = ext_deg_lane[(size_t)v * ext_slots];
+      int d = ext_deg_lane[(size_t)v << b.ext_lr];
       if (ext_member) d = b.fdeg2[v] - d;  // the complement: d'(v) = deg_full(v) + 2 - d(v)
       return __frsqrt_rn((float)d);
     }
@@ -584,8 +585,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
         ebw[j * 64 + lane] = member ? ~wd : wd;
       }
       ext_member = member;
-      ext_slots = b.ext_paired ? 32 : 64;
-      ext_deg_lane = b.ext_deg + (size_t)blk * a.V * ext_slots + (b.ext_paired ? (lane & 31) : lane);
+      ext_deg_lane = b.ext_deg + (((size_t)(rec >> b.ext_lr) * a.V) << b.ext_lr) + (rec & ((1 << b.ext_lr) - 1));
     }
     __syncthreads();
 
@@ -814,22 +814,30 @@ struct StreamArgs {
   const uint64_t* Z;
   const int32_t* sizes;
   const uint32_t* pab;          // [n] end points of player p as local ids: a in the low, b in the high 16 bits
-  const int32_t* a_end;         // [V] one past the last player whose first end point is node v (players with equal a are consecutive)
+  const uint64_t* wsplit;       // [W] bit j: player 64w + j (j > 0) has another first end point than the player before it
+  const int32_t* wfirst;        // [W] first end point of player 64w
   const int32_t* row_ptr;
   const uint64_t* nmask;        // [W] bits of the players whose CSR entries layer 1 reads ("needed" players)
   const int32_t* nbase;         // [W] number of needed players before word w: a needed player's rank = nbase + rank in word
+  const int32_t* need_range;    // [2]: the words that hold needed players lie in [need_range[0], need_range[1])
   int32_t eb_words;             // u32 words of a row's needed bits (rank order)
-  uint16_t* deg_out;            // [block][V][slots]: d(v) = 1 + active entries of row v, record = block*slots + slot
+  uint16_t* deg_out;            // [group][V][R]: d(v) = 1 + active entries of row v, record = group * R + row of the group
   uint32_t* ebits_out;          // [rows][eb_stride] bit r = mask bit of the needed player of rank r
   int64_t eb_stride;
 };
 
-__global__ void pack_endpoints_kernel(const int2* pl, int64_t n, uint32_t* pab, int32_t* a_end) {
+// (256 threads per workgroup: a wave is the 64 players of one mask word)
+__global__ void pack_endpoints_kernel(const int2* pl, int64_t n, uint32_t* pab, unsigned long long* wsplit, int32_t* wfirst) {
   const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (p >= n) return;
-  const int2 e = pl[p];
-  pab[p] = (uint32_t)e.x | ((uint32_t)e.y << 16);
-  if (p == n - 1 || pl[p + 1].x != e.x) a_end[e.x] = (int32_t)(p + 1);
+  bool starts = false;
+  if (p < n) {
+    const int2 e = pl[p];
+    pab[p] = (uint32_t)e.x | ((uint32_t)e.y << 16);
+    if ((p & 63) == 0) wfirst[p >> 6] = e.x;
+    else starts = pl[p - 1].x != e.x;
+  }
+  const unsigned long long m = __ballot(starts);
+  if ((threadIdx.x & 63) == 0 && p < n) wsplit[p >> 6] = m;
 }
 
 // coalition size of every handled row, one wave per row (only when the caller has no sizes at hand)
@@ -865,6 +873,13 @@ __global__ void need_count_kernel(const uint64_t* nmask, int64_t W, int32_t* cnt
   const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (w < W) cnt[w] = __popcll(nmask[w]);
 }
+__global__ void need_range_kernel(const uint64_t* nmask, int64_t W, int32_t* range) {
+  const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w < W && nmask[w] != 0ull) {
+    atomicMin(&range[0], (int32_t)w);
+    atomicMax(&range[1], (int32_t)w + 1);
+  }
+}
 __global__ void need_rank_kernel(const int32_t* eid, int E_need, const uint64_t* nmask, const int32_t* nbase, int32_t* erank) {
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= E_need) return;
@@ -872,40 +887,52 @@ __global__ void need_rank_kernel(const int32_t* eid, int E_need, const uint64_t*
   erank[e] = nbase[p >> 6] + __popcll(nmask[p >> 6] & ((1ull << (p & 63)) - 1ull));
 }
 
-constexpr int kSThreads = 512;
+constexpr int kSThreads = 1024;
 constexpr int kSWaves = kSThreads / 64;
-constexpr int kQueueCap = 768;  // players a wave lists before it looks their end points up
+constexpr int kQueueCap = 512;  // players a wave lists before it looks their end points up
 constexpr int kDenseShift = 4;    // a row walks player by player (not bit by bit) from n / 16 bits to count ...
 constexpr int kDenseMinBits = 64;  // ... and this many
 
-// A workgroup takes R = 2^lr consecutive rows together and counts, for every row, the set bits (or, when more than
-// half are set, the cleared ones) incident to every node, with LDS atomics on 16-bit counters packed in pairs, one
-// array per row. Rows with few bits to count are walked bit by bit: a wave's 64 lanes are R rows x 64/R consecutive
-// words, so the lanes of one word column look up the end points of the same 64 players. Rows with many bits are
-// walked player by player instead: a lane holds the end points of one player of the word (one coalesced load
-// for all dense rows of the group), the row's mask word becomes the execution mask of one atomic add for the
-// second end points; the first end points of consecutive players are equal, so they are counted by the
-// popcount of each run in a separate sweep over the row's words. Degrees go out transposed ([node][record]) so
-// that the layers kernel reads one node's degrees of all its coalitions with one coalesced load.
-// `val` in the lanes whose bit is set in the (wave-uniform) 64-bit mask, 0 in the others: one select on the mask
-__device__ __forceinline__ uint32_t lanes_of_mask(unsigned long long mask, uint32_t val) {
-  uint32_t r;
-  asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(r) : "v"(val), "s"(mask));
-  return r;
+// A workgroup of sixteen waves takes R = 2^lr consecutive rows together and counts, for every row, the set bits (or,
+// when more than half are set, the cleared ones) incident to every node, with LDS atomics on 16-bit counters packed in
+// pairs. The counters of eight rows of a 7,500-node computation graph fill most of a compute unit's LDS, so one
+// workgroup runs per unit: sixteen waves (not eight) are what keeps enough loads in flight.
+// Rows with few bits to count are walked bit by bit, a wave streaming one row 1 KB at a time; set bits are listed
+// in the wave's LDS queue and their end points looked up in batches. Rows with many bits are walked player by player:
+// the 64 words of a block are cut into 16-bit pieces in LDS so that a lane, holding the end points of one player of the
+// word (one coalesced load for all rows of the group), gets the increments of two rows with one shift and one AND
+// and adds four rows to the player's second end point with one 64-bit atomic; the first end points of consecutive
+// players are equal, so they are counted by one popcount per run while a lane still holds the whole word. The
+// needed players' bits are taken from the words as they pass, only in the stretch of the row that holds any.
+// Degrees go out as one contiguous block per workgroup ([group][node][row]).
+// inclusive prefix sum over the 64 lanes of a wave, by data-parallel-primitive moves inside the rows of 16 lanes and two
+// broadcasts across them (no LDS traffic)
+__device__ __forceinline__ int wave_inclusive_sum(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);  // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false); // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false); // row_bcast:31 into rows 2 and 3
+  return v;
 }
 
 template <bool PAIRED, int LR>
 __global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a) {
   extern __shared__ uint32_t ssm[];  // V x R packed 16-bit counters, 8 mode words, the waves' player queues
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  constexpr int R = 1 << LR, wpw = 64 >> LR;  // rows per workgroup, words per wave and row
-  const int q = lane >> (6 - LR), wl = lane & (wpw - 1);
+  constexpr int R = 1 << LR;  // rows per workgroup
   uint32_t* cnt_all = ssm;
   int* modes = (int*)(ssm + a.cnt_words);  // bit 0: the cleared bits are walked, bit 1: player by player
   uint32_t* queue = ssm + a.cnt_words + 8;  // kSWaves queues of kQueueCap players
   uint32_t* nb_all = queue + kSWaves * kQueueCap;       // R x eb_words needed bits
-  constexpr int lrh = LR - 1;  // a node's counters are 2^lrh u32 words; row r sits in word r >> 1, half r & 1
-  auto count_one = [&](uint32_t node, int row) { atomicAdd(&cnt_all[(node << lrh) + (row >> 1)], 1u << ((row & 1) << 4)); };
+  // 16-bit counters, two rows to a u32 (row r: half r & 1 of pair r >> 1). Up to four rows (two pairs) of a node are
+  // consecutive; with eight rows, rows 4..7 form a second array behind the first, so that a 64-bit atomic on the rows
+  // 0..3 (or 4..7) of the nodes spreads over sixteen pairs of LDS banks instead of eight
+  constexpr int lrh = LR == 3 ? 1 : LR - 1;
+  const int cnt_half = LR == 3 ? a.cnt_words / 2 : 0;
+  auto cnt_word = [&](uint32_t node, int pair) -> uint32_t* { return cnt_all + (pair >> 1) * cnt_half + (node << lrh) + (pair & 1); };
+  auto count_one = [&](uint32_t node, int row) { atomicAdd(cnt_word(node, row >> 1), 1u << ((row & 1) << 4)); };
   const int64_t W = a.W;
   const uint64_t tail_mask = (a.n & 63) ? ((1ull << (a.n & 63)) - 1ull) : ~0ull;
   const int64_t groups = (a.rows + R - 1) / R;
@@ -926,6 +953,7 @@ __global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a)
     __syncthreads();
     int any_dense = 0;
     for (int i = 0; i < R; ++i) any_dense |= modes[i] & 2;
+    const int64_t need_lo = a.need_range[0], need_hi = a.need_range[1];
     // the needed players' bits of mask word `word` (true bits, word index w) of group row `row`, in rank order
     auto take_needed = [&](uint64_t word, uint64_t nm, int r0, int row) {  // r0: needed players before this word
       uint64_t x = word & nm;
@@ -947,123 +975,155 @@ __global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a)
     };
     // ---- rows walked bit by bit. Looking up a player's end points right where its bit is found makes every step
     // wait for a memory round trip that serves a few bits; instead the wave first only lists the players (the bit
-    // positions, with the row in the top three bits) in a queue of its own in LDS, and empties the queue when it
-    // is nearly full: then every lane has four independent look-ups in flight, whatever word they came from.
+    // positions) in a queue of its own in LDS, and empties the queue when it is nearly full: then every lane has
+    // eight independent look-ups in flight, whatever word they came from.
+    // A wave streams ONE row (with fewer than eight rows to a group, a part of one): a load is 1 KB of consecutive
+    // mask words, 16 bytes a lane, four loads make a step, and the next step's loads are issued before the current
+    // step's words are looked at.
     {
-      const int64_t r = g * R + q;
-      const int mode = modes[q];
-      const bool active = r < a.rows && !(mode & 2);
+      constexpr int wpr = kSWaves / R;   // waves that share a row
+      const int qrow = __builtin_amdgcn_readfirstlane(wave / wpr), part = __builtin_amdgcn_readfirstlane(wave % wpr);
+      const int64_t r = g * R + qrow;
+      const int mode = modes[qrow];
+      const bool active = r < a.rows && !(mode & 2);   // the same for the whole wave
       const bool flip = mode & 1;
       const uint64_t* z = a.Z + (r < a.rows ? r : 0) * a.row_stride;
       uint32_t* myq = queue + wave * kQueueCap;
       int qfill = 0;  // the same in every lane
       auto drain = [&]() {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        for (int i0 = 0; i0 < qfill; i0 += 256) {
-          uint32_t ent[4], e[4];
+        for (int i0 = 0; i0 < qfill; i0 += 512) {
+          uint32_t ent[8], e[8];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
+          for (int u = 0; u < 8; ++u) {
             const int idx = i0 + u * 64 + lane;
             ent[u] = idx < qfill ? myq[idx] : 0xFFFFFFFFu;
-            e[u] = ent[u] != 0xFFFFFFFFu ? a.pab[ent[u] & 0x0FFFFFFFu] : 0u;
+            e[u] = ent[u] != 0xFFFFFFFFu ? a.pab[ent[u]] : 0u;
           }
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
+          for (int u = 0; u < 8; ++u) {
             if (ent[u] != 0xFFFFFFFFu) {
-              const int row = (int)(ent[u] >> 28);
-              count_one(e[u] >> 16, row);
-              if (!a.directed) count_one(e[u] & 0xFFFFu, row);
+              count_one(e[u] >> 16, qrow);
+              if (!a.directed) count_one(e[u] & 0xFFFFu, qrow);
             }
           }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         qfill = 0;
       };
-      // eight word columns per lane are fetched together (the row's words and the needed-player masks: sixteen
-      // independent loads), then handled two at a time
-      for (int64_t wc0 = (int64_t)wave * wpw; wc0 < W; wc0 += 8 * kSWaves * wpw) {
-        uint64_t tw[8], nm[8];
-        int nr[8];
+      typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+      const bool wide_ok = ((a.row_stride & 1) == 0) && (((uintptr_t)a.Z & 15) == 0);  // rows start on 16 bytes
+      constexpr int kLd = 4;  // loads per step
+      constexpr int wstep = kLd * wpr * 128;  // words of a row one step of its waves covers
+      // first word of this lane's u-th load of the step at wc0
+      auto word_of = [&](int64_t wc0, int u) -> int64_t { return wc0 + (int64_t)(u * wpr + part) * 128 + 2 * lane; };
+      auto fetch = [&](int64_t wc0, u64x2 (&dst)[kLd]) {  // a step that lies wholly inside the row
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int64_t w = wc0 + (int64_t)u * kSWaves * wpw + wl;
-          const bool in = active && w < W;
-          tw[u] = in ? z[w] : 0ull;
-          nm[u] = in ? a.nmask[w] : 0ull;
-          nr[u] = in ? a.nbase[w] : 0;
+        for (int u = 0; u < kLd; ++u) dst[u] = __builtin_nontemporal_load((const u64x2*)(z + word_of(wc0, u)));  // streamed once
+      };
+      auto fetch_checked = [&](int64_t wc0, u64x2 (&dst)[kLd]) {  // the last step, or rows that are not 16-byte aligned
+#pragma unroll
+        for (int u = 0; u < kLd; ++u) {
+          const int64_t w = word_of(wc0, u);
+          dst[u][0] = w < W ? z[w] : (flip ? ~0ull : 0ull);
+          dst[u][1] = w + 1 < W ? z[w + 1] : (flip ? ~0ull : 0ull);
+          if (w == W - 1) dst[u][0] = flip ? dst[u][0] | ~tail_mask : dst[u][0] & tail_mask;  // padding bits name no player
+          if (w + 1 == W - 1) dst[u][1] = flip ? dst[u][1] | ~tail_mask : dst[u][1] & tail_mask;
         }
+      };
+      auto step = [&](int64_t wc0, const u64x2 (&v)[kLd]) {
+        const bool need_here = wc0 < need_hi && wc0 + wstep > need_lo;
 #pragma unroll
-        for (int uu = 0; uu < 4; ++uu) {
-        const int64_t wc = wc0 + (int64_t)(2 * uu) * kSWaves * wpw;
-        if (wc >= W) break;
-        uint64_t bits[2];
-        int64_t base[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int64_t w = wc + (int64_t)u * kSWaves * wpw + wl;
-          uint64_t bw = 0ull;
-          if (active && w < W) {
-            take_needed(tw[2 * uu + u], nm[2 * uu + u], nr[2 * uu + u], q);
-            bw = flip ? ~tw[2 * uu + u] : tw[2 * uu + u];
-            if (w == W - 1) bw &= tail_mask;  // padding bits never name a player
+        for (int u = 0; u < kLd; ++u) {  // one load's 128 words at a time: at most a few hundred bits
+          uint64_t t0 = v[u][0], t1 = v[u][1];
+          const int64_t w = word_of(wc0, u);
+          if (need_here) {  // (true bits: before the flip)
+            if (w < W) take_needed(t0, a.nmask[w], a.nbase[w], qrow);
+            if (w + 1 < W) take_needed(t1, a.nmask[w + 1], a.nbase[w + 1], qrow);
           }
-          bits[u] = bw;
-          base[u] = w * 64;
-        }
-        const int c = __popcll(bits[0]) + __popcll(bits[1]);
-        if (__ballot(c != 0) == 0ull) continue;
-        int incl = c;  // inclusive prefix sum over the lanes
+          if (flip) {
+            t0 = ~t0;
+            t1 = ~t1;
+          }
+          uint32_t x[4] = {(uint32_t)t0, (uint32_t)(t0 >> 32), (uint32_t)t1, (uint32_t)(t1 >> 32)};
+          const int c = __popc(x[0]) + __popc(x[1]) + __popc(x[2]) + __popc(x[3]);
+          if (__ballot(c != 0) == 0ull) continue;
+          const int incl = wave_inclusive_sum(c);
+          const int total = __builtin_amdgcn_readlane(incl, 63);
+          const uint32_t pb = (uint32_t)(w * 64);
+          if (total > kQueueCap) {  // more bits than the queue holds at once: counted directly
+            if (qfill) drain();
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const int t = __shfl_up(incl, o, 64);
-          if (lane >= o) incl += t;
-        }
-        const int total = __shfl(incl, 63, 64);
-        if (total > kQueueCap) {  // does not happen for rows below the dense threshold; counted directly
-          if (qfill) drain();
-#pragma unroll
-          for (int u = 0; u < 2; ++u)
-            while (bits[u]) {
-              const uint32_t e = a.pab[base[u] + (__ffsll((long long)bits[u]) - 1)];
-              bits[u] &= bits[u] - 1;
-              count_one(e >> 16, q);
-              if (!a.directed) count_one(e & 0xFFFFu, q);
+            for (int j = 0; j < 4; ++j) {
+              uint32_t bits = x[j];
+              while (bits) {
+                const uint32_t e = a.pab[pb + 32 * j + (__ffs((int)bits) - 1)];
+                bits &= bits - 1;
+                count_one(e >> 16, qrow);
+                if (!a.directed) count_one(e & 0xFFFFu, qrow);
+              }
             }
-          continue;
-        }
-        if (qfill + total > kQueueCap) drain();
-        int pos = qfill + incl - c;
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-          while (bits[u]) {
-            myq[pos++] = (uint32_t)(base[u] + (__ffsll((long long)bits[u]) - 1)) | ((uint32_t)q << 28);
-            bits[u] &= bits[u] - 1;
+            continue;
           }
-        qfill += total;
+          if (qfill + total > kQueueCap) drain();
+          int pos = qfill + incl - c;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            uint32_t bits = x[j];
+            while (bits) {
+              myq[pos++] = (pb + 32 * j) + (uint32_t)(__ffs((int)bits) - 1);
+              bits &= bits - 1;
+            }
+          }
+          qfill += total;
         }
+      };
+      if (active) {
+        int64_t wc0 = 0;
+        u64x2 cur[kLd], nxt[kLd];
+        if (wide_ok && wstep < W) {
+          fetch(0, cur);
+          for (; wc0 + 2 * wstep < W; wc0 += wstep) {  // the step after this one lies inside the row as well
+            fetch(wc0 + wstep, nxt);
+            step(wc0, cur);
+#pragma unroll
+            for (int u = 0; u < kLd; ++u) cur[u] = nxt[u];
+          }
+          step(wc0, cur);
+          wc0 += wstep;
+        }
+        for (; wc0 < W; wc0 += wstep) {
+          fetch_checked(wc0, cur);
+          step(wc0, cur);
+        }
+        if (qfill) drain();
       }
-      if (qfill) drain();
     }
-    // ---- rows walked player by player (uniform control flow from here to the barrier: every lane of every wave
-    // is active, which the execution-mask atomics below rely on)
+    // ---- rows walked player by player. A wave takes a contiguous range of word columns, 64 words at a time with
+    // lane = word (coalesced loads of every dense row of the group). While a lane holds its word of the R rows it
+    // (a) takes the needed players' bits, (b) counts the FIRST end points: players with the same first end point
+    // are consecutive, so a word is a few runs (wsplit marks where a new one starts, wfirst names the first) and a
+    // run's count in a row is one popcount, (c) leaves the words in the wave's LDS area cut into 16-bit pieces, two
+    // rows to a u32: [word][piece][row pair]. Then the words are walked with lane = player: a lane reads the 16 bytes
+    // that hold its piece of all eight rows, and (x >> (lane & 15)) & 0x00010001 is at once the pair of 16-bit
+    // increments of two rows, so one 64-bit LDS atomic adds four rows' bits to the player's SECOND end point.
     if (any_dense) {
       int dmode[8];  // per row of the group: -1 = not walked this way, else bit 0 of its mode (wave-uniform values)
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int m = i < R ? __builtin_amdgcn_readfirstlane(modes[i < R ? i : 0]) : 0;
-        dmode[i] = (m & 2) ? (m & 1) : -1;
+        dmode[i] = (i < R && (m & 2)) ? (m & 1) : -1;
       }
+      uint32_t* stage = queue + wave * kQueueCap;  // the wave's queue is empty by now: 32 words x 4 pieces x 4 u32
       const int64_t per = ((W + kSWaves - 1) / kSWaves + 63) & ~(int64_t)63;
       const int64_t w_begin = (int64_t)__builtin_amdgcn_readfirstlane(wave) * per;
       const int64_t w_end = w_begin + per < W ? w_begin + per : W;
-      // lane l holds word wb + l of every dense row of the current block of 64 words (and, one block ahead, of the
-      // next); the words are handed to all lanes one at a time below
-      uint64_t mw[8], mw_next[8];
+      uint64_t mw_next[8];
       auto load_words = [&](int64_t wb, uint64_t (&dst)[8]) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           uint64_t m = 0ull;
-          if (dmode[i] >= 0 && wb + lane < w_end) m = a.Z[(g * R + i) * a.row_stride + wb + lane];
+          if (dmode[i] >= 0 && wb + lane < w_end) m = __builtin_nontemporal_load(&a.Z[(g * R + i) * a.row_stride + wb + lane]);
           dst[i] = m;
         }
       };
@@ -1074,118 +1134,141 @@ __global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a)
           dst[u] = p < a.n ? a.pab[p] : 0u;
         }
       };
+      // adds the packed increments inc[h] = (row 2h) | (row 2h+1) << 16 to the counters of `node`
+      auto add_packed = [&](uint32_t node, const uint32_t (&inc)[4]) {
+        if (R == 2) {
+          if (inc[0]) atomicAdd(cnt_word(node, 0), inc[0]);
+        } else {
+          if (inc[0] | inc[1])
+            atomicAdd((unsigned long long*)cnt_word(node, 0), (unsigned long long)inc[0] | ((unsigned long long)inc[1] << 32));
+          if (R == 8 && (inc[2] | inc[3]))
+            atomicAdd((unsigned long long*)cnt_word(node, 2), (unsigned long long)inc[2] | ((unsigned long long)inc[3] << 32));
+        }
+      };
       if (w_begin < w_end) load_words(w_begin, mw_next);
       for (int64_t wb = w_begin; wb < w_end; wb += 64) {
-        const uint64_t nmw = wb + lane < w_end ? a.nmask[wb + lane] : 0ull;
-        const int nrw = wb + lane < w_end ? a.nbase[wb + lane] : 0;
+        const bool in = wb + lane < w_end;
+        const bool need_blk = wb < need_hi && wb + 64 > need_lo;
+        const uint64_t nmw = (in && need_blk) ? a.nmask[wb + lane] : 0ull;
+        const int nrw = (in && need_blk) ? a.nbase[wb + lane] : 0;
+        uint64_t split = (in && !a.directed) ? a.wsplit[wb + lane] : 0ull;
+        uint32_t node = (in && !a.directed) ? (uint32_t)a.wfirst[wb + lane] : 0u;
+        uint64_t mw[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           uint64_t m = mw_next[i];
-          if (dmode[i] >= 0 && wb + lane < w_end) {
-            take_needed(m, nmw, nrw, i);
+          if (dmode[i] >= 0 && in) {
+            if (need_blk) take_needed(m, nmw, nrw, i);
             if (dmode[i]) m = ~m;
             if (wb + lane == W - 1) m &= tail_mask;
           }
           mw[i] = m;
         }
         if (wb + 64 < w_end) load_words(wb + 64, mw_next);
-        uint32_t e[8], e_next[8];
+        uint32_t e_next[8];
         load_players(wb, e_next);
-        for (int j0 = 0; j0 < 64 && wb + j0 < w_end; j0 += 8) {
+        // (b) first end points
+        if (!a.directed) {
+          auto run_counts = [&](uint64_t seg, uint32_t (&inc)[4]) {
 #pragma unroll
-          for (int u = 0; u < 8; ++u) e[u] = e_next[u];
-          if (j0 + 8 < 64 && wb + j0 + 8 < w_end) load_players(wb + j0 + 8, e_next);
+            for (int h = 0; h < 4; ++h) {
+              inc[h] = 0u;
+              if (2 * h < R) inc[h] = (uint32_t)__popcll(mw[2 * h] & seg) | ((uint32_t)__popcll(mw[2 * h + 1] & seg) << 16);
+            }
+          };
+          const uint32_t node0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)node);
+          if (__ballot(split != 0ull || node != node0 || !in) == 0ull) {
+            // one run covers all 64 words (inside a hub's players): add the lanes' counts up first (at most 64 x 64 per
+            // 16-bit field), one lane adds them to the counters
+            uint32_t inc[4];
+            run_counts(~0ull, inc);
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            // this lane's player of word wb + j0 + u: one increment word per four rows (a 16-bit field per row:
-            // the row's bit of this player), added to the player's second end point with one 64-bit atomic.
-            // Rows that are not walked this way hold zero words here.
-            uint32_t* cb = cnt_all + ((e[u] >> 16) << lrh);
-#pragma unroll
-            for (int h = 0; h < (R + 3) / 4; ++h) {
-              uint32_t inc[2] = {0u, 0u};
-#pragma unroll
-              for (int i2 = 0; i2 < 4; ++i2) {
-                const int i = 4 * h + i2;
-                if (i >= R) break;
-                const unsigned long long ms =
-                    ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(mw[i] >> 32), j0 + u) << 32) |
-                    (uint32_t)__builtin_amdgcn_readlane((int)mw[i], j0 + u);
-                inc[i2 >> 1] |= lanes_of_mask(ms, (i2 & 1) ? 0x10000u : 1u);
-              }
-              if (R == 2) {
-                if (inc[0]) atomicAdd(cb, inc[0]);
-              } else if (inc[0] | inc[1]) {
-                atomicAdd((unsigned long long*)cb + h, (unsigned long long)inc[0] | ((unsigned long long)inc[1] << 32));
-              }
+            for (int h = 0; h < 4; ++h)
+              if (2 * h < R)
+                for (int o = 32; o > 0; o >>= 1) inc[h] += __shfl_xor(inc[h], o, 64);
+            if (lane == 0) add_packed(node0, inc);
+          } else if (in) {
+            int lo = 0;
+            for (;;) {
+              const int hi = split ? __ffsll((long long)split) - 1 : 64;  // the run covers bits lo .. hi-1
+              const uint64_t seg = (hi >= 64 ? ~0ull : ((1ull << hi) - 1ull)) & ~((1ull << lo) - 1ull);
+              uint32_t inc[4];
+              run_counts(seg, inc);
+              add_packed(node, inc);
+              if (!split) break;
+              split &= split - 1;
+              lo = hi;
+              node = a.pab[(wb + lane) * 64 + lo] & 0xFFFFu;
             }
           }
         }
-      }
-      // first end points of the dense rows (undirected players only): players with the same first end point are
-      // consecutive, so a word is a few runs of equal a; a run's count in a row is one popcount. The runs of a
-      // word are found once (a chain of dependent look-ups) and applied to every dense row of the group.
-      if (!a.directed) {
-        for (int64_t w = tid; w < W; w += kSThreads) {
-          uint64_t mr[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            uint64_t m = 0ull;
-            if (dmode[i] >= 0) {
-              m = a.Z[(g * R + i) * a.row_stride + w];
-              if (dmode[i]) m = ~m;
-              if (w == W - 1) m &= tail_mask;
-            }
-            mr[i] = m;
+        // (c) + second end points, 32 words at a time
+#pragma unroll 1
+        for (int hb = 0; hb < 2; ++hb) {
+          if (wb + 32 * hb >= w_end) break;
+          __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+          if ((lane >> 5) == hb) {
+            uint4* dst = (uint4*)stage + (lane & 31) * 4;
+            const uint32_t lo0 = (uint32_t)mw[0], lo1 = (uint32_t)mw[1], lo2 = (uint32_t)mw[2], lo3 = (uint32_t)mw[3];
+            const uint32_t lo4 = (uint32_t)mw[4], lo5 = (uint32_t)mw[5], lo6 = (uint32_t)mw[6], lo7 = (uint32_t)mw[7];
+            const uint32_t hi0 = (uint32_t)(mw[0] >> 32), hi1 = (uint32_t)(mw[1] >> 32), hi2 = (uint32_t)(mw[2] >> 32);
+            const uint32_t hi3 = (uint32_t)(mw[3] >> 32), hi4 = (uint32_t)(mw[4] >> 32), hi5 = (uint32_t)(mw[5] >> 32);
+            const uint32_t hi6 = (uint32_t)(mw[6] >> 32), hi7 = (uint32_t)(mw[7] >> 32);
+            // __builtin_amdgcn_perm(x, y, sel): byte k of the result is byte sel[k] of {x (bytes 4..7), y (bytes 0..3)}
+            constexpr uint32_t kLow = 0x05040100u, kHigh = 0x07060302u;  // the low / high halves of y and x
+            dst[0] = make_uint4(__builtin_amdgcn_perm(lo1, lo0, kLow), __builtin_amdgcn_perm(lo3, lo2, kLow),
+                                __builtin_amdgcn_perm(lo5, lo4, kLow), __builtin_amdgcn_perm(lo7, lo6, kLow));
+            dst[1] = make_uint4(__builtin_amdgcn_perm(lo1, lo0, kHigh), __builtin_amdgcn_perm(lo3, lo2, kHigh),
+                                __builtin_amdgcn_perm(lo5, lo4, kHigh), __builtin_amdgcn_perm(lo7, lo6, kHigh));
+            dst[2] = make_uint4(__builtin_amdgcn_perm(hi1, hi0, kLow), __builtin_amdgcn_perm(hi3, hi2, kLow),
+                                __builtin_amdgcn_perm(hi5, hi4, kLow), __builtin_amdgcn_perm(hi7, hi6, kLow));
+            dst[3] = make_uint4(__builtin_amdgcn_perm(hi1, hi0, kHigh), __builtin_amdgcn_perm(hi3, hi2, kHigh),
+                                __builtin_amdgcn_perm(hi5, hi4, kHigh), __builtin_amdgcn_perm(hi7, hi6, kHigh));
           }
-          int64_t p = w * 64;
-          const int64_t p_end = p + 64 < a.n ? p + 64 : a.n;
-          while (p < p_end) {
-            const uint32_t ha = a.pab[p] & 0xFFFFu;
-            int64_t run_end = a.a_end[ha];
-            if (run_end > p_end) run_end = p_end;
-            const int lo = (int)(p - w * 64), hi = (int)(run_end - w * 64);  // bits lo .. hi-1 of the word
-            const uint64_t seg = (hi >= 64 ? ~0ull : ((1ull << hi) - 1ull)) & ~((1ull << lo) - 1ull);
-            uint32_t* cb = cnt_all + (ha << lrh);
+          __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+          const int64_t w0 = wb + 32 * hb;
+          const uint4* src = (const uint4*)stage + (lane >> 4);
+          const int sh = lane & 15;
+          for (int j0 = 0; j0 < 32 && w0 + j0 < w_end; j0 += 8) {
+            uint32_t e[8];
 #pragma unroll
-            for (int h = 0; h < (R + 3) / 4; ++h) {
-              uint32_t inc[2] = {0u, 0u};
+            for (int u = 0; u < 8; ++u) e[u] = e_next[u];
+            if (w0 + j0 + 8 < w_end && (hb == 0 || j0 + 8 < 32)) load_players(w0 + j0 + 8, e_next);
 #pragma unroll
-              for (int i2 = 0; i2 < 4; ++i2) {
-                const int i = 4 * h + i2;
-                if (i >= R) break;
-                inc[i2 >> 1] |= (uint32_t)__popcll(mr[i] & seg) << ((i2 & 1) << 4);  // zero words for the other rows
-              }
-              if (R == 2) {
-                if (inc[0]) atomicAdd(cb, inc[0]);
-              } else if (inc[0] | inc[1]) {
-                atomicAdd((unsigned long long*)cb + h, (unsigned long long)inc[0] | ((unsigned long long)inc[1] << 32));
-              }
+            for (int u = 0; u < 8; ++u) {
+              const uint4 x = src[(j0 + u) * 4];
+              uint32_t inc[4];
+              inc[0] = (x.x >> sh) & 0x00010001u;
+              inc[1] = (x.y >> sh) & 0x00010001u;
+              inc[2] = (x.z >> sh) & 0x00010001u;
+              inc[3] = (x.w >> sh) & 0x00010001u;
+              add_packed(e[u] >> 16, inc);
             }
-            p = run_end;
           }
         }
       }
     }
     __syncthreads();
-    // degrees, transposed: the R records of this workgroup are R consecutive slots of one block
+    // degrees: [group][node][row of the group], one contiguous block per workgroup (whole cache lines are written)
     {
-      const int64_t rec0 = g * R;
-      const int64_t blk = rec0 / a.slots;
-      const int slot0 = (int)(rec0 - blk * a.slots);
-      uint16_t* dst = a.deg_out + ((size_t)blk * a.V) * a.slots + slot0;
+      uint16_t* dst = a.deg_out + (size_t)g * a.V * R;
       for (int v = tid; v < a.V; v += kSThreads) {
         const int full1 = a.row_ptr[v + 1] - a.row_ptr[v] + 1;
-        uint32_t* d32 = (uint32_t*)(dst + (size_t)v * a.slots);
+        uint32_t d[R / 2];
+#pragma unroll
         for (int q2 = 0; q2 < R; q2 += 2) {
-          const uint32_t cw = cnt_all[(v << lrh) + (q2 >> 1)];
+          const uint32_t cw = *cnt_word((uint32_t)v, q2 >> 1);
           int c0 = cw & 0xFFFF, c1 = cw >> 16;
           if (!PAIRED) {
             if (modes[q2] & 1) c0 = full1 - 1 - c0;
             if (modes[q2 + 1] & 1) c1 = full1 - 1 - c1;
           }
-          d32[q2 >> 1] = (uint32_t)(c0 + 1) | ((uint32_t)(c1 + 1) << 16);
+          d[q2 >> 1] = (uint32_t)(c0 + 1) | ((uint32_t)(c1 + 1) << 16);
         }
+        uint32_t* d32 = (uint32_t*)(dst + (size_t)v * R);
+        if (R == 8) *(uint4*)d32 = make_uint4(d[0], d[1 % (R / 2)], d[2 % (R / 2)], d[3 % (R / 2)]);
+        else if (R == 4) *(uint2*)d32 = make_uint2(d[0], d[1 % (R / 2)]);
+        else d32[0] = d[0];
       }
     }
     // the needed players' bits
@@ -1479,7 +1562,7 @@ BatchedLayout make_stream_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t
 size_t stream_bytes(const BatchedLayout& bl, const ds_cgraph* cg) {
   const size_t Wn = (size_t)(cg->info.num_players + 63) / 64;
   return ds_align((size_t)cg->info.num_players * 4) + ds_align((size_t)cg->info.num_nodes * 4) * 2 + ds_align((size_t)bl.records * 4) +
-         ds_align(Wn * 8) + ds_align(Wn * 4) + ds_align((size_t)bl.E_need * 4 + 4) + ds_scan_arena_bytes((int64_t)Wn) +
+         2 * (ds_align(Wn * 8) + ds_align(Wn * 4)) + ds_align(16) + ds_align((size_t)bl.E_need * 4 + 4) + ds_scan_arena_bytes((int64_t)Wn) +
          ds_align((size_t)bl.deg_blocks * cg->info.num_nodes * bl.slots * 2) + ds_align((size_t)bl.records * bl.eb_stride * 4);
 }
 
@@ -1632,20 +1715,23 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
     fill_args(ctx, cg, lay, &b.e);
     DS_TRY(ds_kernel_mark(ctx, 0, 0));
     if (bl.ext) {
-      uint32_t* pab = (uint32_t*)ds_arena_alloc(ctx, (size_t)n * 4);
-      int32_t* a_end = (int32_t*)ds_arena_alloc(ctx, (size_t)cg->info.num_nodes * 4);
-      uint16_t* fdeg2 = (uint16_t*)ds_arena_alloc(ctx, (size_t)cg->info.num_nodes * 2);
       const int64_t Wn = (n + 63) / 64;
+      uint32_t* pab = (uint32_t*)ds_arena_alloc(ctx, (size_t)n * 4);
+      uint64_t* wsplit = (uint64_t*)ds_arena_alloc(ctx, (size_t)Wn * 8);
+      int32_t* wfirst = (int32_t*)ds_arena_alloc(ctx, (size_t)Wn * 4);
+      uint16_t* fdeg2 = (uint16_t*)ds_arena_alloc(ctx, (size_t)cg->info.num_nodes * 2);
       uint64_t* nmask = (uint64_t*)ds_arena_alloc(ctx, (size_t)Wn * 8);
       int32_t* nbase = (int32_t*)ds_arena_alloc(ctx, (size_t)Wn * 4);
+      int32_t* need_range = (int32_t*)ds_arena_alloc(ctx, 16);
       int32_t* erank = (int32_t*)ds_arena_alloc(ctx, (size_t)(bl.E_need > 0 ? bl.E_need : 1) * 4);
       int32_t* sizes = sz ? nullptr : (int32_t*)ds_arena_alloc(ctx, (size_t)bl.records * 4);
       uint16_t* deg = (uint16_t*)ds_arena_alloc(ctx, (size_t)bl.deg_blocks * cg->info.num_nodes * bl.slots * 2);
       uint32_t* ebits = (uint32_t*)ds_arena_alloc(ctx, (size_t)bl.records * bl.eb_stride * 4);
-      if (!pab || !a_end || !fdeg2 || !nmask || !nbase || !erank || (!sz && !sizes) || !deg || !ebits)
+      if (!pab || !wsplit || !wfirst || !fdeg2 || !nmask || !nbase || !need_range || !erank || (!sz && !sizes) || !deg || !ebits)
         return ds_fail(ctx, bounded ? DS_ECAPACITY : DS_EINTERNAL, "eval: workspace exhausted (%lld records of %lld bytes)",
                        (long long)bl.records, (long long)(cg->info.num_nodes * 2 + bl.eb_stride * 4));
-      hipLaunchKernelGGL(pack_endpoints_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, cg->pl, n, pab, a_end);
+      hipLaunchKernelGGL(pack_endpoints_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, cg->pl, n, pab,
+                         (unsigned long long*)wsplit, wfirst);
       hipLaunchKernelGGL(full_degree_kernel, dim3((unsigned)((cg->info.num_nodes + 255) / 256)), dim3(256), 0, ctx->stream, cg->row_ptr,
                          (int)cg->info.num_nodes, fdeg2);
       // the players whose bits layer 1 reads: their words' masks, the rank of every such player, the rank per entry
@@ -1655,6 +1741,9 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
                            (unsigned long long*)nmask);
       hipLaunchKernelGGL(need_count_kernel, dim3((unsigned)((Wn + 255) / 256)), dim3(256), 0, ctx->stream, nmask, Wn, nbase);
       DS_TRY(ds_scan_exclusive_i32(ctx, nbase, nbase, Wn, nullptr));
+      hipLaunchKernelGGL(store_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, need_range, 0x7fffffff);
+      hipLaunchKernelGGL(store_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, need_range + 1, 0);
+      hipLaunchKernelGGL(need_range_kernel, dim3((unsigned)((Wn + 255) / 256)), dim3(256), 0, ctx->stream, nmask, Wn, need_range);
       if (bl.E_need > 0)
         hipLaunchKernelGGL(need_rank_kernel, dim3((unsigned)((bl.E_need + 255) / 256)), dim3(256), 0, ctx->stream, cg->eid, bl.E_need,
                            nmask, nbase, erank);
@@ -1669,10 +1758,12 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
       sa.row_stride = paired ? 2 * sa.W : sa.W;
       sa.Z = Z;
       sa.pab = pab;
-      sa.a_end = a_end;
+      sa.wsplit = wsplit;
+      sa.wfirst = wfirst;
       sa.row_ptr = cg->row_ptr;
       sa.nmask = nmask;
       sa.nbase = nbase;
+      sa.need_range = need_range;
       sa.eb_words = bl.eb_words;
       sa.deg_out = deg;
       sa.ebits_out = ebits;
@@ -1704,6 +1795,7 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
       DS_HIP(ctx, hipGetLastError());
       DS_TRY(ds_kernel_mark(ctx, 4, 1));
       b.ext_deg = deg;
+      b.ext_lr = bl.stream_lr;
       b.ext_bits = ebits;
       b.erank = erank;
       b.fdeg2 = fdeg2;
