@@ -6,7 +6,7 @@ A step is one complete pass of the hot path over one batch of synthetic input: o
 workload's target, or, for the 64-target configuration, one ds_explain_batch call over all 64 targets.
 Graph, features and weights are resident in HBM before the timed region. Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4] [--others c2,c3,c5]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4] [--others c2,c3,c5,c4b]
 
 The headline workload is the largest single-GPU configuration (config 4: one million players, 400,000
 coalitions, a 50 GB mask matrix). Short runs of the other configurations are reported under
@@ -316,7 +316,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c4")
-    ap.add_argument("--others", default="c2,c3,c5",
+    ap.add_argument("--others", default="c2,c3,c5,c4b",
                     help="comma-separated workloads timed briefly after the headline one (\"\" = none)")
     ap.add_argument("--other-steps", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -359,7 +359,7 @@ def main():
     left = lambda: args.time_budget_s - (time.perf_counter() - T_START)
     others = {}
     # rough cost of a short run of each (generation + warm-up + steps), seconds
-    cost = {"c2": 15, "c3": 50, "c5": 25, "c4": 80, "gat_c2": 15, "gat_rmat": 20}
+    cost = {"c2": 15, "c3": 50, "c5": 25, "c4": 80, "c4b": 15, "gat_c2": 15, "gat_rmat": 20}
     for key in [s for s in args.others.split(",") if s and s != args.workload]:
         need = cost.get(key, 30) + (0 if args.no_cpu_baseline else 35)
         if left() < need:

@@ -95,3 +95,32 @@ def induced_undirected_edge_count(row_ptr, col, inside):
         return 0
     idx = np.repeat(starts - np.cumsum(np.r_[0, lens[:-1]]), lens) + np.arange(lens.sum())
     return int(inside[col[idx]].sum()) // 2
+
+
+def fanout_capped_subgraph(row_ptr, col, root, fans):
+    """Neighbourhood sampling with a deterministic fan-out cap: from `root`, hop h keeps, for every node
+    reached at hop h-1, its first fans[h-1] neighbours in CSR order. Returns the graph made of exactly the
+    kept edges (symmetrised, nodes renumbered in ascending order of their old ids) and the root's new id."""
+    src_all, dst_all = [], []
+    seen = np.zeros(len(row_ptr) - 1, dtype=bool)
+    seen[root] = True
+    frontier = np.array([root], dtype=np.int64)
+    for f in fans:
+        if len(frontier) == 0:
+            break
+        starts = row_ptr[frontier]
+        lens = np.minimum(row_ptr[frontier + 1] - starts, f)
+        idx = np.repeat(starts - np.cumsum(np.r_[0, lens[:-1]]), lens) + np.arange(lens.sum())
+        nb = col[idx].astype(np.int64)
+        src_all.append(np.repeat(frontier, lens))
+        dst_all.append(nb)
+        new = np.unique(nb)
+        new = new[~seen[new]]
+        seen[new] = True
+        frontier = new
+    src = np.concatenate(src_all)
+    dst = np.concatenate(dst_all)
+    nodes = np.flatnonzero(seen)
+    num = len(nodes)
+    rp, ci = csr_from_undirected_edges(num, np.searchsorted(nodes, src), np.searchsorted(nodes, dst))
+    return num, rp, ci, int(np.searchsorted(nodes, root))

@@ -176,6 +176,28 @@ def _rmat_workload(name, cfg_id, scale, want, d0, dims, n_samples, solver,
                          "balls": [p[3] for p in picks]})
 
 
+def _hub_fanout_workload(name, cfg_id, scale, edge_factor, want, d0, dims, n_samples, solver):
+    """Hub target with a fan-out cap: the highest-degree node of an R-MAT graph, its 3-hop neighbourhood sampled
+    with the same cap F at every hop (the first F neighbours in CSR order), F the smallest cap that gives at
+    least `want` edges. Unlike the low-degree targets next to a hub, most players here are entries of rows the
+    first layer has to produce, so the evaluation gathers feature rows instead of only counting degrees."""
+    rng = _rng(cfg_id)
+    _, rp, ci = graphs.rmat(scale, edge_factor, rng)
+    hub = int(np.argmax(np.diff(rp)))
+    lo, hi = 1, 2
+    while len(graphs.fanout_capped_subgraph(rp, ci, hub, (hi,) * 3)[2]) // 2 < want:
+        lo, hi = hi, hi * 2
+    while hi - lo > 1:  # the edge count grows with the cap
+        mid = (lo + hi) // 2
+        if len(graphs.fanout_capped_subgraph(rp, ci, hub, (mid,) * 3)[2]) // 2 < want:
+            lo = mid
+        else:
+            hi = mid
+    N, srp, sci, root = graphs.fanout_capped_subgraph(rp, ci, hub, (hi,) * 3)
+    return _finish(name, cfg_id, N, srp, sci, d0, dims, [root], n_samples, solver, rng,
+                   info={"players": len(sci) // 2, "fan_out": hi, "hub_degree": int(rp[hub + 1] - rp[hub])})
+
+
 WORKLOADS = {
     "c1": _c1,
     "c2": _c2,
@@ -188,6 +210,12 @@ WORKLOADS = {
     "c5": lambda: _rmat_workload("c5_rmat18_batch64", 5, 18, 10_000, 512,
                                  (512, 256, 256, 32), 50_000, "gram_chol",
                                  count=64, transform_dtype="bf16", examine=1200),
+    # "4b": a hub target under a fan-out cap, the gather-heavy counterpart of config 4 (at a tenth of its
+    # size: every player is a first-layer entry here, so the work per coalition is ~60 times config 4's)
+    "c4b": lambda: _hub_fanout_workload("c4b_rmat18_hub_fanout_100k_edges", 6, 18, 16, 100_000, 128,
+                                        (128, 64, 64, 10), 20_000, "cgls"),
+    "c4b_small": lambda: _hub_fanout_workload("c4b_small_rmat13_hub_fanout", 16, 13, 3, 1_500, 32,
+                                              (32, 16, 16, 5), 4_000, "cgls"),
     # reduced variants: same structure, sizes the CPU oracle finishes in seconds
     "c2_small": lambda: _small_ba(),
     "c3_small": lambda: _rmat_workload("c3_small_rmat13", 13, 13, 3_000, 64,

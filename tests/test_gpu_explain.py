@@ -79,6 +79,11 @@ def test_small_underdetermined_config_cgls_minimum_norm():
     _explain_case("c4_small", 1e-4, oracle_solver="cgls")
 
 
+def test_small_hub_target_with_fan_out_cap():
+    # a hub target: nearly every player is an entry of a row the first layer produces (the gather-heavy shape)
+    _explain_case("c4b_small", 1e-4, oracle_solver="cgls")
+
+
 def test_underdetermined_config_direct_solver_reports_and_auto_falls_back():
     """Fewer rows than players: the direct solver inside ds_explain must report the singular system (its pivot
     flag only reaches the host with the final read-back), and solver AUTO must then give the minimum-norm
