@@ -157,12 +157,17 @@ typedef struct ds_tuning {
                                  selection (a test hook: the masks are the same either way) */
   int32_t eval_path;          /* masked GCN inference kernel: 0 = chosen by size; 1 = one workgroup per coalition;
                                  2 = one coalition per lane, masks on chip (short mask rows); 3 = the mask-streaming
-                                 kernel followed by the one-coalition-per-lane layers (long mask rows). 2 and 3 need
-                                 256 rows or more and fall back to 1 where they do not apply (a test hook: the
-                                 results agree to rounding) */
+                                 kernel followed by the one-coalition-per-lane layers (long mask rows); 4 = layer by
+                                 layer over blocks of 64 coalitions from a transposed mask matrix (graphs whose first
+                                 layer reads more entries than fit on chip). 2, 3 and 4 need 256 rows or more and fall
+                                 back to 1 where they do not apply (a test hook: the results agree to rounding) */
   int32_t cgls_dense_div;     /* CGLS on large games: pair rows with more than n / div players stay bit-packed and
                                  are multiplied on the int8 matrix cores, the sparser ones become (row, column)
                                  entries multiplied through LDS (default 64, the measured optimum; 32..65536) */
+  int32_t pair_lists;         /* ds_explain with long mask rows: the sampler also writes the players of every sparse
+                                 small member (at most n / div players; 0 = default div 64, a list of half the bit row's
+                                 bytes; 16..2^20) as a list, which the mask-streaming kernel reads instead of
+                                 the bit row; -1 = bit rows only (a test hook: the results are identical) */
 } ds_tuning;
 int ds_set_tuning(ds_ctx* ctx, const ds_tuning* tuning /* [host] or NULL */);
 

@@ -31,7 +31,8 @@ class Options(C.Structure):
 
 class Tuning(C.Structure):
     _fields_ = [("batch_workers", C.c_int32), ("gram_sparse_div", C.c_int32), ("gram_dense_fraction", C.c_float),
-                ("sampler_window", C.c_int32), ("eval_path", C.c_int32), ("cgls_dense_div", C.c_int32)]
+                ("sampler_window", C.c_int32), ("eval_path", C.c_int32), ("cgls_dense_div", C.c_int32),
+                ("pair_lists", C.c_int32)]
 
 
 class Report(C.Structure):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdistshap_hip.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "sampler.hip", "extract.hip", "eval.hip", "gat_eval.hip", "bitmat.hip", "tiles.hip",
+SOURCES = ["api.hip", "sampler.hip", "extract.hip", "eval.hip", "eval_zt.hip", "gat_eval.hip", "bitmat.hip", "tiles.hip",
            "gram_chol.hip", "cgls.hip", "fidelity.hip", "plan.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # The one flag list of the shipped code objects (tests that inspect the generated code import it).

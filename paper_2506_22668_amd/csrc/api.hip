@@ -175,8 +175,9 @@ int ds_set_tuning(ds_ctx* ctx, const ds_tuning* tuning) {
   }
   if (tuning->batch_workers < 0 || tuning->batch_workers > 16 || tuning->gram_sparse_div < 0 ||
       !(tuning->gram_dense_fraction >= 0.f && tuning->gram_dense_fraction <= 1.f) || tuning->sampler_window < -1 ||
-      tuning->eval_path < 0 || tuning->eval_path > 3 ||
-      (tuning->cgls_dense_div != 0 && (tuning->cgls_dense_div < 32 || tuning->cgls_dense_div > 65536)))
+      tuning->eval_path < 0 || tuning->eval_path > 4 ||
+      (tuning->cgls_dense_div != 0 && (tuning->cgls_dense_div < 32 || tuning->cgls_dense_div > 65536)) ||
+      tuning->pair_lists < -1 || (tuning->pair_lists > 0 && (tuning->pair_lists < 16 || tuning->pair_lists > (1 << 20))))
     return ds_fail(ctx, DS_EINVAL, "tuning value out of range");
   ctx->tuning = *tuning;
   return DS_OK;
@@ -542,7 +543,7 @@ static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t
   hipStream_t st = ctx->stream;
   struct Guard {
     ds_ctx* c; ds_cgraph* g;
-    ~Guard() { (void)hipStreamSynchronize(c->side); ds_cgraph_free(c, g); ds_arena_reset(c); }
+    ~Guard() { (void)hipStreamSynchronize(c->side); c->lists = ds_pair_lists{}; ds_cgraph_free(c, g); ds_arena_reset(c); }
   } guard{ctx, cg};
   const int64_t n = cg->info.num_players;
   rep.num_players = n;
@@ -583,6 +584,15 @@ static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t
     // the direct solver's buffers are live during the inference, and a fall-back CGLS comes on top of them
     if (o.solver == DS_SOLVER_GRAM_CHOL || (o.solver == DS_SOLVER_AUTO && n <= 16384)) persistent += ds_gram_arena_bytes(n, k);
   }
+  // Long mask rows: the inference reads the sparse small members (at most n / 64 players: a list is then at most half
+  // the bytes of the bit row) as player lists that the sampler writes beside the rows, instead of streaming their bits.
+  ds_pair_lists lists{};
+  if (n >= 2 && ctx->tuning.pair_lists != -1 && ds_sampler_lists_possible(ctx, plan) && ds_eval_streams_pairs(ctx, cg, k)) {
+    const int64_t div = ctx->tuning.pair_lists > 0 ? ctx->tuning.pair_lists : 64;
+    lists.max_size = n / div < plan.H ? n / div : plan.H;
+    lists.total = ds_pair_list_entries(plan, lists.max_size);
+    if (lists.total > 0) persistent += ds_align((size_t)lists.total * 4) + ds_align((size_t)(k / 2) * 8);
+  }
   ds_arena_reset(ctx);
   DS_TRY(ds_arena_reserve(ctx, persistent + stage));
   uint64_t* Z = (uint64_t*)ds_arena_alloc(ctx, (size_t)k * W * 8);
@@ -590,6 +600,11 @@ static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t
   int32_t* sz = (int32_t*)ds_arena_alloc(ctx, k * 4);
   float* y = (float*)ds_arena_alloc(ctx, k * 4);
   if (!Z || !w || !sz || !y) return ds_fail(ctx, DS_EINTERNAL, "explain: arena exhausted");
+  if (lists.total > 0) {
+    lists.entries = (uint32_t*)ds_arena_alloc(ctx, (size_t)lists.total * 4);
+    lists.offset = (int64_t*)ds_arena_alloc(ctx, (size_t)(k / 2) * 8);
+    if (!lists.entries || !lists.offset) return ds_fail(ctx, DS_EINTERNAL, "explain: arena exhausted");
+  }
   // The shared first transform and the predicted class depend only on the computational graph:
   // they run on the side stream while the main stream draws the coalitions.
   DS_HIP(ctx, hipEventRecord(ctx->fork_ev, st));
@@ -608,7 +623,8 @@ static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t
     DS_HIP(ctx, hipMemcpyAsync(Z, rows, sizeof(rows), hipMemcpyHostToDevice, st));
     DS_HIP(ctx, hipStreamSynchronize(st));
   } else {
-    DS_TRY(ds_sample_launch(ctx, plan, seed, (uint32_t)((uint64_t)target & 0xFFFFFFFFull), 0, k / 2, Z, w, sz));
+    DS_TRY(ds_sample_launch(ctx, plan, seed, (uint32_t)((uint64_t)target & 0xFFFFFFFFull), 0, k / 2, Z, w, sz,
+                            lists.entries ? &lists : nullptr));
   }
   ctx->arena_used = mark;
   DS_HIP(ctx, hipEventRecord(ctx->ev[2], st));
@@ -629,7 +645,10 @@ static int explain_extracted(ds_ctx* ctx, ds_cgraph* cg, int64_t target, int64_t
   const size_t mark2 = ctx->arena_used;
 
   DS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_ev, 0));
-  DS_TRY(ds_eval_impl(ctx, cg, Z, k, o.score, y, DS_EVAL_PAIRED, n >= 2 ? sz : nullptr));  // the sampler's rows are complementary pairs
+  ctx->lists = lists;
+  const int erc = ds_eval_impl(ctx, cg, Z, k, o.score, y, DS_EVAL_PAIRED, n >= 2 ? sz : nullptr);  // the sampler's rows are complementary pairs
+  ctx->lists = ds_pair_lists{};
+  DS_TRY(erc);
   ctx->arena_used = mark2;
   DS_HIP(ctx, hipEventRecord(ctx->ev[3], st));
 

@@ -57,7 +57,7 @@ __device__ __forceinline__ uint64_t transpose64_in_wave(uint64_t x, int lane) {
 
 __global__ __launch_bounds__(kTrThreads) void bit_transpose_kernel(const uint64_t* in, int64_t rows, int64_t cols,
                                                                    int64_t in_stride, int64_t row_first, int64_t row_step,
-                                                                   uint64_t* out, int64_t Wout, int64_t tiles_c) {
+                                                                   uint64_t* out, int64_t Wout, int64_t tiles_c, int block_major) {
   __shared__ uint64_t tin[512 * kTrPitch];
   __shared__ uint64_t tout[512 * kTrPitch];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -80,6 +80,17 @@ __global__ __launch_bounds__(kTrThreads) void bit_transpose_kernel(const uint64_
     tout[(wave * 64 + lane) * kTrPitch + rbi] = x;   // lane = column within the word column, word = row block
   }
   __syncthreads();
+  if (block_major) {
+    // out[row block][column] (Win * 64 columns per row block): a wave writes the 64 columns of one row block, 512
+    // contiguous bytes
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int c = k * 64 + lane, w = wave;
+      const int64_t col = w0 * 64 + c, ow = tr * 8 + w;
+      if (col < Win * 64 && ow < Wout) out[ow * (Win * 64) + col] = tout[c * kTrPitch + w];
+    }
+    return;
+  }
   // store: 8 lanes per output row (64 contiguous bytes)
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
@@ -512,7 +523,18 @@ int ds_bit_transpose(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols
   if (tiles_r < 1 || tiles_c < 1) return DS_OK;
   if (tiles_r * tiles_c > 0x7fffffffLL) return ds_fail(ctx, DS_EINVAL, "bit matrix too large to transpose");
   hipLaunchKernelGGL(bit_transpose_kernel, dim3((unsigned)(tiles_r * tiles_c)), dim3(kTrThreads), 0, ctx->stream, in, rows, cols,
-                     in_stride, row_first, row_step, out, Wout, tiles_c);
+                     in_stride, row_first, row_step, out, Wout, tiles_c, 0);
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}
+
+int ds_bit_transpose_blocks(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols, int64_t in_stride, uint64_t* out) {
+  const int64_t Wout = (rows + 63) / 64, Win = (cols + 63) / 64;
+  const int64_t tiles_r = (rows + 511) / 512, tiles_c = (Win + 7) / 8;
+  if (tiles_r < 1 || tiles_c < 1) return DS_OK;
+  if (tiles_r * tiles_c > 0x7fffffffLL) return ds_fail(ctx, DS_EINVAL, "bit matrix too large to transpose");
+  hipLaunchKernelGGL(bit_transpose_kernel, dim3((unsigned)(tiles_r * tiles_c)), dim3(kTrThreads), 0, ctx->stream, in, rows, cols,
+                     in_stride, (int64_t)0, (int64_t)1, out, Wout, tiles_c, 1);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }

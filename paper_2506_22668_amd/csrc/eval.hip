@@ -352,7 +352,7 @@ __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
 // meet at barriers between the stages.
 constexpr int kBW = 32;        // mask words per coalition held in LDS (at least; more for wider masks, see the layout)
 constexpr int kBWMax = 192;    // ... up to this many (12,288 players) when the rest of the LDS budget allows
-constexpr int kStageRows = 8;  // entries per matrix-core batch; also sizes the shared weight buffer
+constexpr int kStageRows = 4;  // entries per matrix-core batch; also sizes the shared weight buffer
 constexpr int kBThreads = 1024; // sixteen waves share the 64 coalitions of a workgroup: the stages are latency chains per
                                 // wave, and only one workgroup fits a CU's LDS, so more waves per workgroup shorten them
                                 // (measured against eight waves: 0.39 -> 0.32 ms on 1,010 players, 4.1 -> 2.4 ms on 9,647)
@@ -372,7 +372,7 @@ struct BatchedArgs {
   // complements) or per row
   const uint16_t* ext_deg;
   const uint32_t* ext_bits;   // [record][eb_stride]: bit r = mask bit of the needed player of rank r
-  const uint16_t* fdeg2;      // [V]: deg_full(v) + 2
+  const uint32_t* fdeg2;      // [V]: deg_full(v) + 2
   const int32_t* erank;       // [E_need]: rank of the player of CSR entry e among the needed players
   int64_t eb_stride;
   int32_t ext_paired, eb_words;
@@ -534,9 +534,13 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
   int ext_member = 0;
   auto rs_of = [&](int v) -> float {
     if (EXT) {
-      int d = ext_deg_lane[(size_t)v << b.ext_lr];
-      if (ext_member) d = b.fdeg2[v] - d;  // the complement: d'(v) = deg_full(v) + 2 - d(v)
-      return __frsqrt_rn((float)d);
+      // the complement: d'(v) = deg_full(v) + 2 - d(v). The node is the same in every lane: the full degree comes by
+      // a scalar load (no vector register, no branch on the lane's member that would hold its load back)
+      typedef const __attribute__((address_space(4))) uint32_t* scalar_u32_ptr;
+      const int vs = __builtin_amdgcn_readfirstlane(v);
+      const int f = (int)((scalar_u32_ptr)b.fdeg2)[vs];
+      const int d = ext_deg_lane[(size_t)vs << b.ext_lr];
+      return __frsqrt_rn((float)(ext_member ? f - d : d));
     }
     if (DEG_LDS) return __frsqrt_rn((float)degs[v * 64 + lane]);
     return rs[(size_t)v * 64 + lane];
@@ -824,6 +828,10 @@ struct StreamArgs {
   uint16_t* deg_out;            // [group][V][R]: d(v) = 1 + active entries of row v, record = group * R + row of the group
   uint32_t* ebits_out;          // [rows][eb_stride] bit r = mask bit of the needed player of rank r
   int64_t eb_stride;
+  // the players of sparse rows as lists (the sampler writes them beside the mask rows), or null: row r's players are
+  // list[list_offset[r] .. + sizes[r]) in any order when list_offset[r] >= 0; such a row's bits are not read at all
+  const uint32_t* list;
+  const int64_t* list_offset;
 };
 
 // (256 threads per workgroup: a wave is the 64 players of one mask word)
@@ -855,9 +863,9 @@ __global__ __launch_bounds__(kThreads) void mask_row_sizes_kernel(const uint64_t
 }
 
 // needed players: mark, (scan of the per-word counts on the host side), rank of every needed CSR entry's player
-__global__ void full_degree_kernel(const int32_t* row_ptr, int V, uint16_t* fdeg2) {
+__global__ void full_degree_kernel(const int32_t* row_ptr, int V, uint32_t* fdeg2) {
   const int v = blockIdx.x * blockDim.x + threadIdx.x;
-  if (v < V) fdeg2[v] = (uint16_t)(row_ptr[v + 1] - row_ptr[v] + 2);
+  if (v < V) fdeg2[v] = (uint32_t)(row_ptr[v + 1] - row_ptr[v] + 2);
 }
 __global__ void zero_u64_kernel(uint64_t* x, int64_t count) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -923,7 +931,7 @@ __global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int R = 1 << LR;  // rows per workgroup
   uint32_t* cnt_all = ssm;
-  int* modes = (int*)(ssm + a.cnt_words);  // bit 0: the cleared bits are walked, bit 1: player by player
+  int* modes = (int*)(ssm + a.cnt_words);  // bit 0: the cleared bits are walked, bit 1: player by player, bit 2: from a list
   uint32_t* queue = ssm + a.cnt_words + 8;  // kSWaves queues of kQueueCap players
   uint32_t* nb_all = queue + kSWaves * kQueueCap;       // R x eb_words needed bits
   // 16-bit counters, two rows to a u32 (row r: half r & 1 of pair r >> 1). Up to four rows (two pairs) of a node are
@@ -947,6 +955,7 @@ __global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a)
         const bool flip = !PAIRED && 2 * sz > a.n;
         const int64_t walk = flip ? a.n - sz : sz;
         mode = (flip ? 1 : 0) | (((walk << kDenseShift) >= a.n && walk >= kDenseMinBits) ? 2 : 0);
+        if (PAIRED && a.list_offset != nullptr && mode == 0 && a.list_offset[rr] >= 0) mode = 4;  // its players come as a list
       }
       modes[tid] = mode;
     }
@@ -985,7 +994,7 @@ __global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a)
       const int qrow = __builtin_amdgcn_readfirstlane(wave / wpr), part = __builtin_amdgcn_readfirstlane(wave % wpr);
       const int64_t r = g * R + qrow;
       const int mode = modes[qrow];
-      const bool active = r < a.rows && !(mode & 2);   // the same for the whole wave
+      const bool active = r < a.rows && !(mode & 6);   // the same for the whole wave
       const bool flip = mode & 1;
       const uint64_t* z = a.Z + (r < a.rows ? r : 0) * a.row_stride;
       uint32_t* myq = queue + wave * kQueueCap;
@@ -1097,6 +1106,39 @@ __global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a)
           step(wc0, cur);
         }
         if (qfill) drain();
+      }
+      // ---- rows whose players come as a list: 4 bytes per player instead of the n / 8 bytes of the bit row. The waves
+      // of the row take 512 entries at a time, eight per lane, with the eight end-point look-ups in flight together.
+      if (r < a.rows && (mode & 4)) {
+        const uint32_t* lst = a.list + a.list_offset[r];
+        const int s = a.sizes[r * a.size_step];
+        uint32_t* nb = nb_all + (size_t)qrow * a.eb_words;
+        for (int i0 = part * 512; i0 < s; i0 += wpr * 512) {
+          uint32_t ent[8], e[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int idx = i0 + u * 64 + lane;
+            ent[u] = idx < s ? lst[idx] : 0xFFFFFFFFu;
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) e[u] = ent[u] < (uint32_t)a.n ? a.pab[ent[u]] : 0u;
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            if (ent[u] < (uint32_t)a.n) {
+              count_one(e[u] >> 16, qrow);
+              if (!a.directed) count_one(e[u] & 0xFFFFu, qrow);
+              const int64_t w = ent[u] >> 6;
+              if (w >= need_lo && w < need_hi) {
+                const uint64_t nm = a.nmask[w];
+                const int j = ent[u] & 63;
+                if ((nm >> j) & 1ull) {
+                  const int rk = a.nbase[w] + __popcll(nm & ((1ull << j) - 1ull));
+                  atomicOr(&nb[rk >> 5], 1u << (rk & 31));
+                }
+              }
+            }
+          }
+        }
       }
     }
     // ---- rows walked player by player. A wave takes a contiguous range of word columns, 64 words at a time with
@@ -1253,7 +1295,7 @@ __global__ __launch_bounds__(kSThreads) void stream_degrees_kernel(StreamArgs a)
     {
       uint16_t* dst = a.deg_out + (size_t)g * a.V * R;
       for (int v = tid; v < a.V; v += kSThreads) {
-        const int full1 = a.row_ptr[v + 1] - a.row_ptr[v] + 1;
+        const int full1 = PAIRED ? 0 : a.row_ptr[v + 1] - a.row_ptr[v] + 1;  // (only a walk over cleared bits needs it)
         uint32_t d[R / 2];
 #pragma unroll
         for (int q2 = 0; q2 < R; q2 += 2) {
@@ -1647,9 +1689,20 @@ size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
     bl = make_stream_layout(ctx, cg, k, 0);  // the unpaired form is the larger one
     if (bl.use) batched = ds_align((size_t)bl.stride * 4 * bl.grid) + stream_bytes(bl, cg);
   }
+  if (!bl.use && (path == 0 || path == 4)) batched = ds_eval_zt_arena_bytes(ctx, cg, k);
   // the last three terms: what ds_prepare_model allocates (full mask row, logits, one workgroup's scratch)
   return ds_align((size_t)lay.gws_floats * 4 * grid) + batched + ds_align(W * 8 + 8) + ds_align(ctx->dims[ctx->L] * 4 + 8) +
          ds_align((size_t)lay.gws_floats * 4) + 1024;
+}
+
+bool ds_eval_streams_pairs(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
+  if (ctx->model_kind == DS_MODEL_GAT || (k & 1)) return false;
+  const int path = ctx->tuning.eval_path;
+  if (path == 0 || path == 2) {
+    if (make_batched_layout(ctx, cg, k).use) return false;
+  }
+  if (path == 0 || path == 3) return make_stream_layout(ctx, cg, k, 1).use;
+  return false;
 }
 
 // Shared first transform and the class predicted on the full computational graph;
@@ -1719,7 +1772,7 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
       uint32_t* pab = (uint32_t*)ds_arena_alloc(ctx, (size_t)n * 4);
       uint64_t* wsplit = (uint64_t*)ds_arena_alloc(ctx, (size_t)Wn * 8);
       int32_t* wfirst = (int32_t*)ds_arena_alloc(ctx, (size_t)Wn * 4);
-      uint16_t* fdeg2 = (uint16_t*)ds_arena_alloc(ctx, (size_t)cg->info.num_nodes * 2);
+      uint32_t* fdeg2 = (uint32_t*)ds_arena_alloc(ctx, (size_t)cg->info.num_nodes * 4);
       uint64_t* nmask = (uint64_t*)ds_arena_alloc(ctx, (size_t)Wn * 8);
       int32_t* nbase = (int32_t*)ds_arena_alloc(ctx, (size_t)Wn * 4);
       int32_t* need_range = (int32_t*)ds_arena_alloc(ctx, 16);
@@ -1771,6 +1824,10 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
       sa.cnt_words = bl.cnt_words;
       sa.slots = bl.slots;
       sa.eb_stride = bl.eb_stride;
+      if (paired && ctx->lists.entries != nullptr) {  // (set by an explanation whose sampler wrote lists for these very rows)
+        sa.list = ctx->lists.entries;
+        sa.list_offset = ctx->lists.offset;
+      }
       DS_TRY(ds_kernel_mark(ctx, 4, 0));
       if (sz) {  // the sampler's sizes: row r of this launch is row r (or 2r) of the mask matrix
         sa.sizes = sz;
@@ -1830,6 +1887,13 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
     b.zs_words = bl.zs_words;
     if (bl.ext) DS_TRY(launch_batched<true>(ctx, bl, b, bgrid));
     else DS_TRY(launch_batched<false>(ctx, bl, b, bgrid));
+    return ds_kernel_mark(ctx, 0, 1);
+  }
+  // graphs neither of the two can take (needed entries that do not fit LDS for 64 coalitions): layer by layer over
+  // blocks of 64 coalitions, from a transposed mask matrix (needs a large workspace: not for the bounded form)
+  if (!bounded && (path == 0 || path == 4) && ds_eval_zt_applies(ctx, cg, k)) {
+    DS_TRY(ds_kernel_mark(ctx, 0, 0));
+    DS_TRY(ds_eval_zt(ctx, cg, Z, k, score, y));
     return ds_kernel_mark(ctx, 0, 1);
   }
   const size_t avail = ctx->arena_bytes - ctx->arena_used > 512 ? ctx->arena_bytes - ctx->arena_used - 512 : 0;

@@ -1,0 +1,440 @@
+// Masked GCN inference for computational graphs whose first layer reads (nearly) every player: one layer at a
+// time over blocks of 64 coalitions, from a transposed mask matrix.
+//
+// Paper, "Distributed Model Prediction": cost O(b (n d + |V_c| d^2)) per batch of b sub-graphs; the n d term is the
+// masked aggregation. When the target is a hub, the rows the first layer has to produce hold most of the graph's
+// entries (a 100k-player graph: 196k of 200k CSR entries), and one workgroup per coalition pays one gathered
+// feature row per active entry and coalition. Here 64 coalitions are evaluated together: with the mask matrix
+// transposed block-wise, T[block][player] = the player's bits in the block's 64 coalitions, one 8-byte word says for
+// all 64 coalitions whether an entry is active, every row of P = X_c W_1 is loaded once per 64 coalitions, and
+//   H1[t][f][c] = sum_e P[src_e][f] * (bit_e(c) ? d_src(c)^-1/2 : 0)
+// is a (features x entries) . (entries x coalitions) product on the matrix cores (v_mfma_f32_32x32x2f32). Unlike the
+// one-coalition-per-lane kernel for short mask rows, nothing here has to fit a workgroup's LDS: every stage is a
+// kernel of its own over (block, row) tasks, with the per-block operands [row][feature][coalition] in global
+// memory, a bounded number of blocks at a time:
+//   degrees  d(v) = 1 + sum of the bits of row v's entries            (lane = coalition)
+//   layer 1  the contraction above, scaled by d_t^-1/2, + bias, ReLU   (matrix cores)
+//   layer l >= 2: q = D^-1/2 (A_S + I) D^-1/2 H  (lane = coalition, VALU; coefficients differ per coalition),
+//                 then act(q W_l + b_l), (features out x features in) . (features in x coalitions), matrix cores
+//   readout  soft-max (or logit) of the predicted class.
+#include "internal.h"
+#include "solve_common.h"
+
+namespace {
+
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kZThreads = 256;
+constexpr int kZWaves = kZThreads / 64;
+
+struct ZtArgs {
+  int32_t V, L, score, bf16;
+  int32_t dims[DS_MAX_LAYERS + 1];
+  int32_t rows_out[DS_MAX_LAYERS + 1];
+  const int32_t *row_ptr, *col, *eid;
+  const float* P;
+  const float* Wl[DS_MAX_LAYERS];
+  const float* bias[DS_MAX_LAYERS];
+  const uint64_t* T;   // [blocks][npad]
+  int64_t npad, k;
+  int64_t blk0;        // first block of this launch
+  int32_t nblk;        // blocks of this launch
+  float* rs;           // [nblk][V][64]: d^-1/2
+  const int32_t* pred_ptr;
+  float* y;
+};
+
+__device__ __forceinline__ float zt_bf16_round(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even (finite inputs)
+  return __uint_as_float(u & 0xFFFF0000u);
+}
+
+__device__ __forceinline__ uint32_t rl(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
+
+// d(v)^-1/2 for every node and coalition of the launch's blocks. One wave per (block, node): the lanes fetch the
+// words of up to 64 entries of the row together, then every word is broadcast and each lane adds its own bit.
+__global__ __launch_bounds__(kZThreads) void zt_degrees_kernel(ZtArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = ((int64_t)blockIdx.x * kZThreads + threadIdx.x) >> 6, nwaves = ((int64_t)gridDim.x * kZThreads) >> 6;
+  const uint32_t mlo = lane < 32 ? 1u << lane : 0u, mhi = lane >= 32 ? 1u << (lane - 32) : 0u;
+  const int64_t tasks = (int64_t)a.nblk * a.V;
+  for (int64_t task = wave; task < tasks; task += nwaves) {
+    const int64_t cbi = task / a.V;
+    const int v = (int)(task - cbi * a.V);
+    const uint64_t* Tb = a.T + (a.blk0 + cbi) * a.npad;
+    const int e0 = a.row_ptr[v], e1 = a.row_ptr[v + 1];
+    int cnt = 1;
+    for (int eb = e0; eb < e1; eb += 64) {
+      const int m = e1 - eb < 64 ? e1 - eb : 64;
+      const uint64_t word = lane < m ? Tb[a.eid[eb + lane]] : 0ull;
+      const uint32_t lo = (uint32_t)word, hi = (uint32_t)(word >> 32);
+      for (int i = 0; i < m; ++i) cnt += ((rl(lo, i) & mlo) | (rl(hi, i) & mhi)) ? 1 : 0;
+    }
+    a.rs[((size_t)cbi * a.V + v) * 64 + lane] = 1.0f / sqrtf((float)cnt);
+  }
+}
+
+// Layer 1 on the matrix cores, one wave per (block, row t): H1[t][f][c] = act( d_t(c)^-1/2 sum_e P[src_e][f] coef_e(c)
+// + b[f] ), the sum over the row's entries and the self-loop (coef = d_t^-1/2). With v_mfma_f32_32x32x2f32 lane l
+// supplies A[m = l%32][k = l/32] = P[src of entry 2q + l/32][f0 + l%32] and B[k = l/32][n = l%32] = coefficient of
+// entry 2q + l/32 for coalition n (and, for the second accumulator column, coalition 32 + n): a lane reads the
+// degree factors of exactly the two coalitions it feeds and tests their two bits of the entry's word, so no
+// value crosses lanes. Entries are fetched 64 at a time (lane j: entry j's source, word), steps of two entries; the
+// operands of four steps are requested together.
+__global__ __launch_bounds__(kZThreads) void zt_layer1_kernel(ZtArgs a, float* out) {
+  const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+  const int64_t wave = ((int64_t)blockIdx.x * kZThreads + threadIdx.x) >> 6, nwaves = ((int64_t)gridDim.x * kZThreads) >> 6;
+  const int d1 = a.dims[1], rows1 = a.rows_out[1];
+  const bool relu = a.L > 1;
+  const int64_t tasks = (int64_t)a.nblk * rows1;
+  for (int64_t task = wave; task < tasks; task += nwaves) {
+    const int64_t cbi = task / rows1;
+    const int t = (int)(task - cbi * rows1);
+    const uint64_t* Tb = a.T + (a.blk0 + cbi) * a.npad;
+    const float* rsb = a.rs + (size_t)cbi * a.V * 64;
+    const int e0 = a.row_ptr[t], e1 = a.row_ptr[t + 1];  // entry e1 stands for the self-loop
+    const float rst0 = rsb[(size_t)t * 64 + l32], rst1 = rsb[(size_t)t * 64 + 32 + l32];
+    for (int f0 = 0; f0 < d1; f0 += 64) {
+      float16_t acc[2][2];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        acc[0][0][i] = 0.f; acc[0][1][i] = 0.f; acc[1][0][i] = 0.f; acc[1][1][i] = 0.f;
+      }
+      const bool fok0 = f0 + l32 < d1, fok1 = f0 + 32 + l32 < d1;
+      for (int eb = e0; eb <= e1; eb += 64) {
+        const int m = e1 + 1 - eb < 64 ? e1 + 1 - eb : 64;
+        const int e = eb + lane;
+        int sv = t;
+        uint64_t word = 0ull;
+        if (e < e1) {
+          sv = a.col[e];
+          word = Tb[a.eid[e]];
+        } else if (e == e1) {
+          word = ~0ull;
+        }
+        const uint32_t wlo = (uint32_t)word, whi = (uint32_t)(word >> 32);
+        for (int q0 = 0; q0 < m; q0 += 8) {  // four steps of two entries
+          float av[4][2], rv[4][2];
+          uint32_t b0m[4], b1m[4];
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const int i0 = q0 + 2 * s, i1 = i0 + 1;   // (lanes past m hold a zero word and source t)
+            const int il0 = i0 < 64 ? i0 : 63, il1 = i1 < 64 ? i1 : 63;
+            const int s0 = (int)rl((uint32_t)sv, il0), s1 = (int)rl((uint32_t)sv, il1);
+            const uint32_t l0 = rl(wlo, il0), l1 = rl(wlo, il1), h0 = rl(whi, il0), h1 = rl(whi, il1);
+            const bool live0 = i0 < m, live1 = i1 < m;
+            const int src = half ? s1 : s0;
+            const uint32_t lo = half ? (live1 ? l1 : 0u) : (live0 ? l0 : 0u);
+            const uint32_t hi = half ? (live1 ? h1 : 0u) : (live0 ? h0 : 0u);
+            b0m[s] = (lo >> l32) & 1u;
+            b1m[s] = (hi >> l32) & 1u;
+            const float* pr = a.P + (size_t)src * d1 + f0 + l32;
+            av[s][0] = fok0 ? pr[0] : 0.f;
+            av[s][1] = fok1 ? pr[32] : 0.f;
+            const float* rp = rsb + (size_t)src * 64 + l32;
+            rv[s][0] = rp[0];
+            rv[s][1] = rp[32];
+          }
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            if (q0 + 2 * s < m) {
+              const float b0 = b0m[s] ? rv[s][0] : 0.f, b1 = b1m[s] ? rv[s][1] : 0.f;
+              acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][0], b0, acc[0][0], 0, 0, 0);
+              acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][0], b1, acc[0][1], 0, 0, 0);
+              acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][1], b0, acc[1][0], 0, 0, 0);
+              acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][1], b1, acc[1][1], 0, 0, 0);
+            }
+          }
+        }
+      }
+      // accumulator register i of lane l is D[feature 8*(i/4) + 4*(l/32) + i%4][coalition l%32] (+32 features per ft,
+      // +32 coalitions per nb)
+      float* o = out + (((size_t)cbi * rows1 + t) * d1 + f0 + 4 * half) * 64 + l32;
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int fo = ft * 32 + 8 * (i / 4) + (i % 4);
+            const int f = f0 + 4 * half + fo;
+            if (f < d1) {
+              float v = (nb ? rst1 : rst0) * acc[ft][nb][i];
+              if (a.bias[0]) v += a.bias[0][f];
+              o[(size_t)fo * 64 + nb * 32] = relu ? fmaxf(v, 0.f) : v;
+            }
+          }
+    }
+  }
+}
+
+// Aggregation of a later layer, lane = coalition: q[t][f][c] = d_t^-1/2 ( sum_{active e} d_src^-1/2 H[src][f][c] +
+// d_t^-1/2 H[t][f][c] ). One wave per (block, row, slice of 16 features); the sources and words of up to 64 entries
+// are fetched together, four entries' operands are in flight per step.
+__global__ __launch_bounds__(kZThreads) void zt_aggregate_kernel(ZtArgs a, int l, const float* cur, float* q) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = ((int64_t)blockIdx.x * kZThreads + threadIdx.x) >> 6, nwaves = ((int64_t)gridDim.x * kZThreads) >> 6;
+  const uint32_t mlo = lane < 32 ? 1u << lane : 0u, mhi = lane >= 32 ? 1u << (lane - 32) : 0u;
+  const int din = a.dims[l - 1], rows = a.rows_out[l], rows_prev = a.rows_out[l - 1];
+  const int fch = (din + 15) / 16;
+  const int64_t tasks = (int64_t)a.nblk * rows * fch;
+  for (int64_t task = wave; task < tasks; task += nwaves) {
+    const int64_t cbi = task / ((int64_t)rows * fch);
+    const int rem = (int)(task - cbi * rows * fch);
+    const int t = rem / fch, f0 = (rem - t * fch) * 16;
+    const uint64_t* Tb = a.T + (a.blk0 + cbi) * a.npad;
+    const float* rsb = a.rs + (size_t)cbi * a.V * 64;
+    const float* hb = cur + (size_t)cbi * rows_prev * din * 64 + (size_t)f0 * 64 + lane;
+    const int e0 = a.row_ptr[t], e1 = a.row_ptr[t + 1];  // entry e1 stands for the self-loop
+    const float rst = rsb[(size_t)t * 64 + lane];
+    float acc[16];
+#pragma unroll
+    for (int f = 0; f < 16; ++f) acc[f] = 0.f;
+    for (int eb = e0; eb <= e1; eb += 64) {
+      const int m = e1 + 1 - eb < 64 ? e1 + 1 - eb : 64;
+      const int e = eb + lane;
+      int sv = t;
+      uint64_t word = 0ull;
+      if (e < e1) {
+        sv = a.col[e];
+        word = Tb[a.eid[e]];
+      } else if (e == e1) {
+        word = ~0ull;
+      }
+      const uint32_t wlo = (uint32_t)word, whi = (uint32_t)(word >> 32);
+      for (int i0 = 0; i0 < m; i0 += 4) {
+        float c[4];
+        const float* hp[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int i = i0 + u < 64 ? i0 + u : 63;
+          const int src = (int)rl((uint32_t)sv, i);
+          const bool on = i0 + u < m && ((rl(wlo, i) & mlo) | (rl(whi, i) & mhi)) != 0u;
+          c[u] = on ? rsb[(size_t)src * 64 + lane] : 0.f;
+          hp[u] = hb + (size_t)src * din * 64;
+        }
+        float hv[4][16];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int f = 0; f < 16; ++f) hv[u][f] = (f0 + f < din) ? hp[u][(size_t)f * 64] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int f = 0; f < 16; ++f) acc[f] += c[u] * hv[u][f];
+      }
+    }
+    float* qo = q + (((size_t)cbi * rows + t) * din + f0) * 64 + lane;
+#pragma unroll
+    for (int f = 0; f < 16; ++f)
+      if (f0 + f < din) {
+        const float v = rst * acc[f];
+        qo[(size_t)f * 64] = a.bf16 ? zt_bf16_round(v) : v;
+      }
+  }
+}
+
+// Dense transform of a later layer on the matrix cores: nxt[t][j][c] = act( sum_f W[f][j] q[t][f][c] + b[j] ). One
+// wave per (block, row, 32 output features, 32 coalitions): lane l supplies W[f + l/32][j0 + l%32] and
+// q[t][f + l/32][c0 + l%32] (v_mfma_f32_32x32x2f32); in the bfloat16 configuration both operands are rounded to
+// bfloat16 (q already is) and v_mfma_f32_32x32x8bf16_1k accumulates in fp32, lane l supplying k = 4*(l/32) .. +3.
+__global__ __launch_bounds__(kZThreads) void zt_transform_kernel(ZtArgs a, int l, const float* q, float* nxt) {
+  const int lane = threadIdx.x & 63, half = lane >> 5, r = lane & 31;
+  const int64_t wave = ((int64_t)blockIdx.x * kZThreads + threadIdx.x) >> 6, nwaves = ((int64_t)gridDim.x * kZThreads) >> 6;
+  const int din = a.dims[l - 1], dout = a.dims[l], rows = a.rows_out[l];
+  const bool relu = l < a.L, isbf = a.bf16 != 0;
+  const float* Wg = a.Wl[l - 1];
+  const float* bias = a.bias[l - 1];
+  const int jt = (dout + 31) / 32;
+  const int64_t tasks = (int64_t)a.nblk * rows * jt * 2;
+  for (int64_t task = wave; task < tasks; task += nwaves) {
+    const int64_t rt = task / (2 * jt);   // block * rows + row
+    const int rem = (int)(task - rt * 2 * jt);
+    const int j0 = (rem >> 1) * 32, c0 = (rem & 1) * 32;
+    const bool jok = j0 + r < dout;
+    const float* qp = q + (size_t)rt * din * 64 + c0 + r;
+    const float* wp = Wg + (jok ? j0 + r : 0);
+    float16_t acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int fb = 0; fb < din; fb += 32) {  // 32 input features per step: their sixteen operand loads are in flight together
+      float xa[4][4], xb[4][4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int f = fb + 8 * s + (isbf ? 4 * half + u : 2 * u + half);
+          const bool ok = f < din;
+          const float wv = (ok && jok) ? wp[(size_t)f * dout] : 0.f;
+          xa[s][u] = isbf ? zt_bf16_round(wv) : wv;
+          xb[s][u] = ok ? qp[(size_t)f * 64] : 0.f;
+        }
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (fb + 8 * s >= din) break;
+        if (isbf) {
+          short4_t av, bv;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            av[u] = (short)(__float_as_uint(xa[s][u]) >> 16);
+            bv[u] = (short)(__float_as_uint(xb[s][u]) >> 16);
+          }
+          acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(av, bv, acc, 0, 0, 0);
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[s][u], xb[s][u], acc, 0, 0, 0);
+        }
+      }
+    }
+    // accumulator register i of lane l is out[feature j0 + 8*(i/4) + 4*(l/32) + i%4][coalition c0 + l%32]
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int j = j0 + 8 * (i / 4) + 4 * half + (i % 4);
+      if (j < dout) {
+        const float v = acc[i] + (bias ? bias[j] : 0.f);
+        nxt[((size_t)rt * dout + j) * 64 + c0 + r] = relu ? fmaxf(v, 0.f) : v;
+      }
+    }
+  }
+}
+
+// readout: the target is row 0 of the last layer's output; one thread per coalition
+__global__ void zt_readout_kernel(ZtArgs a, const float* cur) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)a.nblk * 64) return;
+  const int64_t cbi = i >> 6;
+  const int lane = (int)(i & 63);
+  const int64_t row = (a.blk0 + cbi) * 64 + lane;
+  if (row >= a.k) return;
+  const int C = a.dims[a.L], rowsL = a.rows_out[a.L];
+  const float* lg = cur + (size_t)cbi * rowsL * C * 64 + lane;
+  float m = -INFINITY;
+  for (int c = 0; c < C; ++c) m = fmaxf(m, lg[(size_t)c * 64]);
+  float sum = 0.f;
+  for (int c = 0; c < C; ++c) sum += expf(lg[(size_t)c * 64] - m);
+  const float zc = lg[(size_t)(*a.pred_ptr) * 64];
+  a.y[row] = a.score == DS_SCORE_LOGIT ? zc : expf(zc - m) / sum;
+}
+
+struct ZtPlan {
+  bool use;
+  int64_t blocks, npad, chunk;        // blocks of 64 coalitions, padded players, blocks per launch
+  int64_t rs_f, a_f, b_f, q_f;        // floats per block of the four scratch regions
+  int32_t rows_out[DS_MAX_LAYERS + 1];
+};
+
+constexpr size_t kZtMaxTransposed = (size_t)16 << 30;  // the transposed mask matrix may take this much
+constexpr size_t kZtScratch = (size_t)6 << 30;         // per-launch operands of the blocks in flight
+
+ZtPlan zt_plan(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
+  ZtPlan p;
+  memset(&p, 0, sizeof(p));
+  const int64_t n = cg->info.num_players, V = cg->info.num_nodes;
+  const int L = ctx->L;
+  if (n < 1 || k < 256 || L < 1 || ctx->model_kind != DS_MODEL_GCN) return p;
+  p.blocks = (k + 63) / 64;
+  p.npad = (n + 63) / 64 * 64;
+  if ((size_t)p.blocks * p.npad * 8 > kZtMaxTransposed) return p;
+  p.rows_out[0] = 0;
+  for (int l = 1; l <= L; ++l) {
+    int h = L - l;
+    if (h > cg->info.hops) h = cg->info.hops;
+    p.rows_out[l] = (int32_t)cg->info.ball[h];
+  }
+  p.rs_f = V * 64;
+  // layer l's output lands in region A for odd l, B for even l; q holds the aggregated rows of the layer in flight
+  for (int l = 1; l <= L; ++l) {
+    const int64_t out = (int64_t)p.rows_out[l] * ctx->dims[l] * 64;
+    if (l & 1) p.a_f = out > p.a_f ? out : p.a_f;
+    else p.b_f = out > p.b_f ? out : p.b_f;
+    if (l >= 2) {
+      const int64_t qf = (int64_t)p.rows_out[l] * ctx->dims[l - 1] * 64;
+      p.q_f = qf > p.q_f ? qf : p.q_f;
+    }
+  }
+  const size_t per_block = (size_t)(p.rs_f + p.a_f + p.b_f + p.q_f) * 4;
+  int64_t c = (int64_t)(kZtScratch / per_block);
+  if (c < 1) c = 1;
+  if (c > p.blocks) c = p.blocks;
+  p.chunk = c;
+  p.use = true;
+  return p;
+}
+
+int64_t grid_for_waves(const ds_ctx* ctx, int64_t tasks) {
+  int64_t g = (tasks + kZWaves - 1) / kZWaves;
+  const int64_t cap = (int64_t)ctx->num_cus * 8;
+  if (g > cap) g = cap;
+  return g < 1 ? 1 : g;
+}
+
+}  // namespace
+
+bool ds_eval_zt_applies(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) { return zt_plan(ctx, cg, k).use; }
+
+size_t ds_eval_zt_arena_bytes(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
+  const ZtPlan p = zt_plan(ctx, cg, k);
+  if (!p.use) return 0;
+  return ds_align((size_t)p.blocks * p.npad * 8) + ds_align((size_t)p.rs_f * 4 * p.chunk) + ds_align((size_t)p.a_f * 4 * p.chunk) +
+         ds_align((size_t)p.b_f * 4 * p.chunk + 256) + ds_align((size_t)p.q_f * 4 * p.chunk + 256) + 1024;
+}
+
+// The model must be prepared (P and the predicted class on the device); temporaries come from the context's arena.
+int ds_eval_zt(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y) {
+  const ZtPlan p = zt_plan(ctx, cg, k);
+  if (!p.use) return ds_fail(ctx, DS_EINTERNAL, "eval: the block-transposed path does not apply");
+  const int64_t n = cg->info.num_players, W = (n + 63) / 64;
+  uint64_t* T = (uint64_t*)ds_arena_alloc(ctx, (size_t)p.blocks * p.npad * 8);
+  float* rs = (float*)ds_arena_alloc(ctx, (size_t)p.rs_f * 4 * p.chunk);
+  float* bufA = (float*)ds_arena_alloc(ctx, (size_t)p.a_f * 4 * p.chunk);
+  float* bufB = (float*)ds_arena_alloc(ctx, (size_t)p.b_f * 4 * p.chunk + 256);
+  float* q = (float*)ds_arena_alloc(ctx, (size_t)p.q_f * 4 * p.chunk + 256);
+  if (!T || !rs || !bufA || !bufB || !q) return ds_fail(ctx, DS_EINTERNAL, "eval: arena exhausted");
+  DS_TRY(ds_bit_transpose_blocks(ctx, Z, k, n, W, T));
+  ZtArgs a;
+  memset(&a, 0, sizeof(a));
+  a.V = (int32_t)cg->info.num_nodes;
+  a.L = ctx->L;
+  a.score = score;
+  a.bf16 = ctx->transform_dtype == DS_BF16_IN_F32_ACC;
+  for (int i = 0; i <= ctx->L; ++i) {
+    a.dims[i] = ctx->dims[i];
+    a.rows_out[i] = p.rows_out[i];
+  }
+  a.row_ptr = cg->row_ptr;
+  a.col = cg->col;
+  a.eid = cg->eid;
+  a.P = cg->P;
+  for (int l = 0; l < ctx->L; ++l) {
+    a.Wl[l] = ctx->W[l];
+    a.bias[l] = ctx->bias[l];
+  }
+  a.T = T;
+  a.npad = p.npad;
+  a.k = k;
+  a.rs = rs;
+  a.pred_ptr = cg->d_pred;
+  a.y = y;
+  for (int64_t b0 = 0; b0 < p.blocks; b0 += p.chunk) {
+    a.blk0 = b0;
+    a.nblk = (int32_t)(p.blocks - b0 < p.chunk ? p.blocks - b0 : p.chunk);
+    hipLaunchKernelGGL(zt_degrees_kernel, dim3((unsigned)grid_for_waves(ctx, (int64_t)a.nblk * a.V)), dim3(kZThreads), 0, ctx->stream, a);
+    hipLaunchKernelGGL(zt_layer1_kernel, dim3((unsigned)grid_for_waves(ctx, (int64_t)a.nblk * a.rows_out[1])), dim3(kZThreads), 0,
+                       ctx->stream, a, bufA);
+    float* cur = bufA;
+    for (int l = 2; l <= ctx->L; ++l) {
+      float* nxt = (l & 1) ? bufA : bufB;
+      const int64_t fch = (a.dims[l - 1] + 15) / 16, jt = (a.dims[l] + 31) / 32;
+      hipLaunchKernelGGL(zt_aggregate_kernel, dim3((unsigned)grid_for_waves(ctx, (int64_t)a.nblk * a.rows_out[l] * fch)), dim3(kZThreads),
+                         0, ctx->stream, a, l, (const float*)cur, q);
+      hipLaunchKernelGGL(zt_transform_kernel, dim3((unsigned)grid_for_waves(ctx, (int64_t)a.nblk * a.rows_out[l] * jt * 2)),
+                         dim3(kZThreads), 0, ctx->stream, a, l, (const float*)q, nxt);
+      cur = nxt;
+    }
+    hipLaunchKernelGGL(zt_readout_kernel, dim3((unsigned)((a.nblk * 64 + 255) / 256)), dim3(256), 0, ctx->stream, a, (const float*)cur);
+  }
+  DS_HIP(ctx, hipGetLastError());
+  return DS_OK;
+}

@@ -53,6 +53,17 @@ struct ds_gat_params {
   float slope;
 };
 
+// The small members of sparse complementary pairs as player lists, written by the sampler beside the mask rows
+// (a row with s of n players set is 4 s bytes as a list and n / 8 bytes as a bit row): pair r's players, in no
+// particular order, are entries[offset[r] .. offset[r] + s), offset[r] < 0 where the pair has no list (a size class
+// above max_size, an enumerated class, a pair the one-pass sampler handed on).
+struct ds_pair_lists {
+  uint32_t* entries;   // device
+  int64_t* offset;     // device, [pairs]
+  int64_t max_size;    // size classes 1..max_size are listed
+  int64_t total;       // entries reserved
+};
+
 struct ds_ctx {
   int device;
   hipStream_t stream;
@@ -99,6 +110,7 @@ struct ds_ctx {
   bool owns_stream;
   ds_tuning tuning;  // zero fields = built-in values
   double cgls_bytes_per_iter;  // bytes of matrix storage the last CGLS solve read per iteration (both products)
+  ds_pair_lists lists;         // set by an explanation between its sampling and its inference; entries == nullptr: none
 };
 
 int ds_fail(ds_ctx* ctx, int code, const char* fmt, ...);
@@ -138,8 +150,15 @@ struct ds_plan {
 int ds_make_plan(ds_ctx* ctx, int64_t n, int64_t n_samples, ds_plan* plan, int weighting = DS_WEIGHT_CLASS_MASS,
                  int saturate = 0);
 // launches the sampler; the overflow flag is left in device mailbox slot DS_MAIL_SAMPLER (checked by the caller)
+// lists (optional, only with pair_begin == 0): filled as described at ds_pair_lists; entries and offset are the
+// caller's allocations (ds_pair_list_entries(plan, max_size) entries, plan.k / 2 offsets)
 int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t tag, int64_t pair_begin,
-                     int64_t pair_end, uint64_t* Z, float* w, int32_t* sz);
+                     int64_t pair_end, uint64_t* Z, float* w, int32_t* sz, const ds_pair_lists* lists = nullptr);
+int64_t ds_pair_list_entries(const ds_plan& plan, int64_t max_size);
+// whether the sampler can write lists for this plan at all (the one-pass kernel runs)
+bool ds_sampler_lists_possible(const ds_ctx* ctx, const ds_plan& plan);
+// whether ds_eval_impl would run the mask-streaming kernel on k paired rows of this graph (the consumer of the lists)
+bool ds_eval_streams_pairs(ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
 int ds_sample_check(ds_ctx* ctx);  // synchronises and turns the flag into a status
 #define DS_MAIL_SAMPLER 20
 int ds_fetch_pred_class(ds_ctx* ctx, ds_cgraph* cg);  // device -> host copy of the predicted class (synchronises)
@@ -162,6 +181,11 @@ int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg);  // shared first transform + p
 int ds_static_scratch_init(int device);
 void* ds_static_scratch(int device);
 size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
+// masked GCN inference layer by layer over blocks of 64 coalitions from a block-transposed mask matrix (graphs whose
+// first layer reads too many entries for the on-chip kernels); the model must be prepared
+bool ds_eval_zt_applies(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
+size_t ds_eval_zt_arena_bytes(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
+int ds_eval_zt(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y);
 // width of the shared first transform P = X_c W_1
 static inline int32_t ds_first_width(const ds_ctx* ctx) {
   if (ctx->L < 1) return 0;

@@ -103,6 +103,12 @@ struct SampleArgs {
   uint32_t window_cap;  // entries of the dynamic-LDS window list
   int32_t* retry;          // pairs the one-pass kernel hands to the multi-pass kernel (offsets from pair_begin), or null
   uint32_t* retry_count;
+  // player lists of the sparse small members (one-pass kernel only; null: none). Pair r of a class s <= list_max
+  // owns list[list_cum[s] + (r - b[s-1] - 1) * s ..][s]; list_offset[r] gets that offset once the list is complete
+  uint32_t* list;
+  const int64_t* list_cum;
+  int64_t* list_offset;
+  int64_t list_max;
 };
 
 __global__ __launch_bounds__(kThreads) void sample_pairs_kernel(SampleArgs a) {
@@ -351,7 +357,7 @@ __global__ __launch_bounds__(kFastThreads) void sample_pairs_fast_kernel(SampleA
   __shared__ uint32_t whist[kWinBins];
   __shared__ unsigned long long cand[kFastCand];
   __shared__ unsigned long long window[kFastWindow];
-  __shared__ uint32_t cand_count, window_count, below_total, sel[2];
+  __shared__ uint32_t cand_count, window_count, below_total, sel[2], list_count;
   __shared__ unsigned long long threshold;
 
   const int t = threadIdx.x;
@@ -382,6 +388,11 @@ __global__ __launch_bounds__(kFastThreads) void sample_pairs_fast_kernel(SampleA
     const uint32_t width = k_hi - k_lo;                          // keys k with k - k_lo <= width are listed
     const int shift = width >= (uint32_t)kWinBins ? 32 - __builtin_clz(width) - 10 : 0;   // (width >> shift) < kWinBins
     bool give_up = r == 0 || (int64_t)s <= a.enum_upto;          // uniform over the workgroup
+    // the small member also goes out as a list of its players (sparse rows only): every lane appends the columns
+    // of the word it has just built, in whatever order the lanes arrive
+    const bool listing = a.list != nullptr && (int64_t)s <= a.list_max;
+    const int64_t list_off = listing ? a.list_cum[s] + (r - a.b[s - 1] - 1) * (int64_t)s : 0;
+    uint32_t* const lst = a.list + list_off;
     if (!give_up) {
       const uint32_t r_lo = (uint32_t)r, r_hi = (uint32_t)((uint64_t)r >> 32);
       for (int i = t; i < kWinBins; i += kFastThreads) whist[i] = 0;
@@ -389,6 +400,7 @@ __global__ __launch_bounds__(kFastThreads) void sample_pairs_fast_kernel(SampleA
         cand_count = 0;
         window_count = 0;
         below_total = 0;
+        list_count = 0;
       }
       __syncthreads();
       uint32_t below = 0;
@@ -421,6 +433,14 @@ __global__ __launch_bounds__(kFastThreads) void sample_pairs_fast_kernel(SampleA
         }
         row_small[d] = word;
         row_big[d] = ~word & valid;
+        if (listing && word) {   // a lane with columns reserves their places by itself
+          uint32_t pos = atomicAdd(&list_count, (uint32_t)__popc(word)), bits = word;
+          while (bits) {
+            if (pos < s) lst[pos] = (uint32_t)c0 + (uint32_t)(__ffs((int)bits) - 1);   // (past s only when the pair is given up)
+            ++pos;
+            bits &= bits - 1;
+          }
+        }
       }
       for (int o = 32; o > 0; o >>= 1) below += __shfl_xor(below, o, 64);
       if (lane == 0) atomicAdd(&below_total, below);
@@ -478,6 +498,10 @@ __global__ __launch_bounds__(kFastThreads) void sample_pairs_fast_kernel(SampleA
               const uint32_t bit = 1u << (col & 31);
               atomicOr(&row_small[col >> 5], bit);
               atomicAnd(&row_big[col >> 5], ~bit);
+              if (listing) {
+                const uint32_t pos = atomicAdd(&list_count, 1u);
+                if (pos < s) lst[pos] = col;
+              }
             }
           }
           if (t == 0) {
@@ -487,6 +511,7 @@ __global__ __launch_bounds__(kFastThreads) void sample_pairs_fast_kernel(SampleA
             a.w[o + 1] = wt;
             a.sz[o] = (int32_t)s;
             a.sz[o + 1] = (int32_t)(n - s);
+            if (listing) a.list_offset[r - a.pair_begin] = list_off;   // below + listed keys up to the threshold = s entries
           }
         }
       }
@@ -517,11 +542,24 @@ __global__ void enumerate_pairs_kernel(SampleArgs a) {
 }  // namespace
 
 size_t ds_sample_arena_bytes(const ds_plan& plan) {
-  return ds_align((plan.H + 1) * sizeof(int64_t)) + ds_align((plan.H + 1) * sizeof(float)) + ds_align((size_t)(plan.k / 2 + 2) * 4) + 512;
+  return 2 * ds_align((plan.H + 2) * sizeof(int64_t)) + ds_align((plan.H + 1) * sizeof(float)) + ds_align((size_t)(plan.k / 2 + 2) * 4) + 512;
+}
+
+// entries of the lists of the size classes 1..max_size: class s has b[s] - b[s-1] pairs of s players
+int64_t ds_pair_list_entries(const ds_plan& plan, int64_t max_size) {
+  int64_t total = 0;
+  for (int64_t s = 1; s <= max_size && s <= plan.H; ++s) total += (plan.b[s] - plan.b[s - 1]) * s;
+  return total;
+}
+
+bool ds_sampler_lists_possible(const ds_ctx* ctx, const ds_plan& plan) {
+  return !plan.enumerate && plan.n >= 4096 && ctx->tuning.sampler_window != -1 && plan.k / 2 < 0x7fffffffLL;
 }
 
 int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t tag, int64_t pair_begin,
-                     int64_t pair_end, uint64_t* Z, float* w, int32_t* sz) {
+                     int64_t pair_end, uint64_t* Z, float* w, int32_t* sz, const ds_pair_lists* lists) {
+  if (lists && (pair_begin != 0 || !ds_sampler_lists_possible(ctx, plan)))
+    return ds_fail(ctx, DS_EINTERNAL, "sampler: player lists are written only by the one-pass kernel from pair 0");
   if (pair_begin < 0 || pair_end > plan.k / 2 || pair_begin > pair_end)
     return ds_fail(ctx, DS_EINVAL, "pair range [%lld, %lld) outside [0, %lld)", (long long)pair_begin,
                    (long long)pair_end, (long long)(plan.k / 2));
@@ -531,9 +569,11 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
   const int64_t H = plan.H;
   int64_t* d_b = (int64_t*)ds_arena_alloc(ctx, (H + 1) * sizeof(int64_t));
   float* d_wtab = (float*)ds_arena_alloc(ctx, (H + 1) * sizeof(float));
-  if (!d_b || !d_wtab) return ds_fail(ctx, DS_EINTERNAL, "sampler: arena exhausted");
+  const int64_t lmax = lists ? (lists->max_size < H ? lists->max_size : H) : 0;
+  int64_t* d_cum = lists ? (int64_t*)ds_arena_alloc(ctx, (lmax + 2) * sizeof(int64_t)) : nullptr;
+  if (!d_b || !d_wtab || (lists && !d_cum)) return ds_fail(ctx, DS_EINTERNAL, "sampler: arena exhausted");
   // the plan tables go through pinned staging so that the upload is asynchronous
-  const size_t need = ds_align((H + 1) * sizeof(int64_t)) + ds_align((H + 1) * sizeof(float));
+  const size_t need = ds_align((H + 1) * sizeof(int64_t)) + ds_align((H + 1) * sizeof(float)) + ds_align((lmax + 2) * sizeof(int64_t));
   if (ctx->stage_busy) {
     DS_HIP(ctx, hipEventSynchronize(ctx->stage_ev));
     ctx->stage_busy = false;
@@ -552,6 +592,15 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
   memcpy(hw, plan.wtab.data(), (H + 1) * sizeof(float));
   DS_HIP(ctx, hipMemcpyAsync(d_b, hb, (H + 1) * sizeof(int64_t), hipMemcpyHostToDevice, ctx->stream));
   DS_HIP(ctx, hipMemcpyAsync(d_wtab, hw, (H + 1) * sizeof(float), hipMemcpyHostToDevice, ctx->stream));
+  if (lists) {   // entries before each listed class; every pair starts without a list
+    int64_t* hc = (int64_t*)(hw + ds_align((H + 1) * sizeof(float)));
+    hc[0] = 0;
+    hc[1] = 0;
+    for (int64_t s = 1; s <= lmax; ++s) hc[s + 1] = hc[s] + (plan.b[s] - plan.b[s - 1]) * s;
+    if (hc[lmax + 1] > lists->total) return ds_fail(ctx, DS_EINTERNAL, "sampler: the player lists need %lld entries, %lld are reserved", (long long)hc[lmax + 1], (long long)lists->total);
+    DS_HIP(ctx, hipMemcpyAsync(d_cum, hc, (lmax + 2) * sizeof(int64_t), hipMemcpyHostToDevice, ctx->stream));
+    DS_HIP(ctx, hipMemsetAsync(lists->offset, 0xFF, (size_t)(pair_end - pair_begin) * sizeof(int64_t), ctx->stream));
+  }
   DS_HIP(ctx, hipEventRecord(ctx->stage_ev, ctx->stream));
   ctx->stage_busy = true;
   int* d_err = (int*)(ctx->d_mail + DS_MAIL_SAMPLER);
@@ -573,6 +622,10 @@ int ds_sample_launch(ds_ctx* ctx, const ds_plan& plan, uint64_t seed, uint32_t t
   a.w = w;
   a.sz = sz;
   a.error_flag = d_err;
+  a.list = lists ? lists->entries : nullptr;
+  a.list_cum = d_cum;
+  a.list_offset = lists ? lists->offset : nullptr;
+  a.list_max = lmax;
   // window list capacity: bins within 3 sigma of the expected threshold position at the widest size (s = n/2)
   {
     const double nn = (double)plan.n, sigma = sqrt(nn / 4.0);

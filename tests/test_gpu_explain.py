@@ -84,6 +84,32 @@ def test_small_hub_target_with_fan_out_cap():
     _explain_case("c4b_small", 1e-4, oracle_solver="cgls")
 
 
+def test_long_row_kernels_inside_an_explanation_with_and_without_player_lists():
+    """The mask-streaming kernel forced on a reduced config (6,000 players: the one-pass sampler runs). By default the
+    sampler then also writes the players of every sparse small member as a list, and the streaming kernel reads the
+    lists instead of those bit rows; with the lists switched off it reads bits only. Both count the same integers:
+    phi must be identical, and equal to the oracle's."""
+    from paper_2506_22668_amd import Options, Tuning
+    w = make_workload("c4_small")
+    ctx = make_context(w)
+    target = w.targets[0]
+    opts = Options(solver=SOLVERS["cgls"], tol=w.tol)
+    got = {}
+    for lists in (0, -1):
+        ctx.set_tuning(Tuning(eval_path=3, pair_lists=lists))
+        say(f"explain c4_small target={target} eval_path=3 pair_lists={lists}")
+        phi, _, _, rep, _ = ctx.explain(target, w.n_samples, w.seed, opts)
+        assert rep.ms_k_stream > 0.0      # the streaming kernel did run
+        got[lists] = phi.cpu().numpy()
+    ctx.set_tuning(None)
+    assert np.array_equal(got[0], got[-1])
+    ref = oexplain.explain(w.row_ptr, w.col, w.features, w.weights, target, w.n_samples, w.seed, solver="cgls", tol=w.tol)
+    err, scale = np.abs(got[0].astype(np.float64) - ref["phi"]).max(), np.abs(ref["phi"]).max()
+    say(f"  n={ref['n']} k={ref['k']} max|phi|={scale:.3e} err={err:.3e}")
+    assert err <= 1e-4 * scale
+    ctx.close()
+
+
 def test_underdetermined_config_direct_solver_reports_and_auto_falls_back():
     """Fewer rows than players: the direct solver inside ds_explain must report the singular system (its pivot
     flag only reaches the host with the final read-back), and solver AUTO must then give the minimum-norm

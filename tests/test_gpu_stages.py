@@ -218,9 +218,10 @@ def _eval_case(w, hops, directed, score, biases, rows, rng, tol=1e-5, layers=Non
     ref = f.batch(bits)
     scale = max(1.0, np.abs(ref).max())
     # every inference kernel on the same rows: the size-based choice, then each kernel forced (one workgroup per
-    # coalition; one coalition per lane with the masks on chip; the mask-streaming kernel + layers on its output)
+    # coalition; one coalition per lane with the masks on chip; the mask-streaming kernel + layers on its output;
+    # layer by layer over blocks of 64 coalitions from the transposed mask matrix)
     from paper_2506_22668_amd import Tuning
-    for path in (0, 1, 2, 3):
+    for path in (0, 1, 2, 3, 4):
         ctx.set_tuning(Tuning(eval_path=path))
         y, pc = ctx.eval(cg, Z, score)
         assert pc == f.pred_class
@@ -232,7 +233,7 @@ def _eval_case(w, hops, directed, score, biases, rows, rng, tol=1e-5, layers=Non
         pbits[1::2] = ~pbits[0::2]
         Zp = torch.from_numpy(sampling.pack_rows(pbits).view(np.int64)).cuda()
         refp = f.batch(pbits)
-        for path in (0, 3):
+        for path in (0, 3, 4):
             ctx.set_tuning(Tuning(eval_path=path))
             y, pc = ctx.eval(cg, Zp, score, pairs=True)
             err = np.abs(y.cpu().numpy().astype(np.float64) - refp).max()
