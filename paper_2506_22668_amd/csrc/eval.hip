@@ -1675,6 +1675,12 @@ int ds_launch_argmax(ds_ctx* ctx, const float* logits, int C, int32_t* out) {
   return DS_OK;
 }
 
+// whether the single evaluation that finds the predicted class goes through the layer-by-layer kernels
+static bool prepare_uses_blocks(const ds_ctx* ctx, const ds_cgraph* cg) {
+  return cg->info.num_entries >= 32768 && ds_eval_zt_applies(ctx, cg, 1, 1) &&
+         ds_eval_zt_arena_bytes(ctx, cg, 1, 1) <= ((size_t)1 << 30);
+}
+
 size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
   if (ctx->model_kind == DS_MODEL_GAT) return ds_gat_eval_arena_bytes(ctx, cg, k);
   const EvalLayout lay = make_layout(ctx, cg);
@@ -1690,9 +1696,10 @@ size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
     if (bl.use) batched = ds_align((size_t)bl.stride * 4 * bl.grid) + stream_bytes(bl, cg);
   }
   if (!bl.use && (path == 0 || path == 4)) batched = ds_eval_zt_arena_bytes(ctx, cg, k);
-  // the last three terms: what ds_prepare_model allocates (full mask row, logits, one workgroup's scratch)
+  // the last terms: what ds_prepare_model allocates (full mask row, logits, one workgroup's scratch or the operands
+  // of one block of the layer-by-layer kernels)
   return ds_align((size_t)lay.gws_floats * 4 * grid) + batched + ds_align(W * 8 + 8) + ds_align(ctx->dims[ctx->L] * 4 + 8) +
-         ds_align((size_t)lay.gws_floats * 4) + 1024;
+         ds_align((size_t)lay.gws_floats * 4) + (prepare_uses_blocks(ctx, cg) ? ds_eval_zt_arena_bytes(ctx, cg, 1, 1) : 0) + 1024;
 }
 
 bool ds_eval_streams_pairs(ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
@@ -1736,7 +1743,13 @@ int ds_prepare_model(ds_ctx* ctx, ds_cgraph* cg) {
   a.score = DS_SCORE_LOGIT;
   hipLaunchKernelGGL(store_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, cg->d_pred, 0);  // a kernel, not a memset node
   a.pred_ptr = cg->d_pred;
-  DS_TRY(launch_eval(ctx, a, lay, 1));
+  // a large graph: one workgroup would walk every entry alone (21 ms for 200k entries); the layer-by-layer kernels
+  // spread the rows of the one coalition over the whole GPU
+  // (where the workspace has the room: the entry point that may not allocate keeps the one-workgroup form)
+  if (prepare_uses_blocks(ctx, cg) && ctx->arena_bytes - ctx->arena_used >= ds_eval_zt_arena_bytes(ctx, cg, 1, 1))
+    DS_TRY(ds_eval_zt(ctx, cg, zfull, 1, DS_SCORE_LOGIT, logits + C, logits, cg->d_pred));
+  else
+    DS_TRY(launch_eval(ctx, a, lay, 1));
   hipLaunchKernelGGL(argmax_kernel, dim3(1), dim3(64), 0, ctx->stream, logits, C, cg->d_pred);
   DS_HIP(ctx, hipGetLastError());
   cg->pred_class = -1;
@@ -1893,7 +1906,7 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
   // blocks of 64 coalitions, from a transposed mask matrix (needs a large workspace: not for the bounded form)
   if (!bounded && (path == 0 || path == 4) && ds_eval_zt_applies(ctx, cg, k)) {
     DS_TRY(ds_kernel_mark(ctx, 0, 0));
-    DS_TRY(ds_eval_zt(ctx, cg, Z, k, score, y));
+    DS_TRY(ds_eval_zt(ctx, cg, Z, k, score, y, nullptr, cg->d_pred));
     return ds_kernel_mark(ctx, 0, 1);
   }
   const size_t avail = ctx->arena_bytes - ctx->arena_used > 512 ? ctx->arena_bytes - ctx->arena_used - 512 : 0;

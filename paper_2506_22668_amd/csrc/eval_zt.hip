@@ -43,6 +43,7 @@ struct ZtArgs {
   float* rs;           // [nblk][V][64]: d^-1/2
   const int32_t* pred_ptr;
   float* y;
+  float* logits_out;   // optional: [k x d_L]
 };
 
 __device__ __forceinline__ float zt_bf16_round(float x) {
@@ -316,6 +317,8 @@ __global__ void zt_readout_kernel(ZtArgs a, const float* cur) {
   for (int c = 0; c < C; ++c) sum += expf(lg[(size_t)c * 64] - m);
   const float zc = lg[(size_t)(*a.pred_ptr) * 64];
   a.y[row] = a.score == DS_SCORE_LOGIT ? zc : expf(zc - m) / sum;
+  if (a.logits_out)
+    for (int c = 0; c < C; ++c) a.logits_out[row * C + c] = lg[(size_t)c * 64];
 }
 
 struct ZtPlan {
@@ -328,12 +331,12 @@ struct ZtPlan {
 constexpr size_t kZtMaxTransposed = (size_t)16 << 30;  // the transposed mask matrix may take this much
 constexpr size_t kZtScratch = (size_t)6 << 30;         // per-launch operands of the blocks in flight
 
-ZtPlan zt_plan(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
+ZtPlan zt_plan(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows) {
   ZtPlan p;
   memset(&p, 0, sizeof(p));
   const int64_t n = cg->info.num_players, V = cg->info.num_nodes;
   const int L = ctx->L;
-  if (n < 1 || k < 256 || L < 1 || ctx->model_kind != DS_MODEL_GCN) return p;
+  if (n < 1 || k < min_rows || L < 1 || ctx->model_kind != DS_MODEL_GCN) return p;
   p.blocks = (k + 63) / 64;
   p.npad = (n + 63) / 64 * 64;
   if ((size_t)p.blocks * p.npad * 8 > kZtMaxTransposed) return p;
@@ -372,18 +375,21 @@ int64_t grid_for_waves(const ds_ctx* ctx, int64_t tasks) {
 
 }  // namespace
 
-bool ds_eval_zt_applies(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) { return zt_plan(ctx, cg, k).use; }
+// (a block of 64 coalitions is the unit of work: with fewer than min_rows rows the other kernels are the better choice,
+// except for the single evaluation of a large graph, where one workgroup would walk every entry alone)
+bool ds_eval_zt_applies(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows) { return zt_plan(ctx, cg, k, min_rows).use; }
 
-size_t ds_eval_zt_arena_bytes(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k) {
-  const ZtPlan p = zt_plan(ctx, cg, k);
+size_t ds_eval_zt_arena_bytes(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows) {
+  const ZtPlan p = zt_plan(ctx, cg, k, min_rows);
   if (!p.use) return 0;
   return ds_align((size_t)p.blocks * p.npad * 8) + ds_align((size_t)p.rs_f * 4 * p.chunk) + ds_align((size_t)p.a_f * 4 * p.chunk) +
          ds_align((size_t)p.b_f * 4 * p.chunk + 256) + ds_align((size_t)p.q_f * 4 * p.chunk + 256) + 1024;
 }
 
 // The model must be prepared (P and the predicted class on the device); temporaries come from the context's arena.
-int ds_eval_zt(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y) {
-  const ZtPlan p = zt_plan(ctx, cg, k);
+int ds_eval_zt(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y, float* logits_out,
+               const int32_t* pred_ptr) {
+  const ZtPlan p = zt_plan(ctx, cg, k, 1);
   if (!p.use) return ds_fail(ctx, DS_EINTERNAL, "eval: the block-transposed path does not apply");
   const int64_t n = cg->info.num_players, W = (n + 63) / 64;
   uint64_t* T = (uint64_t*)ds_arena_alloc(ctx, (size_t)p.blocks * p.npad * 8);
@@ -415,8 +421,9 @@ int ds_eval_zt(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int sco
   a.npad = p.npad;
   a.k = k;
   a.rs = rs;
-  a.pred_ptr = cg->d_pred;
+  a.pred_ptr = pred_ptr;
   a.y = y;
+  a.logits_out = logits_out;
   for (int64_t b0 = 0; b0 < p.blocks; b0 += p.chunk) {
     a.blk0 = b0;
     a.nblk = (int32_t)(p.blocks - b0 < p.chunk ? p.blocks - b0 : p.chunk);

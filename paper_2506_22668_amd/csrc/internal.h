@@ -183,9 +183,11 @@ void* ds_static_scratch(int device);
 size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
 // masked GCN inference layer by layer over blocks of 64 coalitions from a block-transposed mask matrix (graphs whose
 // first layer reads too many entries for the on-chip kernels); the model must be prepared
-bool ds_eval_zt_applies(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
-size_t ds_eval_zt_arena_bytes(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
-int ds_eval_zt(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y);
+bool ds_eval_zt_applies(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows = 256);
+size_t ds_eval_zt_arena_bytes(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows = 256);
+// logits_out: optional [k x d_L]; pred_ptr: device, the class whose score goes to y
+int ds_eval_zt(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y, float* logits_out,
+               const int32_t* pred_ptr);
 // width of the shared first transform P = X_c W_1
 static inline int32_t ds_first_width(const ds_ctx* ctx) {
   if (ctx->L < 1) return 0;
