@@ -13,11 +13,13 @@ torch = pytest.importorskip("torch")
 SOLVERS = {"gram_chol": 1, "cgls": 2}
 
 
-def _explain_case(key, tol, solver=None, oracle_solver="lstsq", targets=None):
-    from paper_2506_22668_amd import Options
+def _explain_case(key, tol, solver=None, oracle_solver="lstsq", targets=None, eval_path=0):
+    from paper_2506_22668_amd import Options, Tuning
     w = make_workload(key)
     dtype = 1 if w.transform_dtype == "bf16" else 0
     ctx = make_context(w, transform_dtype=dtype)
+    if eval_path:
+        ctx.set_tuning(Tuning(eval_path=eval_path))
     opts = Options(solver=SOLVERS[solver or w.solver], tol=w.tol)
     for target in (targets or w.targets):
         say(f"explain {key} target={target}")
@@ -108,6 +110,13 @@ def test_long_row_kernels_inside_an_explanation_with_and_without_player_lists():
     say(f"  n={ref['n']} k={ref['k']} max|phi|={scale:.3e} err={err:.3e}")
     assert err <= 1e-4 * scale
     ctx.close()
+
+
+def test_layer_by_layer_block_kernels_inside_explanations():
+    """The inference that goes layer by layer over blocks of 64 coalitions (transposed mask matrix), forced on reduced
+    configs it would not be chosen for: fp32 with CGLS, and the bfloat16 transforms of the batched config (one target)."""
+    _explain_case("c3_small", 1e-4, oracle_solver="cgls", eval_path=4)
+    _explain_case("c5_small", 1e-2, targets=make_workload("c5_small").targets[:1], eval_path=4)
 
 
 def test_underdetermined_config_direct_solver_reports_and_auto_falls_back():
