@@ -413,14 +413,22 @@ __global__ __launch_bounds__(kFastThreads) void sample_pairs_fast_kernel(SampleA
           for (int i = 0; i < 8; ++i) {
             uint32_t key[4];
             philox4x32_10((uint32_t)(d * 8 + i), r_lo, r_hi, a.tag, a.seed_lo, a.seed_hi, key);
+            // the common case without a branch per key: a key below the window shifts a one into the word (first column
+            // ends up in the top bit: reversed once at the end); key - k_lo <= width (unsigned: a key below k_lo wraps
+            // to more than width, because k_lo + width < 2^32) marks a key inside the window, and the four tests of a
+            // generator call share one branch
+            bool in_window = false;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-              const uint32_t off = key[c] - k_lo;
-              if (key[c] < k_lo) {
-                word |= 1u << (4 * i + c);
-              } else if (off <= width) {
+              word = (word << 1) | (key[c] < k_lo ? 1u : 0u);
+              in_window |= key[c] - k_lo <= width;
+            }
+            if (in_window) {
+#pragma unroll
+              for (int c = 0; c < 4; ++c) {
+                const uint32_t off = key[c] - k_lo;
                 const int64_t col = c0 + 4 * i + c;
-                if (col < n) {
+                if (off <= width && col < n) {
                   atomicAdd(&whist[off >> shift], 1u);
                   const uint32_t pos = atomicAdd(&window_count, 1u);
                   if (pos < wcap) window[pos] = ((unsigned long long)key[c] << 32) | (uint32_t)col;
@@ -428,6 +436,7 @@ __global__ __launch_bounds__(kFastThreads) void sample_pairs_fast_kernel(SampleA
               }
             }
           }
+          word = __brev(word);
           word &= valid;
           below += __popc(word);
         }
