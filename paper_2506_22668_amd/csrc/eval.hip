@@ -352,7 +352,12 @@ __global__ __launch_bounds__(kThreads) void masked_gcn_eval_kernel(EvalArgs a) {
 // meet at barriers between the stages.
 constexpr int kBW = 32;        // mask words per coalition held in LDS (at least; more for wider masks, see the layout)
 constexpr int kBWMax = 192;    // ... up to this many (12,288 players) when the rest of the LDS budget allows
-constexpr int kStageRows = 4;  // entries per matrix-core batch; also sizes the shared weight buffer
+constexpr int kWBufFloats = 4096;  // the workgroup's staging buffer in LDS: weight-matrix chunks of the dense transforms, and
+                                   // the 64 x 64 tile in which the waves add up a shared row of layer 1
+// entries per matrix-core batch of layer 1: short rows (graphs whose masks fit on chip: 15 entries a row on the
+// 1,010-player config) lose less to a partly filled batch with two (0.34 -> 0.27 ms there); the long shared rows of the
+// external-input mode want four entries' loads in flight (8: 14.9 ms, 4: 14.1 ms, 2: 16.2 ms on the 10^6-player config)
+template <bool EXT> constexpr int stage_rows() { return EXT ? 4 : 2; }
 constexpr int kBThreads = 1024; // sixteen waves share the 64 coalitions of a workgroup: the stages are latency chains per
                                 // wave, and only one workgroup fits a CU's LDS, so more waves per workgroup shorten them
                                 // (measured against eight waves: 0.39 -> 0.32 ms on 1,010 players, 4.1 -> 2.4 ms on 9,647)
@@ -413,7 +418,7 @@ __device__ const float zero_bias[4096] = {};
 __device__ __forceinline__ void transform_coalitions(const float* qall, float* nxt, float* Ws, const float* Wg,
                                                   const float* bias, int rows, int din, int dout, bool relu, bool isbf) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int cap = kBWaves * kStageRows * 64;
+  const int cap = kWBufFloats;
   int FB = cap / dout;
   if (FB > din) FB = din;
   if (FB < din && FB > 8) FB &= ~7;  // whole matrix-core steps per chunk
@@ -493,15 +498,18 @@ __device__ __forceinline__ void transform_coalitions(const float* qall, float* n
 
 constexpr int kSharedRow = 256;  // a row with more entries than this is shared by all waves of the workgroup
 
-template <bool DEG_LDS, bool CSR_LDS, bool EXT>
+// PAIRED (external inputs only): the records are complementary pairs and the first layer's coefficients are formed by
+// the lanes that feed them to the matrix cores (see there)
+template <bool DEG_LDS, bool CSR_LDS, bool EXT, bool PAIRED = false>
 __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(BatchedArgs b) {
   const EvalArgs& a = b.e;
+  constexpr int kStageRows = stage_rows<EXT>();
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  // LDS: zs[zs_words][64] u64 | weight-matrix buffer f32[waves*16*64] | deg[V][64] u16 (optional) | local CSR (optional)
+  // LDS: zs[zs_words][64] u64 | staging buffer f32[4096] | deg[V][64] u16 (optional) | local CSR (optional)
   uint64_t* zs = (uint64_t*)smem_raw;
   const uint32_t* ebs = (const uint32_t*)smem_raw;  // EXT: entry bits as ebs[word][lane]
   float* stage_all = (float*)(smem_raw + (size_t)b.zs_words * 64 * 8);
-  unsigned short* degs = (unsigned short*)(smem_raw + (size_t)b.zs_words * 64 * 8 + kBWaves * kStageRows * 64 * 4);
+  unsigned short* degs = (unsigned short*)(smem_raw + (size_t)b.zs_words * 64 * 8 + kWBufFloats * 4);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t *g_rp = a.row_ptr, *g_col = a.col, *g_eid = a.eid;
   if (CSR_LDS) {  // the graph structure is read many times per coalition block: keep it on chip
@@ -656,6 +664,66 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
               av[q][0] = (ok && f0 + l32 < d1) ? pr[0] : 0.f;
               av[q][1] = (ok && f0 + 32 + l32 < d1) ? pr[32] : 0.f;
             }
+            if (EXT && PAIRED) {
+              // Lane (half, j) feeds the matrix cores the coefficients of entry 2q + half for coalition j (the stored
+              // member of pair j) and coalition 32 + j (its complement): both come from one degree of the source and one
+              // bit of the member's row, which this lane reads itself -- no value crosses lanes, and an entry costs one
+              // degree load for the pair instead of one per member.
+              float b0v[kStageRows / 2], b1v[kStageRows / 2];
+#pragma unroll
+              for (int q = 0; q < kStageRows / 2; ++q) {
+                const int ei = 2 * q + half;
+                const int p = half ? readlane_i(pv, 2 * q + 1) : readlane_i(pv, 2 * q);
+                const int src = half ? readlane_i(sv, 2 * q + 1) : readlane_i(sv, 2 * q);
+                const bool ok = ei < cnt, self = eb + ei == e1;
+                const bool bit = (ebs[(p >> 5) * 64 + l32] >> (p & 31)) & 1u;
+                const int d = ext_deg_lane[(size_t)src << b.ext_lr];
+                const int f = (int)b.fdeg2[src];
+                b0v[q] = (ok && (self || bit)) ? __frsqrt_rn((float)d) : 0.f;         // coalitions 0..31: the members
+                b1v[q] = (ok && (self || !bit)) ? __frsqrt_rn((float)(f - d)) : 0.f;  // coalitions 32..63: the complements
+              }
+#pragma unroll
+              for (int q = 0; q < kStageRows / 2; ++q) {
+                if (2 * q < cnt) {
+                  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][0], b0v[q], acc[0][0], 0, 0, 0);
+                  acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][0], b1v[q], acc[0][1], 0, 0, 0);
+                  acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][1], b0v[q], acc[1][0], 0, 0, 0);
+                  acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][1], b1v[q], acc[1][1], 0, 0, 0);
+                }
+              }
+            } else if (!EXT) {
+              // the same without external inputs: lane (half, j) takes the bits of coalitions j and 32 + j from their
+              // mask words and the two degrees from where this kernel keeps them
+              float b0v[kStageRows / 2], b1v[kStageRows / 2];
+#pragma unroll
+              for (int q = 0; q < kStageRows / 2; ++q) {
+                const int ei = 2 * q + half;
+                const int p = half ? readlane_i(pv, 2 * q + 1) : readlane_i(pv, 2 * q);
+                const int src = half ? readlane_i(sv, 2 * q + 1) : readlane_i(sv, 2 * q);
+                const bool ok = ei < cnt, self = eb + ei == e1;
+                const uint64_t* zw = zs + (p >> 6) * 64 + l32;
+                const bool bit0 = (zw[0] >> (p & 63)) & 1ull, bit1 = (zw[32] >> (p & 63)) & 1ull;
+                float r0, r1;
+                if (DEG_LDS) {
+                  r0 = __frsqrt_rn((float)degs[src * 64 + l32]);
+                  r1 = __frsqrt_rn((float)degs[src * 64 + 32 + l32]);
+                } else {
+                  r0 = rs[(size_t)src * 64 + l32];
+                  r1 = rs[(size_t)src * 64 + 32 + l32];
+                }
+                b0v[q] = (ok && (self || bit0)) ? r0 : 0.f;
+                b1v[q] = (ok && (self || bit1)) ? r1 : 0.f;
+              }
+#pragma unroll
+              for (int q = 0; q < kStageRows / 2; ++q) {
+                if (2 * q < cnt) {
+                  acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][0], b0v[q], acc[0][0], 0, 0, 0);
+                  acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][0], b1v[q], acc[0][1], 0, 0, 0);
+                  acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][1], b0v[q], acc[1][0], 0, 0, 0);
+                  acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][1], b1v[q], acc[1][1], 0, 0, 0);
+                }
+              }
+            } else {
             float coef[kStageRows];
 #pragma unroll
             for (int i = 0; i < kStageRows; ++i) {
@@ -679,6 +747,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
                 acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][1], b0, acc[1][0], 0, 0, 0);
                 acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q][1], b1, acc[1][1], 0, 0, 0);
               }
+            }
             }
           }
           // accumulator register i of lane l is D[feature 8*(i/4) + 4*(l/32) + i%4][coalition l%32]
@@ -1533,7 +1602,7 @@ BatchedLayout make_batched_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_
   if (!bl.use) return bl;
   bl.zs_words = (int)(Wn > kBW ? Wn : kBW);
   batched_buffers(ctx, cg, &bl);
-  const size_t fixed = (size_t)bl.zs_words * 64 * 8 + (size_t)kBWaves * kStageRows * 64 * 4;
+  const size_t fixed = (size_t)bl.zs_words * 64 * 8 + (size_t)kWBufFloats * 4;
   bl.deg_lds = cg->info.num_nodes <= kDegLdsMaxNodes && fixed + (size_t)cg->info.num_nodes * 64 * 2 + 16 <= kLdsLimit;
   bl.rs_floats = bl.deg_lds ? 0 : cg->info.num_nodes * 64;
   bl.lds_bytes = fixed + (bl.deg_lds ? (size_t)cg->info.num_nodes * 64 * 2 : 0);
@@ -1570,7 +1639,7 @@ BatchedLayout make_stream_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t
   bl.eb_words = (int)((E_need + 63) / 64 * 2);  // whole 64-entry groups (one ballot each)
   if (bl.eb_words < 2) bl.eb_words = 2;
   bl.zs_words = bl.eb_words / 2;
-  bl.lds_bytes = (size_t)bl.zs_words * 64 * 8 + (size_t)kBWaves * kStageRows * 64 * 4;
+  bl.lds_bytes = (size_t)bl.zs_words * 64 * 8 + (size_t)kWBufFloats * 4;
   if (bl.lds_bytes > kLdsLimit) return bl;
   // the streaming kernel: R = 8 rows per workgroup if their packed 16-bit counters fit LDS, else 4 or 2
   bl.stream_lr = 3;
@@ -1610,21 +1679,17 @@ size_t stream_bytes(const BatchedLayout& bl, const ds_cgraph* cg) {
 
 template <bool EXT>
 int launch_batched(ds_ctx* ctx, const BatchedLayout& bl, const BatchedArgs& b, int grid) {
-  const void* fn;
-  if (bl.deg_lds && bl.csr_lds) fn = (const void*)masked_gcn_eval_batched_kernel<true, true, EXT>;
-  else if (bl.deg_lds) fn = (const void*)masked_gcn_eval_batched_kernel<true, false, EXT>;
-  else if (bl.csr_lds) fn = (const void*)masked_gcn_eval_batched_kernel<false, true, EXT>;
-  else fn = (const void*)masked_gcn_eval_batched_kernel<false, false, EXT>;
+  void (*kern)(BatchedArgs);
+  if (EXT) {  // (external inputs: neither the degrees nor the local CSR are kept in LDS)
+    kern = b.ext_paired ? masked_gcn_eval_batched_kernel<false, false, EXT, EXT> : masked_gcn_eval_batched_kernel<false, false, EXT, false>;
+  } else if (bl.deg_lds && bl.csr_lds) kern = masked_gcn_eval_batched_kernel<true, true, false>;
+  else if (bl.deg_lds) kern = masked_gcn_eval_batched_kernel<true, false, false>;
+  else if (bl.csr_lds) kern = masked_gcn_eval_batched_kernel<false, true, false>;
+  else kern = masked_gcn_eval_batched_kernel<false, false, false>;
+  if (EXT && (bl.deg_lds || bl.csr_lds)) return ds_fail(ctx, DS_EINTERNAL, "eval: external inputs with on-chip degrees or CSR");
   if (bl.lds_bytes > 48 * 1024)
-    DS_HIP(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bl.lds_bytes));
-  if (bl.deg_lds && bl.csr_lds)
-    hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, true, EXT>), dim3(grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
-  else if (bl.deg_lds)
-    hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<true, false, EXT>), dim3(grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
-  else if (bl.csr_lds)
-    hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, true, EXT>), dim3(grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
-  else
-    hipLaunchKernelGGL((masked_gcn_eval_batched_kernel<false, false, EXT>), dim3(grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+    DS_HIP(ctx, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bl.lds_bytes));
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }
