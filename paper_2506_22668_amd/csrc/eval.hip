@@ -358,17 +358,19 @@ constexpr int kWBufFloats = 4096;  // the workgroup's staging buffer in LDS: wei
 // 1,010-player config) lose less to a partly filled batch with two (0.34 -> 0.27 ms there); the long shared rows of the
 // external-input mode want four entries' loads in flight (8: 14.9 ms, 4: 14.1 ms, 2: 16.2 ms on the 10^6-player config)
 template <bool EXT> constexpr int stage_rows() { return EXT ? 4 : 2; }
-constexpr int kBThreads = 1024; // sixteen waves share the 64 coalitions of a workgroup: the stages are latency chains per
-                                // wave, and only one workgroup fits a CU's LDS, so more waves per workgroup shorten them
-                                // (measured against eight waves: 0.39 -> 0.32 ms on 1,010 players, 4.1 -> 2.4 ms on 9,647)
-constexpr int kBWaves = kBThreads / 64;
+// Waves that share the 64 coalitions of a workgroup. Only one workgroup fits a compute unit's LDS and the stages are
+// latency chains per wave, so with the masks on chip sixteen waves shorten them (against eight: 0.39 -> 0.32 ms on 1,010
+// players, 4.1 -> 2.4 ms on 9,647). With external inputs the time is the long shared rows of layer 1, whose loop holds 64
+// accumulator registers: sixteen waves leave a wave 128 registers and the loop spills; eight waves keep it in
+// registers (config 4: 14.1 -> 13.1 ms).
+template <bool EXT> constexpr int batched_threads() { return EXT ? 512 : 1024; }
 constexpr int kDegLdsMaxNodes = 640;  // degrees as u16[V][64] in LDS up to this many nodes (80 KB)
 
 struct BatchedArgs {
   EvalArgs e;
   float* scratch;          // per workgroup: rs[V][64] (if not in LDS) | bufA | bufB | q[waves][dmax][64]
   int64_t scratch_stride;  // floats per workgroup
-  int64_t rs_floats, a_floats, b_floats, q_floats;  // region sizes (floats, already x64); then kBWaves x 64 x 64
+  int64_t rs_floats, a_floats, b_floats, q_floats;  // region sizes (floats, already x64); then waves x 64 x 64
                                                     // floats of partial sums (rows shared by all waves)
   int32_t csr_lds_offset;  // byte offset of the LDS copy of the local CSR (if used)
   int32_t zs_words;        // mask words per coalition reserved in LDS (>= W)
@@ -415,8 +417,10 @@ __device__ const float zero_bias[4096] = {};
 // q[t][f + l/32][c0 + l%32], a coalesced load in the [row][feature][coalition] layout. In the bf16
 // configuration both operands are already rounded to bfloat16 (q where the aggregation stored it, W where it is
 // staged) and v_mfma_f32_32x32x8bf16_1k accumulates in fp32.
+template <int kBThreads>
 __device__ __forceinline__ void transform_coalitions(const float* qall, float* nxt, float* Ws, const float* Wg,
                                                   const float* bias, int rows, int din, int dout, bool relu, bool isbf) {
+  constexpr int kBWaves = kBThreads / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int cap = kWBufFloats;
   int FB = cap / dout;
@@ -501,8 +505,9 @@ constexpr int kSharedRow = 256;  // a row with more entries than this is shared 
 // PAIRED (external inputs only): the records are complementary pairs and the first layer's coefficients are formed by
 // the lanes that feed them to the matrix cores (see there)
 template <bool DEG_LDS, bool CSR_LDS, bool EXT, bool PAIRED = false>
-__global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(BatchedArgs b) {
+__global__ __launch_bounds__(batched_threads<EXT>()) void masked_gcn_eval_batched_kernel(BatchedArgs b) {
   const EvalArgs& a = b.e;
+  constexpr int kBThreads = batched_threads<EXT>(), kBWaves = kBThreads / 64;
   constexpr int kStageRows = stage_rows<EXT>();
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   // LDS: zs[zs_words][64] u64 | staging buffer f32[4096] | deg[V][64] u16 (optional) | local CSR (optional)
@@ -845,7 +850,7 @@ __global__ __launch_bounds__(kBThreads) void masked_gcn_eval_batched_kernel(Batc
           }
       }
       __syncthreads();
-      transform_coalitions(qall, nxt, stage_all, a.Wl[l - 1], a.bias[l - 1], rows, din, dout, relu, a.bf16 != 0);
+      transform_coalitions<kBThreads>(qall, nxt, stage_all, a.Wl[l - 1], a.bias[l - 1], rows, din, dout, relu, a.bf16 != 0);
       __syncthreads();
       float* tmp = cur; cur = nxt; nxt = tmp;
     }
@@ -1689,7 +1694,7 @@ int launch_batched(ds_ctx* ctx, const BatchedLayout& bl, const BatchedArgs& b, i
   if (EXT && (bl.deg_lds || bl.csr_lds)) return ds_fail(ctx, DS_EINTERNAL, "eval: external inputs with on-chip degrees or CSR");
   if (bl.lds_bytes > 48 * 1024)
     DS_HIP(ctx, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bl.lds_bytes));
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBThreads), bl.lds_bytes, ctx->stream, b);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(batched_threads<EXT>()), bl.lds_bytes, ctx->stream, b);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }
