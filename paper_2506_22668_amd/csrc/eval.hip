@@ -650,6 +650,60 @@ __global__ __launch_bounds__(batched_threads<EXT>()) void masked_gcn_eval_batche
             pv_next = key_[s0 + lane];
             sv_next = col_[s0 + lane];
           }
+          if (EXT && PAIRED && shared) {
+            // A shared row's part, two steps deep: the keys of step j + 2 and the operands of step j + 1 (rows of P, the
+            // pair's degree, the source's full degree) are requested before the matrix cores get step j. Every load of the
+            // loop is issued unconditionally (indices clamped into the row, which has more than kSharedRow entries), so
+            // that the wait before a step's operands is a count of younger loads and not a wait for all of them.
+            struct Ops {
+              float av[kStageRows / 2][2];
+              int d[kStageRows / 2], f[kStageRows / 2], p[kStageRows / 2];
+            };
+            auto load_keys = [&](int eb, int& pk, int& sk) {
+              const int e = eb + (lane < kStageRows ? lane : 0);
+              const bool real = e < s1 && e < e1;
+              const int ec = real ? e : e1 - 1;
+              const int k_ = key_[ec], c_ = col_[ec];
+              pk = real ? k_ : 0;
+              sk = real ? c_ : t;
+            };
+            auto load_ops = [&](Ops& o, int pk, int sk) {
+#pragma unroll
+              for (int q = 0; q < kStageRows / 2; ++q) {
+                const int src = half ? readlane_i(sk, 2 * q + 1) : readlane_i(sk, 2 * q);
+                o.p[q] = half ? readlane_i(pk, 2 * q + 1) : readlane_i(pk, 2 * q);
+                const float* pr = a.P + (size_t)src * d1 + f0;
+                o.av[q][0] = pr[f0 + l32 < d1 ? l32 : 0];
+                o.av[q][1] = pr[f0 + 32 + l32 < d1 ? 32 + l32 : 0];
+                o.d[q] = ext_deg_lane[(size_t)src << b.ext_lr];
+                o.f[q] = (int)b.fdeg2[src];
+              }
+            };
+            const bool fok0 = f0 + l32 < d1, fok1 = f0 + 32 + l32 < d1;
+            Ops cur, nxt;
+            int pk1, sk1;
+            load_ops(cur, pv_next, sv_next);
+            load_keys(s0 + kStageRows, pk1, sk1);
+            for (int eb = s0; eb < s1; eb += kStageRows) {
+              const int cnt = s1 - eb < kStageRows ? s1 - eb : kStageRows;
+              load_ops(nxt, pk1, sk1);
+              load_keys(eb + 2 * kStageRows, pk1, sk1);
+#pragma unroll
+              for (int q = 0; q < kStageRows / 2; ++q) {
+                const int ei = 2 * q + half, p = cur.p[q];
+                const bool ok = ei < cnt, self = eb + ei == e1;
+                const bool bit = (ebs[(p >> 5) * 64 + l32] >> (p & 31)) & 1u;
+                const float b0 = (ok && (self || bit)) ? __frsqrt_rn((float)cur.d[q]) : 0.f;              // the members
+                const float b1 = (ok && (self || !bit)) ? __frsqrt_rn((float)(cur.f[q] - cur.d[q])) : 0.f;  // the complements
+                const float a0 = (ok && fok0) ? cur.av[q][0] : 0.f, a1 = (ok && fok1) ? cur.av[q][1] : 0.f;
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+              }
+              cur = nxt;
+            }
+          } else
           for (int eb = s0; eb < s1; eb += kStageRows) {
             const int cnt = s1 - eb < kStageRows ? s1 - eb : kStageRows;
             const int pv = pv_next, sv = sv_next;
