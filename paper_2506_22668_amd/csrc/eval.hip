@@ -650,17 +650,18 @@ __global__ __launch_bounds__(batched_threads<EXT>()) void masked_gcn_eval_batche
             pv_next = key_[s0 + lane];
             sv_next = col_[s0 + lane];
           }
-          if (EXT && PAIRED && shared) {
-            // A shared row's part, two steps deep: the keys of step j + 2 and the operands of step j + 1 (rows of P, the
+          if (EXT && PAIRED && e1 > e0) {
+            // A row's (or, of a shared row, this wave's) entries, two steps deep: the keys of step j + 2 and the operands of step j + 1 (rows of P, the
             // pair's degree, the source's full degree) are requested before the matrix cores get step j. Every load of the
-            // loop is issued unconditionally (indices clamped into the row, which has more than kSharedRow entries), so
+            // loop is issued unconditionally (indices clamped into the row, which has at least one entry), so
             // that the wait before a step's operands is a count of younger loads and not a wait for all of them.
+            constexpr int SRP = 8;   // entries per step here
             struct Ops {
-              float av[kStageRows / 2][2];
-              int d[kStageRows / 2], f[kStageRows / 2], p[kStageRows / 2];
+              float av[SRP / 2][2];
+              int d[SRP / 2], f[SRP / 2], p[SRP / 2];
             };
             auto load_keys = [&](int eb, int& pk, int& sk) {
-              const int e = eb + (lane < kStageRows ? lane : 0);
+              const int e = eb + (lane < SRP ? lane : 0);
               const bool real = e < s1 && e < e1;
               const int ec = real ? e : e1 - 1;
               const int k_ = key_[ec], c_ = col_[ec];
@@ -669,7 +670,7 @@ __global__ __launch_bounds__(batched_threads<EXT>()) void masked_gcn_eval_batche
             };
             auto load_ops = [&](Ops& o, int pk, int sk) {
 #pragma unroll
-              for (int q = 0; q < kStageRows / 2; ++q) {
+              for (int q = 0; q < SRP / 2; ++q) {
                 const int src = half ? readlane_i(sk, 2 * q + 1) : readlane_i(sk, 2 * q);
                 o.p[q] = half ? readlane_i(pk, 2 * q + 1) : readlane_i(pk, 2 * q);
                 const float* pr = a.P + (size_t)src * d1 + f0;
@@ -682,14 +683,15 @@ __global__ __launch_bounds__(batched_threads<EXT>()) void masked_gcn_eval_batche
             const bool fok0 = f0 + l32 < d1, fok1 = f0 + 32 + l32 < d1;
             Ops cur, nxt;
             int pk1, sk1;
-            load_ops(cur, pv_next, sv_next);
-            load_keys(s0 + kStageRows, pk1, sk1);
-            for (int eb = s0; eb < s1; eb += kStageRows) {
-              const int cnt = s1 - eb < kStageRows ? s1 - eb : kStageRows;
+            load_keys(s0, pk1, sk1);
+            load_ops(cur, pk1, sk1);
+            load_keys(s0 + SRP, pk1, sk1);
+            for (int eb = s0; eb < s1; eb += SRP) {
+              const int cnt = s1 - eb < SRP ? s1 - eb : SRP;
               load_ops(nxt, pk1, sk1);
-              load_keys(eb + 2 * kStageRows, pk1, sk1);
+              load_keys(eb + 2 * SRP, pk1, sk1);
 #pragma unroll
-              for (int q = 0; q < kStageRows / 2; ++q) {
+              for (int q = 0; q < SRP / 2; ++q) {
                 const int ei = 2 * q + half, p = cur.p[q];
                 const bool ok = ei < cnt, self = eb + ei == e1;
                 const bool bit = (ebs[(p >> 5) * 64 + l32] >> (p & 31)) & 1u;
