@@ -131,9 +131,12 @@ __global__ __launch_bounds__(kZThreads) void zt_layer1_kernel(ZtArgs a, float* o
             const uint32_t hi = half ? (live1 ? h1 : 0u) : (live0 ? h0 : 0u);
             b0m[s] = (lo >> l32) & 1u;
             b1m[s] = (hi >> l32) & 1u;
-            const float* pr = a.P + (size_t)src * d1 + f0 + l32;
-            av[s][0] = fok0 ? pr[0] : 0.f;
-            av[s][1] = fok1 ? pr[32] : 0.f;
+            // (loads issued unconditionally, a feature past the end reads column 0 and is zeroed: a wait for operands
+            // is then a count of younger loads)
+            const float* pr = a.P + (size_t)src * d1;
+            const float x0 = pr[fok0 ? f0 + l32 : 0], x1 = pr[fok1 ? f0 + 32 + l32 : 0];
+            av[s][0] = fok0 ? x0 : 0.f;
+            av[s][1] = fok1 ? x1 : 0.f;
             const float* rp = rsb + (size_t)src * 64 + l32;
             rv[s][0] = rp[0];
             rv[s][1] = rp[32];
