@@ -149,7 +149,7 @@ def _cgls_config(key, pair_stride, iterations, check_residual):
     # the same number of steps inside a one-shot explanation. There the sampler also writes the sparse small members
     # as player lists and the mask-streaming kernel reads those instead of the bit rows: degrees and entry bits are
     # integers, so y and the iterate must be the very same numbers as from the stages above
-    say(f"{key}: one-shot explain, {iterations} CGLS steps (player lists from the sampler)")
+    say(f"{key}: one-shot explain, {iterations} CGLS steps (with long mask rows: player lists from the sampler)")
     phi3, _, _, rep3, rc3 = ctx.explain(target, w.n_samples, w.seed,
                                         Options(solver=DS_SOLVER_CGLS, tol=1e-300, max_iter=iterations), capacity=n,
                                         want_edges=False, allow_not_converged=True)
@@ -182,6 +182,12 @@ def test_config3_rmat18_100k_players_cgls():
 
 def test_config4_rmat20_1m_players_underdetermined_cgls():
     _cgls_config("c4", pair_stride=4000, iterations=3, check_residual=False)
+
+
+def test_workload_4b_hub_target_block_transposed_inference():
+    """The hub workload at full size (100,428 players, 196,720 of 200,856 entries read by the first layer): the inference
+    is the layer-by-layer path over blocks of 64 coalitions, chosen by size here, not forced."""
+    _cgls_config("c4b", pair_stride=100, iterations=10, check_residual=True)
 
 
 def test_config5_all_64_targets_bf16_gram_cholesky():
