@@ -83,8 +83,10 @@ __global__ __launch_bounds__(kZThreads) void zt_degrees_kernel(ZtArgs a) {
 // entry 2q + l/32 for coalition n (and, for the second accumulator column, coalition 32 + n): a lane reads the
 // degree factors of exactly the two coalitions it feeds and tests their two bits of the entry's word, so no
 // value crosses lanes. Entries are fetched 64 at a time (lane j: entry j's source, word), steps of two entries; the
-// operands of four steps are requested together.
-__global__ __launch_bounds__(kZThreads) void zt_layer1_kernel(ZtArgs a, float* out) {
+// operands of four steps are requested together. Rows are short (20 entries on the hub workload), so a task is mostly
+// the chain row bounds -> entries -> words -> operands: four workgroups a compute unit (the accumulators in ordinary
+// registers, 117 in all) hide it better than two (29 -> 19 ms there).
+__global__ __launch_bounds__(kZThreads, 4) void zt_layer1_kernel(ZtArgs a, float* out) {
   const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
   const int64_t wave = ((int64_t)blockIdx.x * kZThreads + threadIdx.x) >> 6, nwaves = ((int64_t)gridDim.x * kZThreads) >> 6;
   const int d1 = a.dims[1], rows1 = a.rows_out[1];
