@@ -528,13 +528,14 @@ int ds_bit_transpose(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols
   return DS_OK;
 }
 
-int ds_bit_transpose_blocks(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols, int64_t in_stride, uint64_t* out) {
+int ds_bit_transpose_blocks(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols, int64_t in_stride, int64_t row_step,
+                            uint64_t* out) {
   const int64_t Wout = (rows + 63) / 64, Win = (cols + 63) / 64;
   const int64_t tiles_r = (rows + 511) / 512, tiles_c = (Win + 7) / 8;
   if (tiles_r < 1 || tiles_c < 1) return DS_OK;
   if (tiles_r * tiles_c > 0x7fffffffLL) return ds_fail(ctx, DS_EINVAL, "bit matrix too large to transpose");
   hipLaunchKernelGGL(bit_transpose_kernel, dim3((unsigned)(tiles_r * tiles_c)), dim3(kTrThreads), 0, ctx->stream, in, rows, cols,
-                     in_stride, (int64_t)0, (int64_t)1, out, Wout, tiles_c, 1);
+                     in_stride, (int64_t)0, row_step, out, Wout, tiles_c, 1);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }

@@ -2032,7 +2032,7 @@ int ds_eval_impl(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int s
   // blocks of 64 coalitions, from a transposed mask matrix (needs a large workspace: not for the bounded form)
   if (!bounded && (path == 0 || path == 4) && ds_eval_zt_applies(ctx, cg, k)) {
     DS_TRY(ds_kernel_mark(ctx, 0, 0));
-    DS_TRY(ds_eval_zt(ctx, cg, Z, k, score, y, nullptr, cg->d_pred));
+    DS_TRY(ds_eval_zt(ctx, cg, Z, k, score, y, nullptr, cg->d_pred, paired));
     return ds_kernel_mark(ctx, 0, 1);
   }
   const size_t avail = ctx->arena_bytes - ctx->arena_used > 512 ? ctx->arena_bytes - ctx->arena_used - 512 : 0;

@@ -30,6 +30,8 @@ constexpr int kZWaves = kZThreads / 64;
 
 struct ZtArgs {
   int32_t V, L, score, bf16;
+  int32_t paired;      // rows 2r, 2r+1 are complementary: T holds the even rows only, block 2j = the stored members of pairs
+                       // 64j .. 64j+63, block 2j+1 = their complements (the same words inverted)
   int32_t dims[DS_MAX_LAYERS + 1];
   int32_t rows_out[DS_MAX_LAYERS + 1];
   const int32_t *row_ptr, *col, *eid;
@@ -54,6 +56,20 @@ __device__ __forceinline__ float zt_bf16_round(float x) {
 
 __device__ __forceinline__ uint32_t rl(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
 
+// the transposed words of block blk: T row and the mask to XOR onto every word (all ones for a block of complements)
+__device__ __forceinline__ const uint64_t* block_words(const ZtArgs& a, int64_t blk, uint64_t* inv) {
+  if (a.paired) {
+    *inv = (blk & 1) ? ~0ull : 0ull;
+    return a.T + (blk >> 1) * a.npad;
+  }
+  *inv = 0ull;
+  return a.T + blk * a.npad;
+}
+// mask row of lane `lane` of block blk
+__device__ __forceinline__ int64_t block_row(const ZtArgs& a, int64_t blk, int lane) {
+  return a.paired ? 2 * ((blk >> 1) * 64 + lane) + (blk & 1) : blk * 64 + lane;
+}
+
 // d(v)^-1/2 for every node and coalition of the launch's blocks. One wave per (block, node): the lanes fetch the
 // words of up to 64 entries of the row together, then every word is broadcast and each lane adds its own bit.
 __global__ __launch_bounds__(kZThreads) void zt_degrees_kernel(ZtArgs a) {
@@ -64,12 +80,13 @@ __global__ __launch_bounds__(kZThreads) void zt_degrees_kernel(ZtArgs a) {
   for (int64_t task = wave; task < tasks; task += nwaves) {
     const int64_t cbi = task / a.V;
     const int v = (int)(task - cbi * a.V);
-    const uint64_t* Tb = a.T + (a.blk0 + cbi) * a.npad;
+    uint64_t inv;
+    const uint64_t* Tb = block_words(a, a.blk0 + cbi, &inv);
     const int e0 = a.row_ptr[v], e1 = a.row_ptr[v + 1];
     int cnt = 1;
     for (int eb = e0; eb < e1; eb += 64) {
       const int m = e1 - eb < 64 ? e1 - eb : 64;
-      const uint64_t word = lane < m ? Tb[a.eid[eb + lane]] : 0ull;
+      const uint64_t word = lane < m ? Tb[a.eid[eb + lane]] ^ inv : 0ull;
       const uint32_t lo = (uint32_t)word, hi = (uint32_t)(word >> 32);
       for (int i = 0; i < m; ++i) cnt += ((rl(lo, i) & mlo) | (rl(hi, i) & mhi)) ? 1 : 0;
     }
@@ -95,7 +112,8 @@ __global__ __launch_bounds__(kZThreads, 4) void zt_layer1_kernel(ZtArgs a, float
   for (int64_t task = wave; task < tasks; task += nwaves) {
     const int64_t cbi = task / rows1;
     const int t = (int)(task - cbi * rows1);
-    const uint64_t* Tb = a.T + (a.blk0 + cbi) * a.npad;
+    uint64_t inv;
+    const uint64_t* Tb = block_words(a, a.blk0 + cbi, &inv);
     const float* rsb = a.rs + (size_t)cbi * a.V * 64;
     const int e0 = a.row_ptr[t], e1 = a.row_ptr[t + 1];  // entry e1 stands for the self-loop
     const float rst0 = rsb[(size_t)t * 64 + l32], rst1 = rsb[(size_t)t * 64 + 32 + l32];
@@ -113,21 +131,31 @@ __global__ __launch_bounds__(kZThreads, 4) void zt_layer1_kernel(ZtArgs a, float
         uint64_t word = 0ull;
         if (e < e1) {
           sv = a.col[e];
-          word = Tb[a.eid[e]];
+          word = Tb[a.eid[e]] ^ inv;
         } else if (e == e1) {
           word = ~0ull;
         }
         const uint32_t wlo = (uint32_t)word, whi = (uint32_t)(word >> 32);
-        for (int q0 = 0; q0 < m; q0 += 8) {  // four steps of two entries
+        // only entries that are active in some coalition of the block take a step (in a block of sparse stored members
+        // most are not): their lanes are taken from the ballot, eight at a time = four steps of two entries
+        unsigned long long act = __ballot(word != 0ull);
+        while (act) {
+          int il[8];
+          bool live[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            live[j] = act != 0ull;
+            il[j] = live[j] ? __ffsll((long long)act) - 1 : 63;
+            act &= act - 1ull;
+          }
           float av[4][2], rv[4][2];
           uint32_t b0m[4], b1m[4];
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
-            const int i0 = q0 + 2 * s, i1 = i0 + 1;   // (lanes past m hold a zero word and source t)
-            const int il0 = i0 < 64 ? i0 : 63, il1 = i1 < 64 ? i1 : 63;
+            const int il0 = il[2 * s], il1 = il[2 * s + 1];
             const int s0 = (int)rl((uint32_t)sv, il0), s1 = (int)rl((uint32_t)sv, il1);
             const uint32_t l0 = rl(wlo, il0), l1 = rl(wlo, il1), h0 = rl(whi, il0), h1 = rl(whi, il1);
-            const bool live0 = i0 < m, live1 = i1 < m;
+            const bool live0 = live[2 * s], live1 = live[2 * s + 1];
             const int src = half ? s1 : s0;
             const uint32_t lo = half ? (live1 ? l1 : 0u) : (live0 ? l0 : 0u);
             const uint32_t hi = half ? (live1 ? h1 : 0u) : (live0 ? h0 : 0u);
@@ -145,7 +173,7 @@ __global__ __launch_bounds__(kZThreads, 4) void zt_layer1_kernel(ZtArgs a, float
           }
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
-            if (q0 + 2 * s < m) {
+            if (live[2 * s]) {
               const float b0 = b0m[s] ? rv[s][0] : 0.f, b1 = b1m[s] ? rv[s][1] : 0.f;
               acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][0], b0, acc[0][0], 0, 0, 0);
               acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][0], b1, acc[0][1], 0, 0, 0);
@@ -190,7 +218,8 @@ __global__ __launch_bounds__(kZThreads) void zt_aggregate_kernel(ZtArgs a, int l
     const int64_t cbi = task / ((int64_t)rows * fch);
     const int rem = (int)(task - cbi * rows * fch);
     const int t = rem / fch, f0 = (rem - t * fch) * 16;
-    const uint64_t* Tb = a.T + (a.blk0 + cbi) * a.npad;
+    uint64_t inv;
+    const uint64_t* Tb = block_words(a, a.blk0 + cbi, &inv);
     const float* rsb = a.rs + (size_t)cbi * a.V * 64;
     const float* hb = cur + (size_t)cbi * rows_prev * din * 64 + (size_t)f0 * 64 + lane;
     const int e0 = a.row_ptr[t], e1 = a.row_ptr[t + 1];  // entry e1 stands for the self-loop
@@ -205,19 +234,23 @@ __global__ __launch_bounds__(kZThreads) void zt_aggregate_kernel(ZtArgs a, int l
       uint64_t word = 0ull;
       if (e < e1) {
         sv = a.col[e];
-        word = Tb[a.eid[e]];
+        word = Tb[a.eid[e]] ^ inv;
       } else if (e == e1) {
         word = ~0ull;
       }
       const uint32_t wlo = (uint32_t)word, whi = (uint32_t)(word >> 32);
-      for (int i0 = 0; i0 < m; i0 += 4) {
+      // only the entries that are active in some coalition of the block are visited, four at a time
+      unsigned long long act = __ballot(word != 0ull);
+      while (act) {
         float c[4];
         const float* hp[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int i = i0 + u < 64 ? i0 + u : 63;
+          const bool live = act != 0ull;
+          const int i = live ? __ffsll((long long)act) - 1 : 63;
+          act &= act - 1ull;
           const int src = (int)rl((uint32_t)sv, i);
-          const bool on = i0 + u < m && ((rl(wlo, i) & mlo) | (rl(whi, i) & mhi)) != 0u;
+          const bool on = live && ((rl(wlo, i) & mlo) | (rl(whi, i) & mhi)) != 0u;
           c[u] = on ? rsb[(size_t)src * 64 + lane] : 0.f;
           hp[u] = hb + (size_t)src * din * 64;
         }
@@ -312,7 +345,7 @@ __global__ void zt_readout_kernel(ZtArgs a, const float* cur) {
   if (i >= (int64_t)a.nblk * 64) return;
   const int64_t cbi = i >> 6;
   const int lane = (int)(i & 63);
-  const int64_t row = (a.blk0 + cbi) * 64 + lane;
+  const int64_t row = block_row(a, a.blk0 + cbi, lane);
   if (row >= a.k) return;
   const int C = a.dims[a.L], rowsL = a.rows_out[a.L];
   const float* lg = cur + (size_t)cbi * rowsL * C * 64 + lane;
@@ -328,7 +361,7 @@ __global__ void zt_readout_kernel(ZtArgs a, const float* cur) {
 
 struct ZtPlan {
   bool use;
-  int64_t blocks, npad, chunk;        // blocks of 64 coalitions, padded players, blocks per launch
+  int64_t blocks, tblocks, npad, chunk;   // blocks of 64 coalitions, blocks of the transposed matrix, padded players, blocks per launch
   int64_t rs_f, a_f, b_f, q_f;        // floats per block of the four scratch regions
   int32_t rows_out[DS_MAX_LAYERS + 1];
 };
@@ -336,15 +369,16 @@ struct ZtPlan {
 constexpr size_t kZtMaxTransposed = (size_t)16 << 30;  // the transposed mask matrix may take this much
 constexpr size_t kZtScratch = (size_t)6 << 30;         // per-launch operands of the blocks in flight
 
-ZtPlan zt_plan(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows) {
+ZtPlan zt_plan(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows, int paired) {
   ZtPlan p;
   memset(&p, 0, sizeof(p));
   const int64_t n = cg->info.num_players, V = cg->info.num_nodes;
   const int L = ctx->L;
   if (n < 1 || k < min_rows || L < 1 || ctx->model_kind != DS_MODEL_GCN) return p;
-  p.blocks = (k + 63) / 64;
+  p.tblocks = paired ? (k / 2 + 63) / 64 : (k + 63) / 64;   // blocks of 64 transposed rows
+  p.blocks = paired ? 2 * p.tblocks : p.tblocks;
   p.npad = (n + 63) / 64 * 64;
-  if ((size_t)p.blocks * p.npad * 8 > kZtMaxTransposed) return p;
+  if ((size_t)p.tblocks * p.npad * 8 > kZtMaxTransposed) return p;
   p.rows_out[0] = 0;
   for (int l = 1; l <= L; ++l) {
     int h = L - l;
@@ -382,34 +416,39 @@ int64_t grid_for_waves(const ds_ctx* ctx, int64_t tasks) {
 
 // (a block of 64 coalitions is the unit of work: with fewer than min_rows rows the other kernels are the better choice,
 // except for the single evaluation of a large graph, where one workgroup would walk every entry alone)
-bool ds_eval_zt_applies(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows) { return zt_plan(ctx, cg, k, min_rows).use; }
+bool ds_eval_zt_applies(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows) { return zt_plan(ctx, cg, k, min_rows, 0).use; }
 
 size_t ds_eval_zt_arena_bytes(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows) {
-  const ZtPlan p = zt_plan(ctx, cg, k, min_rows);
+  // (the paired form holds half the transposed matrix and may run one block more at a time: room for either)
+  const ZtPlan p = zt_plan(ctx, cg, k, min_rows, 0);
   if (!p.use) return 0;
-  return ds_align((size_t)p.blocks * p.npad * 8) + ds_align((size_t)p.rs_f * 4 * p.chunk) + ds_align((size_t)p.a_f * 4 * p.chunk) +
-         ds_align((size_t)p.b_f * 4 * p.chunk + 256) + ds_align((size_t)p.q_f * 4 * p.chunk + 256) + 1024;
+  const size_t c = (size_t)p.chunk + 1;
+  return ds_align((size_t)p.tblocks * p.npad * 8) + ds_align((size_t)p.rs_f * 4 * c) + ds_align((size_t)p.a_f * 4 * c) +
+         ds_align((size_t)p.b_f * 4 * c + 256) + ds_align((size_t)p.q_f * 4 * c + 256) + 1024;
 }
 
 // The model must be prepared (P and the predicted class on the device); temporaries come from the context's arena.
 int ds_eval_zt(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y, float* logits_out,
-               const int32_t* pred_ptr) {
-  const ZtPlan p = zt_plan(ctx, cg, k, 1);
+               const int32_t* pred_ptr, int paired) {
+  paired = paired && (k & 1) == 0 && k >= 2;
+  const ZtPlan p = zt_plan(ctx, cg, k, 1, paired);
   if (!p.use) return ds_fail(ctx, DS_EINTERNAL, "eval: the block-transposed path does not apply");
   const int64_t n = cg->info.num_players, W = (n + 63) / 64;
-  uint64_t* T = (uint64_t*)ds_arena_alloc(ctx, (size_t)p.blocks * p.npad * 8);
+  uint64_t* T = (uint64_t*)ds_arena_alloc(ctx, (size_t)p.tblocks * p.npad * 8);
   float* rs = (float*)ds_arena_alloc(ctx, (size_t)p.rs_f * 4 * p.chunk);
   float* bufA = (float*)ds_arena_alloc(ctx, (size_t)p.a_f * 4 * p.chunk);
   float* bufB = (float*)ds_arena_alloc(ctx, (size_t)p.b_f * 4 * p.chunk + 256);
   float* q = (float*)ds_arena_alloc(ctx, (size_t)p.q_f * 4 * p.chunk + 256);
   if (!T || !rs || !bufA || !bufB || !q) return ds_fail(ctx, DS_EINTERNAL, "eval: arena exhausted");
-  DS_TRY(ds_bit_transpose_blocks(ctx, Z, k, n, W, T));
+  // (pairs: only the stored members, rows 0, 2, 4, ...)
+  DS_TRY(ds_bit_transpose_blocks(ctx, Z, paired ? k / 2 : k, n, W, paired ? 2 : 1, T));
   ZtArgs a;
   memset(&a, 0, sizeof(a));
   a.V = (int32_t)cg->info.num_nodes;
   a.L = ctx->L;
   a.score = score;
   a.bf16 = ctx->transform_dtype == DS_BF16_IN_F32_ACC;
+  a.paired = paired;
   for (int i = 0; i <= ctx->L; ++i) {
     a.dims[i] = ctx->dims[i];
     a.rows_out[i] = p.rows_out[i];

@@ -185,9 +185,9 @@ size_t ds_eval_arena_bytes(ds_ctx* ctx, const ds_cgraph* cg, int64_t k);
 // first layer reads too many entries for the on-chip kernels); the model must be prepared
 bool ds_eval_zt_applies(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows = 256);
 size_t ds_eval_zt_arena_bytes(const ds_ctx* ctx, const ds_cgraph* cg, int64_t k, int64_t min_rows = 256);
-// logits_out: optional [k x d_L]; pred_ptr: device, the class whose score goes to y
+// logits_out: optional [k x d_L]; pred_ptr: device, the class whose score goes to y; paired: rows 2r, 2r+1 are complements
 int ds_eval_zt(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int score, float* y, float* logits_out,
-               const int32_t* pred_ptr);
+               const int32_t* pred_ptr, int paired = 0);
 // width of the shared first transform P = X_c W_1
 static inline int32_t ds_first_width(const ds_ctx* ctx) {
   if (ctx->L < 1) return 0;

@@ -9,9 +9,10 @@ int ds_row_prep(ds_ctx* ctx, const uint64_t* Z, int64_t k, int64_t n, const floa
 // out[cols x ceil(rows/64)] = transpose of the rows row_first + i*row_step (i < rows) of `in`
 int ds_bit_transpose(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols, int64_t in_stride, int64_t row_first,
                      int64_t row_step, uint64_t* out);
-// the same transpose laid out by blocks of 64 rows: out[b * 64*ceil(cols/64) + j] = bits of column j in rows 64b .. 64b+63
-// (rows past the last and columns past `cols` read as zero)
-int ds_bit_transpose_blocks(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols, int64_t in_stride, uint64_t* out);
+// the same transpose of the rows i * row_step (i < rows), laid out by blocks of 64 of them: out[b * 64*ceil(cols/64) + j] =
+// bits of column j in the rows 64b .. 64b+63 of that selection (rows past the last and columns past `cols` read as zero)
+int ds_bit_transpose_blocks(ds_ctx* ctx, const uint64_t* in, int64_t rows, int64_t cols, int64_t in_stride, int64_t row_step,
+                            uint64_t* out);
 // out[i] = sum of x[j] over the set bits j < cols of row (row_first + i*row_step) of B, i < rows (fp64)
 int ds_bit_spmv(ds_ctx* ctx, const uint64_t* B, int64_t rows, int64_t cols, int64_t stride, int64_t row_first,
                 int64_t row_step, const double* x, double* out);
