@@ -175,165 +175,162 @@ __global__ __launch_bounds__(kZThreads, 4) void zt_layer1_kernel(ZtArgs a, float
           for (int s = 0; s < 4; ++s) {
             if (live[2 * s]) {
               const float b0 = b0m[s] ? rv[s][0] : 0.f, b1 = b1m[s] ? rv[s][1] : 0.f;
-              acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][0], b0, acc[0][0], 0, 0, 0);
-              acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][0], b1, acc[0][1], 0, 0, 0);
-              acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][1], b0, acc[1][0], 0, 0, 0);
-              acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][1], b1, acc[1][1], 0, 0, 0);
+              // (coefficients as the A operand, rows of P as B: the accumulator is [coalition][feature])
+              acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(b0, av[s][0], acc[0][0], 0, 0, 0);
+              acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(b1, av[s][0], acc[0][1], 0, 0, 0);
+              acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(b0, av[s][1], acc[1][0], 0, 0, 0);
+              acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(b1, av[s][1], acc[1][1], 0, 0, 0);
             }
           }
         }
       }
-      // accumulator register i of lane l is D[feature 8*(i/4) + 4*(l/32) + i%4][coalition l%32] (+32 features per ft,
-      // +32 coalitions per nb)
-      float* o = out + (((size_t)cbi * rows1 + t) * d1 + f0 + 4 * half) * 64 + l32;
+      // accumulator register i of lane l of acc[ft][nb] is D[coalition 32*nb + 8*(i/4) + 4*(l/32) + i%4][feature f0 + 32*ft +
+      // l%32]: a store is 128 contiguous bytes of one coalition's row. A layer that another one follows is stored
+      // already multiplied by d_t^-1/2 (the only form the next aggregation uses it in).
 #pragma unroll
-      for (int ft = 0; ft < 2; ++ft)
+      for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int i = 0; i < 16; ++i) {
+          const int c = 32 * nb + 8 * (i / 4) + 4 * half + (i % 4);
+          const float rt = rsb[(size_t)t * 64 + c];
+          float* o = out + (((size_t)cbi * 64 + c) * rows1 + t) * d1 + f0 + l32;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int fo = ft * 32 + 8 * (i / 4) + (i % 4);
-            const int f = f0 + 4 * half + fo;
+          for (int ft = 0; ft < 2; ++ft) {
+            const int f = f0 + 32 * ft + l32;
             if (f < d1) {
-              float v = (nb ? rst1 : rst0) * acc[ft][nb][i];
+              float v = rt * acc[ft][nb][i];
               if (a.bias[0]) v += a.bias[0][f];
-              o[(size_t)fo * 64 + nb * 32] = relu ? fmaxf(v, 0.f) : v;
+              if (relu) v = fmaxf(v, 0.f) * rt;
+              o[32 * ft] = v;
             }
           }
+        }
     }
   }
 }
 
-// Aggregation of a later layer, lane = coalition: q[t][f][c] = d_t^-1/2 ( sum_{active e} d_src^-1/2 H[src][f][c] +
-// d_t^-1/2 H[t][f][c] ). One wave per (block, row, slice of 16 features); the sources and words of up to 64 entries
-// are fetched together, four entries' operands are in flight per step.
-__global__ __launch_bounds__(kZThreads) void zt_aggregate_kernel(ZtArgs a, int l, const float* cur, float* q) {
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = ((int64_t)blockIdx.x * kZThreads + threadIdx.x) >> 6, nwaves = ((int64_t)gridDim.x * kZThreads) >> 6;
-  const uint32_t mlo = lane < 32 ? 1u << lane : 0u, mhi = lane >= 32 ? 1u << (lane - 32) : 0u;
+// Aggregation of a later layer, one wave per (coalition, row t), lanes = features: q[t][f] = d_t^-1/2 ( sum over the
+// ACTIVE entries of H'[src][f] + H'[t][f] ), H' being the previous layer's output times d^-1/2 of its own row (stored that
+// way). Only the coalition's own active entries are visited: the lanes test the bits of 64 entries together and the set
+// ones are walked eight at a time (eight 256-byte row loads in flight). The layer's input of one coalition (rows x d x 4
+// bytes: 2.5 MB on the hub workload) is read by all rows t of that coalition, about sixteen times over; the launch puts
+// the workgroups of a coalition on one XCD (workgroups go to the XCDs round-robin by index) and one row per wave, so
+// that an XCD works on one or two coalitions at a time and those re-reads come from its L2.
+__global__ __launch_bounds__(kZThreads) void zt_aggregate_kernel(ZtArgs a, int l, const float* cur, float* q, int wg_per_coalition) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int din = a.dims[l - 1], rows = a.rows_out[l], rows_prev = a.rows_out[l - 1];
-  const int fch = (din + 15) / 16;
-  const int64_t tasks = (int64_t)a.nblk * rows * fch;
-  for (int64_t task = wave; task < tasks; task += nwaves) {
-    const int64_t cbi = task / ((int64_t)rows * fch);
-    const int rem = (int)(task - cbi * rows * fch);
-    const int t = rem / fch, f0 = (rem - t * fch) * 16;
-    uint64_t inv;
-    const uint64_t* Tb = block_words(a, a.blk0 + cbi, &inv);
-    const float* rsb = a.rs + (size_t)cbi * a.V * 64;
-    const float* hb = cur + (size_t)cbi * rows_prev * din * 64 + (size_t)f0 * 64 + lane;
-    const int e0 = a.row_ptr[t], e1 = a.row_ptr[t + 1];  // entry e1 stands for the self-loop
-    const float rst = rsb[(size_t)t * 64 + lane];
-    float acc[16];
-#pragma unroll
-    for (int f = 0; f < 16; ++f) acc[f] = 0.f;
+  const int xcd = blockIdx.x & 7;
+  const int64_t slot = blockIdx.x >> 3;
+  const int64_t cl = (slot / wg_per_coalition) * 8 + xcd;   // coalition of the launch
+  const int t = (int)(slot % wg_per_coalition) * kZWaves + wave;
+  if (cl >= (int64_t)a.nblk * 64 || t >= rows) return;
+  const int64_t cbi = cl >> 6;
+  const int cb = (int)(cl & 63);   // the coalition's bit in its block's words
+  if (block_row(a, a.blk0 + cbi, cb) >= a.k) return;
+  uint64_t inv;
+  const uint64_t* Tb = block_words(a, a.blk0 + cbi, &inv);
+  const float rst = a.rs[((size_t)cbi * a.V + t) * 64 + cb];
+  const float* hb = cur + (size_t)cl * rows_prev * din;
+  const int e0 = a.row_ptr[t], e1 = a.row_ptr[t + 1];  // entry e1 stands for the self-loop
+  for (int f0 = 0; f0 < din; f0 += 64) {
+    const bool fok = f0 + lane < din;
+    const float* hf = hb + (fok ? f0 + lane : 0);
+    float acc = 0.f;
     for (int eb = e0; eb <= e1; eb += 64) {
-      const int m = e1 + 1 - eb < 64 ? e1 + 1 - eb : 64;
       const int e = eb + lane;
       int sv = t;
-      uint64_t word = 0ull;
+      bool on = e == e1;
       if (e < e1) {
         sv = a.col[e];
-        word = Tb[a.eid[e]] ^ inv;
-      } else if (e == e1) {
-        word = ~0ull;
+        on = ((Tb[a.eid[e]] ^ inv) >> cb) & 1ull;
       }
-      const uint32_t wlo = (uint32_t)word, whi = (uint32_t)(word >> 32);
-      // only the entries that are active in some coalition of the block are visited, four at a time
-      unsigned long long act = __ballot(word != 0ull);
+      unsigned long long act = __ballot(on);
       while (act) {
-        float c[4];
-        const float* hp[4];
+        float hv[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 8; ++u) {
           const bool live = act != 0ull;
           const int i = live ? __ffsll((long long)act) - 1 : 63;
           act &= act - 1ull;
           const int src = (int)rl((uint32_t)sv, i);
-          const bool on = live && ((rl(wlo, i) & mlo) | (rl(whi, i) & mhi)) != 0u;
-          c[u] = on ? rsb[(size_t)src * 64 + lane] : 0.f;
-          hp[u] = hb + (size_t)src * din * 64;
+          const float x = hf[(size_t)src * din];   // (issued unconditionally; a spent slot reads a valid row and adds zero)
+          hv[u] = live ? x : 0.f;
         }
-        float hv[4][16];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-          for (int f = 0; f < 16; ++f) hv[u][f] = (f0 + f < din) ? hp[u][(size_t)f * 64] : 0.f;
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-          for (int f = 0; f < 16; ++f) acc[f] += c[u] * hv[u][f];
+        for (int u = 0; u < 8; ++u) acc += hv[u];
       }
     }
-    float* qo = q + (((size_t)cbi * rows + t) * din + f0) * 64 + lane;
-#pragma unroll
-    for (int f = 0; f < 16; ++f)
-      if (f0 + f < din) {
-        const float v = rst * acc[f];
-        qo[(size_t)f * 64] = a.bf16 ? zt_bf16_round(v) : v;
-      }
+    if (fok) {
+      const float v = rst * acc;
+      q[((size_t)cl * rows + t) * din + f0 + lane] = a.bf16 ? zt_bf16_round(v) : v;
+    }
   }
 }
 
-// Dense transform of a later layer on the matrix cores: nxt[t][j][c] = act( sum_f W[f][j] q[t][f][c] + b[j] ). One
-// wave per (block, row, 32 output features, 32 coalitions): lane l supplies W[f + l/32][j0 + l%32] and
-// q[t][f + l/32][c0 + l%32] (v_mfma_f32_32x32x2f32); in the bfloat16 configuration both operands are rounded to
-// bfloat16 (q already is) and v_mfma_f32_32x32x8bf16_1k accumulates in fp32, lane l supplying k = 4*(l/32) .. +3.
+// Dense transform of a later layer on the matrix cores, per coalition: nxt[t][j] = act( sum_f q[t][f] W[f][j] + b[j] ), a
+// (rows x features in) . (features in x features out) product. One wave per (coalition, 32 rows, 32 output features):
+// lane l supplies q[t0 + l%32][f + l/32] (eight consecutive f of its row per load pair) and W[f + l/32][j0 + l%32]
+// (v_mfma_f32_32x32x2f32); in the bfloat16 configuration both operands are rounded to bfloat16 (q already is) and
+// v_mfma_f32_32x32x8bf16_1k accumulates in fp32, lane l supplying f = 4*(l/32) .. +3. A layer that another one follows
+// is stored times d_t^-1/2.
 __global__ __launch_bounds__(kZThreads) void zt_transform_kernel(ZtArgs a, int l, const float* q, float* nxt) {
   const int lane = threadIdx.x & 63, half = lane >> 5, r = lane & 31;
   const int64_t wave = ((int64_t)blockIdx.x * kZThreads + threadIdx.x) >> 6, nwaves = ((int64_t)gridDim.x * kZThreads) >> 6;
   const int din = a.dims[l - 1], dout = a.dims[l], rows = a.rows_out[l];
-  const bool relu = l < a.L, isbf = a.bf16 != 0;
+  const bool last = l == a.L, isbf = a.bf16 != 0;
   const float* Wg = a.Wl[l - 1];
   const float* bias = a.bias[l - 1];
-  const int jt = (dout + 31) / 32;
-  const int64_t tasks = (int64_t)a.nblk * rows * jt * 2;
+  const int jt = (dout + 31) / 32, tt = (rows + 31) / 32;
+  const int64_t tasks = (int64_t)a.nblk * 64 * tt * jt;
   for (int64_t task = wave; task < tasks; task += nwaves) {
-    const int64_t rt = task / (2 * jt);   // block * rows + row
-    const int rem = (int)(task - rt * 2 * jt);
-    const int j0 = (rem >> 1) * 32, c0 = (rem & 1) * 32;
+    const int64_t cl = task / (tt * jt);
+    const int rem = (int)(task - cl * tt * jt);
+    const int t0 = (rem / jt) * 32, j0 = (rem % jt) * 32;
+    const int64_t cbi = cl >> 6;
+    const int cb = (int)(cl & 63);
+    if (block_row(a, a.blk0 + cbi, cb) >= a.k) continue;
     const bool jok = j0 + r < dout;
-    const float* qp = q + (size_t)rt * din * 64 + c0 + r;
+    const int tr = t0 + r < rows ? t0 + r : rows - 1;   // rows past the end read the last one and are not stored
+    const float* qp = q + ((size_t)cl * rows + tr) * din;
     const float* wp = Wg + (jok ? j0 + r : 0);
     float16_t acc;
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-    for (int fb = 0; fb < din; fb += 32) {  // 32 input features per step: their sixteen operand loads are in flight together
-      float xa[4][4], xb[4][4];
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
+    for (int fb = 0; fb < din; fb += 8) {
+      if (isbf) {
+        short4_t av, bv;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int f = fb + 8 * s + (isbf ? 4 * half + u : 2 * u + half);
+          const int f = fb + 4 * half + u;
           const bool ok = f < din;
-          const float wv = (ok && jok) ? wp[(size_t)f * dout] : 0.f;
-          xa[s][u] = isbf ? zt_bf16_round(wv) : wv;
-          xb[s][u] = ok ? qp[(size_t)f * 64] : 0.f;
+          const float qv = qp[ok ? f : 0], wv = wp[(size_t)(ok ? f : 0) * dout];
+          av[u] = (short)(__float_as_uint(ok ? qv : 0.f) >> 16);
+          bv[u] = (short)(__float_as_uint((ok && jok) ? zt_bf16_round(wv) : 0.f) >> 16);
+        }
+        acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(av, bv, acc, 0, 0, 0);
+      } else {
+        float xa[4], xb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int f = fb + 2 * u + half;
+          const bool ok = f < din;
+          const float qv = qp[ok ? f : 0], wv = wp[(size_t)(ok ? f : 0) * dout];
+          xa[u] = ok ? qv : 0.f;
+          xb[u] = (ok && jok) ? wv : 0.f;
         }
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        if (fb + 8 * s >= din) break;
-        if (isbf) {
-          short4_t av, bv;
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            av[u] = (short)(__float_as_uint(xa[s][u]) >> 16);
-            bv[u] = (short)(__float_as_uint(xb[s][u]) >> 16);
-          }
-          acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(av, bv, acc, 0, 0, 0);
-        } else {
-#pragma unroll
-          for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[s][u], xb[s][u], acc, 0, 0, 0);
-        }
+        for (int u = 0; u < 4; ++u)
+          if (fb + 2 * u < din) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[u], xb[u], acc, 0, 0, 0);
       }
     }
-    // accumulator register i of lane l is out[feature j0 + 8*(i/4) + 4*(l/32) + i%4][coalition c0 + l%32]
+    // accumulator register i of lane l is out[row t0 + 8*(i/4) + 4*(l/32) + i%4][feature j0 + l%32]
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int j = j0 + 8 * (i / 4) + 4 * half + (i % 4);
-      if (j < dout) {
-        const float v = acc[i] + (bias ? bias[j] : 0.f);
-        nxt[((size_t)rt * dout + j) * 64 + c0 + r] = relu ? fmaxf(v, 0.f) : v;
+      const int t = t0 + 8 * (i / 4) + 4 * half + (i % 4);
+      if (t < rows && jok) {
+        float v = acc[i] + (bias ? bias[j0 + r] : 0.f);
+        if (!last) v = fmaxf(v, 0.f) * a.rs[((size_t)cbi * a.V + t) * 64 + cb];
+        nxt[((size_t)cl * rows + t) * dout + j0 + r] = v;
       }
     }
   }
@@ -341,22 +338,20 @@ __global__ __launch_bounds__(kZThreads) void zt_transform_kernel(ZtArgs a, int l
 
 // readout: the target is row 0 of the last layer's output; one thread per coalition
 __global__ void zt_readout_kernel(ZtArgs a, const float* cur) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)a.nblk * 64) return;
-  const int64_t cbi = i >> 6;
-  const int lane = (int)(i & 63);
-  const int64_t row = block_row(a, a.blk0 + cbi, lane);
+  const int64_t cl = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (cl >= (int64_t)a.nblk * 64) return;
+  const int64_t row = block_row(a, a.blk0 + (cl >> 6), (int)(cl & 63));
   if (row >= a.k) return;
   const int C = a.dims[a.L], rowsL = a.rows_out[a.L];
-  const float* lg = cur + (size_t)cbi * rowsL * C * 64 + lane;
+  const float* lg = cur + (size_t)cl * rowsL * C;
   float m = -INFINITY;
-  for (int c = 0; c < C; ++c) m = fmaxf(m, lg[(size_t)c * 64]);
+  for (int c = 0; c < C; ++c) m = fmaxf(m, lg[c]);
   float sum = 0.f;
-  for (int c = 0; c < C; ++c) sum += expf(lg[(size_t)c * 64] - m);
-  const float zc = lg[(size_t)(*a.pred_ptr) * 64];
+  for (int c = 0; c < C; ++c) sum += expf(lg[c] - m);
+  const float zc = lg[*a.pred_ptr];
   a.y[row] = a.score == DS_SCORE_LOGIT ? zc : expf(zc - m) / sum;
   if (a.logits_out)
-    for (int c = 0; c < C; ++c) a.logits_out[row * C + c] = lg[(size_t)c * 64];
+    for (int c = 0; c < C; ++c) a.logits_out[row * C + c] = lg[c];
 }
 
 struct ZtPlan {
@@ -477,11 +472,14 @@ int ds_eval_zt(ds_ctx* ctx, ds_cgraph* cg, const uint64_t* Z, int64_t k, int sco
     float* cur = bufA;
     for (int l = 2; l <= ctx->L; ++l) {
       float* nxt = (l & 1) ? bufA : bufB;
-      const int64_t fch = (a.dims[l - 1] + 15) / 16, jt = (a.dims[l] + 31) / 32;
-      hipLaunchKernelGGL(zt_aggregate_kernel, dim3((unsigned)grid_for_waves(ctx, (int64_t)a.nblk * a.rows_out[l] * fch)), dim3(kZThreads),
-                         0, ctx->stream, a, l, (const float*)cur, q);
-      hipLaunchKernelGGL(zt_transform_kernel, dim3((unsigned)grid_for_waves(ctx, (int64_t)a.nblk * a.rows_out[l] * jt * 2)),
-                         dim3(kZThreads), 0, ctx->stream, a, l, (const float*)q, nxt);
+      const int wg_per_coalition = (a.rows_out[l] + kZWaves - 1) / kZWaves;
+      const int64_t agg_grid = (((int64_t)a.nblk * 64 + 7) / 8) * wg_per_coalition * 8;
+      const int64_t tt = (a.rows_out[l] + 31) / 32, jt = (a.dims[l] + 31) / 32;
+      if (agg_grid > 0x7fffffffLL) return ds_fail(ctx, DS_EINTERNAL, "eval: too many aggregation workgroups");
+      hipLaunchKernelGGL(zt_aggregate_kernel, dim3((unsigned)agg_grid), dim3(kZThreads), 0, ctx->stream, a, l, (const float*)cur, q,
+                         wg_per_coalition);
+      hipLaunchKernelGGL(zt_transform_kernel, dim3((unsigned)grid_for_waves(ctx, (int64_t)a.nblk * 64 * tt * jt)), dim3(kZThreads), 0,
+                         ctx->stream, a, l, (const float*)q, nxt);
       cur = nxt;
     }
     hipLaunchKernelGGL(zt_readout_kernel, dim3((unsigned)((a.nblk * 64 + 255) / 256)), dim3(256), 0, ctx->stream, a, (const float*)cur);
