@@ -187,22 +187,30 @@ __global__ __launch_bounds__(kZThreads, 4) void zt_layer1_kernel(ZtArgs a, float
       // accumulator register i of lane l of acc[ft][nb] is D[coalition 32*nb + 8*(i/4) + 4*(l/32) + i%4][feature f0 + 32*ft +
       // l%32]: a store is 128 contiguous bytes of one coalition's row. A layer that another one follows is stored
       // already multiplied by d_t^-1/2 (the only form the next aggregation uses it in).
+      // (the four coalitions of a register group are consecutive: their d_t^-1/2 come as one 16-byte load, and the
+      // store address advances by one coalition's array at a time instead of being formed 64 times over)
+      const size_t cs = (size_t)rows1 * d1;   // floats between two coalitions
+      float* o = out + (((size_t)cbi * 64 + 4 * half) * rows1 + t) * d1 + f0 + l32;
+      const float* rp = rsb + (size_t)t * 64 + 4 * half;
+      const bool ok0 = f0 + l32 < d1, ok1 = f0 + 32 + l32 < d1;
+      const float bias0 = (a.bias[0] && ok0) ? a.bias[0][f0 + l32] : 0.f, bias1 = (a.bias[0] && ok1) ? a.bias[0][f0 + 32 + l32] : 0.f;
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int c = 32 * nb + 8 * (i / 4) + 4 * half + (i % 4);
-          const float rt = rsb[(size_t)t * 64 + c];
-          float* o = out + (((size_t)cbi * 64 + c) * rows1 + t) * d1 + f0 + l32;
+        for (int g = 0; g < 4; ++g) {
+          const float4 rt4 = *(const float4*)(rp + 32 * nb + 8 * g);
+          const float rt[4] = {rt4.x, rt4.y, rt4.z, rt4.w};
+          float* og = o + (size_t)(32 * nb + 8 * g) * cs;
 #pragma unroll
-          for (int ft = 0; ft < 2; ++ft) {
-            const int f = f0 + 32 * ft + l32;
-            if (f < d1) {
-              float v = rt * acc[ft][nb][i];
-              if (a.bias[0]) v += a.bias[0][f];
-              if (relu) v = fmaxf(v, 0.f) * rt;
-              o[32 * ft] = v;
+          for (int j = 0; j < 4; ++j) {
+            float v0 = rt[j] * acc[0][nb][4 * g + j] + bias0, v1 = rt[j] * acc[1][nb][4 * g + j] + bias1;
+            if (relu) {
+              v0 = fmaxf(v0, 0.f) * rt[j];
+              v1 = fmaxf(v1, 0.f) * rt[j];
             }
+            if (ok0) og[0] = v0;
+            if (ok1) og[32] = v1;
+            og += cs;
           }
         }
     }
