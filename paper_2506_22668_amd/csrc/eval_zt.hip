@@ -8,15 +8,19 @@
 // transposed block-wise, T[block][player] = the player's bits in the block's 64 coalitions, one 8-byte word says for
 // all 64 coalitions whether an entry is active, every row of P = X_c W_1 is loaded once per 64 coalitions, and
 //   H1[t][f][c] = sum_e P[src_e][f] * (bit_e(c) ? d_src(c)^-1/2 : 0)
-// is a (features x entries) . (entries x coalitions) product on the matrix cores (v_mfma_f32_32x32x2f32). Unlike the
+// is an (entries x coalitions)^T . (entries x features) product on the matrix cores (v_mfma_f32_32x32x2f32). Unlike the
 // one-coalition-per-lane kernel for short mask rows, nothing here has to fit a workgroup's LDS: every stage is a
-// kernel of its own over (block, row) tasks, with the per-block operands [row][feature][coalition] in global
-// memory, a bounded number of blocks at a time:
-//   degrees  d(v) = 1 + sum of the bits of row v's entries            (lane = coalition)
-//   layer 1  the contraction above, scaled by d_t^-1/2, + bias, ReLU   (matrix cores)
-//   layer l >= 2: q = D^-1/2 (A_S + I) D^-1/2 H  (lane = coalition, VALU; coefficients differ per coalition),
-//                 then act(q W_l + b_l), (features out x features in) . (features in x coalitions), matrix cores
+// kernel of its own, a bounded number of blocks at a time, with the per-coalition layer outputs [coalition][row][feature]
+// in global memory (a layer that another one follows is stored times d^-1/2 of its own row, the only form the next
+// aggregation uses it in):
+//   degrees  d(v) = 1 + sum of the bits of row v's entries            (one wave per (block, node), lane = coalition)
+//   layer 1  the contraction above, scaled by d_t^-1/2, + bias, ReLU   (one wave per (block, row), matrix cores)
+//   layer l >= 2: q = D^-1/2 (A_S + I) D^-1/2 H  (one wave per (coalition, row), lanes = features, only the coalition's
+//                 active entries are visited), then act(q W_l + b_l) as a (rows x features) product per coalition,
+//                 matrix cores
 //   readout  soft-max (or logit) of the predicted class.
+// With complementary pairs only the stored members are transposed: a block is 64 stored members or their 64 complements
+// (the same words inverted), and a block of sparse members skips the entries none of its coalitions has.
 #include "internal.h"
 #include "solve_common.h"
 
@@ -221,9 +225,11 @@ __global__ __launch_bounds__(kZThreads, 4) void zt_layer1_kernel(ZtArgs a, float
 // ACTIVE entries of H'[src][f] + H'[t][f] ), H' being the previous layer's output times d^-1/2 of its own row (stored that
 // way). Only the coalition's own active entries are visited: the lanes test the bits of 64 entries together and the set
 // ones are walked eight at a time (eight 256-byte row loads in flight). The layer's input of one coalition (rows x d x 4
-// bytes: 2.5 MB on the hub workload) is read by all rows t of that coalition, about sixteen times over; the launch puts
-// the workgroups of a coalition on one XCD (workgroups go to the XCDs round-robin by index) and one row per wave, so
-// that an XCD works on one or two coalitions at a time and those re-reads come from its L2.
+// bytes: 2.5 MB on the hub workload) is read by all rows t of that coalition, about sixteen times over; with one row per
+// wave the whole GPU works on a few dozen coalitions at a time, so those re-reads come from the caches (HBM traffic of
+// the hub workload's second layer: 780 GB as [row][feature][64 coalitions] -> 53 GB). The launch also keeps the workgroups
+// of a coalition on one XCD (workgroups go to the XCDs round-robin by index); measured, that made no difference
+// against plain order.
 __global__ __launch_bounds__(kZThreads) void zt_aggregate_kernel(ZtArgs a, int l, const float* cur, float* q, int wg_per_coalition) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int din = a.dims[l - 1], rows = a.rows_out[l], rows_prev = a.rows_out[l - 1];
