@@ -358,12 +358,15 @@ constexpr int kWBufFloats = 4096;  // the workgroup's staging buffer in LDS: wei
 // 1,010-player config) lose less to a partly filled batch with two (0.34 -> 0.27 ms there); the long shared rows of the
 // external-input mode want four entries' loads in flight (8: 14.9 ms, 4: 14.1 ms, 2: 16.2 ms on the 10^6-player config)
 template <bool EXT> constexpr int stage_rows() { return EXT ? 4 : 2; }
-// Waves that share the 64 coalitions of a workgroup. Only one workgroup fits a compute unit's LDS and the stages are
-// latency chains per wave, so with the masks on chip sixteen waves shorten them (against eight: 0.39 -> 0.32 ms on 1,010
+// Waves that share the 64 coalitions of a workgroup. With the masks on chip only one workgroup fits a compute unit's LDS
+// and the stages are latency chains per wave, so sixteen waves shorten them (against eight: 0.39 -> 0.32 ms on 1,010
 // players, 4.1 -> 2.4 ms on 9,647). With external inputs the time is the long shared rows of layer 1, whose loop holds 64
-// accumulator registers: sixteen waves leave a wave 128 registers and the loop spills; eight waves keep it in
-// registers (config 4: 14.1 -> 13.1 ms).
-template <bool EXT> constexpr int batched_threads() { return EXT ? 512 : 1024; }
+// accumulator registers: sixteen waves leave a wave 128 registers and the loop spills, eight keep it in registers
+// (config 4: 14.1 -> 13.1 ms). External inputs in pairs keep only the stored members' entry bits in LDS (half the
+// bytes), so that two workgroups of four waves fit a compute unit, registers unspilled, and one's barriers and loads
+// overlap the other's matrix-core work (10.2 -> 8.7 ms; three workgroups of 168 registers: 9.3 ms).
+constexpr int kExtPairedThreads = 256;
+template <bool EXT, bool PAIRED = false> constexpr int batched_threads() { return EXT ? (PAIRED ? kExtPairedThreads : 512) : 1024; }
 constexpr int kDegLdsMaxNodes = 640;  // degrees as u16[V][64] in LDS up to this many nodes (80 KB)
 
 struct BatchedArgs {
@@ -505,9 +508,9 @@ constexpr int kSharedRow = 256;  // a row with more entries than this is shared 
 // PAIRED (external inputs only): the records are complementary pairs and the first layer's coefficients are formed by
 // the lanes that feed them to the matrix cores (see there)
 template <bool DEG_LDS, bool CSR_LDS, bool EXT, bool PAIRED = false>
-__global__ __launch_bounds__(batched_threads<EXT>()) void masked_gcn_eval_batched_kernel(BatchedArgs b) {
+__global__ __launch_bounds__((batched_threads<EXT, PAIRED>()), (EXT && PAIRED ? 2 : 1)) void masked_gcn_eval_batched_kernel(BatchedArgs b) {
   const EvalArgs& a = b.e;
-  constexpr int kBThreads = batched_threads<EXT>(), kBWaves = kBThreads / 64;
+  constexpr int kBThreads = batched_threads<EXT, PAIRED>(), kBWaves = kBThreads / 64;
   constexpr int kStageRows = stage_rows<EXT>();
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   // LDS: zs[zs_words][64] u64 | staging buffer f32[4096] | deg[V][64] u16 (optional) | local CSR (optional)
@@ -562,6 +565,8 @@ __global__ __launch_bounds__(batched_threads<EXT>()) void masked_gcn_eval_batche
   // mask bit of CSR entry e (of a row layer 1 produces) in this lane's coalition
   // (x: the player of the entry, or, with external inputs, the rank of that player among the needed ones)
   auto entry_bit = [&](int x) -> bool {
+    // (pairs: only the stored members' words are kept, [word][pair]; the complement's bit is the inverted one)
+    if (EXT && PAIRED) return (((ebs[(x >> 5) * 32 + (lane & 31)] >> (x & 31)) & 1u) ^ (uint32_t)(lane >> 5)) != 0u;
     if (EXT) return (ebs[(x >> 5) * 64 + lane] >> (x & 31)) & 1u;
     return bit_of(x);
   };
@@ -599,7 +604,11 @@ __global__ __launch_bounds__(batched_threads<EXT>()) void masked_gcn_eval_batche
       uint32_t* ebw = (uint32_t*)smem_raw;
       for (int j = wave; j < b.eb_words; j += kBWaves) {
         uint32_t wd = valid ? b.ext_bits[rec * b.eb_stride + j] : 0u;
-        ebw[j * 64 + lane] = member ? ~wd : wd;
+        if (PAIRED) {
+          if (lane < 32) ebw[j * 32 + lane] = wd;
+        } else {
+          ebw[j * 64 + lane] = member ? ~wd : wd;
+        }
       }
       ext_member = member;
       ext_deg_lane = b.ext_deg + (((size_t)(rec >> b.ext_lr) * a.V) << b.ext_lr) + (rec & ((1 << b.ext_lr) - 1));
@@ -694,7 +703,7 @@ __global__ __launch_bounds__(batched_threads<EXT>()) void masked_gcn_eval_batche
               for (int q = 0; q < SRP / 2; ++q) {
                 const int ei = 2 * q + half, p = cur.p[q];
                 const bool ok = ei < cnt, self = eb + ei == e1;
-                const bool bit = (ebs[(p >> 5) * 64 + l32] >> (p & 31)) & 1u;
+                const bool bit = (ebs[(p >> 5) * 32 + l32] >> (p & 31)) & 1u;
                 const float b0 = (ok && (self || bit)) ? __frsqrt_rn((float)cur.d[q]) : 0.f;              // the members
                 const float b1 = (ok && (self || !bit)) ? __frsqrt_rn((float)(cur.f[q] - cur.d[q])) : 0.f;  // the complements
                 const float a0 = (ok && fok0) ? cur.av[q][0] : 0.f, a1 = (ok && fok1) ? cur.av[q][1] : 0.f;
@@ -737,7 +746,7 @@ __global__ __launch_bounds__(batched_threads<EXT>()) void masked_gcn_eval_batche
                 const int p = half ? readlane_i(pv, 2 * q + 1) : readlane_i(pv, 2 * q);
                 const int src = half ? readlane_i(sv, 2 * q + 1) : readlane_i(sv, 2 * q);
                 const bool ok = ei < cnt, self = eb + ei == e1;
-                const bool bit = (ebs[(p >> 5) * 64 + l32] >> (p & 31)) & 1u;
+                const bool bit = (ebs[(p >> 5) * 32 + l32] >> (p & 31)) & 1u;
                 const int d = ext_deg_lane[(size_t)src << b.ext_lr];
                 const int f = (int)b.fdeg2[src];
                 b0v[q] = (ok && (self || bit)) ? __frsqrt_rn((float)d) : 0.f;         // coalitions 0..31: the members
@@ -1699,7 +1708,7 @@ BatchedLayout make_stream_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t
   bl.E_need = (int32_t)E_need;
   bl.eb_words = (int)((E_need + 63) / 64 * 2);  // whole 64-entry groups (one ballot each)
   if (bl.eb_words < 2) bl.eb_words = 2;
-  bl.zs_words = bl.eb_words / 2;
+  bl.zs_words = paired ? (bl.eb_words + 3) / 4 : bl.eb_words / 2;   // (pairs: the stored members' words only)
   bl.lds_bytes = (size_t)bl.zs_words * 64 * 8 + (size_t)kWBufFloats * 4;
   if (bl.lds_bytes > kLdsLimit) return bl;
   // the streaming kernel: R = 8 rows per workgroup if their packed 16-bit counters fit LDS, else 4 or 2
@@ -1716,7 +1725,7 @@ BatchedLayout make_stream_layout(const ds_ctx* ctx, const ds_cgraph* cg, int64_t
   bl.rs_floats = 0;
   bl.stride = bl.a_floats + bl.b_floats + bl.q_floats;
   const int64_t blocks = (k + 63) / 64;
-  int64_t g = (int64_t)ctx->num_cus * 2;
+  int64_t g = (int64_t)ctx->num_cus * 4;
   bl.grid = (int)(blocks < g ? blocks : g);
   bl.records = paired ? k / 2 : k;
   bl.slots = paired ? 32 : 64;
@@ -1750,7 +1759,8 @@ int launch_batched(ds_ctx* ctx, const BatchedLayout& bl, const BatchedArgs& b, i
   if (EXT && (bl.deg_lds || bl.csr_lds)) return ds_fail(ctx, DS_EINTERNAL, "eval: external inputs with on-chip degrees or CSR");
   if (bl.lds_bytes > 48 * 1024)
     DS_HIP(ctx, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bl.lds_bytes));
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(batched_threads<EXT>()), bl.lds_bytes, ctx->stream, b);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(EXT && b.ext_paired ? batched_threads<true, true>() : batched_threads<EXT>()), bl.lds_bytes,
+                     ctx->stream, b);
   DS_HIP(ctx, hipGetLastError());
   return DS_OK;
 }
