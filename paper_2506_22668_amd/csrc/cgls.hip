@@ -56,7 +56,40 @@ struct Vecs {
   double *x, *u, *s, *r, *v, *d, *h;  // n, n, n, k, k, R, R
   double* scal;
   double* part;      // [4 * kRed]
+  // fixed-point products only (else null): where the kernel that writes u (h) leaves the bit pattern of max |u| (max |h|)
+  // for the next forward (adjoint) product, which then needs no pass of its own over the vector
+  unsigned long long *slot_u, *slot_h;
 };
+
+// the workgroup's part of max |x| (bit patterns of non-negative doubles order like the values) into *slot
+// (one atomic per workgroup: every thread of the workgroup must call this)
+__device__ __forceinline__ void publish_absmax(unsigned long long m, unsigned long long* slot) {
+  __shared__ unsigned long long wm[kThreads / 64];
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned long long t = __shfl_xor(m, o, 64);
+    m = t > m ? t : m;
+  }
+  if ((threadIdx.x & 63) == 0) wm[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int i = 1; i < kThreads / 64; ++i) m = wm[i] > m ? wm[i] : m;
+    if (m) atomicMax(slot, m);
+  }
+  __syncthreads();
+}
+__device__ __forceinline__ unsigned long long abs_bits(double x) {
+  return (unsigned long long)__double_as_longlong(x) & 0x7fffffffffffffffull;
+}
+// (an iteration that has stopped leaves the vector alone, but the products queued behind it still read its maximum)
+__device__ __forceinline__ void publish_absmax_of(const double* x, int64_t len, unsigned long long* slot) {
+  if (!slot) return;
+  unsigned long long m = 0;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < len; i += (int64_t)gridDim.x * kThreads) {
+    const unsigned long long b = abs_bits(x[i]);
+    m = b > m ? b : m;
+  }
+  publish_absmax(m, slot);
+}
 
 // r = sqrt(w) t ; h from r
 __global__ void init_r_kernel(Vecs a, const double* t) {
@@ -192,7 +225,10 @@ __global__ __launch_bounds__(kThreads) void loop_update_r_kernel(Vecs a, int par
   const double gamma = a.scal[0];
   const bool null_dir = !(delta > 0.0);
   const double th = null_dir ? 0.0 : gamma / delta;
-  if (done) return;
+  if (done) {
+    publish_absmax_of(a.h, a.R, a.slot_h);
+    return;
+  }
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     a.scal[1] = delta;
     a.scal[2] = th;
@@ -201,18 +237,24 @@ __global__ __launch_bounds__(kThreads) void loop_update_r_kernel(Vecs a, int par
       a.scal[9] += 1.0;
     }
   }
+  unsigned long long hm = 0;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < a.R; i += (int64_t)gridDim.x * kThreads) {
+    double hn;
     if (a.paired) {
       const double r0 = a.r[2 * i] - th * a.v[2 * i], r1 = a.r[2 * i + 1] - th * a.v[2 * i + 1];
       a.r[2 * i] = r0;
       a.r[2 * i + 1] = r1;
-      a.h[i] = a.sqw[2 * i] * (r0 - r1);
+      hn = a.sqw[2 * i] * (r0 - r1);
     } else {
       const double r0 = a.r[i] - th * a.v[i];
       a.r[i] = r0;
-      a.h[i] = a.sqw[i] * r0;
+      hn = a.sqw[i] * r0;
     }
+    a.h[i] = hn;
+    const unsigned long long b = abs_bits(hn);
+    hm = b > hm ? b : hm;
   }
+  if (a.slot_h) publish_absmax(hm, a.slot_h);
 }
 
 __global__ __launch_bounds__(kThreads) void loop_s_sum_kernel(Vecs a) {
@@ -239,7 +281,10 @@ __global__ __launch_bounds__(kThreads) void loop_s_center_kernel(Vecs a, int par
 // x += theta u, u = s + beta u with the partial sums of the new u
 __global__ __launch_bounds__(kThreads) void loop_update_xu_kernel(Vecs a, int parts_g, double tol, int do_update) {
   const double g = block_sum_partials(a, kPartG, parts_g);
-  if (a.scal[8] != 0.0) return;
+  if (a.scal[8] != 0.0) {
+    publish_absmax_of(a.u, a.n, a.slot_u);
+    return;
+  }
   const double gamma = a.scal[0], gamma0 = a.scal[7];
   const double rel = sqrt(g) / sqrt(gamma0);
   const bool stop = rel <= tol;
@@ -255,15 +300,22 @@ __global__ __launch_bounds__(kThreads) void loop_update_xu_kernel(Vecs a, int pa
       a.scal[6] = g;
     }
   }
-  if (stop || !do_update) return;
+  if (stop || !do_update) {
+    publish_absmax_of(a.u, a.n, a.slot_u);
+    return;
+  }
   double acc = 0;
+  unsigned long long um = 0;
   for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) {
     const double uo = a.u[j];
     a.x[j] += th * uo;
     const double un = a.s[j] + beta * uo;
     a.u[j] = un;
     acc += un;
+    const unsigned long long b = abs_bits(un);
+    um = b > um ? b : um;
   }
+  if (a.slot_u) publish_absmax(um, a.slot_u);
   double dummy;
   block_reduce2(acc, 0.0, &a.part[kPartU * kRed + blockIdx.x], &dummy);
 }
@@ -404,16 +456,19 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   // Hybrid layout: the vector is brought into fixed point once per product; the sparse rows' tiles and the dense
   // rows' bitmap are multiplied one after the other (side by side on two streams they only competed for memory
   // bandwidth and the iteration took 8 % longer), the dense product adding the sparse result in the adjoint.
-  auto forward = [&](const double* u, double* d) -> int {  // d = (rows) . u
+  a.slot_u = hybrid ? (unsigned long long*)(scal_f + 1) : nullptr;
+  a.slot_h = hybrid ? (unsigned long long*)(scal_a + 1) : nullptr;
+  // with_absmax = 0: the kernel that wrote the vector has left its maximum in the product's slot
+  auto forward = [&](const double* u, double* d, int with_absmax) -> int {  // d = (rows) . u
     if (!hybrid) return ds_bit_spmv(ctx, Z, R, n, W, 0, paired ? 2 : 1, u, d);
-    DS_TRY(ds_vec_quantize(ctx, u, n, &mm_f, u, u, Rs > 0 ? n : 0, q64u, scal_f));
+    DS_TRY(ds_vec_quantize(ctx, u, n, &mm_f, u, u, Rs > 0 ? n : 0, q64u, scal_f, with_absmax));
     if (Rs > 0) DS_TRY(ds_tile_spmv(ctx, &tiles, 0, q64u, scal_f, d, Rd > 0 ? 0 : 1));
     if (Rd > 0) DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_f, Z, W, 2 * Rs, 2, scal_f, nullptr, d + Rs, 1));
     return DS_OK;
   };
-  auto adjoint = [&](const double* h, double* sv) -> int {  // s = (rows)^T . h
+  auto adjoint = [&](const double* h, double* sv, int with_absmax) -> int {  // s = (rows)^T . h
     if (!hybrid) return ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, h, sv);
-    DS_TRY(ds_vec_quantize(ctx, h, R, &mm_a, h + Rs, h, Rs, q64h, scal_a));
+    DS_TRY(ds_vec_quantize(ctx, h, R, &mm_a, h + Rs, h, Rs, q64h, scal_a, with_absmax));
     if (Rs > 0) DS_TRY(ds_tile_spmv(ctx, &tiles, 1, q64h, scal_a, sv, Rd > 0 ? 0 : 1));
     if (Rd > 0) DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_a, Ztd, RdW, 0, 1, scal_a, Rs > 0 ? sv : nullptr, sv, 1));
     return DS_OK;
@@ -431,7 +486,7 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   // s_0 = P A^T r_0, u_0 = s_0
   hipLaunchKernelGGL(init_r_kernel, dim3(nblocks(k, 256)), dim3(256), 0, st, a, t);
   hipLaunchKernelGGL(make_h_kernel, dim3(nblocks(R, 256)), dim3(256), 0, st, a);
-  DS_TRY(adjoint(a.h, a.s));
+  DS_TRY(adjoint(a.h, a.s, 1));
   hipLaunchKernelGGL(s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
   hipLaunchKernelGGL(fin_mean_kernel, dim3(1), dim3(64), 0, st, a, (int)red_n);
   hipLaunchKernelGGL(s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
@@ -457,10 +512,10 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   while (!converged && launched < max_iter) {
     const int burst = max_iter - launched < kCheckEvery ? max_iter - launched : kCheckEvery;
     for (int b = 0; b < burst; ++b) {
-      DS_TRY(forward(a.u, a.d));
+      DS_TRY(forward(a.u, a.d, launched + b == 0 ? 1 : 0));   // (the first u comes from the set-up, not from the loop's kernel)
       hipLaunchKernelGGL(loop_make_v_kernel, dim3(red_r), dim3(kThreads), 0, st, a, (int)red_n);
       hipLaunchKernelGGL(loop_update_r_kernel, dim3(red_r), dim3(kThreads), 0, st, a, (int)red_r);
-      DS_TRY(adjoint(a.h, a.s));
+      DS_TRY(adjoint(a.h, a.s, 0));
       hipLaunchKernelGGL(loop_s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
       hipLaunchKernelGGL(loop_s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a, (int)red_n);
       // the last iteration allowed takes no further step: it only evaluates the stopping rule

@@ -147,15 +147,18 @@ def _cgls_config(key, pair_stride, iterations, check_residual):
     assert abs(got.sum() - (yh[1] - yh[0])) <= 1e-5
 
     # the same number of steps inside a one-shot explanation. There the sampler also writes the sparse small members
-    # as player lists and the mask-streaming kernel reads those instead of the bit rows: degrees and entry bits are
-    # integers, so y and the iterate must be the very same numbers as from the stages above
+    # as player lists and the mask-streaming kernel reads those instead of the bit rows, and the layers run in their
+    # form for complementary pairs: degrees and entry bits are the same integers, the first layer's long rows are
+    # summed in another grouping, so y and the iterate agree with the stages above to rounding
     say(f"{key}: one-shot explain, {iterations} CGLS steps (with long mask rows: player lists from the sampler)")
     phi3, _, _, rep3, rc3 = ctx.explain(target, w.n_samples, w.seed,
                                         Options(solver=DS_SOLVER_CGLS, tol=1e-300, max_iter=iterations), capacity=n,
                                         want_edges=False, allow_not_converged=True)
     assert rc3 == DS_ENOTCONV and rep3.cgls_iterations == iterations
-    assert np.array_equal(phi3.cpu().numpy(), phi.cpu().numpy())
-    say(f"{key}: identical; ms sample={rep3.ms_sample:.2f} eval={rep3.ms_eval:.2f} (mask-streaming kernel {rep3.ms_k_stream:.2f})")
+    err3 = np.abs(phi3.cpu().numpy().astype(np.float64) - got).max()
+    say(f"{key}: max |phi - stage-wise phi| = {err3:.3e}; ms sample={rep3.ms_sample:.2f} eval={rep3.ms_eval:.2f} "
+        f"(mask-streaming kernel {rep3.ms_k_stream:.2f})")
+    assert err3 <= 1e-6 * scale
 
     # the converged one-shot explanation
     say(f"{key}: one-shot explain")
