@@ -20,7 +20,7 @@
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRed = 256;  // blocks (and partials) of every reduction
+constexpr int kRed = 1024;  // blocks (and partials) of every reduction, at most
 
 __device__ __forceinline__ void block_reduce2(double a, double b, double* pa, double* pb) {
   __shared__ double sh[2][kThreads / 64];
@@ -59,7 +59,27 @@ struct Vecs {
   // fixed-point products only (else null): where the kernel that writes u (h) leaves the bit pattern of max |u| (max |h|)
   // for the next forward (adjoint) product, which then needs no pass of its own over the vector
   unsigned long long *slot_u, *slot_h;
+  // fixed-point products inside the loop (fused != 0): the products leave their integer partial sums, and the loop's
+  // kernel that reads d (s) first adds them up itself, scales them by scal_f[0] (scal_a[0]) and clears the product's
+  // maximum slot. Forward: the rows [0, Rs) come from the tiles, the rest from the matrix cores; adjoint: both parts
+  // cover all n entries and are added, tiles first.
+  int fused;
+  int64_t Rs;
+  ds_fixed_view fwd, adj;
+  const double *scal_f, *scal_a;
 };
+
+__device__ __forceinline__ double forward_result(const Vecs& a, double sc, int64_t i) {
+  if (i < a.Rs)
+    return a.fwd.tile_groups ? ds_tile_sum(a.fwd.tile_partial, a.fwd.tile_len, a.fwd.tile_groups, a.fwd.tile_sh, i) * sc : 0.0;
+  return ds_mm_sum(a.fwd.mm_partial, a.fwd.mm_rows, a.fwd.mm_groups, i - a.Rs) * sc;
+}
+__device__ __forceinline__ double adjoint_result(const Vecs& a, double sc, int64_t j) {
+  const double mm = a.adj.mm_groups ? ds_mm_sum(a.adj.mm_partial, a.adj.mm_rows, a.adj.mm_groups, j) * sc : 0.0;
+  if (!a.adj.tile_groups) return mm;
+  const double tl = ds_tile_sum(a.adj.tile_partial, a.adj.tile_len, a.adj.tile_groups, a.adj.tile_sh, j) * sc;
+  return a.adj.mm_groups ? tl + mm : tl;
+}
 
 // the workgroup's part of max |x| (bit patterns of non-negative doubles order like the values) into *slot
 // (one atomic per workgroup: every thread of the workgroup must call this)
@@ -199,10 +219,12 @@ __global__ __launch_bounds__(kThreads) void loop_make_v_kernel(Vecs a, int parts
     a.scal[4] = U;
     a.scal[0] = a.scal[6];
   }
+  const double sc = a.fused ? a.scal_f[0] : 0.0;
+  if (a.fused && blockIdx.x == 0 && threadIdx.x == 0) *a.slot_u = 0ull;
   double acc = 0.0;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < a.R; i += (int64_t)gridDim.x * kThreads) {
     if (a.paired) {
-      const double w = a.sqw[2 * i], d = a.d[i];
+      const double w = a.sqw[2 * i], d = a.fused ? forward_result(a, sc, i) : a.d[i];
       const double v0 = w * d, v1 = w * (U - d);
       a.v[2 * i] = v0;
       a.v[2 * i + 1] = v1;
@@ -259,7 +281,17 @@ __global__ __launch_bounds__(kThreads) void loop_update_r_kernel(Vecs a, int par
 
 __global__ __launch_bounds__(kThreads) void loop_s_sum_kernel(Vecs a) {
   double s1 = 0;
-  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) s1 += a.s[j];
+  if (a.fused) {
+    const double sc = a.scal_a[0];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.slot_h = 0ull;
+    for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) {
+      const double v = adjoint_result(a, sc, j);
+      a.s[j] = v;
+      s1 += v;
+    }
+  } else {
+    for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) s1 += a.s[j];
+  }
   double dummy;
   block_reduce2(s1, 0.0, &a.part[kPartS * kRed + blockIdx.x], &dummy);
 }
@@ -358,7 +390,7 @@ size_t ds_cgls_arena_bytes(int64_t n, int64_t k) {
   const size_t hybrid = 3 * ds_align((size_t)n * KW * 8) + 4 * ds_align((n + 2) * 4) + 2 * ds_align((k + 2) * 4) +
                         ds_align(96 * (size_t)(n > k ? n : k)) + ((size_t)80 << 20) + tile_scratch +
                         4 * ds_scan_arena_bytes(n > k ? n + 1 : k + 1);
-  return hybrid + 2 * ds_align(k * 4) + 7 * ds_align(k * 8) + 4 * ds_align(n * 8) + 65536;
+  return hybrid + 2 * ds_align(k * 4) + 7 * ds_align(k * 8) + 4 * ds_align(n * 8) + 131072;
 }
 
 int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, const float* w, const float* y, int paired,
@@ -459,20 +491,27 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   a.slot_u = hybrid ? (unsigned long long*)(scal_f + 1) : nullptr;
   a.slot_h = hybrid ? (unsigned long long*)(scal_a + 1) : nullptr;
   // with_absmax = 0: the kernel that wrote the vector has left its maximum in the product's slot
+  // d (sv) == nullptr: the integer partial sums are left for the loop's kernels
   auto forward = [&](const double* u, double* d, int with_absmax) -> int {  // d = (rows) . u
     if (!hybrid) return ds_bit_spmv(ctx, Z, R, n, W, 0, paired ? 2 : 1, u, d);
     DS_TRY(ds_vec_quantize(ctx, u, n, &mm_f, u, u, Rs > 0 ? n : 0, q64u, scal_f, with_absmax));
-    if (Rs > 0) DS_TRY(ds_tile_spmv(ctx, &tiles, 0, q64u, scal_f, d, Rd > 0 ? 0 : 1));
-    if (Rd > 0) DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_f, Z, W, 2 * Rs, 2, scal_f, nullptr, d + Rs, 1));
+    if (Rs > 0) DS_TRY(ds_tile_spmv(ctx, &tiles, 0, q64u, scal_f, d, d && Rd == 0 ? 1 : 0));
+    if (Rd > 0) DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_f, Z, W, 2 * Rs, 2, scal_f, nullptr, d ? d + Rs : nullptr, d ? 1 : 0));
     return DS_OK;
   };
   auto adjoint = [&](const double* h, double* sv, int with_absmax) -> int {  // s = (rows)^T . h
     if (!hybrid) return ds_bit_spmv(ctx, Zt, n, R, RW, 0, 1, h, sv);
     DS_TRY(ds_vec_quantize(ctx, h, R, &mm_a, h + Rs, h, Rs, q64h, scal_a, with_absmax));
-    if (Rs > 0) DS_TRY(ds_tile_spmv(ctx, &tiles, 1, q64h, scal_a, sv, Rd > 0 ? 0 : 1));
-    if (Rd > 0) DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_a, Ztd, RdW, 0, 1, scal_a, Rs > 0 ? sv : nullptr, sv, 1));
+    if (Rs > 0) DS_TRY(ds_tile_spmv(ctx, &tiles, 1, q64h, scal_a, sv, sv && Rd == 0 ? 1 : 0));
+    if (Rd > 0) DS_TRY(ds_bit_spmv_mm_product(ctx, &mm_a, Ztd, RdW, 0, 1, scal_a, sv && Rs > 0 ? sv : nullptr, sv, sv ? 1 : 0));
     return DS_OK;
   };
+  a.fused = hybrid ? 1 : 0;
+  a.Rs = Rs;
+  a.fwd = ds_fixed_view_of(&tiles, &mm_f, 0);
+  a.adj = ds_fixed_view_of(&tiles, &mm_a, 1);
+  a.scal_f = scal_f;
+  a.scal_a = scal_a;
   // what one iteration must read of the matrix: the bitmap rows of both orientations and 4 bytes per tile entry, twice
   ctx->cgls_bytes_per_iter = hybrid ? 2.0 * ((double)Rd * (double)W * 8.0 + 4.0 * (double)nnz_s)
                                     : 2.0 * (double)R * (double)W * 8.0;
@@ -512,10 +551,10 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
   while (!converged && launched < max_iter) {
     const int burst = max_iter - launched < kCheckEvery ? max_iter - launched : kCheckEvery;
     for (int b = 0; b < burst; ++b) {
-      DS_TRY(forward(a.u, a.d, launched + b == 0 ? 1 : 0));   // (the first u comes from the set-up, not from the loop's kernel)
+      DS_TRY(forward(a.u, hybrid ? nullptr : a.d, launched + b == 0 ? 1 : 0));   // (the first u comes from the set-up, not from the loop's kernel)
       hipLaunchKernelGGL(loop_make_v_kernel, dim3(red_r), dim3(kThreads), 0, st, a, (int)red_n);
       hipLaunchKernelGGL(loop_update_r_kernel, dim3(red_r), dim3(kThreads), 0, st, a, (int)red_r);
-      DS_TRY(adjoint(a.h, a.s, 0));
+      DS_TRY(adjoint(a.h, hybrid ? nullptr : a.s, 0));
       hipLaunchKernelGGL(loop_s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
       hipLaunchKernelGGL(loop_s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a, (int)red_n);
       // the last iteration allowed takes no further step: it only evaluates the stopping rule

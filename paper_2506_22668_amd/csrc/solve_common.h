@@ -87,7 +87,14 @@ static inline ds_fixed_view ds_fixed_view_of(const ds_tile_plan* t, const ds_mm_
 // as two 32-bit halves so that the total may exceed 63 bits)
 __device__ __forceinline__ double ds_tile_sum(const long long* partial, int64_t len, int groups, int sh, int64_t i) {
   long long hi = 0, lo = 0;
-  for (int g = 0; g < groups; ++g) {
+  int g = 0;
+  for (; g + 4 <= groups; g += 4) {  // four loads in flight
+    const long long* q = partial + (int64_t)g * len + i;
+    const long long p0 = q[0], p1 = q[len], p2 = q[2 * len], p3 = q[3 * len];
+    hi += (p0 >> 32) + (p1 >> 32) + (p2 >> 32) + (p3 >> 32);
+    lo += (p0 & 0xffffffffll) + (p1 & 0xffffffffll) + (p2 & 0xffffffffll) + (p3 & 0xffffffffll);
+  }
+  for (; g < groups; ++g) {
     const long long p = partial[(int64_t)g * len + i];
     hi += p >> 32;
     lo += p & 0xffffffffll;
@@ -97,7 +104,20 @@ __device__ __forceinline__ double ds_tile_sum(const long long* partial, int64_t 
 // sum_d 256^d * (sum over the groups of digit sum d) of row r of a matrix-core product
 __device__ __forceinline__ double ds_mm_sum(const int32_t* partial, int64_t rows, int groups, int64_t r) {
   long long S0 = 0, S1 = 0, S2 = 0, S3 = 0, S4 = 0, S5 = 0, S6 = 0;
-  for (int g = 0; g < groups; ++g) {
+  int g = 0;
+  for (; g + 2 <= groups; g += 2) {  // four loads in flight
+    const int4* p = (const int4*)(partial + ((int64_t)g * rows + r) * 8);
+    const int4* q = (const int4*)(partial + ((int64_t)(g + 1) * rows + r) * 8);
+    const int4 u = p[0], w = p[1], u2 = q[0], w2 = q[1];
+    S0 += (long long)u.x + u2.x;
+    S1 += (long long)u.y + u2.y;
+    S2 += (long long)u.z + u2.z;
+    S3 += (long long)u.w + u2.w;
+    S4 += (long long)w.x + w2.x;
+    S5 += (long long)w.y + w2.y;
+    S6 += (long long)w.z + w2.z;
+  }
+  for (; g < groups; ++g) {
     const int4* p = (const int4*)(partial + ((int64_t)g * rows + r) * 8);
     const int4 u = p[0], w = p[1];
     S0 += u.x;
