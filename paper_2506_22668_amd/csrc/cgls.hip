@@ -201,15 +201,19 @@ __global__ void fin_u_kernel(Vecs a, int nparts) {
 constexpr int kPartV = 0, kPartS = 1, kPartG = 2, kPartU = 3;
 
 // all threads of the workgroup get the sum of the nparts partials of array `which`
+// (every workgroup adds them in the same order: thread t takes the partials t, t + kThreads, ..., then lanes, then waves)
 __device__ __forceinline__ double block_sum_partials(const Vecs& a, int which, int nparts) {
-  __shared__ double bs;
+  __shared__ double bs[kThreads / 64];
+  const double* part = a.part + which * kRed;
+  double s = 0.0;
+  for (int i = threadIdx.x; i < nparts; i += kThreads) s += part[i];
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
   __syncthreads();
-  if (threadIdx.x < 64) {
-    const double s = wave_sum_partials(a.part + which * kRed, nparts);
-    if (threadIdx.x == 0) bs = s;
-  }
+  if ((threadIdx.x & 63) == 0) bs[threadIdx.x >> 6] = s;
   __syncthreads();
-  return bs;
+  double t = bs[0];
+  for (int i = 1; i < kThreads / 64; ++i) t += bs[i];
+  return t;
 }
 
 // v from d (after finishing sum(u) and moving gamma_new to gamma); partial |v|^2
