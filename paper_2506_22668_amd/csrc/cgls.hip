@@ -69,15 +69,39 @@ struct Vecs {
   const double *scal_f, *scal_a;
 };
 
-__device__ __forceinline__ double forward_result(const Vecs& a, double sc, int64_t i) {
-  if (i < a.Rs)
-    return a.fwd.tile_groups ? ds_tile_sum(a.fwd.tile_partial, a.fwd.tile_len, a.fwd.tile_groups, a.fwd.tile_sh, i) * sc : 0.0;
-  return ds_mm_sum(a.fwd.mm_partial, a.fwd.mm_rows, a.fwd.mm_groups, i - a.Rs) * sc;
+// T lanes (a power of two, consecutive lanes of a wave, `sub` = the lane's place among them) add up one entry together:
+// each takes every T-th group, the integers are added across the lanes, and all T lanes return the same value
+template <int T>
+__device__ __forceinline__ double mm_result(const ds_fixed_view& v, int64_t r, int sub) {
+  long long S[7] = {0, 0, 0, 0, 0, 0, 0};
+  ds_mm_sum_part(v.mm_partial, v.mm_rows, v.mm_groups, r, sub, T, S);
+#pragma unroll
+  for (int o = 1; o < T; o <<= 1)
+#pragma unroll
+    for (int d = 0; d < 7; ++d) S[d] += __shfl_xor(S[d], o, 64);
+  return ds_mm_sum_finish(S);
 }
-__device__ __forceinline__ double adjoint_result(const Vecs& a, double sc, int64_t j) {
-  const double mm = a.adj.mm_groups ? ds_mm_sum(a.adj.mm_partial, a.adj.mm_rows, a.adj.mm_groups, j) * sc : 0.0;
+template <int T>
+__device__ __forceinline__ double tile_result(const ds_fixed_view& v, int64_t i, int sub) {
+  long long hi = 0, lo = 0;
+  ds_tile_sum_part(v.tile_partial, v.tile_len, v.tile_groups, i, sub, T, hi, lo);
+#pragma unroll
+  for (int o = 1; o < T; o <<= 1) {
+    hi += __shfl_xor(hi, o, 64);
+    lo += __shfl_xor(lo, o, 64);
+  }
+  return ds_tile_sum_finish(hi, lo, v.tile_sh);
+}
+template <int T>
+__device__ __forceinline__ double forward_result(const Vecs& a, double sc, int64_t i, int sub) {
+  if (i < a.Rs) return a.fwd.tile_groups ? tile_result<T>(a.fwd, i, sub) * sc : 0.0;
+  return mm_result<T>(a.fwd, i - a.Rs, sub) * sc;
+}
+template <int T>
+__device__ __forceinline__ double adjoint_result(const Vecs& a, double sc, int64_t j, int sub) {
+  const double mm = a.adj.mm_groups ? mm_result<T>(a.adj, j, sub) * sc : 0.0;
   if (!a.adj.tile_groups) return mm;
-  const double tl = ds_tile_sum(a.adj.tile_partial, a.adj.tile_len, a.adj.tile_groups, a.adj.tile_sh, j) * sc;
+  const double tl = tile_result<T>(a.adj, j, sub) * sc;
   return a.adj.mm_groups ? tl + mm : tl;
 }
 
@@ -216,7 +240,8 @@ __device__ __forceinline__ double block_sum_partials(const Vecs& a, int which, i
   return t;
 }
 
-// v from d (after finishing sum(u) and moving gamma_new to gamma); partial |v|^2
+// v from d (after finishing sum(u) and moving gamma_new to gamma); partial |v|^2. T lanes per row (1 unless fused).
+template <int T>
 __global__ __launch_bounds__(kThreads) void loop_make_v_kernel(Vecs a, int parts_u) {
   const double U = block_sum_partials(a, kPartU, parts_u);
   if (blockIdx.x == 0 && threadIdx.x == 0 && a.scal[8] == 0.0) {
@@ -226,17 +251,21 @@ __global__ __launch_bounds__(kThreads) void loop_make_v_kernel(Vecs a, int parts
   const double sc = a.fused ? a.scal_f[0] : 0.0;
   if (a.fused && blockIdx.x == 0 && threadIdx.x == 0) *a.slot_u = 0ull;
   double acc = 0.0;
-  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < a.R; i += (int64_t)gridDim.x * kThreads) {
-    if (a.paired) {
-      const double w = a.sqw[2 * i], d = a.fused ? forward_result(a, sc, i) : a.d[i];
-      const double v0 = w * d, v1 = w * (U - d);
-      a.v[2 * i] = v0;
-      a.v[2 * i + 1] = v1;
-      acc += v0 * v0 + v1 * v1;
-    } else {
-      const double v0 = a.sqw[i] * a.d[i];
-      a.v[i] = v0;
-      acc += v0 * v0;
+  const int sub = threadIdx.x & (T - 1);
+  for (int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / T; i < a.R; i += (int64_t)gridDim.x * (kThreads / T)) {
+    const double d = a.fused ? forward_result<T>(a, sc, i, sub) : a.d[i];
+    if (sub == 0) {   // (all T lanes hold the same d)
+      if (a.paired) {
+        const double w = a.sqw[2 * i];
+        const double v0 = w * d, v1 = w * (U - d);
+        a.v[2 * i] = v0;
+        a.v[2 * i + 1] = v1;
+        acc += v0 * v0 + v1 * v1;
+      } else {
+        const double v0 = a.sqw[i] * d;
+        a.v[i] = v0;
+        acc += v0 * v0;
+      }
     }
   }
   double dummy;
@@ -283,15 +312,19 @@ __global__ __launch_bounds__(kThreads) void loop_update_r_kernel(Vecs a, int par
   if (a.slot_h) publish_absmax(hm, a.slot_h);
 }
 
+template <int T>
 __global__ __launch_bounds__(kThreads) void loop_s_sum_kernel(Vecs a) {
   double s1 = 0;
   if (a.fused) {
     const double sc = a.scal_a[0];
     if (blockIdx.x == 0 && threadIdx.x == 0) *a.slot_h = 0ull;
-    for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) {
-      const double v = adjoint_result(a, sc, j);
-      a.s[j] = v;
-      s1 += v;
+    const int sub = threadIdx.x & (T - 1);
+    for (int64_t j = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / T; j < a.n; j += (int64_t)gridDim.x * (kThreads / T)) {
+      const double v = adjoint_result<T>(a, sc, j, sub);
+      if (sub == 0) {
+        a.s[j] = v;
+        s1 += v;
+      }
     }
   } else {
     for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < a.n; j += (int64_t)gridDim.x * kThreads) s1 += a.s[j];
@@ -525,6 +558,22 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
 
   const unsigned red_n = nblocks(n, kThreads) < (unsigned)kRed ? nblocks(n, kThreads) : (unsigned)kRed;
   const unsigned red_r = nblocks(R, kThreads) < (unsigned)kRed ? nblocks(R, kThreads) : (unsigned)kRed;
+  // lanes per entry in the two kernels that add up the products' partial sums: short vectors take 4 or 16, so that
+  // enough loads are in flight
+  auto lanes_for = [&](int64_t len) { return !hybrid ? 1 : len * 16 <= 262144 ? 16 : len * 4 <= 262144 ? 4 : 1; };
+  const int lanes_v = lanes_for(R), lanes_s = lanes_for(n);
+  const unsigned grid_v = nblocks(R * lanes_v, kThreads) < (unsigned)kRed ? nblocks(R * lanes_v, kThreads) : (unsigned)kRed;
+  const unsigned grid_s = nblocks(n * lanes_s, kThreads) < (unsigned)kRed ? nblocks(n * lanes_s, kThreads) : (unsigned)kRed;
+  auto launch_make_v = [&]() {
+    if (lanes_v == 16) hipLaunchKernelGGL(loop_make_v_kernel<16>, dim3(grid_v), dim3(kThreads), 0, st, a, (int)red_n);
+    else if (lanes_v == 4) hipLaunchKernelGGL(loop_make_v_kernel<4>, dim3(grid_v), dim3(kThreads), 0, st, a, (int)red_n);
+    else hipLaunchKernelGGL(loop_make_v_kernel<1>, dim3(grid_v), dim3(kThreads), 0, st, a, (int)red_n);
+  };
+  auto launch_s_sum = [&]() {
+    if (lanes_s == 16) hipLaunchKernelGGL(loop_s_sum_kernel<16>, dim3(grid_s), dim3(kThreads), 0, st, a);
+    else if (lanes_s == 4) hipLaunchKernelGGL(loop_s_sum_kernel<4>, dim3(grid_s), dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL(loop_s_sum_kernel<1>, dim3(grid_s), dim3(kThreads), 0, st, a);
+  };
 
   // s_0 = P A^T r_0, u_0 = s_0
   hipLaunchKernelGGL(init_r_kernel, dim3(nblocks(k, 256)), dim3(256), 0, st, a, t);
@@ -556,11 +605,11 @@ int ds_solve_cgls_impl(ds_ctx* ctx, int64_t n, int64_t k, const uint64_t* Z, con
     const int burst = max_iter - launched < kCheckEvery ? max_iter - launched : kCheckEvery;
     for (int b = 0; b < burst; ++b) {
       DS_TRY(forward(a.u, hybrid ? nullptr : a.d, launched + b == 0 ? 1 : 0));   // (the first u comes from the set-up, not from the loop's kernel)
-      hipLaunchKernelGGL(loop_make_v_kernel, dim3(red_r), dim3(kThreads), 0, st, a, (int)red_n);
-      hipLaunchKernelGGL(loop_update_r_kernel, dim3(red_r), dim3(kThreads), 0, st, a, (int)red_r);
+      launch_make_v();
+      hipLaunchKernelGGL(loop_update_r_kernel, dim3(red_r), dim3(kThreads), 0, st, a, (int)grid_v);
       DS_TRY(adjoint(a.h, hybrid ? nullptr : a.s, 0));
-      hipLaunchKernelGGL(loop_s_sum_kernel, dim3(red_n), dim3(kThreads), 0, st, a);
-      hipLaunchKernelGGL(loop_s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a, (int)red_n);
+      launch_s_sum();
+      hipLaunchKernelGGL(loop_s_center_kernel, dim3(red_n), dim3(kThreads), 0, st, a, (int)grid_s);
       // the last iteration allowed takes no further step: it only evaluates the stopping rule
       hipLaunchKernelGGL(loop_update_xu_kernel, dim3(red_n), dim3(kThreads), 0, st, a, (int)red_n, tol,
                          launched + b + 1 < max_iter ? 1 : 0);

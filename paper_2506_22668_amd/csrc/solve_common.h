@@ -83,54 +83,71 @@ static inline ds_fixed_view ds_fixed_view_of(const ds_tile_plan* t, const ds_mm_
   return v;
 }
 #ifdef __HIPCC__
-// sum over the groups of entry i of a tile product, times 2^sh (exact up to the final rounding: the groups are added
-// as two 32-bit halves so that the total may exceed 63 bits)
-__device__ __forceinline__ double ds_tile_sum(const long long* partial, int64_t len, int groups, int sh, int64_t i) {
-  long long hi = 0, lo = 0;
-  int g = 0;
-  for (; g + 4 <= groups; g += 4) {  // four loads in flight
+// The sums over the groups are exact integers, so they may be split over T lanes in any way: lane `sub` (0 <= sub < T)
+// adds the groups sub, sub + T, ... (four loads in flight), the lanes' integers are added, and one rounding ends it.
+// tile product, entry i: the groups as two 32-bit halves, so that the total may exceed 63 bits
+__device__ __forceinline__ void ds_tile_sum_part(const long long* partial, int64_t len, int groups, int64_t i, int sub, int T,
+                                                 long long& hi, long long& lo) {
+  int g = sub;
+  for (; g + 3 * T < groups; g += 4 * T) {
     const long long* q = partial + (int64_t)g * len + i;
-    const long long p0 = q[0], p1 = q[len], p2 = q[2 * len], p3 = q[3 * len];
+    const int64_t st = (int64_t)T * len;
+    const long long p0 = q[0], p1 = q[st], p2 = q[2 * st], p3 = q[3 * st];
     hi += (p0 >> 32) + (p1 >> 32) + (p2 >> 32) + (p3 >> 32);
     lo += (p0 & 0xffffffffll) + (p1 & 0xffffffffll) + (p2 & 0xffffffffll) + (p3 & 0xffffffffll);
   }
-  for (; g < groups; ++g) {
+  for (; g < groups; g += T) {
     const long long p = partial[(int64_t)g * len + i];
     hi += p >> 32;
     lo += p & 0xffffffffll;
   }
+}
+// ... times 2^sh
+__device__ __forceinline__ double ds_tile_sum_finish(long long hi, long long lo, int sh) {
   return ((double)hi * 4294967296.0 + (double)lo) * (double)(1ll << sh);
 }
-// sum_d 256^d * (sum over the groups of digit sum d) of row r of a matrix-core product
-__device__ __forceinline__ double ds_mm_sum(const int32_t* partial, int64_t rows, int groups, int64_t r) {
-  long long S0 = 0, S1 = 0, S2 = 0, S3 = 0, S4 = 0, S5 = 0, S6 = 0;
-  int g = 0;
-  for (; g + 2 <= groups; g += 2) {  // four loads in flight
+__device__ __forceinline__ double ds_tile_sum(const long long* partial, int64_t len, int groups, int sh, int64_t i) {
+  long long hi = 0, lo = 0;
+  ds_tile_sum_part(partial, len, groups, i, 0, 1, hi, lo);
+  return ds_tile_sum_finish(hi, lo, sh);
+}
+// matrix-core product, row r: S[d] = sum over the groups of digit sum d; the result is sum_d 256^d S[d]
+__device__ __forceinline__ void ds_mm_sum_part(const int32_t* partial, int64_t rows, int groups, int64_t r, int sub, int T,
+                                               long long S[7]) {
+  int g = sub;
+  for (; g + T < groups; g += 2 * T) {
     const int4* p = (const int4*)(partial + ((int64_t)g * rows + r) * 8);
-    const int4* q = (const int4*)(partial + ((int64_t)(g + 1) * rows + r) * 8);
+    const int4* q = (const int4*)(partial + ((int64_t)(g + T) * rows + r) * 8);
     const int4 u = p[0], w = p[1], u2 = q[0], w2 = q[1];
-    S0 += (long long)u.x + u2.x;
-    S1 += (long long)u.y + u2.y;
-    S2 += (long long)u.z + u2.z;
-    S3 += (long long)u.w + u2.w;
-    S4 += (long long)w.x + w2.x;
-    S5 += (long long)w.y + w2.y;
-    S6 += (long long)w.z + w2.z;
+    S[0] += (long long)u.x + u2.x;
+    S[1] += (long long)u.y + u2.y;
+    S[2] += (long long)u.z + u2.z;
+    S[3] += (long long)u.w + u2.w;
+    S[4] += (long long)w.x + w2.x;
+    S[5] += (long long)w.y + w2.y;
+    S[6] += (long long)w.z + w2.z;
   }
-  for (; g < groups; ++g) {
+  for (; g < groups; g += T) {
     const int4* p = (const int4*)(partial + ((int64_t)g * rows + r) * 8);
     const int4 u = p[0], w = p[1];
-    S0 += u.x;
-    S1 += u.y;
-    S2 += u.z;
-    S3 += u.w;
-    S4 += w.x;
-    S5 += w.y;
-    S6 += w.z;
+    S[0] += u.x;
+    S[1] += u.y;
+    S[2] += u.z;
+    S[3] += u.w;
+    S[4] += w.x;
+    S[5] += w.y;
+    S[6] += w.z;
   }
-  const long long hi = ((S6 * 256 + S5) * 256 + S4) * 256 + S3;
-  const long long lo = (S2 * 256 + S1) * 256 + S0;
+}
+__device__ __forceinline__ double ds_mm_sum_finish(const long long S[7]) {
+  const long long hi = ((S[6] * 256 + S[5]) * 256 + S[4]) * 256 + S[3];
+  const long long lo = (S[2] * 256 + S[1]) * 256 + S[0];
   return (double)hi * 16777216.0 + (double)lo;
+}
+__device__ __forceinline__ double ds_mm_sum(const int32_t* partial, int64_t rows, int groups, int64_t r) {
+  long long S[7] = {0, 0, 0, 0, 0, 0, 0};
+  ds_mm_sum_part(partial, rows, groups, r, 0, 1, S);
+  return ds_mm_sum_finish(S);
 }
 #endif
 
